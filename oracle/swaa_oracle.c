@@ -1,0 +1,156 @@
+/*
+ * swaa_oracle.c -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * Plain fp64 CPU definition of sliding-window attention with "keep first k"
+ * sink tokens (paper Sec. 1: each token attends to a fixed-size local window;
+ * Sec. 3.2.1 and Fig. 1b: every later token attends to its local window AND
+ * the initial k tokens; Sec. 4.1.2: a window at least as long as the context
+ * is full causal attention).  It exists only so that tests, the smoke check
+ * and the benchmark's cpu_baseline leg have an independent answer to compare
+ * the GPU library with.  It shares no code with the GPU path and is never
+ * called by it.
+ *
+ * For batch b, query head h, KV head g = h / (Hq/Hkv), query row i:
+ *
+ *   Vis(i) = { j : 0 <= j <= i  and  ( j > i - W  or  j < S ) }   (a set)
+ *   s_j    = scale * sum_d q[b,h,i,d] * k[b,g,j,d]
+ *   m      = max_{j in Vis(i)} s_j
+ *   lse    = m + ln sum_{j in Vis(i)} exp(s_j - m)                (natural log)
+ *   o[d]   = sum_{j in Vis(i)} exp(s_j - lse) * v[b,g,j,d]
+ *
+ * Inputs are bf16 bit patterns (uint16), widened exactly to double; all
+ * arithmetic is double; outputs are double and are not rounded.  There is no
+ * tiling, no running maximum and no reordering: three passes over the
+ * explicit visible set, exactly as written above.  Rows are independent, so
+ * the only parallelism is an OpenMP loop over (b, h, row).
+ *
+ * Readings where the paper is silent: the window (i-W, i] holds W keys and
+ * includes the query itself; a key that is both a sink and in the window is
+ * counted once; sinks are causal (row i < S sees only [0, i]); the
+ * logsumexp is natural-log of the scaled scores.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static double bf16_to_double(uint16_t bits)
+{
+    uint32_t u = ((uint32_t)bits) << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+/* 1 if key j is visible from query i under (window W, sinks S). */
+static int visible(long i, long j, long W, long S)
+{
+    if (j < 0 || j > i)
+        return 0; /* causal */
+    return (j > i - W) || (j < S);
+}
+
+int swaa_oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/*
+ * Evaluate rows `rows[0..n_rows)` (NULL: every row 0..N-1, n_rows ignored) of
+ * every (b, h).  out: [B, Hq, R, D] doubles, lse: [B, Hq, R] doubles, with
+ * R = n_rows (or N).  n_threads <= 0 keeps the OpenMP default.
+ * Returns 0, or -1 on a bad argument, -2 when out of memory.
+ */
+int swaa_oracle_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v,
+                     int B, int Hq, int Hkv, int N, int D, long W, long S,
+                     double scale, const int *rows, int n_rows, double *out,
+                     double *lse, int n_threads)
+{
+    if (!q || !k || !v || !out || !lse)
+        return -1;
+    if (B < 1 || Hq < 1 || Hkv < 1 || N < 1 || D < 1 || Hq % Hkv || W < 1 || S < 0)
+        return -1;
+    const long R = rows ? n_rows : N;
+    if (R < 0)
+        return -1;
+    for (long r = 0; rows && r < R; r++)
+        if (rows[r] < 0 || rows[r] >= N)
+            return -1;
+    const int G = Hq / Hkv;
+    const long total = (long)B * Hq * R;
+    int failed = 0;
+#ifdef _OPENMP
+    if (n_threads > 0)
+        omp_set_num_threads(n_threads);
+#else
+    (void)n_threads;
+#endif
+
+#pragma omp parallel
+    {
+        double *s = (double *)malloc(sizeof(double) * (size_t)N);
+        double *qi = (double *)malloc(sizeof(double) * (size_t)D);
+        if (!s || !qi) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(dynamic, 1)
+        for (long t = 0; t < total; t++) {
+            if (!s || !qi)
+                continue;
+            const long r = t % R;
+            const long h = (t / R) % Hq;
+            const long b = t / (R * Hq);
+            const long g = h / G;
+            const long i = rows ? rows[r] : r;
+            const uint16_t *qrow = q + (((size_t)b * Hq + h) * N + i) * D;
+            const uint16_t *kb = k + ((size_t)b * Hkv + g) * (size_t)N * D;
+            const uint16_t *vb = v + ((size_t)b * Hkv + g) * (size_t)N * D;
+            double *o = out + (size_t)t * D;
+            for (int d = 0; d < D; d++)
+                qi[d] = bf16_to_double(qrow[d]);
+
+            /* scores and their maximum over the visible set */
+            double m = -INFINITY;
+            for (long j = 0; j <= i; j++) {
+                if (!visible(i, j, W, S))
+                    continue;
+                const uint16_t *kr = kb + (size_t)j * D;
+                double acc = 0.0;
+                for (int d = 0; d < D; d++)
+                    acc += qi[d] * bf16_to_double(kr[d]);
+                s[j] = scale * acc;
+                if (s[j] > m)
+                    m = s[j];
+            }
+            /* normaliser */
+            double l = 0.0;
+            for (long j = 0; j <= i; j++)
+                if (visible(i, j, W, S))
+                    l += exp(s[j] - m);
+            const double lse_i = m + log(l);
+            lse[t] = lse_i;
+            /* weighted sum of value rows */
+            for (int d = 0; d < D; d++)
+                o[d] = 0.0;
+            for (long j = 0; j <= i; j++) {
+                if (!visible(i, j, W, S))
+                    continue;
+                const double p = exp(s[j] - lse_i);
+                const uint16_t *vr = vb + (size_t)j * D;
+                for (int d = 0; d < D; d++)
+                    o[d] += p * bf16_to_double(vr[d]);
+            }
+        }
+        free(s);
+        free(qi);
+    }
+    return failed ? -2 : 0;
+}

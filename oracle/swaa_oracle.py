@@ -1,0 +1,131 @@
+"""Python face of the fp64 CPU oracle.  TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+
+Two independent routes to the same definition (paper Sec. 1, Sec. 3.2.1 /
+Fig. 1b, Sec. 4.1.2):
+
+* :func:`swaa_attn_oracle` -- calls ``swaa_oracle.c`` (plain C, fp64, OpenMP
+  over rows) through ctypes; fast enough for the sampled rows of the largest
+  configurations.
+* :func:`swaa_attn_oracle_numpy` -- the same three lines of mathematics in
+  numpy, one row at a time with an explicit list of visible keys; used for
+  small cases and to cross-check the C build.
+
+Inputs are bf16 bit patterns held in ``uint16`` arrays of shape [B, H, N, D];
+outputs are float64 and unrounded.  Parity status: pinned (see
+``tests/test_oracle_pins.py``): full-causal special case against a library
+softmax-attention, closed forms for W=1 and Q=0, brute-force boolean masks on
+tiny inputs, locality, merge identity, GQA/batch identities.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "swaa_oracle.c")
+_LIB = os.path.join(_HERE, "libswaa_oracle.so")
+_lib = None
+
+
+def build_oracle(force: bool = False) -> str:
+    """Compile ``swaa_oracle.c`` with gcc into ``libswaa_oracle.so`` (beside it)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build_oracle())
+        lib.swaa_oracle_rows.restype = ctypes.c_int
+        lib.swaa_oracle_rows.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_long, ctypes.c_long, ctypes.c_double,
+            ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
+        lib.swaa_oracle_num_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def oracle_num_threads() -> int:
+    """Threads the C oracle's OpenMP loop will use by default."""
+    return int(_load().swaa_oracle_num_threads())
+
+
+def _check(q, k, v):
+    for name, a in (("q", q), ("k", k), ("v", v)):
+        if not isinstance(a, np.ndarray) or a.dtype != np.uint16 or a.ndim != 4:
+            raise TypeError(f"{name}: expected uint16 (bf16 bits) ndarray [B,H,N,D]")
+    B, Hq, N, D = q.shape
+    if k.shape != v.shape or k.shape[0] != B or k.shape[2] != N or k.shape[3] != D:
+        raise ValueError("k/v shape mismatch")
+    Hkv = k.shape[1]
+    if Hq % Hkv:
+        raise ValueError("Hq must be a multiple of Hkv")
+    return B, Hq, Hkv, N, D
+
+
+def swaa_attn_oracle(q, k, v, window, n_sink, scale, rows=None, n_threads=0):
+    """fp64 SWA+sink attention via the C oracle.
+
+    rows: optional 1-D int array of query rows to evaluate (same set for every
+    (b, h)); None evaluates all N rows.  Returns (out [B,Hq,R,D] float64,
+    lse [B,Hq,R] float64).
+    """
+    B, Hq, Hkv, N, D = _check(q, k, v)
+    q = np.ascontiguousarray(q)
+    k = np.ascontiguousarray(k)
+    v = np.ascontiguousarray(v)
+    if rows is None:
+        rows_arr, R, rows_p = None, N, None
+    else:
+        rows_arr = np.ascontiguousarray(np.asarray(rows, dtype=np.int32))
+        R = int(rows_arr.shape[0])
+        rows_p = rows_arr.ctypes.data
+    out = np.empty((B, Hq, R, D), dtype=np.float64)
+    lse = np.empty((B, Hq, R), dtype=np.float64)
+    rc = _load().swaa_oracle_rows(
+        q.ctypes.data, k.ctypes.data, v.ctypes.data, B, Hq, Hkv, N, D,
+        int(window), int(n_sink), float(scale), rows_p, R,
+        out.ctypes.data, lse.ctypes.data, int(n_threads))
+    if rc != 0:
+        raise ValueError(f"swaa_oracle_rows failed with code {rc}")
+    return out, lse
+
+
+def _bf16_bits_to_f64(a: np.ndarray) -> np.ndarray:
+    return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def swaa_attn_oracle_numpy(q, k, v, window, n_sink, scale, rows=None):
+    """The same definition in numpy, row by row (slow; small inputs only)."""
+    B, Hq, Hkv, N, D = _check(q, k, v)
+    W, S = int(window), int(n_sink)
+    if W < 1 or S < 0:
+        raise ValueError("window >= 1 and n_sink >= 0 required")
+    G = Hq // Hkv
+    qf, kf, vf = (_bf16_bits_to_f64(a) for a in (q, k, v))
+    row_list = list(range(N)) if rows is None else [int(r) for r in rows]
+    out = np.empty((B, Hq, len(row_list), D), dtype=np.float64)
+    lse = np.empty((B, Hq, len(row_list)), dtype=np.float64)
+    for b in range(B):
+        for h in range(Hq):
+            g = h // G
+            for r, i in enumerate(row_list):
+                vis = [j for j in range(i + 1) if (j > i - W) or (j < S)]
+                s = scale * (kf[b, g, vis] @ qf[b, h, i])
+                m = s.max()
+                lse_i = m + np.log(np.exp(s - m).sum())
+                p = np.exp(s - lse_i)
+                out[b, h, r] = p @ vf[b, g, vis]
+                lse[b, h, r] = lse_i
+    return out, lse

@@ -1,0 +1,120 @@
+"""Seeded synthetic inputs for SWA+sink prefill attention.
+
+Data only: this module holds none of the method's arithmetic and is the one
+piece that the tests, the benchmark, the GPU binding's callers and the CPU
+oracle's callers share.  Values stand in for the long-context workloads the
+paper evaluates on (16k-32k-token prompts, 128k-token prompts, windows of
+2k/4k/8k or full attention: Sec. 4.1.2, Table 1, Table 5); the paper's own
+efficiency runs use random inputs too (Sec. 4.3).
+
+Tensors are returned as numpy uint16 arrays holding bf16 bit patterns in
+[B, H, N, D] layout, drawn in the order q, k, v from a Philox stream.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass
+
+import numpy as np
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 to bf16 (round-to-nearest-even), return the uint16 bits."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    rounded = u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
+    bits = (rounded >> np.uint32(16)).astype(np.uint16)
+    nan = np.isnan(x)
+    if nan.any():
+        bits[nan] = np.uint16(0x7FC0)
+    return bits
+
+
+def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    """Widen bf16 bit patterns (uint16) to float32 exactly."""
+    return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+@dataclass(frozen=True)
+class Workload:
+    """One attention-forward call: shapes, mask parameters, value recipe."""
+    name: str
+    B: int
+    Hq: int
+    Hkv: int
+    N: int
+    D: int
+    window: int
+    n_sink: int
+    seed: int
+    k_mult: float = 1.0   # k is multiplied by this (exact in bf16 for powers of two)
+
+    @property
+    def scale(self) -> float:
+        return 1.0 / math.sqrt(self.D)
+
+
+_SEED0 = 2512104110
+
+# The five configurations of the benchmark definition (seven runs: the third
+# and fifth are run with an SWA window and again with window = N on the same
+# tensors, modelling an SWA layer next to a full-attention layer).
+WORKLOADS = {
+    "tiny":        Workload("tiny",        1,  4, 1,   1024,  64,   128, 4, _SEED0 + 1),
+    "mid":         Workload("mid",         1, 32, 8,  16384, 128,  2048, 4, _SEED0 + 2),
+    "pair32k_swa": Workload("pair32k_swa", 1, 32, 8,  32768, 128,  4096, 4, _SEED0 + 3, 2.0),
+    "pair32k_full": Workload("pair32k_full", 1, 32, 8, 32768, 128, 32768, 4, _SEED0 + 3, 2.0),
+    "batched":     Workload("batched",     4, 40, 8,   8192, 128,  1024, 4, _SEED0 + 4),
+    "long128k_swa": Workload("long128k_swa", 1, 32, 8, 131072, 128, 8192, 4, _SEED0 + 5),
+    "long128k_full": Workload("long128k_full", 1, 32, 8, 131072, 128, 131072, 4, _SEED0 + 5),
+}
+
+
+def make_qkv(B, Hq, Hkv, N, D, seed, k_mult=1.0, chunk_rows=1 << 22):
+    """i.i.d. N(0,1) q, k, v rounded to bf16; k scaled by k_mult before rounding.
+
+    Generated in row chunks so that the float32 staging buffer stays small even
+    for the 128k-token workloads.
+    """
+    rng = np.random.Generator(np.random.Philox(int(seed)))
+
+    def draw(H, mult):
+        out = np.empty((B * H * N, D), dtype=np.uint16)
+        for r0 in range(0, out.shape[0], chunk_rows):
+            r1 = min(out.shape[0], r0 + chunk_rows)
+            x = rng.standard_normal((r1 - r0, D), dtype=np.float32)
+            if mult != 1.0:
+                x *= np.float32(mult)
+            out[r0:r1] = f32_to_bf16_bits(x)
+        return out.reshape(B, H, N, D)
+
+    q = draw(Hq, 1.0)
+    k = draw(Hkv, k_mult)
+    v = draw(Hkv, 1.0)
+    return q, k, v
+
+
+def make_workload(w: Workload):
+    """q, k, v (uint16 bf16 bits) for a named workload."""
+    return make_qkv(w.B, w.Hq, w.Hkv, w.N, w.D, w.seed, w.k_mult)
+
+
+def sample_rows(N, window, n_sink, count=256, seed=0, tile=64):
+    """Query rows on which large runs are compared with the oracle.
+
+    Always holds the rows where the mask changes shape (first rows, around the
+    sink count, around the window length, the last row), rows around a few
+    seeded tile boundaries, and seeded uniform rows up to `count` in total.
+    Sorted, unique, all in [0, N).
+    """
+    W, S = int(window), int(n_sink)
+    fixed = [0, 1, S - 1, S, S + 1, W - 2, W - 1, W, W + 1, W + S - 1, W + S, W + S + 1, N - 2, N - 1]
+    rng = np.random.Generator(np.random.Philox(int(seed) + 977))
+    n_tiles = max(1, N // tile)
+    for t in rng.integers(1, n_tiles + 1, size=8):
+        fixed += [int(t) * tile - 1, int(t) * tile, int(t) * tile + 1]
+    rows = {r for r in fixed if 0 <= r < N}
+    count = min(count, N)
+    while len(rows) < count:
+        for r in rng.integers(0, N, size=count - len(rows)):
+            rows.add(int(r))
+    return np.array(sorted(rows), dtype=np.int32)
