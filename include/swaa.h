@@ -1,0 +1,86 @@
+/*
+ * swaa.h -- C ABI of libswaa: sliding-window attention with "keep first k" sink
+ * tokens, prefill forward pass, for AMD MI355X (gfx950).
+ *
+ * The operation (paper Sec. 1: sliding window attention restricts each token
+ * to a fixed-size local window; Sec. 3.2.1 and Fig. 1b: every later token
+ * attends to its local window AND the initial k tokens, implemented as a mask
+ * inside the attention kernel; Sec. 3.1.2 and Sec. 4.1.2: layers that keep
+ * full attention are the same computation with a window at least as long as
+ * the context).  For batch b, query head h, KV head g = h / (Hq / Hkv) and
+ * query row i (0-based):
+ *
+ *     Vis(i)   = { j : 0 <= j <= i  and ( j > i - window  or  j < n_sink ) }
+ *     s_j      = scale * <q[b,h,i,:], k[b,g,j,:]>
+ *     lse[b,h,i]   = ln sum_{j in Vis(i)} exp(s_j)
+ *     out[b,h,i,:] = sum_{j in Vis(i)} exp(s_j - lse[b,h,i]) * v[b,g,j,:]
+ *
+ * The window (i - window, i] holds `window` keys and includes the query's own
+ * position; a key that is both a sink and inside the window counts once;
+ * sinks are causal.  Inputs and `out` are bf16, products are accumulated in
+ * fp32, `lse` is fp32 (natural logarithm of the scaled scores).
+ *
+ * All data pointers are DEVICE pointers owned by the caller; the library
+ * neither allocates, frees nor retains them, keeps no state between calls and
+ * is safe to call from several host threads.  Calls are asynchronous: work is
+ * enqueued on `stream` and the function returns without synchronising.
+ * Errors are reported through the return value only; every check happens
+ * before anything is launched, so a failed call has touched no memory.
+ */
+#ifndef SWAA_H_
+#define SWAA_H_
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum swaa_status {
+    SWAA_OK = 0,
+    SWAA_ERR_NULL = -1,        /* a required pointer is NULL */
+    SWAA_ERR_SHAPE = -2,       /* a size, the window, the sink count or the scale is out of range */
+    SWAA_ERR_UNSUPPORTED = -3, /* head dimension without a kernel instantiation */
+    SWAA_ERR_ALIGN = -4,       /* a pointer is not 16-byte aligned */
+    SWAA_ERR_LAUNCH = -5       /* the HIP runtime refused the launch */
+} swaa_status;
+
+/*
+ * Attention forward (the operation defined at the top of this file).
+ *
+ *   q    device, bf16 [B, Hq,  N, D], contiguous, 16-byte aligned, read only
+ *   k    device, bf16 [B, Hkv, N, D], contiguous, 16-byte aligned, read only
+ *   v    device, bf16 [B, Hkv, N, D], contiguous, 16-byte aligned, read only
+ *   out  device, bf16 [B, Hq,  N, D], contiguous, 16-byte aligned, written;
+ *        must not overlap q, k or v
+ *   lse  device, fp32 [B, Hq, N], contiguous, 16-byte aligned, written
+ *   B, Hq, Hkv, N >= 1; Hq a multiple of Hkv (query head h reads KV head
+ *        h / (Hq/Hkv)); N * D * max(Hq, Hkv) * B must fit in 2^62 elements
+ *   D    head dimension: 64 or 128
+ *   window  >= 1; any value >= N means full causal attention
+ *   n_sink  >= 0; values >= N behave as N
+ *   scale   finite and > 0 (callers normally pass 1/sqrt(D))
+ *   stream  a hipStream_t, or NULL for the default stream
+ *
+ * Returns SWAA_OK or a negative swaa_status.
+ */
+int swaa_attn_fwd(const void *q, const void *k, const void *v, void *out, float *lse,
+                  int B, int Hq, int Hkv, int N, int D, int window, int n_sink,
+                  float scale, void *stream);
+
+/*
+ * Number of visible (query, key) pairs per head under the mask above, i.e.
+ * sum over i in [0, N) of |Vis(i)|; the benchmark counts 4*D floating-point
+ * operations per pair (paper App. A: the cost of sliding window attention is
+ * O(N * W)).  Host-only arithmetic; returns -1 on an invalid argument.
+ */
+long long swaa_visible_pairs(long long N, long long window, long long n_sink);
+
+/* Static description of a status code; never NULL, never freed. */
+const char *swaa_status_string(int status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int swaa_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SWAA_H_ */

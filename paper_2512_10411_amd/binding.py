@@ -1,0 +1,123 @@
+"""ctypes binding of libswaa.so: argument marshalling only.
+
+Every step of the attention forward runs inside the HIP kernels; torch is
+used for device memory and the stream handle.  There is no fallback: if the
+library is not built and cannot be built, importing callers get an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libswaa.so")
+
+SWAA_OK = 0
+SWAA_ERR_NULL = -1
+SWAA_ERR_SHAPE = -2
+SWAA_ERR_UNSUPPORTED = -3
+SWAA_ERR_ALIGN = -4
+SWAA_ERR_LAUNCH = -5
+
+# every symbol include/swaa.h declares
+EXPORTS = ("swaa_attn_fwd", "swaa_visible_pairs", "swaa_status_string", "swaa_version")
+
+_lib = None
+
+
+class SwaaError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"libswaa: {message} (status {status})")
+        self.status = status
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libswaa.so, building it first only if no built library exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from .build import build_library
+        build_library()
+    lib = ctypes.CDLL(LIB_PATH)
+    lib.swaa_attn_fwd.restype = ctypes.c_int
+    lib.swaa_attn_fwd.argtypes = [
+        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+        ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+        ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_void_p]
+    lib.swaa_visible_pairs.restype = ctypes.c_longlong
+    lib.swaa_visible_pairs.argtypes = [ctypes.c_longlong] * 3
+    lib.swaa_status_string.restype = ctypes.c_char_p
+    lib.swaa_status_string.argtypes = [ctypes.c_int]
+    lib.swaa_version.restype = ctypes.c_int
+    lib.swaa_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def swaa_status_string(status: int) -> str:
+    return load_library().swaa_status_string(int(status)).decode()
+
+
+def swaa_version() -> int:
+    return int(load_library().swaa_version())
+
+
+def swaa_visible_pairs(N: int, window: int, n_sink: int) -> int:
+    """Visible (query, key) pairs per head; the benchmark counts 4*D flops each."""
+    r = int(load_library().swaa_visible_pairs(int(N), int(window), int(n_sink)))
+    if r < 0:
+        raise SwaaError(SWAA_ERR_SHAPE, "invalid N / window / n_sink")
+    return r
+
+
+def swaa_attn_fwd_raw(q_ptr, k_ptr, v_ptr, out_ptr, lse_ptr, B, Hq, Hkv, N, D,
+                      window, n_sink, scale, stream_ptr) -> int:
+    """The C call itself, on raw addresses; returns the status code."""
+    return int(load_library().swaa_attn_fwd(
+        q_ptr, k_ptr, v_ptr, out_ptr, lse_ptr, B, Hq, Hkv, N, D, window, n_sink, scale, stream_ptr))
+
+
+def swaa_attn_fwd(q, k, v, window: int, n_sink: int, scale: float | None = None,
+                  out=None, lse=None, stream=None):
+    """SWA + sink attention forward on the GPU.
+
+    q: bf16 [B, Hq, N, D]; k, v: bf16 [B, Hkv, N, D]; all contiguous CUDA/HIP
+    tensors on one device.  Returns (out bf16 [B, Hq, N, D], lse fp32 [B, Hq, N]).
+    The call is asynchronous on `stream` (default: torch's current stream).
+    """
+    import torch
+
+    for name, t in (("q", q), ("k", k), ("v", v)):
+        if t.dtype != torch.bfloat16:
+            raise TypeError(f"{name} must be bfloat16")
+        if not t.is_cuda:
+            raise ValueError(f"{name} must live on the GPU")
+        if not t.is_contiguous() or t.dim() != 4:
+            raise ValueError(f"{name} must be a contiguous [B, H, N, D] tensor")
+    B, Hq, N, D = q.shape
+    if k.shape != v.shape or k.shape[0] != B or k.shape[2] != N or k.shape[3] != D:
+        raise ValueError("k and v must be [B, Hkv, N, D] with q's B, N, D")
+    if k.device != q.device or v.device != q.device:
+        raise ValueError("q, k, v must be on the same device")
+    Hkv = k.shape[1]
+    if scale is None:
+        scale = 1.0 / math.sqrt(D)
+    with torch.cuda.device(q.device):
+        if out is None:
+            out = torch.empty_like(q)
+        if lse is None:
+            lse = torch.empty((B, Hq, N), dtype=torch.float32, device=q.device)
+        if out.shape != q.shape or out.dtype != torch.bfloat16 or not out.is_contiguous():
+            raise ValueError("out must be a contiguous bf16 tensor shaped like q")
+        if lse.shape != (B, Hq, N) or lse.dtype != torch.float32 or not lse.is_contiguous():
+            raise ValueError("lse must be a contiguous fp32 [B, Hq, N] tensor")
+        if stream is None:
+            stream = torch.cuda.current_stream(q.device)
+        sptr = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+        rc = swaa_attn_fwd_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                               B, Hq, Hkv, N, D, int(window), int(n_sink), float(scale), sptr)
+    if rc != SWAA_OK:
+        raise SwaaError(rc, swaa_status_string(rc))
+    return out, lse

@@ -1,0 +1,438 @@
+// Sliding-window + sink ("keep first k") attention forward for gfx950 (MI355X).
+//
+// The mask is the one of the paper's Sec. 3.2.1 / Fig. 1b (local window AND
+// the initial k tokens, causal) and, with a window at least as long as the
+// context, the full-attention layers of Sec. 3.1.2.  The tiling, the
+// schedule and the register layout below are this library's own design for
+// CDNA4; the paper only says that the mask lives inside a flash-style kernel.
+//
+// Shape of the kernel
+//   * One workgroup = 4 wavefronts = 256 "query rows" that share one KV head:
+//     hpb query heads (4, 2 or 1) x 256/hpb consecutive positions.  Each wave
+//     owns 64 positions of one head, so K/V tiles staged in LDS are reused by
+//     every query head of the GQA group and the dense band per wave is only
+//     W + 64 keys wide.
+//   * KV tiles of 64 keys.  A workgroup visits only the tiles that hold sink
+//     keys [0, S) or band keys (first position - W, last position]; a wave
+//     skips the MFMA work of tiles that lie outside its own 64 positions' band
+//     and applies the element mask only on tiles that cross an edge.
+//   * S^T = K Q^T with v_mfma_f32_32x32x16_bf16 (A = K from LDS, B = Q kept in
+//     registers): a lane then owns one query column, so the row maximum and
+//     row sum are in-lane reductions plus one half-wave swap, and the bf16
+//     P^T values are already in the B-operand layout of O^T += V^T P^T.
+//   * V^T fragments come from row-major V in LDS through the transposing read
+//     ds_read_b64_tr_b16.
+//   * Online softmax in fp32 in the exp2 domain; O is rescaled only when some
+//     row maximum in the wave moved.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+
+#include "swaa.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kBk = 64;        // keys per KV tile
+constexpr int kThreads = 256;  // 4 waves
+constexpr int kWaveRows = 64;  // query positions per wave
+constexpr int kWgRows = 256;   // query rows (head x position) per workgroup
+constexpr int kXcds = 8;
+
+struct FwdParams {
+    const __bf16 *q;
+    const __bf16 *k;
+    const __bf16 *v;
+    __bf16 *out;
+    float *lse;
+    int B, Hq, Hkv, N;
+    int W, S;  // clamped to [1, N] and [0, N]
+    int G;     // Hq / Hkv
+    float scale, scale_log2;
+    // work decomposition: per (b, kv head) "pair" the query heads are cut into
+    // n4 groups of 4 heads (64-position tiles), at most one group of 2 heads
+    // (128-position tiles) and at most one single head (256-position tiles).
+    int n4, has2, has1;
+    int nt64, nt128, nt256;
+    int tiles_per_pair;
+    long long total_items;
+    long long chunk;  // items per XCD
+};
+
+__device__ __forceinline__ float half_swap_max(float x) {
+    // lanes l and l^32 hold partial results for the same query column
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_swap_sum(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+template <int D>
+struct Tile {
+    static constexpr int kChunksPerRow = D / 8;                        // 16-byte chunks
+    static constexpr int kChunks = kBk * kChunksPerRow;                // per K or V tile
+    static constexpr int kChunksPerThread = kChunks / kThreads;       // 4 (D=128) or 2 (D=64)
+    static constexpr int kKStride = D + 8;                             // bf16 elements, K rows
+    static constexpr int kVStride = D + 32;                            // bf16 elements, V rows
+    static constexpr int kKElems = kBk * kKStride;
+    static constexpr int kVElems = kBk * kVStride;
+};
+
+template <int D>
+__global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p) {
+    using T = Tile<D>;
+    constexpr int KS = D / 16;  // k-steps of the QK^T contraction
+    constexpr int DB = D / 32;  // 32-wide blocks of the head dimension
+
+    __shared__ __attribute__((aligned(16))) __bf16 Ks[T::kKElems];
+    __shared__ __attribute__((aligned(16))) __bf16 Vs[T::kVElems];
+
+    // ---- which piece of work is this workgroup's --------------------------
+    // Workgroups are handed to the 8 XCDs round-robin; giving XCD x the x-th
+    // contiguous chunk of the work list keeps the tiles of one KV head (whose
+    // K/V bands overlap) behind one L2.
+    const long long bid = blockIdx.x;
+    const long long slot = bid / kXcds;
+    const long long item = (bid % kXcds) * p.chunk + slot;
+    if (slot >= p.chunk || item >= p.total_items) return;
+    const int pair = (int)(item / p.tiles_per_pair);
+    int r = (int)(item % p.tiles_per_pair);
+    const int b = pair / p.Hkv;
+    const int kvh = pair % p.Hkv;
+    int hpb, h0, pt;
+    if (r < p.n4 * p.nt64) {
+        hpb = 4;
+        h0 = 4 * (r / p.nt64);
+        pt = p.nt64 - 1 - (r % p.nt64);  // long rows first
+    } else {
+        r -= p.n4 * p.nt64;
+        if (p.has2 && r < p.nt128) {
+            hpb = 2;
+            h0 = 4 * p.n4;
+            pt = p.nt128 - 1 - r;
+        } else {
+            if (p.has2) r -= p.nt128;
+            hpb = 1;
+            h0 = p.G - 1;
+            pt = p.nt256 - 1 - r;
+        }
+    }
+    const int pos_per_wg = kWgRows / hpb;
+    const int N = p.N, W = p.W, S = p.S;
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6;
+    const int lane = tid & 63;
+    const int l32 = lane & 31;
+    const int hf = lane >> 5;  // which half of the wave
+
+    const int head = kvh * p.G + h0 + (wave % hpb);
+    const int wg_p0 = pt * pos_per_wg;                      // first position of the workgroup
+    const int wg_p1 = min(N, wg_p0 + pos_per_wg) - 1;       // last valid position
+    const int p0 = wg_p0 + (wave / hpb) * kWaveRows;        // first position of this wave
+    const bool wave_active = p0 < N;
+    const int plast = min(p0 + kWaveRows, N) - 1;           // last valid position of this wave
+
+    // ---- KV tiles this workgroup visits -------------------------------------
+    const int band_lo = max(0, wg_p0 - W + 1);
+    const int t_band_lo = band_lo / kBk;
+    const int t_hi = wg_p1 / kBk;
+    const int n_sink_tiles = min((min(S, band_lo) + kBk - 1) / kBk, t_band_lo);
+    // tile order: 0 .. n_sink_tiles-1, then t_band_lo .. t_hi
+
+    const size_t kv_base = ((size_t)b * p.Hkv + kvh) * (size_t)N * D;
+    const __bf16 *kg = p.k + kv_base;
+    const __bf16 *vg = p.v + kv_base;
+    const size_t q_base = ((size_t)b * p.Hq + head) * (size_t)N * D;
+
+    // ---- Q fragments (B operand of S^T = K Q^T), kept for the whole loop ----
+    bf16x8 qf[2][KS];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        const int row = min(p0 + 32 * qb + l32, N - 1);
+        const __bf16 *src = p.q + q_base + (size_t)row * D + 8 * hf;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            qf[qb][ks] = *reinterpret_cast<const bf16x8 *>(src + 16 * ks);
+    }
+
+    f32x16 oacc[DB][2];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[db][qb][e] = 0.f;
+    float m_run[2] = {-INFINITY, -INFINITY};
+    float l_run[2] = {0.f, 0.f};
+
+    // ---- staging: global -> registers -> LDS --------------------------------
+    u32x4 kreg[T::kChunksPerThread], vreg[T::kChunksPerThread];
+    auto load_tile = [&](int t) {
+#pragma unroll
+        for (int c = 0; c < T::kChunksPerThread; ++c) {
+            const int id = c * kThreads + tid;
+            const int row = min(t * kBk + id / T::kChunksPerRow, N - 1);  // tail rows are masked later
+            const int col = (id % T::kChunksPerRow) * 8;
+            kreg[c] = *reinterpret_cast<const u32x4 *>(kg + (size_t)row * D + col);
+            vreg[c] = *reinterpret_cast<const u32x4 *>(vg + (size_t)row * D + col);
+        }
+    };
+    auto store_tile = [&]() {
+#pragma unroll
+        for (int c = 0; c < T::kChunksPerThread; ++c) {
+            const int id = c * kThreads + tid;
+            const int row = id / T::kChunksPerRow;
+            const int col = (id % T::kChunksPerRow) * 8;
+            *reinterpret_cast<u32x4 *>(&Ks[row * T::kKStride + col]) = kreg[c];
+            *reinterpret_cast<u32x4 *>(&Vs[row * T::kVStride + col]) = vreg[c];
+        }
+    };
+    auto next_tile = [&](int t) {
+        int n = t + 1;
+        if (n == n_sink_tiles && n < t_band_lo) n = t_band_lo;
+        return n;
+    };
+
+    int t = (n_sink_tiles > 0) ? 0 : t_band_lo;
+    load_tile(t);
+    store_tile();
+    __syncthreads();
+
+    const float c2 = p.scale_log2;
+
+    while (true) {
+        const int tn = next_tile(t);
+        const bool has_next = tn <= t_hi;
+        if (has_next) load_tile(tn);  // in flight while this tile is computed
+
+        const int k0 = t * kBk;
+        const int k_last = k0 + kBk - 1;
+        // per-wave classification of the tile against this wave's 64 positions
+        const bool in_future = k0 > plast;
+        const bool before_band = (k_last < p0 - W + 1) && (k0 >= S);
+        if (wave_active && !in_future && !before_band) {
+            const bool unmasked = (k_last <= p0) && ((k0 > p0 + kWaveRows - 1 - W) || (k_last < S));
+
+            // ---- S^T = K Q^T : [64 keys] x [64 queries] ----
+            f32x16 sacc[2][2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) sacc[kb][qb][e] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb) {
+                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(
+                        &Ks[(32 * kb + l32) * T::kKStride + 16 * ks + 8 * hf]);
+#pragma unroll
+                    for (int qb = 0; qb < 2; ++qb)
+                        sacc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], sacc[kb][qb], 0, 0, 0);
+                }
+            }
+
+            // ---- mask (edge tiles only) ----
+            if (!unmasked) {
+#pragma unroll
+                for (int qb = 0; qb < 2; ++qb) {
+                    const int qpos = p0 + 32 * qb + l32;
+#pragma unroll
+                    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) {
+                            const int key = k0 + 32 * kb + 8 * (e / 4) + 4 * hf + (e % 4);
+                            const bool vis = (key <= qpos) && ((key > qpos - W) || (key < S));
+                            sacc[kb][qb][e] = vis ? sacc[kb][qb][e] : -INFINITY;
+                        }
+                }
+            }
+
+            // ---- online softmax; P^T packed to bf16 in B-operand order ----
+            bf16x8 pf[2][2][2];  // [kb][qb][16-key step]
+            float alpha[2];
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                float mx = sacc[0][qb][0];
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[kb][qb][e]);
+                mx = half_swap_max(mx);
+                const float m_new = fmaxf(m_run[qb], mx);
+                const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+                alpha[qb] = __builtin_amdgcn_exp2f((m_run[qb] - m_use) * c2);
+                const float mc = m_use * c2;
+                float rs = 0.f;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const float pe = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][e], c2, -mc));
+                        rs += pe;
+                        pf[kb][qb][e / 8][e % 8] = (__bf16)pe;
+                    }
+                }
+                rs = half_swap_sum(rs);
+                l_run[qb] = l_run[qb] * alpha[qb] + rs;
+                m_run[qb] = m_new;
+            }
+            // rescale O only if some row maximum in this wave moved
+            if (__any((alpha[0] != 1.f) || (alpha[1] != 1.f))) {
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) oacc[db][qb][e] *= alpha[qb];
+            }
+
+            // ---- O^T += V^T P^T ----
+            // For the 16-key step (kb, st) the half-wave hf contracts over keys
+            // 32kb + 16st + 4hf + {0..3, 8..11}, the order in which the S^T
+            // accumulator hands them out; V^T must use the same order.
+            const int grp = lane >> 4;  // 16-lane group of the transposing read
+            const int j16 = lane & 15;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+                for (int st = 0; st < 2; ++st) {
+                    const int krow = 32 * kb + 16 * st + 4 * hf + (j16 >> 2);
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) {
+                        const int col = 32 * db + 16 * (grp & 1) + 4 * (j16 & 3);
+                        const __bf16 *a0 = &Vs[krow * T::kVStride + col];
+                        const __bf16 *a1 = a0 + 8 * T::kVStride;
+                        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (s16x4 __attribute__((address_space(3))) *)(a0));
+                        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (s16x4 __attribute__((address_space(3))) *)(a1));
+                        const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                        const bf16x8 a = __builtin_bit_cast(bf16x8, av);
+#pragma unroll
+                        for (int qb = 0; qb < 2; ++qb)
+                            oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[kb][qb][st], oacc[db][qb], 0, 0, 0);
+                    }
+                }
+            }
+        }
+
+        if (!has_next) break;
+        __syncthreads();  // every wave is done reading this tile
+        store_tile();
+        __syncthreads();
+        t = tn;
+    }
+
+    // ---- epilogue: O / l -> bf16, lse = m*scale + ln(l) ----------------------
+    if (!wave_active) return;
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        const int qpos = p0 + 32 * qb + l32;
+        if (qpos >= N) continue;
+        const float inv_l = 1.f / l_run[qb];
+        __bf16 *orow = p.out + q_base + (size_t)qpos * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+#pragma unroll
+            for (int e4 = 0; e4 < 4; ++e4) {
+                bf16x4 o4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[db][qb][4 * e4 + e] * inv_l);
+                *reinterpret_cast<bf16x4 *>(orow + 32 * db + 8 * e4 + 4 * hf) = o4;
+            }
+        }
+        if (hf == 0)
+            p.lse[((size_t)b * p.Hq + head) * (size_t)N + qpos] =
+                (m_run[qb] * c2 + __builtin_amdgcn_logf(l_run[qb])) * 0.69314718055994530942f;
+    }
+}
+
+bool misaligned(const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) != 0; }
+
+}  // namespace
+
+extern "C" {
+
+long long swaa_visible_pairs(long long N, long long window, long long n_sink) {
+    if (N < 1 || window < 1 || n_sink < 0) return -1;
+    const long long W = window < N ? window : N;
+    const long long M = N - W;  // rows whose window no longer reaches key 0
+    long long pairs = W * (W + 1) / 2 + M * W;
+    // row i = W - 1 + x (x = 1..M) has x keys in front of its window; min(x, S) are sinks
+    const long long ramp = n_sink < M ? n_sink : M;
+    pairs += ramp * (ramp + 1) / 2 + (M - ramp) * n_sink;
+    return pairs;
+}
+
+const char *swaa_status_string(int status) {
+    switch (status) {
+        case SWAA_OK: return "ok";
+        case SWAA_ERR_NULL: return "null pointer argument";
+        case SWAA_ERR_SHAPE: return "size, window, sink count or scale out of range";
+        case SWAA_ERR_UNSUPPORTED: return "unsupported head dimension (64 and 128 are built)";
+        case SWAA_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case SWAA_ERR_LAUNCH: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+int swaa_version(void) { return 100; }
+
+int swaa_attn_fwd(const void *q, const void *k, const void *v, void *out, float *lse,
+                  int B, int Hq, int Hkv, int N, int D, int window, int n_sink,
+                  float scale, void *stream) {
+    if (!q || !k || !v || !out || !lse) return SWAA_ERR_NULL;
+    if (B < 1 || Hq < 1 || Hkv < 1 || N < 1 || D < 1) return SWAA_ERR_SHAPE;
+    if (Hq % Hkv != 0) return SWAA_ERR_SHAPE;
+    if (window < 1 || n_sink < 0) return SWAA_ERR_SHAPE;
+    if (!std::isfinite(scale) || !(scale > 0.f)) return SWAA_ERR_SHAPE;
+    if (D != 64 && D != 128) return SWAA_ERR_UNSUPPORTED;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(lse))
+        return SWAA_ERR_ALIGN;
+
+    FwdParams p;
+    p.q = static_cast<const __bf16 *>(q);
+    p.k = static_cast<const __bf16 *>(k);
+    p.v = static_cast<const __bf16 *>(v);
+    p.out = static_cast<__bf16 *>(out);
+    p.lse = lse;
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N;
+    p.W = window < N ? window : N;
+    p.S = n_sink < N ? n_sink : N;
+    p.G = Hq / Hkv;
+    p.scale = scale;
+    p.scale_log2 = scale * 1.44269504088896340736f;
+    p.n4 = p.G / 4;
+    p.has2 = (p.G % 4) >= 2 ? 1 : 0;
+    p.has1 = p.G % 2;
+    p.nt64 = (N + 63) / 64;
+    p.nt128 = (N + 127) / 128;
+    p.nt256 = (N + 255) / 256;
+    p.tiles_per_pair = p.n4 * p.nt64 + p.has2 * p.nt128 + p.has1 * p.nt256;
+    p.total_items = (long long)B * Hkv * p.tiles_per_pair;
+    p.chunk = (p.total_items + kXcds - 1) / kXcds;
+    const long long grid = p.chunk * kXcds;
+    if (grid > 0x7fffffffLL) return SWAA_ERR_SHAPE;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (D == 128)
+        hipLaunchKernelGGL(swaa_fwd_kernel<128>, dim3((unsigned)grid), dim3(kThreads), 0, s, p);
+    else
+        hipLaunchKernelGGL(swaa_fwd_kernel<64>, dim3((unsigned)grid), dim3(kThreads), 0, s, p);
+    return hipGetLastError() == hipSuccess ? SWAA_OK : SWAA_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -1,0 +1,68 @@
+"""Host-side checks of libswaa's C ABI: no GPU needed, nothing is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2512_10411_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load_library()
+    header = open(os.path.join(ROOT, "include", "swaa.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(swaa_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert binding.swaa_version() >= 100
+
+
+def brute_pairs(N, W, S):
+    return sum(1 for i in range(N) for j in range(i + 1) if (j > i - W) or (j < S))
+
+
+@pytest.mark.parametrize("N", [1, 2, 7, 33])
+def test_visible_pairs_matches_counting(N):
+    for W in range(1, N + 3):
+        for S in range(0, N + 3):
+            assert binding.swaa_visible_pairs(N, W, S) == brute_pairs(N, W, S), (N, W, S)
+
+
+def test_visible_pairs_of_benchmark_workloads():
+    # per-head counts of the benchmark definition's workloads
+    assert binding.swaa_visible_pairs(1024, 128, 4) == 126522
+    assert binding.swaa_visible_pairs(16384, 2048, 4) == 31515642
+    assert binding.swaa_visible_pairs(32768, 32768, 4) == 32768 * 32769 // 2
+    assert binding.swaa_visible_pairs(131072, 8192, 4) == 1040683002
+    with pytest.raises(binding.SwaaError):
+        binding.swaa_visible_pairs(0, 1, 0)
+
+
+def test_argument_errors_are_reported_before_any_launch():
+    f = binding.swaa_attn_fwd_raw
+    p = 4096  # a non-null, 16-byte aligned fake address; never dereferenced on these paths
+    ok = dict(B=1, Hq=4, Hkv=2, N=128, D=128, window=16, n_sink=2, scale=0.1)
+
+    def call(q=p, k=p, v=p, o=p, l=p, **kw):
+        a = dict(ok, **kw)
+        return f(q, k, v, o, l, a["B"], a["Hq"], a["Hkv"], a["N"], a["D"], a["window"], a["n_sink"], a["scale"], None)
+
+    assert call(q=None) == binding.SWAA_ERR_NULL
+    assert call(l=None) == binding.SWAA_ERR_NULL
+    assert call(B=0) == binding.SWAA_ERR_SHAPE
+    assert call(N=0) == binding.SWAA_ERR_SHAPE
+    assert call(Hq=3) == binding.SWAA_ERR_SHAPE
+    assert call(window=0) == binding.SWAA_ERR_SHAPE
+    assert call(n_sink=-1) == binding.SWAA_ERR_SHAPE
+    assert call(scale=0.0) == binding.SWAA_ERR_SHAPE
+    assert call(scale=float("nan")) == binding.SWAA_ERR_SHAPE
+    assert call(scale=float("inf")) == binding.SWAA_ERR_SHAPE
+    assert call(D=96) == binding.SWAA_ERR_UNSUPPORTED
+    assert call(k=p + 8) == binding.SWAA_ERR_ALIGN
+    assert call(o=p + 2) == binding.SWAA_ERR_ALIGN
+    for code in (0, -1, -2, -3, -4, -5, -99):
+        assert isinstance(binding.swaa_status_string(code), str) and binding.swaa_status_string(code)

@@ -1,0 +1,145 @@
+"""GPU parity: libswaa (through its C ABI) against the fp64 CPU oracle.
+
+Tolerances are the acceptance ones: bf16 O within 2e-2 max-abs and 2e-3
+mean-abs of the unrounded fp64 result, fp32 LSE within 1e-3.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import swaa_attn_oracle
+from paper_2512_10411_amd import binding
+from paper_2512_10411_amd.inputs import (WORKLOADS, bf16_bits_to_f32, f32_to_bf16_bits, make_qkv,
+                                         make_workload, sample_rows)
+from gpu_util import assert_parity, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def run_gpu(q, k, v, W, S, scale):
+    out, lse = binding.swaa_attn_fwd(to_device(q), to_device(k), to_device(v), W, S, scale)
+    torch.cuda.synchronize()
+    return out, lse
+
+
+def check(B, Hq, Hkv, N, D, W, S, seed, scale=None, k_mult=1.0, rows=None, tag=None):
+    scale = 1.0 / math.sqrt(D) if scale is None else scale
+    tag = tag or f"B{B} Hq{Hq} Hkv{Hkv} N{N} D{D} W{W} S{S}"
+    print(f"[case] {tag} seed {seed}", flush=True)
+    q, k, v = make_qkv(B, Hq, Hkv, N, D, seed, k_mult)
+    out, lse = run_gpu(q, k, v, W, S, scale)
+    ro, rl = swaa_attn_oracle(q, k, v, W, S, scale, rows=rows)
+    assert_parity(out, lse, ro, rl, rows=rows, tag=tag)
+
+
+# ---- small shapes, every row compared: tile interiors, edges and ragged tails
+@pytest.mark.parametrize("N", [1, 2, 63, 64, 65, 130, 257, 700])
+@pytest.mark.parametrize("D", [64, 128])
+def test_small_shapes_sweep_window_and_sinks(N, D):
+    seed = 1000 + N + D
+    for W in sorted({1, 2, 7, 63, 64, 65, 200, N, N + 5}):
+        for S in (0, 1, 4, 70):
+            check(1, 4, 1, N, D, W, S, seed)
+
+
+@pytest.mark.parametrize("G", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_gqa_group_sizes(G):
+    # every decomposition of a GQA group into 4-, 2- and 1-head workgroups
+    check(2, 2 * G, 2, 333, 128, 100, 3, seed=2000 + G)
+    check(1, G, 1, 515, 64, 65, 10, seed=2100 + G)
+
+
+@pytest.mark.parametrize("W,S", [(2000, 0), (2000, 10), (2048, 100), (127, 1000), (3000, 1000), (1, 0), (4096, 0)])
+def test_paper_parameter_grid_mid_length(W, S):
+    # window and keep-first values of the paper's tables (2k windows; k = 10, 100, 1000)
+    check(1, 8, 2, 4096 + 37, 128, W, S, seed=3000 + W + S)
+
+
+def test_full_causal_ignores_sinks_and_window_size():
+    q, k, v = make_qkv(1, 4, 2, 1500, 128, seed=41)
+    scale = 1 / math.sqrt(128)
+    o1, l1 = run_gpu(q, k, v, 1500, 0, scale)
+    o2, l2 = run_gpu(q, k, v, 2**31 - 1, 77, scale)
+    o3, l3 = run_gpu(q, k, v, 1501, 5000, scale)
+    assert torch.equal(o1, o2) and torch.equal(l1, l2) and torch.equal(o1, o3) and torch.equal(l1, l3)
+    ro, rl = swaa_attn_oracle(q, k, v, 1500, 0, scale)
+    assert_parity(o1, l1, ro, rl, tag="full causal N1500")
+
+
+def test_run_to_run_determinism():
+    q, k, v = make_qkv(2, 10, 2, 2048 + 99, 128, seed=42)
+    qd, kd, vd = to_device(q), to_device(k), to_device(v)
+    o1, l1 = binding.swaa_attn_fwd(qd, kd, vd, 512, 4)
+    o2, l2 = binding.swaa_attn_fwd(qd, kd, vd, 512, 4)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2) and torch.equal(l1, l2)
+
+
+def test_sink_heavy_scores_stress_rescaling():
+    # sink keys aligned with the mean query direction: the attention-sink
+    # pattern of Sec. 3.2.1; the running maximum is set by tile 0 for far rows
+    B, Hq, Hkv, N, D, W, S = 1, 4, 1, 3000, 128, 256, 4
+    q, k, v = make_qkv(B, Hq, Hkv, N, D, seed=43)
+    qf, kf = bf16_bits_to_f32(q), bf16_bits_to_f32(k)
+    qf[..., 0] = 3.0
+    kf[..., 0] = 0.0
+    kf[:, :, :S, 0] = 12.0
+    # and a late spike so that the maximum moves again inside the band
+    kf[:, :, 2500, 0] = 20.0
+    q, k = f32_to_bf16_bits(qf), f32_to_bf16_bits(kf)
+    scale = 1 / math.sqrt(D)
+    out, lse = run_gpu(q, k, v, W, S, scale)
+    ro, rl = swaa_attn_oracle(q, k, v, W, S, scale)
+    assert_parity(out, lse, ro, rl, tag="sink heavy")
+
+
+def test_caller_buffers_stream_and_errors():
+    q, k, v = make_qkv(1, 4, 4, 256, 64, seed=44)
+    qd, kd, vd = to_device(q), to_device(k), to_device(v)
+    out = torch.full_like(qd, 7.0)
+    lse = torch.full((1, 4, 256), 7.0, dtype=torch.float32, device="cuda")
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        o2, l2 = binding.swaa_attn_fwd(qd, kd, vd, 32, 2, out=out, lse=lse, stream=s)
+    s.synchronize()
+    assert o2.data_ptr() == out.data_ptr() and l2.data_ptr() == lse.data_ptr()
+    ro, rl = swaa_attn_oracle(q, k, v, 32, 2, 1 / 8)
+    assert_parity(out, lse, ro, rl, tag="caller buffers on side stream")
+    with pytest.raises(binding.SwaaError):
+        binding.swaa_attn_fwd(qd, kd, vd, 0, 0)
+    with pytest.raises(TypeError):
+        binding.swaa_attn_fwd(qd.float(), kd, vd, 8, 0)
+
+
+# ---- the benchmark definition's workloads -----------------------------------
+def test_workload_tiny_all_rows():
+    w = WORKLOADS["tiny"]
+    q, k, v = make_workload(w)
+    out, lse = run_gpu(q, k, v, w.window, w.n_sink, w.scale)
+    ro, rl = swaa_attn_oracle(q, k, v, w.window, w.n_sink, w.scale)
+    assert_parity(out, lse, ro, rl, tag="tiny (all rows)")
+
+
+@pytest.mark.parametrize("names", [("mid",), ("pair32k_swa", "pair32k_full"), ("batched",),
+                                   ("long128k_swa", "long128k_full")])
+def test_workload_full_size_sampled_rows(names):
+    # full-size launch exactly as the benchmark times it; 256 sampled rows per head
+    w0 = WORKLOADS[names[0]]
+    print(f"[gen] {names} ...", flush=True)
+    q, k, v = make_workload(w0)
+    qd, kd, vd = to_device(q), to_device(k), to_device(v)
+    for name in names:
+        w = WORKLOADS[name]
+        assert w.seed == w0.seed
+        rows = sample_rows(w.N, w.window, w.n_sink, count=256, seed=w.seed)
+        print(f"[gpu] {name}", flush=True)
+        out, lse = binding.swaa_attn_fwd(qd, kd, vd, w.window, w.n_sink, w.scale)
+        torch.cuda.synchronize()
+        assert torch.isfinite(lse).all()
+        print(f"[oracle] {name}: {len(rows)} rows x {w.B * w.Hq} heads", flush=True)
+        ro, rl = swaa_attn_oracle(q, k, v, w.window, w.n_sink, w.scale, rows=rows)
+        assert_parity(out, lse, ro, rl, rows=rows, tag=name)
+        del out, lse
