@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""Benchmark of the SWA + sink prefill attention forward on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+One "step" is one call of swaa_attn_fwd (the whole hot path: tile schedule,
+Q/K/V staging, QK^T, mask, online softmax, PV, epilogue) over one batch of
+seeded synthetic bf16 inputs that are already resident in HBM.  The default
+workload is the mid-size prefill layer the metric is quoted on (B=1, Hq=32,
+Hkv=8, N=16384, D=128, W=2048, S=4).  Prints ONE JSON line: effective TFLOP/s
+(4*D flops per visible query-key pair per head), the MFMA roofline fraction of
+the kernel measured with HIP events on the launch stream, and the fp64 CPU
+oracle timed on this machine's host cores on a bounded sample of the same rows.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "SWA+sink prefill attention effective TFLOP/s and % bf16 MFMA peak, 1 MI355X"
+BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="mid")
+    ap.add_argument("--no-cpu-baseline", action="store_true",
+                    help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0,
+                    help="target CPU time of the oracle sample")
+    ap.add_argument("--traffic-bytes", type=float, default=None,
+                    help="HBM bytes per launch from a separate rocprofv3 --pmc run, if known")
+    return ap.parse_args()
+
+
+def cpu_baseline(w, q, k, v, target_s):
+    """Time the oracle as it stands on a bounded sample of this workload's rows."""
+    import numpy as np
+    from oracle import oracle_num_threads, swaa_attn_oracle
+    from paper_2512_10411_amd.binding import swaa_visible_pairs
+
+    def pairs_of(rows):
+        r = np.asarray(rows, dtype=np.int64)
+        vis = np.minimum(r + 1, min(w.window, w.N)) + np.clip(r - w.window + 1, 0, min(w.n_sink, w.N))
+        return int(vis.sum()) * w.B * w.Hq
+
+    rng = np.random.Generator(np.random.Philox(w.seed + 5))
+    order = rng.permutation(w.N)
+    pilot = np.sort(order[:8])
+    t0 = time.perf_counter()
+    swaa_attn_oracle(q, k, v, w.window, w.n_sink, w.scale, rows=pilot)
+    t_pilot = max(time.perf_counter() - t0, 1e-4)
+    rate = pairs_of(pilot) / t_pilot
+    mean_pairs_per_row = swaa_visible_pairs(w.N, w.window, w.n_sink) * w.B * w.Hq / w.N
+    n_rows = int(min(w.N, max(8, target_s * rate / mean_pairs_per_row)))
+    rows = np.sort(order[:n_rows])
+    t0 = time.perf_counter()
+    swaa_attn_oracle(q, k, v, w.window, w.n_sink, w.scale, rows=rows)
+    dt = time.perf_counter() - t0
+    pairs = pairs_of(rows)
+    return {
+        "value": 4.0 * w.D * pairs / dt / 1e12,
+        "unit": "TFLOP/s",
+        "cores": oracle_num_threads(),
+        "kind": "oracle",
+        "sample": f"{n_rows} seeded random query rows x all {w.B * w.Hq} (batch, head) of workload "
+                  f"'{w.name}': {pairs} visible pairs in {dt:.2f} s; fp64, OpenMP over rows",
+        "seconds": dt,
+        "pairs_per_s": pairs / dt,
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); "
+              f"--gpus {args.gpus} is not supported, use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2512_10411_amd import binding
+    from paper_2512_10411_amd.inputs import WORKLOADS, make_workload
+
+    if args.workload not in WORKLOADS:
+        print(f"unknown workload {args.workload}; choose from {sorted(WORKLOADS)}", file=sys.stderr)
+        return 2
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (there is no CPU fallback for the product path)", file=sys.stderr)
+        return 2
+    w = WORKLOADS[args.workload]
+    binding.load_library()
+
+    q, k, v = make_workload(w)
+
+    def dev(bits):
+        import numpy as np
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+
+    qd, kd, vd = dev(q), dev(k), dev(v)
+    out = torch.empty_like(qd)
+    lse = torch.empty((w.B, w.Hq, w.N), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        binding.swaa_attn_fwd(qd, kd, vd, w.window, w.n_sink, w.scale, out=out, lse=lse, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # K steps, wall clock bracketed by synchronisation; every launch also
+    # bracketed by HIP events on the launch stream for the per-kernel average
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record(stream)
+        step()
+        b.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = [a.elapsed_time(b) for a, b in ev]
+    kern_avg_ms = sum(kern_ms) / len(kern_ms)
+    ms_per_step = wall * 1e3 / args.steps
+
+    pairs = binding.swaa_visible_pairs(w.N, w.window, w.n_sink) * w.B * w.Hq
+    flops = 4.0 * w.D * pairs
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    achieved = flops / (kern_avg_ms * 1e-3) / 1e12
+
+    res = {
+        "metric": METRIC,
+        "value": value,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "N": w.N, "D": w.D,
+                   "window": w.window, "n_sink": w.n_sink, "seed": w.seed, "k_mult": w.k_mult,
+                   "visible_pairs": pairs, "flops_per_step": flops,
+                   "pct_bf16_mfma_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": args.traffic_bytes,
+                     "kernel": "swaa_fwd_kernel<%d>" % w.D, "kernel_avg_ms": kern_avg_ms,
+                     "kernel_min_ms": min(kern_ms), "kernel_median_ms": sorted(kern_ms)[len(kern_ms) // 2]},
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(w, q, k, v, args.cpu_seconds)
+        res["cpu_baseline"]["gpu_over_cpu"] = value / res["cpu_baseline"]["value"]
+    print(json.dumps(res), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
