@@ -10,7 +10,8 @@ import subprocess
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
-SOURCES = [os.path.join(PKG, "csrc", "swaa_attn_fwd.hip")]
+CSRC = os.path.join(PKG, "csrc")
+SOURCES = [os.path.join(CSRC, f) for f in ("swaa_api.hip", "swaa_fwd_simple.hip", "swaa_fwd_pipelined.hip")]
 LIB = os.path.join(PKG, "libswaa.so")
 
 HIPCC_FLAGS = [
@@ -18,7 +19,7 @@ HIPCC_FLAGS = [
     "-Wall", "-Wno-unused-value",
     # packed fp32 VALU forms are kept out of the generated code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-I", os.path.join(ROOT, "include"),
+    "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG, "csrc"),
 ]
 
 

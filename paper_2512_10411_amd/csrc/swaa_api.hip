@@ -1,0 +1,98 @@
+// C ABI of libswaa: argument checks, work decomposition, kernel choice.
+#include <cmath>
+#include <cstdint>
+#include <cstdlib>
+#include <string>
+
+#include "swaa.h"
+#include "swaa_common.h"
+
+using swaa::FwdParams;
+using swaa::kXcds;
+
+namespace {
+
+bool misaligned(const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) != 0; }
+
+// SWAA_KERNEL=simple selects the plain (unpipelined) kernel for head dimension
+// 128 too; meant for debugging and A/B timing.  Read once.
+bool use_simple_kernel() {
+    static const bool simple = [] {
+        const char *e = std::getenv("SWAA_KERNEL");
+        return e && std::string(e) == "simple";
+    }();
+    return simple;
+}
+
+}  // namespace
+
+extern "C" {
+
+long long swaa_visible_pairs(long long N, long long window, long long n_sink) {
+    if (N < 1 || window < 1 || n_sink < 0) return -1;
+    const long long W = window < N ? window : N;
+    const long long M = N - W;  // rows whose window no longer reaches key 0
+    long long pairs = W * (W + 1) / 2 + M * W;
+    // row i = W - 1 + x (x = 1..M) has x keys in front of its window; min(x, S) are sinks
+    const long long ramp = n_sink < M ? n_sink : M;
+    pairs += ramp * (ramp + 1) / 2 + (M - ramp) * n_sink;
+    return pairs;
+}
+
+const char *swaa_status_string(int status) {
+    switch (status) {
+        case SWAA_OK: return "ok";
+        case SWAA_ERR_NULL: return "null pointer argument";
+        case SWAA_ERR_SHAPE: return "size, window, sink count or scale out of range";
+        case SWAA_ERR_UNSUPPORTED: return "unsupported head dimension (64 and 128 are built)";
+        case SWAA_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case SWAA_ERR_LAUNCH: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+int swaa_version(void) { return 100; }
+
+int swaa_attn_fwd(const void *q, const void *k, const void *v, void *out, float *lse,
+                  int B, int Hq, int Hkv, int N, int D, int window, int n_sink,
+                  float scale, void *stream) {
+    if (!q || !k || !v || !out || !lse) return SWAA_ERR_NULL;
+    if (B < 1 || Hq < 1 || Hkv < 1 || N < 1 || D < 1) return SWAA_ERR_SHAPE;
+    if (Hq % Hkv != 0) return SWAA_ERR_SHAPE;
+    if (window < 1 || n_sink < 0) return SWAA_ERR_SHAPE;
+    if (!std::isfinite(scale) || !(scale > 0.f)) return SWAA_ERR_SHAPE;
+    if (D != 64 && D != 128) return SWAA_ERR_UNSUPPORTED;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(lse))
+        return SWAA_ERR_ALIGN;
+
+    FwdParams p;
+    p.q = static_cast<const __bf16 *>(q);
+    p.k = static_cast<const __bf16 *>(k);
+    p.v = static_cast<const __bf16 *>(v);
+    p.out = static_cast<__bf16 *>(out);
+    p.lse = lse;
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N;
+    p.W = window < N ? window : N;
+    p.S = n_sink < N ? n_sink : N;
+    p.G = Hq / Hkv;
+    p.scale = scale;
+    p.scale_log2 = scale * 1.44269504088896340736f;
+    p.n4 = p.G / 4;
+    p.has2 = (p.G % 4) >= 2 ? 1 : 0;
+    p.has1 = p.G % 2;
+    p.nt64 = (N + 63) / 64;
+    p.nt128 = (N + 127) / 128;
+    p.nt256 = (N + 255) / 256;
+    p.tiles_per_pair = p.n4 * p.nt64 + p.has2 * p.nt128 + p.has1 * p.nt256;
+    p.total_items = (long long)B * Hkv * p.tiles_per_pair;
+    p.chunk = (p.total_items + kXcds - 1) / kXcds;
+    const long long grid = p.chunk * kXcds;
+    if (grid > 0x7fffffffLL) return SWAA_ERR_SHAPE;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const hipError_t err = (D == 128 && !use_simple_kernel()) ? swaa::launch_fwd_pipelined_d128(p, s)
+                                                              : swaa::launch_fwd_simple(p, D, s);
+    return err == hipSuccess ? SWAA_OK : SWAA_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -1,0 +1,102 @@
+// Types, the kernel parameter block and the work decomposition shared by the
+// attention-forward kernels of libswaa (gfx950 only).
+#ifndef SWAA_COMMON_H_
+#define SWAA_COMMON_H_
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace swaa {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kBk = 64;        // keys per KV tile
+constexpr int kThreads = 256;  // 4 waves per workgroup
+constexpr int kWaveRows = 64;  // query positions per wave
+constexpr int kWgRows = 256;   // query rows (head x position) per workgroup
+constexpr int kXcds = 8;       // accelerator dies; workgroups are dealt to them round-robin
+
+struct FwdParams {
+    const __bf16 *q;
+    const __bf16 *k;
+    const __bf16 *v;
+    __bf16 *out;
+    float *lse;
+    int B, Hq, Hkv, N;
+    int W, S;  // clamped to [1, N] and [0, N]
+    int G;     // Hq / Hkv
+    float scale, scale_log2;
+    // Work decomposition.  Per (batch, KV head) "pair" the G query heads are
+    // cut into n4 groups of 4 heads (workgroups of 4 heads x 64 positions), at
+    // most one group of 2 heads (2 x 128) and at most one single head (1 x 256),
+    // so that every workgroup is 4 waves x 64 query rows on one KV head.
+    int n4, has2, has1;
+    int nt64, nt128, nt256;
+    int tiles_per_pair;
+    long long total_items;
+    long long chunk;  // work items per XCD
+};
+
+// What one workgroup computes.
+struct WorkItem {
+    int b, kvh;  // batch entry, KV head
+    int hpb;     // query heads in this workgroup: 4, 2 or 1
+    int h0;      // first of them, relative to the GQA group
+    int pt;      // position tile of 256/hpb positions
+};
+
+// Workgroups reach the 8 XCDs round-robin; XCD x takes the x-th contiguous
+// chunk of the work list, so the position tiles of one KV head, whose K/V
+// bands overlap, run behind the same L2.  Inside a pair, long rows go first.
+__device__ __forceinline__ bool decode_work(const FwdParams &p, WorkItem &w) {
+    const long long bid = blockIdx.x;
+    const long long slot = bid / kXcds;
+    const long long item = (bid % kXcds) * p.chunk + slot;
+    if (slot >= p.chunk || item >= p.total_items) return false;
+    const int pair = (int)(item / p.tiles_per_pair);
+    int r = (int)(item % p.tiles_per_pair);
+    w.b = pair / p.Hkv;
+    w.kvh = pair % p.Hkv;
+    if (r < p.n4 * p.nt64) {
+        w.hpb = 4;
+        w.h0 = 4 * (r / p.nt64);
+        w.pt = p.nt64 - 1 - (r % p.nt64);
+        return true;
+    }
+    r -= p.n4 * p.nt64;
+    if (p.has2 && r < p.nt128) {
+        w.hpb = 2;
+        w.h0 = 4 * p.n4;
+        w.pt = p.nt128 - 1 - r;
+        return true;
+    }
+    if (p.has2) r -= p.nt128;
+    w.hpb = 1;
+    w.h0 = p.G - 1;
+    w.pt = p.nt256 - 1 - r;
+    return true;
+}
+
+// Lanes l and l^32 hold partial results for the same query column.
+__device__ __forceinline__ float half_swap_max(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_swap_sum(float x) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Launchers (one per kernel family); return the HIP error of the launch.
+hipError_t launch_fwd_simple(const FwdParams &p, int D, hipStream_t stream);
+hipError_t launch_fwd_pipelined_d128(const FwdParams &p, hipStream_t stream);
+
+}  // namespace swaa
+
+#endif  // SWAA_COMMON_H_

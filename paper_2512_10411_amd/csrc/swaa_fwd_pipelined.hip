@@ -1,0 +1,360 @@
+// Software-pipelined SWA + sink attention forward, head dimension 128, gfx950.
+//
+// Same mask (paper Sec. 3.2.1 / Fig. 1b; full attention of Sec. 3.1.2 when the
+// window covers the context), same workgroup shape and tile schedule as the
+// plain kernel; what differs is how a wave walks the key axis:
+//
+//   * K and V tiles (64 keys) travel HBM -> LDS with global_load_lds_dwordx4
+//     (no register staging) into two rings of three tiles each, XOR-swizzled
+//     in 16-byte chunks so that the MFMA operand reads are bank-conflict free.
+//     One barrier per tile.
+//   * A wave works on half tiles of 32 keys in a three-stage pipeline:
+//     while the softmax of half n runs on the VALU, the matrix pipe computes
+//     S^T = K Q^T of half n+1 and O^T += V^T P^T of half n-1.  The three are
+//     independent, so the MFMAs and the exponentials of one wave overlap.
+//   * The running maximum is a reference value that moves only when a row's
+//     maximum grows by more than 2^8 (in the exp2 domain); O and the row sum
+//     are rescaled only then.  Results are mathematically unchanged, values of
+//     P stay below 2^8, and the rescale of the 64x128 accumulator all but
+//     disappears from the steady state.
+#include <atomic>
+
+#include "swaa_common.h"
+
+namespace swaa {
+namespace {
+
+constexpr int kD = 128;
+constexpr int kKS = kD / 16;  // k-steps of K Q^T
+constexpr int kDB = kD / 32;  // 32-wide blocks of the head dimension
+constexpr int kStages = 3;
+constexpr int kTileBytes = kBk * kD * 2;            // 16 KiB
+constexpr int kHalfBytes = kTileBytes / 2;          // one 32-key half
+constexpr int kVRing = kStages * kTileBytes;        // V ring follows the K ring
+constexpr int kSmemBytes = 2 * kStages * kTileBytes;  // 96 KiB
+constexpr float kRefSlack = 8.f;  // log2 units a row maximum may exceed its reference
+
+extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+typedef char __attribute__((address_space(3))) * lds_ptr;
+typedef const char __attribute__((address_space(1))) * gbl_ptr;
+
+// S^T (32 keys x 64 queries) = K_half Q^T.  kaddr: this lane's byte address of
+// row (32*half + lane%32), chunk (lane/32) of the K tile, swizzle applied.
+__device__ __forceinline__ void qk_half(uint32_t kaddr, const bf16x8 (&qf)[2][kKS], f32x16 (&s)[2]) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        s[0][e] = 0.f;
+        s[1][e] = 0.f;
+    }
+#pragma unroll
+    for (int ks = 0; ks < kKS; ++ks) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(smem + (kaddr ^ (uint32_t)(ks << 5)));
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][ks], s[0], 0, 0, 0);
+        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[1][ks], s[1], 0, 0, 0);
+    }
+}
+
+// O^T (128 x 64 queries) += V_half^T P^T.  vaddr: this lane's byte address in
+// the V tile for the transposing read of head-dimension block 0, step 0.
+__device__ __forceinline__ void pv_half(uint32_t vaddr, const bf16x8 (&pf)[2][2], f32x16 (&o)[kDB][2]) {
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+#pragma unroll
+        for (int db = 0; db < kDB; ++db) {
+            const uint32_t a0 = (vaddr ^ (uint32_t)(db << 6)) + st * 16 * 256;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(smem + a0));
+            const s16x4 hi =
+                __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(smem + a0 + 8 * 256));
+            const bf16x8 a = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            o[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[0][st], o[db][0], 0, 0, 0);
+            o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[1][st], o[db][1], 0, 0, 0);
+        }
+    }
+}
+
+struct RowState {
+    float m[2];  // reference maximum per query column (raw score units)
+    float l[2];  // sum of exp2((s - m) * c2)
+};
+
+// Mask (optional), reference-maximum update, exponentials, row sums and the
+// bf16 P^T fragments of one half tile.  alpha[qb] is the factor the O
+// accumulator of query block qb must be multiplied with (1 when unchanged).
+template <bool kMask>
+__device__ __forceinline__ void softmax_half(f32x16 (&s)[2], int k0h, int p0, int W, int S, int l32, int hf, float c2,
+                                             RowState &st, bf16x8 (&pf)[2][2], float (&alpha)[2]) {
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        if (kMask) {
+            const int qpos = p0 + 32 * qb + l32;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int key = k0h + 8 * (e / 4) + 4 * hf + (e % 4);
+                const bool vis = (key <= qpos) && ((key > qpos - W) || (key < S));
+                s[qb][e] = vis ? s[qb][e] : -INFINITY;
+            }
+        }
+        float mx = s[qb][0];
+#pragma unroll
+        for (int e = 1; e < 16; ++e) mx = fmaxf(mx, s[qb][e]);
+        mx = half_swap_max(mx);
+        const float m_old = st.m[qb];
+        const float m_new = fmaxf(m_old, mx);
+        const bool move = (m_new - m_old) * c2 > kRefSlack;  // false when both are -inf
+        const float m_ref = move ? m_new : m_old;
+        const float m_use = (kMask && m_ref == -INFINITY) ? 0.f : m_ref;
+        alpha[qb] = move ? __builtin_amdgcn_exp2f((m_old - m_use) * c2) : 1.f;
+        const float mc = m_use * c2;
+        float rs = 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const float pe = __builtin_amdgcn_exp2f(fmaf(s[qb][e], c2, -mc));
+            rs += pe;
+            pf[qb][e / 8][e % 8] = (__bf16)pe;
+        }
+        rs = half_swap_sum(rs);
+        st.l[qb] = st.l[qb] * alpha[qb] + rs;
+        st.m[qb] = m_ref;
+    }
+}
+
+__device__ __forceinline__ void rescale(f32x16 (&o)[kDB][2], const float (&alpha)[2]) {
+    if (__any((alpha[0] != 1.f) || (alpha[1] != 1.f))) {
+#pragma unroll
+        for (int db = 0; db < kDB; ++db)
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) o[db][qb][e] *= alpha[qb];
+    }
+}
+
+__global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const FwdParams p) {
+    WorkItem wi;
+    if (!decode_work(p, wi)) return;
+    const int hpb = wi.hpb;
+    const int pos_per_wg = kWgRows / hpb;
+    const int N = p.N, W = p.W, S = p.S;
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6;
+    const int lane = tid & 63;
+    const int l32 = lane & 31;
+    const int hf = lane >> 5;
+
+    const int head = wi.kvh * p.G + wi.h0 + (wave % hpb);
+    const int wg_p0 = wi.pt * pos_per_wg;
+    const int wg_p1 = min(N, wg_p0 + pos_per_wg) - 1;
+    const int p0 = wg_p0 + (wave / hpb) * kWaveRows;
+    const bool wave_active = p0 < N;
+    const int plast = min(p0 + kWaveRows, N) - 1;
+
+    // visited KV tiles: sink tiles 0 .. n_sink_tiles-1, then band tiles t_band_lo .. t_hi
+    const int band_lo = max(0, wg_p0 - W + 1);
+    const int t_band_lo = band_lo / kBk;
+    const int t_hi = wg_p1 / kBk;
+    const int n_sink_tiles = min((min(S, band_lo) + kBk - 1) / kBk, t_band_lo);
+    const int J = n_sink_tiles + (t_hi - t_band_lo + 1);
+    auto tile_of = [&](int j) { return j < n_sink_tiles ? j : j - n_sink_tiles + t_band_lo; };
+
+    const size_t kv_base = ((size_t)wi.b * p.Hkv + wi.kvh) * (size_t)N * kD;
+    const __bf16 *kg = p.k + kv_base;
+    const __bf16 *vg = p.v + kv_base;
+    const size_t q_base = ((size_t)wi.b * p.Hq + head) * (size_t)N * kD;
+
+    // ---- HBM -> LDS tile copies -------------------------------------------------
+    // One wave instruction moves 64 x 16 bytes = 4 rows of the tile; the LDS
+    // side is linear in the lane id, the swizzle is applied on the global side:
+    // LDS chunk (row, c') receives global chunk c' ^ f(row) of that row.
+    const int lrow = lane >> 4;  // row within the 4-row group
+    const int lchk = lane & 15;  // LDS chunk within the row
+    auto issue_tile = [&](int j, int buf, const __bf16 *src, int ring, bool is_k) {
+        if (j >= J) return;
+        const int k0 = tile_of(j) * kBk;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = 16 * wave + 4 * i + lrow;
+            const int grow = min(k0 + row, N - 1);  // rows past the end are masked, keep the read in bounds
+            const int f = is_k ? (((4 * (i & 1) + lrow) << 1) | (i >> 1)) : (lrow << 2);
+            const __bf16 *g = src + (size_t)grow * kD + ((lchk ^ f) << 3);
+            char *l = smem + ring + buf * kTileBytes + (4 * wave + i) * 1024;
+            __builtin_amdgcn_global_load_lds((gbl_ptr)g, (lds_ptr)l, 16, 0, 0);
+        }
+    };
+    auto issue_k = [&](int j, int buf) { issue_tile(j, buf, kg, 0, true); };
+    auto issue_v = [&](int j, int buf) { issue_tile(j, buf, vg, kVRing, false); };
+
+    issue_k(0, 0);
+    issue_v(0, 0);
+    issue_k(1, 1);
+    issue_k(2, 2);
+    issue_v(1, 1);
+
+    // ---- Q fragments (B operand of S^T = K Q^T) ------------------------------------
+    bf16x8 qf[2][kKS];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        const int row = min(p0 + 32 * qb + l32, N - 1);
+        const __bf16 *src = p.q + q_base + (size_t)row * kD + 8 * hf;
+#pragma unroll
+        for (int ks = 0; ks < kKS; ++ks) qf[qb][ks] = *reinterpret_cast<const bf16x8 *>(src + 16 * ks);
+    }
+
+    f32x16 oacc[kDB][2];
+#pragma unroll
+    for (int db = 0; db < kDB; ++db)
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[db][qb][e] = 0.f;
+    RowState rs;
+    rs.m[0] = rs.m[1] = -INFINITY;
+    rs.l[0] = rs.l[1] = 0.f;
+
+    // per-lane LDS read addresses inside a tile (swizzle folded in)
+    const int fr = ((l32 & 7) << 1) | ((l32 >> 3) & 1);
+    const uint32_t k_lane = (uint32_t)(l32 * 256 + ((hf ^ fr) << 4));
+    const int j16 = lane & 15, grp = lane >> 4;
+    const int low2 = 2 * (grp & 1) + ((j16 & 3) >> 1);
+    const uint32_t v_lane =
+        (uint32_t)(kVRing + (4 * hf + (j16 >> 2)) * 256 + (((((j16 >> 2) & 3) << 2) | low2) << 4) + 8 * (j16 & 1));
+
+    const float c2 = p.scale_log2;
+
+    // activity of a 32-key half for this wave's 64 positions
+    auto half_active = [&](int k0h) {
+        const bool in_future = k0h > plast;
+        const bool before_band = (k0h + 31 < p0 - W + 1) && (k0h >= S);
+        return wave_active && !in_future && !before_band;
+    };
+    auto half_unmasked = [&](int k0h) {
+        return (k0h + 31 <= p0) && ((k0h > p0 + kWaveRows - 1 - W) || (k0h + 31 < S));
+    };
+
+    f32x16 s_a[2], s_b[2];      // scores of half 0 / half 1 of a tile
+    bf16x8 p_a[2][2], p_b[2][2];  // their P^T fragments
+    float alpha[2];
+
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's copies and Q loads have landed
+    __syncthreads();
+
+    // pipeline prologue: scores of the very first half
+    int k0_cur = tile_of(0) * kBk;
+    bool act_prev1 = false;  // half 1 of the previous tile
+    bool act0 = half_active(k0_cur), act1 = half_active(k0_cur + 32);
+    if (act0) qk_half(k_lane, qf, s_a);
+
+    int r3 = 0;  // j % 3
+    for (int j = 0; j < J; ++j) {
+        const int r3n = (r3 == 2) ? 0 : r3 + 1;   // (j + 1) % 3
+        const int r3p = (r3 == 0) ? 2 : r3 - 1;   // (j - 1) % 3
+        const bool has_next = (j + 1) < J;
+        const int k0_next = has_next ? tile_of(j + 1) * kBk : 0;
+        const bool act_next0 = has_next && half_active(k0_next);
+        const bool act_next1 = has_next && half_active(k0_next + 32);
+        const bool unm0 = half_unmasked(k0_cur), unm1 = half_unmasked(k0_cur + 32);
+
+        const uint32_t ka_cur1 = k_lane + r3 * kTileBytes + kHalfBytes;  // K(j), half 1
+        const uint32_t ka_next0 = k_lane + r3n * kTileBytes;             // K(j+1), half 0
+        const uint32_t va_prev1 = v_lane + r3p * kTileBytes + kHalfBytes;  // V(j-1), half 1
+        const uint32_t va_cur0 = v_lane + r3 * kTileBytes;                 // V(j), half 0
+
+        if (act_prev1 && act0 && act1 && act_next0 && unm0 && unm1) {
+            // steady state: three independent streams per sub-step
+            qk_half(ka_cur1, qf, s_b);
+            softmax_half<false>(s_a, k0_cur, p0, W, S, l32, hf, c2, rs, p_a, alpha);
+            pv_half(va_prev1, p_b, oacc);
+            rescale(oacc, alpha);
+
+            qk_half(ka_next0, qf, s_a);
+            softmax_half<false>(s_b, k0_cur + 32, p0, W, S, l32, hf, c2, rs, p_b, alpha);
+            pv_half(va_cur0, p_a, oacc);
+            rescale(oacc, alpha);
+        } else {
+            // edges of the band, the sink tile, first and last tile: same
+            // stages, each guarded; the element mask is applied where needed
+            if (act1) qk_half(ka_cur1, qf, s_b);
+            if (act0) {
+                if (unm0)
+                    softmax_half<false>(s_a, k0_cur, p0, W, S, l32, hf, c2, rs, p_a, alpha);
+                else
+                    softmax_half<true>(s_a, k0_cur, p0, W, S, l32, hf, c2, rs, p_a, alpha);
+            }
+            if (act_prev1) pv_half(va_prev1, p_b, oacc);
+            if (act0) rescale(oacc, alpha);
+
+            if (act_next0) qk_half(ka_next0, qf, s_a);
+            if (act1) {
+                if (unm1)
+                    softmax_half<false>(s_b, k0_cur + 32, p0, W, S, l32, hf, c2, rs, p_b, alpha);
+                else
+                    softmax_half<true>(s_b, k0_cur + 32, p0, W, S, l32, hf, c2, rs, p_b, alpha);
+            }
+            if (act0) pv_half(va_cur0, p_a, oacc);
+            if (act1) rescale(oacc, alpha);
+        }
+
+        // K(j+2), V(j+1) must have landed; K(j) and V(j-1) are free afterwards
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        issue_k(j + 3, r3);
+        issue_v(j + 2, r3p);
+
+        act_prev1 = act1;
+        act0 = act_next0;
+        act1 = act_next1;
+        k0_cur = k0_next;
+        r3 = r3n;
+    }
+    // pipeline drain: P V of the last half (V(J-1) sits in buffer (J-1) % 3)
+    if (act_prev1) {
+        const int r3l = (r3 == 0) ? 2 : r3 - 1;
+        pv_half(v_lane + r3l * kTileBytes + kHalfBytes, p_b, oacc);
+    }
+
+    // ---- epilogue: O / l -> bf16, lse = (m*c2 + log2 l) * ln 2 ----------------------
+    if (!wave_active) return;
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        const int qpos = p0 + 32 * qb + l32;
+        if (qpos >= N) continue;
+        const float inv_l = 1.f / rs.l[qb];
+        __bf16 *orow = p.out + q_base + (size_t)qpos * kD;
+#pragma unroll
+        for (int db = 0; db < kDB; ++db) {
+#pragma unroll
+            for (int e4 = 0; e4 < 4; ++e4) {
+                bf16x4 o4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[db][qb][4 * e4 + e] * inv_l);
+                *reinterpret_cast<bf16x4 *>(orow + 32 * db + 8 * e4 + 4 * hf) = o4;
+            }
+        }
+        if (hf == 0)
+            p.lse[((size_t)wi.b * p.Hq + head) * (size_t)N + qpos] =
+                (rs.m[qb] * c2 + __builtin_amdgcn_logf(rs.l[qb])) * 0.69314718055994530942f;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_fwd_pipelined_d128(const FwdParams &p, hipStream_t stream) {
+    // more than 64 KiB of LDS per workgroup has to be requested once per device
+    static std::atomic<unsigned long long> configured{0};
+    int dev = 0;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return err;
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (!(configured.load(std::memory_order_acquire) & bit)) {
+        err = hipFuncSetAttribute(reinterpret_cast<const void *>(&swaa_fwd_pipelined_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes);
+        if (err != hipSuccess) return err;
+        configured.fetch_or(bit, std::memory_order_release);
+    }
+    const unsigned grid = (unsigned)(p.chunk * kXcds);
+    hipLaunchKernelGGL(swaa_fwd_pipelined_kernel, dim3(grid), dim3(kThreads), kSmemBytes, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace swaa

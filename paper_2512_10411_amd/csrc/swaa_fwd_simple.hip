@@ -24,58 +24,12 @@
 //     ds_read_b64_tr_b16.
 //   * Online softmax in fp32 in the exp2 domain; O is rescaled only when some
 //     row maximum in the wave moved.
-#include <hip/hip_runtime.h>
-
 #include <cmath>
-#include <cstdint>
 
-#include "swaa.h"
+#include "swaa_common.h"
 
+namespace swaa {
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-
-constexpr int kBk = 64;        // keys per KV tile
-constexpr int kThreads = 256;  // 4 waves
-constexpr int kWaveRows = 64;  // query positions per wave
-constexpr int kWgRows = 256;   // query rows (head x position) per workgroup
-constexpr int kXcds = 8;
-
-struct FwdParams {
-    const __bf16 *q;
-    const __bf16 *k;
-    const __bf16 *v;
-    __bf16 *out;
-    float *lse;
-    int B, Hq, Hkv, N;
-    int W, S;  // clamped to [1, N] and [0, N]
-    int G;     // Hq / Hkv
-    float scale, scale_log2;
-    // work decomposition: per (b, kv head) "pair" the query heads are cut into
-    // n4 groups of 4 heads (64-position tiles), at most one group of 2 heads
-    // (128-position tiles) and at most one single head (256-position tiles).
-    int n4, has2, has1;
-    int nt64, nt128, nt256;
-    int tiles_per_pair;
-    long long total_items;
-    long long chunk;  // items per XCD
-};
-
-__device__ __forceinline__ float half_swap_max(float x) {
-    // lanes l and l^32 hold partial results for the same query column
-    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ __forceinline__ float half_swap_sum(float x) {
-    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
 
 template <int D>
 struct Tile {
@@ -97,36 +51,9 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
     __shared__ __attribute__((aligned(16))) __bf16 Ks[T::kKElems];
     __shared__ __attribute__((aligned(16))) __bf16 Vs[T::kVElems];
 
-    // ---- which piece of work is this workgroup's --------------------------
-    // Workgroups are handed to the 8 XCDs round-robin; giving XCD x the x-th
-    // contiguous chunk of the work list keeps the tiles of one KV head (whose
-    // K/V bands overlap) behind one L2.
-    const long long bid = blockIdx.x;
-    const long long slot = bid / kXcds;
-    const long long item = (bid % kXcds) * p.chunk + slot;
-    if (slot >= p.chunk || item >= p.total_items) return;
-    const int pair = (int)(item / p.tiles_per_pair);
-    int r = (int)(item % p.tiles_per_pair);
-    const int b = pair / p.Hkv;
-    const int kvh = pair % p.Hkv;
-    int hpb, h0, pt;
-    if (r < p.n4 * p.nt64) {
-        hpb = 4;
-        h0 = 4 * (r / p.nt64);
-        pt = p.nt64 - 1 - (r % p.nt64);  // long rows first
-    } else {
-        r -= p.n4 * p.nt64;
-        if (p.has2 && r < p.nt128) {
-            hpb = 2;
-            h0 = 4 * p.n4;
-            pt = p.nt128 - 1 - r;
-        } else {
-            if (p.has2) r -= p.nt128;
-            hpb = 1;
-            h0 = p.G - 1;
-            pt = p.nt256 - 1 - r;
-        }
-    }
+    WorkItem wi;
+    if (!decode_work(p, wi)) return;
+    const int b = wi.b, kvh = wi.kvh, hpb = wi.hpb, h0 = wi.h0, pt = wi.pt;
     const int pos_per_wg = kWgRows / hpb;
     const int N = p.N, W = p.W, S = p.S;
 
@@ -360,79 +287,15 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
     }
 }
 
-bool misaligned(const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) != 0; }
-
 }  // namespace
 
-extern "C" {
-
-long long swaa_visible_pairs(long long N, long long window, long long n_sink) {
-    if (N < 1 || window < 1 || n_sink < 0) return -1;
-    const long long W = window < N ? window : N;
-    const long long M = N - W;  // rows whose window no longer reaches key 0
-    long long pairs = W * (W + 1) / 2 + M * W;
-    // row i = W - 1 + x (x = 1..M) has x keys in front of its window; min(x, S) are sinks
-    const long long ramp = n_sink < M ? n_sink : M;
-    pairs += ramp * (ramp + 1) / 2 + (M - ramp) * n_sink;
-    return pairs;
-}
-
-const char *swaa_status_string(int status) {
-    switch (status) {
-        case SWAA_OK: return "ok";
-        case SWAA_ERR_NULL: return "null pointer argument";
-        case SWAA_ERR_SHAPE: return "size, window, sink count or scale out of range";
-        case SWAA_ERR_UNSUPPORTED: return "unsupported head dimension (64 and 128 are built)";
-        case SWAA_ERR_ALIGN: return "pointer not 16-byte aligned";
-        case SWAA_ERR_LAUNCH: return "HIP launch failed";
-        default: return "unknown status";
-    }
-}
-
-int swaa_version(void) { return 100; }
-
-int swaa_attn_fwd(const void *q, const void *k, const void *v, void *out, float *lse,
-                  int B, int Hq, int Hkv, int N, int D, int window, int n_sink,
-                  float scale, void *stream) {
-    if (!q || !k || !v || !out || !lse) return SWAA_ERR_NULL;
-    if (B < 1 || Hq < 1 || Hkv < 1 || N < 1 || D < 1) return SWAA_ERR_SHAPE;
-    if (Hq % Hkv != 0) return SWAA_ERR_SHAPE;
-    if (window < 1 || n_sink < 0) return SWAA_ERR_SHAPE;
-    if (!std::isfinite(scale) || !(scale > 0.f)) return SWAA_ERR_SHAPE;
-    if (D != 64 && D != 128) return SWAA_ERR_UNSUPPORTED;
-    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(lse))
-        return SWAA_ERR_ALIGN;
-
-    FwdParams p;
-    p.q = static_cast<const __bf16 *>(q);
-    p.k = static_cast<const __bf16 *>(k);
-    p.v = static_cast<const __bf16 *>(v);
-    p.out = static_cast<__bf16 *>(out);
-    p.lse = lse;
-    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N;
-    p.W = window < N ? window : N;
-    p.S = n_sink < N ? n_sink : N;
-    p.G = Hq / Hkv;
-    p.scale = scale;
-    p.scale_log2 = scale * 1.44269504088896340736f;
-    p.n4 = p.G / 4;
-    p.has2 = (p.G % 4) >= 2 ? 1 : 0;
-    p.has1 = p.G % 2;
-    p.nt64 = (N + 63) / 64;
-    p.nt128 = (N + 127) / 128;
-    p.nt256 = (N + 255) / 256;
-    p.tiles_per_pair = p.n4 * p.nt64 + p.has2 * p.nt128 + p.has1 * p.nt256;
-    p.total_items = (long long)B * Hkv * p.tiles_per_pair;
-    p.chunk = (p.total_items + kXcds - 1) / kXcds;
-    const long long grid = p.chunk * kXcds;
-    if (grid > 0x7fffffffLL) return SWAA_ERR_SHAPE;
-
-    hipStream_t s = static_cast<hipStream_t>(stream);
+hipError_t launch_fwd_simple(const FwdParams &p, int D, hipStream_t stream) {
+    const unsigned grid = (unsigned)(p.chunk * kXcds);
     if (D == 128)
-        hipLaunchKernelGGL(swaa_fwd_kernel<128>, dim3((unsigned)grid), dim3(kThreads), 0, s, p);
+        hipLaunchKernelGGL(swaa_fwd_kernel<128>, dim3(grid), dim3(kThreads), 0, stream, p);
     else
-        hipLaunchKernelGGL(swaa_fwd_kernel<64>, dim3((unsigned)grid), dim3(kThreads), 0, s, p);
-    return hipGetLastError() == hipSuccess ? SWAA_OK : SWAA_ERR_LAUNCH;
+        hipLaunchKernelGGL(swaa_fwd_kernel<64>, dim3(grid), dim3(kThreads), 0, stream, p);
+    return hipGetLastError();
 }
 
-}  // extern "C"
+}  // namespace swaa
