@@ -19,6 +19,9 @@ HIPCC_FLAGS = [
     "-Wall", "-Wno-unused-value",
     # packed fp32 VALU forms are kept out of the generated code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # S^T accumulators of the builtin MFMAs land in VGPRs (the softmax reads them
+    # with vector instructions); the O^T accumulators are pinned to AccVGPRs by hand
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
     "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG, "csrc"),
 ]
 

@@ -12,6 +12,8 @@
 //     while the softmax of half n runs on the VALU, the matrix pipe computes
 //     S^T = K Q^T of half n+1 and O^T += V^T P^T of half n-1.  The three are
 //     independent, so the MFMAs and the exponentials of one wave overlap.
+//     In the steady state the interleaving is fixed by hand with scheduling
+//     fences: one MFMA, about six vector instructions, the next MFMA, ...
 //   * The running maximum is a reference value that moves only when a row's
 //     maximum grows by more than 2^8 (in the exp2 domain); O and the row sum
 //     are rescaled only then.  Results are mathematically unchanged, values of
@@ -39,6 +41,46 @@ extern __shared__ __attribute__((aligned(1024))) char smem[];
 typedef char __attribute__((address_space(3))) * lds_ptr;
 typedef const char __attribute__((address_space(1))) * gbl_ptr;
 
+// O^T accumulators live in AccVGPRs for the whole kernel; the MFMA that
+// updates them is issued through inline assembly so that the compiler keeps
+// them there while every other value (Q, S^T, P^T, operands) stays in VGPRs.
+// The two idle cycles in front cover the case that the instruction just before
+// is a vector instruction writing one of the operands (the hardware needs two
+// wait states there and the compiler does not know this statement is an MFMA).
+__device__ __forceinline__ void mfma_acc(f32x16 &acc, const bf16x8 a, const bf16x8 b) {
+    asm("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+// The compiler cannot see that `o` comes out of the matrix pipe; before any
+// vector instruction reads it, wait out the longest MFMA write latency.
+__device__ __forceinline__ void settle_acc(f32x16 (&o)[kDB][2]) {
+    asm volatile("s_nop 15\n\ts_nop 7"
+                 : "+a"(o[0][0]), "+a"(o[0][1]), "+a"(o[1][0]), "+a"(o[1][1]), "+a"(o[2][0]), "+a"(o[2][1]),
+                   "+a"(o[3][0]), "+a"(o[3][1]));
+}
+
+// Empty statement that makes the compiler hold `o` in AccVGPRs at this point:
+// placed after every plain C++ write to the accumulators so that the value
+// carried around the key loop never changes register file.
+__device__ __forceinline__ void pin_acc(f32x16 (&o)[kDB][2]) {
+    asm volatile(""
+                 : "+a"(o[0][0]), "+a"(o[0][1]), "+a"(o[1][0]), "+a"(o[1][1]), "+a"(o[2][0]), "+a"(o[2][1]),
+                   "+a"(o[3][0]), "+a"(o[3][1]));
+}
+
+// A-operand fragment of K for k-step ks: rows (32*half + lane%32), 16 bytes.
+__device__ __forceinline__ bf16x8 load_k_frag(uint32_t kaddr, int ks) {
+    return *reinterpret_cast<const bf16x8 *>(smem + (kaddr ^ (uint32_t)(ks << 5)));
+}
+// A-operand fragment of V^T for 16-key step st and head-dimension block db:
+// two transposing reads, keys {0..3} and {8..11} of this half-wave's eight.
+__device__ __forceinline__ bf16x8 load_v_frag(uint32_t vaddr, int st, int db) {
+    const uint32_t a0 = (vaddr ^ (uint32_t)(db << 6)) + st * 16 * 256;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(smem + a0));
+    const s16x4 hi =
+        __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(smem + a0 + 8 * 256));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
 // S^T (32 keys x 64 queries) = K_half Q^T.  kaddr: this lane's byte address of
 // row (32*half + lane%32), chunk (lane/32) of the K tile, swizzle applied.
 __device__ __forceinline__ void qk_half(uint32_t kaddr, const bf16x8 (&qf)[2][kKS], f32x16 (&s)[2]) {
@@ -49,7 +91,7 @@ __device__ __forceinline__ void qk_half(uint32_t kaddr, const bf16x8 (&qf)[2][kK
     }
 #pragma unroll
     for (int ks = 0; ks < kKS; ++ks) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(smem + (kaddr ^ (uint32_t)(ks << 5)));
+        const bf16x8 a = load_k_frag(kaddr, ks);
         s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][ks], s[0], 0, 0, 0);
         s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[1][ks], s[1], 0, 0, 0);
     }
@@ -62,21 +104,29 @@ __device__ __forceinline__ void pv_half(uint32_t vaddr, const bf16x8 (&pf)[2][2]
     for (int st = 0; st < 2; ++st) {
 #pragma unroll
         for (int db = 0; db < kDB; ++db) {
-            const uint32_t a0 = (vaddr ^ (uint32_t)(db << 6)) + st * 16 * 256;
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(smem + a0));
-            const s16x4 hi =
-                __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(smem + a0 + 8 * 256));
-            const bf16x8 a = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-            o[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[0][st], o[db][0], 0, 0, 0);
-            o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[1][st], o[db][1], 0, 0, 0);
+            const bf16x8 a = load_v_frag(vaddr, st, db);
+            mfma_acc(o[db][0], a, pf[0][st]);
+            mfma_acc(o[db][1], a, pf[1][st]);
         }
     }
 }
 
 struct RowState {
-    float m[2];  // reference maximum per query column (raw score units)
-    float l[2];  // sum of exp2((s - m) * c2)
+    float mc[2];  // reference maximum per query column, in exp2 units (m * scale * log2 e)
+    float l[2];   // sum of exp2(s * c2 - mc)
 };
+
+// Reference-maximum update for one query block given the block maximum mx
+// (raw score units, already reduced over the wave halves).
+template <bool kMask>
+__device__ __forceinline__ void update_reference(float mx, float c2, float &mc, float &mc_use, float &alpha) {
+    const float mc_old = mc;
+    const float m_new = fmaxf(mc_old, mx * c2);
+    const bool move = m_new > mc_old + kRefSlack;  // -inf never moves to -inf
+    mc = move ? m_new : mc_old;
+    mc_use = (kMask && mc == -INFINITY) ? 0.f : mc;
+    alpha = move ? __builtin_amdgcn_exp2f(mc_old - mc_use) : 1.f;
+}
 
 // Mask (optional), reference-maximum update, exponentials, row sums and the
 // bf16 P^T fragments of one half tile.  alpha[qb] is the factor the O
@@ -99,34 +149,136 @@ __device__ __forceinline__ void softmax_half(f32x16 (&s)[2], int k0h, int p0, in
 #pragma unroll
         for (int e = 1; e < 16; ++e) mx = fmaxf(mx, s[qb][e]);
         mx = half_swap_max(mx);
-        const float m_old = st.m[qb];
-        const float m_new = fmaxf(m_old, mx);
-        const bool move = (m_new - m_old) * c2 > kRefSlack;  // false when both are -inf
-        const float m_ref = move ? m_new : m_old;
-        const float m_use = (kMask && m_ref == -INFINITY) ? 0.f : m_ref;
-        alpha[qb] = move ? __builtin_amdgcn_exp2f((m_old - m_use) * c2) : 1.f;
-        const float mc = m_use * c2;
+        float mc_use;
+        update_reference<kMask>(mx, c2, st.mc[qb], mc_use, alpha[qb]);
         float rs = 0.f;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            const float pe = __builtin_amdgcn_exp2f(fmaf(s[qb][e], c2, -mc));
+            const float pe = __builtin_amdgcn_exp2f(fmaf(s[qb][e], c2, -mc_use));
             rs += pe;
             pf[qb][e / 8][e % 8] = (__bf16)pe;
         }
         rs = half_swap_sum(rs);
         st.l[qb] = st.l[qb] * alpha[qb] + rs;
-        st.m[qb] = m_ref;
     }
 }
 
 __device__ __forceinline__ void rescale(f32x16 (&o)[kDB][2], const float (&alpha)[2]) {
     if (__any((alpha[0] != 1.f) || (alpha[1] != 1.f))) {
+        settle_acc(o);
 #pragma unroll
         for (int db = 0; db < kDB; ++db)
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) o[db][qb][e] *= alpha[qb];
+        pin_acc(o);
+    }
+}
+
+// ---- steady-state sub-step, scheduled by hand ---------------------------------
+// One sub-step issues 32 MFMAs: S^T(n+1) = K Q^T (16) and O^T += V^T P^T(n-1)
+// (16), and in their shadow the vector work of the softmax of half n, cut into
+// 32 chunks of about six instructions.  Scheduling fences pin the order
+// "MFMA, chunk, MFMA, chunk, ..." so the matrix pipe is re-fed as soon as it
+// drains while the wave keeps issuing vector instructions in between; LDS
+// fragment reads are issued two MFMA pairs ahead of their use.
+struct SoftmaxScratch {
+    float t[2][6];
+    float mx[2];
+    float mc_use[2];
+    float x[3];
+    float pe[32];
+    float sum[2][2];
+};
+
+__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+
+__device__ __forceinline__ void softmax_chunk(int c, f32x16 (&s)[2], float c2, RowState &st, SoftmaxScratch &w,
+                                              bf16x8 (&pf)[2][2], float (&alpha)[2]) {
+    if (c < 6) {  // maxima and reference update: chunks 0-2 for query block 0, 3-5 for block 1
+        const int qb = c / 3;
+        const f32x16 &v = s[qb];
+        switch (c % 3) {
+            case 0:
+                w.t[qb][0] = max3(v[0], v[1], v[2]);
+                w.t[qb][1] = max3(v[3], v[4], v[5]);
+                w.t[qb][2] = max3(v[6], v[7], v[8]);
+                w.t[qb][3] = max3(v[9], v[10], v[11]);
+                w.t[qb][4] = max3(v[12], v[13], v[14]);
+                w.t[qb][5] = max3(w.t[qb][0], w.t[qb][1], v[15]);
+                break;
+            case 1:
+                w.mx[qb] = half_swap_max(fmaxf(max3(w.t[qb][2], w.t[qb][3], w.t[qb][4]), w.t[qb][5]));
+                break;
+            default:
+                update_reference<false>(w.mx[qb], c2, st.mc[qb], w.mc_use[qb], alpha[qb]);
+                w.sum[qb][0] = 0.f;
+                w.sum[qb][1] = 0.f;
+                break;
+        }
+    } else if (c < 28) {  // exponentials: three score elements per pair of chunks
+        const int k = (c - 6) / 2;
+        const int g0 = 3 * k;
+        if (((c - 6) & 1) == 0) {
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                const int g = g0 + i;
+                if (g < 32) w.x[i] = fmaf(s[g / 16][g % 16], c2, -w.mc_use[g / 16]);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                if (g0 + i < 32) w.pe[g0 + i] = __builtin_amdgcn_exp2f(w.x[i]);
+        } else {
+            if (g0 + 2 < 32) w.pe[g0 + 2] = __builtin_amdgcn_exp2f(w.x[2]);
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                const int g = g0 + i;
+                if (g < 32) {
+                    w.sum[g / 16][g & 1] += w.pe[g];
+                    if (g & 1) {  // the pair (g-1, g) is complete: pack it
+                        const int qb = g / 16, e = (g % 16) - 1;
+                        pf[qb][e / 8][e % 8] = (__bf16)w.pe[g - 1];
+                        pf[qb][e / 8][e % 8 + 1] = (__bf16)w.pe[g];
+                    }
+                }
+            }
+        }
+    } else if (c == 28) {
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            const float rs = half_swap_sum(w.sum[qb][0] + w.sum[qb][1]);
+            st.l[qb] = st.l[qb] * alpha[qb] + rs;
+        }
+    }
+}
+
+__device__ __forceinline__ void steady_substep(uint32_t kaddr, uint32_t vaddr, const bf16x8 (&qf)[2][kKS],
+                                               f32x16 (&s_next)[2], f32x16 (&s_cur)[2], bf16x8 (&p_cur)[2][2],
+                                               const bf16x8 (&p_prev)[2][2], f32x16 (&o)[kDB][2], RowState &st, float c2,
+                                               float (&alpha)[2]) {
+    SoftmaxScratch w;
+    bf16x8 frag[16];  // 0..7: K fragments by k-step; 8..15: V^T fragments by (16-key step, d block)
+    auto load_frag = [&](int i) {
+        frag[i] = (i < 8) ? load_k_frag(kaddr, i) : load_v_frag(vaddr, (i - 8) / kDB, (i - 8) % kDB);
+    };
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    load_frag(0);
+    load_frag(1);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        if (i + 2 < 16) load_frag(i + 2);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            if (i < 8) {
+                s_next[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[i], qf[qb][i], (i == 0) ? zero : s_next[qb], 0, 0, 0);
+            } else {
+                mfma_acc(o[(i - 8) % kDB][qb], frag[i], p_prev[qb][(i - 8) / kDB]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            softmax_chunk(2 * i + qb, s_cur, c2, st, w, p_cur, alpha);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 }
 
@@ -208,8 +360,9 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
         for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
             for (int e = 0; e < 16; ++e) oacc[db][qb][e] = 0.f;
+    pin_acc(oacc);
     RowState rs;
-    rs.m[0] = rs.m[1] = -INFINITY;
+    rs.mc[0] = rs.mc[1] = -INFINITY;
     rs.l[0] = rs.l[1] = 0.f;
 
     // per-lane LDS read addresses inside a tile (swizzle folded in)
@@ -262,14 +415,9 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
 
         if (act_prev1 && act0 && act1 && act_next0 && unm0 && unm1) {
             // steady state: three independent streams per sub-step
-            qk_half(ka_cur1, qf, s_b);
-            softmax_half<false>(s_a, k0_cur, p0, W, S, l32, hf, c2, rs, p_a, alpha);
-            pv_half(va_prev1, p_b, oacc);
+            steady_substep(ka_cur1, va_prev1, qf, s_b, s_a, p_a, p_b, oacc, rs, c2, alpha);
             rescale(oacc, alpha);
-
-            qk_half(ka_next0, qf, s_a);
-            softmax_half<false>(s_b, k0_cur + 32, p0, W, S, l32, hf, c2, rs, p_b, alpha);
-            pv_half(va_cur0, p_a, oacc);
+            steady_substep(ka_next0, va_cur0, qf, s_a, s_b, p_b, p_a, oacc, rs, c2, alpha);
             rescale(oacc, alpha);
         } else {
             // edges of the band, the sink tile, first and last tile: same
@@ -315,6 +463,7 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
 
     // ---- epilogue: O / l -> bf16, lse = (m*c2 + log2 l) * ln 2 ----------------------
     if (!wave_active) return;
+    settle_acc(oacc);
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         const int qpos = p0 + 32 * qb + l32;
@@ -333,7 +482,7 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
         }
         if (hf == 0)
             p.lse[((size_t)wi.b * p.Hq + head) * (size_t)N + qpos] =
-                (rs.m[qb] * c2 + __builtin_amdgcn_logf(rs.l[qb])) * 0.69314718055994530942f;
+                (rs.mc[qb] + __builtin_amdgcn_logf(rs.l[qb])) * 0.69314718055994530942f;
     }
 }
 
