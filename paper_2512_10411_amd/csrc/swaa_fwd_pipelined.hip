@@ -41,14 +41,29 @@ extern __shared__ __attribute__((aligned(1024))) char smem[];
 typedef char __attribute__((address_space(3))) * lds_ptr;
 typedef const char __attribute__((address_space(1))) * gbl_ptr;
 
-// O^T accumulators live in AccVGPRs for the whole kernel; the MFMA that
-// updates them is issued through inline assembly so that the compiler keeps
-// them there while every other value (Q, S^T, P^T, operands) stays in VGPRs.
-// The two idle cycles in front cover the case that the instruction just before
-// is a vector instruction writing one of the operands (the hardware needs two
-// wait states there and the compiler does not know this statement is an MFMA).
+// Register files are assigned by hand: the O^T accumulators (128 registers)
+// and the Q fragments (64) live in AccVGPRs for the whole kernel, everything
+// the vector ALU touches (S^T, P^T, K/V fragments) lives in VGPRs.  The
+// compiler does not split one function's MFMAs that way, so every MFMA is
+// issued through inline assembly with the register file in the constraint.
+// The two idle cycles in front cover the case that the instruction just
+// before is a vector instruction writing one of the operands (the hardware
+// needs two wait states there; the compiler cannot know the statement is an
+// MFMA).  They are hidden whenever the matrix pipe is the bottleneck.
 __device__ __forceinline__ void mfma_acc(f32x16 &acc, const bf16x8 a, const bf16x8 b) {
     asm("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+// S^T accumulators: VGPR destination, Q operand read straight from AccVGPRs.
+__device__ __forceinline__ void mfma_s(f32x16 &s, const bf16x8 kfrag, const bf16x8 q_acc) {
+    asm("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(kfrag), "a"(q_acc));
+}
+__device__ __forceinline__ void mfma_s_first(f32x16 &s, const bf16x8 kfrag, const bf16x8 q_acc) {
+    asm("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(kfrag), "a"(q_acc));
+}
+// Before a vector instruction reads what an MFMA wrote, the longest MFMA
+// write latency has to pass; the compiler cannot insert that wait itself.
+__device__ __forceinline__ void settle_s(f32x16 (&s)[2]) {
+    asm volatile("s_nop 15\n\ts_nop 7" : "+v"(s[0]), "+v"(s[1]));
 }
 // The compiler cannot see that `o` comes out of the matrix pipe; before any
 // vector instruction reads it, wait out the longest MFMA write latency.
@@ -85,15 +100,15 @@ __device__ __forceinline__ bf16x8 load_v_frag(uint32_t vaddr, int st, int db) {
 // row (32*half + lane%32), chunk (lane/32) of the K tile, swizzle applied.
 __device__ __forceinline__ void qk_half(uint32_t kaddr, const bf16x8 (&qf)[2][kKS], f32x16 (&s)[2]) {
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-        s[0][e] = 0.f;
-        s[1][e] = 0.f;
-    }
-#pragma unroll
     for (int ks = 0; ks < kKS; ++ks) {
         const bf16x8 a = load_k_frag(kaddr, ks);
-        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][ks], s[0], 0, 0, 0);
-        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[1][ks], s[1], 0, 0, 0);
+        if (ks == 0) {
+            mfma_s_first(s[0], a, qf[0][ks]);
+            mfma_s_first(s[1], a, qf[1][ks]);
+        } else {
+            mfma_s(s[0], a, qf[0][ks]);
+            mfma_s(s[1], a, qf[1][ks]);
+        }
     }
 }
 
@@ -262,7 +277,6 @@ __device__ __forceinline__ void steady_substep(uint32_t kaddr, uint32_t vaddr, c
     auto load_frag = [&](int i) {
         frag[i] = (i < 8) ? load_k_frag(kaddr, i) : load_v_frag(vaddr, (i - 8) / kDB, (i - 8) % kDB);
     };
-    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     load_frag(0);
     load_frag(1);
 #pragma unroll
@@ -270,8 +284,10 @@ __device__ __forceinline__ void steady_substep(uint32_t kaddr, uint32_t vaddr, c
         if (i + 2 < 16) load_frag(i + 2);
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
-            if (i < 8) {
-                s_next[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[i], qf[qb][i], (i == 0) ? zero : s_next[qb], 0, 0, 0);
+            if (i == 0) {
+                mfma_s_first(s_next[qb], frag[i], qf[qb][i]);
+            } else if (i < 8) {
+                mfma_s(s_next[qb], frag[i], qf[qb][i]);
             } else {
                 mfma_acc(o[(i - 8) % kDB][qb], frag[i], p_prev[qb][(i - 8) / kDB]);
             }
@@ -319,6 +335,7 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
     // One wave instruction moves 64 x 16 bytes = 4 rows of the tile; the LDS
     // side is linear in the lane id, the swizzle is applied on the global side:
     // LDS chunk (row, c') receives global chunk c' ^ f(row) of that row.
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int lrow = lane >> 4;  // row within the 4-row group
     const int lchk = lane & 15;  // LDS chunk within the row
     auto issue_tile = [&](int j, int buf, const __bf16 *src, int ring, bool is_k) {
@@ -330,8 +347,10 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
             const int grow = min(k0 + row, N - 1);  // rows past the end are masked, keep the read in bounds
             const int f = is_k ? (((4 * (i & 1) + lrow) << 1) | (i >> 1)) : (lrow << 2);
             const __bf16 *g = src + (size_t)grow * kD + ((lchk ^ f) << 3);
-            char *l = smem + ring + buf * kTileBytes + (4 * wave + i) * 1024;
-            __builtin_amdgcn_global_load_lds((gbl_ptr)g, (lds_ptr)l, 16, 0, 0);
+            const uint32_t l = (uint32_t)(ring + buf * kTileBytes + (4 * wave_u + i) * 1024);
+            // LDS address = M0 + 16 * lane.  Issued as assembly on purpose: the
+            // compiler would otherwise make every later LDS read wait for it.
+            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(l) : "memory");
         }
     };
     auto issue_k = [&](int j, int buf) { issue_tile(j, buf, kg, 0, true); };
@@ -352,6 +371,10 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
 #pragma unroll
         for (int ks = 0; ks < kKS; ++ks) qf[qb][ks] = *reinterpret_cast<const bf16x8 *>(src + 16 * ks);
     }
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int ks = 0; ks < kKS; ++ks) asm volatile("" : "+a"(qf[qb][ks]));
 
     f32x16 oacc[kDB][2];
 #pragma unroll
@@ -424,6 +447,7 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
             // stages, each guarded; the element mask is applied where needed
             if (act1) qk_half(ka_cur1, qf, s_b);
             if (act0) {
+                settle_s(s_a);
                 if (unm0)
                     softmax_half<false>(s_a, k0_cur, p0, W, S, l32, hf, c2, rs, p_a, alpha);
                 else
@@ -434,6 +458,7 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
 
             if (act_next0) qk_half(ka_next0, qf, s_a);
             if (act1) {
+                settle_s(s_b);
                 if (unm1)
                     softmax_half<false>(s_b, k0_cur + 32, p0, W, S, l32, hf, c2, rs, p_b, alpha);
                 else
