@@ -2,6 +2,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstdlib>
+#include <cstring>
 #include <string>
 
 #include "swaa.h"
@@ -11,6 +12,13 @@ using swaa::FwdParams;
 using swaa::kXcds;
 
 namespace {
+
+// finite and > 0, tested on the bit pattern (independent of fast-math flags)
+bool positive_finite(float x) {
+    uint32_t u;
+    std::memcpy(&u, &x, sizeof u);
+    return (u >> 31) == 0 && ((u >> 23) & 0xffu) != 0xffu && (u << 1) != 0;
+}
 
 bool misaligned(const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) != 0; }
 
@@ -60,7 +68,7 @@ int swaa_attn_fwd(const void *q, const void *k, const void *v, void *out, float 
     if (B < 1 || Hq < 1 || Hkv < 1 || N < 1 || D < 1) return SWAA_ERR_SHAPE;
     if (Hq % Hkv != 0) return SWAA_ERR_SHAPE;
     if (window < 1 || n_sink < 0) return SWAA_ERR_SHAPE;
-    if (!std::isfinite(scale) || !(scale > 0.f)) return SWAA_ERR_SHAPE;
+    if (!positive_finite(scale)) return SWAA_ERR_SHAPE;
     if (D != 64 && D != 128) return SWAA_ERR_UNSUPPORTED;
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(lse))
         return SWAA_ERR_ALIGN;

@@ -14,11 +14,18 @@
 //     independent, so the MFMAs and the exponentials of one wave overlap.
 //     In the steady state the interleaving is fixed by hand with scheduling
 //     fences: one MFMA, about six vector instructions, the next MFMA, ...
+//   * With one wave per SIMD the wave's own instruction issue is the limit
+//     (every MFMA leaves room for about seven other instructions), so the
+//     register files are assigned by hand -- O^T and Q in AccVGPRs, S^T, P^T
+//     and the K/V fragments in VGPRs -- which keeps copies out of the loop.
 //   * The running maximum is a reference value that moves only when a row's
 //     maximum grows by more than 2^8 (in the exp2 domain); O and the row sum
 //     are rescaled only then.  Results are mathematically unchanged, values of
 //     P stay below 2^8, and the rescale of the 64x128 accumulator all but
 //     disappears from the steady state.
+//
+// This kernel declares no static LDS: its dynamic LDS starts at address 0 and
+// all LDS accesses below use plain byte addresses.
 #include <atomic>
 
 #include "swaa_common.h"
@@ -30,78 +37,84 @@ constexpr int kD = 128;
 constexpr int kKS = kD / 16;  // k-steps of K Q^T
 constexpr int kDB = kD / 32;  // 32-wide blocks of the head dimension
 constexpr int kStages = 3;
-constexpr int kTileBytes = kBk * kD * 2;            // 16 KiB
-constexpr int kHalfBytes = kTileBytes / 2;          // one 32-key half
-constexpr int kVRing = kStages * kTileBytes;        // V ring follows the K ring
+constexpr int kTileBytes = kBk * kD * 2;              // 16 KiB
+constexpr int kHalfBytes = kTileBytes / 2;            // one 32-key half
+constexpr int kVRing = kStages * kTileBytes;          // V ring follows the K ring
 constexpr int kSmemBytes = 2 * kStages * kTileBytes;  // 96 KiB
 constexpr float kRefSlack = 8.f;  // log2 units a row maximum may exceed its reference
 
 extern __shared__ __attribute__((aligned(1024))) char smem[];
 
-typedef char __attribute__((address_space(3))) * lds_ptr;
-typedef const char __attribute__((address_space(1))) * gbl_ptr;
-
-// Register files are assigned by hand: the O^T accumulators (128 registers)
-// and the Q fragments (64) live in AccVGPRs for the whole kernel, everything
-// the vector ALU touches (S^T, P^T, K/V fragments) lives in VGPRs.  The
-// compiler does not split one function's MFMAs that way, so every MFMA is
-// issued through inline assembly with the register file in the constraint.
-// The two idle cycles in front cover the case that the instruction just
-// before is a vector instruction writing one of the operands (the hardware
-// needs two wait states there; the compiler cannot know the statement is an
-// MFMA).  They are hidden whenever the matrix pipe is the bottleneck.
+// ---- MFMA through inline assembly ------------------------------------------------
+// The compiler cannot be told to keep some MFMA operands in AccVGPRs and others
+// in VGPRs within one function, so every MFMA is written out with the register
+// file in the constraint.  Consequences the code below has to honour itself:
+//   (1) a vector instruction that writes an MFMA operand must be at least two
+//       instructions ahead of the MFMA (hardware needs two wait states);
+//   (2) a vector instruction that reads an MFMA result must wait for the MFMA
+//       to finish (settle_* below).
+// tests/test_asm_hazards.py checks (1) on the generated assembly.
 __device__ __forceinline__ void mfma_acc(f32x16 &acc, const bf16x8 a, const bf16x8 b) {
-    asm("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+    asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 // S^T accumulators: VGPR destination, Q operand read straight from AccVGPRs.
 __device__ __forceinline__ void mfma_s(f32x16 &s, const bf16x8 kfrag, const bf16x8 q_acc) {
-    asm("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(kfrag), "a"(q_acc));
+    asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(kfrag), "a"(q_acc));
 }
 __device__ __forceinline__ void mfma_s_first(f32x16 &s, const bf16x8 kfrag, const bf16x8 q_acc) {
-    asm("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(kfrag), "a"(q_acc));
+    asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(kfrag), "a"(q_acc));
 }
-// Before a vector instruction reads what an MFMA wrote, the longest MFMA
-// write latency has to pass; the compiler cannot insert that wait itself.
 __device__ __forceinline__ void settle_s(f32x16 (&s)[2]) {
     asm volatile("s_nop 15\n\ts_nop 7" : "+v"(s[0]), "+v"(s[1]));
 }
-// The compiler cannot see that `o` comes out of the matrix pipe; before any
-// vector instruction reads it, wait out the longest MFMA write latency.
 __device__ __forceinline__ void settle_acc(f32x16 (&o)[kDB][2]) {
     asm volatile("s_nop 15\n\ts_nop 7"
                  : "+a"(o[0][0]), "+a"(o[0][1]), "+a"(o[1][0]), "+a"(o[1][1]), "+a"(o[2][0]), "+a"(o[2][1]),
                    "+a"(o[3][0]), "+a"(o[3][1]));
 }
-
-// Empty statement that makes the compiler hold `o` in AccVGPRs at this point:
-// placed after every plain C++ write to the accumulators so that the value
-// carried around the key loop never changes register file.
+// Makes the compiler hold `o` in AccVGPRs at this point (placed after every
+// plain C++ write to the accumulators so that the value carried around the key
+// loop never changes register file) and spaces those writes from the next MFMA.
 __device__ __forceinline__ void pin_acc(f32x16 (&o)[kDB][2]) {
-    asm volatile(""
+    asm volatile("s_nop 1"
                  : "+a"(o[0][0]), "+a"(o[0][1]), "+a"(o[1][0]), "+a"(o[1][1]), "+a"(o[2][0]), "+a"(o[2][1]),
                    "+a"(o[3][0]), "+a"(o[3][1]));
 }
+// Materialises a freshly packed P^T fragment here (the compiler would otherwise
+// be free to sink the conversion down to the MFMA that reads it).
+__device__ __forceinline__ void pin_p(bf16x8 &pf) { asm volatile("" : "+v"(pf)); }
 
-// A-operand fragment of K for k-step ks: rows (32*half + lane%32), 16 bytes.
-__device__ __forceinline__ bf16x8 load_k_frag(uint32_t kaddr, int ks) {
-    return *reinterpret_cast<const bf16x8 *>(smem + (kaddr ^ (uint32_t)(ks << 5)));
+// ---- LDS operand reads ---------------------------------------------------------------
+__device__ __forceinline__ bf16x8 lds_read16(uint32_t addr) {
+    return *(const bf16x8 __attribute__((address_space(3))) *)(uintptr_t)addr;
 }
-// A-operand fragment of V^T for 16-key step st and head-dimension block db:
-// two transposing reads, keys {0..3} and {8..11} of this half-wave's eight.
-__device__ __forceinline__ bf16x8 load_v_frag(uint32_t vaddr, int st, int db) {
-    const uint32_t a0 = (vaddr ^ (uint32_t)(db << 6)) + st * 16 * 256;
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(smem + a0));
-    const s16x4 hi =
-        __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(smem + a0 + 8 * 256));
+__device__ __forceinline__ s16x4 lds_read8_tr(uint32_t addr) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(uintptr_t)addr);
+}
+
+// Per-lane byte offsets of the MFMA A-operand fragments inside one 32-key half
+// of a K or V tile, XOR swizzle folded in; a uniform buffer offset is added.
+struct LaneAddr {
+    uint32_t k[kKS];  // K fragment of k-step ks: row lane%32, 16-byte chunk 2*ks + lane/32
+    uint32_t v[kDB];  // V^T fragment of head-dimension block db, 16-key step 0, keys 0..3
+};
+
+__device__ __forceinline__ bf16x8 load_k_frag(const LaneAddr &la, uint32_t boff, int ks) {
+    return lds_read16(la.k[ks] + boff);
+}
+// two transposing reads: keys {0..3} and {8..11} of this half-wave's eight
+__device__ __forceinline__ bf16x8 load_v_frag(const LaneAddr &la, uint32_t boff, int st, int db) {
+    const uint32_t a0 = la.v[db] + boff;
+    const s16x4 lo = lds_read8_tr(a0 + st * 16 * 256);
+    const s16x4 hi = lds_read8_tr(a0 + st * 16 * 256 + 8 * 256);
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
-// S^T (32 keys x 64 queries) = K_half Q^T.  kaddr: this lane's byte address of
-// row (32*half + lane%32), chunk (lane/32) of the K tile, swizzle applied.
-__device__ __forceinline__ void qk_half(uint32_t kaddr, const bf16x8 (&qf)[2][kKS], f32x16 (&s)[2]) {
+// S^T (32 keys x 64 queries) = K_half Q^T
+__device__ __forceinline__ void qk_half(const LaneAddr &la, uint32_t kboff, const bf16x8 (&qf)[2][kKS], f32x16 (&s)[2]) {
 #pragma unroll
     for (int ks = 0; ks < kKS; ++ks) {
-        const bf16x8 a = load_k_frag(kaddr, ks);
+        const bf16x8 a = load_k_frag(la, kboff, ks);
         if (ks == 0) {
             mfma_s_first(s[0], a, qf[0][ks]);
             mfma_s_first(s[1], a, qf[1][ks]);
@@ -112,14 +125,13 @@ __device__ __forceinline__ void qk_half(uint32_t kaddr, const bf16x8 (&qf)[2][kK
     }
 }
 
-// O^T (128 x 64 queries) += V_half^T P^T.  vaddr: this lane's byte address in
-// the V tile for the transposing read of head-dimension block 0, step 0.
-__device__ __forceinline__ void pv_half(uint32_t vaddr, const bf16x8 (&pf)[2][2], f32x16 (&o)[kDB][2]) {
+// O^T (128 x 64 queries) += V_half^T P^T
+__device__ __forceinline__ void pv_half(const LaneAddr &la, uint32_t vboff, const bf16x8 (&pf)[2][2], f32x16 (&o)[kDB][2]) {
 #pragma unroll
     for (int st = 0; st < 2; ++st) {
 #pragma unroll
         for (int db = 0; db < kDB; ++db) {
-            const bf16x8 a = load_v_frag(vaddr, st, db);
+            const bf16x8 a = load_v_frag(la, vboff, st, db);
             mfma_acc(o[db][0], a, pf[0][st]);
             mfma_acc(o[db][1], a, pf[1][st]);
         }
@@ -149,6 +161,7 @@ __device__ __forceinline__ void update_reference(float mx, float c2, float &mc, 
 template <bool kMask>
 __device__ __forceinline__ void softmax_half(f32x16 (&s)[2], int k0h, int p0, int W, int S, int l32, int hf, float c2,
                                              RowState &st, bf16x8 (&pf)[2][2], float (&alpha)[2]) {
+    settle_s(s);
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         if (kMask) {
@@ -176,6 +189,8 @@ __device__ __forceinline__ void softmax_half(f32x16 (&s)[2], int k0h, int p0, in
         rs = half_swap_sum(rs);
         st.l[qb] = st.l[qb] * alpha[qb] + rs;
     }
+    // keep the packing here and two wait states away from the MFMAs that read it
+    asm volatile("s_nop 1" : "+v"(pf[0][0]), "+v"(pf[0][1]), "+v"(pf[1][0]), "+v"(pf[1][1]));
 }
 
 __device__ __forceinline__ void rescale(f32x16 (&o)[kDB][2], const float (&alpha)[2]) {
@@ -191,17 +206,20 @@ __device__ __forceinline__ void rescale(f32x16 (&o)[kDB][2], const float (&alpha
     }
 }
 
-// ---- steady-state sub-step, scheduled by hand ---------------------------------
-// One sub-step issues 32 MFMAs: S^T(n+1) = K Q^T (16) and O^T += V^T P^T(n-1)
-// (16), and in their shadow the vector work of the softmax of half n, cut into
-// 32 chunks of about six instructions.  Scheduling fences pin the order
-// "MFMA, chunk, MFMA, chunk, ..." so the matrix pipe is re-fed as soon as it
-// drains while the wave keeps issuing vector instructions in between; LDS
-// fragment reads are issued two MFMA pairs ahead of their use.
+// ---- steady-state step, scheduled by hand ----------------------------------------
+// A sub-step issues 32 MFMAs: S^T(n+1) = K Q^T (16) and O^T += V^T P^T(n-1) (16),
+// and in their shadow the vector work of the softmax of half n, cut into 32
+// chunks of about six instructions.  Scheduling fences pin the order
+// "MFMA, chunk, MFMA, chunk, ..." so that the matrix pipe is re-fed as soon as
+// it drains while the wave keeps issuing vector instructions in between.  LDS
+// fragment reads are issued two MFMA pairs ahead of their use, across the
+// boundary between the two sub-steps of a step as well.
 struct SoftmaxScratch {
-    float t[2][6];
+    float t[2][7];
     float mx[2];
+    float mc_old[2];
     float mc_use[2];
+    bool move[2];
     float x[3];
     float pe[32];
     float sum[2][2];
@@ -209,33 +227,44 @@ struct SoftmaxScratch {
 
 __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
+constexpr int kChunkExp0 = 8;  // first exponential chunk
+constexpr int kChunkSum = 30;  // row-sum reduction chunk
+
 __device__ __forceinline__ void softmax_chunk(int c, f32x16 (&s)[2], float c2, RowState &st, SoftmaxScratch &w,
                                               bf16x8 (&pf)[2][2], float (&alpha)[2]) {
-    if (c < 6) {  // maxima and reference update: chunks 0-2 for query block 0, 3-5 for block 1
-        const int qb = c / 3;
+    if (c < kChunkExp0) {  // maxima and reference update: chunks 0-3 query block 0, 4-7 block 1
+        const int qb = c / 4;
         const f32x16 &v = s[qb];
-        switch (c % 3) {
+        switch (c % 4) {
             case 0:
                 w.t[qb][0] = max3(v[0], v[1], v[2]);
                 w.t[qb][1] = max3(v[3], v[4], v[5]);
                 w.t[qb][2] = max3(v[6], v[7], v[8]);
                 w.t[qb][3] = max3(v[9], v[10], v[11]);
                 w.t[qb][4] = max3(v[12], v[13], v[14]);
-                w.t[qb][5] = max3(w.t[qb][0], w.t[qb][1], v[15]);
                 break;
             case 1:
-                w.mx[qb] = half_swap_max(fmaxf(max3(w.t[qb][2], w.t[qb][3], w.t[qb][4]), w.t[qb][5]));
+                w.t[qb][5] = max3(w.t[qb][0], w.t[qb][1], v[15]);
+                w.t[qb][6] = max3(w.t[qb][2], w.t[qb][3], w.t[qb][4]);
+                w.mx[qb] = half_swap_max(fmaxf(w.t[qb][5], w.t[qb][6]));
                 break;
+            case 2: {
+                const float mc_old = st.mc[qb];
+                const float m_new = fmaxf(mc_old, w.mx[qb] * c2);
+                w.move[qb] = m_new > mc_old + kRefSlack;
+                w.mc_old[qb] = mc_old;
+                st.mc[qb] = w.move[qb] ? m_new : mc_old;
+                w.mc_use[qb] = st.mc[qb];
+                break;
+            }
             default:
-                update_reference<false>(w.mx[qb], c2, st.mc[qb], w.mc_use[qb], alpha[qb]);
-                w.sum[qb][0] = 0.f;
-                w.sum[qb][1] = 0.f;
+                alpha[qb] = w.move[qb] ? __builtin_amdgcn_exp2f(w.mc_old[qb] - w.mc_use[qb]) : 1.f;
                 break;
         }
-    } else if (c < 28) {  // exponentials: three score elements per pair of chunks
-        const int k = (c - 6) / 2;
+    } else if (c < kChunkSum) {  // exponentials: three score elements per pair of chunks
+        const int k = (c - kChunkExp0) / 2;
         const int g0 = 3 * k;
-        if (((c - 6) & 1) == 0) {
+        if (((c - kChunkExp0) & 1) == 0) {
 #pragma unroll
             for (int i = 0; i < 3; ++i) {
                 const int g = g0 + i;
@@ -250,16 +279,20 @@ __device__ __forceinline__ void softmax_chunk(int c, f32x16 (&s)[2], float c2, R
             for (int i = 0; i < 3; ++i) {
                 const int g = g0 + i;
                 if (g < 32) {
-                    w.sum[g / 16][g & 1] += w.pe[g];
-                    if (g & 1) {  // the pair (g-1, g) is complete: pack it
-                        const int qb = g / 16, e = (g % 16) - 1;
-                        pf[qb][e / 8][e % 8] = (__bf16)w.pe[g - 1];
-                        pf[qb][e / 8][e % 8 + 1] = (__bf16)w.pe[g];
+                    const int qb = g / 16, e = g % 16;
+                    if (e < 2)
+                        w.sum[qb][e] = w.pe[g];
+                    else
+                        w.sum[qb][e & 1] += w.pe[g];
+                    if (e & 1) {  // the pair (e-1, e) is complete: pack it
+                        pf[qb][e / 8][(e - 1) % 8] = (__bf16)w.pe[g - 1];
+                        pf[qb][e / 8][e % 8] = (__bf16)w.pe[g];
+                        if (e % 8 == 7) pin_p(pf[qb][e / 8]);
                     }
                 }
             }
         }
-    } else if (c == 28) {
+    } else if (c == kChunkSum) {
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             const float rs = half_swap_sum(w.sum[qb][0] + w.sum[qb][1]);
@@ -268,20 +301,29 @@ __device__ __forceinline__ void softmax_chunk(int c, f32x16 (&s)[2], float c2, R
     }
 }
 
-__device__ __forceinline__ void steady_substep(uint32_t kaddr, uint32_t vaddr, const bf16x8 (&qf)[2][kKS],
-                                               f32x16 (&s_next)[2], f32x16 (&s_cur)[2], bf16x8 (&p_cur)[2][2],
-                                               const bf16x8 (&p_prev)[2][2], f32x16 (&o)[kDB][2], RowState &st, float c2,
-                                               float (&alpha)[2]) {
+// One sub-step.  kboff / vboff: uniform byte offsets of the K half to multiply
+// and the V half to accumulate.  f0, f1: the first two K fragments, already
+// requested by the caller; nkboff: K half of the following sub-step, whose
+// first two fragments are requested here and returned in f0, f1.
+__device__ __forceinline__ void steady_substep(const LaneAddr &la, uint32_t kboff, uint32_t vboff, uint32_t nkboff,
+                                               bf16x8 &f0, bf16x8 &f1, const bf16x8 (&qf)[2][kKS], f32x16 (&s_next)[2],
+                                               f32x16 (&s_cur)[2], bf16x8 (&p_cur)[2][2], const bf16x8 (&p_prev)[2][2],
+                                               f32x16 (&o)[kDB][2], RowState &st, float c2, float (&alpha)[2]) {
     SoftmaxScratch w;
-    bf16x8 frag[16];  // 0..7: K fragments by k-step; 8..15: V^T fragments by (16-key step, d block)
+    bf16x8 frag[18];  // 0..7: K fragments by k-step; 8..15: V^T fragments by (16-key step, d block); 16, 17: next
+    frag[0] = f0;
+    frag[1] = f1;
     auto load_frag = [&](int i) {
-        frag[i] = (i < 8) ? load_k_frag(kaddr, i) : load_v_frag(vaddr, (i - 8) / kDB, (i - 8) % kDB);
+        if (i < 8)
+            frag[i] = load_k_frag(la, kboff, i);
+        else if (i < 16)
+            frag[i] = load_v_frag(la, vboff, (i - 8) / kDB, (i - 8) % kDB);
+        else
+            frag[i] = load_k_frag(la, nkboff, i - 16);
     };
-    load_frag(0);
-    load_frag(1);
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        if (i + 2 < 16) load_frag(i + 2);
+        load_frag(i + 2);
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             if (i == 0) {
@@ -296,6 +338,8 @@ __device__ __forceinline__ void steady_substep(uint32_t kaddr, uint32_t vaddr, c
             __builtin_amdgcn_sched_barrier(0);
         }
     }
+    f0 = frag[16];
+    f1 = frag[17];
 }
 
 __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const FwdParams p) {
@@ -334,7 +378,10 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
     // ---- HBM -> LDS tile copies -------------------------------------------------
     // One wave instruction moves 64 x 16 bytes = 4 rows of the tile; the LDS
     // side is linear in the lane id, the swizzle is applied on the global side:
-    // LDS chunk (row, c') receives global chunk c' ^ f(row) of that row.
+    // LDS chunk (row, c') receives global chunk c' ^ f(row) of that row, with
+    // f(row) = ((row & 7) << 1) | ((row >> 3) & 1) for K (16 consecutive rows
+    // read the same logical chunk) and (row & 3) << 2 for V (4 consecutive rows
+    // read the same 64 bytes).
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int lrow = lane >> 4;  // row within the 4-row group
     const int lchk = lane & 15;  // LDS chunk within the row
@@ -362,7 +409,7 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
     issue_k(2, 2);
     issue_v(1, 1);
 
-    // ---- Q fragments (B operand of S^T = K Q^T) ------------------------------------
+    // ---- Q fragments (B operand of S^T = K Q^T), parked in AccVGPRs -------------------
     bf16x8 qf[2][kKS];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
@@ -388,13 +435,20 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
     rs.mc[0] = rs.mc[1] = -INFINITY;
     rs.l[0] = rs.l[1] = 0.f;
 
-    // per-lane LDS read addresses inside a tile (swizzle folded in)
-    const int fr = ((l32 & 7) << 1) | ((l32 >> 3) & 1);
-    const uint32_t k_lane = (uint32_t)(l32 * 256 + ((hf ^ fr) << 4));
-    const int j16 = lane & 15, grp = lane >> 4;
-    const int low2 = 2 * (grp & 1) + ((j16 & 3) >> 1);
-    const uint32_t v_lane =
-        (uint32_t)(kVRing + (4 * hf + (j16 >> 2)) * 256 + (((((j16 >> 2) & 3) << 2) | low2) << 4) + 8 * (j16 & 1));
+    // per-lane LDS read offsets inside a half tile (swizzle folded in)
+    LaneAddr la;
+    {
+        const int fr = ((l32 & 7) << 1) | ((l32 >> 3) & 1);
+        const uint32_t k_lane = (uint32_t)(l32 * 256 + ((hf ^ fr) << 4));
+#pragma unroll
+        for (int ks = 0; ks < kKS; ++ks) la.k[ks] = k_lane ^ (uint32_t)(ks << 5);
+        const int j16 = lane & 15, grp = lane >> 4;
+        const int low2 = 2 * (grp & 1) + ((j16 & 3) >> 1);
+        const uint32_t v_lane =
+            (uint32_t)(kVRing + (4 * hf + (j16 >> 2)) * 256 + (((((j16 >> 2) & 3) << 2) | low2) << 4) + 8 * (j16 & 1));
+#pragma unroll
+        for (int db = 0; db < kDB; ++db) la.v[db] = v_lane ^ (uint32_t)(db << 6);
+    }
 
     const float c2 = p.scale_log2;
 
@@ -408,7 +462,7 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
         return (k0h + 31 <= p0) && ((k0h > p0 + kWaveRows - 1 - W) || (k0h + 31 < S));
     };
 
-    f32x16 s_a[2], s_b[2];      // scores of half 0 / half 1 of a tile
+    f32x16 s_a[2], s_b[2];        // scores of half 0 / half 1 of a tile
     bf16x8 p_a[2][2], p_b[2][2];  // their P^T fragments
     float alpha[2];
 
@@ -419,52 +473,53 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
     int k0_cur = tile_of(0) * kBk;
     bool act_prev1 = false;  // half 1 of the previous tile
     bool act0 = half_active(k0_cur), act1 = half_active(k0_cur + 32);
-    if (act0) qk_half(k_lane, qf, s_a);
+    if (act0) qk_half(la, 0, qf, s_a);
 
     int r3 = 0;  // j % 3
     for (int j = 0; j < J; ++j) {
-        const int r3n = (r3 == 2) ? 0 : r3 + 1;   // (j + 1) % 3
-        const int r3p = (r3 == 0) ? 2 : r3 - 1;   // (j - 1) % 3
+        const int r3n = (r3 == 2) ? 0 : r3 + 1;  // (j + 1) % 3
+        const int r3p = (r3 == 0) ? 2 : r3 - 1;  // (j - 1) % 3
         const bool has_next = (j + 1) < J;
         const int k0_next = has_next ? tile_of(j + 1) * kBk : 0;
         const bool act_next0 = has_next && half_active(k0_next);
         const bool act_next1 = has_next && half_active(k0_next + 32);
         const bool unm0 = half_unmasked(k0_cur), unm1 = half_unmasked(k0_cur + 32);
 
-        const uint32_t ka_cur1 = k_lane + r3 * kTileBytes + kHalfBytes;  // K(j), half 1
-        const uint32_t ka_next0 = k_lane + r3n * kTileBytes;             // K(j+1), half 0
-        const uint32_t va_prev1 = v_lane + r3p * kTileBytes + kHalfBytes;  // V(j-1), half 1
-        const uint32_t va_cur0 = v_lane + r3 * kTileBytes;                 // V(j), half 0
+        const uint32_t kb_cur1 = (uint32_t)(r3 * kTileBytes + kHalfBytes);    // K(j), half 1
+        const uint32_t kb_next0 = (uint32_t)(r3n * kTileBytes);               // K(j+1), half 0
+        const uint32_t kb_next1 = kb_next0 + kHalfBytes;                      // K(j+1), half 1
+        const uint32_t vb_prev1 = (uint32_t)(r3p * kTileBytes + kHalfBytes);  // V(j-1), half 1
+        const uint32_t vb_cur0 = (uint32_t)(r3 * kTileBytes);                 // V(j), half 0
 
         if (act_prev1 && act0 && act1 && act_next0 && unm0 && unm1) {
             // steady state: three independent streams per sub-step
-            steady_substep(ka_cur1, va_prev1, qf, s_b, s_a, p_a, p_b, oacc, rs, c2, alpha);
+            bf16x8 f0 = load_k_frag(la, kb_cur1, 0);
+            bf16x8 f1 = load_k_frag(la, kb_cur1, 1);
+            steady_substep(la, kb_cur1, vb_prev1, kb_next0, f0, f1, qf, s_b, s_a, p_a, p_b, oacc, rs, c2, alpha);
             rescale(oacc, alpha);
-            steady_substep(ka_next0, va_cur0, qf, s_a, s_b, p_b, p_a, oacc, rs, c2, alpha);
+            steady_substep(la, kb_next0, vb_cur0, kb_next1, f0, f1, qf, s_a, s_b, p_b, p_a, oacc, rs, c2, alpha);
             rescale(oacc, alpha);
         } else {
             // edges of the band, the sink tile, first and last tile: same
             // stages, each guarded; the element mask is applied where needed
-            if (act1) qk_half(ka_cur1, qf, s_b);
+            if (act1) qk_half(la, kb_cur1, qf, s_b);
             if (act0) {
-                settle_s(s_a);
                 if (unm0)
                     softmax_half<false>(s_a, k0_cur, p0, W, S, l32, hf, c2, rs, p_a, alpha);
                 else
                     softmax_half<true>(s_a, k0_cur, p0, W, S, l32, hf, c2, rs, p_a, alpha);
             }
-            if (act_prev1) pv_half(va_prev1, p_b, oacc);
+            if (act_prev1) pv_half(la, vb_prev1, p_b, oacc);
             if (act0) rescale(oacc, alpha);
 
-            if (act_next0) qk_half(ka_next0, qf, s_a);
+            if (act_next0) qk_half(la, kb_next0, qf, s_a);
             if (act1) {
-                settle_s(s_b);
                 if (unm1)
                     softmax_half<false>(s_b, k0_cur + 32, p0, W, S, l32, hf, c2, rs, p_b, alpha);
                 else
                     softmax_half<true>(s_b, k0_cur + 32, p0, W, S, l32, hf, c2, rs, p_b, alpha);
             }
-            if (act0) pv_half(va_cur0, p_a, oacc);
+            if (act0) pv_half(la, vb_cur0, p_a, oacc);
             if (act1) rescale(oacc, alpha);
         }
 
@@ -483,10 +538,10 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
     // pipeline drain: P V of the last half (V(J-1) sits in buffer (J-1) % 3)
     if (act_prev1) {
         const int r3l = (r3 == 0) ? 2 : r3 - 1;
-        pv_half(v_lane + r3l * kTileBytes + kHalfBytes, p_b, oacc);
+        pv_half(la, (uint32_t)(r3l * kTileBytes + kHalfBytes), p_b, oacc);
     }
 
-    // ---- epilogue: O / l -> bf16, lse = (m*c2 + log2 l) * ln 2 ----------------------
+    // ---- epilogue: O / l -> bf16, lse = (mc + log2 l) * ln 2 -------------------------
     if (!wave_active) return;
     settle_acc(oacc);
 #pragma unroll
