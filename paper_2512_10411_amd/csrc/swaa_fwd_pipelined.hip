@@ -18,11 +18,14 @@
 //     (every MFMA leaves room for about seven other instructions), so the
 //     register files are assigned by hand -- O^T and Q in AccVGPRs, S^T, P^T
 //     and the K/V fragments in VGPRs -- which keeps copies out of the loop.
-//   * The running maximum is a reference value that moves only when a row's
-//     maximum grows by more than 2^8 (in the exp2 domain); O and the row sum
-//     are rescaled only then.  Results are mathematically unchanged, values of
-//     P stay below 2^8, and the rescale of the 64x128 accumulator all but
-//     disappears from the steady state.
+//   * The running maximum is a reference value: softmax is invariant to the
+//     value subtracted before the exponential, so the reference only has to
+//     keep exp2() inside the fp32/bf16 range.  It is set from the first half a
+//     wave processes and moves later only when a row sum shows that scores have
+//     outgrown it (or, on edge tiles, when the maximum grows by more than 2^8);
+//     O and the row sum are rescaled only then.  Results are mathematically
+//     unchanged and the search for the row maximum as well as the rescale of
+//     the 64x128 accumulator disappear from the steady state.
 //
 // This kernel declares no static LDS: its dynamic LDS starts at address 0 and
 // all LDS accesses below use plain byte addresses.
@@ -209,95 +212,62 @@ __device__ __forceinline__ void rescale(f32x16 (&o)[kDB][2], const float (&alpha
 // ---- steady-state step, scheduled by hand ----------------------------------------
 // A sub-step issues 32 MFMAs: S^T(n+1) = K Q^T (16) and O^T += V^T P^T(n-1) (16),
 // and in their shadow the vector work of the softmax of half n, cut into 32
-// chunks of about six instructions.  Scheduling fences pin the order
-// "MFMA, chunk, MFMA, chunk, ..." so that the matrix pipe is re-fed as soon as
-// it drains while the wave keeps issuing vector instructions in between.  LDS
-// fragment reads are issued two MFMA pairs ahead of their use, across the
-// boundary between the two sub-steps of a step as well.
+// chunks.  Scheduling fences pin the order "MFMA, chunk, MFMA, chunk, ..." so
+// that the matrix pipe is re-fed as soon as it drains while the wave keeps
+// issuing vector instructions in between.  LDS fragment reads are issued two
+// MFMA pairs ahead of their use, across the boundary between the two sub-steps
+// of a step as well.
+//
+// In the steady state the softmax does not look for the row maximum at all:
+// it keeps the reference it has (set by the first half the wave processed) and
+// only watches the row sums.  exp2(s*c2 - mc) cannot overflow fp32 or bf16
+// unless a score exceeds the reference by more than 2^7 in the exp2 domain; a
+// row sum at or above kSumLimit sends the half through the max-based routine
+// again (which moves the reference and rescales), everything else is the plain
+// "subtract, exponentiate, add, pack" at 4.5 instructions per score.
+constexpr float kSumLimit = 1.0995116e12f;  // 2^40
+
 struct SoftmaxScratch {
-    float t[2][7];
-    float mx[2];
-    float mc_old[2];
-    float mc_use[2];
-    bool move[2];
-    float x[3];
     float pe[32];
     float sum[2][2];
+    float l_new[2];
+    bool over;
 };
 
-__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+// element index handled up to (exclusive) chunk c: 32 scores over the first 29 chunks
+__device__ __forceinline__ constexpr int chunk_first_elem(int c) { return c >= 29 ? 32 : (c * 32) / 29; }
 
-constexpr int kChunkExp0 = 8;  // first exponential chunk
-constexpr int kChunkSum = 30;  // row-sum reduction chunk
-
-__device__ __forceinline__ void softmax_chunk(int c, f32x16 (&s)[2], float c2, RowState &st, SoftmaxScratch &w,
-                                              bf16x8 (&pf)[2][2], float (&alpha)[2]) {
-    if (c < kChunkExp0) {  // maxima and reference update: chunks 0-3 query block 0, 4-7 block 1
-        const int qb = c / 4;
-        const f32x16 &v = s[qb];
-        switch (c % 4) {
-            case 0:
-                w.t[qb][0] = max3(v[0], v[1], v[2]);
-                w.t[qb][1] = max3(v[3], v[4], v[5]);
-                w.t[qb][2] = max3(v[6], v[7], v[8]);
-                w.t[qb][3] = max3(v[9], v[10], v[11]);
-                w.t[qb][4] = max3(v[12], v[13], v[14]);
-                break;
-            case 1:
-                w.t[qb][5] = max3(w.t[qb][0], w.t[qb][1], v[15]);
-                w.t[qb][6] = max3(w.t[qb][2], w.t[qb][3], w.t[qb][4]);
-                w.mx[qb] = half_swap_max(fmaxf(w.t[qb][5], w.t[qb][6]));
-                break;
-            case 2: {
-                const float mc_old = st.mc[qb];
-                const float m_new = fmaxf(mc_old, w.mx[qb] * c2);
-                w.move[qb] = m_new > mc_old + kRefSlack;
-                w.mc_old[qb] = mc_old;
-                st.mc[qb] = w.move[qb] ? m_new : mc_old;
-                w.mc_use[qb] = st.mc[qb];
-                break;
-            }
-            default:
-                alpha[qb] = w.move[qb] ? __builtin_amdgcn_exp2f(w.mc_old[qb] - w.mc_use[qb]) : 1.f;
-                break;
-        }
-    } else if (c < kChunkSum) {  // exponentials: three score elements per pair of chunks
-        const int k = (c - kChunkExp0) / 2;
-        const int g0 = 3 * k;
-        if (((c - kChunkExp0) & 1) == 0) {
+__device__ __forceinline__ void softmax_chunk(int c, const f32x16 (&s)[2], float c2, const RowState &st,
+                                              SoftmaxScratch &w, bf16x8 (&pf)[2][2]) {
+    // exponentials of this chunk's scores
 #pragma unroll
-            for (int i = 0; i < 3; ++i) {
-                const int g = g0 + i;
-                if (g < 32) w.x[i] = fmaf(s[g / 16][g % 16], c2, -w.mc_use[g / 16]);
-            }
+    for (int g = chunk_first_elem(c); g < chunk_first_elem(c + 1); ++g)
+        w.pe[g] = __builtin_amdgcn_exp2f(fmaf(s[g / 16][g % 16], c2, -st.mc[g / 16]));
+    // sums and packing trail one chunk behind, so that no instruction waits on
+    // a transcendental issued just before it
+    if (c >= 1 && c <= 29) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
-                if (g0 + i < 32) w.pe[g0 + i] = __builtin_amdgcn_exp2f(w.x[i]);
-        } else {
-            if (g0 + 2 < 32) w.pe[g0 + 2] = __builtin_amdgcn_exp2f(w.x[2]);
-#pragma unroll
-            for (int i = 0; i < 3; ++i) {
-                const int g = g0 + i;
-                if (g < 32) {
-                    const int qb = g / 16, e = g % 16;
-                    if (e < 2)
-                        w.sum[qb][e] = w.pe[g];
-                    else
-                        w.sum[qb][e & 1] += w.pe[g];
-                    if (e & 1) {  // the pair (e-1, e) is complete: pack it
-                        pf[qb][e / 8][(e - 1) % 8] = (__bf16)w.pe[g - 1];
-                        pf[qb][e / 8][e % 8] = (__bf16)w.pe[g];
-                        if (e % 8 == 7) pin_p(pf[qb][e / 8]);
-                    }
-                }
+        for (int g = chunk_first_elem(c - 1); g < chunk_first_elem(c); ++g) {
+            const int qb = g / 16, e = g % 16;
+            if (e < 2)
+                w.sum[qb][e] = w.pe[g];
+            else
+                w.sum[qb][e & 1] += w.pe[g];
+            if (e & 1) {  // the pair (e-1, e) is complete: pack it
+                pf[qb][e / 8][(e - 1) % 8] = (__bf16)w.pe[g - 1];
+                pf[qb][e / 8][e % 8] = (__bf16)w.pe[g];
+                if (e % 8 == 7) pin_p(pf[qb][e / 8]);
             }
         }
-    } else if (c == kChunkSum) {
+    }
+    if (c == 30) {
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            const float rs = half_swap_sum(w.sum[qb][0] + w.sum[qb][1]);
-            st.l[qb] = st.l[qb] * alpha[qb] + rs;
-        }
+        for (int qb = 0; qb < 2; ++qb) w.sum[qb][0] = half_swap_sum(w.sum[qb][0] + w.sum[qb][1]);
+    }
+    if (c == 31) {
+        w.over = (w.sum[0][0] >= kSumLimit) || (w.sum[1][0] >= kSumLimit);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) w.l_new[qb] = st.l[qb] + w.sum[qb][0];
     }
 }
 
@@ -305,10 +275,12 @@ __device__ __forceinline__ void softmax_chunk(int c, f32x16 (&s)[2], float c2, R
 // and the V half to accumulate.  f0, f1: the first two K fragments, already
 // requested by the caller; nkboff: K half of the following sub-step, whose
 // first two fragments are requested here and returned in f0, f1.
-__device__ __forceinline__ void steady_substep(const LaneAddr &la, uint32_t kboff, uint32_t vboff, uint32_t nkboff,
+// Returns true when some row sum in the wave reached kSumLimit; st.l is then
+// left untouched and the caller redoes the softmax of this half.
+__device__ __forceinline__ bool steady_substep(const LaneAddr &la, uint32_t kboff, uint32_t vboff, uint32_t nkboff,
                                                bf16x8 &f0, bf16x8 &f1, const bf16x8 (&qf)[2][kKS], f32x16 (&s_next)[2],
-                                               f32x16 (&s_cur)[2], bf16x8 (&p_cur)[2][2], const bf16x8 (&p_prev)[2][2],
-                                               f32x16 (&o)[kDB][2], RowState &st, float c2, float (&alpha)[2]) {
+                                               const f32x16 (&s_cur)[2], bf16x8 (&p_cur)[2][2],
+                                               const bf16x8 (&p_prev)[2][2], f32x16 (&o)[kDB][2], RowState &st, float c2) {
     SoftmaxScratch w;
     bf16x8 frag[18];  // 0..7: K fragments by k-step; 8..15: V^T fragments by (16-key step, d block); 16, 17: next
     frag[0] = f0;
@@ -334,12 +306,18 @@ __device__ __forceinline__ void steady_substep(const LaneAddr &la, uint32_t kbof
                 mfma_acc(o[(i - 8) % kDB][qb], frag[i], p_prev[qb][(i - 8) / kDB]);
             }
             __builtin_amdgcn_sched_barrier(0);
-            softmax_chunk(2 * i + qb, s_cur, c2, st, w, p_cur, alpha);
+            softmax_chunk(2 * i + qb, s_cur, c2, st, w, p_cur);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
     f0 = frag[16];
     f1 = frag[17];
+    const bool over = __any(w.over);
+    if (!over) {
+        st.l[0] = w.l_new[0];
+        st.l[1] = w.l_new[1];
+    }
+    return over;
 }
 
 __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const FwdParams p) {
@@ -495,10 +473,17 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
             // steady state: three independent streams per sub-step
             bf16x8 f0 = load_k_frag(la, kb_cur1, 0);
             bf16x8 f1 = load_k_frag(la, kb_cur1, 1);
-            steady_substep(la, kb_cur1, vb_prev1, kb_next0, f0, f1, qf, s_b, s_a, p_a, p_b, oacc, rs, c2, alpha);
-            rescale(oacc, alpha);
-            steady_substep(la, kb_next0, vb_cur0, kb_next1, f0, f1, qf, s_a, s_b, p_b, p_a, oacc, rs, c2, alpha);
-            rescale(oacc, alpha);
+            // a row that has seen no key yet (fully masked so far) takes 0 as its reference
+            rs.mc[0] = (rs.mc[0] == -INFINITY) ? 0.f : rs.mc[0];
+            rs.mc[1] = (rs.mc[1] == -INFINITY) ? 0.f : rs.mc[1];
+            if (steady_substep(la, kb_cur1, vb_prev1, kb_next0, f0, f1, qf, s_b, s_a, p_a, p_b, oacc, rs, c2)) {
+                softmax_half<false>(s_a, k0_cur, p0, W, S, l32, hf, c2, rs, p_a, alpha);
+                rescale(oacc, alpha);
+            }
+            if (steady_substep(la, kb_next0, vb_cur0, kb_next1, f0, f1, qf, s_a, s_b, p_b, p_a, oacc, rs, c2)) {
+                softmax_half<false>(s_b, k0_cur + 32, p0, W, S, l32, hf, c2, rs, p_b, alpha);
+                rescale(oacc, alpha);
+            }
         } else {
             // edges of the band, the sink tile, first and last tile: same
             // stages, each guarded; the element mask is applied where needed

@@ -95,6 +95,24 @@ def test_sink_heavy_scores_stress_rescaling():
     assert_parity(out, lse, ro, rl, tag="sink heavy")
 
 
+@pytest.mark.parametrize("spike", [40.0, 160.0, 1024.0])
+def test_late_score_spike_far_above_the_first_keys(spike):
+    # interior tiles do not search for the row maximum; a key whose score
+    # exceeds everything seen before by tens of nats must still come out right
+    B, Hq, Hkv, N, D, W, S = 1, 4, 1, 3100, 128, 1024, 4
+    q, k, v = make_qkv(B, Hq, Hkv, N, D, seed=45)
+    qf, kf = bf16_bits_to_f32(q), bf16_bits_to_f32(k)
+    qf[..., 0] = 3.0
+    kf[..., 0] = 0.0
+    kf[:, :, 2500, 0] = spike     # +spike*3*scale nats at one interior key
+    kf[:, :, 2700, 0] = -spike    # and a very negative one
+    q, k = f32_to_bf16_bits(qf), f32_to_bf16_bits(kf)
+    scale = 1 / math.sqrt(D)
+    out, lse = run_gpu(q, k, v, W, S, scale)
+    ro, rl = swaa_attn_oracle(q, k, v, W, S, scale)
+    assert_parity(out, lse, ro, rl, tag=f"late spike {spike}")
+
+
 def test_caller_buffers_stream_and_errors():
     q, k, v = make_qkv(1, 4, 4, 256, 64, seed=44)
     qd, kd, vd = to_device(q), to_device(k), to_device(v)
