@@ -11,7 +11,8 @@ import math
 import os
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libswaa.so")
+# SWAA_LIB selects another build of the same library (A/B timing of kernel variants)
+LIB_PATH = os.environ.get("SWAA_LIB") or os.path.join(_PKG, "libswaa.so")
 
 SWAA_OK = 0
 SWAA_ERR_NULL = -1

@@ -35,9 +35,9 @@ def hipcc_path() -> str:
     return exe
 
 
-def build_library(verbose: bool = False, extra_flags=()) -> str:
-    """Compile every HIP source into paper_2512_10411_amd/libswaa.so."""
-    tmp = LIB + ".tmp.%d" % os.getpid()
+def build_library(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
+    """Compile every HIP source into paper_2512_10411_amd/libswaa.so (or `out`)."""
+    tmp = out + ".tmp.%d" % os.getpid()
     cmd = [hipcc_path(), *HIPCC_FLAGS, *extra_flags, "-o", tmp, *SOURCES]
     if verbose:
         print(" ".join(cmd))
@@ -47,8 +47,8 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
     if verbose and res.stdout.strip():
         # the host pass warns that it does not know the packed-fp32 feature: harmless
         print("\n".join(ln for ln in res.stdout.splitlines() if "packed-fp32-ops" not in ln))
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, out)
+    return out
 
 
 if __name__ == "__main__":

@@ -39,11 +39,15 @@ namespace {
 constexpr int kD = 128;
 constexpr int kKS = kD / 16;  // k-steps of K Q^T
 constexpr int kDB = kD / 32;  // 32-wide blocks of the head dimension
-constexpr int kStages = 3;
+#ifndef SWAA_STAGES
+#define SWAA_STAGES 4
+#endif
+constexpr int kStages = SWAA_STAGES;  // tiles per ring: 3 (copies one step ahead) or 4 (two steps ahead)
+static_assert(kStages == 3 || kStages == 4, "ring depth");
 constexpr int kTileBytes = kBk * kD * 2;              // 16 KiB
 constexpr int kHalfBytes = kTileBytes / 2;            // one 32-key half
 constexpr int kVRing = kStages * kTileBytes;          // V ring follows the K ring
-constexpr int kSmemBytes = 2 * kStages * kTileBytes;  // 96 KiB
+constexpr int kSmemBytes = 2 * kStages * kTileBytes;  // 96 or 128 KiB
 constexpr float kRefSlack = 8.f;  // log2 units a row maximum may exceed its reference
 
 extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -214,9 +218,9 @@ __device__ __forceinline__ void rescale(f32x16 (&o)[kDB][2], const float (&alpha
 // and in their shadow the vector work of the softmax of half n, cut into 32
 // chunks.  Scheduling fences pin the order "MFMA, chunk, MFMA, chunk, ..." so
 // that the matrix pipe is re-fed as soon as it drains while the wave keeps
-// issuing vector instructions in between.  LDS fragment reads are issued two
-// MFMA pairs ahead of their use, across the boundary between the two sub-steps
-// of a step as well.
+// issuing vector instructions in between.  LDS fragment reads are issued
+// kPrefetch MFMA pairs ahead of their use, across the boundary between the two
+// sub-steps of a step as well.
 //
 // In the steady state the softmax does not look for the row maximum at all:
 // it keeps the reference it has (set by the first half the wave processed) and
@@ -272,19 +276,25 @@ __device__ __forceinline__ void softmax_chunk(int c, const f32x16 (&s)[2], float
 }
 
 // One sub-step.  kboff / vboff: uniform byte offsets of the K half to multiply
-// and the V half to accumulate.  f0, f1: the first two K fragments, already
+// and the V half to accumulate.  fpre: the first kPrefetch K fragments, already
 // requested by the caller; nkboff: K half of the following sub-step, whose
-// first two fragments are requested here and returned in f0, f1.
+// first kPrefetch fragments are requested here and returned in fpre.
 // Returns true when some row sum in the wave reached kSumLimit; st.l is then
 // left untouched and the caller redoes the softmax of this half.
+#ifndef SWAA_PREFETCH
+#define SWAA_PREFETCH 3
+#endif
+constexpr int kPrefetch = SWAA_PREFETCH;  // MFMA pairs between an LDS fragment read and its use
+
 __device__ __forceinline__ bool steady_substep(const LaneAddr &la, uint32_t kboff, uint32_t vboff, uint32_t nkboff,
-                                               bf16x8 &f0, bf16x8 &f1, const bf16x8 (&qf)[2][kKS], f32x16 (&s_next)[2],
-                                               const f32x16 (&s_cur)[2], bf16x8 (&p_cur)[2][2],
+                                               bf16x8 (&fpre)[kPrefetch], const bf16x8 (&qf)[2][kKS],
+                                               f32x16 (&s_next)[2], const f32x16 (&s_cur)[2], bf16x8 (&p_cur)[2][2],
                                                const bf16x8 (&p_prev)[2][2], f32x16 (&o)[kDB][2], RowState &st, float c2) {
     SoftmaxScratch w;
-    bf16x8 frag[18];  // 0..7: K fragments by k-step; 8..15: V^T fragments by (16-key step, d block); 16, 17: next
-    frag[0] = f0;
-    frag[1] = f1;
+    // 0..7: K fragments by k-step; 8..15: V^T fragments by (16-key step, d block); 16..: next sub-step's K
+    bf16x8 frag[16 + kPrefetch];
+#pragma unroll
+    for (int i = 0; i < kPrefetch; ++i) frag[i] = fpre[i];
     auto load_frag = [&](int i) {
         if (i < 8)
             frag[i] = load_k_frag(la, kboff, i);
@@ -295,7 +305,7 @@ __device__ __forceinline__ bool steady_substep(const LaneAddr &la, uint32_t kbof
     };
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        load_frag(i + 2);
+        load_frag(i + kPrefetch);
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             if (i == 0) {
@@ -310,8 +320,8 @@ __device__ __forceinline__ bool steady_substep(const LaneAddr &la, uint32_t kbof
             __builtin_amdgcn_sched_barrier(0);
         }
     }
-    f0 = frag[16];
-    f1 = frag[17];
+#pragma unroll
+    for (int i = 0; i < kPrefetch; ++i) fpre[i] = frag[16 + i];
     const bool over = __any(w.over);
     if (!over) {
         st.l[0] = w.l_new[0];
@@ -363,29 +373,45 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int lrow = lane >> 4;  // row within the 4-row group
     const int lchk = lane & 15;  // LDS chunk within the row
+    // byte offset of this lane's 16 bytes inside a tile, instruction 0; K adds an
+    // XOR per instruction because its swizzle uses row bits 2 and 3
+    const uint32_t voff_k = (uint32_t)((16 * wave + lrow) * 256 + ((lchk ^ (lrow << 1)) << 4));
+    const uint32_t voff_v = (uint32_t)((16 * wave + lrow) * 256 + ((lchk ^ (lrow << 2)) << 4));
     auto issue_tile = [&](int j, int buf, const __bf16 *src, int ring, bool is_k) {
         if (j >= J) return;
         const int k0 = tile_of(j) * kBk;
+        const char *base = reinterpret_cast<const char *>(src) + (size_t)k0 * (kD * 2);  // uniform
+        const bool tail = k0 + kBk > N;  // rows past the end are masked later; keep the reads in bounds
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int row = 16 * wave + 4 * i + lrow;
-            const int grow = min(k0 + row, N - 1);  // rows past the end are masked, keep the read in bounds
-            const int f = is_k ? (((4 * (i & 1) + lrow) << 1) | (i >> 1)) : (lrow << 2);
-            const __bf16 *g = src + (size_t)grow * kD + ((lchk ^ f) << 3);
+            // K: f(row) = ((4*(i&1) + lrow) << 1) | (i >> 1)  =>  chunk = lchk ^ (lrow<<1) ^ {0, 8, 1, 9}[i]
+            const uint32_t sw = is_k ? (uint32_t)((((i & 1) << 3) | (i >> 1)) << 4) : 0u;
+            uint32_t off = ((is_k ? voff_k : voff_v) ^ sw) + (uint32_t)(i * 1024);
+            if (tail) {
+                const int row = 16 * wave + 4 * i + lrow;
+                off -= (uint32_t)(max(k0 + row - (N - 1), 0) * (kD * 2));
+            }
             const uint32_t l = (uint32_t)(ring + buf * kTileBytes + (4 * wave_u + i) * 1024);
-            // LDS address = M0 + 16 * lane.  Issued as assembly on purpose: the
-            // compiler would otherwise make every later LDS read wait for it.
-            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(l) : "memory");
+            // LDS address = M0 + 16 * lane; global address = base + off.  Issued as
+            // assembly on purpose: the compiler would otherwise make every later
+            // LDS read wait for it.
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(l)
+                         : "memory");
         }
     };
     auto issue_k = [&](int j, int buf) { issue_tile(j, buf, kg, 0, true); };
     auto issue_v = [&](int j, int buf) { issue_tile(j, buf, vg, kVRing, false); };
 
+    // in the order they are needed: step 0 reads K(0), K(1), V(0)
     issue_k(0, 0);
     issue_v(0, 0);
     issue_k(1, 1);
     issue_k(2, 2);
     issue_v(1, 1);
+    if (kStages == 4) {
+        issue_k(3, 3);
+        issue_v(2, 2);
+    }
 
     // ---- Q fragments (B operand of S^T = K Q^T), parked in AccVGPRs -------------------
     bf16x8 qf[2][kKS];
@@ -447,46 +473,55 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's copies and Q loads have landed
     __syncthreads();
 
+    // Tiles on which this wave runs the hand-scheduled steady step: both halves
+    // fully visible to all 64 rows (inside every row's window and at or below
+    // the first row's diagonal), the previous tile's second half and the next
+    // tile's first half active too.  In tile numbers that is the band tiles t
+    // with 64 t > p0 + 63 - W, t > t_band_lo and 64 t + 63 <= p0.
+    const int w_lo = p0 + kWaveRows - 1 - W;
+    const int t_s_lo = max(t_band_lo + 1, w_lo >= 0 ? w_lo / kBk + 1 : 0);
+    const int t_s_hi = p0 / kBk - 1;
+    const int js_lo = wave_active ? t_s_lo - t_band_lo + n_sink_tiles : J;
+    const int js_hi = t_s_hi - t_band_lo + n_sink_tiles;
+
     // pipeline prologue: scores of the very first half
-    int k0_cur = tile_of(0) * kBk;
-    bool act_prev1 = false;  // half 1 of the previous tile
-    bool act0 = half_active(k0_cur), act1 = half_active(k0_cur + 32);
-    if (act0) qk_half(la, 0, qf, s_a);
+    if (half_active(tile_of(0) * kBk)) qk_half(la, 0, qf, s_a);
 
-    int r3 = 0;  // j % 3
+    int r3 = 0;  // j % kStages
     for (int j = 0; j < J; ++j) {
-        const int r3n = (r3 == 2) ? 0 : r3 + 1;  // (j + 1) % 3
-        const int r3p = (r3 == 0) ? 2 : r3 - 1;  // (j - 1) % 3
-        const bool has_next = (j + 1) < J;
-        const int k0_next = has_next ? tile_of(j + 1) * kBk : 0;
-        const bool act_next0 = has_next && half_active(k0_next);
-        const bool act_next1 = has_next && half_active(k0_next + 32);
-        const bool unm0 = half_unmasked(k0_cur), unm1 = half_unmasked(k0_cur + 32);
-
+        const int r3n = (r3 == kStages - 1) ? 0 : r3 + 1;  // (j + 1) % kStages
+        const int r3p = (r3 == 0) ? kStages - 1 : r3 - 1;  // (j - 1) % kStages
         const uint32_t kb_cur1 = (uint32_t)(r3 * kTileBytes + kHalfBytes);    // K(j), half 1
         const uint32_t kb_next0 = (uint32_t)(r3n * kTileBytes);               // K(j+1), half 0
         const uint32_t kb_next1 = kb_next0 + kHalfBytes;                      // K(j+1), half 1
         const uint32_t vb_prev1 = (uint32_t)(r3p * kTileBytes + kHalfBytes);  // V(j-1), half 1
         const uint32_t vb_cur0 = (uint32_t)(r3 * kTileBytes);                 // V(j), half 0
 
-        if (act_prev1 && act0 && act1 && act_next0 && unm0 && unm1) {
+        if (j >= js_lo && j <= js_hi) {
             // steady state: three independent streams per sub-step
-            bf16x8 f0 = load_k_frag(la, kb_cur1, 0);
-            bf16x8 f1 = load_k_frag(la, kb_cur1, 1);
+            bf16x8 fpre[kPrefetch];
+#pragma unroll
+            for (int i = 0; i < kPrefetch; ++i) fpre[i] = load_k_frag(la, kb_cur1, i);
             // a row that has seen no key yet (fully masked so far) takes 0 as its reference
             rs.mc[0] = (rs.mc[0] == -INFINITY) ? 0.f : rs.mc[0];
             rs.mc[1] = (rs.mc[1] == -INFINITY) ? 0.f : rs.mc[1];
-            if (steady_substep(la, kb_cur1, vb_prev1, kb_next0, f0, f1, qf, s_b, s_a, p_a, p_b, oacc, rs, c2)) {
-                softmax_half<false>(s_a, k0_cur, p0, W, S, l32, hf, c2, rs, p_a, alpha);
+            if (steady_substep(la, kb_cur1, vb_prev1, kb_next0, fpre, qf, s_b, s_a, p_a, p_b, oacc, rs, c2)) {
+                softmax_half<false>(s_a, 0, p0, W, S, l32, hf, c2, rs, p_a, alpha);
                 rescale(oacc, alpha);
             }
-            if (steady_substep(la, kb_next0, vb_cur0, kb_next1, f0, f1, qf, s_a, s_b, p_b, p_a, oacc, rs, c2)) {
-                softmax_half<false>(s_b, k0_cur + 32, p0, W, S, l32, hf, c2, rs, p_b, alpha);
+            if (steady_substep(la, kb_next0, vb_cur0, kb_next1, fpre, qf, s_a, s_b, p_b, p_a, oacc, rs, c2)) {
+                softmax_half<false>(s_b, 0, p0, W, S, l32, hf, c2, rs, p_b, alpha);
                 rescale(oacc, alpha);
             }
         } else {
             // edges of the band, the sink tile, first and last tile: same
             // stages, each guarded; the element mask is applied where needed
+            const int k0_cur = tile_of(j) * kBk;
+            const bool act_prev1 = j > 0 && half_active(tile_of(j - 1) * kBk + 32);
+            const bool act0 = half_active(k0_cur), act1 = half_active(k0_cur + 32);
+            const bool act_next0 = (j + 1) < J && half_active(tile_of(j + 1) * kBk);
+            const bool unm0 = half_unmasked(k0_cur), unm1 = half_unmasked(k0_cur + 32);
+
             if (act1) qk_half(la, kb_cur1, qf, s_b);
             if (act0) {
                 if (unm0)
@@ -508,21 +543,25 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
             if (act1) rescale(oacc, alpha);
         }
 
-        // K(j+2), V(j+1) must have landed; K(j) and V(j-1) are free afterwards
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();
-        issue_k(j + 3, r3);
-        issue_v(j + 2, r3p);
-
-        act_prev1 = act1;
-        act0 = act_next0;
-        act1 = act_next1;
-        k0_cur = k0_next;
+        // K(j+2), V(j+1) must have landed; K(j) and V(j-1) are free afterwards.
+        // With four stages the copies of K(j+3), V(j+2), issued one step ago,
+        // may stay in flight: they are the newest 8 (or 4) of this wave's loads.
+        if (kStages == 4 && j + 3 < J)
+            __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8)
+        else if (kStages == 4 && j + 2 < J)
+            __builtin_amdgcn_s_waitcnt(0x0F74);  // vmcnt(4)
+        else
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+        asm volatile("" ::: "memory");  // no LDS access may be moved across the barrier
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        issue_k(j + kStages, r3);
+        issue_v(j + kStages - 1, r3p);
         r3 = r3n;
     }
     // pipeline drain: P V of the last half (V(J-1) sits in buffer (J-1) % 3)
-    if (act_prev1) {
-        const int r3l = (r3 == 0) ? 2 : r3 - 1;
+    if (half_active(tile_of(J - 1) * kBk + 32)) {
+        const int r3l = (r3 == 0) ? kStages - 1 : r3 - 1;
         pv_half(la, (uint32_t)(r3l * kTileBytes + kHalfBytes), p_b, oacc);
     }
 
