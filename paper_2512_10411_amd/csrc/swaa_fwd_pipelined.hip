@@ -1,31 +1,33 @@
 // Software-pipelined SWA + sink attention forward, head dimension 128, gfx950.
 //
 // Same mask (paper Sec. 3.2.1 / Fig. 1b; full attention of Sec. 3.1.2 when the
-// window covers the context), same workgroup shape and tile schedule as the
-// plain kernel; what differs is how a wave walks the key axis:
+// window covers the context) and the same work decomposition as the plain
+// kernel: one workgroup = 256 query rows (4, 2 or 1 query heads x 64, 128 or
+// 256 positions) on one KV head.  What differs:
 //
+//   * Eight waves of 32 query rows, two per SIMD.  A single wave cannot keep
+//     the matrix pipe busy (back-to-back MFMAs of one wave issue about a third
+//     slower than the pipe could take them, and every vector instruction beyond
+//     four per MFMA adds to that); with two waves per SIMD one wave's
+//     exponentials run while the other wave's MFMAs execute.  Each wave fits in
+//     256 registers: O^T (64) and Q (32) in AccVGPRs, S^T, P^T and the K/V
+//     fragments in VGPRs.
 //   * K and V tiles (64 keys) travel HBM -> LDS with global_load_lds_dwordx4
-//     (no register staging) into two rings of three tiles each, XOR-swizzled
+//     (no register staging) into two rings of kStages tiles each, XOR-swizzled
 //     in 16-byte chunks so that the MFMA operand reads are bank-conflict free.
 //     One barrier per tile.
-//   * A wave works on half tiles of 32 keys in a three-stage pipeline:
-//     while the softmax of half n runs on the VALU, the matrix pipe computes
-//     S^T = K Q^T of half n+1 and O^T += V^T P^T of half n-1.  The three are
-//     independent, so the MFMAs and the exponentials of one wave overlap.
-//     In the steady state the interleaving is fixed by hand with scheduling
-//     fences: one MFMA, about six vector instructions, the next MFMA, ...
-//   * With one wave per SIMD the wave's own instruction issue is the limit
-//     (every MFMA leaves room for about seven other instructions), so the
-//     register files are assigned by hand -- O^T and Q in AccVGPRs, S^T, P^T
-//     and the K/V fragments in VGPRs -- which keeps copies out of the loop.
-//   * The running maximum is a reference value: softmax is invariant to the
-//     value subtracted before the exponential, so the reference only has to
-//     keep exp2() inside the fp32/bf16 range.  It is set from the first half a
-//     wave processes and moves later only when a row sum shows that scores have
-//     outgrown it (or, on edge tiles, when the maximum grows by more than 2^8);
-//     O and the row sum are rescaled only then.  Results are mathematically
-//     unchanged and the search for the row maximum as well as the rescale of
-//     the 64x128 accumulator disappear from the steady state.
+//   * A wave works on half tiles of 32 keys in a three-stage pipeline: while
+//     the softmax of half n runs on the VALU, the matrix pipe computes
+//     S^T = K Q^T of half n+1 and O^T += V^T P^T of half n-1.  In the steady
+//     state the interleaving is fixed by hand with scheduling fences.
+//   * The softmax reference: softmax is invariant to the value subtracted
+//     before the exponential, so the reference only has to keep exp2() inside
+//     the fp32/bf16 range.  It is set from the first half a wave processes and
+//     moves later only when a row sum shows that scores have outgrown it (or,
+//     on edge tiles, when the maximum grows by more than 2^8); O and the row
+//     sum are rescaled only then.  Results are mathematically unchanged; the
+//     search for the row maximum and the rescale of the accumulator disappear
+//     from the steady state.
 //
 // This kernel declares no static LDS: its dynamic LDS starts at address 0 and
 // all LDS accesses below use plain byte addresses.
@@ -39,8 +41,11 @@ namespace {
 constexpr int kD = 128;
 constexpr int kKS = kD / 16;  // k-steps of K Q^T
 constexpr int kDB = kD / 32;  // 32-wide blocks of the head dimension
+constexpr int kPWaves = 8;    // waves per workgroup
+constexpr int kPThreads = 64 * kPWaves;
+constexpr int kPRows = 32;  // query positions per wave
 #ifndef SWAA_STAGES
-#define SWAA_STAGES 4
+#define SWAA_STAGES 3
 #endif
 constexpr int kStages = SWAA_STAGES;  // tiles per ring: 3 (copies one step ahead) or 4 (two steps ahead)
 static_assert(kStages == 3 || kStages == 4, "ring depth");
@@ -48,9 +53,12 @@ constexpr int kTileBytes = kBk * kD * 2;              // 16 KiB
 constexpr int kHalfBytes = kTileBytes / 2;            // one 32-key half
 constexpr int kVRing = kStages * kTileBytes;          // V ring follows the K ring
 constexpr int kSmemBytes = 2 * kStages * kTileBytes;  // 96 or 128 KiB
-constexpr float kRefSlack = 8.f;  // log2 units a row maximum may exceed its reference
-
-extern __shared__ __attribute__((aligned(1024))) char smem[];
+constexpr float kRefSlack = 8.f;            // log2 units a row maximum may exceed its reference (edge tiles)
+constexpr float kSumLimit = 1.0995116e12f;  // 2^40: row sum of one half that sends it back to the max-based path
+#ifndef SWAA_PREFETCH
+#define SWAA_PREFETCH 3
+#endif
+constexpr int kPrefetch = SWAA_PREFETCH;  // MFMAs between an LDS fragment read and its use
 
 // ---- MFMA through inline assembly ------------------------------------------------
 // The compiler cannot be told to keep some MFMA operands in AccVGPRs and others
@@ -64,28 +72,22 @@ extern __shared__ __attribute__((aligned(1024))) char smem[];
 __device__ __forceinline__ void mfma_acc(f32x16 &acc, const bf16x8 a, const bf16x8 b) {
     asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
-// S^T accumulators: VGPR destination, Q operand read straight from AccVGPRs.
+// S^T accumulator: VGPR destination, Q operand read straight from AccVGPRs.
 __device__ __forceinline__ void mfma_s(f32x16 &s, const bf16x8 kfrag, const bf16x8 q_acc) {
     asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(kfrag), "a"(q_acc));
 }
 __device__ __forceinline__ void mfma_s_first(f32x16 &s, const bf16x8 kfrag, const bf16x8 q_acc) {
     asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(kfrag), "a"(q_acc));
 }
-__device__ __forceinline__ void settle_s(f32x16 (&s)[2]) {
-    asm volatile("s_nop 15\n\ts_nop 7" : "+v"(s[0]), "+v"(s[1]));
-}
-__device__ __forceinline__ void settle_acc(f32x16 (&o)[kDB][2]) {
-    asm volatile("s_nop 15\n\ts_nop 7"
-                 : "+a"(o[0][0]), "+a"(o[0][1]), "+a"(o[1][0]), "+a"(o[1][1]), "+a"(o[2][0]), "+a"(o[2][1]),
-                   "+a"(o[3][0]), "+a"(o[3][1]));
+__device__ __forceinline__ void settle_s(f32x16 &s) { asm volatile("s_nop 15\n\ts_nop 7" : "+v"(s)); }
+__device__ __forceinline__ void settle_acc(f32x16 (&o)[kDB]) {
+    asm volatile("s_nop 15\n\ts_nop 7" : "+a"(o[0]), "+a"(o[1]), "+a"(o[2]), "+a"(o[3]));
 }
 // Makes the compiler hold `o` in AccVGPRs at this point (placed after every
 // plain C++ write to the accumulators so that the value carried around the key
 // loop never changes register file) and spaces those writes from the next MFMA.
-__device__ __forceinline__ void pin_acc(f32x16 (&o)[kDB][2]) {
-    asm volatile("s_nop 1"
-                 : "+a"(o[0][0]), "+a"(o[0][1]), "+a"(o[1][0]), "+a"(o[1][1]), "+a"(o[2][0]), "+a"(o[2][1]),
-                   "+a"(o[3][0]), "+a"(o[3][1]));
+__device__ __forceinline__ void pin_acc(f32x16 (&o)[kDB]) {
+    asm volatile("s_nop 1" : "+a"(o[0]), "+a"(o[1]), "+a"(o[2]), "+a"(o[3]));
 }
 // Materialises a freshly packed P^T fragment here (the compiler would otherwise
 // be free to sink the conversion down to the MFMA that reads it).
@@ -117,179 +119,145 @@ __device__ __forceinline__ bf16x8 load_v_frag(const LaneAddr &la, uint32_t boff,
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
-// S^T (32 keys x 64 queries) = K_half Q^T
-__device__ __forceinline__ void qk_half(const LaneAddr &la, uint32_t kboff, const bf16x8 (&qf)[2][kKS], f32x16 (&s)[2]) {
+// S^T (32 keys x 32 queries) = K_half Q^T
+__device__ __forceinline__ void qk_half(const LaneAddr &la, uint32_t kboff, const bf16x8 (&qf)[kKS], f32x16 &s) {
 #pragma unroll
     for (int ks = 0; ks < kKS; ++ks) {
         const bf16x8 a = load_k_frag(la, kboff, ks);
-        if (ks == 0) {
-            mfma_s_first(s[0], a, qf[0][ks]);
-            mfma_s_first(s[1], a, qf[1][ks]);
-        } else {
-            mfma_s(s[0], a, qf[0][ks]);
-            mfma_s(s[1], a, qf[1][ks]);
-        }
+        if (ks == 0)
+            mfma_s_first(s, a, qf[ks]);
+        else
+            mfma_s(s, a, qf[ks]);
     }
 }
 
-// O^T (128 x 64 queries) += V_half^T P^T
-__device__ __forceinline__ void pv_half(const LaneAddr &la, uint32_t vboff, const bf16x8 (&pf)[2][2], f32x16 (&o)[kDB][2]) {
+// O^T (128 x 32 queries) += V_half^T P^T
+__device__ __forceinline__ void pv_half(const LaneAddr &la, uint32_t vboff, const bf16x8 (&pf)[2], f32x16 (&o)[kDB]) {
 #pragma unroll
     for (int st = 0; st < 2; ++st) {
 #pragma unroll
         for (int db = 0; db < kDB; ++db) {
             const bf16x8 a = load_v_frag(la, vboff, st, db);
-            mfma_acc(o[db][0], a, pf[0][st]);
-            mfma_acc(o[db][1], a, pf[1][st]);
+            mfma_acc(o[db], a, pf[st]);
         }
     }
 }
 
 struct RowState {
-    float mc[2];  // reference maximum per query column, in exp2 units (m * scale * log2 e)
-    float l[2];   // sum of exp2(s * c2 - mc)
+    float mc;  // softmax reference of this lane's query column, in exp2 units (m * scale * log2 e)
+    float l;   // sum of exp2(s * c2 - mc)
 };
 
-// Reference-maximum update for one query block given the block maximum mx
-// (raw score units, already reduced over the wave halves).
+// Max-based softmax of one half tile (edge tiles, first tile, and the rare
+// half whose row sums outgrow the reference): optional mask, reference update
+// with slack, exponentials, row sum, bf16 P^T fragments.  alpha is the factor
+// the O accumulator must be multiplied with (1 when the reference stays).
 template <bool kMask>
-__device__ __forceinline__ void update_reference(float mx, float c2, float &mc, float &mc_use, float &alpha) {
-    const float mc_old = mc;
-    const float m_new = fmaxf(mc_old, mx * c2);
-    const bool move = m_new > mc_old + kRefSlack;  // -inf never moves to -inf
-    mc = move ? m_new : mc_old;
-    mc_use = (kMask && mc == -INFINITY) ? 0.f : mc;
-    alpha = move ? __builtin_amdgcn_exp2f(mc_old - mc_use) : 1.f;
-}
-
-// Mask (optional), reference-maximum update, exponentials, row sums and the
-// bf16 P^T fragments of one half tile.  alpha[qb] is the factor the O
-// accumulator of query block qb must be multiplied with (1 when unchanged).
-template <bool kMask>
-__device__ __forceinline__ void softmax_half(f32x16 (&s)[2], int k0h, int p0, int W, int S, int l32, int hf, float c2,
-                                             RowState &st, bf16x8 (&pf)[2][2], float (&alpha)[2]) {
+__device__ __forceinline__ void softmax_half(f32x16 &s, int k0h, int qpos, int W, int S, int hf, float c2, RowState &st,
+                                             bf16x8 (&pf)[2], float &alpha) {
     settle_s(s);
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        if (kMask) {
-            const int qpos = p0 + 32 * qb + l32;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int key = k0h + 8 * (e / 4) + 4 * hf + (e % 4);
-                const bool vis = (key <= qpos) && ((key > qpos - W) || (key < S));
-                s[qb][e] = vis ? s[qb][e] : -INFINITY;
-            }
-        }
-        float mx = s[qb][0];
-#pragma unroll
-        for (int e = 1; e < 16; ++e) mx = fmaxf(mx, s[qb][e]);
-        mx = half_swap_max(mx);
-        float mc_use;
-        update_reference<kMask>(mx, c2, st.mc[qb], mc_use, alpha[qb]);
-        float rs = 0.f;
+    if (kMask) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            const float pe = __builtin_amdgcn_exp2f(fmaf(s[qb][e], c2, -mc_use));
-            rs += pe;
-            pf[qb][e / 8][e % 8] = (__bf16)pe;
+            const int key = k0h + 8 * (e / 4) + 4 * hf + (e % 4);
+            const bool vis = (key <= qpos) && ((key > qpos - W) || (key < S));
+            s[e] = vis ? s[e] : -INFINITY;
         }
-        rs = half_swap_sum(rs);
-        st.l[qb] = st.l[qb] * alpha[qb] + rs;
     }
+    float mx = s[0];
+#pragma unroll
+    for (int e = 1; e < 16; ++e) mx = fmaxf(mx, s[e]);
+    mx = half_swap_max(mx);
+    const float mc_old = st.mc;
+    const float m_new = fmaxf(mc_old, mx * c2);
+    const bool move = m_new > mc_old + kRefSlack;  // -inf never moves to -inf
+    st.mc = move ? m_new : mc_old;
+    const float mc_use = (kMask && st.mc == -INFINITY) ? 0.f : st.mc;
+    alpha = move ? __builtin_amdgcn_exp2f(mc_old - mc_use) : 1.f;
+    float rs = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const float pe = __builtin_amdgcn_exp2f(fmaf(s[e], c2, -mc_use));
+        rs += pe;
+        pf[e / 8][e % 8] = (__bf16)pe;
+    }
+    rs = half_swap_sum(rs);
+    st.l = st.l * alpha + rs;
     // keep the packing here and two wait states away from the MFMAs that read it
-    asm volatile("s_nop 1" : "+v"(pf[0][0]), "+v"(pf[0][1]), "+v"(pf[1][0]), "+v"(pf[1][1]));
+    asm volatile("s_nop 1" : "+v"(pf[0]), "+v"(pf[1]));
 }
 
-__device__ __forceinline__ void rescale(f32x16 (&o)[kDB][2], const float (&alpha)[2]) {
-    if (__any((alpha[0] != 1.f) || (alpha[1] != 1.f))) {
+__device__ __forceinline__ void rescale(f32x16 (&o)[kDB], float alpha) {
+    if (__any(alpha != 1.f)) {
         settle_acc(o);
 #pragma unroll
         for (int db = 0; db < kDB; ++db)
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) o[db][qb][e] *= alpha[qb];
+            for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
         pin_acc(o);
     }
 }
 
-// ---- steady-state step, scheduled by hand ----------------------------------------
-// A sub-step issues 32 MFMAs: S^T(n+1) = K Q^T (16) and O^T += V^T P^T(n-1) (16),
-// and in their shadow the vector work of the softmax of half n, cut into 32
-// chunks.  Scheduling fences pin the order "MFMA, chunk, MFMA, chunk, ..." so
-// that the matrix pipe is re-fed as soon as it drains while the wave keeps
-// issuing vector instructions in between.  LDS fragment reads are issued
-// kPrefetch MFMA pairs ahead of their use, across the boundary between the two
-// sub-steps of a step as well.
+// ---- steady-state sub-step, scheduled by hand -------------------------------------
+// A sub-step issues 16 MFMAs: S^T(n+1) = K Q^T (8) and O^T += V^T P^T(n-1) (8),
+// and in their shadow the vector work of the softmax of half n, cut into 16
+// chunks.  Scheduling fences pin the order "MFMA, chunk, MFMA, chunk, ...".
+// LDS fragment reads are issued kPrefetch MFMAs ahead of their use, across the
+// boundary between consecutive sub-steps of a step as well.
 //
-// In the steady state the softmax does not look for the row maximum at all:
-// it keeps the reference it has (set by the first half the wave processed) and
-// only watches the row sums.  exp2(s*c2 - mc) cannot overflow fp32 or bf16
-// unless a score exceeds the reference by more than 2^7 in the exp2 domain; a
-// row sum at or above kSumLimit sends the half through the max-based routine
-// again (which moves the reference and rescales), everything else is the plain
-// "subtract, exponentiate, add, pack" at 4.5 instructions per score.
-constexpr float kSumLimit = 1.0995116e12f;  // 2^40
-
+// The steady-state softmax does not look for the row maximum: it keeps the
+// reference it has and only watches the row sum.  exp2(s*c2 - mc) cannot
+// overflow fp32 or bf16 unless a score exceeds the reference by more than 2^7
+// in the exp2 domain; a row sum at or above kSumLimit sends the half through
+// softmax_half again, everything else is "subtract, exponentiate, add, pack".
 struct SoftmaxScratch {
-    float pe[32];
-    float sum[2][2];
-    float l_new[2];
+    float pe[16];
+    float sum[2];
+    float l_new;
     bool over;
 };
 
-// element index handled up to (exclusive) chunk c: 32 scores over the first 29 chunks
-__device__ __forceinline__ constexpr int chunk_first_elem(int c) { return c >= 29 ? 32 : (c * 32) / 29; }
+// first score element handled by chunk c: 16 scores over chunks 0..13
+__device__ __forceinline__ constexpr int chunk_first_elem(int c) { return c >= 14 ? 16 : (c * 16) / 14; }
 
-__device__ __forceinline__ void softmax_chunk(int c, const f32x16 (&s)[2], float c2, const RowState &st,
-                                              SoftmaxScratch &w, bf16x8 (&pf)[2][2]) {
-    // exponentials of this chunk's scores
+__device__ __forceinline__ void softmax_chunk(int c, const f32x16 &s, float c2, const RowState &st, SoftmaxScratch &w,
+                                              bf16x8 (&pf)[2]) {
 #pragma unroll
-    for (int g = chunk_first_elem(c); g < chunk_first_elem(c + 1); ++g)
-        w.pe[g] = __builtin_amdgcn_exp2f(fmaf(s[g / 16][g % 16], c2, -st.mc[g / 16]));
+    for (int e = chunk_first_elem(c); e < chunk_first_elem(c + 1); ++e)
+        w.pe[e] = __builtin_amdgcn_exp2f(fmaf(s[e], c2, -st.mc));
     // sums and packing trail one chunk behind, so that no instruction waits on
     // a transcendental issued just before it
-    if (c >= 1 && c <= 29) {
+    if (c >= 1 && c <= 14) {
 #pragma unroll
-        for (int g = chunk_first_elem(c - 1); g < chunk_first_elem(c); ++g) {
-            const int qb = g / 16, e = g % 16;
+        for (int e = chunk_first_elem(c - 1); e < chunk_first_elem(c); ++e) {
             if (e < 2)
-                w.sum[qb][e] = w.pe[g];
+                w.sum[e] = w.pe[e];
             else
-                w.sum[qb][e & 1] += w.pe[g];
+                w.sum[e & 1] += w.pe[e];
             if (e & 1) {  // the pair (e-1, e) is complete: pack it
-                pf[qb][e / 8][(e - 1) % 8] = (__bf16)w.pe[g - 1];
-                pf[qb][e / 8][e % 8] = (__bf16)w.pe[g];
-                if (e % 8 == 7) pin_p(pf[qb][e / 8]);
+                pf[e / 8][(e - 1) % 8] = (__bf16)w.pe[e - 1];
+                pf[e / 8][e % 8] = (__bf16)w.pe[e];
+                if (e % 8 == 7) pin_p(pf[e / 8]);
             }
         }
     }
-    if (c == 30) {
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) w.sum[qb][0] = half_swap_sum(w.sum[qb][0] + w.sum[qb][1]);
-    }
-    if (c == 31) {
-        w.over = (w.sum[0][0] >= kSumLimit) || (w.sum[1][0] >= kSumLimit);
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) w.l_new[qb] = st.l[qb] + w.sum[qb][0];
+    if (c == 15) {
+        const float rs = half_swap_sum(w.sum[0] + w.sum[1]);
+        w.over = rs >= kSumLimit;
+        w.l_new = st.l + rs;
     }
 }
 
-// One sub-step.  kboff / vboff: uniform byte offsets of the K half to multiply
-// and the V half to accumulate.  fpre: the first kPrefetch K fragments, already
-// requested by the caller; nkboff: K half of the following sub-step, whose
-// first kPrefetch fragments are requested here and returned in fpre.
-// Returns true when some row sum in the wave reached kSumLimit; st.l is then
-// left untouched and the caller redoes the softmax of this half.
-#ifndef SWAA_PREFETCH
-#define SWAA_PREFETCH 3
-#endif
-constexpr int kPrefetch = SWAA_PREFETCH;  // MFMA pairs between an LDS fragment read and its use
-
+// kboff / vboff: uniform byte offsets of the K half to multiply and the V half
+// to accumulate.  fpre: the first kPrefetch K fragments, already requested by
+// the caller; nkboff: K half of the following sub-step, whose first kPrefetch
+// fragments are requested here and returned in fpre.  Returns true when some
+// row sum in the wave reached kSumLimit; st.l is then left untouched and the
+// caller redoes the softmax of this half.
 __device__ __forceinline__ bool steady_substep(const LaneAddr &la, uint32_t kboff, uint32_t vboff, uint32_t nkboff,
-                                               bf16x8 (&fpre)[kPrefetch], const bf16x8 (&qf)[2][kKS],
-                                               f32x16 (&s_next)[2], const f32x16 (&s_cur)[2], bf16x8 (&p_cur)[2][2],
-                                               const bf16x8 (&p_prev)[2][2], f32x16 (&o)[kDB][2], RowState &st, float c2) {
+                                               bf16x8 (&fpre)[kPrefetch], const bf16x8 (&qf)[kKS], f32x16 &s_next,
+                                               const f32x16 &s_cur, bf16x8 (&p_cur)[2], const bf16x8 (&p_prev)[2],
+                                               f32x16 (&o)[kDB], RowState &st, float c2) {
     SoftmaxScratch w;
     // 0..7: K fragments by k-step; 8..15: V^T fragments by (16-key step, d block); 16..: next sub-step's K
     bf16x8 frag[16 + kPrefetch];
@@ -306,31 +274,24 @@ __device__ __forceinline__ bool steady_substep(const LaneAddr &la, uint32_t kbof
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         load_frag(i + kPrefetch);
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            if (i == 0) {
-                mfma_s_first(s_next[qb], frag[i], qf[qb][i]);
-            } else if (i < 8) {
-                mfma_s(s_next[qb], frag[i], qf[qb][i]);
-            } else {
-                mfma_acc(o[(i - 8) % kDB][qb], frag[i], p_prev[qb][(i - 8) / kDB]);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            softmax_chunk(2 * i + qb, s_cur, c2, st, w, p_cur);
-            __builtin_amdgcn_sched_barrier(0);
-        }
+        if (i == 0)
+            mfma_s_first(s_next, frag[i], qf[i]);
+        else if (i < 8)
+            mfma_s(s_next, frag[i], qf[i]);
+        else
+            mfma_acc(o[(i - 8) % kDB], frag[i], p_prev[(i - 8) / kDB]);
+        __builtin_amdgcn_sched_barrier(0);
+        softmax_chunk(i, s_cur, c2, st, w, p_cur);
+        __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
     for (int i = 0; i < kPrefetch; ++i) fpre[i] = frag[16 + i];
     const bool over = __any(w.over);
-    if (!over) {
-        st.l[0] = w.l_new[0];
-        st.l[1] = w.l_new[1];
-    }
+    if (!over) st.l = w.l_new;
     return over;
 }
 
-__global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const FwdParams p) {
+__global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const FwdParams p) {
     WorkItem wi;
     if (!decode_work(p, wi)) return;
     const int hpb = wi.hpb;
@@ -346,9 +307,10 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
     const int head = wi.kvh * p.G + wi.h0 + (wave % hpb);
     const int wg_p0 = wi.pt * pos_per_wg;
     const int wg_p1 = min(N, wg_p0 + pos_per_wg) - 1;
-    const int p0 = wg_p0 + (wave / hpb) * kWaveRows;
+    const int p0 = wg_p0 + (wave / hpb) * kPRows;  // first position of this wave
     const bool wave_active = p0 < N;
-    const int plast = min(p0 + kWaveRows, N) - 1;
+    const int plast = min(p0 + kPRows, N) - 1;
+    const int qpos = p0 + l32;  // this lane's query column
 
     // visited KV tiles: sink tiles 0 .. n_sink_tiles-1, then band tiles t_band_lo .. t_hi
     const int band_lo = max(0, wg_p0 - W + 1);
@@ -364,34 +326,32 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
     const size_t q_base = ((size_t)wi.b * p.Hq + head) * (size_t)N * kD;
 
     // ---- HBM -> LDS tile copies -------------------------------------------------
-    // One wave instruction moves 64 x 16 bytes = 4 rows of the tile; the LDS
-    // side is linear in the lane id, the swizzle is applied on the global side:
-    // LDS chunk (row, c') receives global chunk c' ^ f(row) of that row, with
-    // f(row) = ((row & 7) << 1) | ((row >> 3) & 1) for K (16 consecutive rows
-    // read the same logical chunk) and (row & 3) << 2 for V (4 consecutive rows
-    // read the same 64 bytes).
+    // One wave instruction moves 64 x 16 bytes = 4 rows of the tile, a wave moves
+    // 8 rows of K and of V per tile; the LDS side is linear in the lane id, the
+    // swizzle is applied on the global side: LDS chunk (row, c') receives global
+    // chunk c' ^ f(row) of that row, with f(row) = ((row & 7) << 1) | ((row >> 3) & 1)
+    // for K (16 consecutive rows read the same logical chunk) and (row & 3) << 2
+    // for V (4 consecutive rows read the same 64 bytes).
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int lrow = lane >> 4;  // row within the 4-row group
     const int lchk = lane & 15;  // LDS chunk within the row
-    // byte offset of this lane's 16 bytes inside a tile, instruction 0; K adds an
-    // XOR per instruction because its swizzle uses row bits 2 and 3
-    const uint32_t voff_k = (uint32_t)((16 * wave + lrow) * 256 + ((lchk ^ (lrow << 1)) << 4));
-    const uint32_t voff_v = (uint32_t)((16 * wave + lrow) * 256 + ((lchk ^ (lrow << 2)) << 4));
+    // byte offset of this lane's 16 bytes inside a tile, first instruction; row = 8*wave + 4*i + lrow
+    const uint32_t voff_k = (uint32_t)((8 * wave + lrow) * 256 + ((lchk ^ (lrow << 1) ^ (wave & 1)) << 4));
+    const uint32_t voff_v = (uint32_t)((8 * wave + lrow) * 256 + ((lchk ^ (lrow << 2)) << 4));
     auto issue_tile = [&](int j, int buf, const __bf16 *src, int ring, bool is_k) {
         if (j >= J) return;
         const int k0 = tile_of(j) * kBk;
         const char *base = reinterpret_cast<const char *>(src) + (size_t)k0 * (kD * 2);  // uniform
         const bool tail = k0 + kBk > N;  // rows past the end are masked later; keep the reads in bounds
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            // K: f(row) = ((4*(i&1) + lrow) << 1) | (i >> 1)  =>  chunk = lchk ^ (lrow<<1) ^ {0, 8, 1, 9}[i]
-            const uint32_t sw = is_k ? (uint32_t)((((i & 1) << 3) | (i >> 1)) << 4) : 0u;
-            uint32_t off = ((is_k ? voff_k : voff_v) ^ sw) + (uint32_t)(i * 1024);
+        for (int i = 0; i < 2; ++i) {
+            // K: row & 7 = 4*i + lrow, so the second instruction flips chunk bit 3
+            uint32_t off = ((is_k ? voff_k : voff_v) ^ (is_k ? (uint32_t)(i << 7) : 0u)) + (uint32_t)(i * 1024);
             if (tail) {
-                const int row = 16 * wave + 4 * i + lrow;
+                const int row = 8 * wave + 4 * i + lrow;
                 off -= (uint32_t)(max(k0 + row - (N - 1), 0) * (kD * 2));
             }
-            const uint32_t l = (uint32_t)(ring + buf * kTileBytes + (4 * wave_u + i) * 1024);
+            const uint32_t l = (uint32_t)(ring + buf * kTileBytes + (2 * wave_u + i) * 1024);
             // LDS address = M0 + 16 * lane; global address = base + off.  Issued as
             // assembly on purpose: the compiler would otherwise make every later
             // LDS read wait for it.
@@ -414,30 +374,25 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
     }
 
     // ---- Q fragments (B operand of S^T = K Q^T), parked in AccVGPRs -------------------
-    bf16x8 qf[2][kKS];
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        const int row = min(p0 + 32 * qb + l32, N - 1);
+    bf16x8 qf[kKS];
+    {
+        const int row = min(qpos, N - 1);
         const __bf16 *src = p.q + q_base + (size_t)row * kD + 8 * hf;
 #pragma unroll
-        for (int ks = 0; ks < kKS; ++ks) qf[qb][ks] = *reinterpret_cast<const bf16x8 *>(src + 16 * ks);
+        for (int ks = 0; ks < kKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(src + 16 * ks);
+#pragma unroll
+        for (int ks = 0; ks < kKS; ++ks) asm volatile("" : "+a"(qf[ks]));
     }
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-        for (int ks = 0; ks < kKS; ++ks) asm volatile("" : "+a"(qf[qb][ks]));
 
-    f32x16 oacc[kDB][2];
+    f32x16 oacc[kDB];
 #pragma unroll
     for (int db = 0; db < kDB; ++db)
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) oacc[db][qb][e] = 0.f;
+        for (int e = 0; e < 16; ++e) oacc[db][e] = 0.f;
     pin_acc(oacc);
     RowState rs;
-    rs.mc[0] = rs.mc[1] = -INFINITY;
-    rs.l[0] = rs.l[1] = 0.f;
+    rs.mc = -INFINITY;
+    rs.l = 0.f;
 
     // per-lane LDS read offsets inside a half tile (swizzle folded in)
     LaneAddr la;
@@ -456,31 +411,31 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
 
     const float c2 = p.scale_log2;
 
-    // activity of a 32-key half for this wave's 64 positions
+    // activity of a 32-key half for this wave's 32 positions
     auto half_active = [&](int k0h) {
         const bool in_future = k0h > plast;
         const bool before_band = (k0h + 31 < p0 - W + 1) && (k0h >= S);
         return wave_active && !in_future && !before_band;
     };
     auto half_unmasked = [&](int k0h) {
-        return (k0h + 31 <= p0) && ((k0h > p0 + kWaveRows - 1 - W) || (k0h + 31 < S));
+        return (k0h + 31 <= p0) && ((k0h > p0 + kPRows - 1 - W) || (k0h + 31 < S));
     };
 
-    f32x16 s_a[2], s_b[2];        // scores of half 0 / half 1 of a tile
-    bf16x8 p_a[2][2], p_b[2][2];  // their P^T fragments
-    float alpha[2];
+    f32x16 s_a, s_b;        // scores of half 0 / half 1 of a tile
+    bf16x8 p_a[2], p_b[2];  // their P^T fragments
+    float alpha = 1.f;
 
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's copies and Q loads have landed
     __syncthreads();
 
     // Tiles on which this wave runs the hand-scheduled steady step: both halves
-    // fully visible to all 64 rows (inside every row's window and at or below
+    // fully visible to all 32 rows (inside every row's window and at or below
     // the first row's diagonal), the previous tile's second half and the next
     // tile's first half active too.  In tile numbers that is the band tiles t
-    // with 64 t > p0 + 63 - W, t > t_band_lo and 64 t + 63 <= p0.
-    const int w_lo = p0 + kWaveRows - 1 - W;
+    // with 64 t > p0 + 31 - W, t > t_band_lo and 64 t + 63 <= p0.
+    const int w_lo = p0 + kPRows - 1 - W;
     const int t_s_lo = max(t_band_lo + 1, w_lo >= 0 ? w_lo / kBk + 1 : 0);
-    const int t_s_hi = p0 / kBk - 1;
+    const int t_s_hi = (p0 + 1) / kBk - 1;
     const int js_lo = wave_active ? t_s_lo - t_band_lo + n_sink_tiles : J;
     const int js_hi = t_s_hi - t_band_lo + n_sink_tiles;
 
@@ -503,14 +458,13 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
 #pragma unroll
             for (int i = 0; i < kPrefetch; ++i) fpre[i] = load_k_frag(la, kb_cur1, i);
             // a row that has seen no key yet (fully masked so far) takes 0 as its reference
-            rs.mc[0] = (rs.mc[0] == -INFINITY) ? 0.f : rs.mc[0];
-            rs.mc[1] = (rs.mc[1] == -INFINITY) ? 0.f : rs.mc[1];
+            rs.mc = (rs.mc == -INFINITY) ? 0.f : rs.mc;
             if (steady_substep(la, kb_cur1, vb_prev1, kb_next0, fpre, qf, s_b, s_a, p_a, p_b, oacc, rs, c2)) {
-                softmax_half<false>(s_a, 0, p0, W, S, l32, hf, c2, rs, p_a, alpha);
+                softmax_half<false>(s_a, 0, qpos, W, S, hf, c2, rs, p_a, alpha);
                 rescale(oacc, alpha);
             }
             if (steady_substep(la, kb_next0, vb_cur0, kb_next1, fpre, qf, s_a, s_b, p_b, p_a, oacc, rs, c2)) {
-                softmax_half<false>(s_b, 0, p0, W, S, l32, hf, c2, rs, p_b, alpha);
+                softmax_half<false>(s_b, 0, qpos, W, S, hf, c2, rs, p_b, alpha);
                 rescale(oacc, alpha);
             }
         } else {
@@ -525,9 +479,9 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
             if (act1) qk_half(la, kb_cur1, qf, s_b);
             if (act0) {
                 if (unm0)
-                    softmax_half<false>(s_a, k0_cur, p0, W, S, l32, hf, c2, rs, p_a, alpha);
+                    softmax_half<false>(s_a, k0_cur, qpos, W, S, hf, c2, rs, p_a, alpha);
                 else
-                    softmax_half<true>(s_a, k0_cur, p0, W, S, l32, hf, c2, rs, p_a, alpha);
+                    softmax_half<true>(s_a, k0_cur, qpos, W, S, hf, c2, rs, p_a, alpha);
             }
             if (act_prev1) pv_half(la, vb_prev1, p_b, oacc);
             if (act0) rescale(oacc, alpha);
@@ -535,9 +489,9 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
             if (act_next0) qk_half(la, kb_next0, qf, s_a);
             if (act1) {
                 if (unm1)
-                    softmax_half<false>(s_b, k0_cur + 32, p0, W, S, l32, hf, c2, rs, p_b, alpha);
+                    softmax_half<false>(s_b, k0_cur + 32, qpos, W, S, hf, c2, rs, p_b, alpha);
                 else
-                    softmax_half<true>(s_b, k0_cur + 32, p0, W, S, l32, hf, c2, rs, p_b, alpha);
+                    softmax_half<true>(s_b, k0_cur + 32, qpos, W, S, hf, c2, rs, p_b, alpha);
             }
             if (act0) pv_half(la, vb_cur0, p_a, oacc);
             if (act1) rescale(oacc, alpha);
@@ -545,11 +499,11 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
 
         // K(j+2), V(j+1) must have landed; K(j) and V(j-1) are free afterwards.
         // With four stages the copies of K(j+3), V(j+2), issued one step ago,
-        // may stay in flight: they are the newest 8 (or 4) of this wave's loads.
+        // may stay in flight: they are the newest 4 (or 2) of this wave's loads.
         if (kStages == 4 && j + 3 < J)
-            __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8)
-        else if (kStages == 4 && j + 2 < J)
             __builtin_amdgcn_s_waitcnt(0x0F74);  // vmcnt(4)
+        else if (kStages == 4 && j + 2 < J)
+            __builtin_amdgcn_s_waitcnt(0x0F72);  // vmcnt(2)
         else
             __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
         asm volatile("" ::: "memory");  // no LDS access may be moved across the barrier
@@ -559,7 +513,7 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
         issue_v(j + kStages - 1, r3p);
         r3 = r3n;
     }
-    // pipeline drain: P V of the last half (V(J-1) sits in buffer (J-1) % 3)
+    // pipeline drain: P V of the last half (V(J-1) sits in buffer (J-1) % kStages)
     if (half_active(tile_of(J - 1) * kBk + 32)) {
         const int r3l = (r3 == 0) ? kStages - 1 : r3 - 1;
         pv_half(la, (uint32_t)(r3l * kTileBytes + kHalfBytes), p_b, oacc);
@@ -568,11 +522,8 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
     // ---- epilogue: O / l -> bf16, lse = (mc + log2 l) * ln 2 -------------------------
     if (!wave_active) return;
     settle_acc(oacc);
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        const int qpos = p0 + 32 * qb + l32;
-        if (qpos >= N) continue;
-        const float inv_l = 1.f / rs.l[qb];
+    if (qpos < N) {
+        const float inv_l = 1.f / rs.l;
         __bf16 *orow = p.out + q_base + (size_t)qpos * kD;
 #pragma unroll
         for (int db = 0; db < kDB; ++db) {
@@ -580,13 +531,13 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_pipelined_kernel(const F
             for (int e4 = 0; e4 < 4; ++e4) {
                 bf16x4 o4;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[db][qb][4 * e4 + e] * inv_l);
+                for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[db][4 * e4 + e] * inv_l);
                 *reinterpret_cast<bf16x4 *>(orow + 32 * db + 8 * e4 + 4 * hf) = o4;
             }
         }
         if (hf == 0)
             p.lse[((size_t)wi.b * p.Hq + head) * (size_t)N + qpos] =
-                (rs.mc[qb] + __builtin_amdgcn_logf(rs.l[qb])) * 0.69314718055994530942f;
+                (rs.mc + __builtin_amdgcn_logf(rs.l)) * 0.69314718055994530942f;
     }
 }
 
@@ -606,7 +557,7 @@ hipError_t launch_fwd_pipelined_d128(const FwdParams &p, hipStream_t stream) {
         configured.fetch_or(bit, std::memory_order_release);
     }
     const unsigned grid = (unsigned)(p.chunk * kXcds);
-    hipLaunchKernelGGL(swaa_fwd_pipelined_kernel, dim3(grid), dim3(kThreads), kSmemBytes, stream, p);
+    hipLaunchKernelGGL(swaa_fwd_pipelined_kernel, dim3(grid), dim3(kPThreads), kSmemBytes, stream, p);
     return hipGetLastError();
 }
 

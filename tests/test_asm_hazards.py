@@ -71,5 +71,5 @@ def test_no_vector_write_within_two_instructions_of_an_mfma_that_reads_it(tmp_pa
             if is_valu_write(pop) and pops and (reg_set(pops[0]) & srcs):
                 problems.append((insts[i - back], insts[i]))
             wait_states += 1
-    assert n_mfma >= 100, "expected the MFMA-heavy kernel in the assembly"
+    assert n_mfma >= 60, "expected the MFMA-heavy kernel in the assembly"
     assert not problems, problems[:5]
