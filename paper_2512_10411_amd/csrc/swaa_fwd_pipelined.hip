@@ -15,11 +15,14 @@
 //   * K and V tiles (64 keys) travel HBM -> LDS with global_load_lds_dwordx4
 //     (no register staging) into two rings of kStages tiles each, XOR-swizzled
 //     in 16-byte chunks so that the MFMA operand reads are bank-conflict free.
-//     One barrier per tile.
+//     One barrier per tile.  Q rows arrive the same way and O rows leave through
+//     the same per-wave staging area, so that every HBM access of the kernel is a
+//     full 256-byte row per 16 lanes.
 //   * A wave works on half tiles of 32 keys in a three-stage pipeline: while
 //     the softmax of half n runs on the VALU, the matrix pipe computes
-//     S^T = K Q^T of half n+1 and O^T += V^T P^T of half n-1.  In the steady
-//     state the interleaving is fixed by hand with scheduling fences.
+//     S^T = K Q^T of half n+1 and O^T += V^T P^T of half n-1.  The interleaving
+//     is fixed by hand with scheduling fences.  Every visited half goes through
+//     the same pipeline; edge tiles use the variant that masks scores first.
 //   * The softmax reference: softmax is invariant to the value subtracted
 //     before the exponential, so the reference only has to keep exp2() inside
 //     the fp32/bf16 range.  It is set from the first half a wave processes and
@@ -44,15 +47,13 @@ constexpr int kDB = kD / 32;  // 32-wide blocks of the head dimension
 constexpr int kPWaves = 8;    // waves per workgroup
 constexpr int kPThreads = 64 * kPWaves;
 constexpr int kPRows = 32;  // query positions per wave
-#ifndef SWAA_STAGES
-#define SWAA_STAGES 3
-#endif
-constexpr int kStages = SWAA_STAGES;  // tiles per ring: 3 (copies one step ahead) or 4 (two steps ahead)
-static_assert(kStages == 3 || kStages == 4, "ring depth");
+constexpr int kStages = 3;                            // tiles per ring: copies run one step ahead
 constexpr int kTileBytes = kBk * kD * 2;              // 16 KiB
 constexpr int kHalfBytes = kTileBytes / 2;            // one 32-key half
 constexpr int kVRing = kStages * kTileBytes;          // V ring follows the K ring
-constexpr int kSmemBytes = 2 * kStages * kTileBytes;  // 96 or 128 KiB
+constexpr int kStage = 2 * kStages * kTileBytes;      // per-wave staging areas follow the rings
+constexpr int kStageBytes = kPRows * kD * 2;          // 8 KiB: a wave's 32 Q rows on the way in, O rows on the way out
+constexpr int kSmemBytes = kStage + kPWaves * kStageBytes;  // 96 + 64 = 160 KiB, all of a CU's LDS
 constexpr float kRefSlack = 8.f;            // log2 units a row maximum may exceed its reference (edge tiles)
 constexpr float kSumLimit = 1.0995116e12f;  // 2^40: row sum of one half that sends it back to the max-based path
 #ifndef SWAA_PREFETCH
@@ -144,8 +145,9 @@ __device__ __forceinline__ void pv_half(const LaneAddr &la, uint32_t vboff, cons
 }
 
 struct RowState {
-    float mc;  // softmax reference of this lane's query column, in exp2 units (m * scale * log2 e)
-    float l;   // sum of exp2(s * c2 - mc)
+    float mc;     // softmax reference of this lane's query column, in exp2 units (m * scale * log2 e)
+    float l;      // sum of exp2(s * c2 - mc)
+    float watch;  // largest row sum any half produced (pipelined path only)
 };
 
 // Max-based softmax of one half tile (edge tiles, first tile, and the rare
@@ -198,29 +200,37 @@ __device__ __forceinline__ void rescale(f32x16 (&o)[kDB], float alpha) {
     }
 }
 
-// ---- steady-state sub-step, scheduled by hand -------------------------------------
-// A sub-step issues 16 MFMAs: S^T(n+1) = K Q^T (8) and O^T += V^T P^T(n-1) (8),
-// and in their shadow the vector work of the softmax of half n, cut into 16
-// chunks.  Scheduling fences pin the order "MFMA, chunk, MFMA, chunk, ...".
-// LDS fragment reads are issued kPrefetch MFMAs ahead of their use, across the
-// boundary between consecutive sub-steps of a step as well.
+// ---- the pipelined sub-step, scheduled by hand -------------------------------------
+// A sub-step issues 16 MFMAs, alternating S^T(n+1) += K Q^T (8, one chain) and
+// O^T += V^T P^T(n-1) (8, four chains), and in their shadow the vector work of
+// the softmax of half n, cut into 16 chunks.  Scheduling fences pin the order
+// "MFMA, chunk, MFMA, chunk, ...".  LDS fragment reads are issued kPrefetch
+// MFMAs ahead of their use, across the boundary between the two sub-steps of a
+// step as well.
 //
-// The steady-state softmax does not look for the row maximum: it keeps the
-// reference it has and only watches the row sum.  exp2(s*c2 - mc) cannot
-// overflow fp32 or bf16 unless a score exceeds the reference by more than 2^7
-// in the exp2 domain; a row sum at or above kSumLimit sends the half through
-// softmax_half again, everything else is "subtract, exponentiate, add, pack".
+// The mask enters through the accumulator: on a half that is not fully visible
+// to the wave's 32 rows the K Q^T chain starts from a tile of 0 / -inf instead
+// of from zero, so invisible scores come out as -inf and their exponential is
+// an exact 0.  A half that lies wholly outside a wave's rows (before its band,
+// above its diagonal) therefore contributes nothing and needs no special case,
+// and the softmax chunks are the same for every half.
+//
+// The softmax does not look for the row maximum: it keeps the reference it has
+// (taken from the first half the wave sees) and only watches the row sum.
+// exp2(s*c2 - mc) cannot overflow fp32 or bf16 unless a score exceeds the
+// reference by more than 2^7 in the exp2 domain.  The largest row sum is kept on
+// the side; if it ever reaches kSumLimit the workgroup recomputes its rows with
+// the max-based routine after the loop.  Everything else is "subtract,
+// exponentiate, add, pack".
 struct SoftmaxScratch {
     float pe[16];
     float sum[2];
-    float l_new;
-    bool over;
 };
 
 // first score element handled by chunk c: 16 scores over chunks 0..13
 __device__ __forceinline__ constexpr int chunk_first_elem(int c) { return c >= 14 ? 16 : (c * 16) / 14; }
 
-__device__ __forceinline__ void softmax_chunk(int c, const f32x16 &s, float c2, const RowState &st, SoftmaxScratch &w,
+__device__ __forceinline__ void softmax_chunk(int c, const f32x16 &s, float c2, RowState &st, SoftmaxScratch &w,
                                               bf16x8 (&pf)[2]) {
 #pragma unroll
     for (int e = chunk_first_elem(c); e < chunk_first_elem(c + 1); ++e)
@@ -243,52 +253,71 @@ __device__ __forceinline__ void softmax_chunk(int c, const f32x16 &s, float c2, 
     }
     if (c == 15) {
         const float rs = half_swap_sum(w.sum[0] + w.sum[1]);
-        w.over = rs >= kSumLimit;
-        w.l_new = st.l + rs;
+        st.l += rs;
+        st.watch = fmaxf(st.watch, rs);
     }
 }
 
-// kboff / vboff: uniform byte offsets of the K half to multiply and the V half
-// to accumulate.  fpre: the first kPrefetch K fragments, already requested by
-// the caller; nkboff: K half of the following sub-step, whose first kPrefetch
-// fragments are requested here and returned in fpre.  Returns true when some
-// row sum in the wave reached kSumLimit; st.l is then left untouched and the
-// caller redoes the softmax of this half.
-__device__ __forceinline__ bool steady_substep(const LaneAddr &la, uint32_t kboff, uint32_t vboff, uint32_t nkboff,
-                                               bf16x8 (&fpre)[kPrefetch], const bf16x8 (&qf)[kKS], f32x16 &s_next,
-                                               const f32x16 &s_cur, bf16x8 (&p_cur)[2], const bf16x8 (&p_prev)[2],
-                                               f32x16 (&o)[kDB], RowState &st, float c2) {
+// First MFMA of a K Q^T chain.  masked: start from the 0 / -inf visibility tile
+// of the half whose first key is k0h; otherwise from zero.
+__device__ __forceinline__ void qk_chain_start(f32x16 &s, const bf16x8 kfrag, const bf16x8 q_acc, bool masked, int k0h,
+                                               int qpos, int W, int S, int hf) {
+    if (masked) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int key = k0h + 8 * (e / 4) + 4 * hf + (e % 4);
+            const bool vis = (key <= qpos) && ((key > qpos - W) || (key < S));
+            s[e] = vis ? 0.f : -INFINITY;
+        }
+        asm volatile("s_nop 1" : "+v"(s));  // two wait states between these writes and the MFMA
+        mfma_s(s, kfrag, q_acc);
+    } else {
+        mfma_s_first(s, kfrag, q_acc);
+    }
+}
+
+// Uniform byte offsets of the LDS halves one sub-step touches.
+struct HalfOffsets {
+    uint32_t k, v;    // K half to multiply, V half to accumulate
+    uint32_t nk, nv;  // the same for the following sub-step (fragment prefetch)
+};
+
+// Fragment slot i of a sub-step: even slots are K fragments (k-step i/2), odd
+// slots V^T fragments ((i-1)/2 = 4*st + db); slots 16.. belong to the next sub-step.
+__device__ __forceinline__ bf16x8 load_slot(const LaneAddr &la, const HalfOffsets &ho, int i) {
+    const bool next = i >= 16;
+    const int ii = next ? i - 16 : i;
+    if ((ii & 1) == 0) return load_k_frag(la, next ? ho.nk : ho.k, ii / 2);
+    return load_v_frag(la, next ? ho.nv : ho.v, (ii / 2) / kDB, (ii / 2) % kDB);
+}
+
+// fpre: the first kPrefetch fragments, already requested by the caller; on
+// return it holds those of the following sub-step.  k0h_next / mask_next: first
+// key of the half whose scores are computed here, and whether it needs the mask.
+__device__ __forceinline__ void pipelined_substep(const LaneAddr &la, const HalfOffsets &ho, bf16x8 (&fpre)[kPrefetch],
+                                                  const bf16x8 (&qf)[kKS], f32x16 &s_next, const f32x16 &s_cur,
+                                                  bf16x8 (&p_cur)[2], const bf16x8 (&p_prev)[2], f32x16 (&o)[kDB],
+                                                  RowState &st, float c2, bool mask_next, int k0h_next, int qpos, int W,
+                                                  int S, int hf) {
     SoftmaxScratch w;
-    // 0..7: K fragments by k-step; 8..15: V^T fragments by (16-key step, d block); 16..: next sub-step's K
     bf16x8 frag[16 + kPrefetch];
 #pragma unroll
     for (int i = 0; i < kPrefetch; ++i) frag[i] = fpre[i];
-    auto load_frag = [&](int i) {
-        if (i < 8)
-            frag[i] = load_k_frag(la, kboff, i);
-        else if (i < 16)
-            frag[i] = load_v_frag(la, vboff, (i - 8) / kDB, (i - 8) % kDB);
-        else
-            frag[i] = load_k_frag(la, nkboff, i - 16);
-    };
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        load_frag(i + kPrefetch);
+        frag[i + kPrefetch] = load_slot(la, ho, i + kPrefetch);
         if (i == 0)
-            mfma_s_first(s_next, frag[i], qf[i]);
-        else if (i < 8)
-            mfma_s(s_next, frag[i], qf[i]);
+            qk_chain_start(s_next, frag[i], qf[0], mask_next, k0h_next, qpos, W, S, hf);
+        else if ((i & 1) == 0)
+            mfma_s(s_next, frag[i], qf[i / 2]);
         else
-            mfma_acc(o[(i - 8) % kDB], frag[i], p_prev[(i - 8) / kDB]);
+            mfma_acc(o[(i / 2) % kDB], frag[i], p_prev[(i / 2) / kDB]);
         __builtin_amdgcn_sched_barrier(0);
         softmax_chunk(i, s_cur, c2, st, w, p_cur);
         __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
     for (int i = 0; i < kPrefetch; ++i) fpre[i] = frag[16 + i];
-    const bool over = __any(w.over);
-    if (!over) st.l = w.l_new;
-    return over;
 }
 
 __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const FwdParams p) {
@@ -308,9 +337,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     const int wg_p0 = wi.pt * pos_per_wg;
     const int wg_p1 = min(N, wg_p0 + pos_per_wg) - 1;
     const int p0 = wg_p0 + (wave / hpb) * kPRows;  // first position of this wave
-    const bool wave_active = p0 < N;
-    const int plast = min(p0 + kPRows, N) - 1;
-    const int qpos = p0 + l32;  // this lane's query column
+    const int qpos = p0 + l32;                     // this lane's query column
 
     // visited KV tiles: sink tiles 0 .. n_sink_tiles-1, then band tiles t_band_lo .. t_hi
     const int band_lo = max(0, wg_p0 - W + 1);
@@ -368,20 +395,26 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     issue_k(1, 1);
     issue_k(2, 2);
     issue_v(1, 1);
-    if (kStages == 4) {
-        issue_k(3, 3);
-        issue_v(2, 2);
+    // Step 0 multiplies an all-zero P^T with "the tile before the first": give that
+    // V buffer (the last one of the ring, not yet a copy target) defined contents.
+    {
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        for (int i = tid; i < kTileBytes / 16; i += kPThreads)
+            *(u32x4 __attribute__((address_space(3))) *)(uintptr_t)(kVRing + (kStages - 1) * kTileBytes + i * 16) = zero;
     }
 
-    // ---- Q fragments (B operand of S^T = K Q^T), parked in AccVGPRs -------------------
-    bf16x8 qf[kKS];
+    // ---- this wave's 32 Q rows: HBM -> its staging area, laid out like a K half tile ----
+    const uint32_t stage = (uint32_t)(kStage + wave_u * kStageBytes);
     {
-        const int row = min(qpos, N - 1);
-        const __bf16 *src = p.q + q_base + (size_t)row * kD + 8 * hf;
+        const char *qg = reinterpret_cast<const char *>(p.q + q_base);
 #pragma unroll
-        for (int ks = 0; ks < kKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(src + 16 * ks);
-#pragma unroll
-        for (int ks = 0; ks < kKS; ++ks) asm volatile("" : "+a"(qf[ks]));
+        for (int i = 0; i < 8; ++i) {
+            const int row = 4 * i + lrow;
+            const int f = ((4 * (i & 1) + lrow) << 1) | ((i >> 1) & 1);
+            const char *g = qg + (size_t)min(p0 + row, N - 1) * (kD * 2) + ((lchk ^ f) << 4);
+            const uint32_t l = stage + (uint32_t)(i * 1024);
+            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(l) : "memory");
+        }
     }
 
     f32x16 oacc[kDB];
@@ -390,9 +423,6 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
 #pragma unroll
         for (int e = 0; e < 16; ++e) oacc[db][e] = 0.f;
     pin_acc(oacc);
-    RowState rs;
-    rs.mc = -INFINITY;
-    rs.l = 0.f;
 
     // per-lane LDS read offsets inside a half tile (swizzle folded in)
     LaneAddr la;
@@ -411,36 +441,52 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
 
     const float c2 = p.scale_log2;
 
-    // activity of a 32-key half for this wave's 32 positions
-    auto half_active = [&](int k0h) {
-        const bool in_future = k0h > plast;
-        const bool before_band = (k0h + 31 < p0 - W + 1) && (k0h >= S);
-        return wave_active && !in_future && !before_band;
-    };
-    auto half_unmasked = [&](int k0h) {
-        return (k0h + 31 <= p0) && ((k0h > p0 + kPRows - 1 - W) || (k0h + 31 < S));
-    };
-
     f32x16 s_a, s_b;        // scores of half 0 / half 1 of a tile
     bf16x8 p_a[2], p_b[2];  // their P^T fragments
-    float alpha = 1.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        p_b[0][e] = (__bf16)0.f;
+        p_b[1][e] = (__bf16)0.f;
+    }
+    pin_p(p_b[0]);
+    pin_p(p_b[1]);
 
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's copies and Q loads have landed
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's copies have landed
     __syncthreads();
 
-    // Tiles on which this wave runs the hand-scheduled steady step: both halves
-    // fully visible to all 32 rows (inside every row's window and at or below
-    // the first row's diagonal), the previous tile's second half and the next
-    // tile's first half active too.  In tile numbers that is the band tiles t
-    // with 64 t > p0 + 31 - W, t > t_band_lo and 64 t + 63 <= p0.
-    const int w_lo = p0 + kPRows - 1 - W;
-    const int t_s_lo = max(t_band_lo + 1, w_lo >= 0 ? w_lo / kBk + 1 : 0);
-    const int t_s_hi = (p0 + 1) / kBk - 1;
-    const int js_lo = wave_active ? t_s_lo - t_band_lo + n_sink_tiles : J;
-    const int js_hi = t_s_hi - t_band_lo + n_sink_tiles;
+    // ---- Q fragments (B operand of S^T = K Q^T), parked in AccVGPRs -------------------
+    bf16x8 qf[kKS];
+#pragma unroll
+    for (int ks = 0; ks < kKS; ++ks) qf[ks] = load_k_frag(la, stage, ks);
+    // the idle cycles keep the copies two wait states away from the first MFMA that reads them
+    asm volatile("s_nop 1"
+                 : "+a"(qf[0]), "+a"(qf[1]), "+a"(qf[2]), "+a"(qf[3]), "+a"(qf[4]), "+a"(qf[5]), "+a"(qf[6]), "+a"(qf[7]));
 
-    // pipeline prologue: scores of the very first half
-    if (half_active(tile_of(0) * kBk)) qk_half(la, 0, qf, s_a);
+    // ---- pipeline prologue: scores of the very first half, and the softmax reference ----
+    // The reference is the largest visible score of that half (0 for a row that
+    // sees none of its keys); from here on it only moves if a row sum overflows.
+    RowState rs;
+    rs.l = 0.f;
+    rs.watch = 0.f;
+    {
+        const int k0 = tile_of(0) * kBk;
+        qk_chain_start(s_a, load_k_frag(la, 0, 0), qf[0], true, k0, qpos, W, S, hf);
+#pragma unroll
+        for (int ks = 1; ks < kKS; ++ks) mfma_s(s_a, load_k_frag(la, 0, ks), qf[ks]);
+        settle_s(s_a);
+        float mx = s_a[0];
+#pragma unroll
+        for (int e = 1; e < 16; ++e) mx = fmaxf(mx, s_a[e]);
+        mx = half_swap_max(mx);
+        rs.mc = (mx == -INFINITY) ? 0.f : mx * c2;
+    }
+
+    // A wave needs no mask on a 32-key half when all its keys are visible to all
+    // its 32 rows: at or below the first row's diagonal, and inside the last
+    // row's window or all sinks.
+    auto half_masked = [&](int k0h) {
+        return !((k0h + 31 <= p0) && ((k0h > p0 + kPRows - 1 - W) || (k0h + 31 < S)));
+    };
 
     int r3 = 0;  // j % kStages
     for (int j = 0; j < J; ++j) {
@@ -448,64 +494,25 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
         const int r3p = (r3 == 0) ? kStages - 1 : r3 - 1;  // (j - 1) % kStages
         const uint32_t kb_cur1 = (uint32_t)(r3 * kTileBytes + kHalfBytes);    // K(j), half 1
         const uint32_t kb_next0 = (uint32_t)(r3n * kTileBytes);               // K(j+1), half 0
-        const uint32_t kb_next1 = kb_next0 + kHalfBytes;                      // K(j+1), half 1
         const uint32_t vb_prev1 = (uint32_t)(r3p * kTileBytes + kHalfBytes);  // V(j-1), half 1
         const uint32_t vb_cur0 = (uint32_t)(r3 * kTileBytes);                 // V(j), half 0
+        const int k0 = tile_of(j) * kBk;
+        const int k0n = (j + 1 < J) ? tile_of(j + 1) * kBk : k0 + kBk;  // past the end: scores never used
 
-        if (j >= js_lo && j <= js_hi) {
-            // steady state: three independent streams per sub-step
-            bf16x8 fpre[kPrefetch];
+        // softmax of (j, half 0) | scores of (j, half 1) | P V of (j-1, half 1)
+        HalfOffsets h1 = {kb_cur1, vb_prev1, kb_next0, vb_cur0};
+        bf16x8 fpre[kPrefetch];
 #pragma unroll
-            for (int i = 0; i < kPrefetch; ++i) fpre[i] = load_k_frag(la, kb_cur1, i);
-            // a row that has seen no key yet (fully masked so far) takes 0 as its reference
-            rs.mc = (rs.mc == -INFINITY) ? 0.f : rs.mc;
-            if (steady_substep(la, kb_cur1, vb_prev1, kb_next0, fpre, qf, s_b, s_a, p_a, p_b, oacc, rs, c2)) {
-                softmax_half<false>(s_a, 0, qpos, W, S, hf, c2, rs, p_a, alpha);
-                rescale(oacc, alpha);
-            }
-            if (steady_substep(la, kb_next0, vb_cur0, kb_next1, fpre, qf, s_a, s_b, p_b, p_a, oacc, rs, c2)) {
-                softmax_half<false>(s_b, 0, qpos, W, S, hf, c2, rs, p_b, alpha);
-                rescale(oacc, alpha);
-            }
-        } else {
-            // edges of the band, the sink tile, first and last tile: same
-            // stages, each guarded; the element mask is applied where needed
-            const int k0_cur = tile_of(j) * kBk;
-            const bool act_prev1 = j > 0 && half_active(tile_of(j - 1) * kBk + 32);
-            const bool act0 = half_active(k0_cur), act1 = half_active(k0_cur + 32);
-            const bool act_next0 = (j + 1) < J && half_active(tile_of(j + 1) * kBk);
-            const bool unm0 = half_unmasked(k0_cur), unm1 = half_unmasked(k0_cur + 32);
+        for (int i = 0; i < kPrefetch; ++i) fpre[i] = load_slot(la, h1, i);
+        pipelined_substep(la, h1, fpre, qf, s_b, s_a, p_a, p_b, oacc, rs, c2, half_masked(k0 + 32), k0 + 32, qpos, W, S,
+                          hf);
+        // softmax of (j, half 1) | scores of (j+1, half 0) | P V of (j, half 0);
+        // the sub-step after it belongs to the next step, which requests its own fragments
+        HalfOffsets h2 = {kb_next0, vb_cur0, kb_next0, vb_cur0};
+        pipelined_substep(la, h2, fpre, qf, s_a, s_b, p_b, p_a, oacc, rs, c2, half_masked(k0n), k0n, qpos, W, S, hf);
 
-            if (act1) qk_half(la, kb_cur1, qf, s_b);
-            if (act0) {
-                if (unm0)
-                    softmax_half<false>(s_a, k0_cur, qpos, W, S, hf, c2, rs, p_a, alpha);
-                else
-                    softmax_half<true>(s_a, k0_cur, qpos, W, S, hf, c2, rs, p_a, alpha);
-            }
-            if (act_prev1) pv_half(la, vb_prev1, p_b, oacc);
-            if (act0) rescale(oacc, alpha);
-
-            if (act_next0) qk_half(la, kb_next0, qf, s_a);
-            if (act1) {
-                if (unm1)
-                    softmax_half<false>(s_b, k0_cur + 32, qpos, W, S, hf, c2, rs, p_b, alpha);
-                else
-                    softmax_half<true>(s_b, k0_cur + 32, qpos, W, S, hf, c2, rs, p_b, alpha);
-            }
-            if (act0) pv_half(la, vb_cur0, p_a, oacc);
-            if (act1) rescale(oacc, alpha);
-        }
-
-        // K(j+2), V(j+1) must have landed; K(j) and V(j-1) are free afterwards.
-        // With four stages the copies of K(j+3), V(j+2), issued one step ago,
-        // may stay in flight: they are the newest 4 (or 2) of this wave's loads.
-        if (kStages == 4 && j + 3 < J)
-            __builtin_amdgcn_s_waitcnt(0x0F74);  // vmcnt(4)
-        else if (kStages == 4 && j + 2 < J)
-            __builtin_amdgcn_s_waitcnt(0x0F72);  // vmcnt(2)
-        else
-            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+        // K(j+2), V(j+1) must have landed; K(j) and V(j-1) are free afterwards
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
         asm volatile("" ::: "memory");  // no LDS access may be moved across the barrier
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
@@ -514,17 +521,58 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
         r3 = r3n;
     }
     // pipeline drain: P V of the last half (V(J-1) sits in buffer (J-1) % kStages)
-    if (half_active(tile_of(J - 1) * kBk + 32)) {
+    {
         const int r3l = (r3 == 0) ? kStages - 1 : r3 - 1;
         pv_half(la, (uint32_t)(r3l * kTileBytes + kHalfBytes), p_b, oacc);
     }
 
-    // ---- epilogue: O / l -> bf16, lse = (mc + log2 l) * ln 2 -------------------------
-    if (!wave_active) return;
+    // ---- scores outgrew the reference somewhere in this workgroup (inputs with
+    // score jumps of tens of nats): recompute its rows with the max-based routine,
+    // one tile at a time, no pipelining ------------------------------------------
+    // (workgroup-wide OR through eight flag words at the start of the K ring,
+    // which nobody reads any more after the loop's last barrier)
+    bool redo;
+    {
+        const int mine = __any(rs.watch >= kSumLimit) ? 1 : 0;
+        if (lane == 0) *(int __attribute__((address_space(3))) *)(uintptr_t)(wave * 4) = mine;
+        __syncthreads();
+        int any = 0;
+#pragma unroll
+        for (int w = 0; w < kPWaves; ++w) any |= *(const int __attribute__((address_space(3))) *)(uintptr_t)(w * 4);
+        redo = any != 0;
+    }
+    if (redo) {
+#pragma unroll
+        for (int db = 0; db < kDB; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[db][e] = 0.f;
+        pin_acc(oacc);
+        rs.mc = -INFINITY;
+        rs.l = 0.f;
+        for (int j = 0; j < J; ++j) {
+            __syncthreads();  // everyone is done reading the previous tile
+            issue_k(j, 0);
+            issue_v(j, 0);
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+#pragma unroll 1
+            for (int hh = 0; hh < 2; ++hh) {
+                float alpha;
+                qk_half(la, (uint32_t)(hh * kHalfBytes), qf, s_a);
+                softmax_half<true>(s_a, tile_of(j) * kBk + 32 * hh, qpos, W, S, hf, c2, rs, p_a, alpha);
+                rescale(oacc, alpha);
+                pv_half(la, (uint32_t)(hh * kHalfBytes), p_a, oacc);
+            }
+        }
+    }
+
+    // ---- epilogue: O / l -> bf16 through the wave's staging area, so that the stores
+    // to HBM are whole rows; lse = (mc + log2 l) * ln 2 ----------------------------------
     settle_acc(oacc);
-    if (qpos < N) {
-        const float inv_l = 1.f / rs.l;
-        __bf16 *orow = p.out + q_base + (size_t)qpos * kD;
+    {
+        const float inv_l = 1.f / rs.l;  // rows past the end: never stored
+        const int fr = ((l32 & 7) << 1) | ((l32 >> 3) & 1);
+        const uint32_t o_lane = stage + (uint32_t)(l32 * 256 + (fr << 4) + 8 * hf);
 #pragma unroll
         for (int db = 0; db < kDB; ++db) {
 #pragma unroll
@@ -532,10 +580,19 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
                 bf16x4 o4;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[db][4 * e4 + e] * inv_l);
-                *reinterpret_cast<bf16x4 *>(orow + 32 * db + 8 * e4 + 4 * hf) = o4;
+                // d = 32 db + 8 e4 + 4 hf + (0..3): 16-byte chunk 4 db + e4 of row l32, swizzled like K
+                *(bf16x4 __attribute__((address_space(3))) *)(uintptr_t)(o_lane ^ (uint32_t)((4 * db + e4) << 4)) = o4;
             }
         }
-        if (hf == 0)
+        __bf16 *og = p.out + q_base;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = 4 * i + lrow;
+            const int f = ((4 * (i & 1) + lrow) << 1) | ((i >> 1) & 1);
+            const u32x4 val = *(const u32x4 __attribute__((address_space(3))) *)(uintptr_t)(stage + i * 1024 + lane * 16);
+            if (p0 + row < N) *reinterpret_cast<u32x4 *>(og + (size_t)(p0 + row) * kD + ((lchk ^ f) << 3)) = val;
+        }
+        if (hf == 0 && qpos < N)
             p.lse[((size_t)wi.b * p.Hq + head) * (size_t)N + qpos] =
                 (rs.mc + __builtin_amdgcn_logf(rs.l)) * 0.69314718055994530942f;
     }

@@ -52,7 +52,15 @@ def test_no_vector_write_within_two_instructions_of_an_mfma_that_reads_it(tmp_pa
     flags = [f for f in build.HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
     cmd = [build.hipcc_path(), *flags, "--cuda-device-only", "-S", "-o", str(out), SRC]
     subprocess.run(cmd, check=True, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)
-    insts = [p for p in (parse(ln) for ln in open(out)) if p]
+    text = open(out).read()
+    # the pipelined kernel addresses LDS absolutely, so it must own all of it
+    sizes = re.findall(r"\.amdhsa_group_segment_fixed_size\s+(\d+)", text)
+    names = re.findall(r"\.amdhsa_kernel\s+(\S+)", text)
+    assert names and len(sizes) == len(names)
+    for name, size in zip(names, sizes):
+        if "pipelined" in name:
+            assert int(size) == 0, (name, size)
+    insts = [p for p in (parse(ln) for ln in text.splitlines()) if p]
     n_mfma = 0
     problems = []
     for i, (op, ops) in enumerate(insts):
