@@ -39,6 +39,10 @@ def parse():
                     help="target CPU time of the oracle sample")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch from a separate rocprofv3 --pmc run, if known")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also run one plain device-to-device copy of this many MiB after the warm-up: under "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE it is the kernel of known traffic that "
+                         "the attention kernel's counters are scaled by")
     return ap.parse_args()
 
 
@@ -116,6 +120,13 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.copy_probe_mib > 0:
+        src = torch.ones(args.copy_probe_mib << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)  # reads and writes copy_probe_mib MiB once
+        torch.cuda.synchronize()
+        del src, dst
 
     # K steps, wall clock bracketed by synchronisation on both sides.  One HIP event
     # pair on the launch stream brackets the same K launches: its elapsed time / K is
