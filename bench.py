@@ -26,6 +26,12 @@ sys.path.insert(0, ROOT)
 METRIC = "SWA+sink prefill attention effective TFLOP/s and % bf16 MFMA peak, 1 MI355X"
 BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 
+# HBM bytes per launch (read + written) of the attention kernel, measured with two
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by a copy kernel of known size;
+# the summaries are profiles/swaa_fwd_pipelined_<workload>.txt.  Used when
+# --traffic-bytes is not given; workloads not measured yet report null.
+MEASURED_TRAFFIC_BYTES = {"mid": 3.985e8, "batched": 1.048e9}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -168,7 +174,9 @@ def main():
                    "visible_pairs": pairs, "flops_per_step": flops,
                    "pct_bf16_mfma_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": args.traffic_bytes,
+                     "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
+                     "traffic": args.traffic_bytes if args.traffic_bytes is not None
+                     else MEASURED_TRAFFIC_BYTES.get(w.name),
                      "kernel": "swaa_fwd_pipelined_kernel" if w.D == 128 else "swaa_fwd_kernel<64>",
                      "kernel_avg_ms": kern_avg_ms},
     }
