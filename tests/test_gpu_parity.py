@@ -161,3 +161,30 @@ def test_workload_full_size_sampled_rows(names):
         ro, rl = swaa_attn_oracle(q, k, v, w.window, w.n_sink, w.scale, rows=rows)
         assert_parity(out, lse, ro, rl, rows=rows, tag=name)
         del out, lse
+
+
+def test_random_shapes_and_masks():
+    # seeded random (B, G, Hkv, N, W, S): shapes straddling tile and wave boundaries,
+    # windows from 1 key to beyond N, sink counts from 0 to beyond N
+    rng = np.random.Generator(np.random.Philox(46))
+    for case in range(24):
+        B = int(rng.integers(1, 3))
+        Hkv = int(rng.integers(1, 3))
+        G = int(rng.choice([1, 2, 3, 4, 5, 6, 8]))
+        N = int(rng.choice([31, 32, 33, 95, 96, 191, 256, 300, 449, 640, 777, 1025]))
+        W = int(rng.choice([1, 2, 31, 32, 33, 63, 64, 65, 100, 128, 250, N - 1 if N > 1 else 1, N, N + 7]))
+        S = int(rng.choice([0, 1, 3, 4, 31, 32, 33, 64, 65, 130, N, N + 3]))
+        D = int(rng.choice([64, 128, 128, 128]))
+        check(B, Hkv * G, Hkv, N, D, max(W, 1), S, seed=4600 + case)
+
+
+@pytest.mark.parametrize("S", [64, 128, 1000, 1024])
+def test_many_sink_tiles(S):
+    # keep-first values up to 1000 (the paper's largest): several sink tiles, the
+    # last one partial, a gap between sinks and band, and rows inside the sink range
+    check(1, 8, 2, 2500, 128, 200, S, seed=4700 + S)
+
+
+def test_batched_uneven_gqa_groups_at_scale():
+    # G = 7 = 4 + 2 + 1: all three workgroup shapes in one launch, several batch entries
+    check(3, 14, 2, 1111, 128, 300, 4, seed=4800)
