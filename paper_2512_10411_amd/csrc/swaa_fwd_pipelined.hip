@@ -35,6 +35,7 @@
 // This kernel declares no static LDS: its dynamic LDS starts at address 0 and
 // all LDS accesses below use plain byte addresses.
 #include <atomic>
+#include <type_traits>
 
 #include "swaa_common.h"
 
@@ -488,19 +489,22 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
         return !((k0h + 31 <= p0) && ((k0h > p0 + kPRows - 1 - W) || (k0h + 31 < S)));
     };
 
-    int r3 = 0;  // j % kStages
-    for (int j = 0; j < J; ++j) {
-        const int r3n = (r3 == kStages - 1) ? 0 : r3 + 1;  // (j + 1) % kStages
-        const int r3p = (r3 == 0) ? kStages - 1 : r3 - 1;  // (j - 1) % kStages
-        const uint32_t kb_cur1 = (uint32_t)(r3 * kTileBytes + kHalfBytes);    // K(j), half 1
-        const uint32_t kb_next0 = (uint32_t)(r3n * kTileBytes);               // K(j+1), half 0
-        const uint32_t vb_prev1 = (uint32_t)(r3p * kTileBytes + kHalfBytes);  // V(j-1), half 1
-        const uint32_t vb_cur0 = (uint32_t)(r3 * kTileBytes);                 // V(j), half 0
+    // One step = one visited tile.  The ring position R = j % 3 is a template
+    // argument, so every LDS offset below is a constant that folds into the
+    // instructions' offset fields (no address arithmetic in the loop); the loop
+    // walks the three instantiations in turn.
+    auto step = [&](auto ring_pos, int j) {
+        constexpr int R = decltype(ring_pos)::value;
+        constexpr int Rn = (R + 1) % kStages, Rp = (R + kStages - 1) % kStages;
+        constexpr uint32_t kb_cur1 = R * kTileBytes + kHalfBytes;    // K(j), half 1
+        constexpr uint32_t kb_next0 = Rn * kTileBytes;               // K(j+1), half 0
+        constexpr uint32_t vb_prev1 = Rp * kTileBytes + kHalfBytes;  // V(j-1), half 1
+        constexpr uint32_t vb_cur0 = R * kTileBytes;                 // V(j), half 0
         const int k0 = tile_of(j) * kBk;
         const int k0n = (j + 1 < J) ? tile_of(j + 1) * kBk : k0 + kBk;  // past the end: scores never used
 
         // softmax of (j, half 0) | scores of (j, half 1) | P V of (j-1, half 1)
-        HalfOffsets h1 = {kb_cur1, vb_prev1, kb_next0, vb_cur0};
+        const HalfOffsets h1 = {kb_cur1, vb_prev1, kb_next0, vb_cur0};
         bf16x8 fpre[kPrefetch];
 #pragma unroll
         for (int i = 0; i < kPrefetch; ++i) fpre[i] = load_slot(la, h1, i);
@@ -508,7 +512,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
                           hf);
         // softmax of (j, half 1) | scores of (j+1, half 0) | P V of (j, half 0);
         // the sub-step after it belongs to the next step, which requests its own fragments
-        HalfOffsets h2 = {kb_next0, vb_cur0, kb_next0, vb_cur0};
+        const HalfOffsets h2 = {kb_next0, vb_cur0, kb_next0, vb_cur0};
         pipelined_substep(la, h2, fpre, qf, s_a, s_b, p_b, p_a, oacc, rs, c2, half_masked(k0n), k0n, qpos, W, S, hf);
 
         // K(j+2), V(j+1) must have landed; K(j) and V(j-1) are free afterwards
@@ -516,15 +520,20 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
         asm volatile("" ::: "memory");  // no LDS access may be moved across the barrier
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        issue_k(j + kStages, r3);
-        issue_v(j + kStages - 1, r3p);
-        r3 = r3n;
+        issue_k(j + kStages, R);
+        issue_v(j + kStages - 1, Rp);
+    };
+    static_assert(kStages == 3, "the loop below walks three ring positions");
+    for (int j = 0;;) {
+        step(std::integral_constant<int, 0>{}, j);
+        if (++j >= J) break;
+        step(std::integral_constant<int, 1>{}, j);
+        if (++j >= J) break;
+        step(std::integral_constant<int, 2>{}, j);
+        if (++j >= J) break;
     }
     // pipeline drain: P V of the last half (V(J-1) sits in buffer (J-1) % kStages)
-    {
-        const int r3l = (r3 == 0) ? kStages - 1 : r3 - 1;
-        pv_half(la, (uint32_t)(r3l * kTileBytes + kHalfBytes), p_b, oacc);
-    }
+    pv_half(la, (uint32_t)(((J - 1) % kStages) * kTileBytes + kHalfBytes), p_b, oacc);
 
     // ---- scores outgrew the reference somewhere in this workgroup (inputs with
     // score jumps of tens of nats): recompute its rows with the max-based routine,
