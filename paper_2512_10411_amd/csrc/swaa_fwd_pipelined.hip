@@ -390,12 +390,6 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     auto issue_k = [&](int j, int buf) { issue_tile(j, buf, kg, 0, true); };
     auto issue_v = [&](int j, int buf) { issue_tile(j, buf, vg, kVRing, false); };
 
-    // in the order they are needed: step 0 reads K(0), K(1), V(0)
-    issue_k(0, 0);
-    issue_v(0, 0);
-    issue_k(1, 1);
-    issue_k(2, 2);
-    issue_v(1, 1);
     // Step 0 multiplies an all-zero P^T with "the tile before the first": give that
     // V buffer (the last one of the ring, not yet a copy target) defined contents.
     {
@@ -417,6 +411,14 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
             asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(l) : "memory");
         }
     }
+    // Tiles in the order they are needed.  A CU takes in about 64 bytes per cycle,
+    // so the pipeline prologue below starts as soon as Q and K(0) are there (ten
+    // copies per wave) and the other four tiles (eight copies) stream in behind it.
+    issue_k(0, 0);
+    issue_v(0, 0);
+    issue_k(1, 1);
+    issue_k(2, 2);
+    issue_v(1, 1);
 
     f32x16 oacc[kDB];
 #pragma unroll
@@ -452,8 +454,17 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     pin_p(p_b[0]);
     pin_p(p_b[1]);
 
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's copies have landed
-    __syncthreads();
+    // this wave's Q and K(0) copies must have landed; V(0), K(1), K(2), V(1) -- those
+    // of them that exist -- may still fly (two copies per tile)
+    if (J >= 3)
+        __builtin_amdgcn_s_waitcnt(0x0078);  // vmcnt(8) lgkmcnt(0)
+    else if (J == 2)
+        __builtin_amdgcn_s_waitcnt(0x0076);  // vmcnt(6) lgkmcnt(0)
+    else
+        __builtin_amdgcn_s_waitcnt(0x0072);  // vmcnt(2) lgkmcnt(0)
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
 
     // ---- Q fragments (B operand of S^T = K Q^T), parked in AccVGPRs -------------------
     bf16x8 qf[kKS];
@@ -488,6 +499,17 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     auto half_masked = [&](int k0h) {
         return !((k0h + 31 <= p0) && ((k0h > p0 + kPRows - 1 - W) || (k0h + 31 < S)));
     };
+
+    // step 0 reads V(0) and K(1): they must be there for every wave (K(2), V(1) may still fly)
+    if (J >= 3)
+        __builtin_amdgcn_s_waitcnt(0x0074);  // vmcnt(4) lgkmcnt(0)
+    else if (J == 2)
+        __builtin_amdgcn_s_waitcnt(0x0072);  // vmcnt(2) lgkmcnt(0)
+    else
+        __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
 
     // One step = one visited tile.  The ring position R = j % 3 is a template
     // argument, so every LDS offset below is a constant that folds into the
