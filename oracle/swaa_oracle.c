@@ -24,6 +24,11 @@
  * explicit visible set, exactly as written above.  Rows are independent, so
  * the only parallelism is an OpenMP loop over (b, h, row).
  *
+ * FA Decode (paper Sec. 3.1.1, Fig. 1a): the window applies to prompt tokens
+ * only; a generated token attends to every earlier token.  With P = n_prompt,
+ * rows i >= P therefore have Vis(i) = { j : 0 <= j <= i }.  P = N is the pure
+ * prefill mask above, P = 0 is full causal attention.
+ *
  * Readings where the paper is silent: the window (i-W, i] holds W keys and
  * includes the query itself; a key that is both a sink and in the window is
  * counted once; sinks are causal (row i < S sees only [0, i]); the
@@ -45,11 +50,14 @@ static double bf16_to_double(uint16_t bits)
     return (double)f;
 }
 
-/* 1 if key j is visible from query i under (window W, sinks S). */
-static int visible(long i, long j, long W, long S)
+/* 1 if key j is visible from query i under (window W, sinks S), when the
+ * first P rows are prompt tokens and the rest are generated tokens. */
+static int visible(long i, long j, long W, long S, long P)
 {
     if (j < 0 || j > i)
         return 0; /* causal */
+    if (i >= P)
+        return 1; /* a generated token sees everything before it */
     return (j > i - W) || (j < S);
 }
 
@@ -65,17 +73,18 @@ int swaa_oracle_num_threads(void)
 /*
  * Evaluate rows `rows[0..n_rows)` (NULL: every row 0..N-1, n_rows ignored) of
  * every (b, h).  out: [B, Hq, R, D] doubles, lse: [B, Hq, R] doubles, with
- * R = n_rows (or N).  n_threads <= 0 keeps the OpenMP default.
+ * R = n_rows (or N).  P = n_prompt: rows >= P are generated tokens (any P >= N
+ * means there are none).  n_threads <= 0 keeps the OpenMP default.
  * Returns 0, or -1 on a bad argument, -2 when out of memory.
  */
-int swaa_oracle_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v,
-                     int B, int Hq, int Hkv, int N, int D, long W, long S,
-                     double scale, const int *rows, int n_rows, double *out,
-                     double *lse, int n_threads)
+int swaa_oracle_rows_mixed(const uint16_t *q, const uint16_t *k, const uint16_t *v,
+                           int B, int Hq, int Hkv, int N, int D, long W, long S,
+                           long P, double scale, const int *rows, int n_rows,
+                           double *out, double *lse, int n_threads)
 {
     if (!q || !k || !v || !out || !lse)
         return -1;
-    if (B < 1 || Hq < 1 || Hkv < 1 || N < 1 || D < 1 || Hq % Hkv || W < 1 || S < 0)
+    if (B < 1 || Hq < 1 || Hkv < 1 || N < 1 || D < 1 || Hq % Hkv || W < 1 || S < 0 || P < 0)
         return -1;
     const long R = rows ? n_rows : N;
     if (R < 0)
@@ -120,7 +129,7 @@ int swaa_oracle_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v,
             /* scores and their maximum over the visible set */
             double m = -INFINITY;
             for (long j = 0; j <= i; j++) {
-                if (!visible(i, j, W, S))
+                if (!visible(i, j, W, S, P))
                     continue;
                 const uint16_t *kr = kb + (size_t)j * D;
                 double acc = 0.0;
@@ -133,7 +142,7 @@ int swaa_oracle_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v,
             /* normaliser */
             double l = 0.0;
             for (long j = 0; j <= i; j++)
-                if (visible(i, j, W, S))
+                if (visible(i, j, W, S, P))
                     l += exp(s[j] - m);
             const double lse_i = m + log(l);
             lse[t] = lse_i;
@@ -141,7 +150,7 @@ int swaa_oracle_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v,
             for (int d = 0; d < D; d++)
                 o[d] = 0.0;
             for (long j = 0; j <= i; j++) {
-                if (!visible(i, j, W, S))
+                if (!visible(i, j, W, S, P))
                     continue;
                 const double p = exp(s[j] - lse_i);
                 const uint16_t *vr = vb + (size_t)j * D;
@@ -153,4 +162,14 @@ int swaa_oracle_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v,
         free(qi);
     }
     return failed ? -2 : 0;
+}
+
+/* The pure prefill mask: every row is a prompt token. */
+int swaa_oracle_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v,
+                     int B, int Hq, int Hkv, int N, int D, long W, long S,
+                     double scale, const int *rows, int n_rows, double *out,
+                     double *lse, int n_threads)
+{
+    return swaa_oracle_rows_mixed(q, k, v, B, Hq, Hkv, N, D, W, S, (long)N, scale,
+                                  rows, n_rows, out, lse, n_threads);
 }

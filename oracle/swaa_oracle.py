@@ -10,6 +10,10 @@ Fig. 1b, Sec. 4.1.2):
   numpy, one row at a time with an explicit list of visible keys; used for
   small cases and to cross-check the C build.
 
+Both take ``n_prompt`` (FA Decode, paper Sec. 3.1.1 / Fig. 1a): rows at or
+beyond it are generated tokens and see every earlier key; ``None`` means all
+rows are prompt tokens.
+
 Inputs are bf16 bit patterns held in ``uint16`` arrays of shape [B, H, N, D];
 outputs are float64 and unrounded.  Parity status: pinned (see
 ``tests/test_oracle_pins.py``): full-causal special case against a library
@@ -51,6 +55,12 @@ def _load():
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             ctypes.c_long, ctypes.c_long, ctypes.c_double,
             ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
+        lib.swaa_oracle_rows_mixed.restype = ctypes.c_int
+        lib.swaa_oracle_rows_mixed.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_double,
+            ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
         lib.swaa_oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -74,11 +84,12 @@ def _check(q, k, v):
     return B, Hq, Hkv, N, D
 
 
-def swaa_attn_oracle(q, k, v, window, n_sink, scale, rows=None, n_threads=0):
+def swaa_attn_oracle(q, k, v, window, n_sink, scale, rows=None, n_threads=0, n_prompt=None):
     """fp64 SWA+sink attention via the C oracle.
 
     rows: optional 1-D int array of query rows to evaluate (same set for every
-    (b, h)); None evaluates all N rows.  Returns (out [B,Hq,R,D] float64,
+    (b, h)); None evaluates all N rows.  n_prompt: rows >= n_prompt attend to
+    all earlier keys (None: no such rows).  Returns (out [B,Hq,R,D] float64,
     lse [B,Hq,R] float64).
     """
     B, Hq, Hkv, N, D = _check(q, k, v)
@@ -93,10 +104,16 @@ def swaa_attn_oracle(q, k, v, window, n_sink, scale, rows=None, n_threads=0):
         rows_p = rows_arr.ctypes.data
     out = np.empty((B, Hq, R, D), dtype=np.float64)
     lse = np.empty((B, Hq, R), dtype=np.float64)
-    rc = _load().swaa_oracle_rows(
-        q.ctypes.data, k.ctypes.data, v.ctypes.data, B, Hq, Hkv, N, D,
-        int(window), int(n_sink), float(scale), rows_p, R,
-        out.ctypes.data, lse.ctypes.data, int(n_threads))
+    if n_prompt is None:
+        rc = _load().swaa_oracle_rows(
+            q.ctypes.data, k.ctypes.data, v.ctypes.data, B, Hq, Hkv, N, D,
+            int(window), int(n_sink), float(scale), rows_p, R,
+            out.ctypes.data, lse.ctypes.data, int(n_threads))
+    else:
+        rc = _load().swaa_oracle_rows_mixed(
+            q.ctypes.data, k.ctypes.data, v.ctypes.data, B, Hq, Hkv, N, D,
+            int(window), int(n_sink), int(n_prompt), float(scale), rows_p, R,
+            out.ctypes.data, lse.ctypes.data, int(n_threads))
     if rc != 0:
         raise ValueError(f"swaa_oracle_rows failed with code {rc}")
     return out, lse
@@ -106,12 +123,13 @@ def _bf16_bits_to_f64(a: np.ndarray) -> np.ndarray:
     return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
 
 
-def swaa_attn_oracle_numpy(q, k, v, window, n_sink, scale, rows=None):
+def swaa_attn_oracle_numpy(q, k, v, window, n_sink, scale, rows=None, n_prompt=None):
     """The same definition in numpy, row by row (slow; small inputs only)."""
     B, Hq, Hkv, N, D = _check(q, k, v)
     W, S = int(window), int(n_sink)
-    if W < 1 or S < 0:
-        raise ValueError("window >= 1 and n_sink >= 0 required")
+    P = N if n_prompt is None else int(n_prompt)
+    if W < 1 or S < 0 or P < 0:
+        raise ValueError("window >= 1, n_sink >= 0 and n_prompt >= 0 required")
     G = Hq // Hkv
     qf, kf, vf = (_bf16_bits_to_f64(a) for a in (q, k, v))
     row_list = list(range(N)) if rows is None else [int(r) for r in rows]
@@ -121,7 +139,7 @@ def swaa_attn_oracle_numpy(q, k, v, window, n_sink, scale, rows=None):
         for h in range(Hq):
             g = h // G
             for r, i in enumerate(row_list):
-                vis = [j for j in range(i + 1) if (j > i - W) or (j < S)]
+                vis = [j for j in range(i + 1) if (i >= P) or (j > i - W) or (j < S)]
                 s = scale * (kf[b, g, vis] @ qf[b, h, i])
                 m = s.max()
                 lse_i = m + np.log(np.exp(s - m).sum())
