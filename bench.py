@@ -58,25 +58,28 @@ def cpu_baseline(w, q, k, v, target_s):
     """Time the oracle as it stands on a bounded sample of this workload's rows."""
     import numpy as np
     from oracle import oracle_num_threads, swaa_attn_oracle
-    from paper_2512_10411_amd.binding import swaa_visible_pairs
+    from paper_2512_10411_amd.binding import swaa_visible_pairs_fa_decode
+
+    n_prompt = w.N if w.n_prompt is None else w.n_prompt
 
     def pairs_of(rows):
         r = np.asarray(rows, dtype=np.int64)
         vis = np.minimum(r + 1, min(w.window, w.N)) + np.clip(r - w.window + 1, 0, min(w.n_sink, w.N))
+        vis = np.where(r >= n_prompt, r + 1, vis)
         return int(vis.sum()) * w.B * w.Hq
 
     rng = np.random.Generator(np.random.Philox(w.seed + 5))
     order = rng.permutation(w.N)
     pilot = np.sort(order[:8])
     t0 = time.perf_counter()
-    swaa_attn_oracle(q, k, v, w.window, w.n_sink, w.scale, rows=pilot)
+    swaa_attn_oracle(q, k, v, w.window, w.n_sink, w.scale, rows=pilot, n_prompt=n_prompt)
     t_pilot = max(time.perf_counter() - t0, 1e-4)
     rate = pairs_of(pilot) / t_pilot
-    mean_pairs_per_row = swaa_visible_pairs(w.N, w.window, w.n_sink) * w.B * w.Hq / w.N
+    mean_pairs_per_row = swaa_visible_pairs_fa_decode(w.N, w.window, w.n_sink, n_prompt) * w.B * w.Hq / w.N
     n_rows = int(min(w.N, max(8, target_s * rate / mean_pairs_per_row)))
     rows = np.sort(order[:n_rows])
     t0 = time.perf_counter()
-    swaa_attn_oracle(q, k, v, w.window, w.n_sink, w.scale, rows=rows)
+    swaa_attn_oracle(q, k, v, w.window, w.n_sink, w.scale, rows=rows, n_prompt=n_prompt)
     dt = time.perf_counter() - t0
     pairs = pairs_of(rows)
     return {
@@ -122,8 +125,14 @@ def main():
     lse = torch.empty((w.B, w.Hq, w.N), dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
 
+    n_prompt = w.N if w.n_prompt is None else w.n_prompt
+
     def step():
-        binding.swaa_attn_fwd(qd, kd, vd, w.window, w.n_sink, w.scale, out=out, lse=lse, stream=stream)
+        if w.n_prompt is None:
+            binding.swaa_attn_fwd(qd, kd, vd, w.window, w.n_sink, w.scale, out=out, lse=lse, stream=stream)
+        else:
+            binding.swaa_attn_fwd_fa_decode(qd, kd, vd, w.window, w.n_sink, n_prompt, w.scale, out=out, lse=lse,
+                                            stream=stream)
 
     for _ in range(args.warmup):
         step()
@@ -153,7 +162,7 @@ def main():
     kern_avg_ms = ev0.elapsed_time(ev1) / args.steps
     ms_per_step = wall * 1e3 / args.steps
 
-    pairs = binding.swaa_visible_pairs(w.N, w.window, w.n_sink) * w.B * w.Hq
+    pairs = binding.swaa_visible_pairs_fa_decode(w.N, w.window, w.n_sink, n_prompt) * w.B * w.Hq
     flops = 4.0 * w.D * pairs
     value = flops / (ms_per_step * 1e-3) / 1e12
     achieved = flops / (kern_avg_ms * 1e-3) / 1e12
@@ -172,7 +181,7 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "N": w.N, "D": w.D,
-                   "window": w.window, "n_sink": w.n_sink, "seed": w.seed, "k_mult": w.k_mult,
+                   "window": w.window, "n_sink": w.n_sink, "n_prompt": n_prompt, "seed": w.seed, "k_mult": w.k_mult,
                    "visible_pairs": pairs, "flops_per_step": flops,
                    "pct_bf16_mfma_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",

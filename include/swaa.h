@@ -37,7 +37,7 @@ extern "C" {
 typedef enum swaa_status {
     SWAA_OK = 0,
     SWAA_ERR_NULL = -1,        /* a required pointer is NULL */
-    SWAA_ERR_SHAPE = -2,       /* a size, the window, the sink count or the scale is out of range */
+    SWAA_ERR_SHAPE = -2,       /* a size, the window, the sink count, the prompt length or the scale is out of range */
     SWAA_ERR_UNSUPPORTED = -3, /* head dimension without a kernel instantiation */
     SWAA_ERR_ALIGN = -4,       /* a pointer is not 16-byte aligned */
     SWAA_ERR_LAUNCH = -5       /* the HIP runtime refused the launch */
@@ -67,12 +67,38 @@ int swaa_attn_fwd(const void *q, const void *k, const void *v, void *out, float 
                   float scale, void *stream);
 
 /*
+ * Attention forward under the FA Decode mask (paper Sec. 3.1.1 and Fig. 1a:
+ * the sliding window applies to the prefilling stage only; during decoding
+ * each token reverts to full attention over all previous tokens).  The
+ * sequence of N positions is the prompt followed by the generated tokens, as
+ * when a whole conversation is processed in one pass:
+ *
+ *     Vis(i) = { j : 0 <= j <= i  and ( j > i - window  or  j < n_sink ) }   for i <  n_prompt
+ *     Vis(i) = { j : 0 <= j <= i }                                           for i >= n_prompt
+ *
+ * and everything else as in swaa_attn_fwd, whose arguments, layouts, ownership
+ * and error behaviour apply unchanged.
+ *
+ *   n_prompt  >= 0: number of leading prompt rows; values >= N mean that there
+ *             are no generated rows (the call then equals swaa_attn_fwd), 0
+ *             means full causal attention for every row
+ *
+ * Returns SWAA_OK or a negative swaa_status (n_prompt < 0: SWAA_ERR_SHAPE).
+ */
+int swaa_attn_fwd_fa_decode(const void *q, const void *k, const void *v, void *out, float *lse,
+                            int B, int Hq, int Hkv, int N, int D, int window, int n_sink,
+                            int n_prompt, float scale, void *stream);
+
+/*
  * Number of visible (query, key) pairs per head under the mask above, i.e.
  * sum over i in [0, N) of |Vis(i)|; the benchmark counts 4*D floating-point
  * operations per pair (paper App. A: the cost of sliding window attention is
  * O(N * W)).  Host-only arithmetic; returns -1 on an invalid argument.
  */
 long long swaa_visible_pairs(long long N, long long window, long long n_sink);
+
+/* The same count under the FA Decode mask of swaa_attn_fwd_fa_decode. */
+long long swaa_visible_pairs_fa_decode(long long N, long long window, long long n_sink, long long n_prompt);
 
 /* Static description of a status code; never NULL, never freed. */
 const char *swaa_status_string(int status);

@@ -22,7 +22,8 @@ SWAA_ERR_ALIGN = -4
 SWAA_ERR_LAUNCH = -5
 
 # every symbol include/swaa.h declares
-EXPORTS = ("swaa_attn_fwd", "swaa_visible_pairs", "swaa_status_string", "swaa_version")
+EXPORTS = ("swaa_attn_fwd", "swaa_attn_fwd_fa_decode", "swaa_visible_pairs", "swaa_visible_pairs_fa_decode",
+           "swaa_status_string", "swaa_version")
 
 _lib = None
 
@@ -47,8 +48,15 @@ def load_library() -> ctypes.CDLL:
         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
         ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
         ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_void_p]
+    lib.swaa_attn_fwd_fa_decode.restype = ctypes.c_int
+    lib.swaa_attn_fwd_fa_decode.argtypes = [
+        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+        ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+        ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_void_p]
     lib.swaa_visible_pairs.restype = ctypes.c_longlong
     lib.swaa_visible_pairs.argtypes = [ctypes.c_longlong] * 3
+    lib.swaa_visible_pairs_fa_decode.restype = ctypes.c_longlong
+    lib.swaa_visible_pairs_fa_decode.argtypes = [ctypes.c_longlong] * 4
     lib.swaa_status_string.restype = ctypes.c_char_p
     lib.swaa_status_string.argtypes = [ctypes.c_int]
     lib.swaa_version.restype = ctypes.c_int
@@ -73,11 +81,26 @@ def swaa_visible_pairs(N: int, window: int, n_sink: int) -> int:
     return r
 
 
+def swaa_visible_pairs_fa_decode(N: int, window: int, n_sink: int, n_prompt: int) -> int:
+    """Visible pairs per head when rows >= n_prompt attend to every earlier key."""
+    r = int(load_library().swaa_visible_pairs_fa_decode(int(N), int(window), int(n_sink), int(n_prompt)))
+    if r < 0:
+        raise SwaaError(SWAA_ERR_SHAPE, "invalid N / window / n_sink / n_prompt")
+    return r
+
+
 def swaa_attn_fwd_raw(q_ptr, k_ptr, v_ptr, out_ptr, lse_ptr, B, Hq, Hkv, N, D,
                       window, n_sink, scale, stream_ptr) -> int:
     """The C call itself, on raw addresses; returns the status code."""
     return int(load_library().swaa_attn_fwd(
         q_ptr, k_ptr, v_ptr, out_ptr, lse_ptr, B, Hq, Hkv, N, D, window, n_sink, scale, stream_ptr))
+
+
+def swaa_attn_fwd_fa_decode_raw(q_ptr, k_ptr, v_ptr, out_ptr, lse_ptr, B, Hq, Hkv, N, D,
+                                window, n_sink, n_prompt, scale, stream_ptr) -> int:
+    """The C call itself, on raw addresses; returns the status code."""
+    return int(load_library().swaa_attn_fwd_fa_decode(
+        q_ptr, k_ptr, v_ptr, out_ptr, lse_ptr, B, Hq, Hkv, N, D, window, n_sink, n_prompt, scale, stream_ptr))
 
 
 def swaa_attn_fwd(q, k, v, window: int, n_sink: int, scale: float | None = None,
@@ -88,6 +111,16 @@ def swaa_attn_fwd(q, k, v, window: int, n_sink: int, scale: float | None = None,
     tensors on one device.  Returns (out bf16 [B, Hq, N, D], lse fp32 [B, Hq, N]).
     The call is asynchronous on `stream` (default: torch's current stream).
     """
+    return _fwd(q, k, v, window, n_sink, None, scale, out, lse, stream)
+
+
+def swaa_attn_fwd_fa_decode(q, k, v, window: int, n_sink: int, n_prompt: int, scale: float | None = None,
+                            out=None, lse=None, stream=None):
+    """As swaa_attn_fwd, with rows >= n_prompt (generated tokens) attending to every earlier key."""
+    return _fwd(q, k, v, window, n_sink, int(n_prompt), scale, out, lse, stream)
+
+
+def _fwd(q, k, v, window, n_sink, n_prompt, scale, out, lse, stream):
     import torch
 
     for name, t in (("q", q), ("k", k), ("v", v)):
@@ -117,8 +150,12 @@ def swaa_attn_fwd(q, k, v, window: int, n_sink: int, scale: float | None = None,
         if stream is None:
             stream = torch.cuda.current_stream(q.device)
         sptr = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
-        rc = swaa_attn_fwd_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
-                               B, Hq, Hkv, N, D, int(window), int(n_sink), float(scale), sptr)
+        ptrs = (q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr())
+        if n_prompt is None:
+            rc = swaa_attn_fwd_raw(*ptrs, B, Hq, Hkv, N, D, int(window), int(n_sink), float(scale), sptr)
+        else:
+            rc = swaa_attn_fwd_fa_decode_raw(*ptrs, B, Hq, Hkv, N, D, int(window), int(n_sink), n_prompt,
+                                             float(scale), sptr)
     if rc != SWAA_OK:
         raise SwaaError(rc, swaa_status_string(rc))
     return out, lse

@@ -47,11 +47,19 @@ long long swaa_visible_pairs(long long N, long long window, long long n_sink) {
     return pairs;
 }
 
+long long swaa_visible_pairs_fa_decode(long long N, long long window, long long n_sink, long long n_prompt) {
+    if (N < 1 || window < 1 || n_sink < 0 || n_prompt < 0) return -1;
+    const long long P = n_prompt < N ? n_prompt : N;
+    // the visible set of a prompt row does not depend on N; generated row i sees i + 1 keys
+    const long long prompt_pairs = P > 0 ? swaa_visible_pairs(P, window, n_sink) : 0;
+    return prompt_pairs + (N * (N + 1) - P * (P + 1)) / 2;
+}
+
 const char *swaa_status_string(int status) {
     switch (status) {
         case SWAA_OK: return "ok";
         case SWAA_ERR_NULL: return "null pointer argument";
-        case SWAA_ERR_SHAPE: return "size, window, sink count or scale out of range";
+        case SWAA_ERR_SHAPE: return "size, window, sink count, prompt length or scale out of range";
         case SWAA_ERR_UNSUPPORTED: return "unsupported head dimension (64 and 128 are built)";
         case SWAA_ERR_ALIGN: return "pointer not 16-byte aligned";
         case SWAA_ERR_LAUNCH: return "HIP launch failed";
@@ -59,15 +67,15 @@ const char *swaa_status_string(int status) {
     }
 }
 
-int swaa_version(void) { return 100; }
+int swaa_version(void) { return 110; }
 
-int swaa_attn_fwd(const void *q, const void *k, const void *v, void *out, float *lse,
-                  int B, int Hq, int Hkv, int N, int D, int window, int n_sink,
-                  float scale, void *stream) {
+int swaa_attn_fwd_fa_decode(const void *q, const void *k, const void *v, void *out, float *lse,
+                            int B, int Hq, int Hkv, int N, int D, int window, int n_sink,
+                            int n_prompt, float scale, void *stream) {
     if (!q || !k || !v || !out || !lse) return SWAA_ERR_NULL;
     if (B < 1 || Hq < 1 || Hkv < 1 || N < 1 || D < 1) return SWAA_ERR_SHAPE;
     if (Hq % Hkv != 0) return SWAA_ERR_SHAPE;
-    if (window < 1 || n_sink < 0) return SWAA_ERR_SHAPE;
+    if (window < 1 || n_sink < 0 || n_prompt < 0) return SWAA_ERR_SHAPE;
     if (!positive_finite(scale)) return SWAA_ERR_SHAPE;
     if (D != 64 && D != 128) return SWAA_ERR_UNSUPPORTED;
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(lse))
@@ -82,6 +90,7 @@ int swaa_attn_fwd(const void *q, const void *k, const void *v, void *out, float 
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N;
     p.W = window < N ? window : N;
     p.S = n_sink < N ? n_sink : N;
+    p.P = n_prompt < N ? n_prompt : N;
     p.G = Hq / Hkv;
     p.scale = scale;
     p.scale_log2 = scale * 1.44269504088896340736f;
@@ -101,6 +110,13 @@ int swaa_attn_fwd(const void *q, const void *k, const void *v, void *out, float 
     const hipError_t err = (D == 128 && !use_simple_kernel()) ? swaa::launch_fwd_pipelined_d128(p, s)
                                                               : swaa::launch_fwd_simple(p, D, s);
     return err == hipSuccess ? SWAA_OK : SWAA_ERR_LAUNCH;
+}
+
+int swaa_attn_fwd(const void *q, const void *k, const void *v, void *out, float *lse,
+                  int B, int Hq, int Hkv, int N, int D, int window, int n_sink,
+                  float scale, void *stream) {
+    // every row is a prompt token
+    return swaa_attn_fwd_fa_decode(q, k, v, out, lse, B, Hq, Hkv, N, D, window, n_sink, N, scale, stream);
 }
 
 }  // extern "C"

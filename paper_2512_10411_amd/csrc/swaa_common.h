@@ -30,6 +30,7 @@ struct FwdParams {
     float *lse;
     int B, Hq, Hkv, N;
     int W, S;  // clamped to [1, N] and [0, N]
+    int P;     // rows >= P are generated tokens and see every earlier key; clamped to [0, N]
     int G;     // Hq / Hkv
     float scale, scale_log2;
     // Work decomposition.  Per (batch, KV head) "pair" the G query heads are
@@ -81,6 +82,13 @@ __device__ __forceinline__ bool decode_work(const FwdParams &p, WorkItem &w) {
     w.h0 = p.G - 1;
     w.pt = p.nt256 - 1 - r;
     return true;
+}
+
+// Row block [p0, p0 + rows): a key is inside the window of every prompt row of
+// the block iff it lies above the returned bound (last prompt row minus W); a
+// block of generated tokens only has no such bound.
+__device__ __forceinline__ int window_bound(int p0, int rows, int W, int P) {
+    return p0 >= P ? -(1 << 30) : min(p0 + rows - 1, P - 1) - W;
 }
 
 // Lanes l and l^32 hold partial results for the same query column.

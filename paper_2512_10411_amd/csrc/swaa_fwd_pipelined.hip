@@ -326,7 +326,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     if (!decode_work(p, wi)) return;
     const int hpb = wi.hpb;
     const int pos_per_wg = kWgRows / hpb;
-    const int N = p.N, W = p.W, S = p.S;
+    const int N = p.N, S = p.S;
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
@@ -339,9 +339,12 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     const int wg_p1 = min(N, wg_p0 + pos_per_wg) - 1;
     const int p0 = wg_p0 + (wave / hpb) * kPRows;  // first position of this wave
     const int qpos = p0 + l32;                     // this lane's query column
+    // this lane's window: a generated token (position >= P) sees its whole prefix
+    const int W = (qpos >= p.P) ? N : p.W;
 
-    // visited KV tiles: sink tiles 0 .. n_sink_tiles-1, then band tiles t_band_lo .. t_hi
-    const int band_lo = max(0, wg_p0 - W + 1);
+    // visited KV tiles: sink tiles 0 .. n_sink_tiles-1, then band tiles t_band_lo .. t_hi;
+    // a workgroup that holds a generated token visits every tile up to its diagonal
+    const int band_lo = (wg_p1 >= p.P) ? 0 : max(0, wg_p0 - p.W + 1);
     const int t_band_lo = band_lo / kBk;
     const int t_hi = wg_p1 / kBk;
     const int n_sink_tiles = min((min(S, band_lo) + kBk - 1) / kBk, t_band_lo);
@@ -494,11 +497,10 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     }
 
     // A wave needs no mask on a 32-key half when all its keys are visible to all
-    // its 32 rows: at or below the first row's diagonal, and inside the last
-    // row's window or all sinks.
-    auto half_masked = [&](int k0h) {
-        return !((k0h + 31 <= p0) && ((k0h > p0 + kPRows - 1 - W) || (k0h + 31 < S)));
-    };
+    // its 32 rows: at or below the first row's diagonal, and inside the window of
+    // its last prompt row (if it has one) or all sinks.
+    const int wbound = window_bound(p0, kPRows, p.W, p.P);
+    auto half_masked = [&](int k0h) { return !((k0h + 31 <= p0) && ((k0h > wbound) || (k0h + 31 < S))); };
 
     // step 0 reads V(0) and K(1): they must be there for every wave (K(2), V(1) may still fly)
     if (J >= 3)

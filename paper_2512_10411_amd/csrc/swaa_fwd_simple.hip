@@ -55,7 +55,7 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
     if (!decode_work(p, wi)) return;
     const int b = wi.b, kvh = wi.kvh, hpb = wi.hpb, h0 = wi.h0, pt = wi.pt;
     const int pos_per_wg = kWgRows / hpb;
-    const int N = p.N, W = p.W, S = p.S;
+    const int N = p.N, W = p.W, S = p.S, P = p.P;
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
@@ -71,11 +71,13 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
     const int plast = min(p0 + kWaveRows, N) - 1;           // last valid position of this wave
 
     // ---- KV tiles this workgroup visits -------------------------------------
-    const int band_lo = max(0, wg_p0 - W + 1);
+    // (a workgroup that holds a generated token visits every tile up to its diagonal)
+    const int band_lo = (wg_p1 >= P) ? 0 : max(0, wg_p0 - W + 1);
     const int t_band_lo = band_lo / kBk;
     const int t_hi = wg_p1 / kBk;
     const int n_sink_tiles = min((min(S, band_lo) + kBk - 1) / kBk, t_band_lo);
     // tile order: 0 .. n_sink_tiles-1, then t_band_lo .. t_hi
+    const int wbound = window_bound(p0, kWaveRows, W, P);
 
     const size_t kv_base = ((size_t)b * p.Hkv + kvh) * (size_t)N * D;
     const __bf16 *kg = p.k + kv_base;
@@ -147,9 +149,9 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
         const int k_last = k0 + kBk - 1;
         // per-wave classification of the tile against this wave's 64 positions
         const bool in_future = k0 > plast;
-        const bool before_band = (k_last < p0 - W + 1) && (k0 >= S);
+        const bool before_band = (plast < P) && (k_last < p0 - W + 1) && (k0 >= S);
         if (wave_active && !in_future && !before_band) {
-            const bool unmasked = (k_last <= p0) && ((k0 > p0 + kWaveRows - 1 - W) || (k_last < S));
+            const bool unmasked = (k_last <= p0) && ((k0 > wbound) || (k_last < S));
 
             // ---- S^T = K Q^T : [64 keys] x [64 queries] ----
             f32x16 sacc[2][2];
@@ -176,12 +178,13 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
 #pragma unroll
                 for (int qb = 0; qb < 2; ++qb) {
                     const int qpos = p0 + 32 * qb + l32;
+                    const int wq = (qpos >= P) ? N : W;  // a generated token's window is the whole prefix
 #pragma unroll
                     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                         for (int e = 0; e < 16; ++e) {
                             const int key = k0 + 32 * kb + 8 * (e / 4) + 4 * hf + (e % 4);
-                            const bool vis = (key <= qpos) && ((key > qpos - W) || (key < S));
+                            const bool vis = (key <= qpos) && ((key > qpos - wq) || (key < S));
                             sacc[kb][qb][e] = vis ? sacc[kb][qb][e] : -INFINITY;
                         }
                 }

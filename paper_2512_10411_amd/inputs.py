@@ -47,6 +47,7 @@ class Workload:
     n_sink: int
     seed: int
     k_mult: float = 1.0   # k is multiplied by this (exact in bf16 for powers of two)
+    n_prompt: int | None = None  # FA Decode runs: rows >= n_prompt are generated tokens
 
     @property
     def scale(self) -> float:
@@ -66,6 +67,12 @@ WORKLOADS = {
     "batched":     Workload("batched",     4, 40, 8,   8192, 128,  1024, 4, _SEED0 + 4),
     "long128k_swa": Workload("long128k_swa", 1, 32, 8, 131072, 128, 8192, 4, _SEED0 + 5),
     "long128k_full": Workload("long128k_full", 1, 32, 8, 131072, 128, 131072, 4, _SEED0 + 5),
+    # FA Decode over a whole conversation in one pass (same tensors as the runs above):
+    # the last 512 rows are generated tokens, the output length of the paper's
+    # efficiency experiment (Sec. 4.2.2)
+    "mid_fa_decode": Workload("mid_fa_decode", 1, 32, 8, 16384, 128, 2048, 4, _SEED0 + 2, 1.0, 16384 - 512),
+    "long128k_fa_decode": Workload("long128k_fa_decode", 1, 32, 8, 131072, 128, 8192, 4, _SEED0 + 5, 1.0,
+                                   131072 - 512),
 }
 
 

@@ -66,3 +66,24 @@ def test_argument_errors_are_reported_before_any_launch():
     assert call(o=p + 2) == binding.SWAA_ERR_ALIGN
     for code in (0, -1, -2, -3, -4, -5, -99):
         assert isinstance(binding.swaa_status_string(code), str) and binding.swaa_status_string(code)
+
+
+def test_fa_decode_pair_count_and_argument_errors():
+    def brute(N, W, S, P):
+        return sum(1 for i in range(N) for j in range(i + 1) if i >= P or (j > i - W) or (j < S))
+
+    for N in (1, 6, 19):
+        for W in range(1, N + 2, 2):
+            for S in range(0, N + 2, 3):
+                for P in range(0, N + 3):
+                    assert binding.swaa_visible_pairs_fa_decode(N, W, S, P) == brute(N, W, S, P), (N, W, S, P)
+    assert binding.swaa_visible_pairs_fa_decode(500, 40, 3, 500) == binding.swaa_visible_pairs(500, 40, 3)
+    with pytest.raises(binding.SwaaError):
+        binding.swaa_visible_pairs_fa_decode(8, 4, 0, -1)
+
+    p = 4096  # fake aligned address; never dereferenced on these paths
+    f = binding.swaa_attn_fwd_fa_decode_raw
+    assert f(p, p, p, p, p, 1, 4, 2, 128, 128, 16, 2, -1, 0.1, None) == binding.SWAA_ERR_SHAPE
+    assert f(p, p, None, p, p, 1, 4, 2, 128, 128, 16, 2, 64, 0.1, None) == binding.SWAA_ERR_NULL
+    assert f(p, p, p, p, p, 1, 4, 2, 128, 96, 16, 2, 64, 0.1, None) == binding.SWAA_ERR_UNSUPPORTED
+    assert f(p, p, p, p + 4, p, 1, 4, 2, 128, 128, 16, 2, 64, 0.1, None) == binding.SWAA_ERR_ALIGN
