@@ -9,4 +9,6 @@ from .swaa_oracle import (  # noqa: F401
     oracle_num_threads,
     swaa_attn_oracle,
     swaa_attn_oracle_numpy,
+    swaa_decode_oracle,
+    swaa_decode_oracle_numpy,
 )

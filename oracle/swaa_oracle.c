@@ -173,3 +173,88 @@ int swaa_oracle_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v,
     return swaa_oracle_rows_mixed(q, k, v, B, Hq, Hkv, N, D, W, S, (long)N, scale,
                                   rows, n_rows, out, lse, n_threads);
 }
+
+/*
+ * Decode shape (paper Sec. 3.1.1: during auto-regressive generation a token
+ * attends to the cached keys and values of the tokens before it -- all of them
+ * under FA Decode, i.e. W >= Nk, or its window plus the sinks when decoding
+ * stays on sliding-window attention).  The Nq query rows are the newest
+ * tokens of a sequence of Nk: row r sits at position Nk - Nq + r, and the
+ * cache k, v [B, Hkv, Nk, D] already holds their own keys and values.
+ *
+ *   Vis(r) = { j : 0 <= j <= pos and ( j > pos - W or j < S ) },  pos = Nk - Nq + r
+ *
+ * q: [B, Hq, Nq, D] bf16 bits; out: [B, Hq, Nq, D] doubles; lse: [B, Hq, Nq].
+ * Returns 0, or -1 on a bad argument, -2 when out of memory.
+ */
+int swaa_oracle_decode(const uint16_t *q, const uint16_t *k, const uint16_t *v,
+                       int B, int Hq, int Hkv, int Nq, int Nk, int D, long W, long S,
+                       double scale, double *out, double *lse, int n_threads)
+{
+    if (!q || !k || !v || !out || !lse)
+        return -1;
+    if (B < 1 || Hq < 1 || Hkv < 1 || Nq < 1 || Nk < Nq || D < 1 || Hq % Hkv || W < 1 || S < 0)
+        return -1;
+    const int G = Hq / Hkv;
+    const long total = (long)B * Hq * Nq;
+    const long never_generated = (long)Nk + 1; /* every row keeps its window */
+    int failed = 0;
+#ifdef _OPENMP
+    if (n_threads > 0)
+        omp_set_num_threads(n_threads);
+#else
+    (void)n_threads;
+#endif
+
+#pragma omp parallel
+    {
+        double *s = (double *)malloc(sizeof(double) * (size_t)Nk);
+        if (!s) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(dynamic, 1)
+        for (long t = 0; t < total; t++) {
+            if (!s)
+                continue;
+            const long r = t % Nq;
+            const long h = (t / Nq) % Hq;
+            const long b = t / ((long)Nq * Hq);
+            const long g = h / G;
+            const long pos = (long)Nk - Nq + r;
+            const uint16_t *qrow = q + (size_t)t * D;
+            const uint16_t *kb = k + ((size_t)b * Hkv + g) * (size_t)Nk * D;
+            const uint16_t *vb = v + ((size_t)b * Hkv + g) * (size_t)Nk * D;
+            double *o = out + (size_t)t * D;
+
+            double m = -INFINITY;
+            for (long j = 0; j < Nk; j++) {
+                if (!visible(pos, j, W, S, never_generated))
+                    continue;
+                double acc = 0.0;
+                for (int d = 0; d < D; d++)
+                    acc += bf16_to_double(qrow[d]) * bf16_to_double(kb[(size_t)j * D + d]);
+                s[j] = scale * acc;
+                if (s[j] > m)
+                    m = s[j];
+            }
+            double l = 0.0;
+            for (long j = 0; j < Nk; j++)
+                if (visible(pos, j, W, S, never_generated))
+                    l += exp(s[j] - m);
+            const double lse_r = m + log(l);
+            lse[t] = lse_r;
+            for (int d = 0; d < D; d++)
+                o[d] = 0.0;
+            for (long j = 0; j < Nk; j++) {
+                if (!visible(pos, j, W, S, never_generated))
+                    continue;
+                const double p = exp(s[j] - lse_r);
+                for (int d = 0; d < D; d++)
+                    o[d] += p * bf16_to_double(vb[(size_t)j * D + d]);
+            }
+        }
+        free(s);
+    }
+    return failed ? -2 : 0;
+}

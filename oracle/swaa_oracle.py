@@ -14,11 +14,16 @@ Both take ``n_prompt`` (FA Decode, paper Sec. 3.1.1 / Fig. 1a): rows at or
 beyond it are generated tokens and see every earlier key; ``None`` means all
 rows are prompt tokens.
 
+:func:`swaa_decode_oracle` (and its numpy twin) is the decode shape: the Nq
+newest tokens of a sequence against a cache of Nk keys and values.
+
 Inputs are bf16 bit patterns held in ``uint16`` arrays of shape [B, H, N, D];
 outputs are float64 and unrounded.  Parity status: pinned (see
 ``tests/test_oracle_pins.py``): full-causal special case against a library
 softmax-attention, closed forms for W=1 and Q=0, brute-force boolean masks on
-tiny inputs, locality, merge identity, GQA/batch identities.
+tiny inputs, locality, merge identity, GQA/batch identities; the FA Decode
+mask and the decode shape in ``tests/test_oracle_pins_fa_decode.py`` and
+``tests/test_oracle_pins_decode.py``.
 """
 from __future__ import annotations
 
@@ -61,6 +66,11 @@ def _load():
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_double,
             ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
+        lib.swaa_oracle_decode.restype = ctypes.c_int
+        lib.swaa_oracle_decode.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_long, ctypes.c_long, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
         lib.swaa_oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -146,4 +156,60 @@ def swaa_attn_oracle_numpy(q, k, v, window, n_sink, scale, rows=None, n_prompt=N
                 p = np.exp(s - lse_i)
                 out[b, h, r] = p @ vf[b, g, vis]
                 lse[b, h, r] = lse_i
+    return out, lse
+
+
+def _check_decode(q, k, v):
+    for name, a in (("q", q), ("k", k), ("v", v)):
+        if not isinstance(a, np.ndarray) or a.dtype != np.uint16 or a.ndim != 4:
+            raise TypeError(f"{name}: expected uint16 (bf16 bits) ndarray [B,H,N,D]")
+    B, Hq, Nq, D = q.shape
+    if k.shape != v.shape or k.shape[0] != B or k.shape[3] != D:
+        raise ValueError("k/v shape mismatch")
+    Hkv, Nk = k.shape[1], k.shape[2]
+    if Hq % Hkv:
+        raise ValueError("Hq must be a multiple of Hkv")
+    if Nq > Nk:
+        raise ValueError("the cache must hold the query tokens' own keys: Nq <= Nk")
+    return B, Hq, Hkv, Nq, Nk, D
+
+
+def swaa_decode_oracle(q, k, v, window, n_sink, scale, n_threads=0):
+    """fp64 attention of the Nq newest tokens (q [B,Hq,Nq,D]) over a cache of Nk
+    tokens (k, v [B,Hkv,Nk,D]) via the C oracle (paper Sec. 3.1.1).  Row r sits at
+    position Nk - Nq + r; window >= Nk is full attention (FA Decode).  Returns
+    (out [B,Hq,Nq,D] float64, lse [B,Hq,Nq] float64)."""
+    B, Hq, Hkv, Nq, Nk, D = _check_decode(q, k, v)
+    q, k, v = (np.ascontiguousarray(a) for a in (q, k, v))
+    out = np.empty((B, Hq, Nq, D), dtype=np.float64)
+    lse = np.empty((B, Hq, Nq), dtype=np.float64)
+    rc = _load().swaa_oracle_decode(q.ctypes.data, k.ctypes.data, v.ctypes.data, B, Hq, Hkv, Nq, Nk, D,
+                                    int(window), int(n_sink), float(scale), out.ctypes.data, lse.ctypes.data,
+                                    int(n_threads))
+    if rc != 0:
+        raise ValueError(f"swaa_oracle_decode failed with code {rc}")
+    return out, lse
+
+
+def swaa_decode_oracle_numpy(q, k, v, window, n_sink, scale):
+    """The same definition in numpy, row by row (slow; small inputs only)."""
+    B, Hq, Hkv, Nq, Nk, D = _check_decode(q, k, v)
+    W, S = int(window), int(n_sink)
+    if W < 1 or S < 0:
+        raise ValueError("window >= 1 and n_sink >= 0 required")
+    G = Hq // Hkv
+    qf, kf, vf = (_bf16_bits_to_f64(a) for a in (q, k, v))
+    out = np.empty((B, Hq, Nq, D), dtype=np.float64)
+    lse = np.empty((B, Hq, Nq), dtype=np.float64)
+    for b in range(B):
+        for h in range(Hq):
+            g = h // G
+            for r in range(Nq):
+                pos = Nk - Nq + r
+                vis = [j for j in range(pos + 1) if (j > pos - W) or (j < S)]
+                s = scale * (kf[b, g, vis] @ qf[b, h, r])
+                m = s.max()
+                lse_r = m + np.log(np.exp(s - m).sum())
+                out[b, h, r] = np.exp(s - lse_r) @ vf[b, g, vis]
+                lse[b, h, r] = lse_r
     return out, lse

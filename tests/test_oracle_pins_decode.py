@@ -1,0 +1,109 @@
+"""Pins of the oracle's decode shape (paper Sec. 3.1.1): the Nq newest tokens of a
+sequence attend to a cache of Nk keys and values -- all of them under FA Decode, the
+window plus the sinks when decoding stays on sliding-window attention.
+
+The paper prints no numeric example of the attention computation; the pins are a
+library routine without any mask (one new token, full attention), a library routine
+with a boolean mask written from the sentence, the identity with the prefill oracle's
+last rows, and closed forms.  CPU only.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import swaa_attn_oracle, swaa_decode_oracle, swaa_decode_oracle_numpy
+from paper_2512_10411_amd.inputs import bf16_bits_to_f32, make_qkv
+
+
+def f64(bits):
+    return bf16_bits_to_f32(bits).astype(np.float64)
+
+
+def decode_inputs(B, Hq, Hkv, Nq, Nk, D, seed):
+    """q for the Nq newest tokens, cache for all Nk (the full-length q is returned too)."""
+    q_full, k, v = make_qkv(B, Hq, Hkv, Nk, D, seed)
+    return np.ascontiguousarray(q_full[:, :, Nk - Nq:]), k, v, q_full
+
+
+# ---------------------------------------------- D1: one token, full attention = plain softmax attention
+@pytest.mark.parametrize("W", [50, 51, 2**31 - 1])
+def test_one_token_full_attention_is_unmasked_softmax_attention(W):
+    B, Hq, Hkv, Nk, D = 2, 6, 2, 50, 16
+    q, k, v, _ = decode_inputs(B, Hq, Hkv, 1, Nk, D, seed=61)
+    scale = 0.3
+    o, lse = swaa_decode_oracle(q, k, v, W, 0, scale)
+    G = Hq // Hkv
+    kt = torch.from_numpy(f64(k)).repeat_interleave(G, dim=1)
+    vt = torch.from_numpy(f64(v)).repeat_interleave(G, dim=1)
+    s = torch.matmul(torch.from_numpy(f64(q)), kt.transpose(-1, -2)) * scale  # [B,Hq,1,Nk], no mask at all
+    ref = torch.matmul(torch.softmax(s, -1), vt).numpy()
+    assert np.abs(o - ref).max() < 1e-12
+    assert np.abs(lse - torch.logsumexp(s, -1).numpy()).max() < 1e-12
+
+
+# ---------------------------------------------- D2: boolean mask from the sentence, library softmax
+@pytest.mark.parametrize("Nq,Nk", [(1, 23), (3, 23), (8, 23), (23, 23)])
+def test_brute_force_mask_bottom_right_aligned(Nq, Nk):
+    B, Hq, Hkv, D = 1, 4, 2, 8
+    q, k, v, _ = decode_inputs(B, Hq, Hkv, Nq, Nk, D, seed=62 + Nq)
+    G = Hq // Hkv
+    qt = torch.from_numpy(f64(q))
+    kt = torch.from_numpy(f64(k)).repeat_interleave(G, dim=1)
+    vt = torch.from_numpy(f64(v)).repeat_interleave(G, dim=1)
+    for W in range(1, Nk + 2, 3):
+        for S in range(0, Nk + 2, 4):
+            M = np.zeros((Nq, Nk), dtype=bool)
+            for r in range(Nq):
+                pos = Nk - Nq + r  # the r-th newest token's place in the sequence
+                for j in range(Nk):
+                    M[r, j] = j <= pos and ((pos - j) < W or j < S)
+            s = torch.matmul(qt, kt.transpose(-1, -2)) * 0.4
+            s = s.masked_fill(~torch.from_numpy(M), float("-inf"))
+            o, lse = swaa_decode_oracle(q, k, v, W, S, 0.4)
+            assert np.abs(o - torch.matmul(torch.softmax(s, -1), vt).numpy()).max() < 1e-12, (W, S)
+            assert np.abs(lse - torch.logsumexp(s, -1).numpy()).max() < 1e-12, (W, S)
+
+
+# ---------------------------------------------- D3: the same rows of a one-pass (prefill) evaluation
+@pytest.mark.parametrize("W,S", [(1, 0), (9, 3), (40, 0), (100, 5)])
+def test_decode_rows_equal_the_last_rows_of_the_one_pass_result(W, S):
+    B, Hq, Hkv, Nq, Nk, D = 2, 4, 2, 7, 70, 16
+    q, k, v, q_full = decode_inputs(B, Hq, Hkv, Nq, Nk, D, seed=63)
+    o, lse = swaa_decode_oracle(q, k, v, W, S, 0.25)
+    po, pl = swaa_attn_oracle(q_full, k, v, W, S, 0.25)
+    assert np.array_equal(o, po[:, :, Nk - Nq:]) and np.array_equal(lse, pl[:, :, Nk - Nq:])
+    # FA Decode: generated rows of the one-pass FA Decode mask = decode calls with full attention
+    fo, fl = swaa_attn_oracle(q_full, k, v, W, S, 0.25, n_prompt=Nk - Nq)
+    do, dl = swaa_decode_oracle(q, k, v, Nk, 0, 0.25)
+    assert np.array_equal(do, fo[:, :, Nk - Nq:]) and np.array_equal(dl, fl[:, :, Nk - Nq:])
+
+
+# ---------------------------------------------- D4: closed forms
+def test_zero_queries_count_keys_and_window_one_returns_own_value():
+    B, Hq, Hkv, Nq, Nk, D = 1, 2, 1, 5, 40, 8
+    q, k, v, _ = decode_inputs(B, Hq, Hkv, Nq, Nk, D, seed=64)
+    o, lse = swaa_decode_oracle(q, k, v, 1, 0, 0.5)
+    assert np.array_equal(o[0, 0], f64(v)[0, 0, Nk - Nq:])
+    q0 = np.zeros_like(q)
+    for W, S in [(6, 0), (6, 4), (3, 50), (64, 0)]:
+        o, lse = swaa_decode_oracle(q0, k, v, W, S, 1.0)
+        for r in range(Nq):
+            pos = Nk - Nq + r
+            count = min(pos + 1, W) + min(max(pos - W + 1, 0), S)
+            assert abs(lse[0, 1, r] - math.log(count)) < 1e-13
+            vis = [j for j in range(pos + 1) if pos - j < W or j < S]
+            assert np.abs(o[0, 0, r] - f64(v)[0, 0, vis].mean(axis=0)).max() < 1e-13
+
+
+def test_numpy_route_agrees_and_bad_arguments_are_rejected():
+    q, k, v, _ = decode_inputs(2, 6, 3, 4, 45, 16, seed=65)
+    for W, S in [(1, 0), (7, 2), (16, 20), (100, 0)]:
+        o1, l1 = swaa_decode_oracle(q, k, v, W, S, 0.21)
+        o2, l2 = swaa_decode_oracle_numpy(q, k, v, W, S, 0.21)
+        assert np.abs(o1 - o2).max() < 1e-13 and np.abs(l1 - l2).max() < 1e-13
+    with pytest.raises(ValueError):
+        swaa_decode_oracle(q, k, v, 0, 0, 1.0)
+    with pytest.raises(ValueError):
+        swaa_decode_oracle(np.repeat(q, 20, axis=2), k, v, 4, 0, 1.0)  # more query rows than cached tokens
