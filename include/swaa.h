@@ -40,7 +40,8 @@ typedef enum swaa_status {
     SWAA_ERR_SHAPE = -2,       /* a size, the window, the sink count, the prompt length or the scale is out of range */
     SWAA_ERR_UNSUPPORTED = -3, /* head dimension without a kernel instantiation */
     SWAA_ERR_ALIGN = -4,       /* a pointer is not 16-byte aligned */
-    SWAA_ERR_LAUNCH = -5       /* the HIP runtime refused the launch */
+    SWAA_ERR_LAUNCH = -5,      /* the HIP runtime refused the launch */
+    SWAA_ERR_WORKSPACE = -6    /* the workspace is NULL, not 16-byte aligned or too small */
 } swaa_status;
 
 /*
@@ -90,7 +91,7 @@ int swaa_attn_fwd_fa_decode(const void *q, const void *k, const void *v, void *o
                             int n_prompt, float scale, void *stream);
 
 /*
- * Number of visible (query, key) pairs per head under the mask above, i.e.
+ * Number of visible (query, key) pairs per head under the mask of swaa_attn_fwd, i.e.
  * sum over i in [0, N) of |Vis(i)|; the benchmark counts 4*D floating-point
  * operations per pair (paper App. A: the cost of sliding window attention is
  * O(N * W)).  Host-only arithmetic; returns -1 on an invalid argument.
@@ -99,6 +100,43 @@ long long swaa_visible_pairs(long long N, long long window, long long n_sink);
 
 /* The same count under the FA Decode mask of swaa_attn_fwd_fa_decode. */
 long long swaa_visible_pairs_fa_decode(long long N, long long window, long long n_sink, long long n_prompt);
+
+/*
+ * Decode-shape attention (paper Sec. 3.1.1: during auto-regressive generation
+ * each new token attends to the cached keys and values of all previous tokens
+ * -- FA Decode, window >= Nk -- or, when decoding stays on sliding-window
+ * attention, to its local window and the first n_sink tokens of Sec. 3.2.1).
+ * The Nq query rows are the newest tokens of a sequence of Nk tokens whose keys
+ * and values, their own included, are in the cache: row r sits at position
+ * pos = Nk - Nq + r and
+ *
+ *     Vis(r) = { j : 0 <= j <= pos  and ( j > pos - window  or  j < n_sink ) }
+ *
+ * with s_j, lse and out as in swaa_attn_fwd.
+ *
+ *   q    device, bf16 [B, Hq,  Nq, D], contiguous, 16-byte aligned, read only
+ *   k,v  device, bf16 [B, Hkv, Nk, D], contiguous, 16-byte aligned, read only
+ *   out  device, bf16 [B, Hq,  Nq, D], written; lse device, fp32 [B, Hq, Nq], written
+ *   1 <= Nq <= Nk; D = 128; window, n_sink, scale, stream as in swaa_attn_fwd
+ *   workspace  device scratch memory owned by the caller, 16-byte aligned, at
+ *        least swaa_attn_decode_workspace_bytes(same shape arguments) bytes;
+ *        holds the partial results of the key splits between the call's two
+ *        kernels; contents before and after the call are meaningless, and calls
+ *        that may overlap on the device need separate workspaces
+ *
+ * The library allocates nothing.  Returns SWAA_OK or a negative swaa_status;
+ * SWAA_ERR_WORKSPACE if the workspace is NULL, misaligned or too small.
+ */
+int swaa_attn_decode(const void *q, const void *k, const void *v, void *out, float *lse,
+                     int B, int Hq, int Hkv, int Nq, int Nk, int D, int window, int n_sink,
+                     float scale, void *workspace, long long workspace_bytes, void *stream);
+
+/*
+ * Bytes of workspace swaa_attn_decode needs for these shape arguments (a few
+ * KiB per key split; host-only arithmetic), or a negative swaa_status if the
+ * arguments are invalid.
+ */
+long long swaa_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Nq, int Nk, int D, int window, int n_sink);
 
 /* Static description of a status code; never NULL, never freed. */
 const char *swaa_status_string(int status);

@@ -20,10 +20,11 @@ SWAA_ERR_SHAPE = -2
 SWAA_ERR_UNSUPPORTED = -3
 SWAA_ERR_ALIGN = -4
 SWAA_ERR_LAUNCH = -5
+SWAA_ERR_WORKSPACE = -6
 
 # every symbol include/swaa.h declares
 EXPORTS = ("swaa_attn_fwd", "swaa_attn_fwd_fa_decode", "swaa_visible_pairs", "swaa_visible_pairs_fa_decode",
-           "swaa_status_string", "swaa_version")
+           "swaa_attn_decode", "swaa_attn_decode_workspace_bytes", "swaa_status_string", "swaa_version")
 
 _lib = None
 
@@ -57,6 +58,13 @@ def load_library() -> ctypes.CDLL:
     lib.swaa_visible_pairs.argtypes = [ctypes.c_longlong] * 3
     lib.swaa_visible_pairs_fa_decode.restype = ctypes.c_longlong
     lib.swaa_visible_pairs_fa_decode.argtypes = [ctypes.c_longlong] * 4
+    lib.swaa_attn_decode.restype = ctypes.c_int
+    lib.swaa_attn_decode.argtypes = [
+        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+        ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+        ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_void_p, ctypes.c_longlong, ctypes.c_void_p]
+    lib.swaa_attn_decode_workspace_bytes.restype = ctypes.c_longlong
+    lib.swaa_attn_decode_workspace_bytes.argtypes = [ctypes.c_int] * 8
     lib.swaa_status_string.restype = ctypes.c_char_p
     lib.swaa_status_string.argtypes = [ctypes.c_int]
     lib.swaa_version.restype = ctypes.c_int
@@ -156,6 +164,74 @@ def _fwd(q, k, v, window, n_sink, n_prompt, scale, out, lse, stream):
         else:
             rc = swaa_attn_fwd_fa_decode_raw(*ptrs, B, Hq, Hkv, N, D, int(window), int(n_sink), n_prompt,
                                              float(scale), sptr)
+    if rc != SWAA_OK:
+        raise SwaaError(rc, swaa_status_string(rc))
+    return out, lse
+
+
+def swaa_attn_decode_workspace_bytes(B, Hq, Hkv, Nq, Nk, D, window, n_sink) -> int:
+    """Bytes of device scratch swaa_attn_decode needs for this shape."""
+    r = int(load_library().swaa_attn_decode_workspace_bytes(
+        int(B), int(Hq), int(Hkv), int(Nq), int(Nk), int(D), int(window), int(n_sink)))
+    if r < 0:
+        raise SwaaError(r, swaa_status_string(r))
+    return r
+
+
+def swaa_attn_decode_raw(q_ptr, k_ptr, v_ptr, out_ptr, lse_ptr, B, Hq, Hkv, Nq, Nk, D,
+                         window, n_sink, scale, ws_ptr, ws_bytes, stream_ptr) -> int:
+    """The C call itself, on raw addresses; returns the status code."""
+    return int(load_library().swaa_attn_decode(
+        q_ptr, k_ptr, v_ptr, out_ptr, lse_ptr, B, Hq, Hkv, Nq, Nk, D, window, n_sink, scale,
+        ws_ptr, ws_bytes, stream_ptr))
+
+
+def swaa_attn_decode(q, k, v, window: int, n_sink: int, scale: float | None = None,
+                     out=None, lse=None, workspace=None, stream=None):
+    """Attention of the Nq newest tokens over a KV cache of Nk tokens, on the GPU.
+
+    q: bf16 [B, Hq, Nq, D]; k, v: bf16 [B, Hkv, Nk, D] (the cache, the new tokens'
+    own rows included); window >= Nk is full attention (FA Decode).  workspace: a
+    uint8 tensor of at least swaa_attn_decode_workspace_bytes(...) bytes (allocated
+    here with torch when None).  Returns (out bf16 [B, Hq, Nq, D], lse fp32 [B, Hq, Nq]).
+    """
+    import torch
+
+    for name, t in (("q", q), ("k", k), ("v", v)):
+        if t.dtype != torch.bfloat16:
+            raise TypeError(f"{name} must be bfloat16")
+        if not t.is_cuda:
+            raise ValueError(f"{name} must live on the GPU")
+        if not t.is_contiguous() or t.dim() != 4:
+            raise ValueError(f"{name} must be a contiguous [B, H, N, D] tensor")
+    B, Hq, Nq, D = q.shape
+    if k.shape != v.shape or k.shape[0] != B or k.shape[3] != D:
+        raise ValueError("k and v must be [B, Hkv, Nk, D] with q's B and D")
+    if k.device != q.device or v.device != q.device:
+        raise ValueError("q, k, v must be on the same device")
+    Hkv, Nk = k.shape[1], k.shape[2]
+    if scale is None:
+        scale = 1.0 / math.sqrt(D)
+    need = swaa_attn_decode_workspace_bytes(B, Hq, Hkv, Nq, Nk, D, window, n_sink)
+    with torch.cuda.device(q.device):
+        if out is None:
+            out = torch.empty_like(q)
+        if lse is None:
+            lse = torch.empty((B, Hq, Nq), dtype=torch.float32, device=q.device)
+        if workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        if out.shape != q.shape or out.dtype != torch.bfloat16 or not out.is_contiguous():
+            raise ValueError("out must be a contiguous bf16 tensor shaped like q")
+        if lse.shape != (B, Hq, Nq) or lse.dtype != torch.float32 or not lse.is_contiguous():
+            raise ValueError("lse must be a contiguous fp32 [B, Hq, Nq] tensor")
+        if workspace.dtype != torch.uint8 or not workspace.is_cuda or not workspace.is_contiguous():
+            raise ValueError("workspace must be a contiguous uint8 tensor on the GPU")
+        if stream is None:
+            stream = torch.cuda.current_stream(q.device)
+        sptr = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+        rc = swaa_attn_decode_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                                  B, Hq, Hkv, Nq, Nk, D, int(window), int(n_sink), float(scale),
+                                  workspace.data_ptr(), workspace.numel(), sptr)
     if rc != SWAA_OK:
         raise SwaaError(rc, swaa_status_string(rc))
     return out, lse

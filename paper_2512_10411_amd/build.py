@@ -11,7 +11,8 @@ import subprocess
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
-SOURCES = [os.path.join(CSRC, f) for f in ("swaa_api.hip", "swaa_fwd_simple.hip", "swaa_fwd_pipelined.hip")]
+SOURCES = [os.path.join(CSRC, f) for f in ("swaa_api.hip", "swaa_fwd_simple.hip", "swaa_fwd_pipelined.hip",
+                                            "swaa_decode.hip")]
 LIB = os.path.join(PKG, "libswaa.so")
 
 HIPCC_FLAGS = [

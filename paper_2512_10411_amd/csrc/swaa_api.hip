@@ -7,6 +7,7 @@
 
 #include "swaa.h"
 #include "swaa_common.h"
+#include "swaa_decode.h"
 
 using swaa::FwdParams;
 using swaa::kXcds;
@@ -63,11 +64,12 @@ const char *swaa_status_string(int status) {
         case SWAA_ERR_UNSUPPORTED: return "unsupported head dimension (64 and 128 are built)";
         case SWAA_ERR_ALIGN: return "pointer not 16-byte aligned";
         case SWAA_ERR_LAUNCH: return "HIP launch failed";
+        case SWAA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         default: return "unknown status";
     }
 }
 
-int swaa_version(void) { return 110; }
+int swaa_version(void) { return 120; }
 
 int swaa_attn_fwd_fa_decode(const void *q, const void *k, const void *v, void *out, float *lse,
                             int B, int Hq, int Hkv, int N, int D, int window, int n_sink,
@@ -117,6 +119,59 @@ int swaa_attn_fwd(const void *q, const void *k, const void *v, void *out, float 
                   float scale, void *stream) {
     // every row is a prompt token
     return swaa_attn_fwd_fa_decode(q, k, v, out, lse, B, Hq, Hkv, N, D, window, n_sink, N, scale, stream);
+}
+
+namespace {
+
+// Shape checks shared by the two decode entry points; fills the shape fields and the plan.
+int decode_plan(swaa::DecodeParams &p, int B, int Hq, int Hkv, int Nq, int Nk, int D, int window, int n_sink) {
+    if (B < 1 || Hq < 1 || Hkv < 1 || Nq < 1 || Nk < 1 || D < 1) return SWAA_ERR_SHAPE;
+    if (Hq % Hkv != 0 || Nq > Nk) return SWAA_ERR_SHAPE;
+    if (window < 1 || n_sink < 0) return SWAA_ERR_SHAPE;
+    if (D != 128) return SWAA_ERR_UNSUPPORTED;
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.G = Hq / Hkv;
+    p.Nq = Nq; p.Nk = Nk;
+    p.W = window < Nk ? window : Nk;
+    p.S = n_sink < Nk ? n_sink : Nk;
+    if ((long long)p.G * Nq > 0x7fffffffLL / 256) return SWAA_ERR_SHAPE;
+    swaa::plan_decode(p);
+    if ((p.items + kXcds - 1) / kXcds * kXcds > 0x7fffffffLL || (long long)B * Hq * Nq > 0x7fffffffLL)
+        return SWAA_ERR_SHAPE;
+    return SWAA_OK;
+}
+
+}  // namespace
+
+long long swaa_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Nq, int Nk, int D, int window, int n_sink) {
+    swaa::DecodeParams p{};
+    const int rc = decode_plan(p, B, Hq, Hkv, Nq, Nk, D, window, n_sink);
+    if (rc != SWAA_OK) return rc;
+    return swaa::decode_workspace_floats(p) * (long long)sizeof(float);
+}
+
+int swaa_attn_decode(const void *q, const void *k, const void *v, void *out, float *lse,
+                     int B, int Hq, int Hkv, int Nq, int Nk, int D, int window, int n_sink,
+                     float scale, void *workspace, long long workspace_bytes, void *stream) {
+    if (!q || !k || !v || !out || !lse) return SWAA_ERR_NULL;
+    swaa::DecodeParams p{};
+    const int rc = decode_plan(p, B, Hq, Hkv, Nq, Nk, D, window, n_sink);
+    if (rc != SWAA_OK) return rc;
+    if (!positive_finite(scale)) return SWAA_ERR_SHAPE;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(lse))
+        return SWAA_ERR_ALIGN;
+    const long long need = swaa::decode_workspace_floats(p) * (long long)sizeof(float);
+    if (!workspace || misaligned(workspace) || workspace_bytes < need) return SWAA_ERR_WORKSPACE;
+
+    p.q = static_cast<const __bf16 *>(q);
+    p.k = static_cast<const __bf16 *>(k);
+    p.v = static_cast<const __bf16 *>(v);
+    p.out = static_cast<__bf16 *>(out);
+    p.lse = lse;
+    p.ws_o = static_cast<float *>(workspace);
+    p.ws_ml = p.ws_o + p.items * (long long)p.col_stride * 128;
+    p.scale_log2 = scale * 1.44269504088896340736f;
+    const hipError_t err = swaa::launch_decode(p, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? SWAA_OK : SWAA_ERR_LAUNCH;
 }
 
 }  // extern "C"

@@ -1,0 +1,292 @@
+// Decode-shape attention, head dimension 128, gfx950: the Nq newest tokens of a
+// sequence attend to a cache of Nk keys and values (paper Sec. 3.1.1: all of
+// them under FA Decode; their window plus the sink tokens of Sec. 3.2.1 when
+// decoding stays on sliding-window attention).
+//
+// With a handful of query rows the cache is read once and nothing is reused:
+// the bound is HBM bandwidth, and what matters is the number of bytes in flight.
+//
+//   * The G query heads x Nq rows of one (batch, KV head) pair are the 32
+//     columns of an MFMA tile (more rows: more column tiles), so one pass over
+//     K and V serves the whole GQA group.  Padding columns cost matrix-core
+//     time only, of which there is plenty.
+//   * The visited keys are cut into splits; a workgroup is ONE wave that owns a
+//     three-stage ring of 32-key half tiles (K 8 KiB + V 8 KiB per stage) in
+//     LDS, filled by global_load_lds_dwordx4 with whole 256-byte rows per 16
+//     lanes.  No barriers: a wave waits on its own copies only.  48 KiB of LDS
+//     per workgroup lets three of them share a CU: 96 KiB of copies in flight
+//     per CU, 24 MiB over the chip.
+//   * Per half: S^T = K Q^T (8 MFMAs), max-based softmax (mask only on halves
+//     that are not fully visible), O^T += V^T P^T (8 MFMAs, V^T through
+//     transposing LDS reads), then the copy of the half three ahead.  The query
+//     rows arrive through the ring's last stage before the first half needs it.
+//   * Each workgroup leaves (O unnormalised, reference, row sum) for its valid
+//     columns in the workspace; swaa_decode_merge_kernel combines the splits.
+//
+// The split kernel declares no static LDS: its dynamic LDS starts at address 0
+// and all its LDS accesses use plain byte addresses.
+#include <atomic>
+
+#include "swaa_decode.h"
+#include "swaa_tile_d128.h"
+
+namespace swaa {
+namespace {
+
+constexpr int kDStages = 3;
+constexpr int kDStageBytes = 2 * kHalfBytes;          // K half, then V half
+constexpr int kDSmemBytes = kDStages * kDStageBytes;  // 48 KiB
+constexpr int kCopiesPerHalf = 16;                    // wave instructions per stage: 8 for K, 8 for V
+constexpr int kMergeThreads = 512;
+
+__global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParams p) {
+    // XCD x takes the x-th contiguous chunk of the item list (column tiles of one
+    // split, which read the same keys, then run behind the same L2)
+    const long long chunk = (p.items + kXcds - 1) / kXcds;
+    const long long slot = blockIdx.x / kXcds;
+    const long long item = (long long)(blockIdx.x % kXcds) * chunk + slot;
+    if (slot >= chunk || item >= p.items) return;
+    const int ct = (int)(item % p.n_coltiles);
+    const int split = (int)((item / p.n_coltiles) % p.n_splits);
+    const int pair = (int)(item / ((long long)p.n_coltiles * p.n_splits));
+    const int b = pair / p.Hkv, kvh = pair % p.Hkv;
+
+    const int lane = threadIdx.x;
+    const int l32 = lane & 31;
+    const int hf = lane >> 5;
+    const int Nk = p.Nk, W = p.W, S = p.S;
+
+    // this lane's query column: row c of the pair's G x Nq block (clamped: padding
+    // columns repeat the last row and are never stored)
+    const int c = ct * 32 + l32;
+    const bool col_valid = c < p.cols;
+    const int cc = min(c, p.cols - 1);
+    const int qpos = Nk - p.Nq + (cc % p.Nq);  // its position in the sequence
+    const int pos_min = Nk - p.Nq, pos_max = Nk - 1;
+
+    const int h_begin = split * p.halves_per_split;
+    const int n_mine = min(p.n_halves - h_begin, p.halves_per_split);  // >= 1 by construction of the plan
+    auto first_key = [&](int t) {
+        const int h = h_begin + t;
+        return 32 * (h < p.n_sink_halves ? h : h - p.n_sink_halves + p.band_half0);
+    };
+
+    const size_t kv_base = ((size_t)b * p.Hkv + kvh) * (size_t)Nk * kD;
+    const char *kg = reinterpret_cast<const char *>(p.k + kv_base);
+    const char *vg = reinterpret_cast<const char *>(p.v + kv_base);
+
+    // ---- HBM -> LDS copies of one half: instruction i moves rows 4i .. 4i+3, 16 lanes
+    // per row; the XOR swizzle of the operand reads is applied on the global side ----
+    const int lrow = lane >> 4, lchk = lane & 15;
+    auto issue_half = [&](int t, int stage) {
+        const int k0 = first_key(t);
+        const char *kb = kg + (size_t)k0 * kRowBytes;  // uniform
+        const char *vb = vg + (size_t)k0 * kRowBytes;
+        const uint32_t lds = (uint32_t)(stage * kDStageBytes);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = min(4 * i + lrow, Nk - 1 - k0);  // rows past the end repeat the last key; masked later
+            const int fk = ((4 * (i & 1) + lrow) << 1) | ((i >> 1) & 1);
+            const uint32_t off = (uint32_t)(row * kRowBytes + ((lchk ^ fk) << 4));
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(kb),
+                         "s"(lds + (uint32_t)(i * 1024))
+                         : "memory");
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = min(4 * i + lrow, Nk - 1 - k0);
+            const uint32_t off = (uint32_t)(row * kRowBytes + ((lchk ^ (lrow << 2)) << 4));
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(vb),
+                         "s"(lds + (uint32_t)(kHalfBytes + i * 1024))
+                         : "memory");
+        }
+    };
+    const LaneAddr la = make_lane_addr(lane, 0);
+
+    // ---- start-up: the 32 query rows go first, into the K area of the last stage (laid out
+    // like a K half, so that the K fragment reader returns B operands of S^T = K Q^T); then
+    // halves 0 and 1.  Copies complete in order: once only those two are outstanding the
+    // query rows are there, get parked in AccVGPRs, and the last stage is free for half 2. ----
+    {
+        const char *qg = reinterpret_cast<const char *>(p.q + ((size_t)b * p.Hq + (size_t)kvh * p.G) * p.Nq * kD);
+        const uint32_t lds = (uint32_t)((kDStages - 1) * kDStageBytes);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int qrow = min(ct * 32 + 4 * i + lrow, p.cols - 1);
+            const int fk = ((4 * (i & 1) + lrow) << 1) | ((i >> 1) & 1);
+            const uint32_t off = (uint32_t)(qrow * kRowBytes + ((lchk ^ fk) << 4));
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(qg),
+                         "s"(lds + (uint32_t)(i * 1024))
+                         : "memory");
+        }
+    }
+    issue_half(0, 0);
+    if (n_mine >= 2) {
+        issue_half(1, 1);
+        asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
+    } else {
+        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    }
+    bf16x8 qf[kKS];
+#pragma unroll
+    for (int ks = 0; ks < kKS; ++ks) qf[ks] = load_k_frag(la, (uint32_t)((kDStages - 1) * kDStageBytes), ks);
+    // (the idle cycles keep the copies two wait states away from the first MFMA that reads them)
+    asm volatile("s_nop 1"
+                 : "+a"(qf[0]), "+a"(qf[1]), "+a"(qf[2]), "+a"(qf[3]), "+a"(qf[4]), "+a"(qf[5]), "+a"(qf[6]), "+a"(qf[7]));
+    if (n_mine >= 3) issue_half(2, 2);
+
+    f32x16 oacc[kDB];
+#pragma unroll
+    for (int db = 0; db < kDB; ++db)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[db][e] = 0.f;
+    pin_acc(oacc);
+
+    const float c2 = p.scale_log2;
+    RowState rs;
+    rs.mc = -INFINITY;
+    rs.l = 0.f;
+    rs.watch = 0.f;
+
+    int stage = 0;
+    for (int t = 0; t < n_mine; ++t) {
+        // half t has landed when at most the copies of the halves issued after it are outstanding
+        const int later = min(n_mine - 1 - t, kDStages - 1);
+        if (later >= 2)
+            asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
+        else if (later == 1)
+            asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        static_assert(kDStages == 3 && kCopiesPerHalf == 16, "wait counts above");
+
+        const uint32_t so = (uint32_t)(stage * kDStageBytes);
+        const int k0h = first_key(t);
+        // no mask when every key of the half is visible to every column: at or below the
+        // oldest row's diagonal, and inside the newest row's window or all sinks
+        const bool masked = !((k0h + 31 <= pos_min) && ((k0h > pos_max - W) || (k0h + 31 < S)));
+
+        f32x16 s;
+        bf16x8 pf[2];
+        float alpha;
+        qk_half(la, so, qf, s);
+        if (masked)
+            softmax_half<true>(s, k0h, qpos, W, S, hf, c2, rs, pf, alpha);
+        else
+            softmax_half<false>(s, k0h, qpos, W, S, hf, c2, rs, pf, alpha);
+        rescale(oacc, alpha);
+        pv_half<true>(la, so + kHalfBytes, pf, oacc);
+
+        // every LDS read of this stage has returned (the MFMAs above consumed them): refill it
+        if (t + kDStages < n_mine) issue_half(t + kDStages, stage);
+        stage = (stage + 1 == kDStages) ? 0 : stage + 1;
+    }
+
+    // ---- partial result of the valid columns: O^T accumulators (row d, column l32), reference, sum ----
+    if (col_valid) {
+        float *wo = p.ws_o + ((size_t)item * p.col_stride + l32) * kD;
+#pragma unroll
+        for (int db = 0; db < kDB; ++db)
+#pragma unroll
+            for (int e4 = 0; e4 < 4; ++e4) {
+                float4 o4;
+                o4.x = oacc[db][4 * e4 + 0];
+                o4.y = oacc[db][4 * e4 + 1];
+                o4.z = oacc[db][4 * e4 + 2];
+                o4.w = oacc[db][4 * e4 + 3];
+                *reinterpret_cast<float4 *>(wo + 32 * db + 8 * e4 + 4 * hf) = o4;
+            }
+        if (hf == 0) {
+            p.ws_ml[(size_t)item * 64 + l32] = rs.mc;
+            p.ws_ml[(size_t)item * 64 + 32 + l32] = rs.l;
+        }
+    }
+}
+
+// One workgroup per output row: out = sum_s 2^(mc_s - m) O_s / sum_s 2^(mc_s - m) l_s
+// with m = max_s mc_s; lse = (m + log2 of the denominator) ln 2.
+__global__ __launch_bounds__(kMergeThreads) void swaa_decode_merge_kernel(const DecodeParams p) {
+    __shared__ float red[kMergeThreads];
+    __shared__ float lsum[kMergeThreads / kD];
+    const int tid = threadIdx.x;
+    const int row = blockIdx.x;  // (b, hq, r)
+    const int r = row % p.Nq;
+    const int hq = (row / p.Nq) % p.Hq;
+    const int b = row / (p.Nq * p.Hq);
+    const int kvh = hq / p.G;
+    const int c = (hq % p.G) * p.Nq + r;
+    const int ct = c / 32, col = c % 32;
+    const long long pair = (long long)b * p.Hkv + kvh;
+    auto item_of = [&](int s) { return (pair * p.n_splits + s) * p.n_coltiles + ct; };
+
+    float m = -INFINITY;
+    for (int s = tid; s < p.n_splits; s += kMergeThreads) m = fmaxf(m, p.ws_ml[item_of(s) * 64 + col]);
+    red[tid] = m;
+    __syncthreads();
+    for (int w = kMergeThreads / 2; w > 0; w >>= 1) {
+        if (tid < w) red[tid] = fmaxf(red[tid], red[tid + w]);
+        __syncthreads();
+    }
+    m = red[0];  // finite: every row sees at least its own key
+    __syncthreads();
+
+    const int d = tid % kD, g = tid / kD;
+    float acc = 0.f, l = 0.f;
+    for (int s = g; s < p.n_splits; s += kMergeThreads / kD) {
+        const long long it = item_of(s);
+        const float w = __builtin_amdgcn_exp2f(p.ws_ml[it * 64 + col] - m);  // 0 for a split that saw no visible key
+        l += w * p.ws_ml[it * 64 + 32 + col];
+        acc += w * p.ws_o[(it * p.col_stride + col) * kD + d];
+    }
+    red[tid] = acc;
+    if (d == 0) lsum[g] = l;
+    __syncthreads();
+    if (g == 0) {
+        float o = 0.f, lt = 0.f;
+#pragma unroll
+        for (int gg = 0; gg < kMergeThreads / kD; ++gg) {
+            o += red[gg * kD + d];
+            lt += lsum[gg];
+        }
+        p.out[(size_t)row * kD + d] = (__bf16)(o / lt);
+        if (d == 0) p.lse[row] = (m + __builtin_amdgcn_logf(lt)) * 0.69314718055994530942f;
+    }
+}
+
+}  // namespace
+
+void plan_decode(DecodeParams &p) {
+    p.cols = p.G * p.Nq;
+    p.n_coltiles = (p.cols + 31) / 32;
+    p.col_stride = p.cols < 32 ? p.cols : 32;
+    const int band_lo = (p.Nk - p.Nq) - p.W + 1 > 0 ? (p.Nk - p.Nq) - p.W + 1 : 0;  // first key of the oldest row's window
+    p.band_half0 = band_lo / 32;
+    const int sink_keys = p.S < band_lo ? p.S : band_lo;
+    const int sink_halves = (sink_keys + 31) / 32;
+    p.n_sink_halves = sink_halves < p.band_half0 ? sink_halves : p.band_half0;
+    p.n_halves = p.n_sink_halves + ((p.Nk - 1) / 32 - p.band_half0 + 1);
+    // about four rounds of three workgroups per CU, but no split shorter than four halves
+    const long long groups = (long long)p.B * p.Hkv * p.n_coltiles;
+    const long long target_items = 256LL * 3 * 4;
+    long long per_group = target_items / groups;
+    if (per_group < 1) per_group = 1;
+    long long hps = (p.n_halves + per_group - 1) / per_group;
+    if (hps < 4) hps = 4;
+    p.halves_per_split = (int)hps;
+    p.n_splits = (int)((p.n_halves + hps - 1) / hps);
+    p.items = groups * p.n_splits;
+}
+
+long long decode_workspace_floats(const DecodeParams &p) { return p.items * ((long long)p.col_stride * kD + 64); }
+
+hipError_t launch_decode(const DecodeParams &p, hipStream_t stream) {
+    const long long chunk = (p.items + kXcds - 1) / kXcds;
+    hipLaunchKernelGGL(swaa_decode_split_kernel, dim3((unsigned)(chunk * kXcds)), dim3(64), kDSmemBytes, stream, p);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(swaa_decode_merge_kernel, dim3((unsigned)((long long)p.B * p.Hq * p.Nq)), dim3(kMergeThreads), 0,
+                       stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace swaa

@@ -119,7 +119,7 @@ __device__ __forceinline__ void softmax_chunk(int c, const f32x16 &s, float c2, 
 // of the half whose first key is k0h; otherwise from zero.
 __device__ __forceinline__ void qk_chain_start(f32x16 &s, const bf16x8 kfrag, const bf16x8 q_acc, bool masked, int k0h,
                                                int qpos, int W, int S, int hf) {
-    if (masked) {
+    if (__builtin_expect(masked, 0)) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             const int key = k0h + 8 * (e / 4) + 4 * hf + (e % 4);
@@ -185,7 +185,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     const int N = p.N, S = p.S;
 
     const int tid = threadIdx.x;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform, and known to the compiler as such
     const int lane = tid & 63;
     const int l32 = lane & 31;
     const int hf = lane >> 5;
@@ -219,7 +219,6 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     // chunk c' ^ f(row) of that row, with f(row) = ((row & 7) << 1) | ((row >> 3) & 1)
     // for K (16 consecutive rows read the same logical chunk) and (row & 3) << 2
     // for V (4 consecutive rows read the same 64 bytes).
-    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int lrow = lane >> 4;  // row within the 4-row group
     const int lchk = lane & 15;  // LDS chunk within the row
     // byte offset of this lane's 16 bytes inside a tile, first instruction; row = 8*wave + 4*i + lrow
@@ -238,7 +237,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
                 const int row = 8 * wave + 4 * i + lrow;
                 off -= (uint32_t)(max(k0 + row - (N - 1), 0) * (kD * 2));
             }
-            const uint32_t l = (uint32_t)(ring + buf * kTileBytes + (2 * wave_u + i) * 1024);
+            const uint32_t l = (uint32_t)(ring + buf * kTileBytes + (2 * wave + i) * 1024);
             // LDS address = M0 + 16 * lane; global address = base + off.  Issued as
             // assembly on purpose: the compiler would otherwise make every later
             // LDS read wait for it.
@@ -258,7 +257,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     }
 
     // ---- this wave's 32 Q rows: HBM -> its staging area, laid out like a K half tile ----
-    const uint32_t stage = (uint32_t)(kStage + wave_u * kStageBytes);
+    const uint32_t stage = (uint32_t)(kStage + wave * kStageBytes);
     {
         const char *qg = reinterpret_cast<const char *>(p.q + q_base);
 #pragma unroll
@@ -331,8 +330,8 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
         const int k0 = tile_of(0) * kBk;
         qk_chain_start(s_a, load_k_frag(la, 0, 0), qf[0], true, k0, qpos, W, S, hf);
 #pragma unroll
-        for (int ks = 1; ks < kKS; ++ks) mfma_s(s_a, load_k_frag(la, 0, ks), qf[ks]);
-        settle_s(s_a);
+        for (int ks = 1; ks < kKS - 1; ++ks) mfma_s(s_a, load_k_frag(la, 0, ks), qf[ks]);
+        mfma_s_settled(s_a, load_k_frag(la, 0, kKS - 1), qf[kKS - 1]);
         float mx = s_a[0];
 #pragma unroll
         for (int e = 1; e < 16; ++e) mx = fmaxf(mx, s_a[e]);
@@ -401,7 +400,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
         if (++j >= J) break;
     }
     // pipeline drain: P V of the last half (V(J-1) sits in buffer (J-1) % kStages)
-    pv_half(la, (uint32_t)(((J - 1) % kStages) * kTileBytes + kHalfBytes), p_b, oacc);
+    pv_half<true>(la, (uint32_t)(((J - 1) % kStages) * kTileBytes + kHalfBytes), p_b, oacc);
 
     // ---- scores outgrew the reference somewhere in this workgroup (inputs with
     // score jumps of tens of nats): recompute its rows with the max-based routine,
@@ -438,14 +437,14 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
                 qk_half(la, (uint32_t)(hh * kHalfBytes), qf, s_a);
                 softmax_half<true>(s_a, tile_of(j) * kBk + 32 * hh, qpos, W, S, hf, c2, rs, p_a, alpha);
                 rescale(oacc, alpha);
-                pv_half(la, (uint32_t)(hh * kHalfBytes), p_a, oacc);
+                pv_half<true>(la, (uint32_t)(hh * kHalfBytes), p_a, oacc);
             }
         }
     }
 
     // ---- epilogue: O / l -> bf16 through the wave's staging area, so that the stores
     // to HBM are whole rows; lse = (mc + log2 l) * ln 2 ----------------------------------
-    settle_acc(oacc);
+    // (the accumulators are settled: the last P V contraction above waited for its result)
     {
         const float inv_l = 1.f / rs.l;  // rows past the end: never stored
         const int fr = ((l32 & 7) << 1) | ((l32 >> 3) & 1);

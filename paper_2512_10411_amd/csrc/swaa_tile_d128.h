@@ -25,8 +25,11 @@ constexpr float kRefSlack = 8.f;  // log2 units a row maximum may exceed its ref
 //   (1) a vector instruction that writes an MFMA operand must be at least two
 //       instructions ahead of the MFMA (hardware needs two wait states);
 //   (2) a vector instruction that reads an MFMA result must wait for the MFMA
-//       to finish (settle_* below).
-// tests/test_asm_hazards.py checks (1) on the generated assembly.
+//       to finish.  The compiler may copy a result register right after the
+//       statement that produced it, so the idle cycles belong into the same
+//       asm statement as the last MFMA of a chain (*_settled below); settle_*
+//       alone is only safe where other MFMAs lie between producer and reader.
+// tests/test_asm_hazards.py checks both on the generated assembly.
 __device__ __forceinline__ void mfma_acc(f32x16 &acc, const bf16x8 a, const bf16x8 b) {
     asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
@@ -37,9 +40,12 @@ __device__ __forceinline__ void mfma_s(f32x16 &s, const bf16x8 kfrag, const bf16
 __device__ __forceinline__ void mfma_s_first(f32x16 &s, const bf16x8 kfrag, const bf16x8 q_acc) {
     asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(kfrag), "a"(q_acc));
 }
-__device__ __forceinline__ void settle_s(f32x16 &s) { asm volatile("s_nop 15\n\ts_nop 7" : "+v"(s)); }
-__device__ __forceinline__ void settle_acc(f32x16 (&o)[kDB]) {
-    asm volatile("s_nop 15\n\ts_nop 7" : "+a"(o[0]), "+a"(o[1]), "+a"(o[2]), "+a"(o[3]));
+// Last MFMA of a chain whose result the vector ALU reads next.
+__device__ __forceinline__ void mfma_s_settled(f32x16 &s, const bf16x8 kfrag, const bf16x8 q_acc) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\ts_nop 15\n\ts_nop 7" : "+v"(s) : "v"(kfrag), "a"(q_acc));
+}
+__device__ __forceinline__ void mfma_acc_settled(f32x16 &acc, const bf16x8 a, const bf16x8 b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\ts_nop 15\n\ts_nop 7" : "+a"(acc) : "v"(a), "v"(b));
 }
 // Makes the compiler hold `o` in AccVGPRs at this point (placed after every
 // plain C++ write to the accumulators so that the value carried around the key
@@ -77,26 +83,34 @@ __device__ __forceinline__ bf16x8 load_v_frag(const LaneAddr &la, uint32_t boff,
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
-// S^T (32 keys x 32 queries) = K_half Q^T
+// S^T (32 keys x 32 queries) = K_half Q^T; the result is ready for the vector ALU on return
 __device__ __forceinline__ void qk_half(const LaneAddr &la, uint32_t kboff, const bf16x8 (&qf)[kKS], f32x16 &s) {
 #pragma unroll
     for (int ks = 0; ks < kKS; ++ks) {
         const bf16x8 a = load_k_frag(la, kboff, ks);
         if (ks == 0)
             mfma_s_first(s, a, qf[ks]);
-        else
+        else if (ks < kKS - 1)
             mfma_s(s, a, qf[ks]);
+        else
+            mfma_s_settled(s, a, qf[ks]);
     }
 }
 
-// O^T (128 x 32 queries) += V_half^T P^T
+// O^T (128 x 32 queries) += V_half^T P^T.  kSettle: the accumulators are ready for
+// the vector ALU on return (all MFMAs complete in order, so waiting out the last
+// one covers the four chains).
+template <bool kSettle>
 __device__ __forceinline__ void pv_half(const LaneAddr &la, uint32_t vboff, const bf16x8 (&pf)[2], f32x16 (&o)[kDB]) {
 #pragma unroll
     for (int st = 0; st < 2; ++st) {
 #pragma unroll
         for (int db = 0; db < kDB; ++db) {
             const bf16x8 a = load_v_frag(la, vboff, st, db);
-            mfma_acc(o[db], a, pf[st]);
+            if (kSettle && st == 1 && db == kDB - 1)
+                mfma_acc_settled(o[db], a, pf[st]);
+            else
+                mfma_acc(o[db], a, pf[st]);
         }
     }
 }
@@ -110,11 +124,11 @@ struct RowState {
 // Max-based softmax of one half tile (edge tiles, first tile, and the rare
 // half whose row sums outgrow the reference): optional mask, reference update
 // with slack, exponentials, row sum, bf16 P^T fragments.  alpha is the factor
-// the O accumulator must be multiplied with (1 when the reference stays).
+// the O accumulator must be multiplied with (1 when the reference stays).  The
+// scores must be settled (qk_half leaves them so).
 template <bool kMask>
 __device__ __forceinline__ void softmax_half(f32x16 &s, int k0h, int qpos, int W, int S, int hf, float c2, RowState &st,
                                              bf16x8 (&pf)[2], float &alpha) {
-    settle_s(s);
     if (kMask) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
@@ -146,9 +160,9 @@ __device__ __forceinline__ void softmax_half(f32x16 &s, int k0h, int qpos, int W
     asm volatile("s_nop 1" : "+v"(pf[0]), "+v"(pf[1]));
 }
 
+// (the accumulators must be settled: pv_half<true>, or other MFMAs since their last update)
 __device__ __forceinline__ void rescale(f32x16 (&o)[kDB], float alpha) {
     if (__any(alpha != 1.f)) {
-        settle_acc(o);
 #pragma unroll
         for (int db = 0; db < kDB; ++db)
 #pragma unroll

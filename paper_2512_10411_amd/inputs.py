@@ -48,6 +48,7 @@ class Workload:
     seed: int
     k_mult: float = 1.0   # k is multiplied by this (exact in bf16 for powers of two)
     n_prompt: int | None = None  # FA Decode runs: rows >= n_prompt are generated tokens
+    n_query: int | None = None   # decode-shape runs: q holds only the n_query newest of the N tokens
 
     @property
     def scale(self) -> float:
@@ -73,18 +74,25 @@ WORKLOADS = {
     "mid_fa_decode": Workload("mid_fa_decode", 1, 32, 8, 16384, 128, 2048, 4, _SEED0 + 2, 1.0, 16384 - 512),
     "long128k_fa_decode": Workload("long128k_fa_decode", 1, 32, 8, 131072, 128, 8192, 4, _SEED0 + 5, 1.0,
                                    131072 - 512),
+    # decode steps of that experiment: one new token per sequence against a 128k-token cache,
+    # with full attention (FA Decode) and on the window (decoding stays on SWA); and a batch of
+    # 16 sequences of 16k tokens
+    "decode128k_full": Workload("decode128k_full", 1, 32, 8, 131072, 128, 131072, 4, _SEED0 + 6, n_query=1),
+    "decode128k_swa": Workload("decode128k_swa", 1, 32, 8, 131072, 128, 8192, 4, _SEED0 + 6, n_query=1),
+    "decode16k_b16": Workload("decode16k_b16", 16, 32, 8, 16384, 128, 16384, 4, _SEED0 + 7, n_query=1),
 }
 
 
-def make_qkv(B, Hq, Hkv, N, D, seed, k_mult=1.0, chunk_rows=1 << 22):
+def make_qkv(B, Hq, Hkv, N, D, seed, k_mult=1.0, chunk_rows=1 << 22, n_query=None):
     """i.i.d. N(0,1) q, k, v rounded to bf16; k scaled by k_mult before rounding.
 
     Generated in row chunks so that the float32 staging buffer stays small even
-    for the 128k-token workloads.
+    for the 128k-token workloads.  n_query: q has only that many rows per head
+    (decode shape), k and v keep N.
     """
     rng = np.random.Generator(np.random.Philox(int(seed)))
 
-    def draw(H, mult):
+    def draw(H, mult, N=N):
         out = np.empty((B * H * N, D), dtype=np.uint16)
         for r0 in range(0, out.shape[0], chunk_rows):
             r1 = min(out.shape[0], r0 + chunk_rows)
@@ -94,7 +102,7 @@ def make_qkv(B, Hq, Hkv, N, D, seed, k_mult=1.0, chunk_rows=1 << 22):
             out[r0:r1] = f32_to_bf16_bits(x)
         return out.reshape(B, H, N, D)
 
-    q = draw(Hq, 1.0)
+    q = draw(Hq, 1.0) if n_query is None else draw(Hq, 1.0, int(n_query))
     k = draw(Hkv, k_mult)
     v = draw(Hkv, 1.0)
     return q, k, v
@@ -102,7 +110,7 @@ def make_qkv(B, Hq, Hkv, N, D, seed, k_mult=1.0, chunk_rows=1 << 22):
 
 def make_workload(w: Workload):
     """q, k, v (uint16 bf16 bits) for a named workload."""
-    return make_qkv(w.B, w.Hq, w.Hkv, w.N, w.D, w.seed, w.k_mult)
+    return make_qkv(w.B, w.Hq, w.Hkv, w.N, w.D, w.seed, w.k_mult, n_query=w.n_query)
 
 
 def sample_rows(N, window, n_sink, count=256, seed=0, tile=64):

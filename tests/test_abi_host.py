@@ -87,3 +87,40 @@ def test_fa_decode_pair_count_and_argument_errors():
     assert f(p, p, None, p, p, 1, 4, 2, 128, 128, 16, 2, 64, 0.1, None) == binding.SWAA_ERR_NULL
     assert f(p, p, p, p, p, 1, 4, 2, 128, 96, 16, 2, 64, 0.1, None) == binding.SWAA_ERR_UNSUPPORTED
     assert f(p, p, p, p + 4, p, 1, 4, 2, 128, 128, 16, 2, 64, 0.1, None) == binding.SWAA_ERR_ALIGN
+
+
+def test_decode_workspace_size_and_argument_errors():
+    ok = dict(B=1, Hq=32, Hkv=8, Nq=1, Nk=131072, D=128, window=131072, n_sink=4)
+
+    def ws(**kw):
+        a = dict(ok, **kw)
+        return binding.load_library().swaa_attn_decode_workspace_bytes(
+            a["B"], a["Hq"], a["Hkv"], a["Nq"], a["Nk"], a["D"], a["window"], a["n_sink"])
+
+    full = ws()
+    assert 0 < full < 64 << 20 and full % 16 == 0
+    assert 0 < ws(window=8192) <= full       # fewer visited keys never need more
+    assert ws(Nk=1, window=1) > 0
+    assert ws(Nq=0) == binding.SWAA_ERR_SHAPE
+    assert ws(Nq=9, Nk=8) == binding.SWAA_ERR_SHAPE
+    assert ws(Hq=30) == binding.SWAA_ERR_SHAPE
+    assert ws(window=0) == binding.SWAA_ERR_SHAPE
+    assert ws(D=64) == binding.SWAA_ERR_UNSUPPORTED
+
+    p = 4096  # fake aligned address; never dereferenced on these paths
+    f = binding.swaa_attn_decode_raw
+
+    def call(q=p, k=p, v=p, o=p, l=p, w=p, wb=None, scale=0.1, **kw):
+        a = dict(ok, **kw)
+        wb = ws(**kw) if wb is None else wb
+        return f(q, k, v, o, l, a["B"], a["Hq"], a["Hkv"], a["Nq"], a["Nk"], a["D"], a["window"], a["n_sink"],
+                 scale, w, wb, None)
+
+    assert call(v=None) == binding.SWAA_ERR_NULL
+    assert call(Nq=0, wb=1 << 30) == binding.SWAA_ERR_SHAPE
+    assert call(scale=float("nan")) == binding.SWAA_ERR_SHAPE
+    assert call(D=256, wb=1 << 30) == binding.SWAA_ERR_UNSUPPORTED
+    assert call(q=p + 8) == binding.SWAA_ERR_ALIGN
+    assert call(w=None) == binding.SWAA_ERR_WORKSPACE
+    assert call(w=p + 4) == binding.SWAA_ERR_WORKSPACE
+    assert call(wb=full - 1) == binding.SWAA_ERR_WORKSPACE

@@ -1,0 +1,116 @@
+"""GPU parity of swaa_attn_decode (the newest tokens against a KV cache; split keys,
+merged by a second kernel) against the fp64 CPU oracle, through the C ABI.  Same
+tolerances as the prefill tests.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import swaa_decode_oracle
+from paper_2512_10411_amd import binding
+from paper_2512_10411_amd.inputs import WORKLOADS, bf16_bits_to_f32, f32_to_bf16_bits, make_qkv, make_workload
+from gpu_util import assert_parity, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def check(B, Hq, Hkv, Nq, Nk, W, S, seed, D=128):
+    scale = 1.0 / math.sqrt(D)
+    tag = f"decode B{B} Hq{Hq} Hkv{Hkv} Nq{Nq} Nk{Nk} W{W} S{S}"
+    print(f"[case] {tag} seed {seed}", flush=True)
+    q, k, v = make_qkv(B, Hq, Hkv, Nk, D, seed, n_query=Nq)
+    out, lse = binding.swaa_attn_decode(to_device(q), to_device(k), to_device(v), W, S, scale)
+    torch.cuda.synchronize()
+    ro, rl = swaa_decode_oracle(q, k, v, W, S, scale)
+    assert_parity(out, lse, ro, rl, tag=tag)
+
+
+@pytest.mark.parametrize("Nk", [1, 31, 32, 33, 100, 129, 700, 3000])
+def test_small_caches_sweep_rows_window_and_sinks(Nk):
+    # one split and many, ragged last half, more query rows than one column tile holds
+    seed = 7000 + Nk
+    for Nq in (1, 2, 5, 8, 17):
+        if Nq > Nk:
+            continue
+        for W, S in ((1, 0), (7, 4), (64, 0), (200, 70), (Nk, 0), (Nk + 9, 3)):
+            check(1, 4, 1, Nq, Nk, W, S, seed)
+
+
+@pytest.mark.parametrize("G", [1, 2, 3, 5, 8])
+def test_gqa_group_sizes_and_batches(G):
+    check(3, 2 * G, 2, 3, 1111, 300, 3, seed=7100 + G)
+    check(2, G, 1, 1, 2050, 2050, 0, seed=7200 + G)
+
+
+def test_score_spike_deep_in_the_cache():
+    # the reference of a split follows its keys; a score tens of nats above the rest must merge correctly
+    B, Hq, Hkv, Nq, Nk, D = 1, 4, 1, 2, 5000, 128
+    q, k, v = make_qkv(B, Hq, Hkv, Nk, D, seed=73, n_query=Nq)
+    qf, kf = bf16_bits_to_f32(q), bf16_bits_to_f32(k)
+    qf[..., 0] = 3.0
+    kf[..., 0] = 0.0
+    kf[:, :, 3333, 0] = 160.0
+    kf[:, :, 4000, 0] = -160.0
+    q, k = f32_to_bf16_bits(qf), f32_to_bf16_bits(kf)
+    scale = 1 / math.sqrt(D)
+    for W, S in ((Nk, 0), (512, 4)):
+        out, lse = binding.swaa_attn_decode(to_device(q), to_device(k), to_device(v), W, S, scale)
+        torch.cuda.synchronize()
+        ro, rl = swaa_decode_oracle(q, k, v, W, S, scale)
+        assert_parity(out, lse, ro, rl, tag=f"decode spike W{W}")
+
+
+def test_caller_workspace_stream_and_errors():
+    B, Hq, Hkv, Nq, Nk, D, W, S = 2, 8, 2, 1, 4000, 128, 4000, 0
+    q, k, v = make_qkv(B, Hq, Hkv, Nk, D, seed=74, n_query=Nq)
+    qd, kd, vd = to_device(q), to_device(k), to_device(v)
+    need = binding.swaa_attn_decode_workspace_bytes(B, Hq, Hkv, Nq, Nk, D, W, S)
+    assert need > 0
+    ws = torch.full((need,), 0xFF, dtype=torch.uint8, device="cuda")  # NaN bit patterns: stale reads would show
+    out = torch.full_like(qd, 7.0)
+    lse = torch.full((B, Hq, Nq), 7.0, dtype=torch.float32, device="cuda")
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    ro, rl = swaa_decode_oracle(q, k, v, W, S, 1 / math.sqrt(D))
+    with torch.cuda.stream(s):
+        for _ in range(2):  # the second call reuses the workspace the first one left
+            o2, l2 = binding.swaa_attn_decode(qd, kd, vd, W, S, out=out, lse=lse, workspace=ws, stream=s)
+    s.synchronize()
+    assert o2.data_ptr() == out.data_ptr() and l2.data_ptr() == lse.data_ptr()
+    assert_parity(out, lse, ro, rl, tag="decode, caller workspace on side stream")
+    with pytest.raises(binding.SwaaError) as e:
+        binding.swaa_attn_decode(qd, kd, vd, W, S, workspace=ws[:need - 16])
+    assert e.value.status == binding.SWAA_ERR_WORKSPACE
+    with pytest.raises(binding.SwaaError):
+        binding.swaa_attn_decode(qd, kd, vd, 0, 0)
+    with pytest.raises(binding.SwaaError):  # more query rows than cached tokens
+        binding.swaa_attn_decode(torch.zeros((B, Hq, 200, D), dtype=torch.bfloat16, device="cuda"),
+                                 kd[:, :, :100].contiguous(), vd[:, :, :100].contiguous(), 8, 0)
+
+
+def test_decode_rows_equal_one_pass_fa_decode_rows():
+    # the two entry points on the same sequence: rows >= n_prompt of the one-pass call against decode calls
+    B, Hq, Hkv, N, D, W, S, P = 1, 8, 2, 3000, 128, 256, 4, 2990
+    q, k, v = make_qkv(B, Hq, Hkv, N, D, seed=75)
+    qd, kd, vd = to_device(q), to_device(k), to_device(v)
+    o1, l1 = binding.swaa_attn_fwd_fa_decode(qd, kd, vd, W, S, P)
+    o2, l2 = binding.swaa_attn_decode(qd[:, :, P:].contiguous(), kd, vd, N, 0)
+    torch.cuda.synchronize()
+    assert (o1[:, :, P:].float() - o2.float()).abs().max().item() <= 2e-2
+    assert (l1[:, :, P:] - l2).abs().max().item() <= 1e-3
+
+
+@pytest.mark.parametrize("name", ["decode128k_full", "decode128k_swa", "decode16k_b16"])
+def test_decode_workloads_full_size(name):
+    # full-size launches exactly as the benchmark times them; every output row is compared
+    w = WORKLOADS[name]
+    print(f"[gen] {name} ...", flush=True)
+    q, k, v = make_workload(w)
+    print(f"[gpu] {name}", flush=True)
+    out, lse = binding.swaa_attn_decode(to_device(q), to_device(k), to_device(v), w.window, w.n_sink, w.scale)
+    torch.cuda.synchronize()
+    print(f"[oracle] {name}", flush=True)
+    ro, rl = swaa_decode_oracle(q, k, v, w.window, w.n_sink, w.scale)
+    assert_parity(out, lse, ro, rl, tag=name)
