@@ -25,12 +25,13 @@ sys.path.insert(0, ROOT)
 
 METRIC = "SWA+sink prefill attention effective TFLOP/s and % bf16 MFMA peak, 1 MI355X"
 BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E
 
 # HBM bytes per launch (read + written) of the attention kernel, measured with two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by a copy kernel of known size;
 # the summaries are profiles/swaa_fwd_pipelined_<workload>.txt.  Used when
 # --traffic-bytes is not given; workloads not measured yet report null.
-MEASURED_TRAFFIC_BYTES = {"mid": 4.105e8, "batched": 1.078e9}
+MEASURED_TRAFFIC_BYTES = {"mid": 4.105e8, "batched": 1.078e9, "decode128k_full": 5.41e8, "decode16k_b16": 1.079e9}
 
 
 def parse():
@@ -52,6 +53,39 @@ def parse():
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE it is the kernel of known traffic that "
                          "the attention kernel's counters are scaled by")
     return ap.parse_args()
+
+
+def decode_counts(w):
+    """(visible pairs per launch, algorithmic HBM bytes per launch) of a decode-shape workload."""
+    Nq, Nk = w.n_query, w.N
+    W, S = min(w.window, Nk), min(w.n_sink, Nk)
+    pairs = 0
+    for r in range(Nq):
+        pos = Nk - Nq + r
+        pairs += min(pos + 1, W) + min(max(pos - W + 1, 0), S)
+    band_lo = max(0, Nk - Nq - W + 1)
+    keys = min(S, band_lo) + (Nk - band_lo)  # keys some query row sees: read once, K and V
+    nbytes = w.B * w.Hkv * keys * 2 * w.D * 2 + w.B * w.Hq * Nq * (2 * w.D * 2 + 4)
+    return pairs * w.B * w.Hq, nbytes
+
+
+def cpu_baseline_decode(w, q, k, v):
+    """Time the oracle as it stands on the whole decode-shape workload (it is small)."""
+    from oracle import oracle_num_threads, swaa_decode_oracle
+    t0 = time.perf_counter()
+    swaa_decode_oracle(q, k, v, w.window, w.n_sink, w.scale)
+    dt = time.perf_counter() - t0
+    pairs, _ = decode_counts(w)
+    return {
+        "value": 4.0 * w.D * pairs / dt / 1e12,
+        "unit": "TFLOP/s",
+        "cores": oracle_num_threads(),
+        "kind": "oracle",
+        "sample": f"the whole workload '{w.name}' once: all {w.B * w.Hq * w.n_query} query rows, {pairs} visible "
+                  f"pairs in {dt:.2f} s; fp64, OpenMP over rows",
+        "seconds": dt,
+        "pairs_per_s": pairs / dt,
+    }
 
 
 def cpu_baseline(w, q, k, v, target_s):
@@ -122,13 +156,20 @@ def main():
 
     qd, kd, vd = dev(q), dev(k), dev(v)
     out = torch.empty_like(qd)
-    lse = torch.empty((w.B, w.Hq, w.N), dtype=torch.float32, device="cuda")
+    lse = torch.empty(qd.shape[:3], dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
 
     n_prompt = w.N if w.n_prompt is None else w.n_prompt
+    decode = w.n_query is not None
+    if decode:
+        ws = torch.empty(binding.swaa_attn_decode_workspace_bytes(w.B, w.Hq, w.Hkv, w.n_query, w.N, w.D, w.window,
+                                                                  w.n_sink), dtype=torch.uint8, device="cuda")
 
     def step():
-        if w.n_prompt is None:
+        if decode:
+            binding.swaa_attn_decode(qd, kd, vd, w.window, w.n_sink, w.scale, out=out, lse=lse, workspace=ws,
+                                     stream=stream)
+        elif w.n_prompt is None:
             binding.swaa_attn_fwd(qd, kd, vd, w.window, w.n_sink, w.scale, out=out, lse=lse, stream=stream)
         else:
             binding.swaa_attn_fwd_fa_decode(qd, kd, vd, w.window, w.n_sink, n_prompt, w.scale, out=out, lse=lse,
@@ -162,10 +203,26 @@ def main():
     kern_avg_ms = ev0.elapsed_time(ev1) / args.steps
     ms_per_step = wall * 1e3 / args.steps
 
-    pairs = binding.swaa_visible_pairs_fa_decode(w.N, w.window, w.n_sink, n_prompt) * w.B * w.Hq
+    if decode:
+        pairs, algo_bytes = decode_counts(w)
+    else:
+        pairs = binding.swaa_visible_pairs_fa_decode(w.N, w.window, w.n_sink, n_prompt) * w.B * w.Hq
     flops = 4.0 * w.D * pairs
     value = flops / (ms_per_step * 1e-3) / 1e12
     achieved = flops / (kern_avg_ms * 1e-3) / 1e12
+    traffic = args.traffic_bytes if args.traffic_bytes is not None else MEASURED_TRAFFIC_BYTES.get(w.name)
+    if decode:
+        # few query rows against a long cache: the keys and values are read once and nothing is
+        # reused, so HBM bandwidth bounds the call (split kernel + merge kernel, timed together)
+        gbs = algo_bytes / (kern_avg_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                    "traffic": traffic, "kernel": "swaa_decode_split_kernel (+ swaa_decode_merge_kernel)",
+                    "kernel_avg_ms": kern_avg_ms, "algorithmic_bytes": algo_bytes}
+    else:
+        roofline = {"bound": "mfma", "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": traffic,
+                    "kernel": "swaa_fwd_pipelined_kernel" if w.D == 128 else "swaa_fwd_kernel<64>",
+                    "kernel_avg_ms": kern_avg_ms}
 
     res = {
         "metric": METRIC,
@@ -180,19 +237,15 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "N": w.N, "D": w.D,
+        "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "N": w.N, "n_query": w.n_query or w.N,
+                   "D": w.D,
                    "window": w.window, "n_sink": w.n_sink, "n_prompt": n_prompt, "seed": w.seed, "k_mult": w.k_mult,
                    "visible_pairs": pairs, "flops_per_step": flops,
                    "pct_bf16_mfma_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS},
-        "roofline": {"bound": "mfma", "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
-                     "traffic": args.traffic_bytes if args.traffic_bytes is not None
-                     else MEASURED_TRAFFIC_BYTES.get(w.name),
-                     "kernel": "swaa_fwd_pipelined_kernel" if w.D == 128 else "swaa_fwd_kernel<64>",
-                     "kernel_avg_ms": kern_avg_ms},
+        "roofline": roofline,
     }
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(w, q, k, v, args.cpu_seconds)
+        res["cpu_baseline"] = cpu_baseline_decode(w, q, k, v) if decode else cpu_baseline(w, q, k, v, args.cpu_seconds)
         res["cpu_baseline"]["gpu_over_cpu"] = value / res["cpu_baseline"]["value"]
     print(json.dumps(res), flush=True)
     return 0

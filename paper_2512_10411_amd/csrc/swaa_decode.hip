@@ -16,10 +16,12 @@
 //     lanes.  No barriers: a wave waits on its own copies only.  48 KiB of LDS
 //     per workgroup lets three of them share a CU: 96 KiB of copies in flight
 //     per CU, 24 MiB over the chip.
-//   * Per half: S^T = K Q^T (8 MFMAs), max-based softmax (mask only on halves
-//     that are not fully visible), O^T += V^T P^T (8 MFMAs, V^T through
-//     transposing LDS reads), then the copy of the half three ahead.  The query
-//     rows arrive through the ring's last stage before the first half needs it.
+//   * Per half: all K and V^T operand fragments go from LDS to registers (V^T
+//     through transposing reads), the copy of the half three ahead is issued into
+//     the stage just emptied, and only then the arithmetic runs: S^T = K Q^T (8
+//     MFMAs), max-based softmax (mask only on halves that are not fully visible),
+//     O^T += V^T P^T (8 MFMAs).  The copies thus never wait for arithmetic.  The
+//     query rows arrive through the ring's last stage before half 2 needs it.
 //   * Each workgroup leaves (O unnormalised, reference, row sum) for its valid
 //     columns in the workspace; swaa_decode_merge_kernel combines the splits.
 //
@@ -37,7 +39,11 @@ constexpr int kDStages = 3;
 constexpr int kDStageBytes = 2 * kHalfBytes;          // K half, then V half
 constexpr int kDSmemBytes = kDStages * kDStageBytes;  // 48 KiB
 constexpr int kCopiesPerHalf = 16;                    // wave instructions per stage: 8 for K, 8 for V
-constexpr int kMergeThreads = 512;
+constexpr int kMergeThreads = 1024;
+#ifndef SWAA_DECODE_ROUNDS
+#define SWAA_DECODE_ROUNDS 1
+#endif
+constexpr int kRounds = SWAA_DECODE_ROUNDS;
 
 __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParams p) {
     // XCD x takes the x-th contiguous chunk of the item list (column tiles of one
@@ -166,19 +172,39 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
         // oldest row's diagonal, and inside the newest row's window or all sinks
         const bool masked = !((k0h + 31 <= pos_min) && ((k0h > pos_max - W) || (k0h + 31 < S)));
 
+        // all operand fragments of the half go to registers first; once they are there the
+        // stage is free and the copy of the half three ahead leaves before any arithmetic
+        bf16x8 kf[kKS], vf[2][kDB];
+#pragma unroll
+        for (int ks = 0; ks < kKS; ++ks) kf[ks] = load_k_frag(la, so, ks);
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+#pragma unroll
+            for (int db = 0; db < kDB; ++db) vf[st][db] = load_v_frag(la, so + kHalfBytes, st, db);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        if (t + kDStages < n_mine) issue_half(t + kDStages, stage);
+
         f32x16 s;
         bf16x8 pf[2];
         float alpha;
-        qk_half(la, so, qf, s);
+        mfma_s_first(s, kf[0], qf[0]);
+#pragma unroll
+        for (int ks = 1; ks < kKS - 1; ++ks) mfma_s(s, kf[ks], qf[ks]);
+        mfma_s_settled(s, kf[kKS - 1], qf[kKS - 1]);
         if (masked)
             softmax_half<true>(s, k0h, qpos, W, S, hf, c2, rs, pf, alpha);
         else
             softmax_half<false>(s, k0h, qpos, W, S, hf, c2, rs, pf, alpha);
         rescale(oacc, alpha);
-        pv_half<true>(la, so + kHalfBytes, pf, oacc);
-
-        // every LDS read of this stage has returned (the MFMAs above consumed them): refill it
-        if (t + kDStages < n_mine) issue_half(t + kDStages, stage);
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+#pragma unroll
+            for (int db = 0; db < kDB; ++db) {
+                if (st == 1 && db == kDB - 1)
+                    mfma_acc_settled(oacc[db], vf[st][db], pf[st]);  // the accumulators are read below / next time round
+                else
+                    mfma_acc(oacc[db], vf[st][db], pf[st]);
+            }
         stage = (stage + 1 == kDStages) ? 0 : stage + 1;
     }
 
@@ -232,6 +258,7 @@ __global__ __launch_bounds__(kMergeThreads) void swaa_decode_merge_kernel(const 
 
     const int d = tid % kD, g = tid / kD;
     float acc = 0.f, l = 0.f;
+#pragma unroll 4
     for (int s = g; s < p.n_splits; s += kMergeThreads / kD) {
         const long long it = item_of(s);
         const float w = __builtin_amdgcn_exp2f(p.ws_ml[it * 64 + col] - m);  // 0 for a split that saw no visible key
@@ -265,9 +292,10 @@ void plan_decode(DecodeParams &p) {
     const int sink_halves = (sink_keys + 31) / 32;
     p.n_sink_halves = sink_halves < p.band_half0 ? sink_halves : p.band_half0;
     p.n_halves = p.n_sink_halves + ((p.Nk - 1) / 32 - p.band_half0 + 1);
-    // about four rounds of three workgroups per CU, but no split shorter than four halves
+    // kRounds rounds of three workgroups per CU (one round measured fastest: every split is
+    // resident at once and streams for the whole launch), but no split shorter than four halves
     const long long groups = (long long)p.B * p.Hkv * p.n_coltiles;
-    const long long target_items = 256LL * 3 * 4;
+    const long long target_items = 256LL * 3 * kRounds;
     long long per_group = target_items / groups;
     if (per_group < 1) per_group = 1;
     long long hps = (p.n_halves + per_group - 1) / per_group;

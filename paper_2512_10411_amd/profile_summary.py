@@ -40,16 +40,29 @@ def _counter_per_kernel(d, counter):
     return {k: (v[0] / v[1], v[1]) for k, v in acc.items()}
 
 
+def _largest_dispatch(d, counter, exclude):
+    """(kernel name, reading) of the single largest dispatch of a kernel whose name lacks `exclude`."""
+    best = None
+    for r in csv.DictReader(open(_find(d, "*counter_collection.csv"))):
+        if r["Counter_Name"] != counter or exclude in r["Kernel_Name"]:
+            continue
+        v = float(r["Counter_Value"])
+        if best is None or v > best[1]:
+            best = (r["Kernel_Name"], v)
+    return best
+
+
 def traffic(fetch_dir, write_dir, copy_mib):
     copy_bytes = float(copy_mib) * (1 << 20)
     out = {}
     for label, d, counter in (("read", fetch_dir, "FETCH_SIZE"), ("write", write_dir, "WRITE_SIZE")):
         per = _counter_per_kernel(d, counter)
-        copies = {k: v for k, v in per.items() if "swaa" not in k and v[0] * 1024 > 0.5 * copy_bytes}
+        # the probe is the largest dispatch that is not ours (small host-to-device copies use the same kernel)
+        probe = _largest_dispatch(d, counter, "swaa")
         attn = {k: v for k, v in per.items() if "swaa" in k}
-        if not copies or not attn:
+        if probe is None or probe[1] * 1024 < 0.25 * copy_bytes or not attn:
             raise SystemExit(f"{counter}: copy kernel or attention kernel not found in {d}")
-        ck, (cval, _) = max(copies.items(), key=lambda kv: kv[1][0])
+        ck, cval = probe
         factor = copy_bytes / (cval * 1024.0)
         for k, (val, n) in attn.items():
             out.setdefault(k, {})[label] = val * 1024.0 * factor
