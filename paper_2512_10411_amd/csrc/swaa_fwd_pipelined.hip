@@ -224,25 +224,34 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     // byte offset of this lane's 16 bytes inside a tile, first instruction; row = 8*wave + 4*i + lrow
     const uint32_t voff_k = (uint32_t)((8 * wave + lrow) * 256 + ((lchk ^ (lrow << 1) ^ (wave & 1)) << 4));
     const uint32_t voff_v = (uint32_t)((8 * wave + lrow) * 256 + ((lchk ^ (lrow << 2)) << 4));
+    const uint32_t voff_k1 = (voff_k ^ 128u) + 1024u;  // second instruction: row & 7 = 4 + lrow flips chunk bit 3
+    // LDS address = M0 + 16 * lane; global address = base + off.  Issued as assembly on
+    // purpose: the compiler would otherwise make every later LDS read wait for the copy.
+    auto copy16 = [](uint32_t off, const char *base, uint32_t lds) {
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds)
+                     : "memory");
+    };
     auto issue_tile = [&](int j, int buf, const __bf16 *src, int ring, bool is_k) {
         if (j >= J) return;
         const int k0 = tile_of(j) * kBk;
         const char *base = reinterpret_cast<const char *>(src) + (size_t)k0 * (kD * 2);  // uniform
-        const bool tail = k0 + kBk > N;  // rows past the end are masked later; keep the reads in bounds
+        const uint32_t l = (uint32_t)(ring + buf * kTileBytes + 2 * wave * 1024);
+        if (__builtin_expect(k0 + kBk > N, 0)) {
+            // last tile of a ragged sequence: rows past the end repeat the last row (they are
+            // masked later), so that the reads stay in bounds
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            // K: row & 7 = 4*i + lrow, so the second instruction flips chunk bit 3
-            uint32_t off = ((is_k ? voff_k : voff_v) ^ (is_k ? (uint32_t)(i << 7) : 0u)) + (uint32_t)(i * 1024);
-            if (tail) {
+            for (int i = 0; i < 2; ++i) {
+                uint32_t off = is_k ? (i ? voff_k1 : voff_k) : voff_v + (uint32_t)(i * 1024);
                 const int row = 8 * wave + 4 * i + lrow;
                 off -= (uint32_t)(max(k0 + row - (N - 1), 0) * (kD * 2));
+                copy16(off, base, l + (uint32_t)(i * 1024));
             }
-            const uint32_t l = (uint32_t)(ring + buf * kTileBytes + (2 * wave + i) * 1024);
-            // LDS address = M0 + 16 * lane; global address = base + off.  Issued as
-            // assembly on purpose: the compiler would otherwise make every later
-            // LDS read wait for it.
-            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(l)
-                         : "memory");
+        } else if (is_k) {
+            copy16(voff_k, base, l);
+            copy16(voff_k1, base, l + 1024u);
+        } else {
+            copy16(voff_v, base, l);
+            copy16(voff_v + 1024u, base, l + 1024u);
         }
     };
     auto issue_k = [&](int j, int buf) { issue_tile(j, buf, kg, 0, true); };
@@ -360,6 +369,12 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     // argument, so every LDS offset below is a constant that folds into the
     // instructions' offset fields (no address arithmetic in the loop); the loop
     // walks the three instantiations in turn.
+    bf16x8 fpre[kPrefetch];  // the first fragments of the coming sub-step, requested one sub-step ahead
+    {
+        const HalfOffsets h0 = {kHalfBytes, (kStages - 1) * kTileBytes + kHalfBytes, 0, 0};  // step 0, first sub-step
+#pragma unroll
+        for (int i = 0; i < kPrefetch; ++i) fpre[i] = load_slot(la, h0, i);
+    }
     auto step = [&](auto ring_pos, int j) {
         constexpr int R = decltype(ring_pos)::value;
         constexpr int Rn = (R + 1) % kStages, Rp = (R + kStages - 1) % kStages;
@@ -372,14 +387,12 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
 
         // softmax of (j, half 0) | scores of (j, half 1) | P V of (j-1, half 1)
         const HalfOffsets h1 = {kb_cur1, vb_prev1, kb_next0, vb_cur0};
-        bf16x8 fpre[kPrefetch];
-#pragma unroll
-        for (int i = 0; i < kPrefetch; ++i) fpre[i] = load_slot(la, h1, i);
         pipelined_substep(la, h1, fpre, qf, s_b, s_a, p_a, p_b, oacc, rs, c2, half_masked(k0 + 32), k0 + 32, qpos, W, S,
                           hf);
-        // softmax of (j, half 1) | scores of (j+1, half 0) | P V of (j, half 0);
-        // the sub-step after it belongs to the next step, which requests its own fragments
-        const HalfOffsets h2 = {kb_next0, vb_cur0, kb_next0, vb_cur0};
+        // softmax of (j, half 1) | scores of (j+1, half 0) | P V of (j, half 0); its last
+        // fragment requests are the first ones of step j+1 (K(j+1) half 1, V(j) half 1: both
+        // resident), so that they are under way while the waves meet at the barrier
+        const HalfOffsets h2 = {kb_next0, vb_cur0, Rn * kTileBytes + kHalfBytes, R * kTileBytes + kHalfBytes};
         pipelined_substep(la, h2, fpre, qf, s_a, s_b, p_b, p_a, oacc, rs, c2, half_masked(k0n), k0n, qpos, W, S, hf);
 
         // K(j+2), V(j+1) must have landed; K(j) and V(j-1) are free afterwards
