@@ -184,20 +184,25 @@ int swaa_oracle_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v,
  *
  *   Vis(r) = { j : 0 <= j <= pos and ( j > pos - W or j < S ) },  pos = Nk - Nq + r
  *
+ * The same shape is a chunk of a longer prefill (the Nq rows are the next
+ * chunk of the prompt, the cache holds the chunks before it); P is the prompt
+ * length as in swaa_oracle_rows_mixed: a row whose position is >= P is a
+ * generated token and sees every key up to its own (P > Nk: there is none).
+ *
  * q: [B, Hq, Nq, D] bf16 bits; out: [B, Hq, Nq, D] doubles; lse: [B, Hq, Nq].
  * Returns 0, or -1 on a bad argument, -2 when out of memory.
  */
 int swaa_oracle_decode(const uint16_t *q, const uint16_t *k, const uint16_t *v,
                        int B, int Hq, int Hkv, int Nq, int Nk, int D, long W, long S,
-                       double scale, double *out, double *lse, int n_threads)
+                       long P, double scale, double *out, double *lse, int n_threads)
 {
     if (!q || !k || !v || !out || !lse)
         return -1;
-    if (B < 1 || Hq < 1 || Hkv < 1 || Nq < 1 || Nk < Nq || D < 1 || Hq % Hkv || W < 1 || S < 0)
+    if (B < 1 || Hq < 1 || Hkv < 1 || Nq < 1 || Nk < Nq || D < 1 || Hq % Hkv || W < 1 || S < 0 || P < 0)
         return -1;
     const int G = Hq / Hkv;
     const long total = (long)B * Hq * Nq;
-    const long never_generated = (long)Nk + 1; /* every row keeps its window */
+    const long never_generated = P;
     int failed = 0;
 #ifdef _OPENMP
     if (n_threads > 0)

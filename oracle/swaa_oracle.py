@@ -70,7 +70,8 @@ def _load():
         lib.swaa_oracle_decode.argtypes = [
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-            ctypes.c_long, ctypes.c_long, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
+            ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int]
         lib.swaa_oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -174,29 +175,31 @@ def _check_decode(q, k, v):
     return B, Hq, Hkv, Nq, Nk, D
 
 
-def swaa_decode_oracle(q, k, v, window, n_sink, scale, n_threads=0):
+def swaa_decode_oracle(q, k, v, window, n_sink, scale, n_threads=0, n_prompt=None):
     """fp64 attention of the Nq newest tokens (q [B,Hq,Nq,D]) over a cache of Nk
     tokens (k, v [B,Hkv,Nk,D]) via the C oracle (paper Sec. 3.1.1).  Row r sits at
-    position Nk - Nq + r; window >= Nk is full attention (FA Decode).  Returns
+    position Nk - Nq + r; window >= Nk is full attention (FA Decode).  n_prompt:
+    rows at positions >= n_prompt ignore the window (None: no such rows).  Returns
     (out [B,Hq,Nq,D] float64, lse [B,Hq,Nq] float64)."""
     B, Hq, Hkv, Nq, Nk, D = _check_decode(q, k, v)
     q, k, v = (np.ascontiguousarray(a) for a in (q, k, v))
     out = np.empty((B, Hq, Nq, D), dtype=np.float64)
     lse = np.empty((B, Hq, Nq), dtype=np.float64)
     rc = _load().swaa_oracle_decode(q.ctypes.data, k.ctypes.data, v.ctypes.data, B, Hq, Hkv, Nq, Nk, D,
-                                    int(window), int(n_sink), float(scale), out.ctypes.data, lse.ctypes.data,
-                                    int(n_threads))
+                                    int(window), int(n_sink), Nk + 1 if n_prompt is None else int(n_prompt),
+                                    float(scale), out.ctypes.data, lse.ctypes.data, int(n_threads))
     if rc != 0:
         raise ValueError(f"swaa_oracle_decode failed with code {rc}")
     return out, lse
 
 
-def swaa_decode_oracle_numpy(q, k, v, window, n_sink, scale):
+def swaa_decode_oracle_numpy(q, k, v, window, n_sink, scale, n_prompt=None):
     """The same definition in numpy, row by row (slow; small inputs only)."""
     B, Hq, Hkv, Nq, Nk, D = _check_decode(q, k, v)
     W, S = int(window), int(n_sink)
-    if W < 1 or S < 0:
-        raise ValueError("window >= 1 and n_sink >= 0 required")
+    P = Nk + 1 if n_prompt is None else int(n_prompt)
+    if W < 1 or S < 0 or P < 0:
+        raise ValueError("window >= 1, n_sink >= 0 and n_prompt >= 0 required")
     G = Hq // Hkv
     qf, kf, vf = (_bf16_bits_to_f64(a) for a in (q, k, v))
     out = np.empty((B, Hq, Nq, D), dtype=np.float64)
@@ -206,7 +209,7 @@ def swaa_decode_oracle_numpy(q, k, v, window, n_sink, scale):
             g = h // G
             for r in range(Nq):
                 pos = Nk - Nq + r
-                vis = [j for j in range(pos + 1) if (j > pos - W) or (j < S)]
+                vis = [j for j in range(pos + 1) if (pos >= P) or (j > pos - W) or (j < S)]
                 s = scale * (kf[b, g, vis] @ qf[b, h, r])
                 m = s.max()
                 lse_r = m + np.log(np.exp(s - m).sum())

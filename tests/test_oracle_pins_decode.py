@@ -80,6 +80,29 @@ def test_decode_rows_equal_the_last_rows_of_the_one_pass_result(W, S):
     assert np.array_equal(do, fo[:, :, Nk - Nq:]) and np.array_equal(dl, fl[:, :, Nk - Nq:])
 
 
+# ---------------------------------------------- D3b: a chunk of a longer prefill, prompt boundary inside or outside it
+@pytest.mark.parametrize("Nq,P", [(16, 50), (16, 60), (16, 64), (16, 70), (16, 0), (1, 69)])
+def test_chunk_rows_equal_the_one_pass_rows_with_a_prompt_boundary(Nq, P):
+    B, Hq, Hkv, Nk, D, W, S = 1, 4, 2, 70, 16, 9, 3
+    q, k, v, q_full = decode_inputs(B, Hq, Hkv, Nq, Nk, D, seed=66)
+    o, lse = swaa_decode_oracle(q, k, v, W, S, 0.25, n_prompt=P)
+    po, pl = swaa_attn_oracle(q_full, k, v, W, S, 0.25, n_prompt=P)
+    assert np.array_equal(o, po[:, :, Nk - Nq:]) and np.array_equal(lse, pl[:, :, Nk - Nq:])
+    o2, l2 = swaa_decode_oracle_numpy(q, k, v, W, S, 0.25, n_prompt=P)
+    assert np.abs(o - o2).max() < 1e-13 and np.abs(lse - l2).max() < 1e-13
+    # library route: boolean mask from the sentence, bottom-right aligned
+    M = np.zeros((Nq, Nk), dtype=bool)
+    for r in range(Nq):
+        pos = Nk - Nq + r
+        for j in range(pos + 1):
+            M[r, j] = pos >= P or (pos - j) < W or j < S
+    G = Hq // Hkv
+    s = torch.matmul(torch.from_numpy(f64(q)), torch.from_numpy(f64(k)).repeat_interleave(G, 1).transpose(-1, -2)) * 0.25
+    s = s.masked_fill(~torch.from_numpy(M), float("-inf"))
+    ref = torch.matmul(torch.softmax(s, -1), torch.from_numpy(f64(v)).repeat_interleave(G, 1)).numpy()
+    assert np.abs(o - ref).max() < 1e-12
+
+
 # ---------------------------------------------- D4: closed forms
 def test_zero_queries_count_keys_and_window_one_returns_own_value():
     B, Hq, Hkv, Nq, Nk, D = 1, 2, 1, 5, 40, 8
