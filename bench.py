@@ -160,7 +160,7 @@ def main():
     stream = torch.cuda.current_stream()
 
     n_prompt = w.N if w.n_prompt is None else w.n_prompt
-    decode = w.n_query is not None
+    decode = w.n_query is not None and not w.chunk
     if decode:
         ws = torch.empty(binding.swaa_attn_decode_workspace_bytes(w.B, w.Hq, w.Hkv, w.n_query, w.N, w.D, w.window,
                                                                   w.n_sink), dtype=torch.uint8, device="cuda")
@@ -168,6 +168,9 @@ def main():
     def step():
         if decode:
             binding.swaa_attn_decode(qd, kd, vd, w.window, w.n_sink, w.scale, out=out, lse=lse, workspace=ws,
+                                     stream=stream)
+        elif w.chunk:
+            binding.swaa_attn_fwd_ex(qd, kd, vd, w.window, w.n_sink, w.n_prompt, w.scale, out=out, lse=lse,
                                      stream=stream)
         elif w.n_prompt is None:
             binding.swaa_attn_fwd(qd, kd, vd, w.window, w.n_sink, w.scale, out=out, lse=lse, stream=stream)
@@ -203,7 +206,7 @@ def main():
     kern_avg_ms = ev0.elapsed_time(ev1) / args.steps
     ms_per_step = wall * 1e3 / args.steps
 
-    if decode:
+    if decode or w.chunk:
         pairs, algo_bytes = decode_counts(w)
     else:
         pairs = binding.swaa_visible_pairs_fa_decode(w.N, w.window, w.n_sink, n_prompt) * w.B * w.Hq
@@ -245,7 +248,8 @@ def main():
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline_decode(w, q, k, v) if decode else cpu_baseline(w, q, k, v, args.cpu_seconds)
+        res["cpu_baseline"] = (cpu_baseline_decode(w, q, k, v) if decode or w.chunk
+                               else cpu_baseline(w, q, k, v, args.cpu_seconds))
         res["cpu_baseline"]["gpu_over_cpu"] = value / res["cpu_baseline"]["value"]
     print(json.dumps(res), flush=True)
     return 0

@@ -52,7 +52,7 @@ typedef enum swaa_status {
  *   v    device, bf16 [B, Hkv, N, D], contiguous, 16-byte aligned, read only
  *   out  device, bf16 [B, Hq,  N, D], contiguous, 16-byte aligned, written;
  *        must not overlap q, k or v
- *   lse  device, fp32 [B, Hq, N], contiguous, 16-byte aligned, written
+ *   lse  device, fp32 [B, Hq, N], contiguous, written
  *   B, Hq, Hkv, N >= 1; Hq a multiple of Hkv (query head h reads KV head
  *        h / (Hq/Hkv)); N * D * max(Hq, Hkv) * B must fit in 2^62 elements
  *   D    head dimension: 64 or 128
@@ -89,6 +89,60 @@ int swaa_attn_fwd(const void *q, const void *k, const void *v, void *out, float 
 int swaa_attn_fwd_fa_decode(const void *q, const void *k, const void *v, void *out, float *lse,
                             int B, int Hq, int Hkv, int N, int D, int window, int n_sink,
                             int n_prompt, float scale, void *stream);
+
+/*
+ * The general form of the two calls above: strided tensors, query rows that are
+ * the newest Nq of Nk tokens (a chunk of a longer prefill whose earlier keys and
+ * values are cached; row r sits at position Nk - Nq + r, as in swaa_attn_decode),
+ * and packed batches of sequences of different lengths -- the calling
+ * conventions of a serving engine (paper Sec. 4.1.1: vLLM; App. D: prefill and
+ * decode tokens mixed in one batch).  The mask is that of
+ * swaa_attn_fwd_fa_decode, in positions:
+ *
+ *     pos    = Nk - Nq + r
+ *     Vis(r) = { j : 0 <= j <= pos  and ( pos >= n_prompt  or  j > pos - window  or  j < n_sink ) }
+ *
+ * A tensor is a device pointer to element [0, 0, 0, 0] plus the element strides
+ * of batch entry, head and row; the D elements of a row are contiguous.  All
+ * strides are multiples of 8 elements (row starts stay 16-byte aligned);
+ * stride_n >= D and < 2^22.  [B, H, N, D], [B, N, H, D] and slices of either
+ * are all expressible.  lse is fp32 with contiguous rows:
+ * lse[b * lse_stride_b + h * lse_stride_h + r].
+ *
+ * Packed batches: when cu_seqlens_q and cu_seqlens_k (device arrays of B + 1
+ * ints, both or neither) are given, sequence b owns rows
+ * [cu_seqlens_q[b], cu_seqlens_q[b+1]) of q / out / lse and rows
+ * [cu_seqlens_k[b], cu_seqlens_k[b+1]) of k / v along the row axis; batch
+ * strides are ignored, and Nq, Nk are upper bounds on the sequence lengths
+ * (rows beyond Nq are not computed).  A sequence with more query rows than keys
+ * gets only its first Nk_b rows written; empty sequences are skipped.
+ *
+ * Ownership, asynchrony and error reporting as for swaa_attn_fwd; the argument
+ * block is read during the call only.  Without cu_seqlens, Nq <= Nk is required.
+ */
+typedef struct swaa_tensor {
+    void *ptr;
+    long long stride_b, stride_h, stride_n;
+} swaa_tensor;
+
+typedef struct swaa_fwd_args {
+    swaa_tensor q;   /* bf16, Hq heads, query rows; read only */
+    swaa_tensor k;   /* bf16, Hkv heads, key rows; read only */
+    swaa_tensor v;   /* bf16, Hkv heads, key rows; read only */
+    swaa_tensor out; /* bf16, Hq heads, query rows; written; must not overlap the inputs */
+    float *lse;      /* fp32, written */
+    long long lse_stride_b, lse_stride_h;
+    int B, Hq, Hkv, D;      /* D: 64 or 128 */
+    int Nq, Nk;             /* query rows and keys per sequence (upper bounds for packed batches) */
+    const int *cu_seqlens_q; /* device, B + 1 ints, or NULL */
+    const int *cu_seqlens_k; /* device, B + 1 ints, or NULL */
+    int window, n_sink;     /* as in swaa_attn_fwd */
+    int n_prompt;           /* as in swaa_attn_fwd_fa_decode, in positions; >= Nk: no generated rows */
+    float scale;
+    void *stream;
+} swaa_fwd_args;
+
+int swaa_attn_fwd_ex(const swaa_fwd_args *args);
 
 /*
  * Number of visible (query, key) pairs per head under the mask of swaa_attn_fwd, i.e.

@@ -23,10 +23,28 @@ SWAA_ERR_LAUNCH = -5
 SWAA_ERR_WORKSPACE = -6
 
 # every symbol include/swaa.h declares
-EXPORTS = ("swaa_attn_fwd", "swaa_attn_fwd_fa_decode", "swaa_visible_pairs", "swaa_visible_pairs_fa_decode",
+EXPORTS = ("swaa_attn_fwd", "swaa_attn_fwd_fa_decode", "swaa_attn_fwd_ex", "swaa_visible_pairs",
+           "swaa_visible_pairs_fa_decode",
            "swaa_attn_decode", "swaa_attn_decode_workspace_bytes", "swaa_status_string", "swaa_version")
 
 _lib = None
+
+
+class SwaaTensor(ctypes.Structure):
+    """swaa_tensor of include/swaa.h."""
+    _fields_ = [("ptr", ctypes.c_void_p), ("stride_b", ctypes.c_longlong), ("stride_h", ctypes.c_longlong),
+                ("stride_n", ctypes.c_longlong)]
+
+
+class SwaaFwdArgs(ctypes.Structure):
+    """swaa_fwd_args of include/swaa.h."""
+    _fields_ = [("q", SwaaTensor), ("k", SwaaTensor), ("v", SwaaTensor), ("out", SwaaTensor),
+                ("lse", ctypes.c_void_p), ("lse_stride_b", ctypes.c_longlong), ("lse_stride_h", ctypes.c_longlong),
+                ("B", ctypes.c_int), ("Hq", ctypes.c_int), ("Hkv", ctypes.c_int), ("D", ctypes.c_int),
+                ("Nq", ctypes.c_int), ("Nk", ctypes.c_int),
+                ("cu_seqlens_q", ctypes.c_void_p), ("cu_seqlens_k", ctypes.c_void_p),
+                ("window", ctypes.c_int), ("n_sink", ctypes.c_int), ("n_prompt", ctypes.c_int),
+                ("scale", ctypes.c_float), ("stream", ctypes.c_void_p)]
 
 
 class SwaaError(RuntimeError):
@@ -54,6 +72,8 @@ def load_library() -> ctypes.CDLL:
         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
         ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
         ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_void_p]
+    lib.swaa_attn_fwd_ex.restype = ctypes.c_int
+    lib.swaa_attn_fwd_ex.argtypes = [ctypes.POINTER(SwaaFwdArgs)]
     lib.swaa_visible_pairs.restype = ctypes.c_longlong
     lib.swaa_visible_pairs.argtypes = [ctypes.c_longlong] * 3
     lib.swaa_visible_pairs_fa_decode.restype = ctypes.c_longlong
@@ -232,6 +252,83 @@ def swaa_attn_decode(q, k, v, window: int, n_sink: int, scale: float | None = No
         rc = swaa_attn_decode_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
                                   B, Hq, Hkv, Nq, Nk, D, int(window), int(n_sink), float(scale),
                                   workspace.data_ptr(), workspace.numel(), sptr)
+    if rc != SWAA_OK:
+        raise SwaaError(rc, swaa_status_string(rc))
+    return out, lse
+
+
+def swaa_attn_fwd_ex_raw(args: SwaaFwdArgs) -> int:
+    """The C call itself on a filled argument block; returns the status code."""
+    return int(load_library().swaa_attn_fwd_ex(ctypes.byref(args)))
+
+
+def swaa_attn_fwd_ex(q, k, v, window: int, n_sink: int, n_prompt: int | None = None, scale: float | None = None,
+                     cu_seqlens_q=None, cu_seqlens_k=None, max_seqlen_q: int | None = None,
+                     max_seqlen_k: int | None = None, out=None, lse=None, stream=None):
+    """General forward: strided tensors, Nq <= Nk (the query rows are the newest Nq of Nk
+    tokens), packed variable-length batches.
+
+    Fixed-length batches: q [B, Hq, Nq, D] and k, v [B, Hkv, Nk, D] as *views* with any
+    strides whose last dimension is contiguous (a [B, N, H, D] tensor is passed as
+    ``t.permute(0, 2, 1, 3)``).  Packed batches: q [Hq, Tq, D], k, v [Hkv, Tk, D] views plus
+    int32 device tensors cu_seqlens_q / cu_seqlens_k of B + 1 offsets and the largest
+    sequence lengths.  out defaults to a new tensor with q's shape in q's memory order;
+    lse is fp32 [B, Hq, Nq] ([Hq, Tq] when packed).  Returns (out, lse).
+    """
+    import torch
+
+    packed = cu_seqlens_q is not None or cu_seqlens_k is not None
+    nd = 3 if packed else 4
+    for name, t in (("q", q), ("k", k), ("v", v)):
+        if t.dtype != torch.bfloat16 or not t.is_cuda or t.dim() != nd or t.stride(-1) != 1:
+            raise ValueError(f"{name} must be a bf16 GPU tensor view with {nd} dimensions and a contiguous last one")
+    D = q.shape[-1]
+    Hq, Hkv = q.shape[-3], k.shape[-3]
+    if scale is None:
+        scale = 1.0 / math.sqrt(D)
+    if packed:
+        if cu_seqlens_q is None or cu_seqlens_k is None or max_seqlen_q is None or max_seqlen_k is None:
+            raise ValueError("packed batches need cu_seqlens_q, cu_seqlens_k, max_seqlen_q and max_seqlen_k")
+        for name, t in (("cu_seqlens_q", cu_seqlens_q), ("cu_seqlens_k", cu_seqlens_k)):
+            if t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous() or t.dim() != 1:
+                raise ValueError(f"{name} must be a contiguous int32 GPU vector")
+        B = cu_seqlens_q.numel() - 1
+        if cu_seqlens_k.numel() != B + 1:
+            raise ValueError("cu_seqlens_q and cu_seqlens_k must have the same length")
+        Nq, Nk = int(max_seqlen_q), int(max_seqlen_k)
+        lse_shape = (Hq, q.shape[1])
+    else:
+        B, Nq, Nk = q.shape[0], q.shape[2], k.shape[2]
+        lse_shape = (B, Hq, Nq)
+    with torch.cuda.device(q.device):
+        if out is None:
+            out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+        if lse is None:
+            lse = torch.empty(lse_shape, dtype=torch.float32, device=q.device)
+        if out.shape != q.shape or out.dtype != torch.bfloat16 or out.stride(-1) != 1:
+            raise ValueError("out must be a bf16 tensor view shaped like q with a contiguous last dimension")
+        if tuple(lse.shape) != lse_shape or lse.dtype != torch.float32 or not lse.is_contiguous():
+            raise ValueError(f"lse must be a contiguous fp32 tensor of shape {lse_shape}")
+        if stream is None:
+            stream = torch.cuda.current_stream(q.device)
+
+        def tensor(t):
+            if packed:
+                return SwaaTensor(t.data_ptr(), 0, t.stride(0), t.stride(1))
+            return SwaaTensor(t.data_ptr(), t.stride(0), t.stride(1), t.stride(2))
+
+        a = SwaaFwdArgs()
+        a.q, a.k, a.v, a.out = tensor(q), tensor(k), tensor(v), tensor(out)
+        a.lse = lse.data_ptr()
+        a.lse_stride_b, a.lse_stride_h = (0, lse.stride(0)) if packed else (lse.stride(0), lse.stride(1))
+        a.B, a.Hq, a.Hkv, a.D, a.Nq, a.Nk = B, Hq, Hkv, D, Nq, Nk
+        a.cu_seqlens_q = cu_seqlens_q.data_ptr() if packed else None
+        a.cu_seqlens_k = cu_seqlens_k.data_ptr() if packed else None
+        a.window, a.n_sink = int(window), int(n_sink)
+        a.n_prompt = 2**31 - 1 if n_prompt is None else int(n_prompt)
+        a.scale = float(scale)
+        a.stream = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+        rc = swaa_attn_fwd_ex_raw(a)
     if rc != SWAA_OK:
         raise SwaaError(rc, swaa_status_string(rc))
     return out, lse

@@ -71,47 +71,99 @@ const char *swaa_status_string(int status) {
 
 int swaa_version(void) { return 120; }
 
-int swaa_attn_fwd_fa_decode(const void *q, const void *k, const void *v, void *out, float *lse,
-                            int B, int Hq, int Hkv, int N, int D, int window, int n_sink,
-                            int n_prompt, float scale, void *stream) {
-    if (!q || !k || !v || !out || !lse) return SWAA_ERR_NULL;
-    if (B < 1 || Hq < 1 || Hkv < 1 || N < 1 || D < 1) return SWAA_ERR_SHAPE;
+namespace {
+
+bool bad_stride(long long s, bool may_be_zero) {
+    if (s == 0) return !may_be_zero;
+    return s < 0 || (s % 8) != 0;  // row, head and batch starts stay 16-byte aligned
+}
+
+}  // namespace
+
+int swaa_attn_fwd_ex(const swaa_fwd_args *a) {
+    if (!a) return SWAA_ERR_NULL;
+    if (!a->q.ptr || !a->k.ptr || !a->v.ptr || !a->out.ptr || !a->lse) return SWAA_ERR_NULL;
+    const int B = a->B, Hq = a->Hq, Hkv = a->Hkv, D = a->D, Nq = a->Nq, Nk = a->Nk;
+    if (B < 1 || Hq < 1 || Hkv < 1 || Nq < 1 || Nk < 1 || D < 1) return SWAA_ERR_SHAPE;
     if (Hq % Hkv != 0) return SWAA_ERR_SHAPE;
-    if (window < 1 || n_sink < 0 || n_prompt < 0) return SWAA_ERR_SHAPE;
-    if (!positive_finite(scale)) return SWAA_ERR_SHAPE;
+    if (a->window < 1 || a->n_sink < 0 || a->n_prompt < 0) return SWAA_ERR_SHAPE;
+    if (!positive_finite(a->scale)) return SWAA_ERR_SHAPE;
+    const bool packed = a->cu_seqlens_q != nullptr || a->cu_seqlens_k != nullptr;
+    if (packed && (!a->cu_seqlens_q || !a->cu_seqlens_k)) return SWAA_ERR_NULL;
+    if (!packed && Nq > Nk) return SWAA_ERR_SHAPE;  // the query rows are the newest Nq of Nk tokens
     if (D != 64 && D != 128) return SWAA_ERR_UNSUPPORTED;
-    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(lse))
+    for (const swaa_tensor *t : {&a->q, &a->k, &a->v, &a->out}) {
+        if (misaligned(t->ptr)) return SWAA_ERR_ALIGN;
+        if (bad_stride(t->stride_n, false) || t->stride_n < D || t->stride_n >= (1LL << 22)) return SWAA_ERR_SHAPE;
+        if (bad_stride(t->stride_h, Hq == 1 || Hkv == 1) || bad_stride(t->stride_b, packed || B == 1))
+            return SWAA_ERR_SHAPE;
+    }
+    if ((reinterpret_cast<uintptr_t>(a->lse) & 3u) != 0) return SWAA_ERR_ALIGN;
+    if (a->lse_stride_h < 0 || a->lse_stride_b < 0) return SWAA_ERR_SHAPE;
+    if (packed && ((reinterpret_cast<uintptr_t>(a->cu_seqlens_q) | reinterpret_cast<uintptr_t>(a->cu_seqlens_k)) & 3u))
         return SWAA_ERR_ALIGN;
 
     FwdParams p;
-    p.q = static_cast<const __bf16 *>(q);
-    p.k = static_cast<const __bf16 *>(k);
-    p.v = static_cast<const __bf16 *>(v);
-    p.out = static_cast<__bf16 *>(out);
-    p.lse = lse;
-    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N;
-    p.W = window < N ? window : N;
-    p.S = n_sink < N ? n_sink : N;
-    p.P = n_prompt < N ? n_prompt : N;
+    p.q = static_cast<const __bf16 *>(a->q.ptr);
+    p.k = static_cast<const __bf16 *>(a->k.ptr);
+    p.v = static_cast<const __bf16 *>(a->v.ptr);
+    p.out = static_cast<__bf16 *>(a->out.ptr);
+    p.lse = a->lse;
+    p.q_sb = a->q.stride_b; p.q_sh = a->q.stride_h; p.q_sn = a->q.stride_n;
+    p.k_sb = a->k.stride_b; p.k_sh = a->k.stride_h; p.k_sn = a->k.stride_n;
+    p.v_sb = a->v.stride_b; p.v_sh = a->v.stride_h; p.v_sn = a->v.stride_n;
+    p.o_sb = a->out.stride_b; p.o_sh = a->out.stride_h; p.o_sn = a->out.stride_n;
+    p.lse_sb = a->lse_stride_b; p.lse_sh = a->lse_stride_h;
+    p.cu_q = a->cu_seqlens_q;
+    p.cu_k = a->cu_seqlens_k;
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.Nq = Nq; p.Nk = Nk;
+    p.W = a->window < Nk ? a->window : Nk;
+    p.S = a->n_sink < Nk ? a->n_sink : Nk;
+    p.P = a->n_prompt < Nk ? a->n_prompt : Nk;
     p.G = Hq / Hkv;
-    p.scale = scale;
-    p.scale_log2 = scale * 1.44269504088896340736f;
+    p.scale = a->scale;
+    p.scale_log2 = a->scale * 1.44269504088896340736f;
     p.n4 = p.G / 4;
     p.has2 = (p.G % 4) >= 2 ? 1 : 0;
     p.has1 = p.G % 2;
-    p.nt64 = (N + 63) / 64;
-    p.nt128 = (N + 127) / 128;
-    p.nt256 = (N + 255) / 256;
+    p.nt64 = (Nq + 63) / 64;
+    p.nt128 = (Nq + 127) / 128;
+    p.nt256 = (Nq + 255) / 256;
     p.tiles_per_pair = p.n4 * p.nt64 + p.has2 * p.nt128 + p.has1 * p.nt256;
     p.total_items = (long long)B * Hkv * p.tiles_per_pair;
     p.chunk = (p.total_items + kXcds - 1) / kXcds;
     const long long grid = p.chunk * kXcds;
     if (grid > 0x7fffffffLL) return SWAA_ERR_SHAPE;
 
-    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipStream_t s = static_cast<hipStream_t>(a->stream);
     const hipError_t err = (D == 128 && !use_simple_kernel()) ? swaa::launch_fwd_pipelined_d128(p, s)
                                                               : swaa::launch_fwd_simple(p, D, s);
     return err == hipSuccess ? SWAA_OK : SWAA_ERR_LAUNCH;
+}
+
+int swaa_attn_fwd_fa_decode(const void *q, const void *k, const void *v, void *out, float *lse,
+                            int B, int Hq, int Hkv, int N, int D, int window, int n_sink,
+                            int n_prompt, float scale, void *stream) {
+    if (!q || !k || !v || !out || !lse) return SWAA_ERR_NULL;
+    if (B < 1 || Hq < 1 || Hkv < 1 || N < 1 || D < 1) return SWAA_ERR_SHAPE;
+    // contiguous [B, H, N, D] tensors, every sequence N rows on N keys
+    swaa_fwd_args a;
+    const long long nd = (long long)N * D;
+    a.q = {const_cast<void *>(q), Hq * nd, nd, D};
+    a.k = {const_cast<void *>(k), Hkv * nd, nd, D};
+    a.v = {const_cast<void *>(v), Hkv * nd, nd, D};
+    a.out = {out, Hq * nd, nd, D};
+    a.lse = lse;
+    a.lse_stride_b = (long long)Hq * N;
+    a.lse_stride_h = N;
+    a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.D = D;
+    a.Nq = N; a.Nk = N;
+    a.cu_seqlens_q = nullptr;
+    a.cu_seqlens_k = nullptr;
+    a.window = window; a.n_sink = n_sink; a.n_prompt = n_prompt;
+    a.scale = scale;
+    a.stream = stream;
+    return swaa_attn_fwd_ex(&a);
 }
 
 int swaa_attn_fwd(const void *q, const void *k, const void *v, void *out, float *lse,

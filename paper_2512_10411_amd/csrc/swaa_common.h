@@ -28,28 +28,70 @@ struct FwdParams {
     const __bf16 *v;
     __bf16 *out;
     float *lse;
-    int B, Hq, Hkv, N;
-    int W, S;  // clamped to [1, N] and [0, N]
-    int P;     // rows >= P are generated tokens and see every earlier key; clamped to [0, N]
-    int G;     // Hq / Hkv
+    // element strides of batch entry, head and row; the head dimension is contiguous
+    long long q_sb, q_sh, q_sn;
+    long long k_sb, k_sh, k_sn;
+    long long v_sb, v_sh, v_sn;
+    long long o_sb, o_sh, o_sn;
+    long long lse_sb, lse_sh;  // rows contiguous
+    // packed variable-length batches: device arrays of B + 1 row offsets along the row
+    // axis (sequence b owns rows [cu[b], cu[b+1])), batch strides unused; or null
+    const int *cu_q;
+    const int *cu_k;
+    int B, Hq, Hkv;
+    int Nq, Nk;  // query rows and keys per sequence (the largest ones when cu_q / cu_k are given)
+    int W, S;    // clamped to [1, Nk] and [0, Nk]
+    int P;       // rows at positions >= P are generated tokens and see every earlier key; clamped to [0, Nk]
+    int G;       // Hq / Hkv
     float scale, scale_log2;
     // Work decomposition.  Per (batch, KV head) "pair" the G query heads are
-    // cut into n4 groups of 4 heads (workgroups of 4 heads x 64 positions), at
+    // cut into n4 groups of 4 heads (workgroups of 4 heads x 64 rows), at
     // most one group of 2 heads (2 x 128) and at most one single head (1 x 256),
-    // so that every workgroup is 4 waves x 64 query rows on one KV head.
+    // so that every workgroup is 256 query rows on one KV head.
     int n4, has2, has1;
-    int nt64, nt128, nt256;
+    int nt64, nt128, nt256;  // row tiles of a sequence of Nq rows
     int tiles_per_pair;
     long long total_items;
     long long chunk;  // work items per XCD
 };
+
+// One sequence as a workgroup sees it: the query rows are the newest nq of its nk
+// tokens (row r sits at position nk - nq + r; nq = nk for a plain prefill).
+struct SeqGeom {
+    int nq, nk;
+    long long q_row0, k_row0;  // first row along the row axis of q / out / lse and of k / v
+    long long q_batch, k_batch;  // batch index to multiply the batch strides with
+};
+__device__ __forceinline__ bool seq_geom(const FwdParams &p, int b, SeqGeom &g) {
+    if (p.cu_q) {
+        g.q_row0 = p.cu_q[b];
+        g.nq = p.cu_q[b + 1] - (int)g.q_row0;
+        g.q_batch = 0;
+    } else {
+        g.q_row0 = 0;
+        g.nq = p.Nq;
+        g.q_batch = b;
+    }
+    if (p.cu_k) {
+        g.k_row0 = p.cu_k[b];
+        g.nk = p.cu_k[b + 1] - (int)g.k_row0;
+        g.k_batch = 0;
+    } else {
+        g.k_row0 = 0;
+        g.nk = p.Nk;
+        g.k_batch = b;
+    }
+    g.nq = min(min(g.nq, p.Nq), g.nk);  // never more rows than the plan covers, nor than tokens
+    g.nk = min(g.nk, p.Nk);
+    return g.nq > 0;
+}
 
 // What one workgroup computes.
 struct WorkItem {
     int b, kvh;  // batch entry, KV head
     int hpb;     // query heads in this workgroup: 4, 2 or 1
     int h0;      // first of them, relative to the GQA group
-    int pt;      // position tile of 256/hpb positions
+    int pt;      // row tile of 256/hpb rows
 };
 
 // Workgroups reach the 8 XCDs round-robin; XCD x takes the x-th contiguous

@@ -180,9 +180,14 @@ __device__ __forceinline__ void pipelined_substep(const LaneAddr &la, const Half
 __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const FwdParams p) {
     WorkItem wi;
     if (!decode_work(p, wi)) return;
+    SeqGeom sg;
+    if (!seq_geom(p, wi.b, sg)) return;
     const int hpb = wi.hpb;
-    const int pos_per_wg = kWgRows / hpb;
-    const int N = p.N, S = p.S;
+    const int rows_per_wg = kWgRows / hpb;
+    const int wg_r0 = wi.pt * rows_per_wg;  // first query row of the workgroup
+    if (wg_r0 >= sg.nq) return;             // a shorter sequence of a packed batch
+    const int Nq = sg.nq, Nk = sg.nk, S = p.S;
+    const int pos_off = Nk - Nq;  // query row r sits at position pos_off + r
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform, and known to the compiler as such
@@ -191,12 +196,13 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     const int hf = lane >> 5;
 
     const int head = wi.kvh * p.G + wi.h0 + (wave % hpb);
-    const int wg_p0 = wi.pt * pos_per_wg;
-    const int wg_p1 = min(N, wg_p0 + pos_per_wg) - 1;
-    const int p0 = wg_p0 + (wave / hpb) * kPRows;  // first position of this wave
+    const int r0 = wg_r0 + (wave / hpb) * kPRows;  // first query row of this wave
+    const int wg_p0 = pos_off + wg_r0;             // positions of the workgroup's first ...
+    const int wg_p1 = pos_off + min(Nq, wg_r0 + rows_per_wg) - 1;  // ... and last valid row
+    const int p0 = pos_off + r0;                   // first position of this wave
     const int qpos = p0 + l32;                     // this lane's query column
     // this lane's window: a generated token (position >= P) sees its whole prefix
-    const int W = (qpos >= p.P) ? N : p.W;
+    const int W = (qpos >= p.P) ? Nk : p.W;
 
     // visited KV tiles: sink tiles 0 .. n_sink_tiles-1, then band tiles t_band_lo .. t_hi;
     // a workgroup that holds a generated token visits every tile up to its diagonal
@@ -207,10 +213,11 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     const int J = n_sink_tiles + (t_hi - t_band_lo + 1);
     auto tile_of = [&](int j) { return j < n_sink_tiles ? j : j - n_sink_tiles + t_band_lo; };
 
-    const size_t kv_base = ((size_t)wi.b * p.Hkv + wi.kvh) * (size_t)N * kD;
-    const __bf16 *kg = p.k + kv_base;
-    const __bf16 *vg = p.v + kv_base;
-    const size_t q_base = ((size_t)wi.b * p.Hq + head) * (size_t)N * kD;
+    const uint32_t k_rsb = (uint32_t)(p.k_sn * 2), v_rsb = (uint32_t)(p.v_sn * 2);  // row strides in bytes
+    const __bf16 *kg = p.k + sg.k_batch * p.k_sb + (long long)wi.kvh * p.k_sh + sg.k_row0 * p.k_sn;
+    const __bf16 *vg = p.v + sg.k_batch * p.v_sb + (long long)wi.kvh * p.v_sh + sg.k_row0 * p.v_sn;
+    const __bf16 *qg = p.q + sg.q_batch * p.q_sb + (long long)head * p.q_sh + sg.q_row0 * p.q_sn;
+    __bf16 *og = p.out + sg.q_batch * p.o_sb + (long long)head * p.o_sh + sg.q_row0 * p.o_sn;
 
     // ---- HBM -> LDS tile copies -------------------------------------------------
     // One wave instruction moves 64 x 16 bytes = 4 rows of the tile, a wave moves
@@ -221,10 +228,11 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     // for V (4 consecutive rows read the same 64 bytes).
     const int lrow = lane >> 4;  // row within the 4-row group
     const int lchk = lane & 15;  // LDS chunk within the row
-    // byte offset of this lane's 16 bytes inside a tile, first instruction; row = 8*wave + 4*i + lrow
-    const uint32_t voff_k = (uint32_t)((8 * wave + lrow) * 256 + ((lchk ^ (lrow << 1) ^ (wave & 1)) << 4));
-    const uint32_t voff_v = (uint32_t)((8 * wave + lrow) * 256 + ((lchk ^ (lrow << 2)) << 4));
-    const uint32_t voff_k1 = (voff_k ^ 128u) + 1024u;  // second instruction: row & 7 = 4 + lrow flips chunk bit 3
+    // byte offset of this lane's 16 bytes from the tile's first row; row = 8*wave + 4*i + lrow
+    const uint32_t chunk_k = (uint32_t)(lchk ^ (lrow << 1) ^ (wave & 1));
+    const uint32_t voff_k = (uint32_t)(8 * wave + lrow) * k_rsb + (chunk_k << 4);
+    const uint32_t voff_k1 = (uint32_t)(8 * wave + lrow + 4) * k_rsb + ((chunk_k ^ 8u) << 4);  // row & 7 = 4 + lrow
+    const uint32_t voff_v = (uint32_t)(8 * wave + lrow) * v_rsb + (uint32_t)((lchk ^ (lrow << 2)) << 4);
     // LDS address = M0 + 16 * lane; global address = base + off.  Issued as assembly on
     // purpose: the compiler would otherwise make every later LDS read wait for the copy.
     auto copy16 = [](uint32_t off, const char *base, uint32_t lds) {
@@ -234,16 +242,17 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     auto issue_tile = [&](int j, int buf, const __bf16 *src, int ring, bool is_k) {
         if (j >= J) return;
         const int k0 = tile_of(j) * kBk;
-        const char *base = reinterpret_cast<const char *>(src) + (size_t)k0 * (kD * 2);  // uniform
+        const uint32_t rsb = is_k ? k_rsb : v_rsb;
+        const char *base = reinterpret_cast<const char *>(src) + (size_t)k0 * rsb;  // uniform
         const uint32_t l = (uint32_t)(ring + buf * kTileBytes + 2 * wave * 1024);
-        if (__builtin_expect(k0 + kBk > N, 0)) {
+        if (__builtin_expect(k0 + kBk > Nk, 0)) {
             // last tile of a ragged sequence: rows past the end repeat the last row (they are
             // masked later), so that the reads stay in bounds
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                uint32_t off = is_k ? (i ? voff_k1 : voff_k) : voff_v + (uint32_t)(i * 1024);
+                uint32_t off = is_k ? (i ? voff_k1 : voff_k) : voff_v + (uint32_t)(4 * i) * v_rsb;
                 const int row = 8 * wave + 4 * i + lrow;
-                off -= (uint32_t)(max(k0 + row - (N - 1), 0) * (kD * 2));
+                off -= (uint32_t)max(k0 + row - (Nk - 1), 0) * rsb;
                 copy16(off, base, l + (uint32_t)(i * 1024));
             }
         } else if (is_k) {
@@ -251,7 +260,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
             copy16(voff_k1, base, l + 1024u);
         } else {
             copy16(voff_v, base, l);
-            copy16(voff_v + 1024u, base, l + 1024u);
+            copy16(voff_v + 4u * v_rsb, base, l + 1024u);
         }
     };
     auto issue_k = [&](int j, int buf) { issue_tile(j, buf, kg, 0, true); };
@@ -268,12 +277,12 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     // ---- this wave's 32 Q rows: HBM -> its staging area, laid out like a K half tile ----
     const uint32_t stage = (uint32_t)(kStage + wave * kStageBytes);
     {
-        const char *qg = reinterpret_cast<const char *>(p.q + q_base);
+        const char *qb = reinterpret_cast<const char *>(qg);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int row = 4 * i + lrow;
             const int f = ((4 * (i & 1) + lrow) << 1) | ((i >> 1) & 1);
-            const char *g = qg + (size_t)min(p0 + row, N - 1) * (kD * 2) + ((lchk ^ f) << 4);
+            const char *g = qb + (size_t)min(r0 + row, Nq - 1) * (size_t)(p.q_sn * 2) + ((lchk ^ f) << 4);
             const uint32_t l = stage + (uint32_t)(i * 1024);
             asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(l) : "memory");
         }
@@ -473,16 +482,15 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
                 *(bf16x4 __attribute__((address_space(3))) *)(uintptr_t)(o_lane ^ (uint32_t)((4 * db + e4) << 4)) = o4;
             }
         }
-        __bf16 *og = p.out + q_base;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int row = 4 * i + lrow;
             const int f = ((4 * (i & 1) + lrow) << 1) | ((i >> 1) & 1);
             const u32x4 val = *(const u32x4 __attribute__((address_space(3))) *)(uintptr_t)(stage + i * 1024 + lane * 16);
-            if (p0 + row < N) *reinterpret_cast<u32x4 *>(og + (size_t)(p0 + row) * kD + ((lchk ^ f) << 3)) = val;
+            if (r0 + row < Nq) *reinterpret_cast<u32x4 *>(og + (size_t)(r0 + row) * p.o_sn + ((lchk ^ f) << 3)) = val;
         }
-        if (hf == 0 && qpos < N)
-            p.lse[((size_t)wi.b * p.Hq + head) * (size_t)N + qpos] =
+        if (hf == 0 && r0 + l32 < Nq)
+            p.lse[sg.q_batch * p.lse_sb + (long long)head * p.lse_sh + sg.q_row0 + r0 + l32] =
                 (rs.mc + __builtin_amdgcn_logf(rs.l)) * 0.69314718055994530942f;
     }
 }

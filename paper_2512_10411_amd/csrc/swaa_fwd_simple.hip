@@ -54,8 +54,13 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
     WorkItem wi;
     if (!decode_work(p, wi)) return;
     const int b = wi.b, kvh = wi.kvh, hpb = wi.hpb, h0 = wi.h0, pt = wi.pt;
-    const int pos_per_wg = kWgRows / hpb;
-    const int N = p.N, W = p.W, S = p.S, P = p.P;
+    SeqGeom sg;
+    if (!seq_geom(p, b, sg)) return;
+    const int rows_per_wg = kWgRows / hpb;
+    const int wg_r0 = pt * rows_per_wg;  // first query row of the workgroup
+    if (wg_r0 >= sg.nq) return;          // a shorter sequence of a packed batch
+    const int Nq = sg.nq, Nk = sg.nk, W = p.W, S = p.S, P = p.P;
+    const int pos_off = Nk - Nq;  // query row r sits at position pos_off + r
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
@@ -64,11 +69,12 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
     const int hf = lane >> 5;  // which half of the wave
 
     const int head = kvh * p.G + h0 + (wave % hpb);
-    const int wg_p0 = pt * pos_per_wg;                      // first position of the workgroup
-    const int wg_p1 = min(N, wg_p0 + pos_per_wg) - 1;       // last valid position
-    const int p0 = wg_p0 + (wave / hpb) * kWaveRows;        // first position of this wave
-    const bool wave_active = p0 < N;
-    const int plast = min(p0 + kWaveRows, N) - 1;           // last valid position of this wave
+    const int r0 = wg_r0 + (wave / hpb) * kWaveRows;                // first query row of this wave
+    const int wg_p0 = pos_off + wg_r0;                              // first position of the workgroup
+    const int wg_p1 = pos_off + min(Nq, wg_r0 + rows_per_wg) - 1;   // last valid position
+    const int p0 = pos_off + r0;                                    // first position of this wave
+    const bool wave_active = r0 < Nq;
+    const int plast = pos_off + min(r0 + kWaveRows, Nq) - 1;        // last valid position of this wave
 
     // ---- KV tiles this workgroup visits -------------------------------------
     // (a workgroup that holds a generated token visits every tile up to its diagonal)
@@ -79,17 +85,17 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
     // tile order: 0 .. n_sink_tiles-1, then t_band_lo .. t_hi
     const int wbound = window_bound(p0, kWaveRows, W, P);
 
-    const size_t kv_base = ((size_t)b * p.Hkv + kvh) * (size_t)N * D;
-    const __bf16 *kg = p.k + kv_base;
-    const __bf16 *vg = p.v + kv_base;
-    const size_t q_base = ((size_t)b * p.Hq + head) * (size_t)N * D;
+    const __bf16 *kg = p.k + sg.k_batch * p.k_sb + (long long)kvh * p.k_sh + sg.k_row0 * p.k_sn;
+    const __bf16 *vg = p.v + sg.k_batch * p.v_sb + (long long)kvh * p.v_sh + sg.k_row0 * p.v_sn;
+    const __bf16 *qg = p.q + sg.q_batch * p.q_sb + (long long)head * p.q_sh + sg.q_row0 * p.q_sn;
+    __bf16 *og = p.out + sg.q_batch * p.o_sb + (long long)head * p.o_sh + sg.q_row0 * p.o_sn;
 
     // ---- Q fragments (B operand of S^T = K Q^T), kept for the whole loop ----
     bf16x8 qf[2][KS];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-        const int row = min(p0 + 32 * qb + l32, N - 1);
-        const __bf16 *src = p.q + q_base + (size_t)row * D + 8 * hf;
+        const int row = min(r0 + 32 * qb + l32, Nq - 1);
+        const __bf16 *src = qg + (size_t)row * p.q_sn + 8 * hf;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
             qf[qb][ks] = *reinterpret_cast<const bf16x8 *>(src + 16 * ks);
@@ -111,10 +117,10 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
 #pragma unroll
         for (int c = 0; c < T::kChunksPerThread; ++c) {
             const int id = c * kThreads + tid;
-            const int row = min(t * kBk + id / T::kChunksPerRow, N - 1);  // tail rows are masked later
+            const int row = min(t * kBk + id / T::kChunksPerRow, Nk - 1);  // tail rows are masked later
             const int col = (id % T::kChunksPerRow) * 8;
-            kreg[c] = *reinterpret_cast<const u32x4 *>(kg + (size_t)row * D + col);
-            vreg[c] = *reinterpret_cast<const u32x4 *>(vg + (size_t)row * D + col);
+            kreg[c] = *reinterpret_cast<const u32x4 *>(kg + (size_t)row * p.k_sn + col);
+            vreg[c] = *reinterpret_cast<const u32x4 *>(vg + (size_t)row * p.v_sn + col);
         }
     };
     auto store_tile = [&]() {
@@ -178,7 +184,7 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
 #pragma unroll
                 for (int qb = 0; qb < 2; ++qb) {
                     const int qpos = p0 + 32 * qb + l32;
-                    const int wq = (qpos >= P) ? N : W;  // a generated token's window is the whole prefix
+                    const int wq = (qpos >= P) ? Nk : W;  // a generated token's window is the whole prefix
 #pragma unroll
                     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -270,10 +276,10 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
     if (!wave_active) return;
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-        const int qpos = p0 + 32 * qb + l32;
-        if (qpos >= N) continue;
+        const int row = r0 + 32 * qb + l32;
+        if (row >= Nq) continue;
         const float inv_l = 1.f / l_run[qb];
-        __bf16 *orow = p.out + q_base + (size_t)qpos * D;
+        __bf16 *orow = og + (size_t)row * p.o_sn;
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
 #pragma unroll
@@ -285,7 +291,7 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
             }
         }
         if (hf == 0)
-            p.lse[((size_t)b * p.Hq + head) * (size_t)N + qpos] =
+            p.lse[sg.q_batch * p.lse_sb + (long long)head * p.lse_sh + sg.q_row0 + row] =
                 (m_run[qb] * c2 + __builtin_amdgcn_logf(l_run[qb])) * 0.69314718055994530942f;
     }
 }

@@ -124,3 +124,39 @@ def test_decode_workspace_size_and_argument_errors():
     assert call(w=None) == binding.SWAA_ERR_WORKSPACE
     assert call(w=p + 4) == binding.SWAA_ERR_WORKSPACE
     assert call(wb=full - 1) == binding.SWAA_ERR_WORKSPACE
+
+
+def test_general_forward_argument_errors():
+    p = 4096  # fake aligned address; never dereferenced on these paths
+
+    def args(**kw):
+        a = binding.SwaaFwdArgs()
+        Hq, Hkv, N, D = 4, 2, 128, 128
+        for name, H in (("q", Hq), ("k", Hkv), ("v", Hkv), ("out", Hq)):
+            setattr(a, name, binding.SwaaTensor(p, H * N * D, N * D, D))
+        a.lse, a.lse_stride_b, a.lse_stride_h = p, Hq * N, N
+        a.B, a.Hq, a.Hkv, a.D, a.Nq, a.Nk = 2, Hq, Hkv, D, N, N
+        a.cu_seqlens_q = a.cu_seqlens_k = None
+        a.window, a.n_sink, a.n_prompt, a.scale, a.stream = 16, 2, 2**31 - 1, 0.1, None
+        for key, val in kw.items():
+            if "." in key:
+                t, f = key.split(".")
+                setattr(getattr(a, t), f, val)
+            else:
+                setattr(a, key, val)
+        return a
+
+    call = lambda **kw: binding.swaa_attn_fwd_ex_raw(args(**kw))
+    assert binding.load_library().swaa_attn_fwd_ex(None) == binding.SWAA_ERR_NULL
+    assert call(lse=None) == binding.SWAA_ERR_NULL
+    assert call(**{"v.ptr": None}) == binding.SWAA_ERR_NULL
+    assert call(Nq=129) == binding.SWAA_ERR_SHAPE               # more query rows than tokens
+    assert call(n_prompt=-1) == binding.SWAA_ERR_SHAPE
+    assert call(**{"k.stride_n": 132}) == binding.SWAA_ERR_SHAPE  # rows would lose 16-byte alignment
+    assert call(**{"q.stride_n": 64}) == binding.SWAA_ERR_SHAPE   # rows would overlap
+    assert call(**{"out.stride_h": -128}) == binding.SWAA_ERR_SHAPE
+    assert call(**{"q.stride_b": 0}) == binding.SWAA_ERR_SHAPE    # two batch entries on one address
+    assert call(cu_seqlens_q=p) == binding.SWAA_ERR_NULL          # one offset array without the other
+    assert call(cu_seqlens_q=p, cu_seqlens_k=p + 2) == binding.SWAA_ERR_ALIGN
+    assert call(D=96) == binding.SWAA_ERR_UNSUPPORTED
+    assert call(**{"k.ptr": p + 8}) == binding.SWAA_ERR_ALIGN

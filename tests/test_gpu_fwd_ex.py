@@ -1,0 +1,111 @@
+"""GPU parity of swaa_attn_fwd_ex: strided layouts, chunks of a longer prefill (the query
+rows are the newest Nq of Nk tokens) and packed variable-length batches, against the fp64
+CPU oracle, through the C ABI.  Same tolerances as the prefill tests.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import swaa_attn_oracle, swaa_decode_oracle
+from paper_2512_10411_amd import binding
+from paper_2512_10411_amd.inputs import make_qkv
+from gpu_util import assert_parity, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def chunk_case(B, Hq, Hkv, Nq, Nk, D, W, S, P, seed):
+    tag = f"chunk B{B} Hq{Hq} Hkv{Hkv} Nq{Nq} Nk{Nk} D{D} W{W} S{S} P{P}"
+    print(f"[case] {tag} seed {seed}", flush=True)
+    q, k, v = make_qkv(B, Hq, Hkv, Nk, D, seed, n_query=Nq)
+    scale = 1 / math.sqrt(D)
+    out, lse = binding.swaa_attn_fwd_ex(to_device(q), to_device(k), to_device(v), W, S, P, scale)
+    torch.cuda.synchronize()
+    ro, rl = swaa_decode_oracle(q, k, v, W, S, scale, n_prompt=P)
+    assert_parity(out, lse, ro, rl, tag=tag)
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_chunks_of_a_longer_prefill(D):
+    # row tiles and key tiles out of phase (Nk - Nq not a multiple of 64), tiny and ragged chunks
+    for Nq, Nk in ((1, 1), (1, 200), (5, 70), (64, 128), (64, 129), (100, 777), (300, 333), (257, 1500)):
+        for W, S in ((1, 0), (50, 4), (64, 70), (Nk, 0)):
+            for P in (None, Nk - Nq // 2):
+                chunk_case(1, 4, 1, Nq, Nk, D, W, S, P, seed=8000 + Nq + Nk + D)
+    chunk_case(2, 10, 2, 150, 900, D, 200, 3, None, seed=8100 + D)
+
+
+def test_contiguous_arguments_equal_the_plain_call_bit_for_bit():
+    q, k, v = make_qkv(2, 6, 2, 700, 128, seed=81)
+    qd, kd, vd = to_device(q), to_device(k), to_device(v)
+    o0, l0 = binding.swaa_attn_fwd_fa_decode(qd, kd, vd, 100, 4, 650)
+    o1, l1 = binding.swaa_attn_fwd_ex(qd, kd, vd, 100, 4, 650)
+    torch.cuda.synchronize()
+    assert torch.equal(o0, o1) and torch.equal(l0, l1)
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_token_major_layout_and_slices(D):
+    # [B, N, H, D] tensors passed as permuted views; K and V as slices of one fused buffer
+    B, Hq, Hkv, N, W, S = 2, 8, 2, 500, 120, 4
+    q, k, v = make_qkv(B, Hq, Hkv, N, D, seed=82 + D)
+    ro, rl = swaa_attn_oracle(q, k, v, W, S, 1 / math.sqrt(D))
+    q_bnhd = to_device(q).permute(0, 2, 1, 3).contiguous()                      # memory order [B, N, Hq, D]
+    kv = torch.stack([to_device(k), to_device(v)], dim=0).permute(1, 3, 0, 2, 4).contiguous()  # [B, N, 2, Hkv, D]
+    k_view = kv[:, :, 0].permute(0, 2, 1, 3)   # [B, Hkv, N, D] view, row stride 2*Hkv*D
+    v_view = kv[:, :, 1].permute(0, 2, 1, 3)
+    out, lse = binding.swaa_attn_fwd_ex(q_bnhd.permute(0, 2, 1, 3), k_view, v_view, W, S)
+    torch.cuda.synchronize()
+    assert out.stride() == q_bnhd.permute(0, 2, 1, 3).stride()  # written in the caller's memory order
+    assert_parity(out.contiguous(), lse, ro, rl, tag=f"token-major layout D{D}")
+    # a window of heads and rows out of a larger allocation
+    big = torch.zeros((B, Hq + 2, N + 16, D), dtype=torch.bfloat16, device="cuda")
+    big[:, 1:1 + Hq, 8:8 + N] = to_device(q)
+    out2, lse2 = binding.swaa_attn_fwd_ex(big[:, 1:1 + Hq, 8:8 + N], to_device(k), to_device(v), W, S)
+    torch.cuda.synchronize()
+    assert torch.equal(out2.contiguous(), out.contiguous()) and torch.equal(lse2, lse)
+
+
+@pytest.mark.parametrize("D,chunked", [(128, False), (128, True), (64, True)])
+def test_packed_variable_length_batch(D, chunked):
+    Hq, Hkv, W, S = 8, 2, 100, 4
+    lens_k = [1, 63, 64, 65, 300, 1000, 2, 517]
+    lens_q = [max(1, n // 3) for n in lens_k] if chunked else list(lens_k)
+    rng = np.random.Generator(np.random.Philox(83 + D))
+    cu_q = np.concatenate([[0], np.cumsum(lens_q)]).astype(np.int32)
+    cu_k = np.concatenate([[0], np.cumsum(lens_k)]).astype(np.int32)
+    seqs = [make_qkv(1, Hq, Hkv, nk, D, int(rng.integers(1 << 30)), n_query=nq) for nq, nk in zip(lens_q, lens_k)]
+    # packed token-major buffers [T, H, D]
+    q_pack = torch.cat([to_device(s[0])[0].permute(1, 0, 2) for s in seqs], dim=0).contiguous()
+    k_pack = torch.cat([to_device(s[1])[0].permute(1, 0, 2) for s in seqs], dim=0).contiguous()
+    v_pack = torch.cat([to_device(s[2])[0].permute(1, 0, 2) for s in seqs], dim=0).contiguous()
+    P = None if not chunked else 400
+    out, lse = binding.swaa_attn_fwd_ex(
+        q_pack.permute(1, 0, 2), k_pack.permute(1, 0, 2), v_pack.permute(1, 0, 2), W, S, P,
+        cu_seqlens_q=torch.from_numpy(cu_q).cuda(), cu_seqlens_k=torch.from_numpy(cu_k).cuda(),
+        max_seqlen_q=max(lens_q), max_seqlen_k=max(lens_k))
+    torch.cuda.synchronize()
+    assert out.shape == (Hq, int(cu_q[-1]), D) and lse.shape == (Hq, int(cu_q[-1]))
+    for b, (qs, ks, vs) in enumerate(seqs):
+        ro, rl = swaa_decode_oracle(qs, ks, vs, W, S, 1 / math.sqrt(D), n_prompt=P)
+        o_b = out[:, cu_q[b]:cu_q[b + 1]].unsqueeze(0)
+        l_b = lse[:, cu_q[b]:cu_q[b + 1]].unsqueeze(0)
+        assert_parity(o_b, l_b, ro, rl, tag=f"packed seq {b}: Nq{lens_q[b]} Nk{lens_k[b]} D{D}")
+
+
+def test_chunk_against_a_long_cache_full_size():
+    # the benchmark's chunk workload, launched exactly as it is timed: one 2048-row chunk of a
+    # 128k-token prefill, window 8192 + 4 sinks, Hq 32 / Hkv 8; every output row is compared
+    from paper_2512_10411_amd.inputs import WORKLOADS, make_workload
+    w = WORKLOADS["chunk2k_128k_swa"]
+    print("[gen] chunk vs 128k cache ...", flush=True)
+    q, k, v = make_workload(w)
+    print("[gpu]", flush=True)
+    out, lse = binding.swaa_attn_fwd_ex(to_device(q), to_device(k), to_device(v), w.window, w.n_sink, w.n_prompt,
+                                        w.scale)
+    torch.cuda.synchronize()
+    print("[oracle]", flush=True)
+    ro, rl = swaa_decode_oracle(q, k, v, w.window, w.n_sink, w.scale)
+    assert_parity(out, lse, ro, rl, tag="2048-row chunk on a 128k cache")
