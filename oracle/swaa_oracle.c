@@ -263,3 +263,149 @@ int swaa_oracle_decode(const uint16_t *q, const uint16_t *k, const uint16_t *v,
     }
     return failed ? -2 : 0;
 }
+
+/*
+ * Backward pass of the one-pass forward above (SWA-aware fine-tuning, paper
+ * Sec. 3.2.2, trains through this mask).  With p_ij = exp(s_ij - lse_i) on
+ * Vis(i) (0 elsewhere) and the upstream gradient dO:
+ *
+ *   dV_j = sum_i p_ij dO_i
+ *   dP_ij = <dO_i, v_j>,   delta_i = sum_j p_ij dP_ij
+ *   dS_ij = p_ij (dP_ij - delta_i)
+ *   dQ_i = scale * sum_j dS_ij k_j,     dK_j = scale * sum_i dS_ij q_i
+ *
+ * (the derivative of softmax followed by the two products, written out; dK and
+ * dV of a KV head sum over the Hq/Hkv query heads that read it).  Two passes,
+ * each a plain loop: rows i for lse, delta and dQ; then key rows j for dK and
+ * dV, recomputing p_ij from the stored lse_i.  All arithmetic in double.
+ *
+ * dout: [B, Hq, N, D] bf16 bits.  dq: [B, Hq, N, D], dk, dv: [B, Hkv, N, D]
+ * doubles.  Returns 0, -1 on a bad argument, -2 when out of memory.
+ */
+int swaa_oracle_bwd(const uint16_t *q, const uint16_t *k, const uint16_t *v,
+                    const uint16_t *dout, int B, int Hq, int Hkv, int N, int D,
+                    long W, long S, long P, double scale, double *dq, double *dk,
+                    double *dv, int n_threads)
+{
+    if (!q || !k || !v || !dout || !dq || !dk || !dv)
+        return -1;
+    if (B < 1 || Hq < 1 || Hkv < 1 || N < 1 || D < 1 || Hq % Hkv || W < 1 || S < 0 || P < 0)
+        return -1;
+    const int G = Hq / Hkv;
+    const long rows = (long)B * Hq * N;
+    double *lse = (double *)malloc(sizeof(double) * (size_t)rows);
+    double *delta = (double *)malloc(sizeof(double) * (size_t)rows);
+    if (!lse || !delta) {
+        free(lse);
+        free(delta);
+        return -2;
+    }
+    int failed = 0;
+#ifdef _OPENMP
+    if (n_threads > 0)
+        omp_set_num_threads(n_threads);
+#else
+    (void)n_threads;
+#endif
+
+    /* pass 1: per query row */
+#pragma omp parallel
+    {
+        double *s = (double *)malloc(sizeof(double) * (size_t)N);
+        double *dp = (double *)malloc(sizeof(double) * (size_t)N);
+        if (!s || !dp) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(dynamic, 1)
+        for (long t = 0; t < rows; t++) {
+            if (!s || !dp)
+                continue;
+            const long i = t % N;
+            const long h = (t / N) % Hq;
+            const long b = t / ((long)N * Hq);
+            const long g = h / G;
+            const uint16_t *qi = q + (size_t)t * D;
+            const uint16_t *doi = dout + (size_t)t * D;
+            const uint16_t *kb = k + ((size_t)b * Hkv + g) * (size_t)N * D;
+            const uint16_t *vb = v + ((size_t)b * Hkv + g) * (size_t)N * D;
+            double m = -INFINITY;
+            for (long j = 0; j <= i; j++) {
+                if (!visible(i, j, W, S, P))
+                    continue;
+                double a = 0.0, c = 0.0;
+                for (int d = 0; d < D; d++) {
+                    a += bf16_to_double(qi[d]) * bf16_to_double(kb[(size_t)j * D + d]);
+                    c += bf16_to_double(doi[d]) * bf16_to_double(vb[(size_t)j * D + d]);
+                }
+                s[j] = scale * a;
+                dp[j] = c;
+                if (s[j] > m)
+                    m = s[j];
+            }
+            double l = 0.0;
+            for (long j = 0; j <= i; j++)
+                if (visible(i, j, W, S, P))
+                    l += exp(s[j] - m);
+            const double lse_i = m + log(l);
+            double del = 0.0;
+            for (long j = 0; j <= i; j++)
+                if (visible(i, j, W, S, P))
+                    del += exp(s[j] - lse_i) * dp[j];
+            lse[t] = lse_i;
+            delta[t] = del;
+            double *dqi = dq + (size_t)t * D;
+            for (int d = 0; d < D; d++)
+                dqi[d] = 0.0;
+            for (long j = 0; j <= i; j++) {
+                if (!visible(i, j, W, S, P))
+                    continue;
+                const double ds = exp(s[j] - lse_i) * (dp[j] - del);
+                for (int d = 0; d < D; d++)
+                    dqi[d] += scale * ds * bf16_to_double(kb[(size_t)j * D + d]);
+            }
+        }
+        free(s);
+        free(dp);
+    }
+
+    /* pass 2: per key row */
+    const long krows = (long)B * Hkv * N;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long t = 0; t < krows; t++) {
+        const long j = t % N;
+        const long g = (t / N) % Hkv;
+        const long b = t / ((long)N * Hkv);
+        const uint16_t *kj = k + (size_t)t * D;
+        const uint16_t *vj = v + (size_t)t * D;
+        double *dkj = dk + (size_t)t * D;
+        double *dvj = dv + (size_t)t * D;
+        for (int d = 0; d < D; d++) {
+            dkj[d] = 0.0;
+            dvj[d] = 0.0;
+        }
+        for (long h = g * G; h < (g + 1) * G; h++) {
+            for (long i = j; i < N; i++) {
+                if (!visible(i, j, W, S, P))
+                    continue;
+                const size_t r = ((size_t)b * Hq + h) * (size_t)N + i;
+                const uint16_t *qi = q + r * D;
+                const uint16_t *doi = dout + r * D;
+                double a = 0.0, c = 0.0;
+                for (int d = 0; d < D; d++) {
+                    a += bf16_to_double(qi[d]) * bf16_to_double(kj[d]);
+                    c += bf16_to_double(doi[d]) * bf16_to_double(vj[d]);
+                }
+                const double p = exp(scale * a - lse[r]);
+                const double ds = p * (c - delta[r]);
+                for (int d = 0; d < D; d++) {
+                    dvj[d] += p * bf16_to_double(doi[d]);
+                    dkj[d] += scale * ds * bf16_to_double(qi[d]);
+                }
+            }
+        }
+    }
+    free(lse);
+    free(delta);
+    return failed ? -2 : 0;
+}

@@ -72,6 +72,12 @@ def _load():
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_int]
+        lib.swaa_oracle_bwd.restype = ctypes.c_int
+        lib.swaa_oracle_bwd.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+            ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_double,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
         lib.swaa_oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -216,3 +222,22 @@ def swaa_decode_oracle_numpy(q, k, v, window, n_sink, scale, n_prompt=None):
                 out[b, h, r] = np.exp(s - lse_r) @ vf[b, g, vis]
                 lse[b, h, r] = lse_r
     return out, lse
+
+
+def swaa_attn_bwd_oracle(q, k, v, dout, window, n_sink, scale, n_prompt=None, n_threads=0):
+    """fp64 gradients of the one-pass forward (paper Sec. 3.2.2: fine-tuning trains through
+    the mask) via the C oracle.  dout: uint16 bf16 bits [B,Hq,N,D].  Returns
+    (dq [B,Hq,N,D], dk [B,Hkv,N,D], dv [B,Hkv,N,D]) float64."""
+    B, Hq, Hkv, N, D = _check(q, k, v)
+    if not isinstance(dout, np.ndarray) or dout.dtype != np.uint16 or dout.shape != q.shape:
+        raise TypeError("dout: expected uint16 (bf16 bits) ndarray shaped like q")
+    q, k, v, dout = (np.ascontiguousarray(a) for a in (q, k, v, dout))
+    dq = np.empty((B, Hq, N, D), dtype=np.float64)
+    dk = np.empty((B, Hkv, N, D), dtype=np.float64)
+    dv = np.empty((B, Hkv, N, D), dtype=np.float64)
+    rc = _load().swaa_oracle_bwd(q.ctypes.data, k.ctypes.data, v.ctypes.data, dout.ctypes.data, B, Hq, Hkv, N, D,
+                                 int(window), int(n_sink), N if n_prompt is None else int(n_prompt), float(scale),
+                                 dq.ctypes.data, dk.ctypes.data, dv.ctypes.data, int(n_threads))
+    if rc != 0:
+        raise ValueError(f"swaa_oracle_bwd failed with code {rc}")
+    return dq, dk, dv
