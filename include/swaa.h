@@ -192,6 +192,40 @@ int swaa_attn_decode(const void *q, const void *k, const void *v, void *out, flo
  */
 long long swaa_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Nq, int Nk, int D, int window, int n_sink);
 
+/*
+ * Backward pass of swaa_attn_fwd_fa_decode (and, with n_prompt >= N, of
+ * swaa_attn_fwd): the gradients that fine-tuning under the sliding-window mask
+ * (paper Sec. 3.2.2, with the structural masks of Sec. 3.1.1 and Sec. 3.2.1
+ * applied during training) needs.  With P_ij = exp(s_ij - lse[i]) for j in
+ * Vis(i) and 0 elsewhere, and dout the gradient with respect to out:
+ *
+ *     dv[j] = sum_i P_ij dout[i]
+ *     dS_ij = P_ij ( <dout[i], v[j]> - <dout[i], out[i]> )
+ *     dq[i] = scale * sum_j dS_ij k[j]        dk[j] = scale * sum_i dS_ij q[i]
+ *
+ * where dk and dv of a KV head sum over the Hq/Hkv query heads that read it.
+ *
+ *   q, k, v, out, lse   the forward call's inputs and results (same layouts)
+ *   dout                device, bf16 [B, Hq, N, D], contiguous, read only
+ *   dq                  device, bf16 [B, Hq,  N, D], written
+ *   dk, dv              device, bf16 [B, Hkv, N, D], written
+ *   D                   64 or 128; window, n_sink, n_prompt, scale, stream as in the forward call
+ *   workspace           device scratch memory owned by the caller, 16-byte aligned, at
+ *                       least swaa_attn_bwd_workspace_bytes(B, Hq, N) bytes; calls that may
+ *                       overlap on the device need separate workspaces
+ *
+ * bf16 tensors 16-byte aligned; P and dS are rounded to bf16 before the second
+ * products, all sums are fp32.  Deterministic (no atomics).  The library
+ * allocates nothing.  Returns SWAA_OK or a negative swaa_status.
+ */
+int swaa_attn_bwd(const void *q, const void *k, const void *v, const void *out, const float *lse,
+                  const void *dout, void *dq, void *dk, void *dv,
+                  int B, int Hq, int Hkv, int N, int D, int window, int n_sink, int n_prompt,
+                  float scale, void *workspace, long long workspace_bytes, void *stream);
+
+/* Bytes of workspace swaa_attn_bwd needs (one float per query row), or a negative swaa_status. */
+long long swaa_attn_bwd_workspace_bytes(int B, int Hq, int N);
+
 /* Static description of a status code; never NULL, never freed. */
 const char *swaa_status_string(int status);
 

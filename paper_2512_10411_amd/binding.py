@@ -25,7 +25,8 @@ SWAA_ERR_WORKSPACE = -6
 # every symbol include/swaa.h declares
 EXPORTS = ("swaa_attn_fwd", "swaa_attn_fwd_fa_decode", "swaa_attn_fwd_ex", "swaa_visible_pairs",
            "swaa_visible_pairs_fa_decode",
-           "swaa_attn_decode", "swaa_attn_decode_workspace_bytes", "swaa_status_string", "swaa_version")
+           "swaa_attn_decode", "swaa_attn_decode_workspace_bytes", "swaa_attn_bwd", "swaa_attn_bwd_workspace_bytes",
+           "swaa_status_string", "swaa_version")
 
 _lib = None
 
@@ -85,6 +86,11 @@ def load_library() -> ctypes.CDLL:
         ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_void_p, ctypes.c_longlong, ctypes.c_void_p]
     lib.swaa_attn_decode_workspace_bytes.restype = ctypes.c_longlong
     lib.swaa_attn_decode_workspace_bytes.argtypes = [ctypes.c_int] * 8
+    lib.swaa_attn_bwd.restype = ctypes.c_int
+    lib.swaa_attn_bwd.argtypes = [ctypes.c_void_p] * 9 + [ctypes.c_int] * 8 + [
+        ctypes.c_float, ctypes.c_void_p, ctypes.c_longlong, ctypes.c_void_p]
+    lib.swaa_attn_bwd_workspace_bytes.restype = ctypes.c_longlong
+    lib.swaa_attn_bwd_workspace_bytes.argtypes = [ctypes.c_int] * 3
     lib.swaa_status_string.restype = ctypes.c_char_p
     lib.swaa_status_string.argtypes = [ctypes.c_int]
     lib.swaa_version.restype = ctypes.c_int
@@ -332,3 +338,56 @@ def swaa_attn_fwd_ex(q, k, v, window: int, n_sink: int, n_prompt: int | None = N
     if rc != SWAA_OK:
         raise SwaaError(rc, swaa_status_string(rc))
     return out, lse
+
+
+def swaa_attn_bwd_workspace_bytes(B, Hq, N) -> int:
+    r = int(load_library().swaa_attn_bwd_workspace_bytes(int(B), int(Hq), int(N)))
+    if r < 0:
+        raise SwaaError(r, swaa_status_string(r))
+    return r
+
+
+def swaa_attn_bwd_raw(q, k, v, out, lse, dout, dq, dk, dv, B, Hq, Hkv, N, D, window, n_sink, n_prompt, scale,
+                      ws_ptr, ws_bytes, stream_ptr) -> int:
+    """The C call itself, on raw addresses; returns the status code."""
+    return int(load_library().swaa_attn_bwd(q, k, v, out, lse, dout, dq, dk, dv, B, Hq, Hkv, N, D, window, n_sink,
+                                            n_prompt, scale, ws_ptr, ws_bytes, stream_ptr))
+
+
+def swaa_attn_bwd(q, k, v, out, lse, dout, window: int, n_sink: int, n_prompt: int | None = None,
+                  scale: float | None = None, workspace=None, stream=None):
+    """Gradients (dq, dk, dv) of the forward call with the same mask arguments.
+
+    q, out, dout: bf16 [B, Hq, N, D]; k, v: bf16 [B, Hkv, N, D]; lse: fp32 [B, Hq, N]; all
+    contiguous GPU tensors (out and lse as the forward call returned them).
+    """
+    import torch
+
+    for name, t in (("q", q), ("k", k), ("v", v), ("out", out), ("dout", dout)):
+        if t.dtype != torch.bfloat16 or not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
+            raise ValueError(f"{name} must be a contiguous bf16 [B, H, N, D] GPU tensor")
+    B, Hq, N, D = q.shape
+    Hkv = k.shape[1]
+    if k.shape != v.shape or k.shape != (B, Hkv, N, D) or out.shape != q.shape or dout.shape != q.shape:
+        raise ValueError("shape mismatch between q, k, v, out and dout")
+    if lse.shape != (B, Hq, N) or lse.dtype != torch.float32 or not lse.is_contiguous():
+        raise ValueError("lse must be a contiguous fp32 [B, Hq, N] tensor")
+    if scale is None:
+        scale = 1.0 / math.sqrt(D)
+    need = swaa_attn_bwd_workspace_bytes(B, Hq, N)
+    with torch.cuda.device(q.device):
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+        if workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        if workspace.dtype != torch.uint8 or not workspace.is_cuda or not workspace.is_contiguous():
+            raise ValueError("workspace must be a contiguous uint8 tensor on the GPU")
+        if stream is None:
+            stream = torch.cuda.current_stream(q.device)
+        sptr = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+        rc = swaa_attn_bwd_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                               dout.data_ptr(), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), B, Hq, Hkv, N, D,
+                               int(window), int(n_sink), 2**31 - 1 if n_prompt is None else int(n_prompt),
+                               float(scale), workspace.data_ptr(), workspace.numel(), sptr)
+    if rc != SWAA_OK:
+        raise SwaaError(rc, swaa_status_string(rc))
+    return dq, dk, dv

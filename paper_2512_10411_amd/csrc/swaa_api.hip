@@ -7,6 +7,7 @@
 
 #include "swaa.h"
 #include "swaa_common.h"
+#include "swaa_bwd.h"
 #include "swaa_decode.h"
 
 using swaa::FwdParams;
@@ -69,7 +70,7 @@ const char *swaa_status_string(int status) {
     }
 }
 
-int swaa_version(void) { return 120; }
+int swaa_version(void) { return 130; }
 
 namespace {
 
@@ -223,6 +224,61 @@ int swaa_attn_decode(const void *q, const void *k, const void *v, void *out, flo
     p.ws_ml = p.ws_o + p.items * (long long)p.col_stride * 128;
     p.scale_log2 = scale * 1.44269504088896340736f;
     const hipError_t err = swaa::launch_decode(p, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? SWAA_OK : SWAA_ERR_LAUNCH;
+}
+
+long long swaa_attn_bwd_workspace_bytes(int B, int Hq, int N) {
+    if (B < 1 || Hq < 1 || N < 1) return SWAA_ERR_SHAPE;
+    return (long long)B * Hq * N * (long long)sizeof(float);
+}
+
+int swaa_attn_bwd(const void *q, const void *k, const void *v, const void *out, const float *lse,
+                  const void *dout, void *dq, void *dk, void *dv,
+                  int B, int Hq, int Hkv, int N, int D, int window, int n_sink, int n_prompt,
+                  float scale, void *workspace, long long workspace_bytes, void *stream) {
+    if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv) return SWAA_ERR_NULL;
+    if (B < 1 || Hq < 1 || Hkv < 1 || N < 1 || D < 1) return SWAA_ERR_SHAPE;
+    if (Hq % Hkv != 0) return SWAA_ERR_SHAPE;
+    if (window < 1 || n_sink < 0 || n_prompt < 0) return SWAA_ERR_SHAPE;
+    if (!positive_finite(scale)) return SWAA_ERR_SHAPE;
+    if (D != 64 && D != 128) return SWAA_ERR_UNSUPPORTED;
+    for (const void *ptr : {q, k, v, out, dout, (const void *)dq, (const void *)dk, (const void *)dv})
+        if (misaligned(ptr)) return SWAA_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(lse) & 3u) != 0) return SWAA_ERR_ALIGN;
+    if (!workspace || misaligned(workspace) || workspace_bytes < swaa_attn_bwd_workspace_bytes(B, Hq, N))
+        return SWAA_ERR_WORKSPACE;
+
+    swaa::BwdParams p{};
+    FwdParams &f = p.f;
+    f.q = static_cast<const __bf16 *>(q);
+    f.k = static_cast<const __bf16 *>(k);
+    f.v = static_cast<const __bf16 *>(v);
+    f.lse = const_cast<float *>(lse);
+    f.B = B; f.Hq = Hq; f.Hkv = Hkv; f.Nq = N; f.Nk = N;
+    f.W = window < N ? window : N;
+    f.S = n_sink < N ? n_sink : N;
+    f.P = n_prompt < N ? n_prompt : N;
+    f.G = Hq / Hkv;
+    f.scale = scale;
+    f.scale_log2 = scale * 1.44269504088896340736f;
+    f.n4 = f.G / 4;
+    f.has2 = (f.G % 4) >= 2 ? 1 : 0;
+    f.has1 = f.G % 2;
+    f.nt64 = (N + 63) / 64;
+    f.nt128 = (N + 127) / 128;
+    f.nt256 = (N + 255) / 256;
+    f.tiles_per_pair = f.n4 * f.nt64 + f.has2 * f.nt128 + f.has1 * f.nt256;
+    f.total_items = (long long)B * Hkv * f.tiles_per_pair;
+    f.chunk = (f.total_items + kXcds - 1) / kXcds;
+    if (f.chunk * kXcds > 0x7fffffffLL || (long long)B * Hq * N > 0x7fffffffLL * 16) return SWAA_ERR_SHAPE;
+    p.out = static_cast<const __bf16 *>(out);
+    p.dout = static_cast<const __bf16 *>(dout);
+    p.dq = static_cast<__bf16 *>(dq);
+    p.dk = static_cast<__bf16 *>(dk);
+    p.dv = static_cast<__bf16 *>(dv);
+    p.delta = static_cast<float *>(workspace);
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N;
+    const hipError_t err = swaa::launch_bwd(p, D, static_cast<hipStream_t>(stream));
     return err == hipSuccess ? SWAA_OK : SWAA_ERR_LAUNCH;
 }
 

@@ -1,0 +1,475 @@
+// Backward pass of the SWA + sink (+ FA Decode rows) attention, gfx950: the
+// gradients that SWA-aware fine-tuning (paper Sec. 3.2.2) needs, under the same
+// mask as the forward kernels (Sec. 3.2.1 / Fig. 1b, Sec. 3.1.1 / Fig. 1a).
+//
+// With P_ij = exp(s_ij - lse_i) on the visible pairs and 0 elsewhere:
+//
+//   delta_i = <dO_i, O_i>                      (= sum_j P_ij dP_ij)
+//   dV_j = sum_i P_ij dO_i                     dP_ij = <dO_i, v_j>
+//   dS_ij = P_ij (dP_ij - delta_i)
+//   dQ_i = scale sum_j dS_ij k_j               dK_j = scale sum_i dS_ij q_i
+//
+// Three kernels, no atomics, results independent of scheduling:
+//   * swaa_bwd_delta_kernel: delta, one pass over dO and O.
+//   * swaa_bwd_dq_kernel: a workgroup owns 256 query rows (the forward's work
+//     decomposition and tile schedule), walks its visible KV tiles, recomputes
+//     S^T = K Q^T and dP^T = V dO^T and accumulates dQ^T += K^T dS^T.
+//   * swaa_bwd_dkv_kernel: a workgroup owns 128 keys of one KV head (32 per
+//     wave), walks every query head of the GQA group and every 64-row query
+//     tile that can see them, recomputes S = Q K^T and dP = dO V^T and
+//     accumulates dV^T += dO^T P and dK^T += Q^T dS.
+// Each product is a v_mfma_f32_32x32x16_bf16 with the accumulator oriented so
+// that the probabilities come out in the B-operand layout of the product that
+// consumes them (as in the forward kernels); operands that a product needs
+// transposed are read from row-major LDS tiles with ds_read_b64_tr_b16.
+// P and dS are rounded to bf16 before the second products, sums are fp32.
+// This first version stages tiles through registers and leaves instruction
+// scheduling to the compiler.
+#include <cmath>
+
+#include "swaa_bwd.h"
+
+namespace swaa {
+namespace {
+
+constexpr int kBq = 64;  // query rows per tile of the dK/dV kernel
+
+template <int D>
+struct BTile {
+    static constexpr int kChunksPerRow = D / 8;
+    static constexpr int kChunksPerThread = kBk * kChunksPerRow / kThreads;  // 64-row tile, 256 threads
+    static constexpr int kStride = D + 8;  // bf16 elements per LDS row
+    static constexpr int kElems = kBk * kStride;
+};
+
+// A operand "rows of the tile x 16 of the head dimension": row 32*rb + lane%32, elements 16*ks + 8*(lane/32) ..
+template <int D>
+__device__ __forceinline__ bf16x8 row_frag(const __bf16 *tile, int rb, int ks, int l32, int hf) {
+    return *reinterpret_cast<const bf16x8 *>(&tile[(32 * rb + l32) * BTile<D>::kStride + 16 * ks + 8 * hf]);
+}
+
+// A operand "32 of the head dimension x 16 tile rows" (the tile transposed): head-dimension block db,
+// tile rows 32*rb + 16*st + 4*(lane/32) + {0..3, 8..11} -- the order in which a 32x32 accumulator hands
+// its rows to the next product as a B operand.
+template <int D>
+__device__ __forceinline__ bf16x8 col_frag(const __bf16 *tile, int rb, int st, int db, int lane) {
+    const int hf = lane >> 5, grp = lane >> 4, j16 = lane & 15;
+    const int row = 32 * rb + 16 * st + 4 * hf + (j16 >> 2);
+    const int col = 32 * db + 16 * (grp & 1) + 4 * (j16 & 3);
+    const __bf16 *a0 = &tile[row * BTile<D>::kStride + col];
+    const __bf16 *a1 = a0 + 8 * BTile<D>::kStride;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(a0));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(a1));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+__device__ __forceinline__ bool visible(int i, int j, int W, int S, int P) {
+    return (j <= i) && ((i >= P) || (j > i - W) || (j < S));
+}
+
+// ---- delta_i = <dO_i, O_i> ---------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kThreads) void swaa_bwd_delta_kernel(const BwdParams p) {
+    constexpr int L = D / 8;  // lanes per row
+    const long long rows = (long long)p.B * p.Hq * p.N;
+    const long long row = (long long)blockIdx.x * (kThreads / L) + threadIdx.x / L;
+    const int c = threadIdx.x % L;
+    float acc = 0.f;
+    if (row < rows) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(p.dout + row * D + 8 * c);
+        const bf16x8 b = *reinterpret_cast<const bf16x8 *>(p.out + row * D + 8 * c);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc += (float)a[e] * (float)b[e];
+    }
+#pragma unroll
+    for (int w = L / 2; w > 0; w >>= 1) acc += __shfl_xor(acc, w, L);
+    if (row < rows && c == 0) p.delta[row] = acc;
+}
+
+// ---- dQ ------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dq_kernel(const BwdParams p) {
+    using T = BTile<D>;
+    constexpr int KS = D / 16, DB = D / 32;
+    __shared__ __attribute__((aligned(16))) __bf16 Ks[T::kElems];
+    __shared__ __attribute__((aligned(16))) __bf16 Vs[T::kElems];
+
+    WorkItem wi;
+    if (!decode_work(p.f, wi)) return;
+    const int hpb = wi.hpb;
+    const int rows_per_wg = kWgRows / hpb;
+    const int N = p.N, W = p.f.W, S = p.f.S, P = p.f.P;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
+
+    const int head = wi.kvh * p.f.G + wi.h0 + (wave % hpb);
+    const int wg_p0 = wi.pt * rows_per_wg;
+    const int wg_p1 = min(N, wg_p0 + rows_per_wg) - 1;
+    const int p0 = wg_p0 + (wave / hpb) * kWaveRows;
+    const bool wave_active = p0 < N;
+    const int plast = min(p0 + kWaveRows, N) - 1;
+
+    const int band_lo = (wg_p1 >= P) ? 0 : max(0, wg_p0 - W + 1);
+    const int t_band_lo = band_lo / kBk;
+    const int t_hi = wg_p1 / kBk;
+    const int n_sink_tiles = min((min(S, band_lo) + kBk - 1) / kBk, t_band_lo);
+    const int wbound = window_bound(p0, kWaveRows, W, P);
+
+    const size_t kv_base = ((size_t)wi.b * p.Hkv + wi.kvh) * (size_t)N * D;
+    const __bf16 *kg = p.f.k + kv_base;
+    const __bf16 *vg = p.f.v + kv_base;
+    const size_t q_base = ((size_t)wi.b * p.Hq + head) * (size_t)N * D;
+    const size_t r_base = ((size_t)wi.b * p.Hq + head) * (size_t)N;
+
+    // this wave's Q and dO rows as B operands, its rows' lse (log2 units) and delta
+    bf16x8 qf[2][KS], dof[2][KS];
+    float lse2[2], dl[2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        const int row = min(p0 + 32 * qb + l32, N - 1);
+        const __bf16 *qs = p.f.q + q_base + (size_t)row * D + 8 * hf;
+        const __bf16 *ds = p.dout + q_base + (size_t)row * D + 8 * hf;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            qf[qb][ks] = *reinterpret_cast<const bf16x8 *>(qs + 16 * ks);
+            dof[qb][ks] = *reinterpret_cast<const bf16x8 *>(ds + 16 * ks);
+        }
+        lse2[qb] = p.f.lse[r_base + row] * 1.44269504088896340736f;
+        dl[qb] = p.delta[r_base + row];
+    }
+
+    f32x16 dqacc[DB][2];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) dqacc[db][qb][e] = 0.f;
+
+    u32x4 kreg[T::kChunksPerThread], vreg[T::kChunksPerThread];
+    auto load_tile = [&](int t) {
+#pragma unroll
+        for (int c = 0; c < T::kChunksPerThread; ++c) {
+            const int id = c * kThreads + tid;
+            const int row = min(t * kBk + id / T::kChunksPerRow, N - 1);
+            const int col = (id % T::kChunksPerRow) * 8;
+            kreg[c] = *reinterpret_cast<const u32x4 *>(kg + (size_t)row * D + col);
+            vreg[c] = *reinterpret_cast<const u32x4 *>(vg + (size_t)row * D + col);
+        }
+    };
+    auto store_tile = [&]() {
+#pragma unroll
+        for (int c = 0; c < T::kChunksPerThread; ++c) {
+            const int id = c * kThreads + tid;
+            const int row = id / T::kChunksPerRow;
+            const int col = (id % T::kChunksPerRow) * 8;
+            *reinterpret_cast<u32x4 *>(&Ks[row * T::kStride + col]) = kreg[c];
+            *reinterpret_cast<u32x4 *>(&Vs[row * T::kStride + col]) = vreg[c];
+        }
+    };
+    auto next_tile = [&](int t) {
+        int n = t + 1;
+        if (n == n_sink_tiles && n < t_band_lo) n = t_band_lo;
+        return n;
+    };
+
+    int t = (n_sink_tiles > 0) ? 0 : t_band_lo;
+    load_tile(t);
+    store_tile();
+    __syncthreads();
+    const float c2 = p.f.scale_log2;
+
+    while (true) {
+        const int tn = next_tile(t);
+        const bool has_next = tn <= t_hi;
+        if (has_next) load_tile(tn);
+
+        const int k0 = t * kBk, k_last = k0 + kBk - 1;
+        const bool in_future = k0 > plast;
+        const bool before_band = (plast < P) && (k_last < p0 - W + 1) && (k0 >= S);
+        if (wave_active && !in_future && !before_band) {
+            const bool unmasked = (k_last <= p0) && ((k0 > wbound) || (k_last < S));
+
+            // S^T = K Q^T and dP^T = V dO^T : [64 keys] x [64 queries]
+            f32x16 sacc[2][2], dpacc[2][2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        sacc[kb][qb][e] = 0.f;
+                        dpacc[kb][qb][e] = 0.f;
+                    }
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb) {
+                    const bf16x8 ka = row_frag<D>(Ks, kb, ks, l32, hf);
+                    const bf16x8 va = row_frag<D>(Vs, kb, ks, l32, hf);
+#pragma unroll
+                    for (int qb = 0; qb < 2; ++qb) {
+                        sacc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[qb][ks], sacc[kb][qb], 0, 0, 0);
+                        dpacc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, dof[qb][ks], dpacc[kb][qb], 0, 0, 0);
+                    }
+                }
+
+            // P^T = exp2(s c2 - lse2) on visible pairs, dS^T = P^T (dP^T - delta), packed to bf16
+            bf16x8 dsf[2][2][2];  // [kb][qb][16-key step]
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                const int qpos = p0 + 32 * qb + l32;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int key = k0 + 32 * kb + 8 * (e / 4) + 4 * hf + (e % 4);
+                        float pe = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][e], c2, -lse2[qb]));
+                        if (!unmasked && !visible(qpos, key, W, S, P)) pe = 0.f;
+                        dsf[kb][qb][e / 8][e % 8] = (__bf16)(pe * (dpacc[kb][qb][e] - dl[qb]));
+                    }
+            }
+
+            // dQ^T += K^T dS^T
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int st = 0; st < 2; ++st)
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) {
+                        const bf16x8 a = col_frag<D>(Ks, kb, st, db, lane);
+#pragma unroll
+                        for (int qb = 0; qb < 2; ++qb)
+                            dqacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, dsf[kb][qb][st], dqacc[db][qb], 0, 0, 0);
+                    }
+        }
+
+        if (!has_next) break;
+        __syncthreads();
+        store_tile();
+        __syncthreads();
+        t = tn;
+    }
+
+    if (!wave_active) return;
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        const int row = p0 + 32 * qb + l32;
+        if (row >= N) continue;
+        __bf16 *orow = p.dq + q_base + (size_t)row * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int e4 = 0; e4 < 4; ++e4) {
+                bf16x4 o4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(dqacc[db][qb][4 * e4 + e] * p.f.scale);
+                *reinterpret_cast<bf16x4 *>(orow + 32 * db + 8 * e4 + 4 * hf) = o4;
+            }
+    }
+}
+
+// ---- dK, dV --------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dkv_kernel(const BwdParams p) {
+    using T = BTile<D>;
+    constexpr int KS = D / 16, DB = D / 32;
+    __shared__ __attribute__((aligned(16))) __bf16 Qs[T::kElems];
+    __shared__ __attribute__((aligned(16))) __bf16 dOs[T::kElems];
+    __shared__ __attribute__((aligned(16))) float Ls[kBq];   // lse of the tile's rows, log2 units
+    __shared__ __attribute__((aligned(16))) float Dls[kBq];  // their delta
+
+    const int N = p.N, W = p.f.W, S = p.f.S, P = p.f.P, G = p.f.G;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
+    // key tiles of 128: the first ones are seen by the most rows under a causal mask, they go first
+    const int n_kt = (N + 127) / 128;
+    const int kt = blockIdx.x % n_kt;
+    const int pair = blockIdx.x / n_kt;
+    const int b = pair / p.Hkv, kvh = pair % p.Hkv;
+    const int k0 = kt * 128, k1 = min(k0 + 127, N - 1);  // the workgroup's keys
+    const int kw0 = k0 + 32 * wave, kw1 = kw0 + 31;       // this wave's keys
+    const int key = kw0 + l32;                            // this lane's key column
+    const bool wave_active = kw0 < N;
+
+    // the wave's K and V rows as B operands
+    bf16x8 kf[KS], vf[KS];
+    {
+        const size_t kv_row = (((size_t)b * p.Hkv + kvh) * (size_t)N + min(key, N - 1)) * D + 8 * hf;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            kf[ks] = *reinterpret_cast<const bf16x8 *>(p.f.k + kv_row + 16 * ks);
+            vf[ks] = *reinterpret_cast<const bf16x8 *>(p.f.v + kv_row + 16 * ks);
+        }
+    }
+    f32x16 dkacc[DB], dvacc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            dkacc[db][e] = 0.f;
+            dvacc[db][e] = 0.f;
+        }
+
+    // query tiles (64 rows) with a row that sees one of the workgroup's keys: the band tiles
+    // tq_lo .. tq_band_hi, then -- if a key is a sink, or there are generated rows -- the rest
+    const int tq_last = (N - 1) / kBq;
+    const int tq_lo = k0 / kBq;
+    const int tq_band_hi = min(N - 1, k1 + W - 1) / kBq;
+    int tq_x = tq_last + 1;  // first tile of the second range
+    if (k0 < S) tq_x = tq_band_hi + 1;
+    else if (P < N) tq_x = max(tq_band_hi + 1, P / kBq);
+    const int n_band = tq_band_hi - tq_lo + 1;
+    const int n_tiles = n_band + max(0, tq_last - tq_x + 1);
+    auto tile_of = [&](int n) { return n < n_band ? tq_lo + n : tq_x + (n - n_band); };
+
+    const float c2 = p.f.scale_log2;
+    u32x4 qreg[T::kChunksPerThread], dreg[T::kChunksPerThread];
+    float lreg = 0.f, dlreg = 0.f;
+    auto load_tile = [&](int head, int tq) {
+        const size_t base = ((size_t)b * p.Hq + head) * (size_t)N;
+#pragma unroll
+        for (int c = 0; c < T::kChunksPerThread; ++c) {
+            const int id = c * kThreads + tid;
+            const int row = min(tq * kBq + id / T::kChunksPerRow, N - 1);
+            const int col = (id % T::kChunksPerRow) * 8;
+            qreg[c] = *reinterpret_cast<const u32x4 *>(p.f.q + (base + row) * D + col);
+            dreg[c] = *reinterpret_cast<const u32x4 *>(p.dout + (base + row) * D + col);
+        }
+        if (tid < kBq) {
+            const int row = min(tq * kBq + tid, N - 1);
+            lreg = p.f.lse[base + row] * 1.44269504088896340736f;
+            dlreg = p.delta[base + row];
+        }
+    };
+    auto store_tile = [&]() {
+#pragma unroll
+        for (int c = 0; c < T::kChunksPerThread; ++c) {
+            const int id = c * kThreads + tid;
+            const int row = id / T::kChunksPerRow;
+            const int col = (id % T::kChunksPerRow) * 8;
+            *reinterpret_cast<u32x4 *>(&Qs[row * T::kStride + col]) = qreg[c];
+            *reinterpret_cast<u32x4 *>(&dOs[row * T::kStride + col]) = dreg[c];
+        }
+        if (tid < kBq) {
+            Ls[tid] = lreg;
+            Dls[tid] = dlreg;
+        }
+    };
+
+    const int total = G * n_tiles;  // (head, tile) steps, head-major
+    int step = 0;
+    load_tile(kvh * G, tile_of(0));
+    store_tile();
+    __syncthreads();
+
+    while (true) {
+        const bool has_next = step + 1 < total;
+        if (has_next) load_tile(kvh * G + (step + 1) / n_tiles, tile_of((step + 1) % n_tiles));
+
+        const int tq = tile_of(step % n_tiles);
+        const int i0 = tq * kBq, i1 = i0 + kBq - 1;
+        // can any row of the tile see any key of this wave?
+        const bool sees = (i1 >= kw0) && ((i0 < kw1 + W) || (kw0 < S) || (i1 >= P));
+        if (wave_active && sees) {
+            // all 64 x 32 pairs visible: rows at or below the keys' diagonal, inside every row's window
+            // (or the keys are sinks, or the rows are generated tokens), and no row past the end
+            const bool unmasked = (kw1 <= i0) && (i1 < N) && ((i1 - kw0 < W) || (kw1 < S) || (i0 >= P));
+
+            // S = Q K^T and dP = dO V^T : [64 queries] x [32 keys]
+            f32x16 sacc[2], dpacc[2];
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    sacc[qb][e] = 0.f;
+                    dpacc[qb][e] = 0.f;
+                }
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int qb = 0; qb < 2; ++qb) {
+                    sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag<D>(Qs, qb, ks, l32, hf), kf[ks], sacc[qb], 0, 0, 0);
+                    dpacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag<D>(dOs, qb, ks, l32, hf), vf[ks], dpacc[qb], 0, 0, 0);
+                }
+
+            // P and dS in the accumulator layout (row 32 qb + 8 (e/4) + 4 hf + e%4, column = this lane's key)
+            bf16x8 pf[2][2], dsf[2][2];  // [qb][16-row step]
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    const int r4 = 32 * qb + 8 * e4 + 4 * hf;
+                    const float4 l4 = *reinterpret_cast<const float4 *>(&Ls[r4]);
+                    const float4 d4 = *reinterpret_cast<const float4 *>(&Dls[r4]);
+                    const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+                    const float dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        const int e = 4 * e4 + x;
+                        const int row = i0 + r4 + x;
+                        float pe = __builtin_amdgcn_exp2f(fmaf(sacc[qb][e], c2, -lv[x]));
+                        if (!unmasked && !(row < N && visible(row, key, W, S, P))) pe = 0.f;
+                        pf[qb][e / 8][e % 8] = (__bf16)pe;
+                        dsf[qb][e / 8][e % 8] = (__bf16)(pe * (dpacc[qb][e] - dv4[x]));
+                    }
+                }
+
+            // dV^T += dO^T P,  dK^T += Q^T dS
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                for (int st = 0; st < 2; ++st)
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) {
+                        dvacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(col_frag<D>(dOs, qb, st, db, lane), pf[qb][st], dvacc[db], 0, 0, 0);
+                        dkacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(col_frag<D>(Qs, qb, st, db, lane), dsf[qb][st], dkacc[db], 0, 0, 0);
+                    }
+        }
+
+        if (!has_next) break;
+        __syncthreads();
+        store_tile();
+        __syncthreads();
+        ++step;
+    }
+
+    if (key < N) {
+        const size_t row = (((size_t)b * p.Hkv + kvh) * (size_t)N + key) * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int e4 = 0; e4 < 4; ++e4) {
+                bf16x4 k4, v4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    k4[e] = (__bf16)(dkacc[db][4 * e4 + e] * p.f.scale);
+                    v4[e] = (__bf16)dvacc[db][4 * e4 + e];
+                }
+                *reinterpret_cast<bf16x4 *>(p.dk + row + 32 * db + 8 * e4 + 4 * hf) = k4;
+                *reinterpret_cast<bf16x4 *>(p.dv + row + 32 * db + 8 * e4 + 4 * hf) = v4;
+            }
+    }
+}
+
+template <int D>
+hipError_t launch_bwd_d(const BwdParams &p, hipStream_t stream) {
+    const long long rows = (long long)p.B * p.Hq * p.N;
+    const int rows_per_block = kThreads / (D / 8);
+    hipLaunchKernelGGL(swaa_bwd_delta_kernel<D>, dim3((unsigned)((rows + rows_per_block - 1) / rows_per_block)),
+                       dim3(kThreads), 0, stream, p);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(swaa_bwd_dq_kernel<D>, dim3((unsigned)(p.f.chunk * kXcds)), dim3(kThreads), 0, stream, p);
+    err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    const long long n_kt = (p.N + 127) / 128;
+    hipLaunchKernelGGL(swaa_bwd_dkv_kernel<D>, dim3((unsigned)(n_kt * p.B * p.Hkv)), dim3(kThreads), 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_bwd(const BwdParams &p, int D, hipStream_t stream) {
+    return D == 128 ? launch_bwd_d<128>(p, stream) : launch_bwd_d<64>(p, stream);
+}
+
+}  // namespace swaa

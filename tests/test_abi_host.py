@@ -160,3 +160,30 @@ def test_general_forward_argument_errors():
     assert call(cu_seqlens_q=p, cu_seqlens_k=p + 2) == binding.SWAA_ERR_ALIGN
     assert call(D=96) == binding.SWAA_ERR_UNSUPPORTED
     assert call(**{"k.ptr": p + 8}) == binding.SWAA_ERR_ALIGN
+
+
+def test_backward_argument_errors():
+    assert binding.swaa_attn_bwd_workspace_bytes(2, 8, 1000) == 2 * 8 * 1000 * 4
+    with pytest.raises(binding.SwaaError):
+        binding.swaa_attn_bwd_workspace_bytes(0, 8, 1000)
+    p = 4096  # fake aligned address; never dereferenced on these paths
+    f = binding.swaa_attn_bwd_raw
+    ok = [p] * 9 + [1, 4, 2, 128, 128, 16, 2, 128, 0.1, p, 1 << 20, None]
+
+    def call(**kw):
+        a = list(ok)
+        names = ["q", "k", "v", "out", "lse", "dout", "dq", "dk", "dv", "B", "Hq", "Hkv", "N", "D", "window", "n_sink",
+                 "n_prompt", "scale", "ws", "wb", "stream"]
+        for key, val in kw.items():
+            a[names.index(key)] = val
+        return f(*a)
+
+    assert call(dout=None) == binding.SWAA_ERR_NULL
+    assert call(dk=None) == binding.SWAA_ERR_NULL
+    assert call(Hq=3) == binding.SWAA_ERR_SHAPE
+    assert call(n_prompt=-1) == binding.SWAA_ERR_SHAPE
+    assert call(scale=0.0) == binding.SWAA_ERR_SHAPE
+    assert call(D=96) == binding.SWAA_ERR_UNSUPPORTED
+    assert call(dq=p + 8) == binding.SWAA_ERR_ALIGN
+    assert call(ws=None) == binding.SWAA_ERR_WORKSPACE
+    assert call(wb=4 * 128 * 4 - 1) == binding.SWAA_ERR_WORKSPACE
