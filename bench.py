@@ -88,6 +88,29 @@ def cpu_baseline_decode(w, q, k, v):
     }
 
 
+def cpu_baseline_backward(w, q, k, v, dout, prefix=1024):
+    """Time the oracle's backward as it stands on the first `prefix` tokens of every head."""
+    import numpy as np
+    from oracle import oracle_num_threads, swaa_attn_bwd_oracle
+    from paper_2512_10411_amd.binding import swaa_visible_pairs
+    n = min(prefix, w.N)
+    cut = lambda a: np.ascontiguousarray(a[:, :, :n])
+    t0 = time.perf_counter()
+    swaa_attn_bwd_oracle(cut(q), cut(k), cut(v), cut(dout), w.window, w.n_sink, w.scale)
+    dt = time.perf_counter() - t0
+    pairs = swaa_visible_pairs(n, w.window, w.n_sink) * w.B * w.Hq
+    return {
+        "value": 10.0 * w.D * pairs / dt / 1e12,
+        "unit": "TFLOP/s",
+        "cores": oracle_num_threads(),
+        "kind": "oracle",
+        "sample": f"backward of the first {n} tokens of all {w.B * w.Hq} (batch, head) of workload '{w.name}': "
+                  f"{pairs} visible pairs in {dt:.2f} s; fp64, OpenMP over rows",
+        "seconds": dt,
+        "pairs_per_s": pairs / dt,
+    }
+
+
 def cpu_baseline(w, q, k, v, target_s):
     """Time the oracle as it stands on a bounded sample of this workload's rows."""
     import numpy as np
@@ -165,8 +188,20 @@ def main():
         ws = torch.empty(binding.swaa_attn_decode_workspace_bytes(w.B, w.Hq, w.Hkv, w.n_query, w.N, w.D, w.window,
                                                                   w.n_sink), dtype=torch.uint8, device="cuda")
 
+    if w.backward:
+        import numpy as np
+        from paper_2512_10411_amd.inputs import f32_to_bf16_bits
+        dout = f32_to_bf16_bits(np.random.Generator(np.random.Philox(w.seed + 9)).standard_normal(
+            q.shape, dtype=np.float32))
+        dd = dev(dout)
+        binding.swaa_attn_fwd(qd, kd, vd, w.window, w.n_sink, w.scale, out=out, lse=lse, stream=stream)
+        bws = torch.empty(binding.swaa_attn_bwd_workspace_bytes(w.B, w.Hq, w.Hkv, w.N, w.D, w.window, w.n_sink), dtype=torch.uint8, device="cuda")
+
     def step():
-        if decode:
+        if w.backward:
+            binding.swaa_attn_bwd(qd, kd, vd, out, lse, dd, w.window, w.n_sink, None, w.scale, workspace=bws,
+                                  stream=stream)
+        elif decode:
             binding.swaa_attn_decode(qd, kd, vd, w.window, w.n_sink, w.scale, out=out, lse=lse, workspace=ws,
                                      stream=stream)
         elif w.chunk:
@@ -210,7 +245,9 @@ def main():
         pairs, algo_bytes = decode_counts(w)
     else:
         pairs = binding.swaa_visible_pairs_fa_decode(w.N, w.window, w.n_sink, n_prompt) * w.B * w.Hq
-    flops = 4.0 * w.D * pairs
+    # forward: two products per visible pair; backward: five (the customary count; the
+    # recomputation the two-kernel backward does on top of them is not credited)
+    flops = (10.0 if w.backward else 4.0) * w.D * pairs
     value = flops / (ms_per_step * 1e-3) / 1e12
     achieved = flops / (kern_avg_ms * 1e-3) / 1e12
     traffic = args.traffic_bytes if args.traffic_bytes is not None else MEASURED_TRAFFIC_BYTES.get(w.name)
@@ -224,7 +261,8 @@ def main():
     else:
         roofline = {"bound": "mfma", "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": traffic,
-                    "kernel": "swaa_fwd_pipelined_kernel" if w.D == 128 else "swaa_fwd_kernel<64>",
+                    "kernel": ("swaa_bwd_dkv_kernel + swaa_bwd_dq_kernel + swaa_bwd_delta_kernel" if w.backward
+                               else "swaa_fwd_pipelined_kernel" if w.D == 128 else "swaa_fwd_kernel<64>"),
                     "kernel_avg_ms": kern_avg_ms}
 
     res = {
@@ -248,7 +286,8 @@ def main():
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = (cpu_baseline_decode(w, q, k, v) if decode or w.chunk
+        res["cpu_baseline"] = (cpu_baseline_backward(w, q, k, v, dout) if w.backward
+                               else cpu_baseline_decode(w, q, k, v) if decode or w.chunk
                                else cpu_baseline(w, q, k, v, args.cpu_seconds))
         res["cpu_baseline"]["gpu_over_cpu"] = value / res["cpu_baseline"]["value"]
     print(json.dumps(res), flush=True)

@@ -211,8 +211,8 @@ long long swaa_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Nq, int N
  *   dk, dv              device, bf16 [B, Hkv, N, D], written
  *   D                   64 or 128; window, n_sink, n_prompt, scale, stream as in the forward call
  *   workspace           device scratch memory owned by the caller, 16-byte aligned, at
- *                       least swaa_attn_bwd_workspace_bytes(B, Hq, N) bytes; calls that may
- *                       overlap on the device need separate workspaces
+ *                       least swaa_attn_bwd_workspace_bytes(same shape and mask arguments)
+ *                       bytes; calls that may overlap on the device need separate workspaces
  *
  * bf16 tensors 16-byte aligned; P and dS are rounded to bf16 before the second
  * products, all sums are fp32.  Deterministic (no atomics).  The library
@@ -223,8 +223,11 @@ int swaa_attn_bwd(const void *q, const void *k, const void *v, const void *out, 
                   int B, int Hq, int Hkv, int N, int D, int window, int n_sink, int n_prompt,
                   float scale, void *workspace, long long workspace_bytes, void *stream);
 
-/* Bytes of workspace swaa_attn_bwd needs (one float per query row), or a negative swaa_status. */
-long long swaa_attn_bwd_workspace_bytes(int B, int Hq, int N);
+/*
+ * Bytes of workspace swaa_attn_bwd needs (one float per query row, plus partial
+ * sums for the key tiles that hold sink keys), or a negative swaa_status.
+ */
+long long swaa_attn_bwd_workspace_bytes(int B, int Hq, int Hkv, int N, int D, int window, int n_sink, int n_prompt);
 
 /* Static description of a status code; never NULL, never freed. */
 const char *swaa_status_string(int status);

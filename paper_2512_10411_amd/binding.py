@@ -90,7 +90,7 @@ def load_library() -> ctypes.CDLL:
     lib.swaa_attn_bwd.argtypes = [ctypes.c_void_p] * 9 + [ctypes.c_int] * 8 + [
         ctypes.c_float, ctypes.c_void_p, ctypes.c_longlong, ctypes.c_void_p]
     lib.swaa_attn_bwd_workspace_bytes.restype = ctypes.c_longlong
-    lib.swaa_attn_bwd_workspace_bytes.argtypes = [ctypes.c_int] * 3
+    lib.swaa_attn_bwd_workspace_bytes.argtypes = [ctypes.c_int] * 8
     lib.swaa_status_string.restype = ctypes.c_char_p
     lib.swaa_status_string.argtypes = [ctypes.c_int]
     lib.swaa_version.restype = ctypes.c_int
@@ -340,8 +340,11 @@ def swaa_attn_fwd_ex(q, k, v, window: int, n_sink: int, n_prompt: int | None = N
     return out, lse
 
 
-def swaa_attn_bwd_workspace_bytes(B, Hq, N) -> int:
-    r = int(load_library().swaa_attn_bwd_workspace_bytes(int(B), int(Hq), int(N)))
+def swaa_attn_bwd_workspace_bytes(B, Hq, Hkv, N, D, window, n_sink, n_prompt=None) -> int:
+    """Bytes of device scratch swaa_attn_bwd needs for this shape and mask."""
+    r = int(load_library().swaa_attn_bwd_workspace_bytes(
+        int(B), int(Hq), int(Hkv), int(N), int(D), int(window), int(n_sink),
+        2**31 - 1 if n_prompt is None else int(n_prompt)))
     if r < 0:
         raise SwaaError(r, swaa_status_string(r))
     return r
@@ -374,7 +377,7 @@ def swaa_attn_bwd(q, k, v, out, lse, dout, window: int, n_sink: int, n_prompt: i
         raise ValueError("lse must be a contiguous fp32 [B, Hq, N] tensor")
     if scale is None:
         scale = 1.0 / math.sqrt(D)
-    need = swaa_attn_bwd_workspace_bytes(B, Hq, N)
+    need = swaa_attn_bwd_workspace_bytes(B, Hq, Hkv, N, D, window, n_sink, n_prompt)
     with torch.cuda.device(q.device):
         dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
         if workspace is None:

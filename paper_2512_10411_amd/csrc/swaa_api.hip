@@ -227,40 +227,20 @@ int swaa_attn_decode(const void *q, const void *k, const void *v, void *out, flo
     return err == hipSuccess ? SWAA_OK : SWAA_ERR_LAUNCH;
 }
 
-long long swaa_attn_bwd_workspace_bytes(int B, int Hq, int N) {
-    if (B < 1 || Hq < 1 || N < 1) return SWAA_ERR_SHAPE;
-    return (long long)B * Hq * N * (long long)sizeof(float);
-}
+namespace {
 
-int swaa_attn_bwd(const void *q, const void *k, const void *v, const void *out, const float *lse,
-                  const void *dout, void *dq, void *dk, void *dv,
-                  int B, int Hq, int Hkv, int N, int D, int window, int n_sink, int n_prompt,
-                  float scale, void *workspace, long long workspace_bytes, void *stream) {
-    if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv) return SWAA_ERR_NULL;
+// Shape and mask fields of the backward parameter block, and its plan.
+int bwd_plan(swaa::BwdParams &p, int B, int Hq, int Hkv, int N, int D, int window, int n_sink, int n_prompt) {
     if (B < 1 || Hq < 1 || Hkv < 1 || N < 1 || D < 1) return SWAA_ERR_SHAPE;
     if (Hq % Hkv != 0) return SWAA_ERR_SHAPE;
     if (window < 1 || n_sink < 0 || n_prompt < 0) return SWAA_ERR_SHAPE;
-    if (!positive_finite(scale)) return SWAA_ERR_SHAPE;
     if (D != 64 && D != 128) return SWAA_ERR_UNSUPPORTED;
-    for (const void *ptr : {q, k, v, out, dout, (const void *)dq, (const void *)dk, (const void *)dv})
-        if (misaligned(ptr)) return SWAA_ERR_ALIGN;
-    if ((reinterpret_cast<uintptr_t>(lse) & 3u) != 0) return SWAA_ERR_ALIGN;
-    if (!workspace || misaligned(workspace) || workspace_bytes < swaa_attn_bwd_workspace_bytes(B, Hq, N))
-        return SWAA_ERR_WORKSPACE;
-
-    swaa::BwdParams p{};
     FwdParams &f = p.f;
-    f.q = static_cast<const __bf16 *>(q);
-    f.k = static_cast<const __bf16 *>(k);
-    f.v = static_cast<const __bf16 *>(v);
-    f.lse = const_cast<float *>(lse);
     f.B = B; f.Hq = Hq; f.Hkv = Hkv; f.Nq = N; f.Nk = N;
     f.W = window < N ? window : N;
     f.S = n_sink < N ? n_sink : N;
     f.P = n_prompt < N ? n_prompt : N;
     f.G = Hq / Hkv;
-    f.scale = scale;
-    f.scale_log2 = scale * 1.44269504088896340736f;
     f.n4 = f.G / 4;
     f.has2 = (f.G % 4) >= 2 ? 1 : 0;
     f.has1 = f.G % 2;
@@ -271,13 +251,51 @@ int swaa_attn_bwd(const void *q, const void *k, const void *v, const void *out, 
     f.total_items = (long long)B * Hkv * f.tiles_per_pair;
     f.chunk = (f.total_items + kXcds - 1) / kXcds;
     if (f.chunk * kXcds > 0x7fffffffLL || (long long)B * Hq * N > 0x7fffffffLL * 16) return SWAA_ERR_SHAPE;
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N;
+    swaa::plan_bwd(p);
+    return SWAA_OK;
+}
+
+}  // namespace
+
+long long swaa_attn_bwd_workspace_bytes(int B, int Hq, int Hkv, int N, int D, int window, int n_sink, int n_prompt) {
+    swaa::BwdParams p{};
+    const int rc = bwd_plan(p, B, Hq, Hkv, N, D, window, n_sink, n_prompt);
+    if (rc != SWAA_OK) return rc;
+    return swaa::bwd_workspace_floats(p, D) * (long long)sizeof(float);
+}
+
+int swaa_attn_bwd(const void *q, const void *k, const void *v, const void *out, const float *lse,
+                  const void *dout, void *dq, void *dk, void *dv,
+                  int B, int Hq, int Hkv, int N, int D, int window, int n_sink, int n_prompt,
+                  float scale, void *workspace, long long workspace_bytes, void *stream) {
+    if (!q || !k || !v || !out || !lse || !dout || !dq || !dk || !dv) return SWAA_ERR_NULL;
+    swaa::BwdParams p{};
+    const int rc = bwd_plan(p, B, Hq, Hkv, N, D, window, n_sink, n_prompt);
+    if (rc != SWAA_OK) return rc;
+    if (!positive_finite(scale)) return SWAA_ERR_SHAPE;
+    for (const void *ptr : {q, k, v, out, dout, (const void *)dq, (const void *)dk, (const void *)dv})
+        if (misaligned(ptr)) return SWAA_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(lse) & 3u) != 0) return SWAA_ERR_ALIGN;
+    if (!workspace || misaligned(workspace) ||
+        workspace_bytes < swaa::bwd_workspace_floats(p, D) * (long long)sizeof(float))
+        return SWAA_ERR_WORKSPACE;
+
+    FwdParams &f = p.f;
+    f.q = static_cast<const __bf16 *>(q);
+    f.k = static_cast<const __bf16 *>(k);
+    f.v = static_cast<const __bf16 *>(v);
+    f.lse = const_cast<float *>(lse);
+    f.scale = scale;
+    f.scale_log2 = scale * 1.44269504088896340736f;
     p.out = static_cast<const __bf16 *>(out);
     p.dout = static_cast<const __bf16 *>(dout);
     p.dq = static_cast<__bf16 *>(dq);
     p.dk = static_cast<__bf16 *>(dk);
     p.dv = static_cast<__bf16 *>(dv);
     p.delta = static_cast<float *>(workspace);
-    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N;
+    // the partial sums follow delta, on a 16-byte boundary
+    p.partial = p.delta + (((long long)B * Hq * N + 3) / 4) * 4;
     const hipError_t err = swaa::launch_bwd(p, D, static_cast<hipStream_t>(stream));
     return err == hipSuccess ? SWAA_OK : SWAA_ERR_LAUNCH;
 }

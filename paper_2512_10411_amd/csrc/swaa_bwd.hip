@@ -9,7 +9,7 @@
 //   dS_ij = P_ij (dP_ij - delta_i)
 //   dQ_i = scale sum_j dS_ij k_j               dK_j = scale sum_i dS_ij q_i
 //
-// Three kernels, no atomics, results independent of scheduling:
+// Four kernels, no atomics, results independent of scheduling:
 //   * swaa_bwd_delta_kernel: delta, one pass over dO and O.
 //   * swaa_bwd_dq_kernel: a workgroup owns 256 query rows (the forward's work
 //     decomposition and tile schedule), walks its visible KV tiles, recomputes
@@ -17,7 +17,10 @@
 //   * swaa_bwd_dkv_kernel: a workgroup owns 128 keys of one KV head (32 per
 //     wave), walks every query head of the GQA group and every 64-row query
 //     tile that can see them, recomputes S = Q K^T and dP = dO V^T and
-//     accumulates dV^T += dO^T P and dK^T += Q^T dS.
+//     accumulates dV^T += dO^T P and dK^T += Q^T dS.  Key tiles that hold sink
+//     keys are seen by every later row: their rows beyond the band are cut into
+//     segments with a workgroup each, and
+//   * swaa_bwd_sink_sum_kernel adds the fp32 partial sums of those key tiles.
 // Each product is a v_mfma_f32_32x32x16_bf16 with the accumulator oriented so
 // that the probabilities come out in the B-operand layout of the product that
 // consumes them (as in the forward kernels); operands that a product needs
@@ -280,10 +283,23 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dkv_kernel(const BwdPara
 
     const int N = p.N, W = p.f.W, S = p.f.S, P = p.f.P, G = p.f.G;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
-    // key tiles of 128: the first ones are seen by the most rows under a causal mask, they go first
+    // Work list: first the segments of the sink key tiles (rows beyond the band), then one
+    // workgroup per key tile of 128 keys (band rows; for key tiles without sinks also the
+    // generated rows).  Under a causal mask the first key tiles are seen by the most rows.
     const int n_kt = (N + 127) / 128;
-    const int kt = blockIdx.x % n_kt;
-    const int pair = blockIdx.x / n_kt;
+    const int n_extra = p.B * p.Hkv * p.n_sink_kt * p.n_seg;
+    int kt, pair, seg;  // seg: -1 for a key tile's main workgroup
+    if ((int)blockIdx.x < n_extra) {
+        seg = blockIdx.x % p.n_seg;
+        kt = (blockIdx.x / p.n_seg) % p.n_sink_kt;
+        pair = blockIdx.x / (p.n_seg * p.n_sink_kt);
+    } else {
+        const int id = blockIdx.x - n_extra;
+        seg = -1;
+        kt = id % n_kt;
+        pair = id / n_kt;
+    }
+    const bool sink_kt = kt < p.n_sink_kt;  // results go to the partial-sum workspace
     const int b = pair / p.Hkv, kvh = pair % p.Hkv;
     const int k0 = kt * 128, k1 = min(k0 + 127, N - 1);  // the workgroup's keys
     const int kw0 = k0 + 32 * wave, kw1 = kw0 + 31;       // this wave's keys
@@ -310,15 +326,23 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dkv_kernel(const BwdPara
         }
 
     // query tiles (64 rows) with a row that sees one of the workgroup's keys: the band tiles
-    // tq_lo .. tq_band_hi, then -- if a key is a sink, or there are generated rows -- the rest
+    // tq_lo .. tq_band_hi, then -- if a key is a sink, or there are generated rows -- the rest.
+    // For a sink key tile the rest is cut into segments: the main workgroup keeps the band.
     const int tq_last = (N - 1) / kBq;
-    const int tq_lo = k0 / kBq;
     const int tq_band_hi = min(N - 1, k1 + W - 1) / kBq;
-    int tq_x = tq_last + 1;  // first tile of the second range
-    if (k0 < S) tq_x = tq_band_hi + 1;
-    else if (P < N) tq_x = max(tq_band_hi + 1, P / kBq);
-    const int n_band = tq_band_hi - tq_lo + 1;
-    const int n_tiles = n_band + max(0, tq_last - tq_x + 1);
+    int tq_lo = k0 / kBq;
+    int n_band = tq_band_hi - tq_lo + 1;
+    int tq_x = tq_last + 1, tq_x_end = tq_last;  // second range
+    if (sink_kt) {
+        if (seg >= 0) {
+            n_band = 0;
+            tq_x = tq_band_hi + 1 + seg * p.seg_tiles;
+            tq_x_end = min(tq_last, tq_x + p.seg_tiles - 1);
+        }
+    } else if (P < N) {
+        tq_x = max(tq_band_hi + 1, P / kBq);
+    }
+    const int n_tiles = n_band + max(0, tq_x_end - tq_x + 1);
     auto tile_of = [&](int n) { return n < n_band ? tq_lo + n : tq_x + (n - n_band); };
 
     const float c2 = p.f.scale_log2;
@@ -357,11 +381,13 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dkv_kernel(const BwdPara
 
     const int total = G * n_tiles;  // (head, tile) steps, head-major
     int step = 0;
-    load_tile(kvh * G, tile_of(0));
-    store_tile();
+    if (total > 0) {
+        load_tile(kvh * G, tile_of(0));
+        store_tile();
+    }
     __syncthreads();
 
-    while (true) {
+    while (total > 0) {
         const bool has_next = step + 1 < total;
         if (has_next) load_tile(kvh * G + (step + 1) / n_tiles, tile_of((step + 1) % n_tiles));
 
@@ -432,7 +458,20 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dkv_kernel(const BwdPara
         ++step;
     }
 
-    if (key < N) {
+    if (sink_kt) {
+        // fp32 partial sums of all 128 key columns (columns past the end hold zeros)
+        float *slot = p.partial + ((((size_t)pair * p.n_sink_kt + kt) * (p.n_seg + 1) + (seg + 1)) * 2) * (size_t)(128 * D);
+        float *pk = slot + (size_t)(32 * wave + l32) * D, *pv = pk + 128 * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int e4 = 0; e4 < 4; ++e4) {
+                const float4 k4 = {dkacc[db][4 * e4], dkacc[db][4 * e4 + 1], dkacc[db][4 * e4 + 2], dkacc[db][4 * e4 + 3]};
+                const float4 v4 = {dvacc[db][4 * e4], dvacc[db][4 * e4 + 1], dvacc[db][4 * e4 + 2], dvacc[db][4 * e4 + 3]};
+                *reinterpret_cast<float4 *>(pk + 32 * db + 8 * e4 + 4 * hf) = k4;
+                *reinterpret_cast<float4 *>(pv + 32 * db + 8 * e4 + 4 * hf) = v4;
+            }
+    } else if (key < N) {
         const size_t row = (((size_t)b * p.Hkv + kvh) * (size_t)N + key) * D;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
@@ -450,6 +489,36 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dkv_kernel(const BwdPara
     }
 }
 
+// dK, dV of the sink key tiles: sum of the band part and the segments, in a fixed order.
+template <int D>
+__global__ __launch_bounds__(kThreads) void swaa_bwd_sink_sum_kernel(const BwdParams p) {
+    // one thread per 4 consecutive head-dimension elements of one key
+    const long long per_kt = 128LL * D / 4;
+    const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
+    const long long total = (long long)p.B * p.Hkv * p.n_sink_kt * per_kt;
+    if (idx >= total) return;
+    const int e = (int)(idx % per_kt);
+    const long long kt_id = idx / per_kt;  // pair * n_sink_kt + kt
+    const int kt = (int)(kt_id % p.n_sink_kt);
+    const long long pair = kt_id / p.n_sink_kt;
+    const int key = kt * 128 + e / (D / 4);
+    const int d = (e % (D / 4)) * 4;
+    if (key >= p.N) return;
+    const float *slot = p.partial + (kt_id * (p.n_seg + 1) * 2) * (size_t)(128 * D) + (size_t)(e / (D / 4)) * D + d;
+    float4 sk = {0.f, 0.f, 0.f, 0.f}, sv = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s <= p.n_seg; ++s) {
+        const float4 a = *reinterpret_cast<const float4 *>(slot + (size_t)s * 2 * 128 * D);
+        const float4 c = *reinterpret_cast<const float4 *>(slot + (size_t)s * 2 * 128 * D + 128 * D);
+        sk.x += a.x; sk.y += a.y; sk.z += a.z; sk.w += a.w;
+        sv.x += c.x; sv.y += c.y; sv.z += c.z; sv.w += c.w;
+    }
+    const size_t row = ((size_t)pair * p.N + key) * D + d;
+    bf16x4 k4 = {(__bf16)(sk.x * p.f.scale), (__bf16)(sk.y * p.f.scale), (__bf16)(sk.z * p.f.scale), (__bf16)(sk.w * p.f.scale)};
+    bf16x4 v4 = {(__bf16)sv.x, (__bf16)sv.y, (__bf16)sv.z, (__bf16)sv.w};
+    *reinterpret_cast<bf16x4 *>(p.dk + row) = k4;
+    *reinterpret_cast<bf16x4 *>(p.dv + row) = v4;
+}
+
 template <int D>
 hipError_t launch_bwd_d(const BwdParams &p, hipStream_t stream) {
     const long long rows = (long long)p.B * p.Hq * p.N;
@@ -462,11 +531,43 @@ hipError_t launch_bwd_d(const BwdParams &p, hipStream_t stream) {
     err = hipGetLastError();
     if (err != hipSuccess) return err;
     const long long n_kt = (p.N + 127) / 128;
-    hipLaunchKernelGGL(swaa_bwd_dkv_kernel<D>, dim3((unsigned)(n_kt * p.B * p.Hkv)), dim3(kThreads), 0, stream, p);
+    const long long pairs = (long long)p.B * p.Hkv;
+    hipLaunchKernelGGL(swaa_bwd_dkv_kernel<D>, dim3((unsigned)(pairs * (n_kt + (long long)p.n_sink_kt * p.n_seg))),
+                       dim3(kThreads), 0, stream, p);
+    err = hipGetLastError();
+    if (err != hipSuccess || p.n_sink_kt == 0) return err;
+    const long long threads = pairs * p.n_sink_kt * (128LL * D / 4);
+    hipLaunchKernelGGL(swaa_bwd_sink_sum_kernel<D>, dim3((unsigned)((threads + kThreads - 1) / kThreads)), dim3(kThreads),
+                       0, stream, p);
     return hipGetLastError();
 }
 
 }  // namespace
+
+void plan_bwd(BwdParams &p) {
+    const int N = p.N, W = p.f.W, S = p.f.S;
+    p.n_sink_kt = 0;
+    p.n_seg = 0;
+    p.seg_tiles = 1;
+    // rows beyond the band of the last sink key: only worth separate workgroups if there are any
+    const int tq_last = (N - 1) / kBq;
+    const int first_beyond = (min(N - 1, 127 + W - 1)) / kBq + 1;  // of key tile 0, the longest range
+    if (S == 0 || first_beyond > tq_last) return;
+    p.n_sink_kt = (min(S, N) + 127) / 128;
+    const int range = tq_last - first_beyond + 1;
+    // segments about as long as an ordinary key tile's band, but at most 512 of them in all
+    const int band_tiles = (W + 127) / kBq + 1;
+    long long seg = band_tiles;
+    const long long groups = (long long)p.B * p.Hkv * p.n_sink_kt;
+    while ((range + seg - 1) / seg * groups > 512) seg *= 2;
+    p.seg_tiles = (int)seg;
+    p.n_seg = (int)((range + seg - 1) / seg);
+}
+
+long long bwd_workspace_floats(const BwdParams &p, int D) {
+    const long long rows = ((long long)p.B * p.Hq * p.N + 3) / 4 * 4;  // the partial sums start 16-byte aligned
+    return rows + (long long)p.B * p.Hkv * p.n_sink_kt * (p.n_seg + 1) * 2 * 128 * D;
+}
 
 hipError_t launch_bwd(const BwdParams &p, int D, hipStream_t stream) {
     return D == 128 ? launch_bwd_d<128>(p, stream) : launch_bwd_d<64>(p, stream);

@@ -50,6 +50,7 @@ class Workload:
     n_prompt: int | None = None  # FA Decode runs: rows >= n_prompt are generated tokens
     n_query: int | None = None   # decode-shape and chunk runs: q holds only the n_query newest of the N tokens
     chunk: bool = False          # n_query rows are a chunk of a longer prefill (general forward), not a decode step
+    backward: bool = False       # the timed call is the backward pass (the forward runs once, untimed)
 
     @property
     def scale(self) -> float:
@@ -81,6 +82,8 @@ WORKLOADS = {
     "decode128k_full": Workload("decode128k_full", 1, 32, 8, 131072, 128, 131072, 4, _SEED0 + 6, n_query=1),
     "decode128k_swa": Workload("decode128k_swa", 1, 32, 8, 131072, 128, 8192, 4, _SEED0 + 6, n_query=1),
     "decode16k_b16": Workload("decode16k_b16", 16, 32, 8, 16384, 128, 16384, 4, _SEED0 + 7, n_query=1),
+    # backward pass of the mid-size layer (fine-tuning under the window + sink mask)
+    "mid_bwd": Workload("mid_bwd", 1, 32, 8, 16384, 128, 2048, 4, _SEED0 + 2, backward=True),
     # the last 2048-row chunk of a 128k-token prefill whose earlier keys and values are cached
     "chunk2k_128k_swa": Workload("chunk2k_128k_swa", 1, 32, 8, 131072, 128, 8192, 4, _SEED0 + 8, n_query=2048,
                                  chunk=True),

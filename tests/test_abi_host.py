@@ -163,9 +163,11 @@ def test_general_forward_argument_errors():
 
 
 def test_backward_argument_errors():
-    assert binding.swaa_attn_bwd_workspace_bytes(2, 8, 1000) == 2 * 8 * 1000 * 4
+    assert binding.swaa_attn_bwd_workspace_bytes(2, 8, 2, 1000, 128, 100, 0) == 2 * 8 * 1000 * 4  # no sinks: delta only
+    assert binding.swaa_attn_bwd_workspace_bytes(2, 8, 2, 1000, 128, 100, 4) > 2 * 8 * 1000 * 4
+    assert binding.swaa_attn_bwd_workspace_bytes(1, 32, 8, 131072, 128, 8192, 1000) < 256 << 20
     with pytest.raises(binding.SwaaError):
-        binding.swaa_attn_bwd_workspace_bytes(0, 8, 1000)
+        binding.swaa_attn_bwd_workspace_bytes(0, 8, 2, 1000, 128, 100, 0)
     p = 4096  # fake aligned address; never dereferenced on these paths
     f = binding.swaa_attn_bwd_raw
     ok = [p] * 9 + [1, 4, 2, 128, 128, 16, 2, 128, 0.1, p, 1 << 20, None]
@@ -187,3 +189,5 @@ def test_backward_argument_errors():
     assert call(dq=p + 8) == binding.SWAA_ERR_ALIGN
     assert call(ws=None) == binding.SWAA_ERR_WORKSPACE
     assert call(wb=4 * 128 * 4 - 1) == binding.SWAA_ERR_WORKSPACE
+    need = binding.swaa_attn_bwd_workspace_bytes(1, 4, 2, 128, 128, 16, 2, 128)
+    assert call(wb=need - 1) == binding.SWAA_ERR_WORKSPACE
