@@ -6,6 +6,8 @@ It shares no code with ``paper_2512_10411_amd`` and never imports it.
 """
 from .swaa_oracle import (  # noqa: F401
     build_oracle,
+    decode_elems,
+    input_format,
     oracle_num_threads,
     swaa_attn_bwd_oracle,
     swaa_attn_oracle,

@@ -18,7 +18,8 @@
  *   lse    = m + ln sum_{j in Vis(i)} exp(s_j - m)                (natural log)
  *   o[d]   = sum_{j in Vis(i)} exp(s_j - lse) * v[b,g,j,d]
  *
- * Inputs are bf16 bit patterns (uint16), widened exactly to double; all
+ * Inputs are bf16 bit patterns (uint16; binary16 after swaa_oracle_set_format(1)),
+ * widened exactly to double; all
  * arithmetic is double; outputs are double and are not rounded.  There is no
  * tiling, no running maximum and no reordering: three passes over the
  * explicit visible set, exactly as written above.  Rows are independent, so
@@ -42,12 +43,50 @@
 #include <omp.h>
 #endif
 
+/*
+ * Input element format: 0 = bfloat16 (the library's main path), 1 = IEEE binary16
+ * (the precision the paper serves its models in, Sec. 4.1.1).  A process-wide
+ * setting of this test helper; set it before a call, not during one.
+ */
+static int g_format = 0;
+
+int swaa_oracle_set_format(int format)
+{
+    if (format != 0 && format != 1)
+        return -1;
+    g_format = format;
+    return 0;
+}
+
+/* binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits, written out from the format. */
+static double f16_to_double(uint16_t bits)
+{
+    const int sign = bits >> 15, e = (bits >> 10) & 0x1f, frac = bits & 0x3ff;
+    double x;
+    if (e == 0)
+        x = ldexp((double)frac, -24); /* zero and subnormals: frac * 2^-10 * 2^-14 */
+    else if (e == 31)
+        x = frac ? NAN : INFINITY;
+    else
+        x = ldexp(1.0 + (double)frac / 1024.0, e - 15);
+    return sign ? -x : x;
+}
+
 static double bf16_to_double(uint16_t bits)
 {
+    if (g_format == 1)
+        return f16_to_double(bits);
     uint32_t u = ((uint32_t)bits) << 16;
     float f;
     memcpy(&f, &u, sizeof f);
     return (double)f;
+}
+
+/* The decoder on its own (for the tests that pin it). */
+void swaa_oracle_decode_elems(const uint16_t *bits, long n, double *out)
+{
+    for (long i = 0; i < n; i++)
+        out[i] = bf16_to_double(bits[i]);
 }
 
 /* 1 if key j is visible from query i under (window W, sinks S), when the

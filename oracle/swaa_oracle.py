@@ -78,9 +78,44 @@ def _load():
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
             ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_double,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
+        lib.swaa_oracle_set_format.restype = ctypes.c_int
+        lib.swaa_oracle_set_format.argtypes = [ctypes.c_int]
+        lib.swaa_oracle_decode_elems.restype = None
+        lib.swaa_oracle_decode_elems.argtypes = [ctypes.c_void_p, ctypes.c_long, ctypes.c_void_p]
         lib.swaa_oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
+
+
+class input_format:
+    """``with input_format("fp16"):`` -- the uint16 inputs of the oracle calls inside are IEEE
+    binary16 bit patterns instead of bfloat16 (a process-wide switch of the C oracle; the
+    numpy routes read the same switch).  Not for concurrent use."""
+    _current = "bf16"
+
+    def __init__(self, fmt):
+        if fmt not in ("bf16", "fp16"):
+            raise ValueError("format must be 'bf16' or 'fp16'")
+        self.fmt = fmt
+
+    def __enter__(self):
+        self.prev = input_format._current
+        input_format._current = self.fmt
+        _load().swaa_oracle_set_format(1 if self.fmt == "fp16" else 0)
+        return self
+
+    def __exit__(self, *exc):
+        input_format._current = self.prev
+        _load().swaa_oracle_set_format(1 if self.prev == "fp16" else 0)
+        return False
+
+
+def decode_elems(bits: np.ndarray) -> np.ndarray:
+    """The C oracle's element decoder applied to an array of uint16 bit patterns."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    out = np.empty(bits.shape, dtype=np.float64)
+    _load().swaa_oracle_decode_elems(bits.ctypes.data, bits.size, out.ctypes.data)
+    return out
 
 
 def oracle_num_threads() -> int:
@@ -137,6 +172,8 @@ def swaa_attn_oracle(q, k, v, window, n_sink, scale, rows=None, n_threads=0, n_p
 
 
 def _bf16_bits_to_f64(a: np.ndarray) -> np.ndarray:
+    if input_format._current == "fp16":
+        return np.ascontiguousarray(a).view(np.float16).astype(np.float64)
     return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
 
 

@@ -90,13 +90,24 @@ WORKLOADS = {
 }
 
 
-def make_qkv(B, Hq, Hkv, N, D, seed, k_mult=1.0, chunk_rows=1 << 22, n_query=None):
+def f32_to_f16_bits(x: np.ndarray) -> np.ndarray:
+    """float32 -> IEEE binary16 bit patterns (round to nearest even), as uint16."""
+    return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def f16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    return np.ascontiguousarray(bits, dtype=np.uint16).view(np.float16).astype(np.float32)
+
+
+def make_qkv(B, Hq, Hkv, N, D, seed, k_mult=1.0, chunk_rows=1 << 22, n_query=None, fmt="bf16"):
     """i.i.d. N(0,1) q, k, v rounded to bf16; k scaled by k_mult before rounding.
 
     Generated in row chunks so that the float32 staging buffer stays small even
     for the 128k-token workloads.  n_query: q has only that many rows per head
-    (decode shape), k and v keep N.
+    (decode shape), k and v keep N.  fmt: "bf16" or "fp16" (same draws, rounded to
+    the other format).
     """
+    to_bits = f32_to_bf16_bits if fmt == "bf16" else f32_to_f16_bits
     rng = np.random.Generator(np.random.Philox(int(seed)))
 
     def draw(H, mult, N=N):
@@ -106,7 +117,7 @@ def make_qkv(B, Hq, Hkv, N, D, seed, k_mult=1.0, chunk_rows=1 << 22, n_query=Non
             x = rng.standard_normal((r1 - r0, D), dtype=np.float32)
             if mult != 1.0:
                 x *= np.float32(mult)
-            out[r0:r1] = f32_to_bf16_bits(x)
+            out[r0:r1] = to_bits(x)
         return out.reshape(B, H, N, D)
 
     q = draw(Hq, 1.0) if n_query is None else draw(Hq, 1.0, int(n_query))
