@@ -117,9 +117,19 @@ int swaa_attn_fwd_fa_decode(const void *q, const void *k, const void *v, void *o
  * (rows beyond Nq are not computed).  A sequence with more query rows than keys
  * gets only its first Nk_b rows written; empty sequences are skipped.
  *
+ * dtype selects the 16-bit element format of q, k, v and out: SWAA_BF16 (the
+ * format of every other call) or SWAA_F16, which computes the same thing on
+ * binary16 operands and rounds the probabilities and the output to binary16
+ * (fp32 accumulation; runs on the plain kernel).
+ *
  * Ownership, asynchrony and error reporting as for swaa_attn_fwd; the argument
  * block is read during the call only.  Without cu_seqlens, Nq <= Nk is required.
  */
+typedef enum swaa_dtype {
+    SWAA_BF16 = 0, /* bfloat16: every kernel */
+    SWAA_F16 = 1   /* IEEE binary16 (the precision the paper serves in, Sec. 4.1.1): the plain forward kernel */
+} swaa_dtype;
+
 typedef struct swaa_tensor {
     void *ptr;
     long long stride_b, stride_h, stride_n;
@@ -140,6 +150,7 @@ typedef struct swaa_fwd_args {
     int n_prompt;           /* as in swaa_attn_fwd_fa_decode, in positions; >= Nk: no generated rows */
     float scale;
     void *stream;
+    int dtype;              /* swaa_dtype of q, k, v and out */
 } swaa_fwd_args;
 
 int swaa_attn_fwd_ex(const swaa_fwd_args *args);

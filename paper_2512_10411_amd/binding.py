@@ -21,6 +21,8 @@ SWAA_ERR_UNSUPPORTED = -3
 SWAA_ERR_ALIGN = -4
 SWAA_ERR_LAUNCH = -5
 SWAA_ERR_WORKSPACE = -6
+SWAA_BF16 = 0
+SWAA_F16 = 1
 
 # every symbol include/swaa.h declares
 EXPORTS = ("swaa_attn_fwd", "swaa_attn_fwd_fa_decode", "swaa_attn_fwd_ex", "swaa_visible_pairs",
@@ -45,7 +47,7 @@ class SwaaFwdArgs(ctypes.Structure):
                 ("Nq", ctypes.c_int), ("Nk", ctypes.c_int),
                 ("cu_seqlens_q", ctypes.c_void_p), ("cu_seqlens_k", ctypes.c_void_p),
                 ("window", ctypes.c_int), ("n_sink", ctypes.c_int), ("n_prompt", ctypes.c_int),
-                ("scale", ctypes.c_float), ("stream", ctypes.c_void_p)]
+                ("scale", ctypes.c_float), ("stream", ctypes.c_void_p), ("dtype", ctypes.c_int)]
 
 
 class SwaaError(RuntimeError):
@@ -278,16 +280,19 @@ def swaa_attn_fwd_ex(q, k, v, window: int, n_sink: int, n_prompt: int | None = N
     strides whose last dimension is contiguous (a [B, N, H, D] tensor is passed as
     ``t.permute(0, 2, 1, 3)``).  Packed batches: q [Hq, Tq, D], k, v [Hkv, Tk, D] views plus
     int32 device tensors cu_seqlens_q / cu_seqlens_k of B + 1 offsets and the largest
-    sequence lengths.  out defaults to a new tensor with q's shape in q's memory order;
+    sequence lengths.  bfloat16 or float16 tensors (all of one type).  out defaults to a new tensor with q's shape in q's memory order;
     lse is fp32 [B, Hq, Nq] ([Hq, Tq] when packed).  Returns (out, lse).
     """
     import torch
 
     packed = cu_seqlens_q is not None or cu_seqlens_k is not None
     nd = 3 if packed else 4
+    if q.dtype not in (torch.bfloat16, torch.float16):
+        raise TypeError("q must be bfloat16 or float16")
     for name, t in (("q", q), ("k", k), ("v", v)):
-        if t.dtype != torch.bfloat16 or not t.is_cuda or t.dim() != nd or t.stride(-1) != 1:
-            raise ValueError(f"{name} must be a bf16 GPU tensor view with {nd} dimensions and a contiguous last one")
+        if t.dtype != q.dtype or not t.is_cuda or t.dim() != nd or t.stride(-1) != 1:
+            raise ValueError(f"{name} must be a GPU tensor view of q's dtype with {nd} dimensions and a contiguous "
+                             "last one")
     D = q.shape[-1]
     Hq, Hkv = q.shape[-3], k.shape[-3]
     if scale is None:
@@ -311,8 +316,8 @@ def swaa_attn_fwd_ex(q, k, v, window: int, n_sink: int, n_prompt: int | None = N
             out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
         if lse is None:
             lse = torch.empty(lse_shape, dtype=torch.float32, device=q.device)
-        if out.shape != q.shape or out.dtype != torch.bfloat16 or out.stride(-1) != 1:
-            raise ValueError("out must be a bf16 tensor view shaped like q with a contiguous last dimension")
+        if out.shape != q.shape or out.dtype != q.dtype or out.stride(-1) != 1:
+            raise ValueError("out must be a tensor view shaped and typed like q with a contiguous last dimension")
         if tuple(lse.shape) != lse_shape or lse.dtype != torch.float32 or not lse.is_contiguous():
             raise ValueError(f"lse must be a contiguous fp32 tensor of shape {lse_shape}")
         if stream is None:
@@ -334,6 +339,7 @@ def swaa_attn_fwd_ex(q, k, v, window: int, n_sink: int, n_prompt: int | None = N
         a.n_prompt = 2**31 - 1 if n_prompt is None else int(n_prompt)
         a.scale = float(scale)
         a.stream = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+        a.dtype = SWAA_F16 if q.dtype == torch.float16 else SWAA_BF16
         rc = swaa_attn_fwd_ex_raw(a)
     if rc != SWAA_OK:
         raise SwaaError(rc, swaa_status_string(rc))

@@ -93,6 +93,7 @@ int swaa_attn_fwd_ex(const swaa_fwd_args *a) {
     if (packed && (!a->cu_seqlens_q || !a->cu_seqlens_k)) return SWAA_ERR_NULL;
     if (!packed && Nq > Nk) return SWAA_ERR_SHAPE;  // the query rows are the newest Nq of Nk tokens
     if (D != 64 && D != 128) return SWAA_ERR_UNSUPPORTED;
+    if (a->dtype != SWAA_BF16 && a->dtype != SWAA_F16) return SWAA_ERR_UNSUPPORTED;
     for (const swaa_tensor *t : {&a->q, &a->k, &a->v, &a->out}) {
         if (misaligned(t->ptr)) return SWAA_ERR_ALIGN;
         if (bad_stride(t->stride_n, false) || t->stride_n < D || t->stride_n >= (1LL << 22)) return SWAA_ERR_SHAPE;
@@ -115,6 +116,7 @@ int swaa_attn_fwd_ex(const swaa_fwd_args *a) {
     p.v_sb = a->v.stride_b; p.v_sh = a->v.stride_h; p.v_sn = a->v.stride_n;
     p.o_sb = a->out.stride_b; p.o_sh = a->out.stride_h; p.o_sn = a->out.stride_n;
     p.lse_sb = a->lse_stride_b; p.lse_sh = a->lse_stride_h;
+    p.fp16 = a->dtype == SWAA_F16 ? 1 : 0;
     p.cu_q = a->cu_seqlens_q;
     p.cu_k = a->cu_seqlens_k;
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.Nq = Nq; p.Nk = Nk;
@@ -137,8 +139,10 @@ int swaa_attn_fwd_ex(const swaa_fwd_args *a) {
     if (grid > 0x7fffffffLL) return SWAA_ERR_SHAPE;
 
     hipStream_t s = static_cast<hipStream_t>(a->stream);
-    const hipError_t err = (D == 128 && !use_simple_kernel()) ? swaa::launch_fwd_pipelined_d128(p, s)
-                                                              : swaa::launch_fwd_simple(p, D, s);
+    // the pipelined kernel is bfloat16 only: its softmax keeps a fixed reference and leans on
+    // bfloat16's fp32-sized exponent; binary16 runs on the plain kernel, whose probabilities are <= 1
+    const hipError_t err = (D == 128 && !p.fp16 && !use_simple_kernel()) ? swaa::launch_fwd_pipelined_d128(p, s)
+                                                                          : swaa::launch_fwd_simple(p, D, s);
     return err == hipSuccess ? SWAA_OK : SWAA_ERR_LAUNCH;
 }
 
@@ -164,6 +168,7 @@ int swaa_attn_fwd_fa_decode(const void *q, const void *k, const void *v, void *o
     a.window = window; a.n_sink = n_sink; a.n_prompt = n_prompt;
     a.scale = scale;
     a.stream = stream;
+    a.dtype = SWAA_BF16;
     return swaa_attn_fwd_ex(&a);
 }
 
@@ -236,6 +241,7 @@ int bwd_plan(swaa::BwdParams &p, int B, int Hq, int Hkv, int N, int D, int windo
     if (window < 1 || n_sink < 0 || n_prompt < 0) return SWAA_ERR_SHAPE;
     if (D != 64 && D != 128) return SWAA_ERR_UNSUPPORTED;
     FwdParams &f = p.f;
+    f.fp16 = 0;
     f.B = B; f.Hq = Hq; f.Hkv = Hkv; f.Nq = N; f.Nk = N;
     f.W = window < N ? window : N;
     f.S = n_sink < N ? n_sink : N;

@@ -38,6 +38,7 @@ struct FwdParams {
     // axis (sequence b owns rows [cu[b], cu[b+1])), batch strides unused; or null
     const int *cu_q;
     const int *cu_k;
+    int fp16;  // the 16-bit elements of q, k, v, out are IEEE binary16 instead of bfloat16 (plain kernel only)
     int B, Hq, Hkv;
     int Nq, Nk;  // query rows and keys per sequence (the largest ones when cu_q / cu_k are given)
     int W, S;    // clamped to [1, Nk] and [0, Nk]

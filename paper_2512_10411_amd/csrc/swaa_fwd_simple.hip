@@ -42,14 +42,40 @@ struct Tile {
     static constexpr int kVElems = kBk * kVStride;
 };
 
-template <int D>
+// Element types: bfloat16 (the library's main format) and IEEE binary16 (the paper serves its
+// models in float16, Sec. 4.1.1).  Both share the 16-bit storage, the layouts and the MFMA shape.
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+template <typename E>
+struct Elem;
+template <>
+struct Elem<__bf16> {
+    using x8 = bf16x8;
+    using x4 = bf16x4;
+    static __device__ __forceinline__ f32x16 mfma(x8 a, x8 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+};
+template <>
+struct Elem<_Float16> {
+    using x8 = f16x8;
+    using x4 = f16x4;
+    static __device__ __forceinline__ f32x16 mfma(x8 a, x8 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+    }
+};
+
+template <int D, typename E>
 __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p) {
     using T = Tile<D>;
+    using X = Elem<E>;
+    using x8 = typename X::x8;
+    using x4 = typename X::x4;
     constexpr int KS = D / 16;  // k-steps of the QK^T contraction
     constexpr int DB = D / 32;  // 32-wide blocks of the head dimension
 
-    __shared__ __attribute__((aligned(16))) __bf16 Ks[T::kKElems];
-    __shared__ __attribute__((aligned(16))) __bf16 Vs[T::kVElems];
+    __shared__ __attribute__((aligned(16))) E Ks[T::kKElems];
+    __shared__ __attribute__((aligned(16))) E Vs[T::kVElems];
 
     WorkItem wi;
     if (!decode_work(p, wi)) return;
@@ -85,20 +111,20 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
     // tile order: 0 .. n_sink_tiles-1, then t_band_lo .. t_hi
     const int wbound = window_bound(p0, kWaveRows, W, P);
 
-    const __bf16 *kg = p.k + sg.k_batch * p.k_sb + (long long)kvh * p.k_sh + sg.k_row0 * p.k_sn;
-    const __bf16 *vg = p.v + sg.k_batch * p.v_sb + (long long)kvh * p.v_sh + sg.k_row0 * p.v_sn;
-    const __bf16 *qg = p.q + sg.q_batch * p.q_sb + (long long)head * p.q_sh + sg.q_row0 * p.q_sn;
-    __bf16 *og = p.out + sg.q_batch * p.o_sb + (long long)head * p.o_sh + sg.q_row0 * p.o_sn;
+    const E *kg = reinterpret_cast<const E *>(p.k) + sg.k_batch * p.k_sb + (long long)kvh * p.k_sh + sg.k_row0 * p.k_sn;
+    const E *vg = reinterpret_cast<const E *>(p.v) + sg.k_batch * p.v_sb + (long long)kvh * p.v_sh + sg.k_row0 * p.v_sn;
+    const E *qg = reinterpret_cast<const E *>(p.q) + sg.q_batch * p.q_sb + (long long)head * p.q_sh + sg.q_row0 * p.q_sn;
+    E *og = reinterpret_cast<E *>(p.out) + sg.q_batch * p.o_sb + (long long)head * p.o_sh + sg.q_row0 * p.o_sn;
 
     // ---- Q fragments (B operand of S^T = K Q^T), kept for the whole loop ----
-    bf16x8 qf[2][KS];
+    x8 qf[2][KS];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         const int row = min(r0 + 32 * qb + l32, Nq - 1);
-        const __bf16 *src = qg + (size_t)row * p.q_sn + 8 * hf;
+        const E *src = qg + (size_t)row * p.q_sn + 8 * hf;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-            qf[qb][ks] = *reinterpret_cast<const bf16x8 *>(src + 16 * ks);
+            qf[qb][ks] = *reinterpret_cast<const x8 *>(src + 16 * ks);
     }
 
     f32x16 oacc[DB][2];
@@ -171,11 +197,11 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
             for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(
+                    const x8 a = *reinterpret_cast<const x8 *>(
                         &Ks[(32 * kb + l32) * T::kKStride + 16 * ks + 8 * hf]);
 #pragma unroll
                     for (int qb = 0; qb < 2; ++qb)
-                        sacc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][ks], sacc[kb][qb], 0, 0, 0);
+                        sacc[kb][qb] = X::mfma(a, qf[qb][ks], sacc[kb][qb]);
                 }
             }
 
@@ -197,7 +223,7 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
             }
 
             // ---- online softmax; P^T packed to bf16 in B-operand order ----
-            bf16x8 pf[2][2][2];  // [kb][qb][16-key step]
+            x8 pf[2][2][2];  // [kb][qb][16-key step]
             float alpha[2];
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb) {
@@ -218,7 +244,7 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
                     for (int e = 0; e < 16; ++e) {
                         const float pe = __builtin_amdgcn_exp2f(fmaf(sacc[kb][qb][e], c2, -mc));
                         rs += pe;
-                        pf[kb][qb][e / 8][e % 8] = (__bf16)pe;
+                        pf[kb][qb][e / 8][e % 8] = (E)pe;
                     }
                 }
                 rs = half_swap_sum(rs);
@@ -249,17 +275,17 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
 #pragma unroll
                     for (int db = 0; db < DB; ++db) {
                         const int col = 32 * db + 16 * (grp & 1) + 4 * (j16 & 3);
-                        const __bf16 *a0 = &Vs[krow * T::kVStride + col];
-                        const __bf16 *a1 = a0 + 8 * T::kVStride;
+                        const E *a0 = &Vs[krow * T::kVStride + col];
+                        const E *a1 = a0 + 8 * T::kVStride;
                         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                             (s16x4 __attribute__((address_space(3))) *)(a0));
                         const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                             (s16x4 __attribute__((address_space(3))) *)(a1));
                         const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                        const bf16x8 a = __builtin_bit_cast(bf16x8, av);
+                        const x8 a = __builtin_bit_cast(x8, av);
 #pragma unroll
                         for (int qb = 0; qb < 2; ++qb)
-                            oacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[kb][qb][st], oacc[db][qb], 0, 0, 0);
+                            oacc[db][qb] = X::mfma(a, pf[kb][qb][st], oacc[db][qb]);
                     }
                 }
             }
@@ -279,15 +305,15 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
         const int row = r0 + 32 * qb + l32;
         if (row >= Nq) continue;
         const float inv_l = 1.f / l_run[qb];
-        __bf16 *orow = og + (size_t)row * p.o_sn;
+        E *orow = og + (size_t)row * p.o_sn;
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
 #pragma unroll
             for (int e4 = 0; e4 < 4; ++e4) {
-                bf16x4 o4;
+                x4 o4;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[db][qb][4 * e4 + e] * inv_l);
-                *reinterpret_cast<bf16x4 *>(orow + 32 * db + 8 * e4 + 4 * hf) = o4;
+                for (int e = 0; e < 4; ++e) o4[e] = (E)(oacc[db][qb][4 * e4 + e] * inv_l);
+                *reinterpret_cast<x4 *>(orow + 32 * db + 8 * e4 + 4 * hf) = o4;
             }
         }
         if (hf == 0)
@@ -300,10 +326,16 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
 
 hipError_t launch_fwd_simple(const FwdParams &p, int D, hipStream_t stream) {
     const unsigned grid = (unsigned)(p.chunk * kXcds);
-    if (D == 128)
-        hipLaunchKernelGGL(swaa_fwd_kernel<128>, dim3(grid), dim3(kThreads), 0, stream, p);
-    else
-        hipLaunchKernelGGL(swaa_fwd_kernel<64>, dim3(grid), dim3(kThreads), 0, stream, p);
+    if (p.fp16) {
+        if (D == 128)
+            hipLaunchKernelGGL((swaa_fwd_kernel<128, _Float16>), dim3(grid), dim3(kThreads), 0, stream, p);
+        else
+            hipLaunchKernelGGL((swaa_fwd_kernel<64, _Float16>), dim3(grid), dim3(kThreads), 0, stream, p);
+    } else if (D == 128) {
+        hipLaunchKernelGGL((swaa_fwd_kernel<128, __bf16>), dim3(grid), dim3(kThreads), 0, stream, p);
+    } else {
+        hipLaunchKernelGGL((swaa_fwd_kernel<64, __bf16>), dim3(grid), dim3(kThreads), 0, stream, p);
+    }
     return hipGetLastError();
 }
 

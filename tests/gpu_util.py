@@ -8,9 +8,10 @@ O_MEAN_ABS = 2e-3
 LSE_MAX_ABS = 1e-3
 
 
-def to_device(bits: np.ndarray) -> torch.Tensor:
-    """uint16 bf16 bit patterns -> bf16 tensor on cuda:0 (bit-exact)."""
-    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).cuda()
+def to_device(bits: np.ndarray, fmt: str = "bf16") -> torch.Tensor:
+    """uint16 bf16 (or binary16) bit patterns -> tensor of that type on cuda:0 (bit-exact)."""
+    dtype = torch.bfloat16 if fmt == "bf16" else torch.float16
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(dtype).cuda()
 
 
 def errors(out_gpu: torch.Tensor, lse_gpu: torch.Tensor, out_ref: np.ndarray, lse_ref: np.ndarray, rows=None):

@@ -1,0 +1,58 @@
+"""GPU parity of the binary16 path of swaa_attn_fwd_ex (the precision the paper serves its
+models in, Sec. 4.1.1) against the fp64 CPU oracle reading the same binary16 inputs.  The
+acceptance tolerances of the bfloat16 path apply (binary16 rounds three bits finer).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import input_format, swaa_attn_oracle, swaa_decode_oracle
+from paper_2512_10411_amd import binding
+from paper_2512_10411_amd.inputs import make_qkv, sample_rows
+from gpu_util import assert_parity, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def check(B, Hq, Hkv, Nq, Nk, D, W, S, P, seed, rows=None):
+    tag = f"fp16 B{B} Hq{Hq} Hkv{Hkv} Nq{Nq} Nk{Nk} D{D} W{W} S{S} P{P}"
+    print(f"[case] {tag} seed {seed}", flush=True)
+    scale = 1 / math.sqrt(D)
+    q, k, v = make_qkv(B, Hq, Hkv, Nk, D, seed, n_query=None if Nq == Nk else Nq, fmt="fp16")
+    out, lse = binding.swaa_attn_fwd_ex(to_device(q, "fp16"), to_device(k, "fp16"), to_device(v, "fp16"), W, S, P, scale)
+    torch.cuda.synchronize()
+    assert out.dtype == torch.float16
+    with input_format("fp16"):
+        if Nq == Nk:
+            ro, rl = swaa_attn_oracle(q, k, v, W, S, scale, rows=rows, n_prompt=P)
+        else:
+            ro, rl = swaa_decode_oracle(q, k, v, W, S, scale, n_prompt=P)
+    assert_parity(out, lse, ro, rl, rows=rows, tag=tag)
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_small_shapes(D):
+    for N in (1, 63, 65, 257, 700):
+        for W, S, P in ((1, 0, None), (7, 4, None), (64, 70, None), (N, 0, None), (50, 3, N // 2)):
+            check(1, 4, 1, N, N, D, W, S, P, seed=9600 + N + D)
+    check(2, 10, 2, 333, 333, D, 100, 3, None, seed=9700 + D)   # GQA 5 = 4 + 1, two batch entries
+    check(1, 4, 2, 100, 777, D, 64, 4, None, seed=9710 + D)     # a chunk of a longer prefill
+
+
+def test_sink_heavy_scores_keep_probabilities_in_range():
+    # scores tens of nats apart: the plain kernel's probabilities never exceed 1, so binary16 cannot overflow
+    B, Hq, Hkv, N, D = 1, 4, 1, 2000, 128
+    q, k, v = make_qkv(B, Hq, Hkv, N, D, seed=9720, k_mult=4.0, fmt="fp16")
+    out, lse = binding.swaa_attn_fwd_ex(to_device(q, "fp16"), to_device(k, "fp16"), to_device(v, "fp16"), 512, 4)
+    torch.cuda.synchronize()
+    with input_format("fp16"):
+        ro, rl = swaa_attn_oracle(q, k, v, 512, 4, 1 / math.sqrt(D))
+    assert_parity(out, lse, ro, rl, tag="fp16 peaked softmax")
+
+
+def test_mid_size_sampled_rows():
+    B, Hq, Hkv, N, D, W, S = 1, 32, 8, 16384, 128, 2048, 4
+    rows = sample_rows(N, W, S, count=128, seed=9730)
+    check(B, Hq, Hkv, N, N, D, W, S, None, seed=9730, rows=rows)
