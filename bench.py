@@ -175,7 +175,7 @@ def main():
 
     def dev(bits):
         import numpy as np
-        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+        return torch.from_numpy(bits.view(np.int16)).view(torch.float16 if w.fmt == "fp16" else torch.bfloat16).cuda()
 
     qd, kd, vd = dev(q), dev(k), dev(v)
     out = torch.empty_like(qd)
@@ -204,7 +204,7 @@ def main():
         elif decode:
             binding.swaa_attn_decode(qd, kd, vd, w.window, w.n_sink, w.scale, out=out, lse=lse, workspace=ws,
                                      stream=stream)
-        elif w.chunk:
+        elif w.chunk or w.fmt == "fp16":
             binding.swaa_attn_fwd_ex(qd, kd, vd, w.window, w.n_sink, w.n_prompt, w.scale, out=out, lse=lse,
                                      stream=stream)
         elif w.n_prompt is None:
@@ -259,10 +259,12 @@ def main():
                     "traffic": traffic, "kernel": "swaa_decode_split_kernel (+ swaa_decode_merge_kernel)",
                     "kernel_avg_ms": kern_avg_ms, "algorithmic_bytes": algo_bytes}
     else:
+        # (the fp16 matrix peak equals the bf16 one)
         roofline = {"bound": "mfma", "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": traffic,
                     "kernel": ("swaa_bwd_dkv_kernel + swaa_bwd_dq_kernel + swaa_bwd_delta_kernel" if w.backward
-                               else "swaa_fwd_pipelined_kernel" if w.D == 128 else "swaa_fwd_kernel<64>"),
+                               else "swaa_fwd_pipelined_kernel" if w.D == 128 and w.fmt == "bf16"
+                               else f"swaa_fwd_kernel<{w.D}>"),
                     "kernel_avg_ms": kern_avg_ms}
 
     res = {
@@ -276,7 +278,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": "f16" if w.fmt == "fp16" else "bf16",
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "N": w.N, "n_query": w.n_query or w.N,
                    "D": w.D,
@@ -286,9 +288,11 @@ def main():
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = (cpu_baseline_backward(w, q, k, v, dout) if w.backward
-                               else cpu_baseline_decode(w, q, k, v) if decode or w.chunk
-                               else cpu_baseline(w, q, k, v, args.cpu_seconds))
+        from oracle import input_format
+        with input_format(w.fmt):
+            res["cpu_baseline"] = (cpu_baseline_backward(w, q, k, v, dout) if w.backward
+                                   else cpu_baseline_decode(w, q, k, v) if decode or w.chunk
+                                   else cpu_baseline(w, q, k, v, args.cpu_seconds))
         res["cpu_baseline"]["gpu_over_cpu"] = value / res["cpu_baseline"]["value"]
     print(json.dumps(res), flush=True)
     return 0

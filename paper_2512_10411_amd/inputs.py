@@ -51,6 +51,7 @@ class Workload:
     n_query: int | None = None   # decode-shape and chunk runs: q holds only the n_query newest of the N tokens
     chunk: bool = False          # n_query rows are a chunk of a longer prefill (general forward), not a decode step
     backward: bool = False       # the timed call is the backward pass (the forward runs once, untimed)
+    fmt: str = "bf16"            # element format of q, k, v, out: "bf16" or "fp16"
 
     @property
     def scale(self) -> float:
@@ -82,6 +83,8 @@ WORKLOADS = {
     "decode128k_full": Workload("decode128k_full", 1, 32, 8, 131072, 128, 131072, 4, _SEED0 + 6, n_query=1),
     "decode128k_swa": Workload("decode128k_swa", 1, 32, 8, 131072, 128, 8192, 4, _SEED0 + 6, n_query=1),
     "decode16k_b16": Workload("decode16k_b16", 16, 32, 8, 16384, 128, 16384, 4, _SEED0 + 7, n_query=1),
+    # the mid-size layer in binary16, the precision the paper serves in (Sec. 4.1.1); same draws
+    "mid_fp16": Workload("mid_fp16", 1, 32, 8, 16384, 128, 2048, 4, _SEED0 + 2, fmt="fp16"),
     # backward pass of the mid-size layer (fine-tuning under the window + sink mask)
     "mid_bwd": Workload("mid_bwd", 1, 32, 8, 16384, 128, 2048, 4, _SEED0 + 2, backward=True),
     # the last 2048-row chunk of a 128k-token prefill whose earlier keys and values are cached
@@ -128,7 +131,7 @@ def make_qkv(B, Hq, Hkv, N, D, seed, k_mult=1.0, chunk_rows=1 << 22, n_query=Non
 
 def make_workload(w: Workload):
     """q, k, v (uint16 bf16 bits) for a named workload."""
-    return make_qkv(w.B, w.Hq, w.Hkv, w.N, w.D, w.seed, w.k_mult, n_query=w.n_query)
+    return make_qkv(w.B, w.Hq, w.Hkv, w.N, w.D, w.seed, w.k_mult, n_query=w.n_query, fmt=w.fmt)
 
 
 def sample_rows(N, window, n_sink, count=256, seed=0, tile=64):
