@@ -197,6 +197,47 @@ int swaa_attn_decode(const void *q, const void *k, const void *v, void *out, flo
                      float scale, void *workspace, long long workspace_bytes, void *stream);
 
 /*
+ * The general form of swaa_attn_decode, for the caches of a serving engine
+ * (paper Sec. 4.1.1: the models are served with vLLM, batch size 64): strided
+ * or PAGED key/value caches and a batch of sequences with different cache
+ * lengths.
+ *
+ *   q, out, lse   as in swaa_attn_decode (contiguous [B, Hq, Nq, D] / [B, Hq, Nq])
+ *   seq_lens      device, B ints, or NULL: the number of cached tokens of each
+ *                 sequence, the Nq newest included (values are clamped to [Nq, Nk]);
+ *                 NULL: every sequence holds Nk tokens
+ *   contiguous cache (block_table NULL): k, v are tensors as in swaa_fwd_args, key
+ *                 row j of (b, kvh) at ptr + b * stride_b + kvh * stride_h + j * stride_n
+ *   paged cache   block_table: device, B rows of block_table_stride ints; token j of
+ *                 sequence b lives in page block_table[b][j / page_size], and its
+ *                 row of KV head kvh at
+ *                 ptr + page * stride_b + kvh * stride_h + (j % page_size) * stride_n;
+ *                 page_size a multiple of 4, block_table_stride * page_size >= Nk,
+ *                 num_pages = pages in the cache (page numbers are clamped to it)
+ *   Nk            the largest cache length (the key splits are planned for it);
+ *                 workspace from swaa_attn_decode_workspace_bytes with this Nk
+ *
+ * Everything else as in swaa_attn_decode.
+ */
+typedef struct swaa_decode_args {
+    const void *q;
+    void *out;
+    float *lse;
+    swaa_tensor k, v;
+    const int *seq_lens;
+    const int *block_table;
+    int block_table_stride, page_size, num_pages;
+    int B, Hq, Hkv, Nq, Nk, D;
+    int window, n_sink;
+    float scale;
+    void *workspace;
+    long long workspace_bytes;
+    void *stream;
+} swaa_decode_args;
+
+int swaa_attn_decode_ex(const swaa_decode_args *args);
+
+/*
  * Bytes of workspace swaa_attn_decode needs for these shape arguments (a few
  * KiB per key split; host-only arithmetic), or a negative swaa_status if the
  * arguments are invalid.

@@ -27,7 +27,7 @@ SWAA_F16 = 1
 # every symbol include/swaa.h declares
 EXPORTS = ("swaa_attn_fwd", "swaa_attn_fwd_fa_decode", "swaa_attn_fwd_ex", "swaa_visible_pairs",
            "swaa_visible_pairs_fa_decode",
-           "swaa_attn_decode", "swaa_attn_decode_workspace_bytes", "swaa_attn_bwd", "swaa_attn_bwd_workspace_bytes",
+           "swaa_attn_decode", "swaa_attn_decode_ex", "swaa_attn_decode_workspace_bytes", "swaa_attn_bwd", "swaa_attn_bwd_workspace_bytes",
            "swaa_status_string", "swaa_version")
 
 _lib = None
@@ -48,6 +48,18 @@ class SwaaFwdArgs(ctypes.Structure):
                 ("cu_seqlens_q", ctypes.c_void_p), ("cu_seqlens_k", ctypes.c_void_p),
                 ("window", ctypes.c_int), ("n_sink", ctypes.c_int), ("n_prompt", ctypes.c_int),
                 ("scale", ctypes.c_float), ("stream", ctypes.c_void_p), ("dtype", ctypes.c_int)]
+
+
+class SwaaDecodeArgs(ctypes.Structure):
+    """swaa_decode_args of include/swaa.h."""
+    _fields_ = [("q", ctypes.c_void_p), ("out", ctypes.c_void_p), ("lse", ctypes.c_void_p),
+                ("k", SwaaTensor), ("v", SwaaTensor),
+                ("seq_lens", ctypes.c_void_p), ("block_table", ctypes.c_void_p),
+                ("block_table_stride", ctypes.c_int), ("page_size", ctypes.c_int), ("num_pages", ctypes.c_int),
+                ("B", ctypes.c_int), ("Hq", ctypes.c_int), ("Hkv", ctypes.c_int), ("Nq", ctypes.c_int),
+                ("Nk", ctypes.c_int), ("D", ctypes.c_int), ("window", ctypes.c_int), ("n_sink", ctypes.c_int),
+                ("scale", ctypes.c_float), ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_longlong),
+                ("stream", ctypes.c_void_p)]
 
 
 class SwaaError(RuntimeError):
@@ -86,6 +98,8 @@ def load_library() -> ctypes.CDLL:
         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
         ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
         ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_void_p, ctypes.c_longlong, ctypes.c_void_p]
+    lib.swaa_attn_decode_ex.restype = ctypes.c_int
+    lib.swaa_attn_decode_ex.argtypes = [ctypes.POINTER(SwaaDecodeArgs)]
     lib.swaa_attn_decode_workspace_bytes.restype = ctypes.c_longlong
     lib.swaa_attn_decode_workspace_bytes.argtypes = [ctypes.c_int] * 8
     lib.swaa_attn_bwd.restype = ctypes.c_int
@@ -400,3 +414,73 @@ def swaa_attn_bwd(q, k, v, out, lse, dout, window: int, n_sink: int, n_prompt: i
     if rc != SWAA_OK:
         raise SwaaError(rc, swaa_status_string(rc))
     return dq, dk, dv
+
+
+def swaa_attn_decode_ex_raw(args: SwaaDecodeArgs) -> int:
+    """The C call itself on a filled argument block; returns the status code."""
+    return int(load_library().swaa_attn_decode_ex(ctypes.byref(args)))
+
+
+def swaa_attn_decode_ex(q, k, v, window: int, n_sink: int, scale: float | None = None, seq_lens=None,
+                        block_table=None, max_seqlen_k: int | None = None, out=None, lse=None, workspace=None,
+                        stream=None):
+    """Decode-shape attention on a strided or paged cache, with per-sequence cache lengths.
+
+    q: bf16 [B, Hq, Nq, D] contiguous.  Contiguous cache: k, v views [B, Hkv, Nk, D] with any
+    strides (last dimension contiguous).  Paged cache: block_table int32 [B, pages_per_seq] on
+    the GPU and k, v views [num_pages, Hkv, page_size, D] (a [num_pages, page_size, Hkv, D]
+    cache is passed as ``cache.permute(0, 2, 1, 3)``).  seq_lens: int32 [B] GPU tensor of cache
+    lengths (the Nq newest tokens included) or None; max_seqlen_k: the largest of them (required
+    with a paged cache).  Returns (out, lse).
+    """
+    import torch
+
+    if q.dtype != torch.bfloat16 or not q.is_cuda or not q.is_contiguous() or q.dim() != 4:
+        raise ValueError("q must be a contiguous bf16 [B, Hq, Nq, D] GPU tensor")
+    for name, t in (("k", k), ("v", v)):
+        if t.dtype != torch.bfloat16 or not t.is_cuda or t.dim() != 4 or t.stride(-1) != 1:
+            raise ValueError(f"{name} must be a bf16 GPU tensor view with 4 dimensions and a contiguous last one")
+    B, Hq, Nq, D = q.shape
+    Hkv = k.shape[1]
+    paged = block_table is not None
+    if paged:
+        if max_seqlen_k is None:
+            raise ValueError("a paged cache needs max_seqlen_k")
+        if block_table.dtype != torch.int32 or not block_table.is_cuda or block_table.dim() != 2 \
+                or block_table.stride(1) != 1 or block_table.shape[0] != B:
+            raise ValueError("block_table must be an int32 [B, pages_per_seq] GPU tensor with contiguous rows")
+        Nk = int(max_seqlen_k)
+    else:
+        Nk = k.shape[2] if max_seqlen_k is None else int(max_seqlen_k)
+    if seq_lens is not None and (seq_lens.dtype != torch.int32 or not seq_lens.is_cuda or not seq_lens.is_contiguous()
+                                 or seq_lens.shape != (B,)):
+        raise ValueError("seq_lens must be a contiguous int32 [B] GPU tensor")
+    if scale is None:
+        scale = 1.0 / math.sqrt(D)
+    need = swaa_attn_decode_workspace_bytes(B, Hq, Hkv, Nq, Nk, D, window, n_sink)
+    with torch.cuda.device(q.device):
+        if out is None:
+            out = torch.empty_like(q)
+        if lse is None:
+            lse = torch.empty((B, Hq, Nq), dtype=torch.float32, device=q.device)
+        if workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        if stream is None:
+            stream = torch.cuda.current_stream(q.device)
+        a = SwaaDecodeArgs()
+        a.q, a.out, a.lse = q.data_ptr(), out.data_ptr(), lse.data_ptr()
+        a.k = SwaaTensor(k.data_ptr(), k.stride(0), k.stride(1), k.stride(2))
+        a.v = SwaaTensor(v.data_ptr(), v.stride(0), v.stride(1), v.stride(2))
+        a.seq_lens = seq_lens.data_ptr() if seq_lens is not None else None
+        a.block_table = block_table.data_ptr() if paged else None
+        a.block_table_stride = block_table.stride(0) if paged else 0
+        a.page_size = k.shape[2] if paged else 0
+        a.num_pages = k.shape[0] if paged else 0
+        a.B, a.Hq, a.Hkv, a.Nq, a.Nk, a.D = B, Hq, Hkv, Nq, Nk, D
+        a.window, a.n_sink, a.scale = int(window), int(n_sink), float(scale)
+        a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
+        a.stream = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+        rc = swaa_attn_decode_ex_raw(a)
+    if rc != SWAA_OK:
+        raise SwaaError(rc, swaa_status_string(rc))
+    return out, lse

@@ -207,29 +207,64 @@ long long swaa_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Nq, int N
     return swaa::decode_workspace_floats(p) * (long long)sizeof(float);
 }
 
+int swaa_attn_decode_ex(const swaa_decode_args *a) {
+    if (!a) return SWAA_ERR_NULL;
+    if (!a->q || !a->k.ptr || !a->v.ptr || !a->out || !a->lse) return SWAA_ERR_NULL;
+    swaa::DecodeParams p{};
+    const int rc = decode_plan(p, a->B, a->Hq, a->Hkv, a->Nq, a->Nk, a->D, a->window, a->n_sink);
+    if (rc != SWAA_OK) return rc;
+    if (!positive_finite(a->scale)) return SWAA_ERR_SHAPE;
+    const bool paged = a->block_table != nullptr;
+    if (paged && (a->page_size < 4 || a->page_size % 4 != 0 || a->num_pages < 1 || a->block_table_stride < 1))
+        return SWAA_ERR_SHAPE;
+    if (paged && (long long)a->block_table_stride * a->page_size < a->Nk) return SWAA_ERR_SHAPE;  // table too short for Nk tokens
+    for (const swaa_tensor *t : {&a->k, &a->v}) {
+        if (misaligned(t->ptr)) return SWAA_ERR_ALIGN;
+        if (bad_stride(t->stride_n, false) || t->stride_n < a->D || t->stride_n >= (1LL << 22)) return SWAA_ERR_SHAPE;
+        if (bad_stride(t->stride_h, a->Hkv == 1) || bad_stride(t->stride_b, paged ? a->num_pages == 1 : a->B == 1))
+            return SWAA_ERR_SHAPE;
+    }
+    if (misaligned(a->q) || misaligned(a->out)) return SWAA_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(a->lse) & 3u) != 0) return SWAA_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(a->seq_lens) | reinterpret_cast<uintptr_t>(a->block_table)) & 3u) return SWAA_ERR_ALIGN;
+    const long long need = swaa::decode_workspace_floats(p) * (long long)sizeof(float);
+    if (!a->workspace || misaligned(a->workspace) || a->workspace_bytes < need) return SWAA_ERR_WORKSPACE;
+
+    p.q = static_cast<const __bf16 *>(a->q);
+    p.k = static_cast<const __bf16 *>(a->k.ptr);
+    p.v = static_cast<const __bf16 *>(a->v.ptr);
+    p.out = static_cast<__bf16 *>(a->out);
+    p.lse = a->lse;
+    p.k_sb = a->k.stride_b; p.k_sh = a->k.stride_h; p.k_sn = a->k.stride_n;
+    p.v_sb = a->v.stride_b; p.v_sh = a->v.stride_h; p.v_sn = a->v.stride_n;
+    p.block_table = a->block_table;
+    p.bt_stride = a->block_table_stride;
+    p.page_size = paged ? a->page_size : 1;
+    p.num_pages = paged ? a->num_pages : 1;
+    p.seq_lens = a->seq_lens;
+    p.ws_o = static_cast<float *>(a->workspace);
+    p.ws_ml = p.ws_o + p.items * (long long)p.col_stride * 128;
+    p.scale_log2 = a->scale * 1.44269504088896340736f;
+    const hipError_t err = swaa::launch_decode(p, static_cast<hipStream_t>(a->stream));
+    return err == hipSuccess ? SWAA_OK : SWAA_ERR_LAUNCH;
+}
+
 int swaa_attn_decode(const void *q, const void *k, const void *v, void *out, float *lse,
                      int B, int Hq, int Hkv, int Nq, int Nk, int D, int window, int n_sink,
                      float scale, void *workspace, long long workspace_bytes, void *stream) {
     if (!q || !k || !v || !out || !lse) return SWAA_ERR_NULL;
-    swaa::DecodeParams p{};
-    const int rc = decode_plan(p, B, Hq, Hkv, Nq, Nk, D, window, n_sink);
-    if (rc != SWAA_OK) return rc;
-    if (!positive_finite(scale)) return SWAA_ERR_SHAPE;
-    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(lse))
-        return SWAA_ERR_ALIGN;
-    const long long need = swaa::decode_workspace_floats(p) * (long long)sizeof(float);
-    if (!workspace || misaligned(workspace) || workspace_bytes < need) return SWAA_ERR_WORKSPACE;
-
-    p.q = static_cast<const __bf16 *>(q);
-    p.k = static_cast<const __bf16 *>(k);
-    p.v = static_cast<const __bf16 *>(v);
-    p.out = static_cast<__bf16 *>(out);
-    p.lse = lse;
-    p.ws_o = static_cast<float *>(workspace);
-    p.ws_ml = p.ws_o + p.items * (long long)p.col_stride * 128;
-    p.scale_log2 = scale * 1.44269504088896340736f;
-    const hipError_t err = swaa::launch_decode(p, static_cast<hipStream_t>(stream));
-    return err == hipSuccess ? SWAA_OK : SWAA_ERR_LAUNCH;
+    swaa_decode_args a{};
+    a.q = q;
+    a.out = out;
+    a.lse = lse;
+    // a contiguous [B, Hkv, Nk, D] cache, every sequence Nk tokens long
+    const long long nd = (long long)(Nk > 0 ? Nk : 0) * (D > 0 ? D : 0);
+    a.k = {const_cast<void *>(k), (long long)(Hkv > 0 ? Hkv : 0) * nd, nd, D};
+    a.v = {const_cast<void *>(v), (long long)(Hkv > 0 ? Hkv : 0) * nd, nd, D};
+    a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.Nq = Nq; a.Nk = Nk; a.D = D;
+    a.window = window; a.n_sink = n_sink; a.scale = scale;
+    a.workspace = workspace; a.workspace_bytes = workspace_bytes; a.stream = stream;
+    return swaa_attn_decode_ex(&a);
 }
 
 namespace {

@@ -10,7 +10,7 @@ namespace swaa {
 // The query rows of one (batch, KV head) pair -- G heads x Nq rows, contiguous
 // in q -- are the columns of 32-wide column tiles.  The visited keys (sink
 // halves, then the halves from the first row's window to the end of the cache;
-// a half is 32 keys) are cut into splits; one single-wave workgroup computes
+// a half is 32 keys; `visited_halves` below) are cut into splits; one single-wave workgroup computes
 // one (pair, column tile, split) item and leaves an unnormalised partial result
 // in the workspace; a second kernel merges the splits.
 struct DecodeParams {
@@ -21,17 +21,41 @@ struct DecodeParams {
     float *lse;
     float *ws_o;   // [items][col_stride][128]: sum of 2^(s c2 - mc) v over the item's keys
     float *ws_ml;  // [items][2][32]: mc (softmax reference, log2 units) and l (sum of 2^(s c2 - mc))
+    // Cache addressing, in elements; the head dimension is contiguous.
+    //   contiguous: row `key` of (b, kvh) at  k + b * k_sb + kvh * k_sh + key * k_sn
+    //   paged:      page = block_table[b * bt_stride + key / page_size] and the row at
+    //               k + page * k_sb + kvh * k_sh + (key % page_size) * k_sn
+    long long k_sb, k_sh, k_sn;
+    long long v_sb, v_sh, v_sn;
+    const int *block_table;  // device, or null for a contiguous cache
+    int bt_stride, page_size, num_pages;
+    const int *seq_lens;  // device, B cache lengths (each <= Nk), or null: every sequence holds Nk tokens
     int B, Hq, Hkv, G;
-    int Nq, Nk;
-    int W, S;  // clamped to [1, Nk] and [0, Nk]
+    int Nq, Nk;  // Nk: the (largest) cache length; the plan is made for it
+    int W, S;    // clamped to [1, Nk] and [0, Nk]
     float scale_log2;
     int cols;        // G * Nq query rows per pair
     int n_coltiles;  // ceil(cols / 32)
     int col_stride;  // min(cols, 32): columns an item stores
-    int n_sink_halves, band_half0, n_halves;  // visited halves: sink halves 0.., then key halves band_half0..
+    int n_halves;  // visited halves of a sequence of Nk tokens (shorter sequences visit fewer)
     int halves_per_split, n_splits;
     long long items;  // B * Hkv * n_coltiles * n_splits
 };
+
+// The halves a sequence of nk cached tokens visits: halves 0 .. n_sink-1, then key halves band0 ..
+struct VisitedHalves {
+    int n_sink, band0, n;
+};
+__host__ __device__ inline VisitedHalves visited_halves(int nk, int nq, int W, int S) {
+    VisitedHalves h;
+    const int band_lo = (nk - nq) - W + 1 > 0 ? (nk - nq) - W + 1 : 0;  // first key of the oldest row's window
+    h.band0 = band_lo / 32;
+    const int sink_keys = S < band_lo ? S : band_lo;
+    const int sink_halves = (sink_keys + 31) / 32;
+    h.n_sink = sink_halves < h.band0 ? sink_halves : h.band0;
+    h.n = h.n_sink + ((nk - 1) / 32 - h.band0 + 1);
+    return h;
+}
 
 // Fills the plan fields (everything from `cols` on) from the shape fields.
 void plan_decode(DecodeParams &p);

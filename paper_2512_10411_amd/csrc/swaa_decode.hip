@@ -22,6 +22,10 @@
 //     MFMAs), max-based softmax (mask only on halves that are not fully visible),
 //     O^T += V^T P^T (8 MFMAs).  The copies thus never wait for arithmetic.  The
 //     query rows arrive through the ring's last stage before half 2 needs it.
+//   * The cache is a contiguous strided tensor or a paged one (a block table of
+//     page numbers per sequence, pages of page_size tokens: the layout of a
+//     serving engine's cache manager); sequences of a batch may have different
+//     cache lengths (seq_lens), shorter ones leave empty partial results.
 //   * Each workgroup leaves (O unnormalised, reference, row sum) for its valid
 //     columns in the workspace; swaa_decode_merge_kernel combines the splits.
 //
@@ -60,7 +64,10 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
     const int lane = threadIdx.x;
     const int l32 = lane & 31;
     const int hf = lane >> 5;
-    const int Nk = p.Nk, W = p.W, S = p.S;
+    // this sequence's cache length (at least the query rows themselves) and its visited halves
+    const int Nk = p.seq_lens ? max(min(p.seq_lens[b], p.Nk), p.Nq) : p.Nk;
+    const int W = p.W, S = p.S;
+    const VisitedHalves vh = visited_halves(Nk, p.Nq, W, S);
 
     // this lane's query column: row c of the pair's G x Nq block (clamped: padding
     // columns repeat the last row and are never stored)
@@ -71,29 +78,63 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
     const int pos_min = Nk - p.Nq, pos_max = Nk - 1;
 
     const int h_begin = split * p.halves_per_split;
-    const int n_mine = min(p.n_halves - h_begin, p.halves_per_split);  // >= 1 by construction of the plan
+    const int n_mine = min(vh.n - h_begin, p.halves_per_split);
+    if (n_mine <= 0) {
+        // a shorter sequence has no keys for this split: an empty partial result (weight 0 in the merge)
+        if (col_valid && hf == 0) {
+            p.ws_ml[(size_t)item * 64 + l32] = -INFINITY;
+            p.ws_ml[(size_t)item * 64 + 32 + l32] = 0.f;
+        }
+        return;
+    }
     auto first_key = [&](int t) {
         const int h = h_begin + t;
-        return 32 * (h < p.n_sink_halves ? h : h - p.n_sink_halves + p.band_half0);
+        return 32 * (h < vh.n_sink ? h : h - vh.n_sink + vh.band0);
     };
 
-    const size_t kv_base = ((size_t)b * p.Hkv + kvh) * (size_t)Nk * kD;
-    const char *kg = reinterpret_cast<const char *>(p.k + kv_base);
-    const char *vg = reinterpret_cast<const char *>(p.v + kv_base);
+    const bool paged = p.block_table != nullptr;
+    const uint32_t k_rsb = (uint32_t)(p.k_sn * 2), v_rsb = (uint32_t)(p.v_sn * 2);  // row strides in bytes
+    const char *kg = reinterpret_cast<const char *>(p.k + (paged ? 0 : b * p.k_sb) + (long long)kvh * p.k_sh);
+    const char *vg = reinterpret_cast<const char *>(p.v + (paged ? 0 : b * p.v_sb) + (long long)kvh * p.v_sh);
+    const int *bt = paged ? p.block_table + (size_t)b * p.bt_stride : nullptr;
 
     // ---- HBM -> LDS copies of one half: instruction i moves rows 4i .. 4i+3, 16 lanes
-    // per row; the XOR swizzle of the operand reads is applied on the global side ----
+    // per row; the XOR swizzle of the operand reads is applied on the global side.  Rows
+    // past the end of the cache repeat its last row (they are masked later). ----
     const int lrow = lane >> 4, lchk = lane & 15;
     auto issue_half = [&](int t, int stage) {
         const int k0 = first_key(t);
-        const char *kb = kg + (size_t)k0 * kRowBytes;  // uniform
-        const char *vb = vg + (size_t)k0 * kRowBytes;
         const uint32_t lds = (uint32_t)(stage * kDStageBytes);
+        if (paged) {
+            // page_size is a multiple of 4, halves start at multiples of 32: the four rows of one
+            // instruction share a page, so the page number is a uniform (scalar) table lookup
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int key4 = min(k0 + 4 * i, Nk - 1) & ~3;  // first row of the instruction, inside the cache
+                const int page = min(max(bt[key4 / p.page_size], 0), p.num_pages - 1);  // inside the cache whatever the table says
+                const int in_page = key4 % p.page_size;
+                const char *kb = kg + ((long long)page * p.k_sb + (long long)in_page * p.k_sn) * 2;
+                const char *vb = vg + ((long long)page * p.v_sb + (long long)in_page * p.v_sn) * 2;
+                const int row = min(key4 + lrow, Nk - 1) - key4;
+                const int fk = ((4 * (i & 1) + lrow) << 1) | ((i >> 1) & 1);
+                const uint32_t koff = (uint32_t)row * k_rsb + (uint32_t)((lchk ^ fk) << 4);
+                const uint32_t voff = (uint32_t)row * v_rsb + (uint32_t)((lchk ^ (lrow << 2)) << 4);
+                asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(koff), "s"(kb),
+                             "s"(lds + (uint32_t)(i * 1024))
+                             : "memory");
+                asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(vb),
+                             "s"(lds + (uint32_t)(kHalfBytes + i * 1024))
+                             : "memory");
+            }
+            return;
+        }
+        const char *kb = kg + (size_t)k0 * k_rsb;  // uniform
+        const char *vb = vg + (size_t)k0 * v_rsb;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int row = min(4 * i + lrow, Nk - 1 - k0);  // rows past the end repeat the last key; masked later
+            const int row = min(4 * i + lrow, Nk - 1 - k0);
             const int fk = ((4 * (i & 1) + lrow) << 1) | ((i >> 1) & 1);
-            const uint32_t off = (uint32_t)(row * kRowBytes + ((lchk ^ fk) << 4));
+            const uint32_t off = (uint32_t)row * k_rsb + (uint32_t)((lchk ^ fk) << 4);
             asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(kb),
                          "s"(lds + (uint32_t)(i * 1024))
                          : "memory");
@@ -101,7 +142,7 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int row = min(4 * i + lrow, Nk - 1 - k0);
-            const uint32_t off = (uint32_t)(row * kRowBytes + ((lchk ^ (lrow << 2)) << 4));
+            const uint32_t off = (uint32_t)row * v_rsb + (uint32_t)((lchk ^ (lrow << 2)) << 4);
             asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(vb),
                          "s"(lds + (uint32_t)(kHalfBytes + i * 1024))
                          : "memory");
@@ -261,7 +302,9 @@ __global__ __launch_bounds__(kMergeThreads) void swaa_decode_merge_kernel(const 
 #pragma unroll 4
     for (int s = g; s < p.n_splits; s += kMergeThreads / kD) {
         const long long it = item_of(s);
-        const float w = __builtin_amdgcn_exp2f(p.ws_ml[it * 64 + col] - m);  // 0 for a split that saw no visible key
+        const float mcs = p.ws_ml[it * 64 + col];
+        if (mcs == -INFINITY) continue;  // no visible key in this split (its O may not even be written)
+        const float w = __builtin_amdgcn_exp2f(mcs - m);
         l += w * p.ws_ml[it * 64 + 32 + col];
         acc += w * p.ws_o[(it * p.col_stride + col) * kD + d];
     }
@@ -286,12 +329,7 @@ void plan_decode(DecodeParams &p) {
     p.cols = p.G * p.Nq;
     p.n_coltiles = (p.cols + 31) / 32;
     p.col_stride = p.cols < 32 ? p.cols : 32;
-    const int band_lo = (p.Nk - p.Nq) - p.W + 1 > 0 ? (p.Nk - p.Nq) - p.W + 1 : 0;  // first key of the oldest row's window
-    p.band_half0 = band_lo / 32;
-    const int sink_keys = p.S < band_lo ? p.S : band_lo;
-    const int sink_halves = (sink_keys + 31) / 32;
-    p.n_sink_halves = sink_halves < p.band_half0 ? sink_halves : p.band_half0;
-    p.n_halves = p.n_sink_halves + ((p.Nk - 1) / 32 - p.band_half0 + 1);
+    p.n_halves = visited_halves(p.Nk, p.Nq, p.W, p.S).n;
     // kRounds rounds of three workgroups per CU (one round measured fastest: every split is
     // resident at once and streams for the whole launch), but no split shorter than four halves
     const long long groups = (long long)p.B * p.Hkv * p.n_coltiles;

@@ -192,3 +192,35 @@ def test_backward_argument_errors():
     assert call(wb=4 * 128 * 4 - 1) == binding.SWAA_ERR_WORKSPACE
     need = binding.swaa_attn_bwd_workspace_bytes(1, 4, 2, 128, 128, 16, 2, 128)
     assert call(wb=need - 1) == binding.SWAA_ERR_WORKSPACE
+
+
+def test_general_decode_argument_errors():
+    p = 4096  # fake aligned address; never dereferenced on these paths
+
+    def args(**kw):
+        a = binding.SwaaDecodeArgs()
+        a.q = a.out = a.lse = p
+        a.k = binding.SwaaTensor(p, 2 * 1024 * 128, 1024 * 128, 128)
+        a.v = binding.SwaaTensor(p, 2 * 1024 * 128, 1024 * 128, 128)
+        a.B, a.Hq, a.Hkv, a.Nq, a.Nk, a.D = 2, 8, 2, 1, 1024, 128
+        a.window, a.n_sink, a.scale = 1024, 0, 0.1
+        a.workspace, a.workspace_bytes = p, 1 << 30
+        for key, val in kw.items():
+            if "." in key:
+                t, f = key.split(".")
+                setattr(getattr(a, t), f, val)
+            else:
+                setattr(a, key, val)
+        return a
+
+    call = lambda **kw: binding.swaa_attn_decode_ex_raw(args(**kw))
+    assert binding.load_library().swaa_attn_decode_ex(None) == binding.SWAA_ERR_NULL
+    assert call(out=None) == binding.SWAA_ERR_NULL
+    assert call(Nq=2000) == binding.SWAA_ERR_SHAPE
+    assert call(**{"v.stride_n": 100}) == binding.SWAA_ERR_SHAPE
+    assert call(block_table=p, page_size=6, num_pages=10, block_table_stride=512) == binding.SWAA_ERR_SHAPE
+    assert call(block_table=p, page_size=16, num_pages=10, block_table_stride=8) == binding.SWAA_ERR_SHAPE  # 128 < Nk
+    assert call(block_table=p, page_size=16, num_pages=0, block_table_stride=64) == binding.SWAA_ERR_SHAPE
+    assert call(seq_lens=p + 2) == binding.SWAA_ERR_ALIGN
+    assert call(D=64) == binding.SWAA_ERR_UNSUPPORTED
+    assert call(workspace_bytes=16) == binding.SWAA_ERR_WORKSPACE

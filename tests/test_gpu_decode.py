@@ -114,3 +114,63 @@ def test_decode_workloads_full_size(name):
     print(f"[oracle] {name}", flush=True)
     ro, rl = swaa_decode_oracle(q, k, v, w.window, w.n_sink, w.scale)
     assert_parity(out, lse, ro, rl, tag=name)
+
+
+def _paged_cache(seqs, page_size, Hkv, D, rng, extra_pages=3):
+    """Scatter per-sequence K/V [1, Hkv, n, D] device tensors into a paged cache
+    [num_pages, page_size, Hkv, D] under a random page order; returns (k_cache, v_cache, block_table)."""
+    pages_of = [(-(-s[1].shape[2] // page_size)) for s in seqs]
+    num_pages = sum(pages_of) + extra_pages
+    order = rng.permutation(num_pages)
+    kc = torch.randn((num_pages, page_size, Hkv, D), device="cuda").to(torch.bfloat16)  # unused slots hold noise
+    vc = torch.randn((num_pages, page_size, Hkv, D), device="cuda").to(torch.bfloat16)
+    table = np.full((len(seqs), max(pages_of) + 2), num_pages + 7, dtype=np.int32)   # unused entries: out of range
+    nxt = 0
+    for b, (_, k, v) in enumerate(seqs):
+        n = k.shape[2]
+        for pg in range(pages_of[b]):
+            page = int(order[nxt]); nxt += 1
+            table[b, pg] = page
+            t0, t1 = pg * page_size, min(n, (pg + 1) * page_size)
+            kc[page, :t1 - t0] = k[0, :, t0:t1].permute(1, 0, 2)
+            vc[page, :t1 - t0] = v[0, :, t0:t1].permute(1, 0, 2)
+    return kc, vc, torch.from_numpy(table).cuda()
+
+
+@pytest.mark.parametrize("page_size,Nq", [(16, 1), (4, 3), (64, 1), (128, 2)])
+def test_paged_cache_with_ragged_sequence_lengths(page_size, Nq):
+    Hq, Hkv, D = 8, 2, 128
+    lens = [1 + Nq, 31, 32, 33, 700, 2049, 129, 5000]
+    rng = np.random.Generator(np.random.Philox(76 + page_size))
+    host = [make_qkv(1, Hq, Hkv, n, D, int(rng.integers(1 << 30)), n_query=Nq) for n in lens]
+    seqs = [tuple(to_device(a) for a in s) for s in host]
+    kc, vc, table = _paged_cache(seqs, page_size, Hkv, D, rng)
+    q = torch.cat([s[0] for s in seqs], dim=0)
+    seq_lens = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    for W, S in ((10**9, 0), (512, 4)):
+        out, lse = binding.swaa_attn_decode_ex(q, kc.permute(0, 2, 1, 3), vc.permute(0, 2, 1, 3), W, S,
+                                               seq_lens=seq_lens, block_table=table, max_seqlen_k=max(lens))
+        torch.cuda.synchronize()
+        for b, (qs, ks, vs) in enumerate(host):
+            ro, rl = swaa_decode_oracle(qs, ks, vs, W, S, 1 / math.sqrt(D))
+            assert_parity(out[b:b + 1], lse[b:b + 1], ro, rl, tag=f"paged ps{page_size} seq {b} Nk{lens[b]} W{W}")
+
+
+def test_contiguous_cache_with_sequence_lengths_and_strides():
+    # a [B, max_len, Hkv, D] token-major cache buffer, each sequence filled up to its own length
+    B, Hq, Hkv, Nq, D, max_len = 4, 8, 2, 1, 128, 3000
+    lens = [3000, 17, 1500, 64]
+    rng = np.random.Generator(np.random.Philox(77))
+    host = [make_qkv(1, Hq, Hkv, n, D, int(rng.integers(1 << 30)), n_query=Nq) for n in lens]
+    kbuf = torch.randn((B, max_len, Hkv, D), device="cuda").to(torch.bfloat16)
+    vbuf = torch.randn((B, max_len, Hkv, D), device="cuda").to(torch.bfloat16)
+    for b, (_, k, v) in enumerate(host):
+        kbuf[b, :lens[b]] = to_device(k)[0].permute(1, 0, 2)
+        vbuf[b, :lens[b]] = to_device(v)[0].permute(1, 0, 2)
+    q = torch.cat([to_device(s[0]) for s in host], dim=0)
+    out, lse = binding.swaa_attn_decode_ex(q, kbuf.permute(0, 2, 1, 3), vbuf.permute(0, 2, 1, 3), 10**9, 0,
+                                           seq_lens=torch.tensor(lens, dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    for b, (qs, ks, vs) in enumerate(host):
+        ro, rl = swaa_decode_oracle(qs, ks, vs, 10**9, 0, 1 / math.sqrt(D))
+        assert_parity(out[b:b + 1], lse[b:b + 1], ro, rl, tag=f"strided cache seq {b} Nk{lens[b]}")
