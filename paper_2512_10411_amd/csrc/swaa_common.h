@@ -17,8 +17,8 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBk = 64;        // keys per KV tile
-constexpr int kThreads = 256;  // 4 waves per workgroup
-constexpr int kWaveRows = 64;  // query positions per wave
+constexpr int kThreads = 256;  // plain kernels: 4 waves per workgroup ...
+constexpr int kWaveRows = 64;  // ... of 64 query rows each (the pipelined kernel: 8 waves of 32)
 constexpr int kWgRows = 256;   // query rows (head x position) per workgroup
 constexpr int kXcds = 8;       // accelerator dies; workgroups are dealt to them round-robin
 
