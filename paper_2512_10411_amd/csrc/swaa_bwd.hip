@@ -14,10 +14,10 @@
 //   * swaa_bwd_dq_kernel: a workgroup owns 256 query rows (the forward's work
 //     decomposition and tile schedule), walks its visible KV tiles, recomputes
 //     S^T = K Q^T and dP^T = V dO^T and accumulates dQ^T += K^T dS^T.
-//   * swaa_bwd_dkv_kernel: a workgroup owns 128 keys of one KV head (32 per
-//     wave), walks every query head of the GQA group and every 64-row query
-//     tile that can see them, recomputes S = Q K^T and dP = dO V^T and
-//     accumulates dV^T += dO^T P and dK^T += Q^T dS.  Key tiles that hold sink
+//   * swaa_bwd_dkv_kernel: a workgroup owns 128 keys of one KV head, walks
+//     every query head of the GQA group and every 64-row query tile that can
+//     see them, recomputes S = Q K^T and dP = dO V^T and accumulates
+//     dV^T += dO^T P and dK^T += Q^T dS.  Key tiles that hold sink
 //     keys are seen by every later row: their rows beyond the band are cut into
 //     segments with a workgroup each, and
 //   * swaa_bwd_sink_sum_kernel adds the fp32 partial sums of those key tiles.
@@ -26,8 +26,9 @@
 // consumes them (as in the forward kernels); operands that a product needs
 // transposed are read from row-major LDS tiles with ds_read_b64_tr_b16.
 // P and dS are rounded to bf16 before the second products, sums are fp32.
-// This first version stages tiles through registers and leaves instruction
-// scheduling to the compiler.
+// This version stages tiles through registers and leaves instruction scheduling
+// to the compiler; both big kernels run two waves per SIMD.
+#include <atomic>
 #include <cmath>
 
 #include "swaa_bwd.h"
@@ -36,6 +37,10 @@ namespace swaa {
 namespace {
 
 constexpr int kBq = 64;  // query rows per tile of the dK/dV kernel
+#ifndef SWAA_DQ_BLOCKS
+#define SWAA_DQ_BLOCKS 1
+#endif
+constexpr int kDqBlocks = SWAA_DQ_BLOCKS;  // 32-row blocks per wave of the dQ kernel
 
 template <int D>
 struct BTile {
@@ -90,10 +95,15 @@ __global__ __launch_bounds__(kThreads) void swaa_bwd_delta_kernel(const BwdParam
 }
 
 // ---- dQ ------------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dq_kernel(const BwdParams p) {
+// QB: 32-row blocks per wave.  QB = 1 runs eight waves of 32 rows (two per SIMD, so that one
+// wave's exponentials overlap the other's MFMAs), QB = 2 four waves of 64 rows.
+template <int D, int QB>
+__global__ __launch_bounds__(512 / QB, 1) void swaa_bwd_dq_kernel(const BwdParams p) {
     using T = BTile<D>;
     constexpr int KS = D / 16, DB = D / 32;
+    constexpr int TH = 512 / QB;           // threads per workgroup
+    constexpr int kRows = 32 * QB;         // query rows per wave
+    constexpr int kCPT = kBk * T::kChunksPerRow / TH;  // 16-byte chunks of a tile per thread
     __shared__ __attribute__((aligned(16))) __bf16 Ks[T::kElems];
     __shared__ __attribute__((aligned(16))) __bf16 Vs[T::kElems];
 
@@ -107,15 +117,15 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dq_kernel(const BwdParam
     const int head = wi.kvh * p.f.G + wi.h0 + (wave % hpb);
     const int wg_p0 = wi.pt * rows_per_wg;
     const int wg_p1 = min(N, wg_p0 + rows_per_wg) - 1;
-    const int p0 = wg_p0 + (wave / hpb) * kWaveRows;
+    const int p0 = wg_p0 + (wave / hpb) * kRows;
     const bool wave_active = p0 < N;
-    const int plast = min(p0 + kWaveRows, N) - 1;
+    const int plast = min(p0 + kRows, N) - 1;
 
     const int band_lo = (wg_p1 >= P) ? 0 : max(0, wg_p0 - W + 1);
     const int t_band_lo = band_lo / kBk;
     const int t_hi = wg_p1 / kBk;
     const int n_sink_tiles = min((min(S, band_lo) + kBk - 1) / kBk, t_band_lo);
-    const int wbound = window_bound(p0, kWaveRows, W, P);
+    const int wbound = window_bound(p0, kRows, W, P);
 
     const size_t kv_base = ((size_t)wi.b * p.Hkv + wi.kvh) * (size_t)N * D;
     const __bf16 *kg = p.f.k + kv_base;
@@ -124,10 +134,10 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dq_kernel(const BwdParam
     const size_t r_base = ((size_t)wi.b * p.Hq + head) * (size_t)N;
 
     // this wave's Q and dO rows as B operands, its rows' lse (log2 units) and delta
-    bf16x8 qf[2][KS], dof[2][KS];
-    float lse2[2], dl[2];
+    bf16x8 qf[QB][KS], dof[QB][KS];
+    float lse2[QB], dl[QB];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
         const int row = min(p0 + 32 * qb + l32, N - 1);
         const __bf16 *qs = p.f.q + q_base + (size_t)row * D + 8 * hf;
         const __bf16 *ds = p.dout + q_base + (size_t)row * D + 8 * hf;
@@ -140,19 +150,19 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dq_kernel(const BwdParam
         dl[qb] = p.delta[r_base + row];
     }
 
-    f32x16 dqacc[DB][2];
+    f32x16 dqacc[DB][QB];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
+        for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
             for (int e = 0; e < 16; ++e) dqacc[db][qb][e] = 0.f;
 
-    u32x4 kreg[T::kChunksPerThread], vreg[T::kChunksPerThread];
+    u32x4 kreg[kCPT], vreg[kCPT];
     auto load_tile = [&](int t) {
 #pragma unroll
-        for (int c = 0; c < T::kChunksPerThread; ++c) {
-            const int id = c * kThreads + tid;
+        for (int c = 0; c < kCPT; ++c) {
+            const int id = c * TH + tid;
             const int row = min(t * kBk + id / T::kChunksPerRow, N - 1);
             const int col = (id % T::kChunksPerRow) * 8;
             kreg[c] = *reinterpret_cast<const u32x4 *>(kg + (size_t)row * D + col);
@@ -161,8 +171,8 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dq_kernel(const BwdParam
     };
     auto store_tile = [&]() {
 #pragma unroll
-        for (int c = 0; c < T::kChunksPerThread; ++c) {
-            const int id = c * kThreads + tid;
+        for (int c = 0; c < kCPT; ++c) {
+            const int id = c * TH + tid;
             const int row = id / T::kChunksPerRow;
             const int col = (id % T::kChunksPerRow) * 8;
             *reinterpret_cast<u32x4 *>(&Ks[row * T::kStride + col]) = kreg[c];
@@ -193,11 +203,11 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dq_kernel(const BwdParam
             const bool unmasked = (k_last <= p0) && ((k0 > wbound) || (k_last < S));
 
             // S^T = K Q^T and dP^T = V dO^T : [64 keys] x [64 queries]
-            f32x16 sacc[2][2], dpacc[2][2];
+            f32x16 sacc[2][QB], dpacc[2][QB];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int qb = 0; qb < 2; ++qb)
+                for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
                     for (int e = 0; e < 16; ++e) {
                         sacc[kb][qb][e] = 0.f;
@@ -210,16 +220,16 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dq_kernel(const BwdParam
                     const bf16x8 ka = row_frag<D>(Ks, kb, ks, l32, hf);
                     const bf16x8 va = row_frag<D>(Vs, kb, ks, l32, hf);
 #pragma unroll
-                    for (int qb = 0; qb < 2; ++qb) {
+                    for (int qb = 0; qb < QB; ++qb) {
                         sacc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[qb][ks], sacc[kb][qb], 0, 0, 0);
                         dpacc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, dof[qb][ks], dpacc[kb][qb], 0, 0, 0);
                     }
                 }
 
             // P^T = exp2(s c2 - lse2) on visible pairs, dS^T = P^T (dP^T - delta), packed to bf16
-            bf16x8 dsf[2][2][2];  // [kb][qb][16-key step]
+            bf16x8 dsf[2][QB][2];  // [kb][qb][16-key step]
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
+            for (int qb = 0; qb < QB; ++qb) {
                 const int qpos = p0 + 32 * qb + l32;
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
@@ -241,7 +251,7 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dq_kernel(const BwdParam
                     for (int db = 0; db < DB; ++db) {
                         const bf16x8 a = col_frag<D>(Ks, kb, st, db, lane);
 #pragma unroll
-                        for (int qb = 0; qb < 2; ++qb)
+                        for (int qb = 0; qb < QB; ++qb)
                             dqacc[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, dsf[kb][qb][st], dqacc[db][qb], 0, 0, 0);
                     }
         }
@@ -255,7 +265,7 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dq_kernel(const BwdParam
 
     if (!wave_active) return;
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
         const int row = p0 + 32 * qb + l32;
         if (row >= N) continue;
         __bf16 *orow = p.dq + q_base + (size_t)row * D;
@@ -272,17 +282,38 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dq_kernel(const BwdParam
 }
 
 // ---- dK, dV --------------------------------------------------------------------------
+// Eight waves, two per SIMD (one wave's exponentials overlap the other's MFMAs): wave w owns
+// the 32 keys 32*(w%4).. of the workgroup's 128 and the 32 rows 32*(w/4).. of every 64-row
+// query tile; the two row halves are added through LDS at the end.  The workgroup's K and V
+// rows stay in LDS for the whole kernel (B operands of S = Q K^T and dP = dO V^T), the query
+// tile's Q and dO are staged per step and read both row-wise and transposed.
+constexpr int kDkvThreads = 512;
 template <int D>
-__global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dkv_kernel(const BwdParams p) {
+struct DkvSmem {
     using T = BTile<D>;
+    static constexpr int kKeyTileBytes = 128 * T::kStride * 2;  // K or V rows of the workgroup's keys
+    static constexpr int kQTileBytes = T::kElems * 2;
+    static constexpr int kK = 0, kV = kKeyTileBytes, kQ = 2 * kKeyTileBytes, kDO = kQ + kQTileBytes,
+                         kL = kDO + kQTileBytes, kDl = kL + kBq * 4, kBytes = kDl + kBq * 4;
+    static_assert(2 * kKeyTileBytes >= 4 * 32 * D * 4, "the K/V area doubles as the buffer of the final sum");
+};
+
+template <int D>
+__global__ __launch_bounds__(kDkvThreads, 1) void swaa_bwd_dkv_kernel(const BwdParams p) {
+    using T = BTile<D>;
+    using M = DkvSmem<D>;
     constexpr int KS = D / 16, DB = D / 32;
-    __shared__ __attribute__((aligned(16))) __bf16 Qs[T::kElems];
-    __shared__ __attribute__((aligned(16))) __bf16 dOs[T::kElems];
-    __shared__ __attribute__((aligned(16))) float Ls[kBq];   // lse of the tile's rows, log2 units
-    __shared__ __attribute__((aligned(16))) float Dls[kBq];  // their delta
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    __bf16 *Ks = reinterpret_cast<__bf16 *>(smem + M::kK);
+    __bf16 *Vs = reinterpret_cast<__bf16 *>(smem + M::kV);
+    __bf16 *Qs = reinterpret_cast<__bf16 *>(smem + M::kQ);
+    __bf16 *dOs = reinterpret_cast<__bf16 *>(smem + M::kDO);
+    float *Ls = reinterpret_cast<float *>(smem + M::kL);    // lse of the tile's rows, log2 units
+    float *Dls = reinterpret_cast<float *>(smem + M::kDl);  // their delta
 
     const int N = p.N, W = p.f.W, S = p.f.S, P = p.f.P, G = p.f.G;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
+    const int kq = wave & 3, qb = wave >> 2;  // key block and row half of this wave
     // Work list: first the segments of the sink key tiles (rows beyond the band), then one
     // workgroup per key tile of 128 keys (band rows; for key tiles without sinks also the
     // generated rows).  Under a causal mask the first key tiles are seen by the most rows.
@@ -302,18 +333,20 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dkv_kernel(const BwdPara
     const bool sink_kt = kt < p.n_sink_kt;  // results go to the partial-sum workspace
     const int b = pair / p.Hkv, kvh = pair % p.Hkv;
     const int k0 = kt * 128, k1 = min(k0 + 127, N - 1);  // the workgroup's keys
-    const int kw0 = k0 + 32 * wave, kw1 = kw0 + 31;       // this wave's keys
+    const int kw0 = k0 + 32 * kq, kw1 = kw0 + 31;         // this wave's keys
     const int key = kw0 + l32;                            // this lane's key column
     const bool wave_active = kw0 < N;
 
-    // the wave's K and V rows as B operands
-    bf16x8 kf[KS], vf[KS];
+    // the workgroup's K and V rows -> LDS (rows past the end repeat the last key; they stay invisible)
     {
-        const size_t kv_row = (((size_t)b * p.Hkv + kvh) * (size_t)N + min(key, N - 1)) * D + 8 * hf;
+        const size_t kv_base = ((size_t)b * p.Hkv + kvh) * (size_t)N * D;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            kf[ks] = *reinterpret_cast<const bf16x8 *>(p.f.k + kv_row + 16 * ks);
-            vf[ks] = *reinterpret_cast<const bf16x8 *>(p.f.v + kv_row + 16 * ks);
+        for (int c = 0; c < 128 * T::kChunksPerRow / kDkvThreads; ++c) {
+            const int id = c * kDkvThreads + tid;
+            const int row = id / T::kChunksPerRow, col = (id % T::kChunksPerRow) * 8;
+            const size_t g = kv_base + (size_t)min(k0 + row, N - 1) * D + col;
+            *reinterpret_cast<u32x4 *>(&Ks[row * T::kStride + col]) = *reinterpret_cast<const u32x4 *>(p.f.k + g);
+            *reinterpret_cast<u32x4 *>(&Vs[row * T::kStride + col]) = *reinterpret_cast<const u32x4 *>(p.f.v + g);
         }
     }
     f32x16 dkacc[DB], dvacc[DB];
@@ -346,13 +379,14 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dkv_kernel(const BwdPara
     auto tile_of = [&](int n) { return n < n_band ? tq_lo + n : tq_x + (n - n_band); };
 
     const float c2 = p.f.scale_log2;
-    u32x4 qreg[T::kChunksPerThread], dreg[T::kChunksPerThread];
+    constexpr int kCPT = kBk * T::kChunksPerRow / kDkvThreads;
+    u32x4 qreg[kCPT], dreg[kCPT];
     float lreg = 0.f, dlreg = 0.f;
     auto load_tile = [&](int head, int tq) {
         const size_t base = ((size_t)b * p.Hq + head) * (size_t)N;
 #pragma unroll
-        for (int c = 0; c < T::kChunksPerThread; ++c) {
-            const int id = c * kThreads + tid;
+        for (int c = 0; c < kCPT; ++c) {
+            const int id = c * kDkvThreads + tid;
             const int row = min(tq * kBq + id / T::kChunksPerRow, N - 1);
             const int col = (id % T::kChunksPerRow) * 8;
             qreg[c] = *reinterpret_cast<const u32x4 *>(p.f.q + (base + row) * D + col);
@@ -366,8 +400,8 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dkv_kernel(const BwdPara
     };
     auto store_tile = [&]() {
 #pragma unroll
-        for (int c = 0; c < T::kChunksPerThread; ++c) {
-            const int id = c * kThreads + tid;
+        for (int c = 0; c < kCPT; ++c) {
+            const int id = c * kDkvThreads + tid;
             const int row = id / T::kChunksPerRow;
             const int col = (id % T::kChunksPerRow) * 8;
             *reinterpret_cast<u32x4 *>(&Qs[row * T::kStride + col]) = qreg[c];
@@ -392,63 +426,57 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dkv_kernel(const BwdPara
         if (has_next) load_tile(kvh * G + (step + 1) / n_tiles, tile_of((step + 1) % n_tiles));
 
         const int tq = tile_of(step % n_tiles);
-        const int i0 = tq * kBq, i1 = i0 + kBq - 1;
-        // can any row of the tile see any key of this wave?
-        const bool sees = (i1 >= kw0) && ((i0 < kw1 + W) || (kw0 < S) || (i1 >= P));
+        const int i0 = tq * kBq + 32 * qb, i1 = i0 + 31;  // this wave's rows of the tile
+        // can any of them see any key of this wave?
+        const bool sees = (i0 < N) && (i1 >= kw0) && ((i0 < kw1 + W) || (kw0 < S) || (i1 >= P));
         if (wave_active && sees) {
-            // all 64 x 32 pairs visible: rows at or below the keys' diagonal, inside every row's window
+            // all 32 x 32 pairs visible: rows at or below the keys' diagonal, inside every row's window
             // (or the keys are sinks, or the rows are generated tokens), and no row past the end
             const bool unmasked = (kw1 <= i0) && (i1 < N) && ((i1 - kw0 < W) || (kw1 < S) || (i0 >= P));
 
-            // S = Q K^T and dP = dO V^T : [64 queries] x [32 keys]
-            f32x16 sacc[2], dpacc[2];
+            // S = Q K^T and dP = dO V^T : [32 queries] x [32 keys]
+            f32x16 sacc, dpacc;
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb)
+            for (int e = 0; e < 16; ++e) {
+                sacc[e] = 0.f;
+                dpacc[e] = 0.f;
+            }
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    sacc[qb][e] = 0.f;
-                    dpacc[qb][e] = 0.f;
-                }
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                for (int qb = 0; qb < 2; ++qb) {
-                    sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag<D>(Qs, qb, ks, l32, hf), kf[ks], sacc[qb], 0, 0, 0);
-                    dpacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag<D>(dOs, qb, ks, l32, hf), vf[ks], dpacc[qb], 0, 0, 0);
-                }
+            for (int ks = 0; ks < KS; ++ks) {
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag<D>(Qs, qb, ks, l32, hf),
+                                                               row_frag<D>(Ks, kq, ks, l32, hf), sacc, 0, 0, 0);
+                dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag<D>(dOs, qb, ks, l32, hf),
+                                                                row_frag<D>(Vs, kq, ks, l32, hf), dpacc, 0, 0, 0);
+            }
 
-            // P and dS in the accumulator layout (row 32 qb + 8 (e/4) + 4 hf + e%4, column = this lane's key)
-            bf16x8 pf[2][2], dsf[2][2];  // [qb][16-row step]
+            // P and dS in the accumulator layout (row 8 (e/4) + 4 hf + e%4, column = this lane's key)
+            bf16x8 pf[2], dsf[2];  // [16-row step]
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb)
+            for (int e4 = 0; e4 < 4; ++e4) {
+                const int r4 = 32 * qb + 8 * e4 + 4 * hf;
+                const float4 l4 = *reinterpret_cast<const float4 *>(&Ls[r4]);
+                const float4 d4 = *reinterpret_cast<const float4 *>(&Dls[r4]);
+                const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+                const float dv4[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4) {
-                    const int r4 = 32 * qb + 8 * e4 + 4 * hf;
-                    const float4 l4 = *reinterpret_cast<const float4 *>(&Ls[r4]);
-                    const float4 d4 = *reinterpret_cast<const float4 *>(&Dls[r4]);
-                    const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
-                    const float dv4[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-                    for (int x = 0; x < 4; ++x) {
-                        const int e = 4 * e4 + x;
-                        const int row = i0 + r4 + x;
-                        float pe = __builtin_amdgcn_exp2f(fmaf(sacc[qb][e], c2, -lv[x]));
-                        if (!unmasked && !(row < N && visible(row, key, W, S, P))) pe = 0.f;
-                        pf[qb][e / 8][e % 8] = (__bf16)pe;
-                        dsf[qb][e / 8][e % 8] = (__bf16)(pe * (dpacc[qb][e] - dv4[x]));
-                    }
+                for (int x = 0; x < 4; ++x) {
+                    const int e = 4 * e4 + x;
+                    const int row = tq * kBq + r4 + x;
+                    float pe = __builtin_amdgcn_exp2f(fmaf(sacc[e], c2, -lv[x]));
+                    if (!unmasked && !(row < N && visible(row, key, W, S, P))) pe = 0.f;
+                    pf[e / 8][e % 8] = (__bf16)pe;
+                    dsf[e / 8][e % 8] = (__bf16)(pe * (dpacc[e] - dv4[x]));
                 }
+            }
 
             // dV^T += dO^T P,  dK^T += Q^T dS
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb)
+            for (int st = 0; st < 2; ++st)
 #pragma unroll
-                for (int st = 0; st < 2; ++st)
-#pragma unroll
-                    for (int db = 0; db < DB; ++db) {
-                        dvacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(col_frag<D>(dOs, qb, st, db, lane), pf[qb][st], dvacc[db], 0, 0, 0);
-                        dkacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(col_frag<D>(Qs, qb, st, db, lane), dsf[qb][st], dkacc[db], 0, 0, 0);
-                    }
+                for (int db = 0; db < DB; ++db) {
+                    dvacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(col_frag<D>(dOs, qb, st, db, lane), pf[st], dvacc[db], 0, 0, 0);
+                    dkacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(col_frag<D>(Qs, qb, st, db, lane), dsf[st], dkacc[db], 0, 0, 0);
+                }
         }
 
         if (!has_next) break;
@@ -458,10 +486,42 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_bwd_dkv_kernel(const BwdPara
         ++step;
     }
 
+    // ---- add the two row halves: waves 4..7 hand their sums to waves 0..3 through LDS
+    // (the K/V area, which nobody reads any more), first dK, then dV ----
+    float *xbuf = reinterpret_cast<float *>(smem);  // [4 key blocks][D][32 key columns]
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+        __syncthreads();
+        if (qb == 1) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int d = 32 * db + 8 * (e / 4) + 4 * hf + (e % 4);
+                    xbuf[(kq * D + d) * 32 + l32] = which == 0 ? dkacc[db][e] : dvacc[db][e];
+                }
+        }
+        __syncthreads();
+        if (qb == 0) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int d = 32 * db + 8 * (e / 4) + 4 * hf + (e % 4);
+                    const float other = xbuf[(kq * D + d) * 32 + l32];
+                    if (which == 0)
+                        dkacc[db][e] += other;
+                    else
+                        dvacc[db][e] += other;
+                }
+        }
+    }
+    if (qb != 0) return;
+
     if (sink_kt) {
         // fp32 partial sums of all 128 key columns (columns past the end hold zeros)
         float *slot = p.partial + ((((size_t)pair * p.n_sink_kt + kt) * (p.n_seg + 1) + (seg + 1)) * 2) * (size_t)(128 * D);
-        float *pk = slot + (size_t)(32 * wave + l32) * D, *pv = pk + 128 * D;
+        float *pk = slot + (size_t)(32 * kq + l32) * D, *pv = pk + 128 * D;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -527,13 +587,26 @@ hipError_t launch_bwd_d(const BwdParams &p, hipStream_t stream) {
                        dim3(kThreads), 0, stream, p);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    hipLaunchKernelGGL(swaa_bwd_dq_kernel<D>, dim3((unsigned)(p.f.chunk * kXcds)), dim3(kThreads), 0, stream, p);
+    hipLaunchKernelGGL((swaa_bwd_dq_kernel<D, kDqBlocks>), dim3((unsigned)(p.f.chunk * kXcds)), dim3(512 / kDqBlocks), 0,
+                       stream, p);
     err = hipGetLastError();
     if (err != hipSuccess) return err;
     const long long n_kt = (p.N + 127) / 128;
     const long long pairs = (long long)p.B * p.Hkv;
+    // more than 64 KiB of LDS per workgroup has to be requested once per device
+    static std::atomic<unsigned long long> configured{0};
+    int dev = 0;
+    err = hipGetDevice(&dev);
+    if (err != hipSuccess) return err;
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (!(configured.load(std::memory_order_acquire) & bit)) {
+        err = hipFuncSetAttribute(reinterpret_cast<const void *>(&swaa_bwd_dkv_kernel<D>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, DkvSmem<D>::kBytes);
+        if (err != hipSuccess) return err;
+        configured.fetch_or(bit, std::memory_order_release);
+    }
     hipLaunchKernelGGL(swaa_bwd_dkv_kernel<D>, dim3((unsigned)(pairs * (n_kt + (long long)p.n_sink_kt * p.n_seg))),
-                       dim3(kThreads), 0, stream, p);
+                       dim3(kDkvThreads), DkvSmem<D>::kBytes, stream, p);
     err = hipGetLastError();
     if (err != hipSuccess || p.n_sink_kt == 0) return err;
     const long long threads = pairs * p.n_sink_kt * (128LL * D / 4);
