@@ -37,7 +37,7 @@ struct DecodeParams {
     int cols;        // G * Nq query rows per pair
     int n_coltiles;  // ceil(cols / 32)
     int col_stride;  // min(cols, 32): columns an item stores
-    int n_halves;  // visited halves of a sequence of Nk tokens (shorter sequences visit fewer)
+    int n_halves;  // upper bound on the halves a sequence of at most Nk tokens visits
     int halves_per_split, n_splits;
     long long items;  // B * Hkv * n_coltiles * n_splits
 };

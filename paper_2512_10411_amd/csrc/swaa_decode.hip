@@ -329,7 +329,11 @@ void plan_decode(DecodeParams &p) {
     p.cols = p.G * p.Nq;
     p.n_coltiles = (p.cols + 31) / 32;
     p.col_stride = p.cols < 32 ? p.cols : 32;
-    p.n_halves = visited_halves(p.Nk, p.Nq, p.W, p.S).n;
+    // an upper bound on the halves any sequence of at most Nk tokens visits (a shorter sequence's
+    // band can straddle one half more than the longest one's): the splits are planned for it
+    const int all = (p.Nk + 31) / 32;
+    const int bound = (p.S + 31) / 32 + (p.W + p.Nq - 2) / 32 + 2;
+    p.n_halves = all < bound ? all : bound;
     // kRounds rounds of three workgroups per CU (one round measured fastest: every split is
     // resident at once and streams for the whole launch), but no split shorter than four halves
     const long long groups = (long long)p.B * p.Hkv * p.n_coltiles;

@@ -174,3 +174,20 @@ def test_contiguous_cache_with_sequence_lengths_and_strides():
     for b, (qs, ks, vs) in enumerate(host):
         ro, rl = swaa_decode_oracle(qs, ks, vs, 10**9, 0, 1 / math.sqrt(D))
         assert_parity(out[b:b + 1], lse[b:b + 1], ro, rl, tag=f"strided cache seq {b} Nk{lens[b]}")
+
+
+def test_shorter_sequence_whose_band_straddles_one_more_half():
+    # the splits are planned for the longest cache; a shorter one's window can touch one half more
+    Hq, Hkv, D, W, S = 2, 1, 128, 500, 100
+    lens = [2584, 1710, 1303]
+    host = [make_qkv(1, Hq, Hkv, n, D, 7800 + i, n_query=1) for i, n in enumerate(lens)]
+    kb = torch.zeros((3, Hkv, max(lens), D), dtype=torch.bfloat16, device="cuda")
+    vb = torch.zeros_like(kb)
+    for b, (_, k, v) in enumerate(host):
+        kb[b, :, :lens[b]], vb[b, :, :lens[b]] = to_device(k)[0], to_device(v)[0]
+    q = torch.cat([to_device(s[0]) for s in host], dim=0)
+    out, lse = binding.swaa_attn_decode_ex(q, kb, vb, W, S, seq_lens=torch.tensor(lens, dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    for b, (qs, ks, vs) in enumerate(host):
+        ro, rl = swaa_decode_oracle(qs, ks, vs, W, S, 1 / math.sqrt(D))
+        assert_parity(out[b:b + 1], lse[b:b + 1], ro, rl, tag=f"ragged windowed decode seq {b} Nk{lens[b]}")
