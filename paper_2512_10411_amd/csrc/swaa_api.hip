@@ -95,10 +95,10 @@ int swaa_attn_fwd_ex(const swaa_fwd_args *a) {
     if (D != 64 && D != 128) return SWAA_ERR_UNSUPPORTED;
     if (a->dtype != SWAA_BF16 && a->dtype != SWAA_F16) return SWAA_ERR_UNSUPPORTED;
     for (const swaa_tensor *t : {&a->q, &a->k, &a->v, &a->out}) {
+        const int heads = (t == &a->k || t == &a->v) ? Hkv : Hq;
         if (misaligned(t->ptr)) return SWAA_ERR_ALIGN;
         if (bad_stride(t->stride_n, false) || t->stride_n < D || t->stride_n >= (1LL << 22)) return SWAA_ERR_SHAPE;
-        if (bad_stride(t->stride_h, Hq == 1 || Hkv == 1) || bad_stride(t->stride_b, packed || B == 1))
-            return SWAA_ERR_SHAPE;
+        if (bad_stride(t->stride_h, heads == 1) || bad_stride(t->stride_b, packed || B == 1)) return SWAA_ERR_SHAPE;
     }
     if ((reinterpret_cast<uintptr_t>(a->lse) & 3u) != 0) return SWAA_ERR_ALIGN;
     if (a->lse_stride_h < 0 || a->lse_stride_b < 0) return SWAA_ERR_SHAPE;
