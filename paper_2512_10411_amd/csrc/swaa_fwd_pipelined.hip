@@ -239,20 +239,19 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
         asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds)
                      : "memory");
     };
-    auto issue_tile = [&](int j, int buf, const __bf16 *src, int ring, bool is_k) {
-        if (j >= J) return;
-        const int k0 = tile_of(j) * kBk;
-        const uint32_t rsb = is_k ? k_rsb : v_rsb;
-        const char *base = reinterpret_cast<const char *>(src) + (size_t)k0 * rsb;  // uniform
+    // The wave's two copies of one tile into ring buffer `buf`; base: the tile's first row in
+    // HBM; ragged: the tile runs past the sequence's last row (only the last visited tile
+    // can), and rows past the end repeat the last row -- they are masked later -- so that the
+    // reads stay in bounds.
+    auto copy_tile = [&](const char *base, int buf, int ring, bool is_k, bool ragged) {
         const uint32_t l = (uint32_t)(ring + buf * kTileBytes + 2 * wave * 1024);
-        if (__builtin_expect(k0 + kBk > Nk, 0)) {
-            // last tile of a ragged sequence: rows past the end repeat the last row (they are
-            // masked later), so that the reads stay in bounds
+        if (__builtin_expect(ragged, 0)) {
+            const uint32_t rsb = is_k ? k_rsb : v_rsb;
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 uint32_t off = is_k ? (i ? voff_k1 : voff_k) : voff_v + (uint32_t)(4 * i) * v_rsb;
                 const int row = 8 * wave + 4 * i + lrow;
-                off -= (uint32_t)max(k0 + row - (Nk - 1), 0) * rsb;
+                off -= (uint32_t)max(t_hi * kBk + row - (Nk - 1), 0) * rsb;
                 copy16(off, base, l + (uint32_t)(i * 1024));
             }
         } else if (is_k) {
@@ -263,8 +262,38 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
             copy16(voff_v + 4u * v_rsb, base, l + 1024u);
         }
     };
+    const int j_ragged = ((t_hi + 1) * kBk > Nk) ? J - 1 : -1;
+    // any visited tile (the recomputation path)
+    auto issue_tile = [&](int j, int buf, const __bf16 *src, int ring, bool is_k) {
+        if (j >= J) return;
+        const char *base = reinterpret_cast<const char *>(src) + (size_t)(tile_of(j) * kBk) * (is_k ? k_rsb : v_rsb);
+        copy_tile(base, buf, ring, is_k, j == j_ragged);
+    };
     auto issue_k = [&](int j, int buf) { issue_tile(j, buf, kg, 0, true); };
     auto issue_v = [&](int j, int buf) { issue_tile(j, buf, vg, kVRing, false); };
+    // The pipeline asks for the visited tiles in order, so their addresses are kept as two
+    // running pointers: a handful of scalar instructions per tile instead of a 64-bit
+    // multiplication (every wave executes them, at the start of every step).
+    struct TileStream {
+        const char *next;   // first row of the next tile to copy
+        size_t step, jump;  // bytes to the following tile: the usual one, and from the last sink tile to the band
+    };
+    auto make_stream = [&](const __bf16 *src, uint32_t rsb) {
+        TileStream ts;
+        ts.next = reinterpret_cast<const char *>(src) + (size_t)(tile_of(0) * kBk) * rsb;
+        ts.step = (size_t)kBk * rsb;
+        ts.jump = (size_t)(t_band_lo - n_sink_tiles + 1) * kBk * rsb;
+        return ts;
+    };
+    TileStream k_stream = make_stream(kg, k_rsb), v_stream = make_stream(vg, v_rsb);
+    auto stream_tile = [&](TileStream &ts, int j, int buf, int ring, bool is_k) {
+        if (j >= J) return;
+        const char *base = ts.next;
+        ts.next += (j + 1 == n_sink_tiles) ? ts.jump : ts.step;
+        copy_tile(base, buf, ring, is_k, j == j_ragged);
+    };
+    auto stream_k = [&](int j, int buf) { stream_tile(k_stream, j, buf, 0, true); };
+    auto stream_v = [&](int j, int buf) { stream_tile(v_stream, j, buf, kVRing, false); };
 
     // Step 0 multiplies an all-zero P^T with "the tile before the first": give that
     // V buffer (the last one of the ring, not yet a copy target) defined contents.
@@ -290,11 +319,11 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     // Tiles in the order they are needed.  A CU takes in about 64 bytes per cycle,
     // so the pipeline prologue below starts as soon as Q and K(0) are there (ten
     // copies per wave) and the other four tiles (eight copies) stream in behind it.
-    issue_k(0, 0);
-    issue_v(0, 0);
-    issue_k(1, 1);
-    issue_k(2, 2);
-    issue_v(1, 1);
+    stream_k(0, 0);
+    stream_v(0, 0);
+    stream_k(1, 1);
+    stream_k(2, 2);
+    stream_v(1, 1);
 
     f32x16 oacc[kDB];
 #pragma unroll
@@ -384,41 +413,68 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
 #pragma unroll
         for (int i = 0; i < kPrefetch; ++i) fpre[i] = load_slot(la, h0, i);
     }
-    auto step = [&](auto ring_pos, int j) {
+    // checked: the step looks at its two score halves and masks them where needed.  In the
+    // interior of a wave's band no half needs a mask, and the step skips that scalar
+    // bookkeeping.
+    auto step = [&](auto ring_pos, bool checked, int j) {
         constexpr int R = decltype(ring_pos)::value;
         constexpr int Rn = (R + 1) % kStages, Rp = (R + kStages - 1) % kStages;
         constexpr uint32_t kb_cur1 = R * kTileBytes + kHalfBytes;    // K(j), half 1
         constexpr uint32_t kb_next0 = Rn * kTileBytes;               // K(j+1), half 0
         constexpr uint32_t vb_prev1 = Rp * kTileBytes + kHalfBytes;  // V(j-1), half 1
         constexpr uint32_t vb_cur0 = R * kTileBytes;                 // V(j), half 0
-        const int k0 = tile_of(j) * kBk;
-        const int k0n = (j + 1 < J) ? tile_of(j + 1) * kBk : k0 + kBk;  // past the end: scores never used
+        int k0 = 0, k0n = 0;
+        bool mask1 = false, mask2 = false;
+        if (__builtin_expect(checked, 0)) {
+            k0 = tile_of(j) * kBk;
+            k0n = (j + 1 < J) ? tile_of(j + 1) * kBk : k0 + kBk;  // past the end: scores never used
+            mask1 = half_masked(k0 + 32);
+            mask2 = half_masked(k0n);
+        }
 
         // softmax of (j, half 0) | scores of (j, half 1) | P V of (j-1, half 1)
         const HalfOffsets h1 = {kb_cur1, vb_prev1, kb_next0, vb_cur0};
-        pipelined_substep(la, h1, fpre, qf, s_b, s_a, p_a, p_b, oacc, rs, c2, half_masked(k0 + 32), k0 + 32, qpos, W, S,
-                          hf);
+        pipelined_substep(la, h1, fpre, qf, s_b, s_a, p_a, p_b, oacc, rs, c2, mask1, k0 + 32, qpos, W, S, hf);
         // softmax of (j, half 1) | scores of (j+1, half 0) | P V of (j, half 0); its last
         // fragment requests are the first ones of step j+1 (K(j+1) half 1, V(j) half 1: both
         // resident), so that they are under way while the waves meet at the barrier
         const HalfOffsets h2 = {kb_next0, vb_cur0, Rn * kTileBytes + kHalfBytes, R * kTileBytes + kHalfBytes};
-        pipelined_substep(la, h2, fpre, qf, s_a, s_b, p_b, p_a, oacc, rs, c2, half_masked(k0n), k0n, qpos, W, S, hf);
+        pipelined_substep(la, h2, fpre, qf, s_a, s_b, p_b, p_a, oacc, rs, c2, mask2, k0n, qpos, W, S, hf);
 
         // K(j+2), V(j+1) must have landed; K(j) and V(j-1) are free afterwards
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
         asm volatile("" ::: "memory");  // no LDS access may be moved across the barrier
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        issue_k(j + kStages, R);
-        issue_v(j + kStages - 1, Rp);
+        stream_k(j + kStages, R);
+        stream_v(j + kStages - 1, Rp);
     };
+    // Steps [ja, jb) of this wave need no mask: band tiles t with both score halves of the
+    // step (tile t half 1, tile t+1 half 0) inside every row's window and at or below the
+    // first row's diagonal.  The two loops only run if the closed form is off.
+    int ja, jb;
+    {
+        auto unmasked_step = [&](int j) {
+            if (j < n_sink_tiles || j + 1 >= J) return false;
+            const int k0 = tile_of(j) * kBk;
+            return !half_masked(k0 + 32) && !half_masked(k0 + kBk);
+        };
+        const int t_min = max(((wbound - 32) >> 6) + 1, t_band_lo);  // 64 t + 32 > wbound
+        const int t_max = min((p0 - 95) >> 6, t_hi - 1);             // 64 t + 64 + 31 <= p0
+        ja = n_sink_tiles + (t_min - t_band_lo);
+        jb = max(ja, n_sink_tiles + (t_max - t_band_lo) + 1);
+        while (ja < jb && !unmasked_step(ja)) ++ja;
+        while (jb > ja && !unmasked_step(jb - 1)) --jb;
+    }
+    const unsigned n_interior = (unsigned)(jb - ja);
     static_assert(kStages == 3, "the loop below walks three ring positions");
+    auto ring_step = [&](auto ring_pos, int j) { step(ring_pos, (unsigned)(j - ja) >= n_interior, j); };
     for (int j = 0;;) {
-        step(std::integral_constant<int, 0>{}, j);
+        ring_step(std::integral_constant<int, 0>{}, j);
         if (++j >= J) break;
-        step(std::integral_constant<int, 1>{}, j);
+        ring_step(std::integral_constant<int, 1>{}, j);
         if (++j >= J) break;
-        step(std::integral_constant<int, 2>{}, j);
+        ring_step(std::integral_constant<int, 2>{}, j);
         if (++j >= J) break;
     }
     // pipeline drain: P V of the last half (V(J-1) sits in buffer (J-1) % kStages)
