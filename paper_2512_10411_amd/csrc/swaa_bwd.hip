@@ -549,6 +549,314 @@ __global__ __launch_bounds__(kDkvThreads, 1) void swaa_bwd_dkv_kernel(const BwdP
     }
 }
 
+// ---- dK, dV, head dimension 128: tiles by LDS DMA -------------------------------------------
+// Same decomposition, arithmetic and summation order as swaa_bwd_dkv_kernel; what differs is
+// how the tiles reach LDS and how they lie there.  K, V (once per workgroup) and the query
+// tile's Q and dO (per step, two buffers each) travel HBM -> LDS with global_load_lds_dwordx4,
+// no register staging and no store phase: one barrier per step instead of two.  Rows are 256
+// bytes without padding; 16-byte chunk c of row r lies at chunk c ^ g(r), g(r) = ((r & 3) << 2)
+// | ((r >> 2) & 3), applied on the global side of the copy.  That one layout serves both read
+// patterns without bank conflicts: 16 consecutive rows reading the same logical chunk
+// (ds_read_b128 row fragments: g takes 16 different values) and 4 consecutive rows reading the
+// same 64 bytes (ds_read_b64_tr_b16 transposed fragments: the upper two bits of g differ).
+// This kernel declares no static LDS: its dynamic LDS starts at address 0 and all LDS accesses
+// below use plain byte addresses.
+namespace dma128 {
+constexpr int kD = 128, kRowBytes = 256;
+#ifndef SWAA_BWD_AHEAD
+#define SWAA_BWD_AHEAD 2
+#endif
+constexpr int kAhead = SWAA_BWD_AHEAD;  // MFMAs between an LDS operand read and its use
+constexpr int kKeyTileBytes = 128 * kRowBytes;  // 32 KiB: the workgroup's K rows, or V rows
+constexpr int kQTileBytes = kBq * kRowBytes;    // 16 KiB
+constexpr int kK = 0, kV = kKeyTileBytes, kQ = 2 * kKeyTileBytes, kDO = kQ + 2 * kQTileBytes, kL = kDO + 2 * kQTileBytes,
+              kDl = kL + 2 * kBq * 4, kBytes = kDl + 2 * kBq * 4;
+static_assert(2 * kKeyTileBytes >= 4 * 32 * kD * 4, "the K/V area doubles as the buffer of the final sum");
+__device__ __forceinline__ bf16x8 lds16(uint32_t addr) {
+    return *(const bf16x8 __attribute__((address_space(3))) *)(uintptr_t)addr;
+}
+__device__ __forceinline__ s16x4 lds8_tr(uint32_t addr) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)(uintptr_t)addr);
+}
+}  // namespace dma128
+
+__global__ __launch_bounds__(kDkvThreads, 1) void swaa_bwd_dkv_dma_kernel(const BwdParams p) {
+    using namespace dma128;
+    constexpr int D = kD, KS = D / 16, DB = D / 32;
+
+    const int N = p.N, W = p.f.W, S = p.f.S, P = p.f.P, G = p.f.G;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
+    const int kq = wave & 3, qb = wave >> 2;  // key block and row half of this wave
+    // (work list as in swaa_bwd_dkv_kernel)
+    const int n_kt = (N + 127) / 128;
+    const int n_extra = p.B * p.Hkv * p.n_sink_kt * p.n_seg;
+    int kt, pair, seg;  // seg: -1 for a key tile's main workgroup
+    if ((int)blockIdx.x < n_extra) {
+        seg = blockIdx.x % p.n_seg;
+        kt = (blockIdx.x / p.n_seg) % p.n_sink_kt;
+        pair = blockIdx.x / (p.n_seg * p.n_sink_kt);
+    } else {
+        const int id = blockIdx.x - n_extra;
+        seg = -1;
+        kt = id % n_kt;
+        pair = id / n_kt;
+    }
+    const bool sink_kt = kt < p.n_sink_kt;  // results go to the partial-sum workspace
+    const int b = pair / p.Hkv, kvh = pair % p.Hkv;
+    const int k0 = kt * 128, k1 = min(k0 + 127, N - 1);  // the workgroup's keys
+    const int kw0 = k0 + 32 * kq, kw1 = kw0 + 31;         // this wave's keys
+    const int key = kw0 + l32;                            // this lane's key column
+    const bool wave_active = kw0 < N;
+
+    // ---- HBM -> LDS copies: one wave instruction moves 64 x 16 bytes = 4 rows; the LDS side
+    // is linear in the lane id, LDS address = M0 + 16 * lane.  Rows past the end of the
+    // sequence repeat its last row (they stay invisible), so that the reads stay in bounds.
+    const int lrow = lane >> 4, lchk = lane & 15;
+    auto copy16 = [](const char *g, uint32_t lds) {
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds) : "memory");
+    };
+    // rows [4 ii, 4 ii + 4) of a tile whose first row is row `first` of a [N][D] matrix
+    auto copy_rows = [&](const __bf16 *mat, int first, int ii, uint32_t tile) {
+        const int r = 4 * ii + lrow;
+        const int g = (lrow << 2) | (ii & 3);  // g(r): r & 3 = lrow, (r >> 2) & 3 = ii & 3
+        const char *src = reinterpret_cast<const char *>(mat + (size_t)min(first + r, N - 1) * D) + ((lchk ^ g) << 4);
+        copy16(src, tile + (uint32_t)(ii * 1024));
+    };
+    {
+        const size_t kv_base = ((size_t)b * p.Hkv + kvh) * (size_t)N * D;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            copy_rows(p.f.k + kv_base, k0, 4 * wave + i, kK);
+            copy_rows(p.f.v + kv_base, k0, 4 * wave + i, kV);
+        }
+    }
+    f32x16 dkacc[DB], dvacc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            dkacc[db][e] = 0.f;
+            dvacc[db][e] = 0.f;
+        }
+
+    // query tiles (as in swaa_bwd_dkv_kernel)
+    const int tq_last = (N - 1) / kBq;
+    const int tq_band_hi = min(N - 1, k1 + W - 1) / kBq;
+    int tq_lo = k0 / kBq;
+    int n_band = tq_band_hi - tq_lo + 1;
+    int tq_x = tq_last + 1, tq_x_end = tq_last;  // second range
+    if (sink_kt) {
+        if (seg >= 0) {
+            n_band = 0;
+            tq_x = tq_band_hi + 1 + seg * p.seg_tiles;
+            tq_x_end = min(tq_last, tq_x + p.seg_tiles - 1);
+        }
+    } else if (P < N) {
+        tq_x = max(tq_band_hi + 1, P / kBq);
+    }
+    const int n_tiles = n_band + max(0, tq_x_end - tq_x + 1);
+    auto tile_of = [&](int n) { return n < n_band ? tq_lo + n : tq_x + (n - n_band); };
+
+    const float c2 = p.f.scale_log2;
+    float lreg = 0.f, dlreg = 0.f;
+    // step `st` = (head, query tile): its Q and dO rows into buffer `buf`, its lse and delta into registers
+    auto request_tile = [&](int st, int buf) {
+        const int head = kvh * G + st / n_tiles, tq = tile_of(st % n_tiles);
+        const size_t base = ((size_t)b * p.Hq + head) * (size_t)N;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            copy_rows(p.f.q + base * D, tq * kBq, 2 * wave + i, (uint32_t)(kQ + buf * kQTileBytes));
+            copy_rows(p.dout + base * D, tq * kBq, 2 * wave + i, (uint32_t)(kDO + buf * kQTileBytes));
+        }
+        if (tid < kBq) {
+            const int row = min(tq * kBq + tid, N - 1);
+            lreg = p.f.lse[base + row] * 1.44269504088896340736f;
+            dlreg = p.delta[base + row];
+        }
+    };
+    auto publish_rows = [&](int buf) {
+        if (tid < kBq) {
+            *(float __attribute__((address_space(3))) *)(uintptr_t)(kL + buf * kBq * 4 + tid * 4) = lreg;
+            *(float __attribute__((address_space(3))) *)(uintptr_t)(kDl + buf * kBq * 4 + tid * 4) = dlreg;
+        }
+    };
+
+    // per-lane fragment addresses inside a tile (swizzle folded in)
+    //  * row fragment, k-step ks: row 32 rb + l32, logical chunk 2 ks + hf:  row_lane ^ (ks << 5), + 32 rb rows
+    //  * transposed fragment, 16-row step st, head-dimension block db: rows 32 rb + 16 st + 4 hf + j16/4 (lo)
+    //    and 8 further (hi), logical chunk 4 db + 2 (grp & 1) + (j16 & 3) / 2:  col_lane ^ (db << 6), + rows
+    const int gl = ((l32 & 3) << 2) | ((l32 >> 2) & 3);
+    const uint32_t row_lane = (uint32_t)(l32 * kRowBytes + ((hf ^ gl) << 4));
+    const int grp = lane >> 4, j16 = lane & 15;
+    const int rr = 4 * hf + (j16 >> 2);
+    const int cl = 2 * (grp & 1) + ((j16 & 3) >> 1);
+    const uint32_t col_lo = (uint32_t)(rr * kRowBytes + ((((rr & 3) << 2) | (cl ^ hf)) << 4) + 8 * (j16 & 1));
+    const uint32_t col_hi = (uint32_t)((rr + 8) * kRowBytes + ((((rr & 3) << 2) | (cl ^ (hf + 2))) << 4) + 8 * (j16 & 1));
+    auto row_frag_at = [&](uint32_t tile, int rb, int ks) {
+        return lds16(tile + (uint32_t)(32 * rb * kRowBytes) + (row_lane ^ (uint32_t)(ks << 5)));
+    };
+    auto col_frag_at = [&](uint32_t tile, int rb, int st, int db) {
+        const uint32_t off = tile + (uint32_t)((32 * rb + 16 * st) * kRowBytes);
+        const s16x4 lo = lds8_tr(off + (col_lo ^ (uint32_t)(db << 6)));
+        const s16x4 hi = lds8_tr(off + (col_hi ^ (uint32_t)(db << 6)));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+
+    const int total = G * n_tiles;  // (head, tile) steps, head-major
+    if (total > 0) {
+        request_tile(0, 0);
+        publish_rows(0);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0): this wave's copies have landed
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+
+    for (int step = 0; step < total; ++step) {
+        const int buf = step & 1;
+        const bool has_next = step + 1 < total;
+        // the other buffers were last read one step ago, before the barrier that ended it
+        if (has_next) request_tile(step + 1, buf ^ 1);
+
+        const uint32_t Qs = (uint32_t)(kQ + buf * kQTileBytes), dOs = (uint32_t)(kDO + buf * kQTileBytes);
+        const int tq = tile_of(step % n_tiles);
+        const int i0 = tq * kBq + 32 * qb, i1 = i0 + 31;  // this wave's rows of the tile
+        // can any of them see any key of this wave?
+        const bool sees = (i0 < N) && (i1 >= kw0) && ((i0 < kw1 + W) || (kw0 < S) || (i1 >= P));
+        if (wave_active && sees) {
+            // all 32 x 32 pairs visible: rows at or below the keys' diagonal, inside every row's window
+            // (or the keys are sinks, or the rows are generated tokens), and no row past the end
+            const bool unmasked = (kw1 <= i0) && (i1 < N) && ((i1 - kw0 < W) || (kw1 < S) || (i0 >= P));
+
+            // S = Q K^T and dP = dO V^T : [32 queries] x [32 keys]
+            f32x16 sacc, dpacc;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                sacc[e] = 0.f;
+                dpacc[e] = 0.f;
+            }
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag_at(Qs, qb, ks), row_frag_at(kK, kq, ks), sacc, 0, 0, 0);
+                dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag_at(dOs, qb, ks), row_frag_at(kV, kq, ks), dpacc, 0, 0, 0);
+            }
+            // operand reads run kAhead MFMAs ahead of their use (two reads per MFMA)
+            __builtin_amdgcn_sched_group_barrier(0x100, 2 * kAhead, 0);
+#pragma unroll
+            for (int i = 0; i < 2 * KS; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            }
+
+            // P and dS in the accumulator layout (row 8 (e/4) + 4 hf + e%4, column = this lane's key)
+            bf16x8 pf[2], dsf[2];  // [16-row step]
+#pragma unroll
+            for (int e4 = 0; e4 < 4; ++e4) {
+                const int r4 = 32 * qb + 8 * e4 + 4 * hf;
+                typedef float f32x4 __attribute__((ext_vector_type(4)));
+                const f32x4 l4 = *(const f32x4 __attribute__((address_space(3))) *)(uintptr_t)(kL + buf * kBq * 4 + r4 * 4);
+                const f32x4 d4 = *(const f32x4 __attribute__((address_space(3))) *)(uintptr_t)(kDl + buf * kBq * 4 + r4 * 4);
+                const float lv[4] = {l4[0], l4[1], l4[2], l4[3]};
+                const float dv4[4] = {d4[0], d4[1], d4[2], d4[3]};
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    const int e = 4 * e4 + x;
+                    const int row = tq * kBq + r4 + x;
+                    float pe = __builtin_amdgcn_exp2f(fmaf(sacc[e], c2, -lv[x]));
+                    if (!unmasked && !(row < N && visible(row, key, W, S, P))) pe = 0.f;
+                    pf[e / 8][e % 8] = (__bf16)pe;
+                    dsf[e / 8][e % 8] = (__bf16)(pe * (dpacc[e] - dv4[x]));
+                }
+            }
+
+            // dV^T += dO^T P,  dK^T += Q^T dS
+#pragma unroll
+            for (int st = 0; st < 2; ++st)
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    dvacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(col_frag_at(dOs, qb, st, db), pf[st], dvacc[db], 0, 0, 0);
+                    dkacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(col_frag_at(Qs, qb, st, db), dsf[st], dkacc[db], 0, 0, 0);
+                }
+            __builtin_amdgcn_sched_group_barrier(0x100, 2 * kAhead, 1);
+#pragma unroll
+            for (int i = 0; i < 4 * DB; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
+            }
+        }
+
+        if (has_next) publish_rows(buf ^ 1);
+        // the next tile has landed (this wave's part, then everybody's), this one is free afterwards
+        __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    }
+
+    // ---- add the two row halves: waves 4..7 hand their sums to waves 0..3 through LDS
+    // (the K/V area, which nobody reads any more), first dK, then dV ----
+    // [4 key blocks][D][32 key columns] floats from LDS address 0
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+        if (which) __syncthreads();
+        if (qb == 1) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int d = 32 * db + 8 * (e / 4) + 4 * hf + (e % 4);
+                    *(float __attribute__((address_space(3))) *)(uintptr_t)(((kq * D + d) * 32 + l32) * 4) =
+                        which == 0 ? dkacc[db][e] : dvacc[db][e];
+                }
+        }
+        __syncthreads();
+        if (qb == 0) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int d = 32 * db + 8 * (e / 4) + 4 * hf + (e % 4);
+                    const float other = *(const float __attribute__((address_space(3))) *)(uintptr_t)(((kq * D + d) * 32 + l32) * 4);
+                    if (which == 0)
+                        dkacc[db][e] += other;
+                    else
+                        dvacc[db][e] += other;
+                }
+        }
+    }
+    if (qb != 0) return;
+
+    if (sink_kt) {
+        // fp32 partial sums of all 128 key columns (columns past the end hold zeros)
+        float *slot = p.partial + ((((size_t)pair * p.n_sink_kt + kt) * (p.n_seg + 1) + (seg + 1)) * 2) * (size_t)(128 * D);
+        float *pk = slot + (size_t)(32 * kq + l32) * D, *pv = pk + 128 * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int e4 = 0; e4 < 4; ++e4) {
+                const float4 k4 = {dkacc[db][4 * e4], dkacc[db][4 * e4 + 1], dkacc[db][4 * e4 + 2], dkacc[db][4 * e4 + 3]};
+                const float4 v4 = {dvacc[db][4 * e4], dvacc[db][4 * e4 + 1], dvacc[db][4 * e4 + 2], dvacc[db][4 * e4 + 3]};
+                *reinterpret_cast<float4 *>(pk + 32 * db + 8 * e4 + 4 * hf) = k4;
+                *reinterpret_cast<float4 *>(pv + 32 * db + 8 * e4 + 4 * hf) = v4;
+            }
+    } else if (key < N) {
+        const size_t row = (((size_t)b * p.Hkv + kvh) * (size_t)N + key) * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int e4 = 0; e4 < 4; ++e4) {
+                bf16x4 k4, v4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    k4[e] = (__bf16)(dkacc[db][4 * e4 + e] * p.f.scale);
+                    v4[e] = (__bf16)dvacc[db][4 * e4 + e];
+                }
+                *reinterpret_cast<bf16x4 *>(p.dk + row + 32 * db + 8 * e4 + 4 * hf) = k4;
+                *reinterpret_cast<bf16x4 *>(p.dv + row + 32 * db + 8 * e4 + 4 * hf) = v4;
+            }
+    }
+}
+
 // dK, dV of the sink key tiles: sum of the band part and the segments, in a fixed order.
 template <int D>
 __global__ __launch_bounds__(kThreads) void swaa_bwd_sink_sum_kernel(const BwdParams p) {
@@ -603,10 +911,16 @@ hipError_t launch_bwd_d(const BwdParams &p, hipStream_t stream) {
         err = hipFuncSetAttribute(reinterpret_cast<const void *>(&swaa_bwd_dkv_kernel<D>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, DkvSmem<D>::kBytes);
         if (err != hipSuccess) return err;
+        err = hipFuncSetAttribute(reinterpret_cast<const void *>(&swaa_bwd_dkv_dma_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, dma128::kBytes);
+        if (err != hipSuccess) return err;
         configured.fetch_or(bit, std::memory_order_release);
     }
-    hipLaunchKernelGGL(swaa_bwd_dkv_kernel<D>, dim3((unsigned)(pairs * (n_kt + (long long)p.n_sink_kt * p.n_seg))),
-                       dim3(kDkvThreads), DkvSmem<D>::kBytes, stream, p);
+    const dim3 dkv_grid((unsigned)(pairs * (n_kt + (long long)p.n_sink_kt * p.n_seg)));
+    if (D == 128)
+        hipLaunchKernelGGL(swaa_bwd_dkv_dma_kernel, dkv_grid, dim3(kDkvThreads), dma128::kBytes, stream, p);
+    else
+        hipLaunchKernelGGL(swaa_bwd_dkv_kernel<D>, dkv_grid, dim3(kDkvThreads), DkvSmem<D>::kBytes, stream, p);
     err = hipGetLastError();
     if (err != hipSuccess || p.n_sink_kt == 0) return err;
     const long long threads = pairs * p.n_sink_kt * (128LL * D / 4);
