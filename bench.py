@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0           # MI355X HBM3E
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by a copy kernel of known size;
 # the summaries are profiles/swaa_fwd_pipelined_<workload>.txt.  Used when
 # --traffic-bytes is not given; workloads not measured yet report null.
-MEASURED_TRAFFIC_BYTES = {"mid": 4.12e8, "batched": 1.076e9, "decode128k_full": 5.41e8, "decode16k_b16": 1.079e9}
+MEASURED_TRAFFIC_BYTES = {"mid": 4.05e8, "batched": 1.076e9, "decode128k_full": 5.41e8, "decode16k_b16": 1.079e9}
 
 
 def parse():
@@ -262,7 +262,8 @@ def main():
         # (the fp16 matrix peak equals the bf16 one)
         roofline = {"bound": "mfma", "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": traffic,
-                    "kernel": ("swaa_bwd_dkv_kernel + swaa_bwd_dq_kernel + swaa_bwd_delta_kernel" if w.backward
+                    "kernel": (("swaa_bwd_dkv_dma_kernel + swaa_bwd_dq_dma_kernel + swaa_bwd_delta_kernel" if w.D == 128 else
+                                f"swaa_bwd_dkv_kernel<{w.D}> + swaa_bwd_dq_kernel<{w.D}> + swaa_bwd_delta_kernel") if w.backward
                                else "swaa_fwd_pipelined_kernel" if w.D == 128 and w.fmt == "bf16"
                                else f"swaa_fwd_kernel<{w.D}>"),
                     "kernel_avg_ms": kern_avg_ms}
