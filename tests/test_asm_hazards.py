@@ -159,3 +159,29 @@ def test_no_vector_write_within_two_instructions_of_an_mfma_that_reads_it(tmp_pa
     assert not problems, problems[:5]
     late = result_hazards(insts, labels)
     assert not late, late[:5]
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None and not os.path.exists("/opt/rocm/bin/hipcc"),
+                    reason="hipcc not available")
+def test_backward_dma_kernels_own_all_lds(tmp_path):
+    """The two LDS-DMA backward kernels address LDS with plain byte addresses from 0 (their
+    MFMAs go through compiler builtins, so the wait-state rules above are the compiler's)."""
+    out = tmp_path / "b.s"
+    flags = [f for f in build.HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
+    cmd = [build.hipcc_path(), *flags, "--cuda-device-only", "-S", "-o", str(out), os.path.join(build.CSRC, "swaa_bwd.hip")]
+    subprocess.run(cmd, check=True, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)
+    text = open(out).read()
+    sizes = re.findall(r"\.amdhsa_group_segment_fixed_size\s+(\d+)", text)
+    names = re.findall(r"\.amdhsa_kernel\s+(\S+)", text)
+    assert names and len(sizes) == len(names)
+    seen = set()
+    for name, size in zip(names, sizes):
+        for k in ("dkv_dma", "dq_dma"):
+            if k in name:
+                seen.add(k)
+                assert int(size) == 0, (name, size)
+    assert seen == {"dkv_dma", "dq_dma"}
+    # and they do not spill (a spill would also mean scratch traffic inside the key loop)
+    for name, spill in zip(names, re.findall(r"\.amdhsa_private_segment_fixed_size\s+(\d+)", text)):
+        if "dma" in name:
+            assert int(spill) == 0, (name, spill)
