@@ -99,31 +99,36 @@ struct WorkItem {
 // chunk of the work list, so the position tiles of one KV head, whose K/V
 // bands overlap, run behind the same L2.  Inside a pair, long rows go first.
 __device__ __forceinline__ bool decode_work(const FwdParams &p, WorkItem &w) {
-    const long long bid = blockIdx.x;
-    const long long slot = bid / kXcds;
-    const long long item = (bid % kXcds) * p.chunk + slot;
-    if (slot >= p.chunk || item >= p.total_items) return false;
-    const int pair = (int)(item / p.tiles_per_pair);
-    int r = (int)(item % p.tiles_per_pair);
-    w.b = pair / p.Hkv;
-    w.kvh = pair % p.Hkv;
-    if (r < p.n4 * p.nt64) {
+    // (the entry points refuse work lists of 2^31 items or more: 32-bit arithmetic, whose
+    // divisions cost a fraction of the 64-bit ones -- every wave of every workgroup pays them)
+    const unsigned bid = blockIdx.x;
+    const unsigned slot = bid / kXcds, chunk = (unsigned)p.chunk;
+    const unsigned item = (bid % kXcds) * chunk + slot;
+    if (slot >= chunk || item >= (unsigned)p.total_items) return false;
+    const unsigned tpp = (unsigned)p.tiles_per_pair, hkv = (unsigned)p.Hkv;
+    const unsigned pair = item / tpp;
+    unsigned r = item - pair * tpp;
+    w.b = (int)(pair / hkv);
+    w.kvh = (int)(pair - (unsigned)w.b * hkv);
+    const unsigned nt64 = (unsigned)p.nt64, nt128 = (unsigned)p.nt128;
+    if (r < (unsigned)p.n4 * nt64) {
+        const unsigned g = r / nt64;
         w.hpb = 4;
-        w.h0 = 4 * (r / p.nt64);
-        w.pt = p.nt64 - 1 - (r % p.nt64);
+        w.h0 = 4 * (int)g;
+        w.pt = (int)(nt64 - 1 - (r - g * nt64));
         return true;
     }
-    r -= p.n4 * p.nt64;
-    if (p.has2 && r < p.nt128) {
+    r -= (unsigned)p.n4 * nt64;
+    if (p.has2 && r < nt128) {
         w.hpb = 2;
         w.h0 = 4 * p.n4;
-        w.pt = p.nt128 - 1 - r;
+        w.pt = (int)(nt128 - 1 - r);
         return true;
     }
-    if (p.has2) r -= p.nt128;
+    if (p.has2) r -= nt128;
     w.hpb = 1;
     w.h0 = p.G - 1;
-    w.pt = p.nt256 - 1 - r;
+    w.pt = p.nt256 - 1 - (int)r;
     return true;
 }
 
