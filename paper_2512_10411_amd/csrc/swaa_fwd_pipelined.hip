@@ -333,7 +333,14 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     pin_acc(oacc);
 
     // per-lane LDS read offsets inside a half tile (swizzle folded in)
-    const LaneAddr la = make_lane_addr(lane, kVRing);
+    // (made opaque: otherwise the compiler precomputes "lane offset + buffer offset" for many
+    // (buffer, fragment) pairs, parks those addresses in AccVGPRs and copies one back before
+    // every read; this way the buffers' constant offsets go into the instructions' offset fields)
+    LaneAddr la = make_lane_addr(lane, kVRing);
+#pragma unroll
+    for (int ks = 0; ks < kKS; ++ks) asm volatile("" : "+v"(la.k[ks]));
+#pragma unroll
+    for (int db = 0; db < kDB; ++db) asm volatile("" : "+v"(la.v[db]));
 
     const float c2 = p.scale_log2;
 
