@@ -30,7 +30,6 @@
 // to the compiler; both big kernels run two waves per SIMD.
 #include <atomic>
 #include <cmath>
-#include <type_traits>
 
 #include "swaa_bwd.h"
 
@@ -660,36 +659,14 @@ __global__ __launch_bounds__(kDkvThreads, 1) void swaa_bwd_dkv_dma_kernel(const 
 
     const float c2 = p.f.scale_log2;
     float lreg = 0.f, dlreg = 0.f;
-    // step `st` = (head, query tile): its Q and dO rows into buffer `buf`, its lse and delta into registers.
-    // A full tile takes the fast path: uniform base address plus this lane's constant offsets.
-    auto copy16u = [](uint32_t off, const char *base, uint32_t lds) {
-        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds)
-                     : "memory");
-    };
-    uint32_t qoff[2];  // byte offset of this lane's 16 bytes from the tile's first row, copies 2 wave + i
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int ii = 2 * wave + i;
-        qoff[i] = (uint32_t)((4 * ii + lrow) * kRowBytes + ((lchk ^ ((lrow << 2) | (ii & 3))) << 4));
-    }
+    // step `st` = (head, query tile): its Q and dO rows into buffer `buf`, its lse and delta into registers
     auto request_tile = [&](int st, int buf) {
         const int head = kvh * G + st / n_tiles, tq = tile_of(st % n_tiles);
         const size_t base = ((size_t)b * p.Hq + head) * (size_t)N;
-        if (__builtin_expect(tq * kBq + kBq <= N, 1)) {
-            const char *qt = reinterpret_cast<const char *>(p.f.q + (base + (size_t)tq * kBq) * D);
-            const char *dt = reinterpret_cast<const char *>(p.dout + (base + (size_t)tq * kBq) * D);
-            const uint32_t l = (uint32_t)(buf * kQTileBytes + 2 * wave * 1024);
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                copy16u(qoff[i], qt, (uint32_t)kQ + l + (uint32_t)(i * 1024));
-                copy16u(qoff[i], dt, (uint32_t)kDO + l + (uint32_t)(i * 1024));
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                copy_rows(p.f.q + base * D, tq * kBq, 2 * wave + i, (uint32_t)(kQ + buf * kQTileBytes));
-                copy_rows(p.dout + base * D, tq * kBq, 2 * wave + i, (uint32_t)(kDO + buf * kQTileBytes));
-            }
+        for (int i = 0; i < 2; ++i) {
+            copy_rows(p.f.q + base * D, tq * kBq, 2 * wave + i, (uint32_t)(kQ + buf * kQTileBytes));
+            copy_rows(p.dout + base * D, tq * kBq, 2 * wave + i, (uint32_t)(kDO + buf * kQTileBytes));
         }
         if (tid < kBq) {
             const int row = min(tq * kBq + tid, N - 1);
@@ -773,30 +750,24 @@ __global__ __launch_bounds__(kDkvThreads, 1) void swaa_bwd_dkv_dma_kernel(const 
 
             // P and dS in the accumulator layout (row 8 (e/4) + 4 hf + e%4, column = this lane's key)
             bf16x8 pf[2], dsf[2];  // [16-row step]
-            typedef float f32x4 __attribute__((ext_vector_type(4)));
-            auto p_and_ds = [&](auto masked) {
 #pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4) {
-                    const int r4 = 32 * qb + 8 * e4 + 4 * hf;
-                    const f32x4 l4 = *(const f32x4 __attribute__((address_space(3))) *)(uintptr_t)(kL + buf * kBq * 4 + r4 * 4);
-                    const f32x4 d4 = *(const f32x4 __attribute__((address_space(3))) *)(uintptr_t)(kDl + buf * kBq * 4 + r4 * 4);
+            for (int e4 = 0; e4 < 4; ++e4) {
+                const int r4 = 32 * qb + 8 * e4 + 4 * hf;
+                typedef float f32x4 __attribute__((ext_vector_type(4)));
+                const f32x4 l4 = *(const f32x4 __attribute__((address_space(3))) *)(uintptr_t)(kL + buf * kBq * 4 + r4 * 4);
+                const f32x4 d4 = *(const f32x4 __attribute__((address_space(3))) *)(uintptr_t)(kDl + buf * kBq * 4 + r4 * 4);
+                const float lv[4] = {l4[0], l4[1], l4[2], l4[3]};
+                const float dv4[4] = {d4[0], d4[1], d4[2], d4[3]};
 #pragma unroll
-                    for (int x = 0; x < 4; ++x) {
-                        const int e = 4 * e4 + x;
-                        float pe = __builtin_amdgcn_exp2f(fmaf(sacc[e], c2, -l4[x]));
-                        if (decltype(masked)::value) {
-                            const int row = tq * kBq + r4 + x;
-                            if (!(row < N && visible(row, key, W, S, P))) pe = 0.f;
-                        }
-                        pf[e / 8][e % 8] = (__bf16)pe;
-                        dsf[e / 8][e % 8] = (__bf16)(pe * (dpacc[e] - d4[x]));
-                    }
+                for (int x = 0; x < 4; ++x) {
+                    const int e = 4 * e4 + x;
+                    const int row = tq * kBq + r4 + x;
+                    float pe = __builtin_amdgcn_exp2f(fmaf(sacc[e], c2, -lv[x]));
+                    if (!unmasked && !(row < N && visible(row, key, W, S, P))) pe = 0.f;
+                    pf[e / 8][e % 8] = (__bf16)pe;
+                    dsf[e / 8][e % 8] = (__bf16)(pe * (dpacc[e] - dv4[x]));
                 }
-            };
-            if (unmasked)
-                p_and_ds(std::false_type{});
-            else
-                p_and_ds(std::true_type{});
+            }
 
             // dV^T += dO^T P,  dK^T += Q^T dS
 #pragma unroll
