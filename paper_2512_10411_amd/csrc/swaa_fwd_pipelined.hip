@@ -277,20 +277,38 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     struct TileStream {
         const char *next;   // first row of the next tile to copy
         size_t step, jump;  // bytes to the following tile: the usual one, and from the last sink tile to the band
+        int plain;          // tiles to copy before the next one that needs a closer look
+    };
+    // A tile needs a closer look if it is the last sink tile before a jump, runs past the
+    // sequence's end, or does not exist; all others take "copy, advance by one tile".
+    auto special = [&](int j) { return j + 1 == n_sink_tiles || j == j_ragged || j >= J; };
+    auto plain_from = [&](int j) {  // number of consecutive tiles from j on that are not special
+        int e = J;
+        if (j_ragged >= j) e = min(e, j_ragged);
+        if (n_sink_tiles - 1 >= j) e = min(e, n_sink_tiles - 1);
+        return max(e - j, 0);
     };
     auto make_stream = [&](const __bf16 *src, uint32_t rsb) {
         TileStream ts;
         ts.next = reinterpret_cast<const char *>(src) + (size_t)(tile_of(0) * kBk) * rsb;
         ts.step = (size_t)kBk * rsb;
         ts.jump = (size_t)(t_band_lo - n_sink_tiles + 1) * kBk * rsb;
+        ts.plain = plain_from(0);
         return ts;
     };
     TileStream k_stream = make_stream(kg, k_rsb), v_stream = make_stream(vg, v_rsb);
     auto stream_tile = [&](TileStream &ts, int j, int buf, int ring, bool is_k) {
-        if (j >= J) return;
+        if (__builtin_expect(--ts.plain >= 0, 1)) {
+            const char *base = ts.next;
+            ts.next += ts.step;
+            copy_tile(base, buf, ring, is_k, false);
+            return;
+        }
+        if (j >= J) return;  // (plain stays negative: every later call ends here)
         const char *base = ts.next;
         ts.next += (j + 1 == n_sink_tiles) ? ts.jump : ts.step;
         copy_tile(base, buf, ring, is_k, j == j_ragged);
+        ts.plain = plain_from(j + 1);
     };
     auto stream_k = [&](int j, int buf) { stream_tile(k_stream, j, buf, 0, true); };
     auto stream_v = [&](int j, int buf) { stream_tile(v_stream, j, buf, kVRing, false); };
