@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0           # MI355X HBM3E
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by a copy kernel of known size;
 # the summaries are profiles/swaa_fwd_pipelined_<workload>.txt.  Used when
 # --traffic-bytes is not given; workloads not measured yet report null.
-MEASURED_TRAFFIC_BYTES = {"mid": 4.05e8, "batched": 1.076e9, "decode128k_full": 5.41e8, "decode16k_b16": 1.079e9}
+MEASURED_TRAFFIC_BYTES = {"mid": 3.97e8, "batched": 1.032e9, "decode128k_full": 5.41e8, "decode16k_b16": 1.079e9}
 
 
 def parse():
