@@ -116,3 +116,29 @@ def test_run_to_run_determinism_and_errors():
 def test_mid_size_every_element(shape):
     B, Hq, Hkv, N, D, W, S, P = shape
     check(B, Hq, Hkv, N, D, W, S, P, seed=9500 + N)
+
+
+def test_benchmark_workload_at_full_size_two_kv_heads():
+    """The launch configuration bench.py times (workload mid_bwd, all 32 heads), checked on
+    every element of the first and the last KV head with their query heads: heads are
+    independent, so the oracle runs on those slices only (about 20 s on the host)."""
+    from paper_2512_10411_amd.inputs import WORKLOADS, make_workload
+
+    w = WORKLOADS["mid_bwd"]
+    q, k, v = make_workload(w)
+    dout = make_dout(q.shape, w.seed + 1)
+    qd, kd, vd, dd = to_device(q), to_device(k), to_device(v), to_device(dout)
+    out, lse = binding.swaa_attn_fwd(qd, kd, vd, w.window, w.n_sink, w.scale)
+    dq, dk, dv = binding.swaa_attn_bwd(qd, kd, vd, out, lse, dd, w.window, w.n_sink, None, w.scale)
+    torch.cuda.synchronize()
+    G = w.Hq // w.Hkv
+    for kvh in (0, w.Hkv - 1):
+        tag = f"mid_bwd full size, KV head {kvh}"
+        print(f"[case] {tag}", flush=True)
+        hs = slice(kvh * G, (kvh + 1) * G)
+        rq, rk, rv = swaa_attn_bwd_oracle(np.ascontiguousarray(q[:, hs]), np.ascontiguousarray(k[:, kvh:kvh + 1]),
+                                          np.ascontiguousarray(v[:, kvh:kvh + 1]), np.ascontiguousarray(dout[:, hs]),
+                                          w.window, w.n_sink, w.scale)
+        assert_grad("dq", dq[:, hs], rq, tag)
+        assert_grad("dk", dk[:, kvh:kvh + 1], rk, tag)
+        assert_grad("dv", dv[:, kvh:kvh + 1], rv, tag)
