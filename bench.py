@@ -262,7 +262,7 @@ def main():
         # (the fp16 matrix peak equals the bf16 one)
         roofline = {"bound": "mfma", "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": traffic,
-                    "kernel": (("swaa_bwd_dkv_dma_kernel + swaa_bwd_dq_dma_kernel + swaa_bwd_delta_kernel" if w.D == 128 else
+                    "kernel": (("swaa_bwd_dkv_dma_kernel + swaa_bwd_dq_pipelined_kernel + swaa_bwd_delta_kernel" if w.D == 128 else
                                 f"swaa_bwd_dkv_kernel<{w.D}> + swaa_bwd_dq_kernel<{w.D}> + swaa_bwd_delta_kernel") if w.backward
                                else "swaa_fwd_pipelined_kernel" if w.D == 128 and w.fmt == "bf16"
                                else f"swaa_fwd_kernel<{w.D}>"),

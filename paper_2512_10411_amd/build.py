@@ -12,7 +12,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 SOURCES = [os.path.join(CSRC, f) for f in ("swaa_api.hip", "swaa_fwd_simple.hip", "swaa_fwd_pipelined.hip",
-                                            "swaa_decode.hip", "swaa_bwd.hip")]
+                                            "swaa_decode.hip", "swaa_bwd.hip", "swaa_bwd_dq_pipelined.hip")]
 LIB = os.path.join(PKG, "libswaa.so")
 
 HIPCC_FLAGS = [

@@ -29,6 +29,8 @@ void plan_bwd(BwdParams &p);
 long long bwd_workspace_floats(const BwdParams &p, int D);
 
 hipError_t launch_bwd(const BwdParams &p, int D, hipStream_t stream);
+// dQ alone, head dimension 128, software-pipelined (swaa_bwd_dq_pipelined.hip); delta must be there
+hipError_t launch_bwd_dq_pipelined_d128(const BwdParams &p, hipStream_t stream);
 
 }  // namespace swaa
 

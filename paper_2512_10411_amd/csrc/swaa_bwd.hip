@@ -26,8 +26,10 @@
 // consumes them (as in the forward kernels); operands that a product needs
 // transposed are read from row-major LDS tiles with ds_read_b64_tr_b16.
 // P and dS are rounded to bf16 before the second products, sums are fp32.
-// This version stages tiles through registers and leaves instruction scheduling
-// to the compiler; both big kernels run two waves per SIMD.
+// The kernels in this file stage tiles through registers (the templates, used for head
+// dimension 64) or by LDS DMA (dK/dV for head dimension 128) and leave instruction scheduling
+// to the compiler; dQ for head dimension 128 is the hand-pipelined kernel of
+// swaa_bwd_dq_pipelined.hip.  All big kernels run two waves per SIMD.
 #include <atomic>
 #include <cmath>
 
@@ -857,208 +859,6 @@ __global__ __launch_bounds__(kDkvThreads, 1) void swaa_bwd_dkv_dma_kernel(const 
     }
 }
 
-// ---- dQ, head dimension 128: K/V tiles by LDS DMA ------------------------------------------
-// Same decomposition, arithmetic and summation order as swaa_bwd_dq_kernel<128, 1>; the K and
-// V tiles (64 keys, two buffers each) travel HBM -> LDS with global_load_lds_dwordx4 in the
-// swizzled layout described above, one barrier per tile, operand reads scheduled ahead of the
-// MFMAs.  No static LDS: plain byte addresses from 0.
-namespace dma128 {
-constexpr int kTileBytes = kBk * kRowBytes;  // 16 KiB: 64 keys
-constexpr int kDqK = 0, kDqV = 2 * kTileBytes, kDqBytes = 4 * kTileBytes;
-}  // namespace dma128
-
-__global__ __launch_bounds__(512, 1) void swaa_bwd_dq_dma_kernel(const BwdParams p) {
-    using namespace dma128;
-    constexpr int D = kD, KS = D / 16, DB = D / 32, kRows = 32;
-
-    WorkItem wi;
-    if (!decode_work(p.f, wi)) return;
-    const int hpb = wi.hpb;
-    const int rows_per_wg = kWgRows / hpb;
-    const int N = p.N, W = p.f.W, S = p.f.S, P = p.f.P;
-    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, l32 = lane & 31, hf = lane >> 5;
-
-    const int head = wi.kvh * p.f.G + wi.h0 + (wave % hpb);
-    const int wg_p0 = wi.pt * rows_per_wg;
-    const int wg_p1 = min(N, wg_p0 + rows_per_wg) - 1;
-    const int p0 = wg_p0 + (wave / hpb) * kRows;
-    const bool wave_active = p0 < N;
-    const int plast = min(p0 + kRows, N) - 1;
-
-    const int band_lo = (wg_p1 >= P) ? 0 : max(0, wg_p0 - W + 1);
-    const int t_band_lo = band_lo / kBk;
-    const int t_hi = wg_p1 / kBk;
-    const int n_sink_tiles = min((min(S, band_lo) + kBk - 1) / kBk, t_band_lo);
-    const int wbound = window_bound(p0, kRows, W, P);
-
-    const size_t kv_base = ((size_t)wi.b * p.Hkv + wi.kvh) * (size_t)N * D;
-    const __bf16 *kg = p.f.k + kv_base;
-    const __bf16 *vg = p.f.v + kv_base;
-    const size_t q_base = ((size_t)wi.b * p.Hq + head) * (size_t)N * D;
-    const size_t r_base = ((size_t)wi.b * p.Hq + head) * (size_t)N;
-
-    // ---- HBM -> LDS copies (see swaa_bwd_dkv_dma_kernel) ----
-    const int lrow = lane >> 4, lchk = lane & 15;
-    auto copy16 = [](const char *g, uint32_t lds) {
-        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds) : "memory");
-    };
-    auto copy_rows = [&](const __bf16 *mat, int first, int ii, uint32_t tile) {
-        const int r = 4 * ii + lrow;
-        const int g = (lrow << 2) | (ii & 3);
-        const char *src = reinterpret_cast<const char *>(mat + (size_t)min(first + r, N - 1) * D) + ((lchk ^ g) << 4);
-        copy16(src, tile + (uint32_t)(ii * 1024));
-    };
-    auto request_tile = [&](int t, int buf) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            copy_rows(kg, t * kBk, 2 * wave + i, (uint32_t)(kDqK + buf * kTileBytes));
-            copy_rows(vg, t * kBk, 2 * wave + i, (uint32_t)(kDqV + buf * kTileBytes));
-        }
-    };
-    auto next_tile = [&](int t) {
-        int n = t + 1;
-        if (n == n_sink_tiles && n < t_band_lo) n = t_band_lo;
-        return n;
-    };
-    int t = (n_sink_tiles > 0) ? 0 : t_band_lo;
-    request_tile(t, 0);
-
-    // this wave's Q and dO rows as B operands, its rows' lse (log2 units) and delta
-    bf16x8 qf[KS], dof[KS];
-    float lse2, dl;
-    {
-        const int row = min(p0 + l32, N - 1);
-        const __bf16 *qs = p.f.q + q_base + (size_t)row * D + 8 * hf;
-        const __bf16 *ds = p.dout + q_base + (size_t)row * D + 8 * hf;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            qf[ks] = *reinterpret_cast<const bf16x8 *>(qs + 16 * ks);
-            dof[ks] = *reinterpret_cast<const bf16x8 *>(ds + 16 * ks);
-        }
-        lse2 = p.f.lse[r_base + row] * 1.44269504088896340736f;
-        dl = p.delta[r_base + row];
-    }
-
-    f32x16 dqacc[DB];
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) dqacc[db][e] = 0.f;
-
-    // per-lane fragment addresses inside a tile (see swaa_bwd_dkv_dma_kernel)
-    const int gl = ((l32 & 3) << 2) | ((l32 >> 2) & 3);
-    const uint32_t row_lane = (uint32_t)(l32 * kRowBytes + ((hf ^ gl) << 4));
-    const int grp = lane >> 4, j16 = lane & 15;
-    const int rr = 4 * hf + (j16 >> 2);
-    const int cl = 2 * (grp & 1) + ((j16 & 3) >> 1);
-    const uint32_t col_lo = (uint32_t)(rr * kRowBytes + ((((rr & 3) << 2) | (cl ^ hf)) << 4) + 8 * (j16 & 1));
-    const uint32_t col_hi = (uint32_t)((rr + 8) * kRowBytes + ((((rr & 3) << 2) | (cl ^ (hf + 2))) << 4) + 8 * (j16 & 1));
-    auto row_frag_at = [&](uint32_t tile, int rb, int ks) {
-        return lds16(tile + (uint32_t)(32 * rb * kRowBytes) + (row_lane ^ (uint32_t)(ks << 5)));
-    };
-    auto col_frag_at = [&](uint32_t tile, int rb, int st, int db) {
-        const uint32_t off = tile + (uint32_t)((32 * rb + 16 * st) * kRowBytes);
-        const s16x4 lo = lds8_tr(off + (col_lo ^ (uint32_t)(db << 6)));
-        const s16x4 hi = lds8_tr(off + (col_hi ^ (uint32_t)(db << 6)));
-        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-    };
-
-    __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0): this wave's copies have landed
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    const float c2 = p.f.scale_log2;
-
-    for (int buf = 0;; buf ^= 1) {
-        const int tn = next_tile(t);
-        const bool has_next = tn <= t_hi;
-        // the other buffers were last read one tile ago, before the barrier that ended it
-        if (has_next) request_tile(tn, buf ^ 1);
-
-        const uint32_t Ks = (uint32_t)(kDqK + buf * kTileBytes), Vs = (uint32_t)(kDqV + buf * kTileBytes);
-        const int k0 = t * kBk, k_last = k0 + kBk - 1;
-        const bool in_future = k0 > plast;
-        const bool before_band = (plast < P) && (k_last < p0 - W + 1) && (k0 >= S);
-        if (wave_active && !in_future && !before_band) {
-            const bool unmasked = (k_last <= p0) && ((k0 > wbound) || (k_last < S));
-
-            // S^T = K Q^T and dP^T = V dO^T : [64 keys] x [32 queries]
-            f32x16 sacc[2], dpacc[2];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    sacc[kb][e] = 0.f;
-                    dpacc[kb][e] = 0.f;
-                }
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb) {
-                    sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag_at(Ks, kb, ks), qf[ks], sacc[kb], 0, 0, 0);
-                    dpacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag_at(Vs, kb, ks), dof[ks], dpacc[kb], 0, 0, 0);
-                }
-            // operand reads run kAhead MFMAs ahead of their use (one read per MFMA)
-            __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
-#pragma unroll
-            for (int i = 0; i < 4 * KS; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-
-            // P^T = exp2(s c2 - lse2) on visible pairs, dS^T = P^T (dP^T - delta), packed to bf16
-            bf16x8 dsf[2][2];  // [kb][16-key step]
-            const int qpos = p0 + l32;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int key = k0 + 32 * kb + 8 * (e / 4) + 4 * hf + (e % 4);
-                    float pe = __builtin_amdgcn_exp2f(fmaf(sacc[kb][e], c2, -lse2));
-                    if (!unmasked && !visible(qpos, key, W, S, P)) pe = 0.f;
-                    dsf[kb][e / 8][e % 8] = (__bf16)(pe * (dpacc[kb][e] - dl));
-                }
-
-            // dQ^T += K^T dS^T
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int st = 0; st < 2; ++st)
-#pragma unroll
-                    for (int db = 0; db < DB; ++db)
-                        dqacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(col_frag_at(Ks, kb, st, db), dsf[kb][st], dqacc[db], 0, 0, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 2 * kAhead, 1);
-#pragma unroll
-            for (int i = 0; i < 4 * DB; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
-                __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
-            }
-        }
-
-        if (!has_next) break;
-        // the next tile has landed (this wave's part, then everybody's), this one is free afterwards
-        __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        t = tn;
-    }
-
-    if (!wave_active) return;
-    const int row = p0 + l32;
-    if (row >= N) return;
-    __bf16 *orow = p.dq + q_base + (size_t)row * D;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4) {
-            bf16x4 o4;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(dqacc[db][4 * e4 + e] * p.f.scale);
-            *reinterpret_cast<bf16x4 *>(orow + 32 * db + 8 * e4 + 4 * hf) = o4;
-        }
-}
-
 // dK, dV of the sink key tiles: sum of the band part and the segments, in a fixed order.
 template <int D>
 __global__ __launch_bounds__(kThreads) void swaa_bwd_sink_sum_kernel(const BwdParams p) {
@@ -1104,17 +904,12 @@ hipError_t launch_bwd_d(const BwdParams &p, hipStream_t stream) {
     if (err != hipSuccess) return err;
     const unsigned long long bit = 1ull << (dev & 63);
     const bool first_time = !(configured.load(std::memory_order_acquire) & bit);
-    if (first_time) {
-        err = hipFuncSetAttribute(reinterpret_cast<const void *>(&swaa_bwd_dq_dma_kernel),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, dma128::kDqBytes);
-        if (err != hipSuccess) return err;
-    }
     if (D == 128)
-        hipLaunchKernelGGL(swaa_bwd_dq_dma_kernel, dim3((unsigned)(p.f.chunk * kXcds)), dim3(512), dma128::kDqBytes, stream, p);
+        err = launch_bwd_dq_pipelined_d128(p, stream);  // swaa_bwd_dq_pipelined.hip
     else
         hipLaunchKernelGGL((swaa_bwd_dq_kernel<D, kDqBlocks>), dim3((unsigned)(p.f.chunk * kXcds)), dim3(512 / kDqBlocks), 0,
                            stream, p);
-    err = hipGetLastError();
+    if (err == hipSuccess) err = hipGetLastError();
     if (err != hipSuccess) return err;
     const long long n_kt = (p.N + 127) / 128;
     const long long pairs = (long long)p.B * p.Hkv;

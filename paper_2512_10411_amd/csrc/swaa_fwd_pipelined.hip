@@ -115,24 +115,6 @@ __device__ __forceinline__ void softmax_chunk(int c, const f32x16 &s, float c2, 
     }
 }
 
-// First MFMA of a K Q^T chain.  masked: start from the 0 / -inf visibility tile
-// of the half whose first key is k0h; otherwise from zero.
-__device__ __forceinline__ void qk_chain_start(f32x16 &s, const bf16x8 kfrag, const bf16x8 q_acc, bool masked, int k0h,
-                                               int qpos, int W, int S, int hf) {
-    if (__builtin_expect(masked, 0)) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int key = k0h + 8 * (e / 4) + 4 * hf + (e % 4);
-            const bool vis = (key <= qpos) && ((key > qpos - W) || (key < S));
-            s[e] = vis ? 0.f : -INFINITY;
-        }
-        asm volatile("s_nop 1" : "+v"(s));  // two wait states between these writes and the MFMA
-        mfma_s(s, kfrag, q_acc);
-    } else {
-        mfma_s_first(s, kfrag, q_acc);
-    }
-}
-
 // Uniform byte offsets of the LDS halves one sub-step touches.
 struct HalfOffsets {
     uint32_t k, v;    // K half to multiply, V half to accumulate

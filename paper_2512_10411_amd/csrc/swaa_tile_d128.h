@@ -57,6 +57,24 @@ __device__ __forceinline__ void pin_acc(f32x16 (&o)[kDB]) {
 // be free to sink the conversion down to the MFMA that reads it).
 __device__ __forceinline__ void pin_p(bf16x8 &pf) { asm volatile("" : "+v"(pf)); }
 
+// First MFMA of a K Q^T chain.  masked: start from the 0 / -inf visibility tile
+// of the half whose first key is k0h; otherwise from zero.
+__device__ __forceinline__ void qk_chain_start(f32x16 &s, const bf16x8 kfrag, const bf16x8 q_acc, bool masked, int k0h,
+                                               int qpos, int W, int S, int hf) {
+    if (__builtin_expect(masked, 0)) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int key = k0h + 8 * (e / 4) + 4 * hf + (e % 4);
+            const bool vis = (key <= qpos) && ((key > qpos - W) || (key < S));
+            s[e] = vis ? 0.f : -INFINITY;
+        }
+        asm volatile("s_nop 1" : "+v"(s));  // two wait states between these writes and the MFMA
+        mfma_s(s, kfrag, q_acc);
+    } else {
+        mfma_s_first(s, kfrag, q_acc);
+    }
+}
+
 // ---- LDS operand reads ---------------------------------------------------------------
 __device__ __forceinline__ bf16x8 lds_read16(uint32_t addr) {
     return *(const bf16x8 __attribute__((address_space(3))) *)(uintptr_t)addr;

@@ -21,7 +21,8 @@ import pytest
 from paper_2512_10411_amd import build
 
 # source file, substring of the kernel that addresses LDS absolutely, fewest MFMAs expected
-CASES = [("swaa_fwd_pipelined.hip", "pipelined", 60), ("swaa_decode.hip", "decode_split", 16)]
+CASES = [("swaa_fwd_pipelined.hip", "pipelined", 60), ("swaa_decode.hip", "decode_split", 16),
+         ("swaa_bwd_dq_pipelined.hip", "dq_pipelined", 100)]
 
 
 def reg_set(tok):
@@ -164,8 +165,8 @@ def test_no_vector_write_within_two_instructions_of_an_mfma_that_reads_it(tmp_pa
 @pytest.mark.skipif(shutil.which("hipcc") is None and not os.path.exists("/opt/rocm/bin/hipcc"),
                     reason="hipcc not available")
 def test_backward_dma_kernels_own_all_lds(tmp_path):
-    """The two LDS-DMA backward kernels address LDS with plain byte addresses from 0 (their
-    MFMAs go through compiler builtins, so the wait-state rules above are the compiler's)."""
+    """The LDS-DMA dK/dV kernel addresses LDS with plain byte addresses from 0 (its MFMAs go
+    through compiler builtins, so the wait-state rules above are the compiler's)."""
     out = tmp_path / "b.s"
     flags = [f for f in build.HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
     cmd = [build.hipcc_path(), *flags, "--cuda-device-only", "-S", "-o", str(out), os.path.join(build.CSRC, "swaa_bwd.hip")]
@@ -176,11 +177,11 @@ def test_backward_dma_kernels_own_all_lds(tmp_path):
     assert names and len(sizes) == len(names)
     seen = set()
     for name, size in zip(names, sizes):
-        for k in ("dkv_dma", "dq_dma"):
+        for k in ("dkv_dma",):
             if k in name:
                 seen.add(k)
                 assert int(size) == 0, (name, size)
-    assert seen == {"dkv_dma", "dq_dma"}
+    assert seen == {"dkv_dma"}
     # and they do not spill (a spill would also mean scratch traffic inside the key loop)
     for name, spill in zip(names, re.findall(r"\.amdhsa_private_segment_fixed_size\s+(\d+)", text)):
         if "dma" in name:
