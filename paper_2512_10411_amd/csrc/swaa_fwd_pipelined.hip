@@ -354,6 +354,32 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     pin_p(p_b[0]);
     pin_p(p_b[1]);
 
+    // A wave needs no mask on a 32-key half when all its keys are visible to all
+    // its 32 rows: at or below the first row's diagonal, and inside the window of
+    // its last prompt row (if it has one) or all sinks.
+    const int wbound = window_bound(p0, kPRows, p.W, p.P);
+    auto half_masked = [&](int k0h) { return !((k0h + 31 <= p0) && ((k0h > wbound) || (k0h + 31 < S))); };
+
+    // (Worked out here, while the first copies travel.)
+    // Steps [ja, jb) of this wave need no mask: band tiles t with both score halves of the
+    // step (tile t half 1, tile t+1 half 0) inside every row's window and at or below the
+    // first row's diagonal.  The two loops only run if the closed form is off.
+    int ja, jb;
+    {
+        auto unmasked_step = [&](int j) {
+            if (j < n_sink_tiles || j + 1 >= J) return false;
+            const int k0 = tile_of(j) * kBk;
+            return !half_masked(k0 + 32) && !half_masked(k0 + kBk);
+        };
+        const int t_min = max(((wbound - 32) >> 6) + 1, t_band_lo);  // 64 t + 32 > wbound
+        const int t_max = min((p0 - 95) >> 6, t_hi - 1);             // 64 t + 64 + 31 <= p0
+        ja = n_sink_tiles + (t_min - t_band_lo);
+        jb = max(ja, n_sink_tiles + (t_max - t_band_lo) + 1);
+        while (ja < jb && !unmasked_step(ja)) ++ja;
+        while (jb > ja && !unmasked_step(jb - 1)) --jb;
+    }
+    const unsigned n_interior = (unsigned)(jb - ja);
+
     // this wave's Q and K(0) copies must have landed; V(0), K(1), K(2), V(1) -- those
     // of them that exist -- may still fly (two copies per tile)
     if (J >= 3)
@@ -392,12 +418,6 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
         mx = half_swap_max(mx);
         rs.mc = (mx == -INFINITY) ? 0.f : mx * c2;
     }
-
-    // A wave needs no mask on a 32-key half when all its keys are visible to all
-    // its 32 rows: at or below the first row's diagonal, and inside the window of
-    // its last prompt row (if it has one) or all sinks.
-    const int wbound = window_bound(p0, kPRows, p.W, p.P);
-    auto half_masked = [&](int k0h) { return !((k0h + 31 <= p0) && ((k0h > wbound) || (k0h + 31 < S))); };
 
     // step 0 reads V(0) and K(1): they must be there for every wave (K(2), V(1) may still fly)
     if (J >= 3)
@@ -456,24 +476,6 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
         stream_k(j + kStages, R);
         stream_v(j + kStages - 1, Rp);
     };
-    // Steps [ja, jb) of this wave need no mask: band tiles t with both score halves of the
-    // step (tile t half 1, tile t+1 half 0) inside every row's window and at or below the
-    // first row's diagonal.  The two loops only run if the closed form is off.
-    int ja, jb;
-    {
-        auto unmasked_step = [&](int j) {
-            if (j < n_sink_tiles || j + 1 >= J) return false;
-            const int k0 = tile_of(j) * kBk;
-            return !half_masked(k0 + 32) && !half_masked(k0 + kBk);
-        };
-        const int t_min = max(((wbound - 32) >> 6) + 1, t_band_lo);  // 64 t + 32 > wbound
-        const int t_max = min((p0 - 95) >> 6, t_hi - 1);             // 64 t + 64 + 31 <= p0
-        ja = n_sink_tiles + (t_min - t_band_lo);
-        jb = max(ja, n_sink_tiles + (t_max - t_band_lo) + 1);
-        while (ja < jb && !unmasked_step(ja)) ++ja;
-        while (jb > ja && !unmasked_step(jb - 1)) --jb;
-    }
-    const unsigned n_interior = (unsigned)(jb - ja);
     static_assert(kStages == 3, "the loop below walks three ring positions");
     auto ring_step = [&](auto ring_pos, int j) { step(ring_pos, (unsigned)(j - ja) >= n_interior, j); };
     for (int j = 0;;) {
