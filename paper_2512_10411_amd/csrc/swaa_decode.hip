@@ -193,7 +193,7 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
     RowState rs;
     rs.mc = -INFINITY;
     rs.l = 0.f;
-    rs.watch = 0.f;
+    rs.lb = 0.f;
 
     int stage = 0;
     for (int t = 0; t < n_mine; ++t) {
@@ -250,6 +250,11 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
     }
 
     // ---- partial result of the valid columns: O^T accumulators (row d, column l32), reference, sum ----
+    // The merge divides by the fp32 sums it combines; a partial O is the sum over the
+    // rounded P, so it is stored scaled by l / (sum of the rounded P).
+    float l_row, lb_row;
+    row_sums(rs, l_row, lb_row);
+    const float fix = lb_row > 0.f ? l_row / lb_row : 0.f;  // a column that saw no key: O = 0, l = 0
     if (col_valid) {
         float *wo = p.ws_o + ((size_t)item * p.col_stride + l32) * kD;
 #pragma unroll
@@ -257,15 +262,15 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
 #pragma unroll
             for (int e4 = 0; e4 < 4; ++e4) {
                 float4 o4;
-                o4.x = oacc[db][4 * e4 + 0];
-                o4.y = oacc[db][4 * e4 + 1];
-                o4.z = oacc[db][4 * e4 + 2];
-                o4.w = oacc[db][4 * e4 + 3];
+                o4.x = oacc[db][4 * e4 + 0] * fix;
+                o4.y = oacc[db][4 * e4 + 1] * fix;
+                o4.z = oacc[db][4 * e4 + 2] * fix;
+                o4.w = oacc[db][4 * e4 + 3] * fix;
                 *reinterpret_cast<float4 *>(wo + 32 * db + 8 * e4 + 4 * hf) = o4;
             }
         if (hf == 0) {
             p.ws_ml[(size_t)item * 64 + l32] = rs.mc;
-            p.ws_ml[(size_t)item * 64 + 32 + l32] = rs.l;
+            p.ws_ml[(size_t)item * 64 + 32 + l32] = l_row;
         }
     }
 }

@@ -51,7 +51,7 @@ constexpr int kVRing = kStages * kTileBytes;          // V ring follows the K ri
 constexpr int kStage = 2 * kStages * kTileBytes;      // per-wave staging areas follow the rings
 constexpr int kStageBytes = kPRows * kD * 2;          // 8 KiB: a wave's 32 Q rows on the way in, O rows on the way out
 constexpr int kSmemBytes = kStage + kPWaves * kStageBytes;  // 96 + 64 = 160 KiB, all of a CU's LDS
-constexpr float kSumLimit = 1.0995116e12f;  // 2^40: row sum of one half that sends it back to the max-based path
+constexpr float kSumLimit = 1.0995116e12f;  // 2^40: a row sum that sends the workgroup back to the max-based path
 #ifndef SWAA_PREFETCH
 #define SWAA_PREFETCH 3
 #endif
@@ -73,15 +73,14 @@ constexpr int kPrefetch = SWAA_PREFETCH;  // MFMAs between an LDS fragment read 
 // and the softmax chunks are the same for every half.
 //
 // The softmax does not look for the row maximum: it keeps the reference it has
-// (taken from the first half the wave sees) and only watches the row sum.
-// exp2(s*c2 - mc) cannot overflow fp32 or bf16 unless a score exceeds the
-// reference by more than 2^7 in the exp2 domain.  The largest row sum is kept on
-// the side; if it ever reaches kSumLimit the workgroup recomputes its rows with
-// the max-based routine after the loop.  Everything else is "subtract,
-// exponentiate, add, pack".
+// (taken from the first half the wave sees).  exp2(s*c2 - mc) cannot overflow
+// fp32 or bf16 unless a score exceeds the reference by more than 2^7 in the exp2
+// domain, and the terms are never negative, so the final row sum bounds every
+// term and every partial sum: if it reaches kSumLimit (or is not a number) the
+// workgroup recomputes its rows with the max-based routine after the loop.
+// Everything else is "subtract, exponentiate, add, pack".
 struct SoftmaxScratch {
     float pe[16];
-    float sum[2];
 };
 
 // first score element handled by chunk c: 16 scores over chunks 0..13
@@ -97,10 +96,7 @@ __device__ __forceinline__ void softmax_chunk(int c, const f32x16 &s, float c2, 
     if (c >= 1 && c <= 14) {
 #pragma unroll
         for (int e = chunk_first_elem(c - 1); e < chunk_first_elem(c); ++e) {
-            if (e < 2)
-                w.sum[e] = w.pe[e];
-            else
-                w.sum[e & 1] += w.pe[e];
+            st.l += w.pe[e];
             if (e & 1) {  // the pair (e-1, e) is complete: pack it
                 pf[e / 8][(e - 1) % 8] = (__bf16)w.pe[e - 1];
                 pf[e / 8][e % 8] = (__bf16)w.pe[e];
@@ -108,11 +104,38 @@ __device__ __forceinline__ void softmax_chunk(int c, const f32x16 &s, float c2, 
             }
         }
     }
-    if (c == 15) {
-        const float rs = half_swap_sum(w.sum[0] + w.sum[1]);
-        st.l += rs;
-        st.watch = fmaxf(st.watch, rs);
-    }
+}
+
+// ---- the divisor of O: column sums of the rounded P^T, on the matrix pipe -------------
+// The P V contraction weights V with the bf16 entries of P^T, so O has to be
+// divided by the sum of those (add_rounded_pair has the reason).  In this loop
+// the vector ALU has no slot to spare for that sum, the matrix pipe has: a P^T
+// fragment (B operand of the 32x32x16 MFMA: lane l holds eight keys of query
+// column l % 32) is read as the B operand of a 16x16x32 MFMA, which takes lane l
+// as column l % 16, k-group l / 16.  Against an A operand whose row 0 is ones on
+// k-groups 0 and 2 and whose row 1 is ones on k-groups 1 and 3 (zero elsewhere),
+// D[0][j] is the sum over the fragment's 16 keys of query column j and D[1][j]
+// that of column 16 + j; lanes 0..15 hold them as elements 0 and 1.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ bf16x8 rowsum_selector(int lane) {
+    // A operand: lane l holds row l % 16, k-group l / 16
+    const int m = lane & 15, kg = lane >> 4;
+    const bool on = (m == 0 && (kg & 1) == 0) || (m == 1 && (kg & 1) == 1);
+    bf16x8 a;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a[e] = on ? (__bf16)1.f : (__bf16)0.f;
+    return a;
+}
+__device__ __forceinline__ void mfma_rowsum(f32x4 &acc, const bf16x8 sel_acc, const bf16x8 pfrag) {
+    asm("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "a"(sel_acc), "v"(pfrag));
+}
+// The sums of this lane's query column, from the two accumulators of the loop.
+// (They must be settled: other MFMAs lie between the loop and this.)
+__device__ __forceinline__ float rowsum_of_column(const f32x4 (&lsum)[2], int l32) {
+    const float lo = __shfl(lsum[0][0] + lsum[1][0], l32 & 15);
+    const float hi = __shfl(lsum[0][1] + lsum[1][1], l32 & 15);
+    return l32 < 16 ? lo : hi;
 }
 
 // Uniform byte offsets of the LDS halves one sub-step touches.
@@ -136,8 +159,8 @@ __device__ __forceinline__ bf16x8 load_slot(const LaneAddr &la, const HalfOffset
 __device__ __forceinline__ void pipelined_substep(const LaneAddr &la, const HalfOffsets &ho, bf16x8 (&fpre)[kPrefetch],
                                                   const bf16x8 (&qf)[kKS], f32x16 &s_next, const f32x16 &s_cur,
                                                   bf16x8 (&p_cur)[2], const bf16x8 (&p_prev)[2], f32x16 (&o)[kDB],
-                                                  RowState &st, float c2, bool mask_next, int k0h_next, int qpos, int W,
-                                                  int S, int hf) {
+                                                  RowState &st, f32x4 (&lsum)[2], const bf16x8 &sel, float c2,
+                                                  bool mask_next, int k0h_next, int qpos, int W, int S, int hf) {
     SoftmaxScratch w;
     bf16x8 frag[16 + kPrefetch];
 #pragma unroll
@@ -153,6 +176,10 @@ __device__ __forceinline__ void pipelined_substep(const LaneAddr &la, const Half
             mfma_acc(o[(i / 2) % kDB], frag[i], p_prev[(i / 2) / kDB]);
         __builtin_amdgcn_sched_barrier(0);
         softmax_chunk(i, s_cur, c2, st, w, p_cur);
+        if (i == 15) {  // P^T of this half is complete (and two MFMAs old)
+            mfma_rowsum(lsum[0], sel, p_cur[0]);
+            mfma_rowsum(lsum[1], sel, p_cur[1]);
+        }
         __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
@@ -353,6 +380,11 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     }
     pin_p(p_b[0]);
     pin_p(p_b[1]);
+    f32x4 lsum[2];  // column sums of the rounded P^T (mfma_rowsum), one accumulator per fragment
+#pragma unroll
+    for (int e = 0; e < 4; ++e) lsum[0][e] = lsum[1][e] = 0.f;
+    bf16x8 sel = rowsum_selector(lane);
+    asm volatile("s_nop 1" : "+a"(lsum[0]), "+a"(lsum[1]), "+a"(sel));
 
     // A wave needs no mask on a 32-key half when all its keys are visible to all
     // its 32 rows: at or below the first row's diagonal, and inside the window of
@@ -405,7 +437,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     // sees none of its keys); from here on it only moves if a row sum overflows.
     RowState rs;
     rs.l = 0.f;
-    rs.watch = 0.f;
+    rs.lb = 0.f;
     {
         const int k0 = tile_of(0) * kBk;
         qk_chain_start(s_a, load_k_frag(la, 0, 0), qf[0], true, k0, qpos, W, S, hf);
@@ -461,12 +493,12 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
 
         // softmax of (j, half 0) | scores of (j, half 1) | P V of (j-1, half 1)
         const HalfOffsets h1 = {kb_cur1, vb_prev1, kb_next0, vb_cur0};
-        pipelined_substep(la, h1, fpre, qf, s_b, s_a, p_a, p_b, oacc, rs, c2, mask1, k0 + 32, qpos, W, S, hf);
+        pipelined_substep(la, h1, fpre, qf, s_b, s_a, p_a, p_b, oacc, rs, lsum, sel, c2, mask1, k0 + 32, qpos, W, S, hf);
         // softmax of (j, half 1) | scores of (j+1, half 0) | P V of (j, half 0); its last
         // fragment requests are the first ones of step j+1 (K(j+1) half 1, V(j) half 1: both
         // resident), so that they are under way while the waves meet at the barrier
         const HalfOffsets h2 = {kb_next0, vb_cur0, Rn * kTileBytes + kHalfBytes, R * kTileBytes + kHalfBytes};
-        pipelined_substep(la, h2, fpre, qf, s_a, s_b, p_b, p_a, oacc, rs, c2, mask2, k0n, qpos, W, S, hf);
+        pipelined_substep(la, h2, fpre, qf, s_a, s_b, p_b, p_a, oacc, rs, lsum, sel, c2, mask2, k0n, qpos, W, S, hf);
 
         // K(j+2), V(j+1) must have landed; K(j) and V(j-1) are free afterwards
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
@@ -494,9 +526,12 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     // one tile at a time, no pipelining ------------------------------------------
     // (workgroup-wide OR through eight flag words at the start of the K ring,
     // which nobody reads any more after the loop's last barrier)
+    // (the drain above waited for its own result, hence for the column sums issued before it)
+    float l_row = half_swap_sum(rs.l);
+    float lb_row = rowsum_of_column(lsum, l32);
     bool redo;
     {
-        const int mine = __any(rs.watch >= kSumLimit) ? 1 : 0;
+        const int mine = __any(!(l_row < kSumLimit)) ? 1 : 0;
         if (lane == 0) *(int __attribute__((address_space(3))) *)(uintptr_t)(wave * 4) = mine;
         __syncthreads();
         int any = 0;
@@ -512,6 +547,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
         pin_acc(oacc);
         rs.mc = -INFINITY;
         rs.l = 0.f;
+        rs.lb = 0.f;
         for (int j = 0; j < J; ++j) {
             __syncthreads();  // everyone is done reading the previous tile
             issue_k(j, 0);
@@ -527,13 +563,14 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
                 pv_half<true>(la, (uint32_t)(hh * kHalfBytes), p_a, oacc);
             }
         }
+        row_sums(rs, l_row, lb_row);
     }
 
-    // ---- epilogue: O / l -> bf16 through the wave's staging area, so that the stores
-    // to HBM are whole rows; lse = (mc + log2 l) * ln 2 ----------------------------------
+    // ---- epilogue: O / (sum of the rounded P) -> bf16 through the wave's staging area, so
+    // that the stores to HBM are whole rows; lse = (mc + log2 l) * ln 2 -------------------
     // (the accumulators are settled: the last P V contraction above waited for its result)
     {
-        const float inv_l = 1.f / rs.l;  // rows past the end: never stored
+        const float inv_l = 1.f / lb_row;  // rows past the end: never stored
         const int fr = ((l32 & 7) << 1) | ((l32 >> 3) & 1);
         const uint32_t o_lane = stage + (uint32_t)(l32 * 256 + (fr << 4) + 8 * hf);
 #pragma unroll
@@ -556,7 +593,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
         }
         if (hf == 0 && r0 + l32 < Nq)
             p.lse[sg.q_batch * p.lse_sb + (long long)head * p.lse_sh + sg.q_row0 + r0 + l32] =
-                (rs.mc + __builtin_amdgcn_logf(rs.l)) * 0.69314718055994530942f;
+                (rs.mc + __builtin_amdgcn_logf(l_row)) * 0.69314718055994530942f;
     }
 }
 

@@ -133,11 +133,35 @@ __device__ __forceinline__ void pv_half(const LaneAddr &la, uint32_t vboff, cons
     }
 }
 
+// Softmax state of one query column.  The column's 32 scores of a half are
+// split over the lane pair (l32, l32 + 32); each lane keeps the sums over its
+// own 16 scores, and row_sums adds the two shares when a total is needed.
 struct RowState {
-    float mc;     // softmax reference of this lane's query column, in exp2 units (m * scale * log2 e)
-    float l;      // sum of exp2(s * c2 - mc)
-    float watch;  // largest row sum any half produced (pipelined path only)
+    float mc;  // softmax reference, in exp2 units (m * scale * log2 e); the same in both lanes
+    float l;   // share of the sum of exp2(s * c2 - mc): the log-sum-exp comes from this one
+    float lb;  // share of the sum of the same terms after rounding to bf16: the divisor of O
 };
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// acc + lo + hi for two entries of P as the P V contraction sees them.  The
+// contraction weights V with the rounded entries, so O has to be divided by
+// their sum: then the weights add up to one whatever the rounding did to them,
+// and a row with a single visible key returns that key's V row exactly even
+// when its reference is not its own score.  (Dividing by the fp32 sum leaves a
+// relative error of up to 2^-9 in such a row, a whole bf16 step after the
+// final rounding.)  One dot-product instruction per pair.
+__device__ __forceinline__ float add_rounded_pair(float acc, bf16x2 pr) {
+    bf16x2 one;
+    one[0] = (__bf16)1.f;
+    one[1] = (__bf16)1.f;
+    return __builtin_amdgcn_fdot2_f32_bf16(pr, one, acc, false);
+}
+
+__device__ __forceinline__ void row_sums(const RowState &st, float &l, float &lb) {
+    l = half_swap_sum(st.l);
+    lb = half_swap_sum(st.lb);
+}
 
 // Max-based softmax of one half tile (edge tiles, first tile, and the rare
 // half whose row sums outgrow the reference): optional mask, reference update
@@ -165,15 +189,21 @@ __device__ __forceinline__ void softmax_half(f32x16 &s, int k0h, int qpos, int W
     st.mc = move ? m_new : mc_old;
     const float mc_use = (kMask && st.mc == -INFINITY) ? 0.f : st.mc;
     alpha = move ? __builtin_amdgcn_exp2f(mc_old - mc_use) : 1.f;
-    float rs = 0.f;
+    float rs = 0.f, rb = 0.f;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-        const float pe = __builtin_amdgcn_exp2f(fmaf(s[e], c2, -mc_use));
-        rs += pe;
-        pf[e / 8][e % 8] = (__bf16)pe;
+    for (int e = 0; e < 16; e += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(s[e], c2, -mc_use));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(s[e + 1], c2, -mc_use));
+        rs += p0 + p1;
+        bf16x2 pr;
+        pr[0] = (__bf16)p0;
+        pr[1] = (__bf16)p1;
+        pf[e / 8][e % 8] = pr[0];
+        pf[e / 8][e % 8 + 1] = pr[1];
+        rb = add_rounded_pair(rb, pr);
     }
-    rs = half_swap_sum(rs);
-    st.l = st.l * alpha + rs;
+    st.l = st.l * alpha + rs;  // (alpha is the same in both lanes of a column)
+    st.lb = st.lb * alpha + rb;
     // keep the packing here and two wait states away from the MFMAs that read it
     asm volatile("s_nop 1" : "+v"(pf[0]), "+v"(pf[1]));
 }

@@ -68,6 +68,27 @@ def test_full_causal_ignores_sinks_and_window_size():
     assert_parity(o1, l1, ro, rl, tag="full causal N1500")
 
 
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("scale", [None, 0.02])
+def test_window_of_one_returns_the_value_rows_bit_for_bit(D, scale):
+    # Every row sees only its own key: its softmax weight is one whatever the kernel took as
+    # the reference of the exponentials, so O is the bf16 V row itself, also where |v| > 4 and
+    # one bf16 step is wider than the acceptance bar.  (Rows of the second half of a tile get
+    # their reference from a half that is invisible to them.)
+    G, Hkv, N = 5, 2, 865
+    scale = 1 / math.sqrt(D) if scale is None else scale
+    q, k, v = make_qkv(2, G * Hkv, Hkv, N, D, seed=32249)
+    vd = to_device(v)
+    out, lse = run_gpu(q, k, v, 1, 0, scale)
+    assert torch.equal(out, vd.repeat_interleave(G, dim=1))
+    dec, lse_dec = binding.swaa_attn_fwd_ex(to_device(q)[:, :, -3:], to_device(k), vd, 1, 0, None, scale)
+    torch.cuda.synchronize()
+    assert torch.equal(dec, out[:, :, -3:])
+    ro, rl = swaa_attn_oracle(q, k, v, 1, 0, scale)
+    assert_parity(out, lse, ro, rl, tag=f"window 1, D{D}")
+    assert float((lse_dec - lse[:, :, -3:]).abs().max()) <= 1e-5
+
+
 def test_run_to_run_determinism():
     q, k, v = make_qkv(2, 10, 2, 2048 + 99, 128, seed=42)
     qd, kd, vd = to_device(q), to_device(k), to_device(v)
