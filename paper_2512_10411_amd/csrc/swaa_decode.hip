@@ -291,27 +291,42 @@ __global__ __launch_bounds__(kMergeThreads) void swaa_decode_merge_kernel(const 
     const long long pair = (long long)b * p.Hkv + kvh;
     auto item_of = [&](int s) { return (pair * p.n_splits + s) * p.n_coltiles + ct; };
 
+    // largest reference over the splits: wave maxima by lane exchange, then one LDS round
     float m = -INFINITY;
     for (int s = tid; s < p.n_splits; s += kMergeThreads) m = fmaxf(m, p.ws_ml[item_of(s) * 64 + col]);
-    red[tid] = m;
+#pragma unroll
+    for (int sh = 32; sh > 0; sh >>= 1) m = fmaxf(m, __shfl_xor(m, sh));
+    if ((tid & 63) == 0) red[tid >> 6] = m;
     __syncthreads();
-    for (int w = kMergeThreads / 2; w > 0; w >>= 1) {
-        if (tid < w) red[tid] = fmaxf(red[tid], red[tid + w]);
-        __syncthreads();
-    }
-    m = red[0];  // finite: every row sees at least its own key
+#pragma unroll
+    for (int w = 0; w < kMergeThreads / 64; ++w) m = fmaxf(m, red[w]);  // finite: every row sees at least its own key
     __syncthreads();
 
+    // Four splits per round, their loads issued together.  A split that saw no visible
+    // key has reference -inf and may not have written its O: it is loaded all the same
+    // (the workspace is there) and left out of the sums by selection, not by a branch.
     const int d = tid % kD, g = tid / kD;
+    constexpr int kGroups = kMergeThreads / kD;
     float acc = 0.f, l = 0.f;
-#pragma unroll 4
-    for (int s = g; s < p.n_splits; s += kMergeThreads / kD) {
-        const long long it = item_of(s);
-        const float mcs = p.ws_ml[it * 64 + col];
-        if (mcs == -INFINITY) continue;  // no visible key in this split (its O may not even be written)
-        const float w = __builtin_amdgcn_exp2f(mcs - m);
-        l += w * p.ws_ml[it * 64 + 32 + col];
-        acc += w * p.ws_o[(it * p.col_stride + col) * kD + d];
+    for (int s0 = g; s0 < p.n_splits; s0 += 4 * kGroups) {
+        float mcs[4], ls[4], os[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int s = s0 + u * kGroups;
+            const bool there = s < p.n_splits;
+            const long long it = item_of(there ? s : s0);
+            mcs[u] = p.ws_ml[it * 64 + col];
+            ls[u] = p.ws_ml[it * 64 + 32 + col];
+            os[u] = p.ws_o[(it * p.col_stride + col) * kD + d];
+            if (!there) mcs[u] = -INFINITY;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const bool empty = mcs[u] == -INFINITY;
+            const float w = __builtin_amdgcn_exp2f(mcs[u] - m);
+            l += empty ? 0.f : w * ls[u];
+            acc += empty ? 0.f : w * os[u];
+        }
     }
     red[tid] = acc;
     if (d == 0) lsum[g] = l;
