@@ -35,6 +35,8 @@
 
 #include "swaa_bwd.h"
 
+#include <type_traits>
+
 namespace swaa {
 namespace {
 
@@ -75,6 +77,12 @@ __device__ __forceinline__ bf16x8 col_frag(const __bf16 *tile, int rb, int st, i
 
 __device__ __forceinline__ bool visible(int i, int j, int W, int S, int P) {
     return (j <= i) && ((i >= P) || (j > i - W) || (j < S));
+}
+// The same without short-circuit evaluation, for code that must stay free of branches:
+// per-element branches in the softmax stage of the dK/dV kernels (sixteen elements, several
+// conditions each) cost more than all of the stage's arithmetic.
+__device__ __forceinline__ bool visible_in_range(int i, int j, int N, int W, int S, int P) {
+    return (i < N) & (j <= i) & ((i >= P) | (j > i - W) | (j < S));
 }
 
 // ---- delta_i = <dO_i, O_i> ---------------------------------------------------------
@@ -470,23 +478,30 @@ __global__ __launch_bounds__(kDkvThreads, 1) void swaa_bwd_dkv_kernel(const BwdP
 
             // P and dS in the accumulator layout (row 8 (e/4) + 4 hf + e%4, column = this lane's key)
             bf16x8 pf[2], dsf[2];  // [16-row step]
+            // (one uniform branch per tile, none per element: see visible_in_range)
+            auto softmax_stage = [&](auto masked) {
 #pragma unroll
-            for (int e4 = 0; e4 < 4; ++e4) {
-                const int r4 = 32 * qb + 8 * e4 + 4 * hf;
-                const float4 l4 = *reinterpret_cast<const float4 *>(&Ls[r4]);
-                const float4 d4 = *reinterpret_cast<const float4 *>(&Dls[r4]);
-                const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
-                const float dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    const int r4 = 32 * qb + 8 * e4 + 4 * hf;
+                    const float4 l4 = *reinterpret_cast<const float4 *>(&Ls[r4]);
+                    const float4 d4 = *reinterpret_cast<const float4 *>(&Dls[r4]);
+                    const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+                    const float dv4[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    const int e = 4 * e4 + x;
-                    const int row = tq * kBq + r4 + x;
-                    float pe = __builtin_amdgcn_exp2f(fmaf(sacc[e], c2, -lv[x]));
-                    if (!unmasked && !(row < N && visible(row, key, W, S, P))) pe = 0.f;
-                    pf[e / 8][e % 8] = (__bf16)pe;
-                    dsf[e / 8][e % 8] = (__bf16)(pe * (dpacc[e] - dv4[x]));
+                    for (int x = 0; x < 4; ++x) {
+                        const int e = 4 * e4 + x;
+                        const int row = tq * kBq + r4 + x;
+                        float pe = __builtin_amdgcn_exp2f(fmaf(sacc[e], c2, -lv[x]));
+                        if (decltype(masked)::value) pe = visible_in_range(row, key, N, W, S, P) ? pe : 0.f;
+                        pf[e / 8][e % 8] = (__bf16)pe;
+                        dsf[e / 8][e % 8] = (__bf16)(pe * (dpacc[e] - dv4[x]));
+                    }
                 }
-            }
+            };
+            if (unmasked)
+                softmax_stage(std::false_type{});
+            else
+                softmax_stage(std::true_type{});
 
             // dV^T += dO^T P,  dK^T += Q^T dS
 #pragma unroll
@@ -771,24 +786,31 @@ __global__ __launch_bounds__(kDkvThreads, 1) void swaa_bwd_dkv_dma_kernel(const 
 
             // P and dS in the accumulator layout (row 8 (e/4) + 4 hf + e%4, column = this lane's key)
             bf16x8 pf[2], dsf[2];  // [16-row step]
+            // (one uniform branch per tile, none per element: see visible_in_range)
+            auto softmax_stage = [&](auto masked) {
 #pragma unroll
-            for (int e4 = 0; e4 < 4; ++e4) {
-                const int r4 = 32 * qb + 8 * e4 + 4 * hf;
-                typedef float f32x4 __attribute__((ext_vector_type(4)));
-                const f32x4 l4 = *(const f32x4 __attribute__((address_space(3))) *)(uintptr_t)(kL + buf * kBq * 4 + r4 * 4);
-                const f32x4 d4 = *(const f32x4 __attribute__((address_space(3))) *)(uintptr_t)(kDl + buf * kBq * 4 + r4 * 4);
-                const float lv[4] = {l4[0], l4[1], l4[2], l4[3]};
-                const float dv4[4] = {d4[0], d4[1], d4[2], d4[3]};
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    const int r4 = 32 * qb + 8 * e4 + 4 * hf;
+                    typedef float f32x4 __attribute__((ext_vector_type(4)));
+                    const f32x4 l4 = *(const f32x4 __attribute__((address_space(3))) *)(uintptr_t)(kL + buf * kBq * 4 + r4 * 4);
+                    const f32x4 d4 = *(const f32x4 __attribute__((address_space(3))) *)(uintptr_t)(kDl + buf * kBq * 4 + r4 * 4);
+                    const float lv[4] = {l4[0], l4[1], l4[2], l4[3]};
+                    const float dv4[4] = {d4[0], d4[1], d4[2], d4[3]};
 #pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    const int e = 4 * e4 + x;
-                    const int row = tq * kBq + r4 + x;
-                    float pe = __builtin_amdgcn_exp2f(fmaf(sacc[e], c2, -lv[x]));
-                    if (!unmasked && !(row < N && visible(row, key, W, S, P))) pe = 0.f;
-                    pf[e / 8][e % 8] = (__bf16)pe;
-                    dsf[e / 8][e % 8] = (__bf16)(pe * (dpacc[e] - dv4[x]));
+                    for (int x = 0; x < 4; ++x) {
+                        const int e = 4 * e4 + x;
+                        const int row = tq * kBq + r4 + x;
+                        float pe = __builtin_amdgcn_exp2f(fmaf(sacc[e], c2, -lv[x]));
+                        if (decltype(masked)::value) pe = visible_in_range(row, key, N, W, S, P) ? pe : 0.f;
+                        pf[e / 8][e % 8] = (__bf16)pe;
+                        dsf[e / 8][e % 8] = (__bf16)(pe * (dpacc[e] - dv4[x]));
+                    }
                 }
-            }
+            };
+            if (unmasked)
+                softmax_stage(std::false_type{});
+            else
+                softmax_stage(std::true_type{});
 
             // dV^T += dO^T P,  dK^T += Q^T dS
 #pragma unroll
