@@ -29,9 +29,11 @@ HBM_PEAK_GBS = 8000.0           # MI355X HBM3E
 
 # HBM bytes per launch (read + written) of the attention kernel, measured with two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by a copy kernel of known size;
-# the summaries are profiles/swaa_fwd_pipelined_<workload>.txt.  Used when
+# the summaries are under profiles/ (swaa_fwd_pipelined_<workload>.txt, swaa_decode_<workload>.txt,
+# swaa_bwd_mid_bwd.txt; calls made of several kernels: the sum over them).  Used when
 # --traffic-bytes is not given; workloads not measured yet report null.
-MEASURED_TRAFFIC_BYTES = {"mid": 3.97e8, "batched": 1.032e9, "decode128k_full": 5.41e8, "decode16k_b16": 1.079e9}
+MEASURED_TRAFFIC_BYTES = {"mid": 3.97e8, "batched": 1.033e9, "decode128k_full": 5.41e8, "decode16k_b16": 1.079e9,
+                          "mid_bwd": 1.63e9}
 
 
 def parse():
