@@ -89,6 +89,28 @@ def test_window_of_one_returns_the_value_rows_bit_for_bit(D, scale):
     assert float((lse_dec - lse[:, :, -3:]).abs().max()) <= 1e-5
 
 
+def test_rows_dominated_by_one_key_outside_the_first_tile_with_large_values():
+    # Every key at a multiple of 97 is aligned with the queries' common component, and the
+    # window holds at most one of them: a row that sees one gives it nearly all its weight.
+    # For most such rows the key is not in the first half tile they visit, so its score differs
+    # from the softmax reference by some arbitrary amount and its P entry is an inexact bf16.
+    # Those keys' V rows are scaled so that |o| reaches 4..8, where one bf16 step (3.1e-2)
+    # exceeds the bar: dividing O by anything but the sum of the rounded P entries fails here.
+    B, Hq, Hkv, N, D, W, S = 1, 4, 2, 1500, 128, 90, 0
+    q, k, v = make_qkv(B, Hq, Hkv, N, D, seed=4711)
+    qf, kf, vf = bf16_bits_to_f32(q), bf16_bits_to_f32(k), bf16_bits_to_f32(v)
+    qf[..., :16] += 4.0
+    kf[:, :, ::97, :16] = 3.0
+    kf[:, :, ::97, 16:] = 0.0
+    vf[:, :, ::97, :] *= 1.75
+    q, k, v = f32_to_bf16_bits(qf), f32_to_bf16_bits(kf), f32_to_bf16_bits(vf)
+    scale = 1 / math.sqrt(D)
+    out, lse = run_gpu(q, k, v, W, S, scale)
+    ro, rl = swaa_attn_oracle(q, k, v, W, S, scale)
+    assert float(np.abs(ro).max()) > 4.5  # the case is what it claims to be
+    assert_parity(out, lse, ro, rl, tag="dominant far key, large values")
+
+
 def test_run_to_run_determinism():
     q, k, v = make_qkv(2, 10, 2, 2048 + 99, 128, seed=42)
     qd, kd, vd = to_device(q), to_device(k), to_device(v)
