@@ -52,6 +52,7 @@ constexpr int kStage = 2 * kStages * kTileBytes;      // per-wave staging areas 
 constexpr int kStageBytes = kPRows * kD * 2;          // 8 KiB: a wave's 32 Q rows on the way in, O rows on the way out
 constexpr int kSmemBytes = kStage + kPWaves * kStageBytes;  // 96 + 64 = 160 KiB, all of a CU's LDS
 constexpr float kSumLimit = 1.0995116e12f;  // 2^40: a row sum that sends the workgroup back to the max-based path
+constexpr float kSumFloor = 7.8886091e-31f;  // 2^-100: so does one this small (every score far below the reference)
 #ifndef SWAA_PREFETCH
 #define SWAA_PREFETCH 3
 #endif
@@ -77,7 +78,10 @@ constexpr int kPrefetch = SWAA_PREFETCH;  // MFMAs between an LDS fragment read 
 // fp32 or bf16 unless a score exceeds the reference by more than 2^7 in the exp2
 // domain, and the terms are never negative, so the final row sum bounds every
 // term and every partial sum: if it reaches kSumLimit (or is not a number) the
-// workgroup recomputes its rows with the max-based routine after the loop.
+// workgroup recomputes its rows with the max-based routine after the loop.  It
+// does the same if a row sum comes out below kSumFloor: a row whose first half
+// was invisible to it has reference 0, and if all its scores lie a hundred
+// binary orders below that, its terms leave the range fp32 resolves.
 // Everything else is "subtract, exponentiate, add, pack".
 struct SoftmaxScratch {
     float pe[16];
@@ -531,7 +535,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     float lb_row = rowsum_of_column(lsum, l32);
     bool redo;
     {
-        const int mine = __any(!(l_row < kSumLimit)) ? 1 : 0;
+        const int mine = __any(!(l_row < kSumLimit) || !(l_row > kSumFloor)) ? 1 : 0;
         if (lane == 0) *(int __attribute__((address_space(3))) *)(uintptr_t)(wave * 4) = mine;
         __syncthreads();
         int any = 0;

@@ -13,7 +13,7 @@ from oracle import swaa_attn_oracle
 from paper_2512_10411_amd import binding
 from paper_2512_10411_amd.inputs import (WORKLOADS, bf16_bits_to_f32, f32_to_bf16_bits, make_qkv,
                                          make_workload, sample_rows)
-from gpu_util import assert_parity, to_device
+from gpu_util import assert_parity, errors as errors_of, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -154,6 +154,30 @@ def test_late_score_spike_far_above_the_first_keys(spike):
     out, lse = run_gpu(q, k, v, W, S, scale)
     ro, rl = swaa_attn_oracle(q, k, v, W, S, scale)
     assert_parity(out, lse, ro, rl, tag=f"late spike {spike}")
+
+
+@pytest.mark.parametrize("level", [-40.0, -200.0, -3000.0])
+def test_all_scores_far_below_zero(level):
+    # q and k anti-aligned along one component: every scaled score is about `level` nats.  Rows
+    # whose first visited half tile is invisible to them start from reference 0; their
+    # exponentials underflow (to nothing at all for the lower levels) and the kernel has to
+    # notice and fall back to the maximum-based routine.  MHA, so that a workgroup holds 256
+    # consecutive rows and most of its waves are such rows.
+    B, H, N, D, W, S = 1, 2, 900, 128, 70, 0
+    scale = 1 / math.sqrt(D)
+    q, k, v = make_qkv(B, H, H, N, D, seed=808)
+    qf, kf = bf16_bits_to_f32(q), bf16_bits_to_f32(k)
+    a = math.sqrt(-level / scale)
+    qf[..., 0] = a
+    kf[..., 0] = -a
+    q, k = f32_to_bf16_bits(qf), f32_to_bf16_bits(kf)
+    out, lse = run_gpu(q, k, v, W, S, scale)
+    ro, rl = swaa_attn_oracle(q, k, v, W, S, scale)
+    assert float(rl.max()) < 0.5 * level
+    mx, mean, _ = errors_of(out, lse, ro, rl)
+    assert mx <= 2e-2 and mean <= 2e-3
+    # the log-sum-exp is about `level` in size: fp32 resolves it to 2^-24 relative
+    assert float(np.abs(lse.cpu().numpy().astype(np.float64) - rl).max()) <= 1e-3 + 2.0 ** -22 * abs(level)
 
 
 def test_caller_buffers_stream_and_errors():
