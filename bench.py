@@ -6,11 +6,15 @@
 One "step" is one call of swaa_attn_fwd (the whole hot path: tile schedule,
 Q/K/V staging, QK^T, mask, online softmax, PV, epilogue) over one batch of
 seeded synthetic bf16 inputs that are already resident in HBM.  The default
-workload is the mid-size prefill layer the metric is quoted on (B=1, Hq=32,
-Hkv=8, N=16384, D=128, W=2048, S=4).  Prints ONE JSON line: effective TFLOP/s
-(4*D flops per visible query-key pair per head), the MFMA roofline fraction of
-the kernel measured with HIP events on the launch stream, and the fp64 CPU
-oracle timed on this machine's host cores on a bounded sample of the same rows.
+workload is the largest configuration of the benchmark definition, the 128k-token
+prompt with an 8k window (long128k_swa: B=1, Hq=32, Hkv=8, N=131072, D=128,
+W=8192, S=4; the prompt length of the paper's efficiency experiment, Sec. 4.2.2 /
+App. D).  Prints ONE JSON line: effective TFLOP/s (4*D flops per visible
+query-key pair per head), the MFMA roofline fraction of the kernel measured with
+HIP events on the launch stream, for window < N also the same tensors timed with
+window = N (linear_in_w: time ratio against visible-pair ratio, App. A: O(N W)),
+and the fp64 CPU oracle timed on this machine's host cores on a bounded sample of
+the same rows.
 """
 from __future__ import annotations
 
@@ -28,22 +32,31 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E
 
 # HBM bytes per launch (read + written) of the attention kernel, measured with two
-# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by a copy kernel of known size;
-# the summaries are under profiles/ (swaa_fwd_pipelined_<workload>.txt, swaa_decode_<workload>.txt,
-# swaa_bwd_mid_bwd.txt; calls made of several kernels: the sum over them).  Used when
-# --traffic-bytes is not given; workloads not measured yet report null.
-MEASURED_TRAFFIC_BYTES = {"mid": 3.97e8, "batched": 1.033e9, "decode128k_full": 5.41e8, "decode16k_b16": 1.079e9,
-                          "mid_bwd": 1.63e9}
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by a copy kernel of known size, and
+# the summary under profiles/ each figure is taken from (calls made of several kernels: the
+# sum over them).  roofline.traffic is NOT a reading of this run: traffic_source names the
+# file (or "--traffic-bytes"); workloads without a summary report null.
+MEASURED_TRAFFIC_BYTES = {
+    "mid": (3.97e8, "profiles/swaa_fwd_pipelined_mid.txt"),
+    "batched": (1.033e9, "profiles/swaa_fwd_pipelined_batched.txt"),
+    "decode128k_full": (5.41e8, "profiles/swaa_decode_decode128k_full.txt"),
+    "decode16k_b16": (1.079e9, "profiles/swaa_decode_decode16k_b16.txt"),
+    "mid_bwd": (1.63e9, "profiles/swaa_bwd_mid_bwd.txt"),
+}
+MIN_WARMUP_S = 0.05  # the clocks settle only after some tens of ms of continuous work
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     # The GPU's clocks take some tens of milliseconds of continuous work to settle after the
-    # host-side input generation; 100 untimed launches cover that for every workload here.
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=100)
-    ap.add_argument("--workload", default="mid")
+    # host-side input generation: whatever --warmup says, untimed launches go on until
+    # MIN_WARMUP_S have passed (the JSON line reports how many ran).
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="long128k_swa")
+    ap.add_argument("--no-linear-in-w", action="store_true",
+                    help="skip the window = N launches on the same tensors (profiling runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true",
                     help="skip the oracle timing (profiling runs)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
@@ -215,8 +228,13 @@ def main():
             binding.swaa_attn_fwd_fa_decode(qd, kd, vd, w.window, w.n_sink, n_prompt, w.scale, out=out, lse=lse,
                                             stream=stream)
 
-    for _ in range(args.warmup):
+    warmup_done = 0
+    t_w = time.perf_counter()
+    while warmup_done < args.warmup or time.perf_counter() - t_w < MIN_WARMUP_S:
         step()
+        warmup_done += 1
+        if warmup_done >= args.warmup:
+            torch.cuda.synchronize()  # (only while topping up to the minimum time)
     torch.cuda.synchronize()
     if args.copy_probe_mib > 0:
         src = torch.ones(args.copy_probe_mib << 20, dtype=torch.uint8, device="cuda")
@@ -252,18 +270,54 @@ def main():
     flops = (10.0 if w.backward else 4.0) * w.D * pairs
     value = flops / (ms_per_step * 1e-3) / 1e12
     achieved = flops / (kern_avg_ms * 1e-3) / 1e12
-    traffic = args.traffic_bytes if args.traffic_bytes is not None else MEASURED_TRAFFIC_BYTES.get(w.name)
+    if args.traffic_bytes is not None:
+        traffic, traffic_source = args.traffic_bytes, "--traffic-bytes"
+    else:
+        traffic, traffic_source = MEASURED_TRAFFIC_BYTES.get(w.name, (None, None))
+
+    # The same tensors with window = N (the full-attention layer next to this SWA layer):
+    # the time ratio should follow the visible-pair ratio if the work is linear in N * W.
+    linear_in_w = None
+    plain_prefill = not (decode or w.chunk or w.backward or w.fmt == "fp16") and w.n_prompt is None
+    if plain_prefill and w.window < w.N and not args.no_linear_in_w:
+        def full_step():
+            binding.swaa_attn_fwd(qd, kd, vd, w.N, w.n_sink, w.scale, out=out, lse=lse, stream=stream)
+        full_step()
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        full_step()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        t_one = e0.elapsed_time(e1)
+        n_full = max(2, min(args.steps, int(300.0 / max(t_one, 1e-3))))  # about 0.3 s of launches
+        e0.record(stream)
+        for _ in range(n_full):
+            full_step()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        t_full_ms = e0.elapsed_time(e1) / n_full
+        pairs_full = binding.swaa_visible_pairs(w.N, w.N, w.n_sink) * w.B * w.Hq
+        linear_in_w = {"t_swa_ms": kern_avg_ms, "t_full_ms": t_full_ms, "time_ratio": kern_avg_ms / t_full_ms,
+                       "pair_ratio": pairs / pairs_full, "full_steps": n_full,
+                       "full_tflops": 4.0 * w.D * pairs_full / (t_full_ms * 1e-3) / 1e12,
+                       "full_frac": 4.0 * w.D * pairs_full / (t_full_ms * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS}
+        # leave the SWA result in out / lse (nothing below reads them, but a reader of this file might)
+        step()
+        torch.cuda.synchronize()
     if decode:
         # few query rows against a long cache: the keys and values are read once and nothing is
         # reused, so HBM bandwidth bounds the call (split kernel + merge kernel, timed together)
         gbs = algo_bytes / (kern_avg_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
-                    "traffic": traffic, "kernel": "swaa_decode_split_kernel (+ swaa_decode_merge_kernel)",
+                    "traffic": traffic, "traffic_source": traffic_source,
+                    "kernel": "swaa_decode_split_kernel (+ swaa_decode_merge_kernel)",
                     "kernel_avg_ms": kern_avg_ms, "algorithmic_bytes": algo_bytes}
     else:
         # (the fp16 matrix peak equals the bf16 one)
         roofline = {"bound": "mfma", "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": traffic,
+                    "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": traffic, "traffic_source": traffic_source,
                     "kernel": (("swaa_bwd_dkv_dma_kernel + swaa_bwd_dq_pipelined_kernel + swaa_bwd_delta_kernel" if w.D == 128 else
                                 f"swaa_bwd_dkv_kernel<{w.D}> + swaa_bwd_dq_kernel<{w.D}> + swaa_bwd_delta_kernel") if w.backward
                                else "swaa_fwd_pipelined_kernel" if w.D == 128 and w.fmt == "bf16"
@@ -277,6 +331,7 @@ def main():
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "warmup_launches": warmup_done,
         "ms_per_step": ms_per_step,
         "higher_is_better": True,
         "scaling": "weak",
@@ -290,6 +345,8 @@ def main():
                    "pct_bf16_mfma_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS},
         "roofline": roofline,
     }
+    if linear_in_w is not None:
+        res["linear_in_w"] = linear_in_w
     if not args.no_cpu_baseline:
         from oracle import input_format
         with input_format(w.fmt):

@@ -2,7 +2,8 @@
 
 Every step of the attention forward runs inside the HIP kernels; torch is
 used for device memory and the stream handle.  There is no fallback: if the
-library is not built and cannot be built, importing callers get an error.
+library has not been built (python -m paper_2512_10411_amd.build), the first
+call raises.
 """
 from __future__ import annotations
 
@@ -11,8 +12,7 @@ import math
 import os
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-# SWAA_LIB selects another build of the same library (A/B timing of kernel variants)
-LIB_PATH = os.environ.get("SWAA_LIB") or os.path.join(_PKG, "libswaa.so")
+LIB_PATH = os.path.join(_PKG, "libswaa.so")
 
 SWAA_OK = 0
 SWAA_ERR_NULL = -1
@@ -69,13 +69,13 @@ class SwaaError(RuntimeError):
 
 
 def load_library() -> ctypes.CDLL:
-    """Load libswaa.so, building it first only if no built library exists."""
+    """Load libswaa.so.  A missing library is an error: nothing is built or substituted here."""
     global _lib
     if _lib is not None:
         return _lib
     if not os.path.exists(LIB_PATH):
-        from .build import build_library
-        build_library()
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2512_10411_amd.build` "
+                           "(there is no CPU or PyTorch fallback for the attention kernels)")
     lib = ctypes.CDLL(LIB_PATH)
     lib.swaa_attn_fwd.restype = ctypes.c_int
     lib.swaa_attn_fwd.argtypes = [

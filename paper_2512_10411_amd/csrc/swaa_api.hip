@@ -1,9 +1,7 @@
 // C ABI of libswaa: argument checks, work decomposition, kernel choice.
 #include <cmath>
 #include <cstdint>
-#include <cstdlib>
 #include <cstring>
-#include <string>
 
 #include "swaa.h"
 #include "swaa_common.h"
@@ -23,16 +21,6 @@ bool positive_finite(float x) {
 }
 
 bool misaligned(const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) != 0; }
-
-// SWAA_KERNEL=simple selects the plain (unpipelined) kernel for head dimension
-// 128 too; meant for debugging and A/B timing.  Read once.
-bool use_simple_kernel() {
-    static const bool simple = [] {
-        const char *e = std::getenv("SWAA_KERNEL");
-        return e && std::string(e) == "simple";
-    }();
-    return simple;
-}
 
 }  // namespace
 
@@ -141,7 +129,7 @@ int swaa_attn_fwd_ex(const swaa_fwd_args *a) {
     hipStream_t s = static_cast<hipStream_t>(a->stream);
     // the pipelined kernel is bfloat16 only: its softmax keeps a fixed reference and leans on
     // bfloat16's fp32-sized exponent; binary16 runs on the plain kernel, whose probabilities are <= 1
-    const hipError_t err = (D == 128 && !p.fp16 && !use_simple_kernel()) ? swaa::launch_fwd_pipelined_d128(p, s)
+    const hipError_t err = (D == 128 && !p.fp16) ? swaa::launch_fwd_pipelined_d128(p, s)
                                                                           : swaa::launch_fwd_simple(p, D, s);
     return err == hipSuccess ? SWAA_OK : SWAA_ERR_LAUNCH;
 }

@@ -41,10 +41,7 @@ namespace swaa {
 namespace {
 
 constexpr int kBq = 64;  // query rows per tile of the dK/dV kernel
-#ifndef SWAA_DQ_BLOCKS
-#define SWAA_DQ_BLOCKS 1
-#endif
-constexpr int kDqBlocks = SWAA_DQ_BLOCKS;  // 32-row blocks per wave of the dQ kernel
+constexpr int kDqBlocks = 1;  // 32-row blocks per wave of the dQ kernel
 
 template <int D>
 struct BTile {

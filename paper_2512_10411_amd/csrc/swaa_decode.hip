@@ -44,10 +44,7 @@ constexpr int kDStageBytes = 2 * kHalfBytes;          // K half, then V half
 constexpr int kDSmemBytes = kDStages * kDStageBytes;  // 48 KiB
 constexpr int kCopiesPerHalf = 16;                    // wave instructions per stage: 8 for K, 8 for V
 constexpr int kMergeThreads = 1024;
-#ifndef SWAA_DECODE_ROUNDS
-#define SWAA_DECODE_ROUNDS 1
-#endif
-constexpr int kRounds = SWAA_DECODE_ROUNDS;
+constexpr int kRounds = 1;  // rounds of resident workgroups the split plan aims for
 
 __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParams p) {
     // XCD x takes the x-th contiguous chunk of the item list (column tiles of one

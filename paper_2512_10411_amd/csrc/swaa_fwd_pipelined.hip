@@ -53,10 +53,7 @@ constexpr int kStageBytes = kPRows * kD * 2;          // 8 KiB: a wave's 32 Q ro
 constexpr int kSmemBytes = kStage + kPWaves * kStageBytes;  // 96 + 64 = 160 KiB, all of a CU's LDS
 constexpr float kSumLimit = 1.0995116e12f;  // 2^40: a row sum that sends the workgroup back to the max-based path
 constexpr float kSumFloor = 7.8886091e-31f;  // 2^-100: so does one this small (every score far below the reference)
-#ifndef SWAA_PREFETCH
-#define SWAA_PREFETCH 3
-#endif
-constexpr int kPrefetch = SWAA_PREFETCH;  // MFMAs between an LDS fragment read and its use
+constexpr int kPrefetch = 3;  // MFMAs between an LDS fragment read and its use
 
 // ---- the pipelined sub-step, scheduled by hand -------------------------------------
 // A sub-step issues 16 MFMAs, alternating S^T(n+1) += K Q^T (8, one chain) and
@@ -535,7 +532,13 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     float lb_row = rowsum_of_column(lsum, l32);
     bool redo;
     {
-        const int mine = __any(!(l_row < kSumLimit) || !(l_row > kSumFloor)) ? 1 : 0;
+        // a sum inside (kSumFloor, kSumLimit), tested on the bit pattern: positive floats order like
+        // unsigned integers, and zero, infinity and every NaN pattern fall outside the interval
+        // (the build does not honour NaNs in float comparisons).  Rows past the end of the
+        // sequence (the ragged last tile; they may see no key at all) have no say.
+        const bool in_range = (__float_as_uint(l_row) - (__float_as_uint(kSumFloor) + 1u)) <
+                              (__float_as_uint(kSumLimit) - (__float_as_uint(kSumFloor) + 1u));
+        const int mine = __any(!in_range && r0 + l32 < Nq) ? 1 : 0;
         if (lane == 0) *(int __attribute__((address_space(3))) *)(uintptr_t)(wave * 4) = mine;
         __syncthreads();
         int any = 0;

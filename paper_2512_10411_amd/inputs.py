@@ -5,7 +5,7 @@ piece that the tests, the benchmark, the GPU binding's callers and the CPU
 oracle's callers share.  Values stand in for the long-context workloads the
 paper evaluates on (16k-32k-token prompts, 128k-token prompts, windows of
 2k/4k/8k or full attention: Sec. 4.1.2, Table 1, Table 5); the paper's own
-efficiency runs use random inputs too (Sec. 4.3).
+efficiency experiment uses random inputs too (Sec. 4.2.2; its table is in App. D).
 
 Tensors are returned as numpy uint16 arrays holding bf16 bit patterns in
 [B, H, N, D] layout, drawn in the order q, k, v from a Philox stream.
@@ -52,6 +52,7 @@ class Workload:
     chunk: bool = False          # n_query rows are a chunk of a longer prefill (general forward), not a decode step
     backward: bool = False       # the timed call is the backward pass (the forward runs once, untimed)
     fmt: str = "bf16"            # element format of q, k, v, out: "bf16" or "fp16"
+    recipe: str = "iid"          # "iid", or a structured score pattern laid over the draws (apply_recipe)
 
     @property
     def scale(self) -> float:
@@ -90,7 +91,39 @@ WORKLOADS = {
     # the last 2048-row chunk of a 128k-token prefill whose earlier keys and values are cached
     "chunk2k_128k_swa": Workload("chunk2k_128k_swa", 1, 32, 8, 131072, 128, 8192, 4, _SEED0 + 8, n_query=2048,
                                  chunk=True),
+    # the mid-size layer with the paper's larger keep-first values (Table 1: k = 100, 1000; the
+    # efficiency table of App. D has time to first token about 2 % higher at k = 100)
+    "mid_s100": Workload("mid_s100", 1, 32, 8, 16384, 128, 2048, 100, _SEED0 + 2),
+    "mid_s1000": Workload("mid_s1000", 1, 32, 8, 16384, 128, 2048, 1000, _SEED0 + 2),
+    # the mid-size layer with attention-sink scores (Sec. 3.2.1): every query scores the first
+    # tokens about 13 nats above the rest
+    "mid_sinkheavy": Workload("mid_sinkheavy", 1, 32, 8, 16384, 128, 2048, 4, _SEED0 + 2, recipe="sink_heavy"),
+    # and with isolated keys, one per 2048 positions deep inside the windows, that score about 42
+    # nats above everything else: scores that outgrow a softmax reference taken from the first keys
+    "mid_spike": Workload("mid_spike", 1, 32, 8, 16384, 128, 2048, 4, _SEED0 + 2, recipe="late_spike"),
 }
+
+
+def apply_recipe(w: Workload, q: np.ndarray, k: np.ndarray):
+    """Lay a structured score pattern over i.i.d. draws, in place (bit patterns of w.fmt).
+
+    Component 0 of every query becomes 3 and that of every key 0, so that a key whose
+    component 0 is set to c scores 3 c / sqrt(D) nats above the rest for every query.
+      sink_heavy: the first n_sink keys get c = 48 (about 12.7 nats at D = 128);
+      late_spike: keys 1500, 3548, 5596, ... (one per 2048 positions) get c = 160 (42 nats).
+    """
+    if w.recipe == "iid":
+        return
+    to_bits = f32_to_bf16_bits if w.fmt == "bf16" else f32_to_f16_bits
+    bits = lambda x: to_bits(np.array([x], dtype=np.float32))[0]
+    q[..., 0] = bits(3.0)
+    k[..., 0] = bits(0.0)
+    if w.recipe == "sink_heavy":
+        k[:, :, :w.n_sink, 0] = bits(48.0)
+    elif w.recipe == "late_spike":
+        k[:, :, 1500::2048, 0] = bits(160.0)
+    else:
+        raise ValueError(f"unknown recipe {w.recipe}")
 
 
 def f32_to_f16_bits(x: np.ndarray) -> np.ndarray:
@@ -131,7 +164,9 @@ def make_qkv(B, Hq, Hkv, N, D, seed, k_mult=1.0, chunk_rows=1 << 22, n_query=Non
 
 def make_workload(w: Workload):
     """q, k, v (uint16 bf16 bits) for a named workload."""
-    return make_qkv(w.B, w.Hq, w.Hkv, w.N, w.D, w.seed, w.k_mult, n_query=w.n_query, fmt=w.fmt)
+    q, k, v = make_qkv(w.B, w.Hq, w.Hkv, w.N, w.D, w.seed, w.k_mult, n_query=w.n_query, fmt=w.fmt)
+    apply_recipe(w, q, k)
+    return q, k, v
 
 
 def sample_rows(N, window, n_sink, count=256, seed=0, tile=64):
