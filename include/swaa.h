@@ -245,6 +245,31 @@ int swaa_attn_decode_ex(const swaa_decode_args *args);
 long long swaa_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Nq, int Nk, int D, int window, int n_sink);
 
 /*
+ * swaa_attn_decode for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, results and kernels as swaa_attn_decode,
+ * except that the partial results of the key splits go to a static device array
+ * of SWAA_DECODE_STATIC_SCRATCH_BYTES inside the library instead of a workspace.
+ * The call allocates and frees nothing; the array's device address is looked up
+ * on the first call on each GPU (each GPU the library runs on holds its own copy
+ * until the process ends).
+ *
+ *   - a shape whose swaa_attn_decode_workspace_bytes exceeds
+ *     SWAA_DECODE_STATIC_SCRATCH_BYTES is refused with SWAA_ERR_WORKSPACE before
+ *     anything is launched (use swaa_attn_decode with a workspace for those);
+ *   - every call on a GPU shares that GPU's array: calls that may overlap on one
+ *     GPU (two streams, two host threads) race on it and must be serialised by
+ *     the caller; consecutive calls on one stream are fine.  The array keeps the
+ *     last call's contents, and nothing in it has to be cleared between calls:
+ *     every slot the merge kernel takes into account is written first by the same
+ *     call's split kernel.
+ */
+#define SWAA_DECODE_STATIC_SCRATCH_BYTES (16LL << 20)
+int swaa_attn_decode_static(const void *q, const void *k, const void *v, void *out, float *lse,
+                            int B, int Hq, int Hkv, int Nq, int Nk, int D, int window, int n_sink,
+                            float scale, void *stream);
+
+/*
  * Backward pass of swaa_attn_fwd_fa_decode (and, with n_prompt >= N, of
  * swaa_attn_fwd): the gradients that fine-tuning under the sliding-window mask
  * (paper Sec. 3.2.2, with the structural masks of Sec. 3.1.1 and Sec. 3.2.1

@@ -27,7 +27,7 @@ SWAA_F16 = 1
 # every symbol include/swaa.h declares
 EXPORTS = ("swaa_attn_fwd", "swaa_attn_fwd_fa_decode", "swaa_attn_fwd_ex", "swaa_visible_pairs",
            "swaa_visible_pairs_fa_decode",
-           "swaa_attn_decode", "swaa_attn_decode_ex", "swaa_attn_decode_workspace_bytes", "swaa_attn_bwd", "swaa_attn_bwd_workspace_bytes",
+           "swaa_attn_decode", "swaa_attn_decode_ex", "swaa_attn_decode_workspace_bytes", "swaa_attn_decode_static", "swaa_attn_bwd", "swaa_attn_bwd_workspace_bytes",
            "swaa_status_string", "swaa_version")
 
 _lib = None
@@ -98,6 +98,8 @@ def load_library() -> ctypes.CDLL:
         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
         ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
         ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_void_p, ctypes.c_longlong, ctypes.c_void_p]
+    lib.swaa_attn_decode_static.restype = ctypes.c_int
+    lib.swaa_attn_decode_static.argtypes = lib.swaa_attn_decode.argtypes[:14] + [ctypes.c_void_p]
     lib.swaa_attn_decode_ex.restype = ctypes.c_int
     lib.swaa_attn_decode_ex.argtypes = [ctypes.POINTER(SwaaDecodeArgs)]
     lib.swaa_attn_decode_workspace_bytes.restype = ctypes.c_longlong
@@ -274,6 +276,38 @@ def swaa_attn_decode(q, k, v, window: int, n_sink: int, scale: float | None = No
         rc = swaa_attn_decode_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
                                   B, Hq, Hkv, Nq, Nk, D, int(window), int(n_sink), float(scale),
                                   workspace.data_ptr(), workspace.numel(), sptr)
+    if rc != SWAA_OK:
+        raise SwaaError(rc, swaa_status_string(rc))
+    return out, lse
+
+
+SWAA_DECODE_STATIC_SCRATCH_BYTES = 16 << 20  # include/swaa.h
+
+
+def swaa_attn_decode_static_raw(q_ptr, k_ptr, v_ptr, out_ptr, lse_ptr, B, Hq, Hkv, Nq, Nk, D,
+                                window, n_sink, scale, stream_ptr) -> int:
+    """The C call itself, on raw addresses; returns the status code.  Allocates nothing."""
+    return int(load_library().swaa_attn_decode_static(
+        q_ptr, k_ptr, v_ptr, out_ptr, lse_ptr, B, Hq, Hkv, Nq, Nk, D, window, n_sink, scale, stream_ptr))
+
+
+def swaa_attn_decode_static(q, k, v, out, lse, window: int, n_sink: int, scale: float | None = None, stream=None):
+    """swaa_attn_decode on the library's own static scratch array: nothing is allocated,
+    here or in the library, so `out` (bf16 [B, Hq, Nq, D]) and `lse` (fp32 [B, Hq, Nq]) are
+    the caller's.  Calls that may overlap on one GPU must be serialised by the caller."""
+    B, Hq, Nq, D = q.shape
+    Hkv, Nk = k.shape[1], k.shape[2]
+    if scale is None:
+        scale = 1.0 / math.sqrt(D)
+    for name, t in (("q", q), ("k", k), ("v", v), ("out", out), ("lse", lse)):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous GPU tensor")
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream(q.device)
+    sptr = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+    rc = swaa_attn_decode_static_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), lse.data_ptr(),
+                                     B, Hq, Hkv, Nq, Nk, D, int(window), int(n_sink), float(scale), sptr)
     if rc != SWAA_OK:
         raise SwaaError(rc, swaa_status_string(rc))
     return out, lse

@@ -53,7 +53,7 @@ const char *swaa_status_string(int status) {
         case SWAA_ERR_UNSUPPORTED: return "unsupported head dimension (64 and 128 are built)";
         case SWAA_ERR_ALIGN: return "pointer not 16-byte aligned";
         case SWAA_ERR_LAUNCH: return "HIP launch failed";
-        case SWAA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case SWAA_ERR_WORKSPACE: return "workspace missing, misaligned or too small (or the call needs more scratch than the static array holds)";
         default: return "unknown status";
     }
 }
@@ -195,7 +195,11 @@ long long swaa_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Nq, int N
     return swaa::decode_workspace_floats(p) * (long long)sizeof(float);
 }
 
-int swaa_attn_decode_ex(const swaa_decode_args *a) {
+namespace {
+
+// Both decode entry points.  own_scratch: the partial results go to the library's static
+// device array instead of the caller's workspace (whose two fields are then ignored).
+int decode_call(const swaa_decode_args *a, bool own_scratch) {
     if (!a) return SWAA_ERR_NULL;
     if (!a->q || !a->k.ptr || !a->v.ptr || !a->out || !a->lse) return SWAA_ERR_NULL;
     swaa::DecodeParams p{};
@@ -216,7 +220,13 @@ int swaa_attn_decode_ex(const swaa_decode_args *a) {
     if ((reinterpret_cast<uintptr_t>(a->lse) & 3u) != 0) return SWAA_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(a->seq_lens) | reinterpret_cast<uintptr_t>(a->block_table)) & 3u) return SWAA_ERR_ALIGN;
     const long long need = swaa::decode_workspace_floats(p) * (long long)sizeof(float);
-    if (!a->workspace || misaligned(a->workspace) || a->workspace_bytes < need) return SWAA_ERR_WORKSPACE;
+    void *workspace = a->workspace;
+    if (own_scratch) {
+        if (need > swaa::kDecodeStaticScratchBytes) return SWAA_ERR_WORKSPACE;
+        if (swaa::decode_static_scratch(&workspace) != hipSuccess) return SWAA_ERR_LAUNCH;
+    } else if (!workspace || misaligned(workspace) || a->workspace_bytes < need) {
+        return SWAA_ERR_WORKSPACE;
+    }
 
     p.q = static_cast<const __bf16 *>(a->q);
     p.k = static_cast<const __bf16 *>(a->k.ptr);
@@ -230,30 +240,54 @@ int swaa_attn_decode_ex(const swaa_decode_args *a) {
     p.page_size = paged ? a->page_size : 1;
     p.num_pages = paged ? a->num_pages : 1;
     p.seq_lens = a->seq_lens;
-    p.ws_o = static_cast<float *>(a->workspace);
+    p.ws_o = static_cast<float *>(workspace);
     p.ws_ml = p.ws_o + p.items * (long long)p.col_stride * 128;
     p.scale_log2 = a->scale * 1.44269504088896340736f;
     const hipError_t err = swaa::launch_decode(p, static_cast<hipStream_t>(a->stream));
     return err == hipSuccess ? SWAA_OK : SWAA_ERR_LAUNCH;
 }
 
-int swaa_attn_decode(const void *q, const void *k, const void *v, void *out, float *lse,
-                     int B, int Hq, int Hkv, int Nq, int Nk, int D, int window, int n_sink,
-                     float scale, void *workspace, long long workspace_bytes, void *stream) {
-    if (!q || !k || !v || !out || !lse) return SWAA_ERR_NULL;
+// The argument block of a contiguous [B, Hkv, Nk, D] cache, every sequence Nk tokens long.
+swaa_decode_args contiguous_decode_args(const void *q, const void *k, const void *v, void *out, float *lse, int B,
+                                        int Hq, int Hkv, int Nq, int Nk, int D, int window, int n_sink, float scale,
+                                        void *stream) {
     swaa_decode_args a{};
     a.q = q;
     a.out = out;
     a.lse = lse;
-    // a contiguous [B, Hkv, Nk, D] cache, every sequence Nk tokens long
     const long long nd = (long long)(Nk > 0 ? Nk : 0) * (D > 0 ? D : 0);
     a.k = {const_cast<void *>(k), (long long)(Hkv > 0 ? Hkv : 0) * nd, nd, D};
     a.v = {const_cast<void *>(v), (long long)(Hkv > 0 ? Hkv : 0) * nd, nd, D};
     a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.Nq = Nq; a.Nk = Nk; a.D = D;
     a.window = window; a.n_sink = n_sink; a.scale = scale;
-    a.workspace = workspace; a.workspace_bytes = workspace_bytes; a.stream = stream;
-    return swaa_attn_decode_ex(&a);
+    a.stream = stream;
+    return a;
 }
+
+}  // namespace
+
+int swaa_attn_decode_ex(const swaa_decode_args *a) { return decode_call(a, false); }
+
+int swaa_attn_decode(const void *q, const void *k, const void *v, void *out, float *lse,
+                     int B, int Hq, int Hkv, int Nq, int Nk, int D, int window, int n_sink,
+                     float scale, void *workspace, long long workspace_bytes, void *stream) {
+    if (!q || !k || !v || !out || !lse) return SWAA_ERR_NULL;
+    swaa_decode_args a = contiguous_decode_args(q, k, v, out, lse, B, Hq, Hkv, Nq, Nk, D, window, n_sink, scale, stream);
+    a.workspace = workspace;
+    a.workspace_bytes = workspace_bytes;
+    return decode_call(&a, false);
+}
+
+int swaa_attn_decode_static(const void *q, const void *k, const void *v, void *out, float *lse,
+                            int B, int Hq, int Hkv, int Nq, int Nk, int D, int window, int n_sink,
+                            float scale, void *stream) {
+    if (!q || !k || !v || !out || !lse) return SWAA_ERR_NULL;
+    const swaa_decode_args a =
+        contiguous_decode_args(q, k, v, out, lse, B, Hq, Hkv, Nq, Nk, D, window, n_sink, scale, stream);
+    return decode_call(&a, true);
+}
+
+static_assert(SWAA_DECODE_STATIC_SCRATCH_BYTES == swaa::kDecodeStaticScratchBytes, "the header states the array's size");
 
 namespace {
 

@@ -64,6 +64,11 @@ long long decode_workspace_floats(const DecodeParams &p);
 
 hipError_t launch_decode(const DecodeParams &p, hipStream_t stream);
 
+// Size of the library's own scratch array (one per GPU) behind swaa_attn_decode_static,
+// and its device address on the current device (looked up on the first call per device).
+constexpr long long kDecodeStaticScratchBytes = 16LL << 20;
+hipError_t decode_static_scratch(void **ptr);
+
 }  // namespace swaa
 
 #endif  // SWAA_DECODE_H_

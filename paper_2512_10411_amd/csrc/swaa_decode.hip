@@ -366,6 +366,33 @@ void plan_decode(DecodeParams &p) {
 
 long long decode_workspace_floats(const DecodeParams &p) { return p.items * ((long long)p.col_stride * kD + 64); }
 
+// ---- scratch memory for callers that cannot allocate -----------------------------------
+// swaa_attn_decode_static keeps the partial results of the key splits here instead of in
+// a caller's workspace.  In host code the array's name is only a stand-in for the device
+// object: its device address comes from hipGetSymbolAddress, asked once per device with
+// that device current (every GPU the library runs on holds its own copy of the array at
+// its own address until the process ends), and host code passes that address, never the
+// name, to kernels.
+static __device__ __align__(256) unsigned char scratch[kDecodeStaticScratchBytes];
+
+hipError_t decode_static_scratch(void **ptr) {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void *> address[kMaxDevices];  // zero-initialised
+    int dev = 0;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return err;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void *a = address[dev].load(std::memory_order_acquire);
+    if (!a) {
+        err = hipGetSymbolAddress(&a, HIP_SYMBOL(scratch));
+        if (err != hipSuccess) return err;
+        if (!a) return hipErrorInvalidSymbol;
+        address[dev].store(a, std::memory_order_release);  // (two threads racing here store the same value)
+    }
+    *ptr = a;
+    return hipSuccess;
+}
+
 hipError_t launch_decode(const DecodeParams &p, hipStream_t stream) {
     const long long chunk = (p.items + kXcds - 1) / kXcds;
     hipLaunchKernelGGL(swaa_decode_split_kernel, dim3((unsigned)(chunk * kXcds)), dim3(64), kDSmemBytes, stream, p);
