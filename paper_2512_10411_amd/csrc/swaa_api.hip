@@ -114,23 +114,14 @@ int swaa_attn_fwd_ex(const swaa_fwd_args *a) {
     p.G = Hq / Hkv;
     p.scale = a->scale;
     p.scale_log2 = a->scale * 1.44269504088896340736f;
-    p.n4 = p.G / 4;
-    p.has2 = (p.G % 4) >= 2 ? 1 : 0;
-    p.has1 = p.G % 2;
-    p.nt64 = (Nq + 63) / 64;
-    p.nt128 = (Nq + 127) / 128;
-    p.nt256 = (Nq + 255) / 256;
-    p.tiles_per_pair = p.n4 * p.nt64 + p.has2 * p.nt128 + p.has1 * p.nt256;
-    p.total_items = (long long)B * Hkv * p.tiles_per_pair;
-    p.chunk = (p.total_items + kXcds - 1) / kXcds;
-    const long long grid = p.chunk * kXcds;
-    if (grid > 0x7fffffffLL) return SWAA_ERR_SHAPE;
+    // the pipelined kernel (bfloat16, head dimension 128) runs workgroups of 128 rows, two per
+    // compute unit; its softmax keeps a fixed reference and leans on bfloat16's fp32-sized
+    // exponent, so binary16 runs on the plain kernel, whose probabilities are <= 1
+    const bool pipelined = D == 128 && !p.fp16;
+    if (!swaa::plan_work(p, Nq, pipelined ? 128 : swaa::kWgRows)) return SWAA_ERR_SHAPE;
 
     hipStream_t s = static_cast<hipStream_t>(a->stream);
-    // the pipelined kernel is bfloat16 only: its softmax keeps a fixed reference and leans on
-    // bfloat16's fp32-sized exponent; binary16 runs on the plain kernel, whose probabilities are <= 1
-    const hipError_t err = (D == 128 && !p.fp16) ? swaa::launch_fwd_pipelined_d128(p, s)
-                                                                          : swaa::launch_fwd_simple(p, D, s);
+    const hipError_t err = pipelined ? swaa::launch_fwd_pipelined_d128(p, s) : swaa::launch_fwd_simple(p, D, s);
     return err == hipSuccess ? SWAA_OK : SWAA_ERR_LAUNCH;
 }
 
@@ -304,16 +295,7 @@ int bwd_plan(swaa::BwdParams &p, int B, int Hq, int Hkv, int N, int D, int windo
     f.S = n_sink < N ? n_sink : N;
     f.P = n_prompt < N ? n_prompt : N;
     f.G = Hq / Hkv;
-    f.n4 = f.G / 4;
-    f.has2 = (f.G % 4) >= 2 ? 1 : 0;
-    f.has1 = f.G % 2;
-    f.nt64 = (N + 63) / 64;
-    f.nt128 = (N + 127) / 128;
-    f.nt256 = (N + 255) / 256;
-    f.tiles_per_pair = f.n4 * f.nt64 + f.has2 * f.nt128 + f.has1 * f.nt256;
-    f.total_items = (long long)B * Hkv * f.tiles_per_pair;
-    f.chunk = (f.total_items + kXcds - 1) / kXcds;
-    if (f.chunk * kXcds > 0x7fffffffLL || (long long)B * Hq * N > 0x7fffffffLL * 16) return SWAA_ERR_SHAPE;
+    if (!swaa::plan_work(f, N, swaa::kWgRows) || (long long)B * Hq * N > 0x7fffffffLL * 16) return SWAA_ERR_SHAPE;
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N;
     swaa::plan_bwd(p);
     return SWAA_OK;

@@ -19,7 +19,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kBk = 64;        // keys per KV tile
 constexpr int kThreads = 256;  // plain kernels: 4 waves per workgroup ...
 constexpr int kWaveRows = 64;  // ... of 64 query rows each (the pipelined kernel: 8 waves of 32)
-constexpr int kWgRows = 256;   // query rows (head x position) per workgroup
+constexpr int kWgRows = 256;   // query rows (head x position) per workgroup of the plain and backward kernels
 constexpr int kXcds = 8;       // accelerator dies; workgroups are dealt to them round-robin
 
 struct FwdParams {
@@ -46,11 +46,12 @@ struct FwdParams {
     int G;       // Hq / Hkv
     float scale, scale_log2;
     // Work decomposition.  Per (batch, KV head) "pair" the G query heads are
-    // cut into n4 groups of 4 heads (workgroups of 4 heads x 64 rows), at
-    // most one group of 2 heads (2 x 128) and at most one single head (1 x 256),
-    // so that every workgroup is 256 query rows on one KV head.
+    // cut into n4 groups of 4 heads, at most one group of 2 heads and at most
+    // one single head; a workgroup is wg_rows query rows (head x position) on one
+    // KV head: 4 heads x wg_rows/4 positions, 2 x wg_rows/2 or 1 x wg_rows.
+    int wg_rows;  // 256 (plain forward and backward kernels) or 128 (pipelined forward)
     int n4, has2, has1;
-    int nt64, nt128, nt256;  // row tiles of a sequence of Nq rows
+    int nt_h4, nt_h2, nt_h1;  // row tiles of a sequence of Nq rows for workgroups of 4, 2 and 1 heads
     int tiles_per_pair;
     long long total_items;
     long long chunk;  // work items per XCD
@@ -110,26 +111,42 @@ __device__ __forceinline__ bool decode_work(const FwdParams &p, WorkItem &w) {
     unsigned r = item - pair * tpp;
     w.b = (int)(pair / hkv);
     w.kvh = (int)(pair - (unsigned)w.b * hkv);
-    const unsigned nt64 = (unsigned)p.nt64, nt128 = (unsigned)p.nt128;
-    if (r < (unsigned)p.n4 * nt64) {
-        const unsigned g = r / nt64;
+    const unsigned nt4 = (unsigned)p.nt_h4, nt2 = (unsigned)p.nt_h2;
+    if (r < (unsigned)p.n4 * nt4) {
+        const unsigned g = r / nt4;
         w.hpb = 4;
         w.h0 = 4 * (int)g;
-        w.pt = (int)(nt64 - 1 - (r - g * nt64));
+        w.pt = (int)(nt4 - 1 - (r - g * nt4));
         return true;
     }
-    r -= (unsigned)p.n4 * nt64;
-    if (p.has2 && r < nt128) {
+    r -= (unsigned)p.n4 * nt4;
+    if (p.has2 && r < nt2) {
         w.hpb = 2;
         w.h0 = 4 * p.n4;
-        w.pt = (int)(nt128 - 1 - r);
+        w.pt = (int)(nt2 - 1 - r);
         return true;
     }
-    if (p.has2) r -= nt128;
+    if (p.has2) r -= nt2;
     w.hpb = 1;
     w.h0 = p.G - 1;
-    w.pt = p.nt256 - 1 - (int)r;
+    w.pt = p.nt_h1 - 1 - (int)r;
     return true;
+}
+
+// Fills the work-decomposition fields (everything from wg_rows on) for sequences of
+// `rows` query rows; needs B, Hkv and G.  False if the work list does not fit 31 bits.
+inline bool plan_work(FwdParams &p, int rows, int wg_rows) {
+    p.wg_rows = wg_rows;
+    p.n4 = p.G / 4;
+    p.has2 = (p.G % 4) >= 2 ? 1 : 0;
+    p.has1 = p.G % 2;
+    p.nt_h4 = (rows + wg_rows / 4 - 1) / (wg_rows / 4);
+    p.nt_h2 = (rows + wg_rows / 2 - 1) / (wg_rows / 2);
+    p.nt_h1 = (rows + wg_rows - 1) / wg_rows;
+    p.tiles_per_pair = p.n4 * p.nt_h4 + p.has2 * p.nt_h2 + p.has1 * p.nt_h1;
+    p.total_items = (long long)p.B * p.Hkv * p.tiles_per_pair;
+    p.chunk = (p.total_items + kXcds - 1) / kXcds;
+    return p.chunk * kXcds <= 0x7fffffffLL;
 }
 
 // Row block [p0, p0 + rows): a key is inside the window of every prompt row of

@@ -1,36 +1,39 @@
 // Software-pipelined SWA + sink attention forward, head dimension 128, gfx950.
 //
 // Same mask (paper Sec. 3.2.1 / Fig. 1b; full attention of Sec. 3.1.2 when the
-// window covers the context) and the same work decomposition as the plain
-// kernel: one workgroup = 256 query rows (4, 2 or 1 query heads x 64, 128 or
-// 256 positions) on one KV head.  What differs:
+// window covers the context) as the plain kernel.  Design:
 //
-//   * Eight waves of 32 query rows, two per SIMD.  A single wave cannot keep
-//     the matrix pipe busy (back-to-back MFMAs of one wave issue about a third
-//     slower than the pipe could take them, and every vector instruction beyond
-//     four per MFMA adds to that); with two waves per SIMD one wave's
-//     exponentials run while the other wave's MFMAs execute.  Each wave fits in
-//     256 registers: O^T (64) and Q (32) in AccVGPRs, S^T, P^T and the K/V
-//     fragments in VGPRs.
-//   * K and V tiles (64 keys) travel HBM -> LDS with global_load_lds_dwordx4
-//     (no register staging) into two rings of kStages tiles each, XOR-swizzled
-//     in 16-byte chunks so that the MFMA operand reads are bank-conflict free.
-//     One barrier per tile.  Q rows arrive the same way and O rows leave through
-//     the same per-wave staging area, so that every HBM access of the kernel is a
-//     full 256-byte row per 16 lanes.
-//   * A wave works on half tiles of 32 keys in a three-stage pipeline: while
-//     the softmax of half n runs on the VALU, the matrix pipe computes
-//     S^T = K Q^T of half n+1 and O^T += V^T P^T of half n-1.  The interleaving
-//     is fixed by hand with scheduling fences.  Every visited half goes through
-//     the same pipeline; edge tiles use the variant that masks scores first.
-//   * The softmax reference: softmax is invariant to the value subtracted
-//     before the exponential, so the reference only has to keep exp2() inside
-//     the fp32/bf16 range.  It is set from the first half a wave processes and
-//     moves later only when a row sum shows that scores have outgrown it (or,
-//     on edge tiles, when the maximum grows by more than 2^8); O and the row
-//     sum are rescaled only then.  Results are mathematically unchanged; the
-//     search for the row maximum and the rescale of the accumulator disappear
-//     from the steady state.
+//   * A workgroup is FOUR waves of 32 query rows: 128 rows (4, 2 or 1 query heads
+//     x 32, 64 or 128 positions) on one KV head, 64 KiB of LDS, 256 registers per
+//     wave -- so TWO workgroups share a compute unit, one wave of each per SIMD.
+//     A single wave cannot keep the matrix pipe busy (its exponentials, its tile
+//     copies, its waits at the workgroup barrier and its start-up all leave the
+//     pipe idle); two waves of DIFFERENT workgroups fill each other's gaps, and
+//     because they meet at different barriers neither ever waits for the other:
+//     one workgroup's prologue, epilogue and barrier waits run under the other's
+//     matrix work.  (Eight waves of one workgroup, two per SIMD, are coupled by
+//     their common barrier: the four that lose the arbitration for the matrix pipe
+//     finish their step alone, and start-up and drain of a workgroup are not
+//     overlapped with anything.)
+//   * K and V tiles (64 keys) travel HBM -> LDS with global_load_lds_dwordx4 (no
+//     register staging) into two rings of two tiles each, XOR-swizzled in 16-byte
+//     chunks so that the MFMA operand reads are bank-conflict free.  One barrier
+//     per tile.  O rows leave through the (then idle) rings, so that every store
+//     to HBM is a full 256-byte row per 16 lanes; Q fragments are loaded straight
+//     from HBM in operand layout and parked in AccVGPRs.
+//   * A wave works on half tiles of 32 keys in a three-stage pipeline: while the
+//     softmax of half n runs on the VALU, the matrix pipe computes S^T = K Q^T of
+//     half n+1 and O^T += V^T P^T of half n-1.  The interleaving is fixed by hand
+//     with scheduling fences.  A step of the loop is aligned to the tiles it
+//     READS -- halves (2t-1, 2t) take both halves of K tile t and of V tile t-1 --
+//     so a tile is dead when its step ends and two buffers per ring suffice.
+//   * The softmax reference: softmax is invariant to the value subtracted before
+//     the exponential, so the reference only has to keep exp2() inside the
+//     fp32/bf16 range.  It is set from the first half a wave processes and does
+//     not move in the loop; a workgroup whose row sums show that scores have
+//     outgrown it recomputes its rows with the max-based routine.  Results are
+//     mathematically unchanged; the search for the row maximum and the rescale of
+//     the accumulator disappear from the steady state.
 //
 // This kernel declares no static LDS: its dynamic LDS starts at address 0 and
 // all LDS accesses below use plain byte addresses.
@@ -42,15 +45,16 @@
 namespace swaa {
 namespace {
 
-constexpr int kPWaves = 8;    // waves per workgroup
+constexpr int kPWaves = 4;    // waves per workgroup
 constexpr int kPThreads = 64 * kPWaves;
-constexpr int kPRows = 32;  // query positions per wave
-constexpr int kStages = 3;                            // tiles per ring: copies run one step ahead
+constexpr int kPRows = 32;    // query positions per wave
+constexpr int kPWgRows = kPWaves * kPRows;            // query rows (head x position) per workgroup
+constexpr int kStages = 2;                            // tiles per ring
 constexpr int kTileBytes = kBk * kD * 2;              // 16 KiB
 constexpr int kVRing = kStages * kTileBytes;          // V ring follows the K ring
-constexpr int kStage = 2 * kStages * kTileBytes;      // per-wave staging areas follow the rings
-constexpr int kStageBytes = kPRows * kD * 2;          // 8 KiB: a wave's 32 Q rows on the way in, O rows on the way out
-constexpr int kSmemBytes = kStage + kPWaves * kStageBytes;  // 96 + 64 = 160 KiB, all of a CU's LDS
+constexpr int kSmemBytes = 2 * kStages * kTileBytes;  // 64 KiB: two workgroups per compute unit
+constexpr int kStageBytes = kPRows * kD * 2;          // 8 KiB: a wave's 32 O rows on the way out (inside the K ring)
+constexpr int kFlagBase = kSmemBytes - 64;            // four flag words of the fallback vote (tail of the V ring)
 constexpr float kSumLimit = 1.0995116e12f;  // 2^40: a row sum that sends the workgroup back to the max-based path
 constexpr float kSumFloor = 7.8886091e-31f;  // 2^-100: so does one this small (every score far below the reference)
 constexpr int kPrefetch = 3;  // MFMAs between an LDS fragment read and its use
@@ -61,14 +65,17 @@ constexpr int kPrefetch = 3;  // MFMAs between an LDS fragment read and its use
 // the softmax of half n, cut into 16 chunks.  Scheduling fences pin the order
 // "MFMA, chunk, MFMA, chunk, ...".  LDS fragment reads are issued kPrefetch
 // MFMAs ahead of their use, across the boundary between the two sub-steps of a
-// step as well.
+// step as well (not across steps: the next step's tiles are only known to have
+// landed after the barrier between them).
 //
-// The mask enters through the accumulator: on a half that is not fully visible
-// to the wave's 32 rows the K Q^T chain starts from a tile of 0 / -inf instead
-// of from zero, so invisible scores come out as -inf and their exponential is
-// an exact 0.  A half that lies wholly outside a wave's rows (before its band,
-// above its diagonal) therefore contributes nothing and needs no special case,
-// and the softmax chunks are the same for every half.
+// The mask: a half that is not fully visible to the wave's 32 rows has its
+// invisible scores replaced by -inf right before its softmax (a select, so
+// whatever an invisible key row holds -- NaN, infinities, stale LDS contents
+// of a tile that does not exist -- never reaches a row that must not see it);
+// their exponential is an exact 0.  A half that lies wholly outside a wave's
+// rows (before its band, above its diagonal, past the last tile) therefore
+// contributes nothing and needs no special case, and the softmax chunks are the
+// same for every half.
 //
 // The softmax does not look for the row maximum: it keeps the reference it has
 // (taken from the first half the wave sees).  exp2(s*c2 - mc) cannot overflow
@@ -104,6 +111,17 @@ __device__ __forceinline__ void softmax_chunk(int c, const f32x16 &s, float c2, 
                 if (e % 8 == 7) pin_p(pf[e / 8]);
             }
         }
+    }
+}
+
+// Scores of keys a lane's query row must not see become -inf (a select: the old
+// value, whatever it is, is dropped).  k0h: first key of the half.
+__device__ __forceinline__ void mask_scores(f32x16 &s, int k0h, int qpos, int W, int S, int hf) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const int key = k0h + 8 * (e / 4) + 4 * hf + (e % 4);
+        const bool vis = (key <= qpos) && ((key > qpos - W) || (key < S));
+        s[e] = vis ? s[e] : -INFINITY;
     }
 }
 
@@ -154,28 +172,43 @@ __device__ __forceinline__ bf16x8 load_slot(const LaneAddr &la, const HalfOffset
     return load_v_frag(la, next ? ho.nv : ho.v, (ii / 2) / kDB, (ii / 2) % kDB);
 }
 
-// fpre: the first kPrefetch fragments, already requested by the caller; on
-// return it holds those of the following sub-step.  k0h_next / mask_next: first
-// key of the half whose scores are computed here, and whether it needs the mask.
+// kHasS: the scores of the following half are computed here (not in the last sub-step of a
+//   workgroup, which issues the P V MFMAs only).
+// kHasPV: there is a previous half whose P V product is due (not in the very first
+//   sub-step of a workgroup, which issues the K Q^T MFMAs only).
+// kLoadFirst: the first kPrefetch fragments are requested here (first sub-step of a
+//   step); otherwise the caller passes them in fpre.
+// kPrefetchNext: on return fpre holds the first fragments of the following sub-step.
+// mask_cur / k0h_cur: whether the half whose softmax runs here (s_cur) needs the
+//   mask, and its first key.
+template <bool kHasS, bool kHasPV, bool kLoadFirst, bool kPrefetchNext>
 __device__ __forceinline__ void pipelined_substep(const LaneAddr &la, const HalfOffsets &ho, bf16x8 (&fpre)[kPrefetch],
-                                                  const bf16x8 (&qf)[kKS], f32x16 &s_next, const f32x16 &s_cur,
+                                                  const bf16x8 (&qf)[kKS], f32x16 &s_next, f32x16 &s_cur,
                                                   bf16x8 (&p_cur)[2], const bf16x8 (&p_prev)[2], f32x16 (&o)[kDB],
                                                   RowState &st, f32x4 (&lsum)[2], const bf16x8 &sel, float c2,
-                                                  bool mask_next, int k0h_next, int qpos, int W, int S, int hf) {
+                                                  bool mask_cur, int k0h_cur, int qpos, int W, int S, int hf) {
     SoftmaxScratch w;
     bf16x8 frag[16 + kPrefetch];
+    auto wanted = [](int slot) __attribute__((always_inline)) { return (slot & 1) ? kHasPV : kHasS; };
 #pragma unroll
-    for (int i = 0; i < kPrefetch; ++i) frag[i] = fpre[i];
+    for (int i = 0; i < kPrefetch; ++i)
+        if (wanted(i)) frag[i] = kLoadFirst ? load_slot(la, ho, i) : fpre[i];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        frag[i + kPrefetch] = load_slot(la, ho, i + kPrefetch);
-        if (i == 0)
-            qk_chain_start(s_next, frag[i], qf[0], mask_next, k0h_next, qpos, W, S, hf);
-        else if ((i & 1) == 0)
-            mfma_s(s_next, frag[i], qf[i / 2]);
-        else
+        const int nxt = i + kPrefetch;
+        if ((nxt < 16 || kPrefetchNext) && (nxt >= 16 || wanted(nxt))) frag[nxt] = load_slot(la, ho, nxt);
+        if ((i & 1) == 0) {
+            if (kHasS) {
+                if (i == 0)
+                    mfma_s_first(s_next, frag[i], qf[0]);
+                else
+                    mfma_s(s_next, frag[i], qf[i / 2]);
+            }
+        } else if (kHasPV) {
             mfma_acc(o[(i / 2) % kDB], frag[i], p_prev[(i / 2) / kDB]);
+        }
         __builtin_amdgcn_sched_barrier(0);
+        if (i == 0 && __builtin_expect(mask_cur, 0)) mask_scores(s_cur, k0h_cur, qpos, W, S, hf);
         softmax_chunk(i, s_cur, c2, st, w, p_cur);
         if (i == 15) {  // P^T of this half is complete (and two MFMAs old)
             mfma_rowsum(lsum[0], sel, p_cur[0]);
@@ -183,8 +216,10 @@ __device__ __forceinline__ void pipelined_substep(const LaneAddr &la, const Half
         }
         __builtin_amdgcn_sched_barrier(0);
     }
+    if (kPrefetchNext) {
 #pragma unroll
-    for (int i = 0; i < kPrefetch; ++i) fpre[i] = frag[16 + i];
+        for (int i = 0; i < kPrefetch; ++i) fpre[i] = frag[16 + i];
+    }
 }
 
 __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const FwdParams p) {
@@ -193,7 +228,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     SeqGeom sg;
     if (!seq_geom(p, wi.b, sg)) return;
     const int hpb = wi.hpb;
-    const int rows_per_wg = kWgRows / hpb;
+    const int rows_per_wg = kPWgRows / hpb;
     const int wg_r0 = wi.pt * rows_per_wg;  // first query row of the workgroup
     if (wg_r0 >= sg.nq) return;             // a shorter sequence of a packed batch
     const int Nq = sg.nq, Nk = sg.nk, S = p.S;
@@ -214,144 +249,111 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     // this lane's window: a generated token (position >= P) sees its whole prefix
     const int W = (qpos >= p.P) ? Nk : p.W;
 
-    // visited KV tiles: sink tiles 0 .. n_sink_tiles-1, then band tiles t_band_lo .. t_hi;
-    // a workgroup that holds a generated token visits every tile up to its diagonal
+    const __bf16 *qg = p.q + sg.q_batch * p.q_sb + (long long)head * p.q_sh + sg.q_row0 * p.q_sn;
+
+    // ---- this lane's Q fragments (B operand of S^T = K Q^T: query row l32, 16 bytes at
+    // 32 ks + 16 hf), straight from HBM (ordinary loads: the compiler places their wait in
+    // front of the first use; that wait also covers the tile copies issued below, which
+    // it cannot see -- the loads complete in order) ----
+    bf16x8 qf[kKS];
+    {
+        const char *qrow =
+            reinterpret_cast<const char *>(qg) + (size_t)min(r0 + l32, Nq - 1) * (size_t)(p.q_sn * 2) + 16 * hf;
+#pragma unroll
+        for (int ks = 0; ks < kKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qrow + 32 * ks);
+    }
+
+    // ---- the schedule, in halves of 32 keys: the halves that hold sink keys in front of the
+    // band, then the halves from the one that holds the first row's first window key to the one
+    // that holds the last row; a workgroup that holds a generated token visits every half up
+    // to its diagonal.  Two consecutive visited halves make one 64-key tile of the rings (a
+    // tile need not be 64 consecutive keys: the last sink half and the first band half share
+    // one); an odd count is padded with a half past the last row, which no row can see.
     const int band_lo = (wg_p1 >= p.P) ? 0 : max(0, wg_p0 - p.W + 1);
-    const int t_band_lo = band_lo / kBk;
-    const int t_hi = wg_p1 / kBk;
-    const int n_sink_tiles = min((min(S, band_lo) + kBk - 1) / kBk, t_band_lo);
-    const int J = n_sink_tiles + (t_hi - t_band_lo + 1);
-    auto tile_of = [&](int j) { return j < n_sink_tiles ? j : j - n_sink_tiles + t_band_lo; };
+    const int hb_lo = band_lo >> 5, hb_hi = wg_p1 >> 5;
+    const int n_sink_h = min((min(S, band_lo) + 31) >> 5, hb_lo);
+    const int n_halves = n_sink_h + (hb_hi - hb_lo + 1);
+    const int J = (n_halves + 1) >> 1;  // tiles
+    // i-th visited half -> its index among all halves of the sequence (first key / 32); the
+    // padding half comes out as hb_hi + 1
+    auto half_of = [&](int i) __attribute__((always_inline)) { return i < n_sink_h ? i : i - n_sink_h + hb_lo; };
 
     const uint32_t k_rsb = (uint32_t)(p.k_sn * 2), v_rsb = (uint32_t)(p.v_sn * 2);  // row strides in bytes
     const __bf16 *kg = p.k + sg.k_batch * p.k_sb + (long long)wi.kvh * p.k_sh + sg.k_row0 * p.k_sn;
     const __bf16 *vg = p.v + sg.k_batch * p.v_sb + (long long)wi.kvh * p.v_sh + sg.k_row0 * p.v_sn;
-    const __bf16 *qg = p.q + sg.q_batch * p.q_sb + (long long)head * p.q_sh + sg.q_row0 * p.q_sn;
     __bf16 *og = p.out + sg.q_batch * p.o_sb + (long long)head * p.o_sh + sg.q_row0 * p.o_sn;
 
     // ---- HBM -> LDS tile copies -------------------------------------------------
-    // One wave instruction moves 64 x 16 bytes = 4 rows of the tile, a wave moves
-    // 8 rows of K and of V per tile; the LDS side is linear in the lane id, the
-    // swizzle is applied on the global side: LDS chunk (row, c') receives global
-    // chunk c' ^ f(row) of that row, with f(row) = ((row & 7) << 1) | ((row >> 3) & 1)
-    // for K (16 consecutive rows read the same logical chunk) and (row & 3) << 2
-    // for V (4 consecutive rows read the same 64 bytes).
+    // One wave instruction moves 64 x 16 bytes = 4 rows, a wave moves 16 rows of K and of V
+    // per tile: waves 0, 1 the tile's first half, waves 2, 3 its second (instruction i of wave
+    // w: rows 16 (w & 1) + 4 i + lrow of that half).  The LDS side is linear in the lane id,
+    // the swizzle is applied on the global side: LDS chunk (row, c') receives global chunk
+    // c' ^ f(row) of that row, with f(row) = ((row & 7) << 1) | ((row >> 3) & 1) for K (16
+    // consecutive rows read the same logical chunk) and (row & 3) << 2 for V (4 consecutive
+    // rows read the same 64 bytes).
     const int lrow = lane >> 4;  // row within the 4-row group
     const int lchk = lane & 15;  // LDS chunk within the row
-    // byte offset of this lane's 16 bytes from the tile's first row; row = 8*wave + 4*i + lrow
-    const uint32_t chunk_k = (uint32_t)(lchk ^ (lrow << 1) ^ (wave & 1));
-    const uint32_t voff_k = (uint32_t)(8 * wave + lrow) * k_rsb + (chunk_k << 4);
-    const uint32_t voff_k1 = (uint32_t)(8 * wave + lrow + 4) * k_rsb + ((chunk_k ^ 8u) << 4);  // row & 7 = 4 + lrow
-    const uint32_t voff_v = (uint32_t)(8 * wave + lrow) * v_rsb + (uint32_t)((lchk ^ (lrow << 2)) << 4);
-    // LDS address = M0 + 16 * lane; global address = base + off.  Issued as assembly on
-    // purpose: the compiler would otherwise make every later LDS read wait for the copy.
-    auto copy16 = [](uint32_t off, const char *base, uint32_t lds) {
-        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds)
-                     : "memory");
-    };
-    // The wave's two copies of one tile into ring buffer `buf`; base: the tile's first row in
-    // HBM; ragged: the tile runs past the sequence's last row (only the last visited tile
-    // can), and rows past the end repeat the last row -- they are masked later -- so that the
-    // reads stay in bounds.
-    auto copy_tile = [&](const char *base, int buf, int ring, bool is_k, bool ragged) {
-        const uint32_t l = (uint32_t)(ring + buf * kTileBytes + 2 * wave * 1024);
-        if (__builtin_expect(ragged, 0)) {
-            const uint32_t rsb = is_k ? k_rsb : v_rsb;
+    const int hslot = wave >> 1;  // which half of a tile this wave copies
+    const int hrow0 = 16 * (wave & 1);
+    // byte offsets of this lane's 16 bytes from the half's first row, minus 1024 i: the four
+    // copies of a tile share one M0 value and use the instruction's offset field (1024 i), which
+    // moves the LDS address and the global address alike
+    uint32_t voff_k[4], voff_v[4];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                uint32_t off = is_k ? (i ? voff_k1 : voff_k) : voff_v + (uint32_t)(4 * i) * v_rsb;
-                const int row = 8 * wave + 4 * i + lrow;
-                off -= (uint32_t)max(t_hi * kBk + row - (Nk - 1), 0) * rsb;
-                copy16(off, base, l + (uint32_t)(i * 1024));
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t row = (uint32_t)(hrow0 + 4 * i + lrow);
+        // row & 7 = 4 (i & 1) + lrow, (row >> 3) & 1 = i >> 1
+        const uint32_t fk = (uint32_t)(((4 * (i & 1) + lrow) << 1) | (i >> 1));
+        voff_k[i] = row * k_rsb + (((uint32_t)lchk ^ fk) << 4) - (uint32_t)(1024 * i);
+        voff_v[i] = row * v_rsb + (((uint32_t)lchk ^ (uint32_t)(lrow << 2)) << 4) - (uint32_t)(1024 * i);
+    }
+    // LDS address = M0 + offset field + 16 * lane; global address = base + off + offset field.
+    // Issued as assembly on purpose: the compiler would otherwise make every later LDS read
+    // wait for the copy.
+    auto copy4 = [](const uint32_t (&vo)[4], const char *base, uint32_t lds) __attribute__((always_inline)) {
+        asm volatile(
+            "s_mov_b32 m0, %5\n\ts_nop 0\n\t"
+            "global_load_lds_dwordx4 %0, %4\n\t"
+            "global_load_lds_dwordx4 %1, %4 offset:1024\n\t"
+            "global_load_lds_dwordx4 %2, %4 offset:2048\n\t"
+            "global_load_lds_dwordx4 %3, %4 offset:3072" ::"v"(vo[0]),
+            "v"(vo[1]), "v"(vo[2]), "v"(vo[3]), "s"(base), "s"(lds)
+            : "memory");
+    };
+    const bool last_ragged = ((hb_hi + 1) << 5) > Nk;  // the last band half runs past the sequence's end
+    // This wave's four copies of tile j (K or V) into ring buffer `buf`, from scratch: which
+    // half, where it starts, whether its rows run past the sequence's last row (then they
+    // repeat that row -- they are masked later -- so that the reads stay in bounds; the padding
+    // half repeats the last real half).  A tile that does not exist is not copied.
+    auto issue_tile = [&](int j, int buf, bool is_k) __attribute__((always_inline)) {
+        if (2 * j >= n_halves) return;
+        const int g = min(half_of(2 * j + hslot), hb_hi);
+        const uint32_t rsb = is_k ? k_rsb : v_rsb;
+        const char *base = reinterpret_cast<const char *>(is_k ? kg : vg) + (size_t)(32 * g) * rsb;
+        const uint32_t l = (uint32_t)((is_k ? 0 : kVRing) + buf * kTileBytes + wave * 4096);
+        if (__builtin_expect(last_ragged && g == hb_hi, 0)) {
+            // (one M0 value per copy and no offset field: a clamped row may lie less than
+            // 1024 i bytes behind the half's first row)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t off = (is_k ? voff_k[i] : voff_v[i]) + (uint32_t)(1024 * i) -
+                                     (uint32_t)max(32 * g + hrow0 + 4 * i + lrow - (Nk - 1), 0) * rsb;
+                asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base),
+                             "s"(l + (uint32_t)(1024 * i))
+                             : "memory");
             }
-        } else if (is_k) {
-            copy16(voff_k, base, l);
-            copy16(voff_k1, base, l + 1024u);
         } else {
-            copy16(voff_v, base, l);
-            copy16(voff_v + 4u * v_rsb, base, l + 1024u);
+            copy4(is_k ? voff_k : voff_v, base, l);
         }
     };
-    const int j_ragged = ((t_hi + 1) * kBk > Nk) ? J - 1 : -1;
-    // any visited tile (the recomputation path)
-    auto issue_tile = [&](int j, int buf, const __bf16 *src, int ring, bool is_k) {
-        if (j >= J) return;
-        const char *base = reinterpret_cast<const char *>(src) + (size_t)(tile_of(j) * kBk) * (is_k ? k_rsb : v_rsb);
-        copy_tile(base, buf, ring, is_k, j == j_ragged);
-    };
-    auto issue_k = [&](int j, int buf) { issue_tile(j, buf, kg, 0, true); };
-    auto issue_v = [&](int j, int buf) { issue_tile(j, buf, vg, kVRing, false); };
-    // The pipeline asks for the visited tiles in order, so their addresses are kept as two
-    // running pointers: a handful of scalar instructions per tile instead of a 64-bit
-    // multiplication (every wave executes them, at the start of every step).
-    struct TileStream {
-        const char *next;   // first row of the next tile to copy
-        size_t step, jump;  // bytes to the following tile: the usual one, and from the last sink tile to the band
-        int plain;          // tiles to copy before the next one that needs a closer look
-    };
-    // A tile needs a closer look if it is the last sink tile before a jump, runs past the
-    // sequence's end, or does not exist; all others take "copy, advance by one tile".
-    auto special = [&](int j) { return j + 1 == n_sink_tiles || j == j_ragged || j >= J; };
-    auto plain_from = [&](int j) {  // number of consecutive tiles from j on that are not special
-        int e = J;
-        if (j_ragged >= j) e = min(e, j_ragged);
-        if (n_sink_tiles - 1 >= j) e = min(e, n_sink_tiles - 1);
-        return max(e - j, 0);
-    };
-    auto make_stream = [&](const __bf16 *src, uint32_t rsb) {
-        TileStream ts;
-        ts.next = reinterpret_cast<const char *>(src) + (size_t)(tile_of(0) * kBk) * rsb;
-        ts.step = (size_t)kBk * rsb;
-        ts.jump = (size_t)(t_band_lo - n_sink_tiles + 1) * kBk * rsb;
-        ts.plain = plain_from(0);
-        return ts;
-    };
-    TileStream k_stream = make_stream(kg, k_rsb), v_stream = make_stream(vg, v_rsb);
-    auto stream_tile = [&](TileStream &ts, int j, int buf, int ring, bool is_k) {
-        if (__builtin_expect(--ts.plain >= 0, 1)) {
-            const char *base = ts.next;
-            ts.next += ts.step;
-            copy_tile(base, buf, ring, is_k, false);
-            return;
-        }
-        if (j >= J) return;  // (plain stays negative: every later call ends here)
-        const char *base = ts.next;
-        ts.next += (j + 1 == n_sink_tiles) ? ts.jump : ts.step;
-        copy_tile(base, buf, ring, is_k, j == j_ragged);
-        ts.plain = plain_from(j + 1);
-    };
-    auto stream_k = [&](int j, int buf) { stream_tile(k_stream, j, buf, 0, true); };
-    auto stream_v = [&](int j, int buf) { stream_tile(v_stream, j, buf, kVRing, false); };
+    auto issue_k = [&](int j, int buf) __attribute__((always_inline)) { issue_tile(j, buf, true); };
+    auto issue_v = [&](int j, int buf) __attribute__((always_inline)) { issue_tile(j, buf, false); };
 
-    // Step 0 multiplies an all-zero P^T with "the tile before the first": give that
-    // V buffer (the last one of the ring, not yet a copy target) defined contents.
-    {
-        const u32x4 zero = {0u, 0u, 0u, 0u};
-        for (int i = tid; i < kTileBytes / 16; i += kPThreads)
-            *(u32x4 __attribute__((address_space(3))) *)(uintptr_t)(kVRing + (kStages - 1) * kTileBytes + i * 16) = zero;
-    }
-
-    // ---- this wave's 32 Q rows: HBM -> its staging area, laid out like a K half tile ----
-    const uint32_t stage = (uint32_t)(kStage + wave * kStageBytes);
-    {
-        const char *qb = reinterpret_cast<const char *>(qg);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int row = 4 * i + lrow;
-            const int f = ((4 * (i & 1) + lrow) << 1) | ((i >> 1) & 1);
-            const char *g = qb + (size_t)min(r0 + row, Nq - 1) * (size_t)(p.q_sn * 2) + ((lchk ^ f) << 4);
-            const uint32_t l = stage + (uint32_t)(i * 1024);
-            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(l) : "memory");
-        }
-    }
-    // Tiles in the order they are needed.  A CU takes in about 64 bytes per cycle,
-    // so the pipeline prologue below starts as soon as Q and K(0) are there (ten
-    // copies per wave) and the other four tiles (eight copies) stream in behind it.
-    stream_k(0, 0);
-    stream_v(0, 0);
-    stream_k(1, 1);
-    stream_k(2, 2);
-    stream_v(1, 1);
+    // Tiles in the order they are needed: K(0) first, the other three stream in behind it.
+    issue_k(0, 0);
+    issue_v(0, 0);
+    issue_k(1, 1);
+    issue_v(1, 1);
 
     f32x16 oacc[kDB];
 #pragma unroll
@@ -374,13 +376,6 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
 
     f32x16 s_a, s_b;        // scores of half 0 / half 1 of a tile
     bf16x8 p_a[2], p_b[2];  // their P^T fragments
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        p_b[0][e] = (__bf16)0.f;
-        p_b[1][e] = (__bf16)0.f;
-    }
-    pin_p(p_b[0]);
-    pin_p(p_b[1]);
     f32x4 lsum[2];  // column sums of the rounded P^T (mfma_rowsum), one accumulator per fragment
 #pragma unroll
     for (int e = 0; e < 4; ++e) lsum[0][e] = lsum[1][e] = 0.f;
@@ -391,60 +386,41 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     // its 32 rows: at or below the first row's diagonal, and inside the window of
     // its last prompt row (if it has one) or all sinks.
     const int wbound = window_bound(p0, kPRows, p.W, p.P);
-    auto half_masked = [&](int k0h) { return !((k0h + 31 <= p0) && ((k0h > wbound) || (k0h + 31 < S))); };
+    auto half_masked = [&](int k0h) __attribute__((always_inline)) { return !((k0h + 31 <= p0) && ((k0h > wbound) || (k0h + 31 < S))); };
 
     // (Worked out here, while the first copies travel.)
-    // Steps [ja, jb) of this wave need no mask: band tiles t with both score halves of the
-    // step (tile t half 1, tile t+1 half 0) inside every row's window and at or below the
-    // first row's diagonal.  The two loops only run if the closed form is off.
+    // Steps [ja, jb) of this wave need no mask.  Step t runs the softmax of the visited halves
+    // 2 t - 1 and 2 t.  A band half g (keys 32 g .. 32 g + 31) lies inside every row's window
+    // iff 32 g > wbound and at or below the first row's diagonal iff 32 g + 31 <= p0.
+    // (Halves that need no mask because they hold sink keys only take the general step.)
     int ja, jb;
     {
-        auto unmasked_step = [&](int j) {
-            if (j < n_sink_tiles || j + 1 >= J) return false;
-            const int k0 = tile_of(j) * kBk;
-            return !half_masked(k0 + 32) && !half_masked(k0 + kBk);
-        };
-        const int t_min = max(((wbound - 32) >> 6) + 1, t_band_lo);  // 64 t + 32 > wbound
-        const int t_max = min((p0 - 95) >> 6, t_hi - 1);             // 64 t + 64 + 31 <= p0
-        ja = n_sink_tiles + (t_min - t_band_lo);
-        jb = max(ja, n_sink_tiles + (t_max - t_band_lo) + 1);
-        while (ja < jb && !unmasked_step(ja)) ++ja;
-        while (jb > ja && !unmasked_step(jb - 1)) --jb;
+        const int g_min = (wbound >> 5) + 1, g_max = (p0 - 31) >> 5;
+        const int i_min = max(n_sink_h, g_min - hb_lo + n_sink_h);  // first unmasked band half
+        const int i_max = min(g_max - hb_lo + n_sink_h, n_halves - 1);  // last one
+        ja = (i_min + 2) >> 1;       // 2 t - 1 >= i_min
+        jb = max(ja, (i_max >> 1) + 1);  // 2 t <= i_max
     }
-    const unsigned n_interior = (unsigned)(jb - ja);
 
-    // this wave's Q and K(0) copies must have landed; V(0), K(1), K(2), V(1) -- those
-    // of them that exist -- may still fly (two copies per tile)
-    if (J >= 3)
-        __builtin_amdgcn_s_waitcnt(0x0078);  // vmcnt(8) lgkmcnt(0)
-    else if (J == 2)
-        __builtin_amdgcn_s_waitcnt(0x0076);  // vmcnt(6) lgkmcnt(0)
-    else
-        __builtin_amdgcn_s_waitcnt(0x0072);  // vmcnt(2) lgkmcnt(0)
+    // The Q fragments move to AccVGPRs (the idle cycles keep the copies two wait states away
+    // from the first MFMA that reads them).  The compiler waits for the loads here, hence
+    // for every tile copy issued so far as well: K(0), V(0), K(1), V(1) have landed.
+    asm volatile("s_nop 1"
+                 : "+a"(qf[0]), "+a"(qf[1]), "+a"(qf[2]), "+a"(qf[3]), "+a"(qf[4]), "+a"(qf[5]), "+a"(qf[6]), "+a"(qf[7]));
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), should the compiler's own wait ever be weaker
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 
-    // ---- Q fragments (B operand of S^T = K Q^T), parked in AccVGPRs -------------------
-    bf16x8 qf[kKS];
-#pragma unroll
-    for (int ks = 0; ks < kKS; ++ks) qf[ks] = load_k_frag(la, stage, ks);
-    // the idle cycles keep the copies two wait states away from the first MFMA that reads them
-    asm volatile("s_nop 1"
-                 : "+a"(qf[0]), "+a"(qf[1]), "+a"(qf[2]), "+a"(qf[3]), "+a"(qf[4]), "+a"(qf[5]), "+a"(qf[6]), "+a"(qf[7]));
-
     // ---- pipeline prologue: scores of the very first half, and the softmax reference ----
     // The reference is the largest visible score of that half (0 for a row that
-    // sees none of its keys); from here on it only moves if a row sum overflows.
+    // sees none of its keys); from here on it does not move.
     RowState rs;
     rs.l = 0.f;
     rs.lb = 0.f;
     {
-        const int k0 = tile_of(0) * kBk;
-        qk_chain_start(s_a, load_k_frag(la, 0, 0), qf[0], true, k0, qpos, W, S, hf);
-#pragma unroll
-        for (int ks = 1; ks < kKS - 1; ++ks) mfma_s(s_a, load_k_frag(la, 0, ks), qf[ks]);
-        mfma_s_settled(s_a, load_k_frag(la, 0, kKS - 1), qf[kKS - 1]);
+        qk_half(la, 0u, qf, s_a);
+        mask_scores(s_a, 32 * half_of(0), qpos, W, S, hf);
         float mx = s_a[0];
 #pragma unroll
         for (int e = 1; e < 16; ++e) mx = fmaxf(mx, s_a[e]);
@@ -452,82 +428,105 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
         rs.mc = (mx == -INFINITY) ? 0.f : mx * c2;
     }
 
-    // step 0 reads V(0) and K(1): they must be there for every wave (K(2), V(1) may still fly)
-    if (J >= 3)
-        __builtin_amdgcn_s_waitcnt(0x0074);  // vmcnt(4) lgkmcnt(0)
-    else if (J == 2)
-        __builtin_amdgcn_s_waitcnt(0x0072);  // vmcnt(2) lgkmcnt(0)
-    else
-        __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+    bf16x8 fpre[kPrefetch];  // first fragments of the second sub-step of a step, requested during the first
+    // softmax of (tile 0, half 0) | scores of (tile 0, half 1); no P V product is due yet
+    {
+        const HalfOffsets h = {kHalfBytes, 0, 0, 0};
+        pipelined_substep<true, false, true, false>(la, h, fpre, qf, s_b, s_a, p_a, p_b, oacc, rs, lsum, sel, c2, false, 0,
+                                              qpos, W, S, hf);
+    }
+    // every wave is done with K(0), which is free afterwards
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+    issue_k(2, 0);
 
-    // One step = one visited tile.  The ring position R = j % 3 is a template
-    // argument, so every LDS offset below is a constant that folds into the
-    // instructions' offset fields (no address arithmetic in the loop); the loop
-    // walks the three instantiations in turn.
-    bf16x8 fpre[kPrefetch];  // the first fragments of the coming sub-step, requested one sub-step ahead
-    {
-        const HalfOffsets h0 = {kHalfBytes, (kStages - 1) * kTileBytes + kHalfBytes, 0, 0};  // step 0, first sub-step
-#pragma unroll
-        for (int i = 0; i < kPrefetch; ++i) fpre[i] = load_slot(la, h0, i);
-    }
-    // checked: the step looks at its two score halves and masks them where needed.  In the
-    // interior of a wave's band no half needs a mask, and the step skips that scalar
-    // bookkeeping.
-    auto step = [&](auto ring_pos, bool checked, int j) {
+    // Step t = 1 .. J - 1 reads K tile t (ring buffer t % 2) and V tile t - 1 (buffer
+    // (t - 1) % 2).  The ring position R = t % 2 is a template argument, so every LDS offset
+    // below is a constant that folds into the instructions' offset fields (no address
+    // arithmetic in the loop).
+    //
+    // Two versions of the step.  The general one looks at the two halves whose softmax it
+    // runs, masks them where needed, and works out the next copies from scratch (sink
+    // halves, the jump to the band, the ragged last half, the end of the list).  The lean one
+    // serves the interior of a wave's band, where no half needs a mask and the next tiles
+    // simply follow the previous ones in memory.
+    auto substeps = [&](auto ring_pos, bool mask_p, int k0p, bool mask_0, int k0) __attribute__((always_inline)) {
         constexpr int R = decltype(ring_pos)::value;
-        constexpr int Rn = (R + 1) % kStages, Rp = (R + kStages - 1) % kStages;
-        constexpr uint32_t kb_cur1 = R * kTileBytes + kHalfBytes;    // K(j), half 1
-        constexpr uint32_t kb_next0 = Rn * kTileBytes;               // K(j+1), half 0
-        constexpr uint32_t vb_prev1 = Rp * kTileBytes + kHalfBytes;  // V(j-1), half 1
-        constexpr uint32_t vb_cur0 = R * kTileBytes;                 // V(j), half 0
-        int k0 = 0, k0n = 0;
-        bool mask1 = false, mask2 = false;
-        if (__builtin_expect(checked, 0)) {
-            k0 = tile_of(j) * kBk;
-            k0n = (j + 1 < J) ? tile_of(j + 1) * kBk : k0 + kBk;  // past the end: scores never used
-            mask1 = half_masked(k0 + 32);
-            mask2 = half_masked(k0n);
-        }
-
-        // softmax of (j, half 0) | scores of (j, half 1) | P V of (j-1, half 1)
-        const HalfOffsets h1 = {kb_cur1, vb_prev1, kb_next0, vb_cur0};
-        pipelined_substep(la, h1, fpre, qf, s_b, s_a, p_a, p_b, oacc, rs, lsum, sel, c2, mask1, k0 + 32, qpos, W, S, hf);
-        // softmax of (j, half 1) | scores of (j+1, half 0) | P V of (j, half 0); its last
-        // fragment requests are the first ones of step j+1 (K(j+1) half 1, V(j) half 1: both
-        // resident), so that they are under way while the waves meet at the barrier
-        const HalfOffsets h2 = {kb_next0, vb_cur0, Rn * kTileBytes + kHalfBytes, R * kTileBytes + kHalfBytes};
-        pipelined_substep(la, h2, fpre, qf, s_a, s_b, p_b, p_a, oacc, rs, lsum, sel, c2, mask2, k0n, qpos, W, S, hf);
-
-        // K(j+2), V(j+1) must have landed; K(j) and V(j-1) are free afterwards
+        constexpr uint32_t kb0 = R * kTileBytes, kb1 = kb0 + kHalfBytes;        // K(t)
+        constexpr uint32_t vb0 = (1 - R) * kTileBytes, vb1 = vb0 + kHalfBytes;  // V(t-1)
+        // softmax of (t-1, half 1) | scores of (t, half 0) | P V of (t-1, half 0)
+        const HalfOffsets h1 = {kb0, vb0, kb1, vb1};
+        pipelined_substep<true, true, true, true>(la, h1, fpre, qf, s_a, s_b, p_b, p_a, oacc, rs, lsum, sel, c2, mask_p,
+                                                  k0p, qpos, W, S, hf);
+        // softmax of (t, half 0) | scores of (t, half 1) | P V of (t-1, half 1)
+        const HalfOffsets h2 = {kb1, vb1, 0, 0};
+        pipelined_substep<true, true, false, false>(la, h2, fpre, qf, s_b, s_a, p_a, p_b, oacc, rs, lsum, sel, c2, mask_0,
+                                                    k0, qpos, W, S, hf);
+        // K(t+1), V(t) must have landed; K(t) and V(t-1) are free afterwards
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
         asm volatile("" ::: "memory");  // no LDS access may be moved across the barrier
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        stream_k(j + kStages, R);
-        stream_v(j + kStages - 1, Rp);
     };
-    static_assert(kStages == 3, "the loop below walks three ring positions");
-    auto ring_step = [&](auto ring_pos, int j) { step(ring_pos, (unsigned)(j - ja) >= n_interior, j); };
-    for (int j = 0;;) {
-        ring_step(std::integral_constant<int, 0>{}, j);
-        if (++j >= J) break;
-        ring_step(std::integral_constant<int, 1>{}, j);
-        if (++j >= J) break;
-        ring_step(std::integral_constant<int, 2>{}, j);
-        if (++j >= J) break;
+    auto general_step = [&](auto ring_pos, int t) __attribute__((always_inline)) {
+        constexpr int R = decltype(ring_pos)::value;
+        const int k0p = 32 * half_of(2 * t - 1), k0 = 32 * half_of(2 * t);
+        substeps(ring_pos, half_masked(k0p), k0p, half_masked(k0), k0);
+        issue_k(t + 2, R);
+        issue_v(t + 1, 1 - R);
+    };
+    // the lean step's copies: this wave's half of K tile t + 2 and of V tile t + 1
+    const char *k_next = nullptr, *v_next = nullptr;
+    auto lean_step = [&](auto ring_pos) __attribute__((always_inline)) {
+        constexpr int R = decltype(ring_pos)::value;
+        substeps(ring_pos, false, 0, false, 0);
+        copy4(voff_k, k_next, (uint32_t)(R * kTileBytes + wave * 4096));
+        k_next += (size_t)kBk * k_rsb;
+        copy4(voff_v, v_next, (uint32_t)(kVRing + (1 - R) * kTileBytes + wave * 4096));
+        v_next += (size_t)kBk * v_rsb;
+    };
+    static_assert(kStages == 2, "the loops below walk two ring positions");
+    const std::integral_constant<int, 0> even{};
+    const std::integral_constant<int, 1> odd{};
+    // Lean steps: [ja, jb) needs no mask; the copies step t issues are the visited halves
+    // 2 t + 2 .. 2 t + 5, which must be band halves (they are: 2 t - 1 >= n_sink_h) that exist
+    // and do not run past the sequence's end.  The range starts at an odd step (steps run
+    // in pairs: odd, even).
+    const int lean_end = min(jb, ((n_halves - 6 - (last_ragged ? 1 : 0)) >> 1) + 1);
+    const int lean_begin = ja | 1;
+    bool lean_pending = lean_begin + 1 < lean_end;
+    for (int t = 1; t < J;) {  // t is odd here
+        if (lean_pending && t == lean_begin) {
+            k_next = reinterpret_cast<const char *>(kg) + (size_t)(32 * half_of(2 * t + 4 + hslot)) * k_rsb;
+            v_next = reinterpret_cast<const char *>(vg) + (size_t)(32 * half_of(2 * t + 2 + hslot)) * v_rsb;
+            for (; t + 1 < lean_end; t += 2) {
+                lean_step(odd);
+                lean_step(even);
+            }
+            lean_pending = false;
+        }
+        general_step(odd, t);
+        if (++t >= J) break;
+        general_step(even, t);
+        ++t;
     }
-    // pipeline drain: P V of the last half (V(J-1) sits in buffer (J-1) % kStages)
-    pv_half<true>(la, (uint32_t)(((J - 1) % kStages) * kTileBytes + kHalfBytes), p_b, oacc);
+    // ---- tail: softmax of the last half | P V of the half before it, then the last P V ----
+    {
+        const uint32_t vb = (uint32_t)(((J - 1) & 1) * kTileBytes);  // V(J-1)
+        const int k0l = 32 * half_of(2 * J - 1);
+        const HalfOffsets h = {0, vb, 0, 0};
+        pipelined_substep<false, true, true, false>(la, h, fpre, qf, s_a, s_b, p_b, p_a, oacc, rs, lsum, sel, c2,
+                                                    half_masked(k0l), k0l, qpos, W, S, hf);
+        // (the column sums of p_b, issued at the end of the sub-step, complete under these)
+        pv_half<true>(la, vb + kHalfBytes, p_b, oacc);
+    }
 
     // ---- scores outgrew the reference somewhere in this workgroup (inputs with
     // score jumps of tens of nats): recompute its rows with the max-based routine,
     // one tile at a time, no pipelining ------------------------------------------
-    // (workgroup-wide OR through eight flag words at the start of the K ring,
-    // which nobody reads any more after the loop's last barrier)
-    // (the drain above waited for its own result, hence for the column sums issued before it)
+    // (workgroup-wide OR through four flag words at the end of the V ring, which
+    // nobody reads any more after the loop's last barrier)
     float l_row = half_swap_sum(rs.l);
     float lb_row = rowsum_of_column(lsum, l32);
     bool redo;
@@ -539,11 +538,12 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
         const bool in_range = (__float_as_uint(l_row) - (__float_as_uint(kSumFloor) + 1u)) <
                               (__float_as_uint(kSumLimit) - (__float_as_uint(kSumFloor) + 1u));
         const int mine = __any(!in_range && r0 + l32 < Nq) ? 1 : 0;
-        if (lane == 0) *(int __attribute__((address_space(3))) *)(uintptr_t)(wave * 4) = mine;
+        if (lane == 0) *(int __attribute__((address_space(3))) *)(uintptr_t)(kFlagBase + wave * 4) = mine;
         __syncthreads();
         int any = 0;
 #pragma unroll
-        for (int w = 0; w < kPWaves; ++w) any |= *(const int __attribute__((address_space(3))) *)(uintptr_t)(w * 4);
+        for (int w = 0; w < kPWaves; ++w)
+            any |= *(const int __attribute__((address_space(3))) *)(uintptr_t)(kFlagBase + w * 4);
         redo = any != 0;
     }
     if (redo) {
@@ -565,18 +565,20 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
             for (int hh = 0; hh < 2; ++hh) {
                 float alpha;
                 qk_half(la, (uint32_t)(hh * kHalfBytes), qf, s_a);
-                softmax_half<true>(s_a, tile_of(j) * kBk + 32 * hh, qpos, W, S, hf, c2, rs, p_a, alpha);
+                softmax_half<true>(s_a, 32 * half_of(2 * j + hh), qpos, W, S, hf, c2, rs, p_a, alpha);
                 rescale(oacc, alpha);
                 pv_half<true>(la, (uint32_t)(hh * kHalfBytes), p_a, oacc);
             }
         }
         row_sums(rs, l_row, lb_row);
+        __syncthreads();  // the rings become the O staging area below
     }
 
-    // ---- epilogue: O / (sum of the rounded P) -> bf16 through the wave's staging area, so
-    // that the stores to HBM are whole rows; lse = (mc + log2 l) * ln 2 -------------------
-    // (the accumulators are settled: the last P V contraction above waited for its result)
+    // ---- epilogue: O / (sum of the rounded P) -> bf16 through LDS (8 KiB per wave at the start
+    // of the K ring, which nobody reads any more), so that the stores to HBM are whole rows;
+    // lse = (mc + log2 l) * ln 2 -------------------
     {
+        const uint32_t stage = (uint32_t)(wave * kStageBytes);
         const float inv_l = 1.f / lb_row;  // rows past the end: never stored
         const int fr = ((l32 & 7) << 1) | ((l32 >> 3) & 1);
         const uint32_t o_lane = stage + (uint32_t)(l32 * 256 + (fr << 4) + 8 * hf);
@@ -607,7 +609,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
 }  // namespace
 
 hipError_t launch_fwd_pipelined_d128(const FwdParams &p, hipStream_t stream) {
-    // more than 64 KiB of LDS per workgroup has to be requested once per device
+    // (64 KiB of dynamic LDS is the most a kernel gets without asking; asking is harmless)
     static std::atomic<unsigned long long> configured{0};
     int dev = 0;
     hipError_t err = hipGetDevice(&dev);
@@ -619,6 +621,7 @@ hipError_t launch_fwd_pipelined_d128(const FwdParams &p, hipStream_t stream) {
         if (err != hipSuccess) return err;
         configured.fetch_or(bit, std::memory_order_release);
     }
+    if (p.wg_rows != kPWgRows) return hipErrorInvalidValue;  // the plan must be the one for this kernel's workgroups
     const unsigned grid = (unsigned)(p.chunk * kXcds);
     hipLaunchKernelGGL(swaa_fwd_pipelined_kernel, dim3(grid), dim3(kPThreads), kSmemBytes, stream, p);
     return hipGetLastError();
