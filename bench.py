@@ -324,7 +324,7 @@ def main():
                     "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": traffic, "traffic_source": traffic_source,
                     "kernel": (("swaa_bwd_dkv_dma_kernel + swaa_bwd_dq_pipelined_kernel + swaa_bwd_delta_kernel" if w.D == 128 else
                                 f"swaa_bwd_dkv_kernel<{w.D}> + swaa_bwd_dq_kernel<{w.D}> + swaa_bwd_delta_kernel") if w.backward
-                               else "swaa_fwd_pipelined_kernel" if w.D == 128 and w.fmt == "bf16"
+                               else "swaa_fwd_pipelined_kernel" if w.D == 128
                                else f"swaa_fwd_kernel<{w.D}>"),
                     "kernel_avg_ms": kern_avg_ms}
 

@@ -114,10 +114,9 @@ int swaa_attn_fwd_ex(const swaa_fwd_args *a) {
     p.G = Hq / Hkv;
     p.scale = a->scale;
     p.scale_log2 = a->scale * 1.44269504088896340736f;
-    // the pipelined kernel (bfloat16, head dimension 128) runs workgroups of 128 rows, two per
-    // compute unit; its softmax keeps a fixed reference and leans on bfloat16's fp32-sized
-    // exponent, so binary16 runs on the plain kernel, whose probabilities are <= 1
-    const bool pipelined = D == 128 && !p.fp16;
+    // the pipelined kernel (head dimension 128, either 16-bit format) runs workgroups of 128
+    // rows, two per compute unit; other head dimensions run on the plain kernel
+    const bool pipelined = D == 128;
     if (!swaa::plan_work(p, Nq, pipelined ? 128 : swaa::kWgRows)) return SWAA_ERR_SHAPE;
 
     hipStream_t s = static_cast<hipStream_t>(a->stream);

@@ -37,7 +37,6 @@
 //
 // This kernel declares no static LDS: its dynamic LDS starts at address 0 and
 // all LDS accesses below use plain byte addresses.
-#include <atomic>
 #include <type_traits>
 
 #include "swaa_tile_d128.h"
@@ -55,7 +54,7 @@ constexpr int kVRing = kStages * kTileBytes;          // V ring follows the K ri
 constexpr int kSmemBytes = 2 * kStages * kTileBytes;  // 64 KiB: two workgroups per compute unit
 constexpr int kStageBytes = kPRows * kD * 2;          // 8 KiB: a wave's 32 O rows on the way out (inside the K ring)
 constexpr int kFlagBase = kSmemBytes - 64;            // four flag words of the fallback vote (tail of the V ring)
-constexpr float kSumLimit = 1.0995116e12f;  // 2^40: a row sum that sends the workgroup back to the max-based path
+constexpr float kSumLimit = 1.2089258e24f;  // 2^80: a row sum that sends the workgroup back to the max-based path
 constexpr float kSumFloor = 7.8886091e-31f;  // 2^-100: so does one this small (every score far below the reference)
 constexpr int kPrefetch = 3;  // MFMAs between an LDS fragment read and its use
 
@@ -82,7 +81,10 @@ constexpr int kPrefetch = 3;  // MFMAs between an LDS fragment read and its use
 // fp32 or bf16 unless a score exceeds the reference by more than 2^7 in the exp2
 // domain, and the terms are never negative, so the final row sum bounds every
 // term and every partial sum: if it reaches kSumLimit (or is not a number) the
-// workgroup recomputes its rows with the max-based routine after the loop.  It
+// workgroup recomputes its rows with the max-based routine after the loop.
+// (2^80: scores up to 55 nats above the reference pass, and the products with V
+// in the O accumulators stay inside fp32 for |v| < 2^47; bf16 carries eight bits
+// of P at any magnitude, so nothing is lost by a reference far below the maximum.)  It
 // does the same if a row sum comes out below kSumFloor: a row whose first half
 // was invisible to it has reference 0, and if all its scores lie a hundred
 // binary orders below that, its terms leave the range fp32 resolves.
@@ -94,6 +96,7 @@ struct SoftmaxScratch {
 // first score element handled by chunk c: 16 scores over chunks 0..13
 __device__ __forceinline__ constexpr int chunk_first_elem(int c) { return c >= 14 ? 16 : (c * 16) / 14; }
 
+template <bool kF16>
 __device__ __forceinline__ void softmax_chunk(int c, const f32x16 &s, float c2, RowState &st, SoftmaxScratch &w,
                                               bf16x8 (&pf)[2]) {
 #pragma unroll
@@ -106,8 +109,9 @@ __device__ __forceinline__ void softmax_chunk(int c, const f32x16 &s, float c2, 
         for (int e = chunk_first_elem(c - 1); e < chunk_first_elem(c); ++e) {
             st.l += w.pe[e];
             if (e & 1) {  // the pair (e-1, e) is complete: pack it
-                pf[e / 8][(e - 1) % 8] = (__bf16)w.pe[e - 1];
-                pf[e / 8][e % 8] = (__bf16)w.pe[e];
+                const bf16x2 pr = pack_pair<kF16>(w.pe[e - 1], w.pe[e]);
+                pf[e / 8][(e - 1) % 8] = pr[0];
+                pf[e / 8][e % 8] = pr[1];
                 if (e % 8 == 7) pin_p(pf[e / 8]);
             }
         }
@@ -137,17 +141,23 @@ __device__ __forceinline__ void mask_scores(f32x16 &s, int k0h, int qpos, int W,
 // that of column 16 + j; lanes 0..15 hold them as elements 0 and 1.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+template <bool kF16>
 __device__ __forceinline__ bf16x8 rowsum_selector(int lane) {
     // A operand: lane l holds row l % 16, k-group l / 16
     const int m = lane & 15, kg = lane >> 4;
     const bool on = (m == 0 && (kg & 1) == 0) || (m == 1 && (kg & 1) == 1);
+    const bf16x2 one = pack_pair<kF16>(1.f, 1.f), zero = pack_pair<kF16>(0.f, 0.f);
     bf16x8 a;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) a[e] = on ? (__bf16)1.f : (__bf16)0.f;
+    for (int e = 0; e < 8; ++e) a[e] = on ? one[0] : zero[0];
     return a;
 }
+template <bool kF16>
 __device__ __forceinline__ void mfma_rowsum(f32x4 &acc, const bf16x8 sel_acc, const bf16x8 pfrag) {
-    asm("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "a"(sel_acc), "v"(pfrag));
+    if constexpr (kF16)
+        asm("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc) : "a"(sel_acc), "v"(pfrag));
+    else
+        asm("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "a"(sel_acc), "v"(pfrag));
 }
 // The sums of this lane's query column, from the two accumulators of the loop.
 // (They must be settled: other MFMAs lie between the loop and this.)
@@ -181,7 +191,7 @@ __device__ __forceinline__ bf16x8 load_slot(const LaneAddr &la, const HalfOffset
 // kPrefetchNext: on return fpre holds the first fragments of the following sub-step.
 // mask_cur / k0h_cur: whether the half whose softmax runs here (s_cur) needs the
 //   mask, and its first key.
-template <bool kHasS, bool kHasPV, bool kLoadFirst, bool kPrefetchNext>
+template <bool kF16, bool kHasS, bool kHasPV, bool kLoadFirst, bool kPrefetchNext>
 __device__ __forceinline__ void pipelined_substep(const LaneAddr &la, const HalfOffsets &ho, bf16x8 (&fpre)[kPrefetch],
                                                   const bf16x8 (&qf)[kKS], f32x16 &s_next, f32x16 &s_cur,
                                                   bf16x8 (&p_cur)[2], const bf16x8 (&p_prev)[2], f32x16 (&o)[kDB],
@@ -200,19 +210,19 @@ __device__ __forceinline__ void pipelined_substep(const LaneAddr &la, const Half
         if ((i & 1) == 0) {
             if (kHasS) {
                 if (i == 0)
-                    mfma_s_first(s_next, frag[i], qf[0]);
+                    mfma_s_first<kF16>(s_next, frag[i], qf[0]);
                 else
-                    mfma_s(s_next, frag[i], qf[i / 2]);
+                    mfma_s<kF16>(s_next, frag[i], qf[i / 2]);
             }
         } else if (kHasPV) {
-            mfma_acc(o[(i / 2) % kDB], frag[i], p_prev[(i / 2) / kDB]);
+            mfma_acc<kF16>(o[(i / 2) % kDB], frag[i], p_prev[(i / 2) / kDB]);
         }
         __builtin_amdgcn_sched_barrier(0);
         if (i == 0 && __builtin_expect(mask_cur, 0)) mask_scores(s_cur, k0h_cur, qpos, W, S, hf);
-        softmax_chunk(i, s_cur, c2, st, w, p_cur);
+        softmax_chunk<kF16>(i, s_cur, c2, st, w, p_cur);
         if (i == 15) {  // P^T of this half is complete (and two MFMAs old)
-            mfma_rowsum(lsum[0], sel, p_cur[0]);
-            mfma_rowsum(lsum[1], sel, p_cur[1]);
+            mfma_rowsum<kF16>(lsum[0], sel, p_cur[0]);
+            mfma_rowsum<kF16>(lsum[1], sel, p_cur[1]);
         }
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -222,6 +232,16 @@ __device__ __forceinline__ void pipelined_substep(const LaneAddr &la, const Half
     }
 }
 
+// kF16: q, k, v and out hold IEEE binary16 instead of bfloat16 (the precision the paper serves
+// its models in, Sec. 4.1.1).  Same kernel; what differs is the exponent range of P: binary16
+// ends at 65504, so the reference is set 2^4 below the first half's largest score (later
+// scores may exceed it by 2^12, about 8 nats, before a P overflows; smaller terms keep full
+// precision down to 2^-18 of it and fade out through the subnormals), and a P that did
+// overflow shows as a non-finite sum of the rounded P and sends the workgroup to the
+// max-based second pass; so does a sum of rounded P below 2^-6 (a row without a visible
+// key in its first half has reference 0, and if all its scores lie several nats below that
+// its terms are subnormal or vanish).
+template <bool kF16>
 __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const FwdParams p) {
     WorkItem wi;
     if (!decode_work(p, wi)) return;
@@ -379,7 +399,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     f32x4 lsum[2];  // column sums of the rounded P^T (mfma_rowsum), one accumulator per fragment
 #pragma unroll
     for (int e = 0; e < 4; ++e) lsum[0][e] = lsum[1][e] = 0.f;
-    bf16x8 sel = rowsum_selector(lane);
+    bf16x8 sel = rowsum_selector<kF16>(lane);
     asm volatile("s_nop 1" : "+a"(lsum[0]), "+a"(lsum[1]), "+a"(sel));
 
     // A wave needs no mask on a 32-key half when all its keys are visible to all
@@ -419,20 +439,20 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     rs.l = 0.f;
     rs.lb = 0.f;
     {
-        qk_half(la, 0u, qf, s_a);
+        qk_half<kF16>(la, 0u, qf, s_a);
         mask_scores(s_a, 32 * half_of(0), qpos, W, S, hf);
         float mx = s_a[0];
 #pragma unroll
         for (int e = 1; e < 16; ++e) mx = fmaxf(mx, s_a[e]);
         mx = half_swap_max(mx);
-        rs.mc = (mx == -INFINITY) ? 0.f : mx * c2;
+        rs.mc = (mx == -INFINITY) ? 0.f : mx * c2 - (kF16 ? 4.f : 0.f);
     }
 
     bf16x8 fpre[kPrefetch];  // first fragments of the second sub-step of a step, requested during the first
     // softmax of (tile 0, half 0) | scores of (tile 0, half 1); no P V product is due yet
     {
         const HalfOffsets h = {kHalfBytes, 0, 0, 0};
-        pipelined_substep<true, false, true, false>(la, h, fpre, qf, s_b, s_a, p_a, p_b, oacc, rs, lsum, sel, c2, false, 0,
+        pipelined_substep<kF16, true, false, true, false>(la, h, fpre, qf, s_b, s_a, p_a, p_b, oacc, rs, lsum, sel, c2, false, 0,
                                               qpos, W, S, hf);
     }
     // every wave is done with K(0), which is free afterwards
@@ -457,11 +477,11 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
         constexpr uint32_t vb0 = (1 - R) * kTileBytes, vb1 = vb0 + kHalfBytes;  // V(t-1)
         // softmax of (t-1, half 1) | scores of (t, half 0) | P V of (t-1, half 0)
         const HalfOffsets h1 = {kb0, vb0, kb1, vb1};
-        pipelined_substep<true, true, true, true>(la, h1, fpre, qf, s_a, s_b, p_b, p_a, oacc, rs, lsum, sel, c2, mask_p,
+        pipelined_substep<kF16, true, true, true, true>(la, h1, fpre, qf, s_a, s_b, p_b, p_a, oacc, rs, lsum, sel, c2, mask_p,
                                                   k0p, qpos, W, S, hf);
         // softmax of (t, half 0) | scores of (t, half 1) | P V of (t-1, half 1)
         const HalfOffsets h2 = {kb1, vb1, 0, 0};
-        pipelined_substep<true, true, false, false>(la, h2, fpre, qf, s_b, s_a, p_a, p_b, oacc, rs, lsum, sel, c2, mask_0,
+        pipelined_substep<kF16, true, true, false, false>(la, h2, fpre, qf, s_b, s_a, p_a, p_b, oacc, rs, lsum, sel, c2, mask_0,
                                                     k0, qpos, W, S, hf);
         // K(t+1), V(t) must have landed; K(t) and V(t-1) are free afterwards
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
@@ -516,10 +536,10 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
         const uint32_t vb = (uint32_t)(((J - 1) & 1) * kTileBytes);  // V(J-1)
         const int k0l = 32 * half_of(2 * J - 1);
         const HalfOffsets h = {0, vb, 0, 0};
-        pipelined_substep<false, true, true, false>(la, h, fpre, qf, s_a, s_b, p_b, p_a, oacc, rs, lsum, sel, c2,
+        pipelined_substep<kF16, false, true, true, false>(la, h, fpre, qf, s_a, s_b, p_b, p_a, oacc, rs, lsum, sel, c2,
                                                     half_masked(k0l), k0l, qpos, W, S, hf);
         // (the column sums of p_b, issued at the end of the sub-step, complete under these)
-        pv_half<true>(la, vb + kHalfBytes, p_b, oacc);
+        pv_half<true, kF16>(la, vb + kHalfBytes, p_b, oacc);
     }
 
     // ---- scores outgrew the reference somewhere in this workgroup (inputs with
@@ -537,7 +557,11 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
         // sequence (the ragged last tile; they may see no key at all) have no say.
         const bool in_range = (__float_as_uint(l_row) - (__float_as_uint(kSumFloor) + 1u)) <
                               (__float_as_uint(kSumLimit) - (__float_as_uint(kSumFloor) + 1u));
-        const int mine = __any(!in_range && r0 + l32 < Nq) ? 1 : 0;
+        // binary16: a P beyond 65504 became infinity, and the sum of the rounded P with it; and a
+        // row whose terms all sank into (or below) the subnormals has a small sum of rounded P
+        // (a row that took its reference from a visible key has a term of 2^4)
+        const bool p_sound = !kF16 || (__float_as_uint(lb_row) - 0x3c800000u) < (0x7f800000u - 0x3c800000u);  // [2^-6, inf)
+        const int mine = __any(!(in_range && p_sound) && r0 + l32 < Nq) ? 1 : 0;
         if (lane == 0) *(int __attribute__((address_space(3))) *)(uintptr_t)(kFlagBase + wave * 4) = mine;
         __syncthreads();
         int any = 0;
@@ -555,23 +579,33 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
         rs.mc = -INFINITY;
         rs.l = 0.f;
         rs.lb = 0.f;
+        // tiles alternate between the two buffers of each ring: the copy of tile j + 1 travels
+        // while tile j is worked on
+        __syncthreads();  // everyone has read the vote (its flag words lie inside the V ring)
+        issue_k(0, 0);
+        issue_v(0, 0);
         for (int j = 0; j < J; ++j) {
-            __syncthreads();  // everyone is done reading the previous tile
-            issue_k(j, 0);
-            issue_v(j, 0);
-            __builtin_amdgcn_s_waitcnt(0x0F70);
-            __syncthreads();
+            const uint32_t boff = (uint32_t)((j & 1) * kTileBytes);
+            if (j + 1 < J) {
+                issue_k(j + 1, (j + 1) & 1);
+                issue_v(j + 1, (j + 1) & 1);
+                __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8): all but the eight copies just issued
+            } else {
+                __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+            }
+            __syncthreads();  // tile j has landed for every wave
 #pragma unroll 1
             for (int hh = 0; hh < 2; ++hh) {
                 float alpha;
-                qk_half(la, (uint32_t)(hh * kHalfBytes), qf, s_a);
-                softmax_half<true>(s_a, 32 * half_of(2 * j + hh), qpos, W, S, hf, c2, rs, p_a, alpha);
+                qk_half<kF16>(la, boff + (uint32_t)(hh * kHalfBytes), qf, s_a);
+                softmax_half<true, kF16>(s_a, 32 * half_of(2 * j + hh), qpos, W, S, hf, c2, rs, p_a, alpha);
                 rescale(oacc, alpha);
-                pv_half<true>(la, (uint32_t)(hh * kHalfBytes), p_a, oacc);
+                pv_half<true, kF16>(la, boff + (uint32_t)(hh * kHalfBytes), p_a, oacc);
             }
+            __syncthreads();  // everyone is done with this buffer: tile j + 2 is copied into it next
         }
         row_sums(rs, l_row, lb_row);
-        __syncthreads();  // the rings become the O staging area below
+        // (after the loop's last barrier the rings are free: they become the O staging area below)
     }
 
     // ---- epilogue: O / (sum of the rounded P) -> bf16 through LDS (8 KiB per wave at the start
@@ -586,9 +620,9 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
         for (int db = 0; db < kDB; ++db) {
 #pragma unroll
             for (int e4 = 0; e4 < 4; ++e4) {
-                bf16x4 o4;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[db][4 * e4 + e] * inv_l);
+                const bf16x2 lo = pack_pair<kF16>(oacc[db][4 * e4 + 0] * inv_l, oacc[db][4 * e4 + 1] * inv_l);
+                const bf16x2 hi = pack_pair<kF16>(oacc[db][4 * e4 + 2] * inv_l, oacc[db][4 * e4 + 3] * inv_l);
+                const bf16x4 o4 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
                 // d = 32 db + 8 e4 + 4 hf + (0..3): 16-byte chunk 4 db + e4 of row l32, swizzled like K
                 *(bf16x4 __attribute__((address_space(3))) *)(uintptr_t)(o_lane ^ (uint32_t)((4 * db + e4) << 4)) = o4;
             }
@@ -609,21 +643,14 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
 }  // namespace
 
 hipError_t launch_fwd_pipelined_d128(const FwdParams &p, hipStream_t stream) {
-    // (64 KiB of dynamic LDS is the most a kernel gets without asking; asking is harmless)
-    static std::atomic<unsigned long long> configured{0};
-    int dev = 0;
-    hipError_t err = hipGetDevice(&dev);
-    if (err != hipSuccess) return err;
-    const unsigned long long bit = 1ull << (dev & 63);
-    if (!(configured.load(std::memory_order_acquire) & bit)) {
-        err = hipFuncSetAttribute(reinterpret_cast<const void *>(&swaa_fwd_pipelined_kernel),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, kSmemBytes);
-        if (err != hipSuccess) return err;
-        configured.fetch_or(bit, std::memory_order_release);
-    }
     if (p.wg_rows != kPWgRows) return hipErrorInvalidValue;  // the plan must be the one for this kernel's workgroups
     const unsigned grid = (unsigned)(p.chunk * kXcds);
-    hipLaunchKernelGGL(swaa_fwd_pipelined_kernel, dim3(grid), dim3(kPThreads), kSmemBytes, stream, p);
+    // (64 KiB of dynamic LDS is what a kernel gets without asking)
+    static_assert(kSmemBytes <= 64 * 1024, "more would need hipFuncSetAttribute");
+    if (p.fp16)
+        hipLaunchKernelGGL(swaa_fwd_pipelined_kernel<true>, dim3(grid), dim3(kPThreads), kSmemBytes, stream, p);
+    else
+        hipLaunchKernelGGL(swaa_fwd_pipelined_kernel<false>, dim3(grid), dim3(kPThreads), kSmemBytes, stream, p);
     return hipGetLastError();
 }
 

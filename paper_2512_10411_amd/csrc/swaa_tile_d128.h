@@ -30,22 +30,63 @@ constexpr float kRefSlack = 8.f;  // log2 units a row maximum may exceed its ref
 //       asm statement as the last MFMA of a chain (*_settled below); settle_*
 //       alone is only safe where other MFMAs lie between producer and reader.
 // tests/test_asm_hazards.py checks both on the generated assembly.
+// kF16: the 16-bit operands are IEEE binary16 instead of bfloat16.  Fragments are carried
+// in bf16x8 registers either way (eight 16-bit lanes; only the MFMA's mnemonic and the
+// float -> 16-bit conversions look at the format).
+template <bool kF16 = false>
 __device__ __forceinline__ void mfma_acc(f32x16 &acc, const bf16x8 a, const bf16x8 b) {
-    asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+    if constexpr (kF16)
+        asm("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+    else
+        asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 // S^T accumulator: VGPR destination, Q operand read straight from AccVGPRs.
+template <bool kF16 = false>
 __device__ __forceinline__ void mfma_s(f32x16 &s, const bf16x8 kfrag, const bf16x8 q_acc) {
-    asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(kfrag), "a"(q_acc));
+    if constexpr (kF16)
+        asm("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(s) : "v"(kfrag), "a"(q_acc));
+    else
+        asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(kfrag), "a"(q_acc));
 }
+template <bool kF16 = false>
 __device__ __forceinline__ void mfma_s_first(f32x16 &s, const bf16x8 kfrag, const bf16x8 q_acc) {
-    asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(kfrag), "a"(q_acc));
+    if constexpr (kF16)
+        asm("v_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&v"(s) : "v"(kfrag), "a"(q_acc));
+    else
+        asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(kfrag), "a"(q_acc));
 }
 // Last MFMA of a chain whose result the vector ALU reads next.
+template <bool kF16 = false>
 __device__ __forceinline__ void mfma_s_settled(f32x16 &s, const bf16x8 kfrag, const bf16x8 q_acc) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\ts_nop 15\n\ts_nop 7" : "+v"(s) : "v"(kfrag), "a"(q_acc));
+    if constexpr (kF16)
+        asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0\n\ts_nop 15\n\ts_nop 7" : "+v"(s) : "v"(kfrag), "a"(q_acc));
+    else
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\ts_nop 15\n\ts_nop 7" : "+v"(s) : "v"(kfrag), "a"(q_acc));
 }
+template <bool kF16 = false>
 __device__ __forceinline__ void mfma_acc_settled(f32x16 &acc, const bf16x8 a, const bf16x8 b) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\ts_nop 15\n\ts_nop 7" : "+a"(acc) : "v"(a), "v"(b));
+    if constexpr (kF16)
+        asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0\n\ts_nop 15\n\ts_nop 7" : "+a"(acc) : "v"(a), "v"(b));
+    else
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\ts_nop 15\n\ts_nop 7" : "+a"(acc) : "v"(a), "v"(b));
+}
+// Two floats -> two 16-bit elements of the chosen format (round to nearest even), as the
+// bit pattern of two fragment lanes.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+template <bool kF16>
+__device__ __forceinline__ bf16x2 pack_pair(float a, float b) {
+    if constexpr (kF16) {
+        typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+        f16x2 h;
+        h[0] = (_Float16)a;
+        h[1] = (_Float16)b;
+        return __builtin_bit_cast(bf16x2, h);
+    } else {
+        bf16x2 r;
+        r[0] = (__bf16)a;
+        r[1] = (__bf16)b;
+        return r;
+    }
 }
 // Makes the compiler hold `o` in AccVGPRs at this point (placed after every
 // plain C++ write to the accumulators so that the value carried around the key
@@ -102,23 +143,24 @@ __device__ __forceinline__ bf16x8 load_v_frag(const LaneAddr &la, uint32_t boff,
 }
 
 // S^T (32 keys x 32 queries) = K_half Q^T; the result is ready for the vector ALU on return
+template <bool kF16 = false>
 __device__ __forceinline__ void qk_half(const LaneAddr &la, uint32_t kboff, const bf16x8 (&qf)[kKS], f32x16 &s) {
 #pragma unroll
     for (int ks = 0; ks < kKS; ++ks) {
         const bf16x8 a = load_k_frag(la, kboff, ks);
         if (ks == 0)
-            mfma_s_first(s, a, qf[ks]);
+            mfma_s_first<kF16>(s, a, qf[ks]);
         else if (ks < kKS - 1)
-            mfma_s(s, a, qf[ks]);
+            mfma_s<kF16>(s, a, qf[ks]);
         else
-            mfma_s_settled(s, a, qf[ks]);
+            mfma_s_settled<kF16>(s, a, qf[ks]);
     }
 }
 
 // O^T (128 x 32 queries) += V_half^T P^T.  kSettle: the accumulators are ready for
 // the vector ALU on return (all MFMAs complete in order, so waiting out the last
 // one covers the four chains).
-template <bool kSettle>
+template <bool kSettle, bool kF16 = false>
 __device__ __forceinline__ void pv_half(const LaneAddr &la, uint32_t vboff, const bf16x8 (&pf)[2], f32x16 (&o)[kDB]) {
 #pragma unroll
     for (int st = 0; st < 2; ++st) {
@@ -126,9 +168,9 @@ __device__ __forceinline__ void pv_half(const LaneAddr &la, uint32_t vboff, cons
         for (int db = 0; db < kDB; ++db) {
             const bf16x8 a = load_v_frag(la, vboff, st, db);
             if (kSettle && st == 1 && db == kDB - 1)
-                mfma_acc_settled(o[db], a, pf[st]);
+                mfma_acc_settled<kF16>(o[db], a, pf[st]);
             else
-                mfma_acc(o[db], a, pf[st]);
+                mfma_acc<kF16>(o[db], a, pf[st]);
         }
     }
 }
@@ -142,8 +184,6 @@ struct RowState {
     float lb;  // share of the sum of the same terms after rounding to bf16: the divisor of O
 };
 
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-
 // acc + lo + hi for two entries of P as the P V contraction sees them.  The
 // contraction weights V with the rounded entries, so O has to be divided by
 // their sum: then the weights add up to one whatever the rounding did to them,
@@ -151,11 +191,20 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // when its reference is not its own score.  (Dividing by the fp32 sum leaves a
 // relative error of up to 2^-9 in such a row, a whole bf16 step after the
 // final rounding.)  One dot-product instruction per pair.
+template <bool kF16 = false>
 __device__ __forceinline__ float add_rounded_pair(float acc, bf16x2 pr) {
-    bf16x2 one;
-    one[0] = (__bf16)1.f;
-    one[1] = (__bf16)1.f;
-    return __builtin_amdgcn_fdot2_f32_bf16(pr, one, acc, false);
+    if constexpr (kF16) {
+        typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+        f16x2 one;
+        one[0] = (_Float16)1.f;
+        one[1] = (_Float16)1.f;
+        return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, pr), one, acc, false);
+    } else {
+        bf16x2 one;
+        one[0] = (__bf16)1.f;
+        one[1] = (__bf16)1.f;
+        return __builtin_amdgcn_fdot2_f32_bf16(pr, one, acc, false);
+    }
 }
 
 __device__ __forceinline__ void row_sums(const RowState &st, float &l, float &lb) {
@@ -168,7 +217,7 @@ __device__ __forceinline__ void row_sums(const RowState &st, float &l, float &lb
 // with slack, exponentials, row sum, bf16 P^T fragments.  alpha is the factor
 // the O accumulator must be multiplied with (1 when the reference stays).  The
 // scores must be settled (qk_half leaves them so).
-template <bool kMask>
+template <bool kMask, bool kF16 = false>
 __device__ __forceinline__ void softmax_half(f32x16 &s, int k0h, int qpos, int W, int S, int hf, float c2, RowState &st,
                                              bf16x8 (&pf)[2], float &alpha) {
     if (kMask) {
@@ -195,12 +244,10 @@ __device__ __forceinline__ void softmax_half(f32x16 &s, int k0h, int qpos, int W
         const float p0 = __builtin_amdgcn_exp2f(fmaf(s[e], c2, -mc_use));
         const float p1 = __builtin_amdgcn_exp2f(fmaf(s[e + 1], c2, -mc_use));
         rs += p0 + p1;
-        bf16x2 pr;
-        pr[0] = (__bf16)p0;
-        pr[1] = (__bf16)p1;
+        const bf16x2 pr = pack_pair<kF16>(p0, p1);
         pf[e / 8][e % 8] = pr[0];
         pf[e / 8][e % 8 + 1] = pr[1];
-        rb = add_rounded_pair(rb, pr);
+        rb = add_rounded_pair<kF16>(rb, pr);
     }
     st.l = st.l * alpha + rs;  // (alpha is the same in both lanes of a column)
     st.lb = st.lb * alpha + rb;

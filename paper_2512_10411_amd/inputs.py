@@ -101,6 +101,9 @@ WORKLOADS = {
     # and with isolated keys, one per 2048 positions deep inside the windows, that score about 42
     # nats above everything else: scores that outgrow a softmax reference taken from the first keys
     "mid_spike": Workload("mid_spike", 1, 32, 8, 16384, 128, 2048, 4, _SEED0 + 2, recipe="late_spike"),
+    # the same with 80 nats: beyond what the pipelined kernel's fixed softmax reference covers, so
+    # every workgroup takes its max-based second pass (the cost of that fallback)
+    "mid_spike80": Workload("mid_spike80", 1, 32, 8, 16384, 128, 2048, 4, _SEED0 + 2, recipe="late_spike80"),
 }
 
 
@@ -110,7 +113,8 @@ def apply_recipe(w: Workload, q: np.ndarray, k: np.ndarray):
     Component 0 of every query becomes 3 and that of every key 0, so that a key whose
     component 0 is set to c scores 3 c / sqrt(D) nats above the rest for every query.
       sink_heavy: the first n_sink keys get c = 48 (about 12.7 nats at D = 128);
-      late_spike: keys 1500, 3548, 5596, ... (one per 2048 positions) get c = 160 (42 nats).
+      late_spike: keys 1500, 3548, 5596, ... (one per 2048 positions) get c = 160 (42 nats);
+      late_spike80: the same keys get c = 304 (80 nats).
     """
     if w.recipe == "iid":
         return
@@ -122,6 +126,8 @@ def apply_recipe(w: Workload, q: np.ndarray, k: np.ndarray):
         k[:, :, :w.n_sink, 0] = bits(48.0)
     elif w.recipe == "late_spike":
         k[:, :, 1500::2048, 0] = bits(160.0)
+    elif w.recipe == "late_spike80":
+        k[:, :, 1500::2048, 0] = bits(304.0)
     else:
         raise ValueError(f"unknown recipe {w.recipe}")
 

@@ -42,7 +42,8 @@ def test_small_shapes(D):
 
 
 def test_sink_heavy_scores_keep_probabilities_in_range():
-    # scores tens of nats apart: the plain kernel's probabilities never exceed 1, so binary16 cannot overflow
+    # scores tens of nats apart (k scaled by 4): later keys outgrow the reference taken from the
+    # first half tile by more than binary16 holds in places, which must end in the max-based pass
     B, Hq, Hkv, N, D = 1, 4, 1, 2000, 128
     q, k, v = make_qkv(B, Hq, Hkv, N, D, seed=9720, k_mult=4.0, fmt="fp16")
     out, lse = binding.swaa_attn_fwd_ex(to_device(q, "fp16"), to_device(k, "fp16"), to_device(v, "fp16"), 512, 4)
@@ -50,6 +51,51 @@ def test_sink_heavy_scores_keep_probabilities_in_range():
     with input_format("fp16"):
         ro, rl = swaa_attn_oracle(q, k, v, 512, 4, 1 / math.sqrt(D))
     assert_parity(out, lse, ro, rl, tag="fp16 peaked softmax")
+
+
+@pytest.mark.parametrize("spike", [0.0, 24.0, 40.0, 160.0])
+def test_late_score_spike_against_the_binary16_range(spike):
+    # one key deep inside the windows scores 3 * spike / sqrt(D) nats above the rest: 6 nats stay
+    # inside binary16 with the fixed reference (P up to 2^13), 10 nats and more overflow a P and
+    # must be caught; a very negative key and small values ride along
+    B, Hq, Hkv, N, D, W, S = 1, 4, 1, 3100, 128, 1024, 4
+    q, k, v = make_qkv(B, Hq, Hkv, N, D, seed=9740, fmt="fp16")
+    qf = q.view(np.float16).astype(np.float32)
+    kf = k.view(np.float16).astype(np.float32)
+    qf[..., 0] = 3.0
+    kf[..., 0] = 0.0
+    kf[:, :, 2500, 0] = spike
+    kf[:, :, 2700, 0] = -spike
+    q = qf.astype(np.float16).view(np.uint16)
+    k = kf.astype(np.float16).view(np.uint16)
+    scale = 1 / math.sqrt(D)
+    out, lse = binding.swaa_attn_fwd_ex(to_device(q, "fp16"), to_device(k, "fp16"), to_device(v, "fp16"), W, S, None, scale)
+    torch.cuda.synchronize()
+    with input_format("fp16"):
+        ro, rl = swaa_attn_oracle(q, k, v, W, S, scale)
+    assert_parity(out, lse, ro, rl, tag=f"fp16 late spike {spike}")
+
+
+def test_all_scores_far_below_the_reference():
+    # rows whose first visited half tile is invisible to them start from reference 0; with every
+    # score near -30 nats their binary16 probabilities vanish altogether and the kernel has to
+    # notice (the sum of the rounded P is zero although the fp32 sum is in range)
+    B, H, N, D, W, S = 1, 2, 900, 128, 70, 0
+    scale = 1 / math.sqrt(D)
+    q, k, v = make_qkv(B, H, H, N, D, seed=9750, fmt="fp16")
+    qf = q.view(np.float16).astype(np.float32)
+    kf = k.view(np.float16).astype(np.float32)
+    a = math.sqrt(30.0 / scale)
+    qf[..., 0] = a
+    kf[..., 0] = -a
+    q = qf.astype(np.float16).view(np.uint16)
+    k = kf.astype(np.float16).view(np.uint16)
+    out, lse = binding.swaa_attn_fwd_ex(to_device(q, "fp16"), to_device(k, "fp16"), to_device(v, "fp16"), W, S, None, scale)
+    torch.cuda.synchronize()
+    with input_format("fp16"):
+        ro, rl = swaa_attn_oracle(q, k, v, W, S, scale)
+    assert float(rl.max()) < -15.0
+    assert_parity(out, lse, ro, rl, tag="fp16 scores far below the reference")
 
 
 def test_mid_size_sampled_rows():

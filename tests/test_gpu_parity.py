@@ -138,7 +138,7 @@ def test_sink_heavy_scores_stress_rescaling():
     assert_parity(out, lse, ro, rl, tag="sink heavy")
 
 
-@pytest.mark.parametrize("spike", [40.0, 160.0, 1024.0])
+@pytest.mark.parametrize("spike", [40.0, 160.0, 216.0, 304.0, 1024.0])
 def test_late_score_spike_far_above_the_first_keys(spike):
     # interior tiles do not search for the row maximum; a key whose score
     # exceeds everything seen before by tens of nats must still come out right
@@ -154,6 +154,29 @@ def test_late_score_spike_far_above_the_first_keys(spike):
     out, lse = run_gpu(q, k, v, W, S, scale)
     ro, rl = swaa_attn_oracle(q, k, v, W, S, scale)
     assert_parity(out, lse, ro, rl, tag=f"late spike {spike}")
+
+
+def test_non_finite_key_rows_reach_only_the_rows_that_see_them():
+    # Locality of the mask on the GPU (the oracle's own locality is pinned on the CPU): NaN and
+    # infinity in a few key rows.  A row that does not see such a key -- it lies in the row's
+    # future, or behind its window and outside the sinks -- must come out exactly as the oracle
+    # has it, although the key sits inside a half tile the row's wave visits (its diagonal half,
+    # its band's first half); rows that do see it are left out of the comparison.
+    B, Hq, Hkv, N, D, W, S = 1, 8, 2, 1500, 128, 100, 4
+    q, k, v = make_qkv(B, Hq, Hkv, N, D, seed=4910)
+    poisoned = {500: 0x7FC0, 777: 0x7F80, 778: 0xFF80, 1290: 0xFFC1}  # NaN, +inf, -inf, another NaN pattern
+    for j, bits in poisoned.items():
+        k[:, :, j, 5::7] = np.uint16(bits)
+    scale = 1 / math.sqrt(D)
+    out, lse = run_gpu(q, k, v, W, S, scale)
+    touched = set()
+    for j in poisoned:
+        touched.update(range(j, min(N, j + W)))
+    rows = np.array([i for i in range(N) if i not in touched], dtype=np.int32)
+    assert len(rows) > N // 2
+    ro, rl = swaa_attn_oracle(q, k, v, W, S, scale, rows=rows)
+    assert np.isfinite(ro).all() and np.isfinite(rl).all()
+    assert_parity(out, lse, ro, rl, rows=rows, tag="non-finite invisible keys")
 
 
 @pytest.mark.parametrize("level", [-40.0, -200.0, -3000.0])
