@@ -55,7 +55,8 @@ typedef enum swaa_status {
  *   lse  device, fp32 [B, Hq, N], contiguous, written
  *   B, Hq, Hkv, N >= 1; Hq a multiple of Hkv (query head h reads KV head
  *        h / (Hq/Hkv)); N * D * max(Hq, Hkv) * B must fit in 2^62 elements
- *   D    head dimension: 64 or 128
+ *   D    head dimension: a multiple of 32 up to 256 (128 has the tuned, software-pipelined
+ *        kernel; the others run on a plain tiled kernel)
  *   window  >= 1; any value >= N means full causal attention
  *   n_sink  >= 0; values >= N behave as N
  *   scale   finite and > 0 (callers normally pass 1/sqrt(D))
@@ -127,7 +128,7 @@ int swaa_attn_fwd_fa_decode(const void *q, const void *k, const void *v, void *o
  */
 typedef enum swaa_dtype {
     SWAA_BF16 = 0, /* bfloat16: every kernel */
-    SWAA_F16 = 1   /* IEEE binary16 (the precision the paper serves in, Sec. 4.1.1): the plain forward kernel */
+    SWAA_F16 = 1   /* IEEE binary16 (the precision the paper serves in, Sec. 4.1.1) */
 } swaa_dtype;
 
 typedef struct swaa_tensor {
@@ -142,7 +143,7 @@ typedef struct swaa_fwd_args {
     swaa_tensor out; /* bf16, Hq heads, query rows; written; must not overlap the inputs */
     float *lse;      /* fp32, written */
     long long lse_stride_b, lse_stride_h;
-    int B, Hq, Hkv, D;      /* D: 64 or 128 */
+    int B, Hq, Hkv, D;      /* D: a multiple of 32 up to 256 */
     int Nq, Nk;             /* query rows and keys per sequence (upper bounds for packed batches) */
     const int *cu_seqlens_q; /* device, B + 1 ints, or NULL */
     const int *cu_seqlens_k; /* device, B + 1 ints, or NULL */

@@ -50,7 +50,7 @@ const char *swaa_status_string(int status) {
         case SWAA_OK: return "ok";
         case SWAA_ERR_NULL: return "null pointer argument";
         case SWAA_ERR_SHAPE: return "size, window, sink count, prompt length or scale out of range";
-        case SWAA_ERR_UNSUPPORTED: return "unsupported head dimension (64 and 128 are built)";
+        case SWAA_ERR_UNSUPPORTED: return "unsupported head dimension or element type (forward: multiples of 32 up to 256; decode: 128; backward: 64 and 128)";
         case SWAA_ERR_ALIGN: return "pointer not 16-byte aligned";
         case SWAA_ERR_LAUNCH: return "HIP launch failed";
         case SWAA_ERR_WORKSPACE: return "workspace missing, misaligned or too small (or the call needs more scratch than the static array holds)";
@@ -80,7 +80,7 @@ int swaa_attn_fwd_ex(const swaa_fwd_args *a) {
     const bool packed = a->cu_seqlens_q != nullptr || a->cu_seqlens_k != nullptr;
     if (packed && (!a->cu_seqlens_q || !a->cu_seqlens_k)) return SWAA_ERR_NULL;
     if (!packed && Nq > Nk) return SWAA_ERR_SHAPE;  // the query rows are the newest Nq of Nk tokens
-    if (D != 64 && D != 128) return SWAA_ERR_UNSUPPORTED;
+    if (D % 32 != 0 || D > 256) return SWAA_ERR_UNSUPPORTED;
     if (a->dtype != SWAA_BF16 && a->dtype != SWAA_F16) return SWAA_ERR_UNSUPPORTED;
     for (const swaa_tensor *t : {&a->q, &a->k, &a->v, &a->out}) {
         const int heads = (t == &a->k || t == &a->v) ? Hkv : Hq;
@@ -117,7 +117,7 @@ int swaa_attn_fwd_ex(const swaa_fwd_args *a) {
     // the pipelined kernel (head dimension 128, either 16-bit format) runs workgroups of 128
     // rows, two per compute unit; other head dimensions run on the plain kernel
     const bool pipelined = D == 128;
-    if (!swaa::plan_work(p, Nq, pipelined ? 128 : swaa::kWgRows)) return SWAA_ERR_SHAPE;
+    if (!swaa::plan_work(p, Nq, pipelined ? 128 : swaa::fwd_simple_wg_rows(D))) return SWAA_ERR_SHAPE;
 
     hipStream_t s = static_cast<hipStream_t>(a->stream);
     const hipError_t err = pipelined ? swaa::launch_fwd_pipelined_d128(p, s) : swaa::launch_fwd_simple(p, D, s);

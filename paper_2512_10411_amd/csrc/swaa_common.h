@@ -167,7 +167,10 @@ __device__ __forceinline__ float half_swap_sum(float x) {
 }
 
 // Launchers (one per kernel family); return the HIP error of the launch.
+// (the plain kernel: head dimensions 32 .. 256 in steps of 32 except 128; its workgroups hold
+// fwd_simple_wg_rows(D) query rows)
 hipError_t launch_fwd_simple(const FwdParams &p, int D, hipStream_t stream);
+int fwd_simple_wg_rows(int D);
 hipError_t launch_fwd_pipelined_d128(const FwdParams &p, hipStream_t stream);
 
 }  // namespace swaa

@@ -6,12 +6,16 @@
 // schedule and the register layout below are this library's own design for
 // CDNA4; the paper only says that the mask lives inside a flash-style kernel.
 //
+// This is the plain kernel: it serves every head dimension that is a multiple of
+// 32 up to 256 except 128, which has the software-pipelined kernel of its own.
+//
 // Shape of the kernel
 //   * One workgroup = 4 wavefronts = 256 "query rows" that share one KV head:
 //     hpb query heads (4, 2 or 1) x 256/hpb consecutive positions.  Each wave
 //     owns 64 positions of one head, so K/V tiles staged in LDS are reused by
 //     every query head of the GQA group and the dense band per wave is only
-//     W + 64 keys wide.
+//     W + 64 keys wide.  (Head dimensions above 128: 32 positions per wave, 128
+//     rows per workgroup, so that O^T and Q still fit the register file.)
 //   * KV tiles of 64 keys.  A workgroup visits only the tiles that hold sink
 //     keys [0, S) or band keys (first position - W, last position]; a wave
 //     skips the MFMA work of tiles that lie outside its own 64 positions' band
@@ -35,7 +39,8 @@ template <int D>
 struct Tile {
     static constexpr int kChunksPerRow = D / 8;                        // 16-byte chunks
     static constexpr int kChunks = kBk * kChunksPerRow;                // per K or V tile
-    static constexpr int kChunksPerThread = kChunks / kThreads;       // 4 (D=128) or 2 (D=64)
+    static constexpr int kChunksPerThread = kChunks / kThreads;       // D / 32
+    static_assert(D % 32 == 0 && D >= 32 && D <= 256, "head dimension: a multiple of 32 up to 256");
     static constexpr int kKStride = D + 8;                             // bf16 elements, K rows
     static constexpr int kVStride = D + 32;                            // bf16 elements, V rows
     static constexpr int kKElems = kBk * kKStride;
@@ -65,7 +70,8 @@ struct Elem<_Float16> {
     }
 };
 
-template <int D, typename E>
+// QB: 32-row blocks of query positions per wave (2, or 1 for head dimensions above 128)
+template <int D, typename E, int QB>
 __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p) {
     using T = Tile<D>;
     using X = Elem<E>;
@@ -73,9 +79,12 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
     using x4 = typename X::x4;
     constexpr int KS = D / 16;  // k-steps of the QK^T contraction
     constexpr int DB = D / 32;  // 32-wide blocks of the head dimension
+    constexpr int kWaveRows = 32 * QB;           // (hides the namespace's constants of the same names)
+    constexpr int kWgRows = 4 * kWaveRows;
 
-    __shared__ __attribute__((aligned(16))) E Ks[T::kKElems];
-    __shared__ __attribute__((aligned(16))) E Vs[T::kVElems];
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    E *Ks = reinterpret_cast<E *>(smem_raw);
+    E *Vs = Ks + T::kKElems;
 
     WorkItem wi;
     if (!decode_work(p, wi)) return;
@@ -117,9 +126,9 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
     E *og = reinterpret_cast<E *>(p.out) + sg.q_batch * p.o_sb + (long long)head * p.o_sh + sg.q_row0 * p.o_sn;
 
     // ---- Q fragments (B operand of S^T = K Q^T), kept for the whole loop ----
-    x8 qf[2][KS];
+    x8 qf[QB][KS];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
         const int row = min(r0 + 32 * qb + l32, Nq - 1);
         const E *src = qg + (size_t)row * p.q_sn + 8 * hf;
 #pragma unroll
@@ -127,15 +136,19 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
             qf[qb][ks] = *reinterpret_cast<const x8 *>(src + 16 * ks);
     }
 
-    f32x16 oacc[DB][2];
+    f32x16 oacc[DB][QB];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
+        for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
             for (int e = 0; e < 16; ++e) oacc[db][qb][e] = 0.f;
-    float m_run[2] = {-INFINITY, -INFINITY};
-    float l_run[2] = {0.f, 0.f};
+    float m_run[QB], l_run[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        m_run[qb] = -INFINITY;
+        l_run[qb] = 0.f;
+    }
 
     // ---- staging: global -> registers -> LDS --------------------------------
     u32x4 kreg[T::kChunksPerThread], vreg[T::kChunksPerThread];
@@ -186,11 +199,11 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
             const bool unmasked = (k_last <= p0) && ((k0 > wbound) || (k_last < S));
 
             // ---- S^T = K Q^T : [64 keys] x [64 queries] ----
-            f32x16 sacc[2][2];
+            f32x16 sacc[2][QB];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int qb = 0; qb < 2; ++qb)
+                for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
                     for (int e = 0; e < 16; ++e) sacc[kb][qb][e] = 0.f;
 #pragma unroll
@@ -200,7 +213,7 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
                     const x8 a = *reinterpret_cast<const x8 *>(
                         &Ks[(32 * kb + l32) * T::kKStride + 16 * ks + 8 * hf]);
 #pragma unroll
-                    for (int qb = 0; qb < 2; ++qb)
+                    for (int qb = 0; qb < QB; ++qb)
                         sacc[kb][qb] = X::mfma(a, qf[qb][ks], sacc[kb][qb]);
                 }
             }
@@ -208,7 +221,7 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
             // ---- mask (edge tiles only) ----
             if (!unmasked) {
 #pragma unroll
-                for (int qb = 0; qb < 2; ++qb) {
+                for (int qb = 0; qb < QB; ++qb) {
                     const int qpos = p0 + 32 * qb + l32;
                     const int wq = (qpos >= P) ? Nk : W;  // a generated token's window is the whole prefix
 #pragma unroll
@@ -223,10 +236,10 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
             }
 
             // ---- online softmax; P^T packed to bf16 in B-operand order ----
-            x8 pf[2][2][2];  // [kb][qb][16-key step]
-            float alpha[2];
+            x8 pf[2][QB][2];  // [kb][qb][16-key step]
+            float alpha[QB];
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
+            for (int qb = 0; qb < QB; ++qb) {
                 float mx = sacc[0][qb][0];
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
@@ -252,11 +265,14 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
                 m_run[qb] = m_new;
             }
             // rescale O only if some row maximum in this wave moved
-            if (__any((alpha[0] != 1.f) || (alpha[1] != 1.f))) {
+            bool moved = false;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) moved = moved || (alpha[qb] != 1.f);
+            if (__any(moved)) {
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
 #pragma unroll
-                    for (int qb = 0; qb < 2; ++qb)
+                    for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
                         for (int e = 0; e < 16; ++e) oacc[db][qb][e] *= alpha[qb];
             }
@@ -284,7 +300,7 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
                         const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                         const x8 a = __builtin_bit_cast(x8, av);
 #pragma unroll
-                        for (int qb = 0; qb < 2; ++qb)
+                        for (int qb = 0; qb < QB; ++qb)
                             oacc[db][qb] = X::mfma(a, pf[kb][qb][st], oacc[db][qb]);
                     }
                 }
@@ -301,7 +317,7 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
     // ---- epilogue: O / l -> bf16, lse = m*scale + ln(l) ----------------------
     if (!wave_active) return;
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
         const int row = r0 + 32 * qb + l32;
         if (row >= Nq) continue;
         const float inv_l = 1.f / l_run[qb];
@@ -324,19 +340,45 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
 
 }  // namespace
 
-hipError_t launch_fwd_simple(const FwdParams &p, int D, hipStream_t stream) {
-    const unsigned grid = (unsigned)(p.chunk * kXcds);
-    if (p.fp16) {
-        if (D == 128)
-            hipLaunchKernelGGL((swaa_fwd_kernel<128, _Float16>), dim3(grid), dim3(kThreads), 0, stream, p);
-        else
-            hipLaunchKernelGGL((swaa_fwd_kernel<64, _Float16>), dim3(grid), dim3(kThreads), 0, stream, p);
-    } else if (D == 128) {
-        hipLaunchKernelGGL((swaa_fwd_kernel<128, __bf16>), dim3(grid), dim3(kThreads), 0, stream, p);
-    } else {
-        hipLaunchKernelGGL((swaa_fwd_kernel<64, __bf16>), dim3(grid), dim3(kThreads), 0, stream, p);
+namespace {
+
+template <int D, typename E>
+hipError_t launch_one(const FwdParams &p, hipStream_t stream) {
+    constexpr int QB = D > 128 ? 1 : 2;
+    using T = Tile<D>;
+    constexpr int kBytes = (T::kKElems + T::kVElems) * 2;
+    if (p.wg_rows != 4 * 32 * QB) return hipErrorInvalidValue;  // the plan must be the one for this instantiation
+    auto kernel = swaa_fwd_kernel<D, E, QB>;
+    if (kBytes > 64 * 1024) {
+        // more than 64 KiB of dynamic LDS has to be asked for (harmless to repeat)
+        const hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, kBytes);
+        if (err != hipSuccess) return err;
     }
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(p.chunk * kXcds)), dim3(kThreads), kBytes, stream, p);
     return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_format(const FwdParams &p, hipStream_t stream) {
+    return p.fp16 ? launch_one<D, _Float16>(p, stream) : launch_one<D, __bf16>(p, stream);
+}
+
+}  // namespace
+
+int fwd_simple_wg_rows(int D) { return D > 128 ? 128 : 256; }
+
+hipError_t launch_fwd_simple(const FwdParams &p, int D, hipStream_t stream) {
+    switch (D) {
+        case 32: return launch_format<32>(p, stream);
+        case 64: return launch_format<64>(p, stream);
+        case 96: return launch_format<96>(p, stream);
+        case 160: return launch_format<160>(p, stream);
+        case 192: return launch_format<192>(p, stream);
+        case 224: return launch_format<224>(p, stream);
+        case 256: return launch_format<256>(p, stream);
+        default: return hipErrorInvalidValue;  // (128 has the pipelined kernel)
+    }
 }
 
 }  // namespace swaa

@@ -61,7 +61,8 @@ def test_argument_errors_are_reported_before_any_launch():
     assert call(scale=0.0) == binding.SWAA_ERR_SHAPE
     assert call(scale=float("nan")) == binding.SWAA_ERR_SHAPE
     assert call(scale=float("inf")) == binding.SWAA_ERR_SHAPE
-    assert call(D=96) == binding.SWAA_ERR_UNSUPPORTED
+    assert call(D=80) == binding.SWAA_ERR_UNSUPPORTED
+    assert call(D=288) == binding.SWAA_ERR_UNSUPPORTED
     assert call(k=p + 8) == binding.SWAA_ERR_ALIGN
     assert call(o=p + 2) == binding.SWAA_ERR_ALIGN
     for code in (0, -1, -2, -3, -4, -5, -99):
@@ -85,7 +86,7 @@ def test_fa_decode_pair_count_and_argument_errors():
     f = binding.swaa_attn_fwd_fa_decode_raw
     assert f(p, p, p, p, p, 1, 4, 2, 128, 128, 16, 2, -1, 0.1, None) == binding.SWAA_ERR_SHAPE
     assert f(p, p, None, p, p, 1, 4, 2, 128, 128, 16, 2, 64, 0.1, None) == binding.SWAA_ERR_NULL
-    assert f(p, p, p, p, p, 1, 4, 2, 128, 96, 16, 2, 64, 0.1, None) == binding.SWAA_ERR_UNSUPPORTED
+    assert f(p, p, p, p, p, 1, 4, 2, 128, 80, 16, 2, 64, 0.1, None) == binding.SWAA_ERR_UNSUPPORTED
     assert f(p, p, p, p + 4, p, 1, 4, 2, 128, 128, 16, 2, 64, 0.1, None) == binding.SWAA_ERR_ALIGN
 
 
@@ -158,7 +159,7 @@ def test_general_forward_argument_errors():
     assert call(**{"q.stride_b": 0}) == binding.SWAA_ERR_SHAPE    # two batch entries on one address
     assert call(cu_seqlens_q=p) == binding.SWAA_ERR_NULL          # one offset array without the other
     assert call(cu_seqlens_q=p, cu_seqlens_k=p + 2) == binding.SWAA_ERR_ALIGN
-    assert call(D=96) == binding.SWAA_ERR_UNSUPPORTED
+    assert call(D=80) == binding.SWAA_ERR_UNSUPPORTED
     assert call(dtype=7) == binding.SWAA_ERR_UNSUPPORTED
     assert call(**{"k.ptr": p + 8}) == binding.SWAA_ERR_ALIGN
 

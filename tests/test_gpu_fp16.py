@@ -32,7 +32,7 @@ def check(B, Hq, Hkv, Nq, Nk, D, W, S, P, seed, rows=None):
     assert_parity(out, lse, ro, rl, rows=rows, tag=tag)
 
 
-@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("D", [64, 96, 128, 256])
 def test_small_shapes(D):
     for N in (1, 63, 65, 257, 700):
         for W, S, P in ((1, 0, None), (7, 4, None), (64, 70, None), (N, 0, None), (50, 3, N // 2)):

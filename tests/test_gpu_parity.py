@@ -44,6 +44,17 @@ def test_small_shapes_sweep_window_and_sinks(N, D):
             check(1, 4, 1, N, D, W, S, seed)
 
 
+@pytest.mark.parametrize("D", [32, 96, 160, 192, 224, 256])
+def test_other_head_dimensions(D):
+    # every multiple of 32 up to 256 has an instantiation of the plain kernel (above 128: 32 rows
+    # per wave); windows, sinks, ragged lengths, GQA groups of 5 = 4 + 1 and 3 = 2 + 1
+    for N in (1, 65, 257, 700):
+        for W, S in ((1, 0), (64, 4), (200, 70), (N + 5, 0)):
+            check(1, 4, 1, N, D, W, S, seed=1500 + N + D)
+    check(2, 10, 2, 333, D, 100, 3, seed=1600 + D)
+    check(1, 3, 1, 515, D, 65, 10, seed=1700 + D)
+
+
 @pytest.mark.parametrize("G", [1, 2, 3, 4, 5, 6, 7, 8])
 def test_gqa_group_sizes(G):
     # every decomposition of a GQA group into 4-, 2- and 1-head workgroups
