@@ -1,17 +1,35 @@
 """GPU parity of swaa_attn_bwd (dQ, dK, dV) against the fp64 CPU oracle, through the C ABI.
 
 The forward results the backward call consumes (out, lse) come from the library's own
-forward call, as in training.  Tolerances: the gradients are bf16, and P and dS are rounded
-to bf16 before the second products (relative 2^-9 each, accumulated in fp32 over up to a few
-thousand terms of mixed sign), so an element is off by about 2^-9 of its own size plus
-2^-9 of the root-sum-square of its terms; measured against the largest and the mean
-magnitude of each gradient: max-abs error <= 1e-2 * max|ref| + abs and mean-abs error <=
-4e-3 * mean|ref| + 1e-3, with abs = 1e-2 for dV and 6e-2 for dQ and dK.  The larger absolute
-term covers delta = <dO, O> being formed from the forward's bf16 output: O carries the bf16
-rounding of P and of itself, up to 2^-8 relative and, for a row dominated by one key, of one
-sign across the head dimension, so delta is off by up to 2^-8 |delta| and, where P ~ 1, dS by
-as much; with N(0,1) data (|delta| <~ 45, |k|, |q| <~ 4.5) that is scale * 2^-8 * 45 * 4.5 =
-0.07 for D = 128 at the very worst, 0.04 seen.  It vanishes for rows that spread over many keys.
+forward call, as in training.
+
+Tolerance (no figure is given for the backward pass; this one is derived from the arithmetic).
+Every gradient element is a sum  x = c * sum_t a_t b_t  whose factor a_t (P for dV, dS for dQ
+and dK) is rounded to bf16 before the product, accumulated in fp32, and rounded to bf16 at the
+end.  With u = 2^-9 (half a bf16 step, relative) and rounding errors spread evenly over
+[-u, u] (standard deviation u / sqrt 3):
+
+    |error(x)|  <=  u |x|  +  4 * (u / sqrt 3) * rss(terms)          (four standard deviations)
+
+and rss(terms) <= max|x| over the tensor for the elements that matter (an element is large
+exactly when its terms align), so  error <= (1 + 4 / sqrt 3) u max|ref| = 6.5e-3 max|ref|; the
+bar is MAX_REL = 8e-3.  One more channel reaches dQ and dK only: delta_i = <dO_i, O_i> is formed
+from the forward's bf16 output, whose elements carry independent roundings of up to u |O_id|
+(the forward divides by the sum of the ROUNDED P, so a row that sees a single key returns that
+key's value row exactly and delta is exact there; the one-signed error of up to 2^-8 |delta| that
+an earlier forward left in rows dominated by one key is gone).  So delta_i is off by about
+(u / sqrt 3) * sqrt(sum_d dO_id^2 O_id^2), 0.013 for D = 128 and 0.009 for D = 64 with N(0,1)
+data, dS_ij by P_ij times that, and dQ_i (dK_j) by scale * that * |P-weighted mean of k| (of q):
+at four standard deviations and |k|, |q| <= 4.5 this is scale * 4.5 * 4 * 0.013 = 2e-2 for both
+head dimensions, reached only by rows that put nearly all weight on one key with a large
+component; rows that spread over many keys average it out.  Hence
+
+    max-abs error  <=  8e-3 * max|ref| + abs,    abs = 2e-2 (dQ, dK), 2e-3 (dV)
+    mean-abs error <=  4e-3 * mean|ref| + 1e-3
+
+Measured over every case below: max-abs error <= 5.8e-3 max|ref| (dQ), 4.6e-3 (dK), 4.4e-3 (dV);
+the absolute terms are never drawn upon by more than 1e-6 (they matter where the true gradient
+is zero).
 """
 import math
 
@@ -26,8 +44,8 @@ from gpu_util import to_device
 
 pytestmark = pytest.mark.gpu
 
-MAX_REL = 1e-2
-MAX_ABS = {"dq": 6e-2, "dk": 6e-2, "dv": 1e-2}
+MAX_REL = 8e-3
+MAX_ABS = {"dq": 2e-2, "dk": 2e-2, "dv": 2e-3}
 MEAN_REL, MEAN_ABS = 4e-3, 1e-3
 
 
@@ -83,8 +101,11 @@ def test_window_one_gives_zero_dq_dk_and_dv_equal_to_dout():
     out, lse = binding.swaa_attn_fwd(qd, kd, vd, 1, 0)
     dq, dk, dv = binding.swaa_attn_bwd(qd, kd, vd, out, lse, dd, 1, 0)
     torch.cuda.synchronize()
-    assert dq.float().abs().max().item() <= MAX_ABS["dq"] and dk.float().abs().max().item() <= MAX_ABS["dk"]
-    assert dq.float().abs().mean().item() <= MEAN_ABS and dk.float().abs().mean().item() <= MEAN_ABS
+    # a row that sees one key has O = v exactly, so dP - delta vanishes up to the order of two
+    # fp32 sums of 128 products of N(0,1) values: 1e-5 at most, times scale * |k| <= 0.4
+    print(f"[grad] W=1: max |dq| {dq.float().abs().max().item():.3e}, max |dk| {dk.float().abs().max().item():.3e}",
+          flush=True)
+    assert dq.float().abs().max().item() <= 1e-4 and dk.float().abs().max().item() <= 1e-4
     want = dd.float().view(B, Hkv, 2, N, D).sum(dim=2)
     assert (dv.float() - want).abs().max().item() <= 2.0 ** -7 * want.abs().max().item()
 
