@@ -123,6 +123,16 @@ int swaa_attn_fwd_fa_decode(const void *q, const void *k, const void *v, void *o
  * binary16 operands and rounds the probabilities and the output to binary16
  * (fp32 accumulation; runs on the plain kernel).
  *
+ * Paged key/value cache (prefill of a chunk against a serving engine's cache, as
+ * swaa_attn_decode_ex reads it): with block_table given, token j of sequence b
+ * lives in page block_table[b][j / page_size], and its row of KV head kvh at
+ * k.ptr + page * k.stride_b + kvh * k.stride_h + (j % page_size) * k.stride_n
+ * (likewise v); page_size a multiple of 16, block_table_stride * page_size >= Nk,
+ * num_pages = pages in the cache (page numbers are clamped to it).  With
+ * cu_seqlens the keys' offsets only give each sequence's number of cached tokens
+ * (cu_seqlens_k[b+1] - cu_seqlens_k[b]); q, out and lse stay packed.  Head
+ * dimension 128 only (SWAA_ERR_UNSUPPORTED otherwise).
+ *
  * Ownership, asynchrony and error reporting as for swaa_attn_fwd; the argument
  * block is read during the call only.  Without cu_seqlens, Nq <= Nk is required.
  */
@@ -152,6 +162,9 @@ typedef struct swaa_fwd_args {
     float scale;
     void *stream;
     int dtype;              /* swaa_dtype of q, k, v and out */
+    /* paged key/value cache (block_table NULL: k, v are tensors as described above) */
+    const int *block_table; /* device, B rows of block_table_stride ints, or NULL */
+    int block_table_stride, page_size, num_pages;
 } swaa_fwd_args;
 
 int swaa_attn_fwd_ex(const swaa_fwd_args *args);

@@ -47,7 +47,9 @@ class SwaaFwdArgs(ctypes.Structure):
                 ("Nq", ctypes.c_int), ("Nk", ctypes.c_int),
                 ("cu_seqlens_q", ctypes.c_void_p), ("cu_seqlens_k", ctypes.c_void_p),
                 ("window", ctypes.c_int), ("n_sink", ctypes.c_int), ("n_prompt", ctypes.c_int),
-                ("scale", ctypes.c_float), ("stream", ctypes.c_void_p), ("dtype", ctypes.c_int)]
+                ("scale", ctypes.c_float), ("stream", ctypes.c_void_p), ("dtype", ctypes.c_int),
+                ("block_table", ctypes.c_void_p), ("block_table_stride", ctypes.c_int), ("page_size", ctypes.c_int),
+                ("num_pages", ctypes.c_int)]
 
 
 class SwaaDecodeArgs(ctypes.Structure):
@@ -320,7 +322,7 @@ def swaa_attn_fwd_ex_raw(args: SwaaFwdArgs) -> int:
 
 def swaa_attn_fwd_ex(q, k, v, window: int, n_sink: int, n_prompt: int | None = None, scale: float | None = None,
                      cu_seqlens_q=None, cu_seqlens_k=None, max_seqlen_q: int | None = None,
-                     max_seqlen_k: int | None = None, out=None, lse=None, stream=None):
+                     max_seqlen_k: int | None = None, out=None, lse=None, stream=None, block_table=None):
     """General forward: strided tensors, Nq <= Nk (the query rows are the newest Nq of Nk
     tokens), packed variable-length batches.
 
@@ -328,7 +330,10 @@ def swaa_attn_fwd_ex(q, k, v, window: int, n_sink: int, n_prompt: int | None = N
     strides whose last dimension is contiguous (a [B, N, H, D] tensor is passed as
     ``t.permute(0, 2, 1, 3)``).  Packed batches: q [Hq, Tq, D], k, v [Hkv, Tk, D] views plus
     int32 device tensors cu_seqlens_q / cu_seqlens_k of B + 1 offsets and the largest
-    sequence lengths.  bfloat16 or float16 tensors (all of one type).  out defaults to a new tensor with q's shape in q's memory order;
+    sequence lengths.  Paged cache (head dimension 128): block_table int32 [B, pages_per_seq] on the
+    GPU, k, v views [num_pages, Hkv, page_size, D], max_seqlen_k the (largest) number of cached tokens;
+    with cu_seqlens the key offsets only give the cache lengths.  bfloat16 or float16 tensors (all of
+    one type).  out defaults to a new tensor with q's shape in q's memory order;
     lse is fp32 [B, Hq, Nq] ([Hq, Tq] when packed).  Returns (out, lse).
     """
     import torch
@@ -338,8 +343,9 @@ def swaa_attn_fwd_ex(q, k, v, window: int, n_sink: int, n_prompt: int | None = N
     if q.dtype not in (torch.bfloat16, torch.float16):
         raise TypeError("q must be bfloat16 or float16")
     for name, t in (("q", q), ("k", k), ("v", v)):
-        if t.dtype != q.dtype or not t.is_cuda or t.dim() != nd or t.stride(-1) != 1:
-            raise ValueError(f"{name} must be a GPU tensor view of q's dtype with {nd} dimensions and a contiguous "
+        want = 4 if (block_table is not None and name != "q") else nd  # (pages of a paged cache are 4-dimensional)
+        if t.dtype != q.dtype or not t.is_cuda or t.dim() != want or t.stride(-1) != 1:
+            raise ValueError(f"{name} must be a GPU tensor view of q's dtype with {want} dimensions and a contiguous "
                              "last one")
     D = q.shape[-1]
     Hq, Hkv = q.shape[-3], k.shape[-3]
@@ -359,6 +365,14 @@ def swaa_attn_fwd_ex(q, k, v, window: int, n_sink: int, n_prompt: int | None = N
     else:
         B, Nq, Nk = q.shape[0], q.shape[2], k.shape[2]
         lse_shape = (B, Hq, Nq)
+    paged = block_table is not None
+    if paged:
+        if block_table.dtype != torch.int32 or not block_table.is_cuda or block_table.dim() != 2 \
+                or block_table.stride(1) != 1 or block_table.shape[0] != B:
+            raise ValueError("block_table must be an int32 [B, pages_per_seq] GPU tensor with contiguous rows")
+        if max_seqlen_k is None or k.dim() != 4:
+            raise ValueError("a paged cache needs max_seqlen_k and k, v views [num_pages, Hkv, page_size, D]")
+        Nk = int(max_seqlen_k)
     with torch.cuda.device(q.device):
         if out is None:
             out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
@@ -372,7 +386,7 @@ def swaa_attn_fwd_ex(q, k, v, window: int, n_sink: int, n_prompt: int | None = N
             stream = torch.cuda.current_stream(q.device)
 
         def tensor(t):
-            if packed:
+            if t.dim() == 3:
                 return SwaaTensor(t.data_ptr(), 0, t.stride(0), t.stride(1))
             return SwaaTensor(t.data_ptr(), t.stride(0), t.stride(1), t.stride(2))
 
@@ -388,6 +402,10 @@ def swaa_attn_fwd_ex(q, k, v, window: int, n_sink: int, n_prompt: int | None = N
         a.scale = float(scale)
         a.stream = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
         a.dtype = SWAA_F16 if q.dtype == torch.float16 else SWAA_BF16
+        a.block_table = block_table.data_ptr() if paged else None
+        a.block_table_stride = block_table.stride(0) if paged else 0
+        a.page_size = k.shape[2] if paged else 0
+        a.num_pages = k.shape[0] if paged else 0
         rc = swaa_attn_fwd_ex_raw(a)
     if rc != SWAA_OK:
         raise SwaaError(rc, swaa_status_string(rc))

@@ -82,12 +82,21 @@ int swaa_attn_fwd_ex(const swaa_fwd_args *a) {
     if (!packed && Nq > Nk) return SWAA_ERR_SHAPE;  // the query rows are the newest Nq of Nk tokens
     if (D % 32 != 0 || D > 256) return SWAA_ERR_UNSUPPORTED;
     if (a->dtype != SWAA_BF16 && a->dtype != SWAA_F16) return SWAA_ERR_UNSUPPORTED;
+    const bool paged = a->block_table != nullptr;
+    if (paged && D != 128) return SWAA_ERR_UNSUPPORTED;
+    if (paged && (a->page_size < 16 || a->page_size % 16 != 0 || a->num_pages < 1 || a->block_table_stride < 1))
+        return SWAA_ERR_SHAPE;
+    if (paged && (long long)a->block_table_stride * a->page_size < Nk) return SWAA_ERR_SHAPE;  // table too short for Nk tokens
     for (const swaa_tensor *t : {&a->q, &a->k, &a->v, &a->out}) {
-        const int heads = (t == &a->k || t == &a->v) ? Hkv : Hq;
+        const bool kv = t == &a->k || t == &a->v;
+        const int heads = kv ? Hkv : Hq;
         if (misaligned(t->ptr)) return SWAA_ERR_ALIGN;
         if (bad_stride(t->stride_n, false) || t->stride_n < D || t->stride_n >= (1LL << 22)) return SWAA_ERR_SHAPE;
-        if (bad_stride(t->stride_h, heads == 1) || bad_stride(t->stride_b, packed || B == 1)) return SWAA_ERR_SHAPE;
+        // (the batch stride of a paged k or v is the page stride)
+        const bool one_block = (kv && paged) ? a->num_pages == 1 : (packed || B == 1);
+        if (bad_stride(t->stride_h, heads == 1) || bad_stride(t->stride_b, one_block)) return SWAA_ERR_SHAPE;
     }
+    if (paged && (reinterpret_cast<uintptr_t>(a->block_table) & 3u)) return SWAA_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(a->lse) & 3u) != 0) return SWAA_ERR_ALIGN;
     if (a->lse_stride_h < 0 || a->lse_stride_b < 0) return SWAA_ERR_SHAPE;
     if (packed && ((reinterpret_cast<uintptr_t>(a->cu_seqlens_q) | reinterpret_cast<uintptr_t>(a->cu_seqlens_k)) & 3u))
@@ -107,6 +116,10 @@ int swaa_attn_fwd_ex(const swaa_fwd_args *a) {
     p.fp16 = a->dtype == SWAA_F16 ? 1 : 0;
     p.cu_q = a->cu_seqlens_q;
     p.cu_k = a->cu_seqlens_k;
+    p.block_table = a->block_table;
+    p.bt_stride = paged ? a->block_table_stride : 0;
+    p.page_size = paged ? a->page_size : 1;
+    p.num_pages = paged ? a->num_pages : 1;
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.Nq = Nq; p.Nk = Nk;
     p.W = a->window < Nk ? a->window : Nk;
     p.S = a->n_sink < Nk ? a->n_sink : Nk;
@@ -147,6 +160,8 @@ int swaa_attn_fwd_fa_decode(const void *q, const void *k, const void *v, void *o
     a.scale = scale;
     a.stream = stream;
     a.dtype = SWAA_BF16;
+    a.block_table = nullptr;
+    a.block_table_stride = a.page_size = a.num_pages = 0;
     return swaa_attn_fwd_ex(&a);
 }
 

@@ -38,6 +38,11 @@ struct FwdParams {
     // axis (sequence b owns rows [cu[b], cu[b+1])), batch strides unused; or null
     const int *cu_q;
     const int *cu_k;
+    // paged key/value cache (pipelined kernel only), or block_table null: token j of sequence b
+    // lives in page block_table[b * bt_stride + j / page_size], row j % page_size; k, v then point
+    // at page 0 and k_sb, v_sb are the page strides.  page_size is a multiple of 16.
+    const int *block_table;
+    int bt_stride, page_size, num_pages;
     int fp16;  // the 16-bit elements of q, k, v, out are IEEE binary16 instead of bfloat16 (plain kernel only)
     int B, Hq, Hkv;
     int Nq, Nk;  // query rows and keys per sequence (the largest ones when cu_q / cu_k are given)
@@ -77,6 +82,11 @@ __device__ __forceinline__ bool seq_geom(const FwdParams &p, int b, SeqGeom &g) 
     if (p.cu_k) {
         g.k_row0 = p.cu_k[b];
         g.nk = p.cu_k[b + 1] - (int)g.k_row0;
+        g.k_batch = 0;
+        if (p.block_table) g.k_row0 = 0;  // a paged cache: the offsets only give the lengths
+    } else if (p.block_table) {
+        g.k_row0 = 0;
+        g.nk = p.Nk;
         g.k_batch = 0;
     } else {
         g.k_row0 = 0;

@@ -345,12 +345,33 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     // half, where it starts, whether its rows run past the sequence's last row (then they
     // repeat that row -- they are masked later -- so that the reads stay in bounds; the padding
     // half repeats the last real half).  A tile that does not exist is not copied.
+    const int *bt = p.block_table ? p.block_table + (size_t)wi.b * p.bt_stride : nullptr;
     auto issue_tile = [&](int j, int buf, bool is_k) __attribute__((always_inline)) {
         if (2 * j >= n_halves) return;
         const int g = min(half_of(2 * j + hslot), hb_hi);
         const uint32_t rsb = is_k ? k_rsb : v_rsb;
-        const char *base = reinterpret_cast<const char *>(is_k ? kg : vg) + (size_t)(32 * g) * rsb;
         const uint32_t l = (uint32_t)((is_k ? 0 : kVRing) + buf * kTileBytes + wave * 4096);
+        if (bt) {
+            // Paged cache: this wave's 16 rows start at a multiple of 16, so they share a page and
+            // the table lookup is uniform.  A block that starts past the last token is replaced by
+            // the block that holds it, rows past it repeat it (all masked later); the page number
+            // is clamped to the cache whatever the table says.
+            const int key0 = min(32 * g + hrow0, (Nk - 1) & ~15);
+            const int page = min(max(bt[key0 / p.page_size], 0), p.num_pages - 1);
+            const char *base = reinterpret_cast<const char *>(is_k ? kg : vg) +
+                               ((long long)page * (is_k ? p.k_sb : p.v_sb)) * 2 + (size_t)(key0 % p.page_size) * rsb;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int r = 4 * i + lrow;  // row of the block, and how far it lies past the last token
+                const uint32_t off = (is_k ? voff_k[i] : voff_v[i]) + (uint32_t)(1024 * i) -
+                                     (uint32_t)(hrow0 + max(key0 + r - (Nk - 1), 0)) * rsb;
+                asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base),
+                             "s"(l + (uint32_t)(1024 * i))
+                             : "memory");
+            }
+            return;
+        }
+        const char *base = reinterpret_cast<const char *>(is_k ? kg : vg) + (size_t)(32 * g) * rsb;
         if (__builtin_expect(last_ragged && g == hb_hi, 0)) {
             // (one M0 value per copy and no offset field: a clamped row may lie less than
             // 1024 i bytes behind the half's first row)
@@ -515,7 +536,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     // in pairs: odd, even).
     const int lean_end = min(jb, ((n_halves - 6 - (last_ragged ? 1 : 0)) >> 1) + 1);
     const int lean_begin = ja | 1;
-    bool lean_pending = lean_begin + 1 < lean_end;
+    bool lean_pending = lean_begin + 1 < lean_end && !bt;  // (a paged cache has no "next 64 rows")
     for (int t = 1; t < J;) {  // t is odd here
         if (lean_pending && t == lean_begin) {
             k_next = reinterpret_cast<const char *>(kg) + (size_t)(32 * half_of(2 * t + 4 + hslot)) * k_rsb;

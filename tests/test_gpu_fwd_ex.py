@@ -109,3 +109,68 @@ def test_chunk_against_a_long_cache_full_size():
     print("[oracle]", flush=True)
     ro, rl = swaa_decode_oracle(q, k, v, w.window, w.n_sink, w.scale)
     assert_parity(out, lse, ro, rl, tag="2048-row chunk on a 128k cache")
+
+
+def build_paged_cache(host_kv, lens, page_size, Hkv, D, rng):
+    """Scatter each sequence's [1, Hkv, n, D] keys and values into pages in a random order;
+    returns the cache views [num_pages, Hkv, page_size, D] and the block table."""
+    B = len(lens)
+    pages_per_seq = -(-max(lens) // page_size)
+    num_pages = B * pages_per_seq + 3
+    order = rng.permutation(num_pages)
+    kc = torch.full((num_pages, page_size, Hkv, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    vc = torch.zeros((num_pages, page_size, Hkv, D), dtype=torch.bfloat16, device="cuda")
+    table = np.full((B, pages_per_seq), -7, dtype=np.int32)  # unused entries hold a bad page number
+    nxt = 0
+    for b, (k, v) in enumerate(host_kv):
+        kt, vt = to_device(k)[0].permute(1, 0, 2), to_device(v)[0].permute(1, 0, 2)  # [n, Hkv, D]
+        for pg in range(-(-lens[b] // page_size)):
+            page = int(order[nxt]); nxt += 1
+            table[b, pg] = page
+            t0, t1 = pg * page_size, min(lens[b], (pg + 1) * page_size)
+            kc[page, :t1 - t0], vc[page, :t1 - t0] = kt[t0:t1], vt[t0:t1]
+            kc[page, t1 - t0:] = 0  # rows of a page past the sequence's end: finite, never visible
+    return kc.permute(0, 2, 1, 3), vc.permute(0, 2, 1, 3), torch.from_numpy(table).cuda()
+
+
+@pytest.mark.parametrize("page_size", [16, 32, 64, 256])
+def test_chunked_prefill_over_a_paged_cache(page_size):
+    # the query rows are the newest Nq of Nk cached tokens; pages in random order; cache lengths
+    # on and off every alignment; whole prefills (Nq = Nk) as well
+    rng = np.random.Generator(np.random.Philox(8800 + page_size))
+    D, Hq, Hkv = 128, 8, 2
+    for Nq, Nk, W, S, P in ((1, 1, 5, 0, None), (5, 70, 50, 4, None), (64, 129, 64, 70, None), (100, 777, 200, 4, None),
+                            (300, 333, 1000, 0, None), (257, 1500, 300, 33, 1400), (700, 700, 128, 4, None),
+                            (129, 2049, 2049, 0, None)):
+        B = 2
+        tag = f"paged prefill page{page_size} B{B} Nq{Nq} Nk{Nk} W{W} S{S} P{P}"
+        print(f"[case] {tag}", flush=True)
+        host = [make_qkv(1, Hq, Hkv, Nk, D, 8900 + 7 * i + Nk + page_size, n_query=Nq) for i in range(B)]
+        kc, vc, table = build_paged_cache([(h[1], h[2]) for h in host], [Nk] * B, page_size, Hkv, D, rng)
+        qd = torch.cat([to_device(h[0]) for h in host], dim=0)
+        out, lse = binding.swaa_attn_fwd_ex(qd, kc, vc, W, S, P, block_table=table, max_seqlen_k=Nk)
+        torch.cuda.synchronize()
+        for b, (q, k, v) in enumerate(host):
+            ro, rl = swaa_decode_oracle(q, k, v, W, S, 1 / math.sqrt(D), n_prompt=P)
+            assert_parity(out[b:b + 1], lse[b:b + 1], ro, rl, tag=f"{tag} / seq {b}")
+
+
+def test_packed_chunks_over_a_paged_cache_with_different_lengths():
+    # packed query rows (cu_seqlens_q), cache lengths from cu_seqlens_k's differences, keys from the block table
+    rng = np.random.Generator(np.random.Philox(8850))
+    D, Hq, Hkv, page_size, W, S = 128, 4, 1, 32, 100, 4
+    nq = [1, 63, 300, 64, 17]
+    nk = [1, 500, 300, 1000, 77]
+    host = [make_qkv(1, Hq, Hkv, nk[i], D, 8860 + i, n_query=nq[i]) for i in range(len(nq))]
+    kc, vc, table = build_paged_cache([(h[1], h[2]) for h in host], nk, page_size, Hkv, D, rng)
+    q_packed = torch.cat([to_device(h[0])[0] for h in host], dim=1)  # [Hq, sum nq, D]
+    cu_q = torch.tensor(np.concatenate([[0], np.cumsum(nq)]), dtype=torch.int32, device="cuda")
+    cu_k = torch.tensor(np.concatenate([[0], np.cumsum(nk)]), dtype=torch.int32, device="cuda")
+    out, lse = binding.swaa_attn_fwd_ex(q_packed, kc, vc, W, S, None, cu_seqlens_q=cu_q, cu_seqlens_k=cu_k,
+                                        max_seqlen_q=max(nq), max_seqlen_k=max(nk), block_table=table)
+    torch.cuda.synchronize()
+    r0 = 0
+    for b, (q, k, v) in enumerate(host):
+        ro, rl = swaa_decode_oracle(q, k, v, W, S, 1 / math.sqrt(D))
+        assert_parity(out[None, :, r0:r0 + nq[b]], lse[None, :, r0:r0 + nq[b]], ro, rl, tag=f"packed paged seq {b}")
+        r0 += nq[b]
