@@ -594,10 +594,7 @@ __global__ __launch_bounds__(kDkvThreads, 1) void swaa_bwd_dkv_kernel(const BwdP
 // below use plain byte addresses.
 namespace dma128 {
 constexpr int kD = 128, kRowBytes = 256;
-#ifndef SWAA_BWD_AHEAD
-#define SWAA_BWD_AHEAD 2
-#endif
-constexpr int kAhead = SWAA_BWD_AHEAD;  // MFMAs between an LDS operand read and its use
+constexpr int kAhead = 2;  // MFMAs between an LDS operand read and its use
 constexpr int kKeyTileBytes = 128 * kRowBytes;  // 32 KiB: the workgroup's K rows, or V rows
 constexpr int kQTileBytes = kBq * kRowBytes;    // 16 KiB
 constexpr int kK = 0, kV = kKeyTileBytes, kQ = 2 * kKeyTileBytes, kDO = kQ + 2 * kQTileBytes, kL = kDO + 2 * kQTileBytes,
