@@ -230,6 +230,9 @@ int swaa_attn_decode(const void *q, const void *k, const void *v, void *out, flo
  *                 num_pages = pages in the cache (page numbers are clamped to it)
  *   Nk            the largest cache length (the key splits are planned for it);
  *                 workspace from swaa_attn_decode_workspace_bytes with this Nk
+ *   dtype         swaa_dtype of q, k, v and out: SWAA_BF16 (0, what a zeroed struct
+ *                 and swaa_attn_decode select) or SWAA_F16, the precision the paper
+ *                 serves in (Sec. 4.1.1); anything else: SWAA_ERR_UNSUPPORTED
  *
  * Everything else as in swaa_attn_decode.
  */
@@ -247,6 +250,7 @@ typedef struct swaa_decode_args {
     void *workspace;
     long long workspace_bytes;
     void *stream;
+    int dtype;
 } swaa_decode_args;
 
 int swaa_attn_decode_ex(const swaa_decode_args *args);

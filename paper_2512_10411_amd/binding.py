@@ -61,7 +61,7 @@ class SwaaDecodeArgs(ctypes.Structure):
                 ("B", ctypes.c_int), ("Hq", ctypes.c_int), ("Hkv", ctypes.c_int), ("Nq", ctypes.c_int),
                 ("Nk", ctypes.c_int), ("D", ctypes.c_int), ("window", ctypes.c_int), ("n_sink", ctypes.c_int),
                 ("scale", ctypes.c_float), ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_longlong),
-                ("stream", ctypes.c_void_p)]
+                ("stream", ctypes.c_void_p), ("dtype", ctypes.c_int)]
 
 
 class SwaaError(RuntimeError):
@@ -478,7 +478,8 @@ def swaa_attn_decode_ex(q, k, v, window: int, n_sink: int, scale: float | None =
                         stream=None):
     """Decode-shape attention on a strided or paged cache, with per-sequence cache lengths.
 
-    q: bf16 [B, Hq, Nq, D] contiguous.  Contiguous cache: k, v views [B, Hkv, Nk, D] with any
+    q: bf16 or fp16 [B, Hq, Nq, D] contiguous (k, v in the same format; out takes it too).
+    Contiguous cache: k, v views [B, Hkv, Nk, D] with any
     strides (last dimension contiguous).  Paged cache: block_table int32 [B, pages_per_seq] on
     the GPU and k, v views [num_pages, Hkv, page_size, D] (a [num_pages, page_size, Hkv, D]
     cache is passed as ``cache.permute(0, 2, 1, 3)``).  seq_lens: int32 [B] GPU tensor of cache
@@ -487,11 +488,11 @@ def swaa_attn_decode_ex(q, k, v, window: int, n_sink: int, scale: float | None =
     """
     import torch
 
-    if q.dtype != torch.bfloat16 or not q.is_cuda or not q.is_contiguous() or q.dim() != 4:
-        raise ValueError("q must be a contiguous bf16 [B, Hq, Nq, D] GPU tensor")
-    for name, t in (("k", k), ("v", v)):
-        if t.dtype != torch.bfloat16 or not t.is_cuda or t.dim() != 4 or t.stride(-1) != 1:
-            raise ValueError(f"{name} must be a bf16 GPU tensor view with 4 dimensions and a contiguous last one")
+    if q.dtype not in (torch.bfloat16, torch.float16) or not q.is_cuda or not q.is_contiguous() or q.dim() != 4:
+        raise ValueError("q must be a contiguous bf16 or fp16 [B, Hq, Nq, D] GPU tensor")
+    for name, t in (("k", k), ("v", v)) + ((("out", out),) if out is not None else ()):
+        if t.dtype != q.dtype or not t.is_cuda or t.dim() != 4 or t.stride(-1) != 1:
+            raise ValueError(f"{name} must be a GPU tensor view of q's format with 4 dimensions and a contiguous last one")
     B, Hq, Nq, D = q.shape
     Hkv = k.shape[1]
     paged = block_table is not None
@@ -532,6 +533,7 @@ def swaa_attn_decode_ex(q, k, v, window: int, n_sink: int, scale: float | None =
         a.window, a.n_sink, a.scale = int(window), int(n_sink), float(scale)
         a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
         a.stream = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+        a.dtype = SWAA_F16 if q.dtype == torch.float16 else SWAA_BF16
         rc = swaa_attn_decode_ex_raw(a)
     if rc != SWAA_OK:
         raise SwaaError(rc, swaa_status_string(rc))

@@ -211,6 +211,7 @@ int decode_call(const swaa_decode_args *a, bool own_scratch) {
     const int rc = decode_plan(p, a->B, a->Hq, a->Hkv, a->Nq, a->Nk, a->D, a->window, a->n_sink);
     if (rc != SWAA_OK) return rc;
     if (!positive_finite(a->scale)) return SWAA_ERR_SHAPE;
+    if (a->dtype != SWAA_BF16 && a->dtype != SWAA_F16) return SWAA_ERR_UNSUPPORTED;
     const bool paged = a->block_table != nullptr;
     if (paged && (a->page_size < 4 || a->page_size % 4 != 0 || a->num_pages < 1 || a->block_table_stride < 1))
         return SWAA_ERR_SHAPE;
@@ -247,6 +248,7 @@ int decode_call(const swaa_decode_args *a, bool own_scratch) {
     p.seq_lens = a->seq_lens;
     p.ws_o = static_cast<float *>(workspace);
     p.ws_ml = p.ws_o + p.items * (long long)p.col_stride * 128;
+    p.fp16 = a->dtype == SWAA_F16 ? 1 : 0;
     p.scale_log2 = a->scale * 1.44269504088896340736f;
     const hipError_t err = swaa::launch_decode(p, static_cast<hipStream_t>(a->stream));
     return err == hipSuccess ? SWAA_OK : SWAA_ERR_LAUNCH;

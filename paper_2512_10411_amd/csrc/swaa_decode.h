@@ -40,6 +40,7 @@ struct DecodeParams {
     int n_halves;  // upper bound on the halves a sequence of at most Nk tokens visits
     int halves_per_split, n_splits;
     long long items;  // B * Hkv * n_coltiles * n_splits
+    int fp16;         // elements of q, k, v, out are IEEE binary16 instead of bfloat16
 };
 
 // The halves a sequence of nk cached tokens visits: halves 0 .. n_sink-1, then key halves band0 ..

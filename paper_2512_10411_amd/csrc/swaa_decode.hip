@@ -46,6 +46,7 @@ constexpr int kCopiesPerHalf = 16;                    // wave instructions per s
 constexpr int kMergeThreads = 1024;
 constexpr int kRounds = 1;  // rounds of resident workgroups the split plan aims for
 
+template <bool kF16>
 __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParams p) {
     // XCD x takes the x-th contiguous chunk of the item list (column tiles of one
     // split, which read the same keys, then run behind the same L2)
@@ -225,23 +226,23 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
         f32x16 s;
         bf16x8 pf[2];
         float alpha;
-        mfma_s_first(s, kf[0], qf[0]);
+        mfma_s_first<kF16>(s, kf[0], qf[0]);
 #pragma unroll
-        for (int ks = 1; ks < kKS - 1; ++ks) mfma_s(s, kf[ks], qf[ks]);
-        mfma_s_settled(s, kf[kKS - 1], qf[kKS - 1]);
+        for (int ks = 1; ks < kKS - 1; ++ks) mfma_s<kF16>(s, kf[ks], qf[ks]);
+        mfma_s_settled<kF16>(s, kf[kKS - 1], qf[kKS - 1]);
         if (masked)
-            softmax_half<true>(s, k0h, qpos, W, S, hf, c2, rs, pf, alpha);
+            softmax_half<true, kF16>(s, k0h, qpos, W, S, hf, c2, rs, pf, alpha);
         else
-            softmax_half<false>(s, k0h, qpos, W, S, hf, c2, rs, pf, alpha);
+            softmax_half<false, kF16>(s, k0h, qpos, W, S, hf, c2, rs, pf, alpha);
         rescale(oacc, alpha);
 #pragma unroll
         for (int st = 0; st < 2; ++st)
 #pragma unroll
             for (int db = 0; db < kDB; ++db) {
                 if (st == 1 && db == kDB - 1)
-                    mfma_acc_settled(oacc[db], vf[st][db], pf[st]);  // the accumulators are read below / next time round
+                    mfma_acc_settled<kF16>(oacc[db], vf[st][db], pf[st]);  // the accumulators are read below / next time round
                 else
-                    mfma_acc(oacc[db], vf[st][db], pf[st]);
+                    mfma_acc<kF16>(oacc[db], vf[st][db], pf[st]);
             }
         stage = (stage + 1 == kDStages) ? 0 : stage + 1;
     }
@@ -335,7 +336,10 @@ __global__ __launch_bounds__(kMergeThreads) void swaa_decode_merge_kernel(const 
             o += red[gg * kD + d];
             lt += lsum[gg];
         }
-        p.out[(size_t)row * kD + d] = (__bf16)(o / lt);
+        if (p.fp16)
+            reinterpret_cast<_Float16 *>(p.out)[(size_t)row * kD + d] = (_Float16)(o / lt);
+        else
+            p.out[(size_t)row * kD + d] = (__bf16)(o / lt);
         if (d == 0) p.lse[row] = (m + __builtin_amdgcn_logf(lt)) * 0.69314718055994530942f;
     }
 }
@@ -395,7 +399,11 @@ hipError_t decode_static_scratch(void **ptr) {
 
 hipError_t launch_decode(const DecodeParams &p, hipStream_t stream) {
     const long long chunk = (p.items + kXcds - 1) / kXcds;
-    hipLaunchKernelGGL(swaa_decode_split_kernel, dim3((unsigned)(chunk * kXcds)), dim3(64), kDSmemBytes, stream, p);
+    const dim3 grid((unsigned)(chunk * kXcds));
+    if (p.fp16)
+        hipLaunchKernelGGL(swaa_decode_split_kernel<true>, grid, dim3(64), kDSmemBytes, stream, p);
+    else
+        hipLaunchKernelGGL(swaa_decode_split_kernel<false>, grid, dim3(64), kDSmemBytes, stream, p);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL(swaa_decode_merge_kernel, dim3((unsigned)((long long)p.B * p.Hq * p.Nq)), dim3(kMergeThreads), 0,

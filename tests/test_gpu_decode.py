@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 import torch
 
-from oracle import swaa_decode_oracle
+from oracle import input_format, swaa_decode_oracle
 from paper_2512_10411_amd import binding
 from paper_2512_10411_amd.inputs import WORKLOADS, bf16_bits_to_f32, f32_to_bf16_bits, make_qkv, make_workload
 from gpu_util import assert_parity, to_device
@@ -191,3 +191,89 @@ def test_shorter_sequence_whose_band_straddles_one_more_half():
     for b, (qs, ks, vs) in enumerate(host):
         ro, rl = swaa_decode_oracle(qs, ks, vs, W, S, 1 / math.sqrt(D))
         assert_parity(out[b:b + 1], lse[b:b + 1], ro, rl, tag=f"ragged windowed decode seq {b} Nk{lens[b]}")
+
+
+@pytest.mark.parametrize("Nk", [250, 1024, 1030, 8192, 8200, 17000, 70000])
+def test_one_pair_cut_into_many_splits(Nk):
+    # one KV head, one token: the only pair has 2, 8, 9, 64, 65, 133 and 547 splits of four halves
+    # (the merge kernel's strides of 4 x 8 splits with ragged ends); the workspace starts as noise
+    # and is used twice
+    B, Hq, Hkv, Nq, D = 1, 4, 1, 1, 128
+    q, k, v = make_qkv(B, Hq, Hkv, Nk, D, seed=7900 + Nk % 97, n_query=Nq)
+    qd, kd, vd = to_device(q), to_device(k), to_device(v)
+    need = binding.swaa_attn_decode_workspace_bytes(B, Hq, Hkv, Nq, Nk, D, Nk, 0)
+    ws = torch.randint(0, 256, (need,), dtype=torch.uint8, device="cuda")
+    ro, rl = swaa_decode_oracle(q, k, v, Nk, 0, 1 / math.sqrt(D))
+    for call in range(2):
+        out, lse = binding.swaa_attn_decode(qd, kd, vd, Nk, 0, workspace=ws)
+        torch.cuda.synchronize()
+        assert_parity(out, lse, ro, rl, tag=f"many splits Nk{Nk} call {call}")
+
+
+def test_replays_of_a_captured_decode_call():
+    # both kernels of the call in a captured graph, replayed with new inputs each time, eager
+    # work and synchronisation between the replays; every replay against the oracle and the eager call
+    B, Hq, Hkv, Nq, Nk, D, W, S = 2, 8, 2, 1, 6000, 128, 2048, 4
+    need = binding.swaa_attn_decode_workspace_bytes(B, Hq, Hkv, Nq, Nk, D, W, S)
+    ws = torch.randint(0, 256, (need,), dtype=torch.uint8, device="cuda")
+    host = [make_qkv(B, Hq, Hkv, Nk, D, seed=7950 + i, n_query=Nq) for i in range(3)]
+    qd, kd, vd = (torch.empty_like(to_device(a)) for a in host[0])
+    out = torch.empty_like(qd)
+    lse = torch.empty((B, Hq, Nq), dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):  # warm-up outside the capture
+        binding.swaa_attn_decode(qd.zero_(), kd.zero_(), vd.zero_(), W, S, out=out, lse=lse, workspace=ws, stream=side)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        binding.swaa_attn_decode(qd, kd, vd, W, S, out=out, lse=lse, workspace=ws, stream=torch.cuda.current_stream())
+    for i, (q, k, v) in enumerate(host):
+        qd.copy_(to_device(q)); kd.copy_(to_device(k)); vd.copy_(to_device(v))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ro, rl = swaa_decode_oracle(q, k, v, W, S, 1 / math.sqrt(D))
+        assert_parity(out, lse, ro, rl, tag=f"captured decode, replay {i}")
+        eo, el = binding.swaa_attn_decode(qd, kd, vd, W, S, workspace=ws)   # eager, same workspace
+        torch.cuda.synchronize()
+        assert torch.equal(eo, out) and torch.equal(el, lse)
+
+
+@pytest.mark.parametrize("Nq,G", [(1, 4), (2, 4), (1, 8), (3, 5), (9, 4)])
+def test_binary16_caches(Nq, G):
+    # the paper serves in float16 (Sec. 4.1.1): q, k, v, out in binary16, one and several column
+    # tiles, contiguous caches with sequence lengths and a paged cache
+    Hkv, D = 2, 128
+    Hq = Hkv * G
+    lens = [Nq, 33, 700, 4100]
+    rng = np.random.Generator(np.random.Philox(7970 + Nq + G))
+    host = [make_qkv(1, Hq, Hkv, n, D, int(rng.integers(1 << 30)), n_query=Nq, fmt="fp16") for n in lens]
+    q = torch.cat([to_device(s[0], "fp16") for s in host], dim=0)
+    seq_lens = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    kb = torch.zeros((len(lens), Hkv, max(lens), D), dtype=torch.float16, device="cuda")
+    vb = torch.zeros_like(kb)
+    for b, (_, k, v) in enumerate(host):
+        kb[b, :, :lens[b]], vb[b, :, :lens[b]] = to_device(k, "fp16")[0], to_device(v, "fp16")[0]
+    page = 16
+    pages = -(-max(lens) // page)
+    order = rng.permutation(len(lens) * pages)
+    kc = torch.zeros((len(lens) * pages, page, Hkv, D), dtype=torch.float16, device="cuda")
+    vc = torch.zeros_like(kc)
+    table = torch.from_numpy(order.reshape(len(lens), pages).astype(np.int32)).cuda()
+    for b in range(len(lens)):
+        kp = torch.zeros((pages * page, Hkv, D), dtype=torch.float16, device="cuda")
+        vp = torch.zeros_like(kp)
+        kp[:lens[b]], vp[:lens[b]] = kb[b, :, :lens[b]].permute(1, 0, 2), vb[b, :, :lens[b]].permute(1, 0, 2)
+        kc[table[b].long()] = kp.view(pages, page, Hkv, D)
+        vc[table[b].long()] = vp.view(pages, page, Hkv, D)
+    for W, S in ((10**9, 0), (300, 4)):
+        o1, l1 = binding.swaa_attn_decode_ex(q, kb, vb, W, S, seq_lens=seq_lens)
+        o2, l2 = binding.swaa_attn_decode_ex(q, kc.permute(0, 2, 1, 3), vc.permute(0, 2, 1, 3), W, S, seq_lens=seq_lens,
+                                             block_table=table, max_seqlen_k=max(lens))
+        torch.cuda.synchronize()
+        assert o1.dtype == torch.float16 and torch.equal(o1, o2) and torch.equal(l1, l2)
+        for b, (qs, ks, vs) in enumerate(host):
+            with input_format("fp16"):
+                ro, rl = swaa_decode_oracle(qs, ks, vs, W, S, 1 / math.sqrt(D))
+            assert_parity(o1[b:b + 1], l1[b:b + 1], ro, rl, tag=f"fp16 decode Nq{Nq} G{G} seq {b} Nk{lens[b]} W{W}")
