@@ -118,35 +118,13 @@ __device__ __forceinline__ void softmax_chunk(int c, const f32x16 &s, float c2, 
 }
 
 // Scores of keys a lane's query row must not see become -inf (a select: the old
-// value, whatever it is, is dropped).  k0h: first key of the half.  Element e of
-// the lane is key k0h + 4 hf + c_e with c_e = 8 (e / 4) + e % 4, so every test is
-// a comparison of the constant c_e with a per-lane bound.  Most halves that need
-// a mask need one of the three tests only; the workgroup-uniform `kind` says which:
-//   causal  key <= qpos              (the diagonal half, the padding half)
-//   window  key > qpos - W           (the band's first half)
-//   sink    key < S                  (a sink half that lies in front of every row's window)
-//   all     (key <= qpos) and (key > qpos - W or key < S)
-enum MaskKind : int { kMaskNone = 0, kMaskCausal, kMaskWindow, kMaskSink, kMaskAll };
-
-__device__ __forceinline__ void mask_scores(f32x16 &s, int kind, int k0h, int qpos, int W, int S, int hf) {
-    const int a = qpos - k0h - 4 * hf;   // key <= qpos      <=>  c_e <= a
-    const int b = a - W;                 // key >  qpos - W  <=>  c_e >  b
-    const int sk = S - k0h - 4 * hf;     // key <  S         <=>  c_e <  sk
-    if (kind == kMaskCausal) {
+// value, whatever it is, is dropped).  k0h: first key of the half.
+__device__ __forceinline__ void mask_scores(f32x16 &s, int k0h, int qpos, int W, int S, int hf) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) s[e] = (8 * (e / 4) + e % 4 <= a) ? s[e] : -INFINITY;
-    } else if (kind == kMaskWindow) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) s[e] = (8 * (e / 4) + e % 4 > b) ? s[e] : -INFINITY;
-    } else if (kind == kMaskSink) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) s[e] = (8 * (e / 4) + e % 4 < sk) ? s[e] : -INFINITY;
-    } else {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int c = 8 * (e / 4) + e % 4;
-            s[e] = ((c <= a) && ((c > b) || (c < sk))) ? s[e] : -INFINITY;
-        }
+    for (int e = 0; e < 16; ++e) {
+        const int key = k0h + 8 * (e / 4) + 4 * hf + (e % 4);
+        const bool vis = (key <= qpos) && ((key > qpos - W) || (key < S));
+        s[e] = vis ? s[e] : -INFINITY;
     }
 }
 
@@ -210,14 +188,14 @@ __device__ __forceinline__ bf16x8 load_slot(const LaneAddr &la, const HalfOffset
 // kLoadFirst: the first kPrefetch fragments are requested here (first sub-step of a
 //   step); otherwise the caller passes them in fpre.
 // kPrefetchNext: on return fpre holds the first fragments of the following sub-step.
-// mask_cur / k0h_cur: the mask (MaskKind) the half whose softmax runs here (s_cur) needs,
-//   and its first key.
+// mask_cur / k0h_cur: whether the half whose softmax runs here (s_cur) needs the
+//   mask, and its first key.
 template <bool kF16, bool kHasS, bool kHasPV, bool kLoadFirst, bool kPrefetchNext>
 __device__ __forceinline__ void pipelined_substep(const LaneAddr &la, const HalfOffsets &ho, bf16x8 (&fpre)[kPrefetch],
                                                   const bf16x8 (&qf)[kKS], f32x16 &s_next, f32x16 &s_cur,
                                                   bf16x8 (&p_cur)[2], const bf16x8 (&p_prev)[2], f32x16 (&o)[kDB],
                                                   RowState &st, f32x4 (&lsum)[2], const bf16x8 &sel, float c2,
-                                                  int mask_cur, int k0h_cur, int qpos, int W, int S, int hf) {
+                                                  bool mask_cur, int k0h_cur, int qpos, int W, int S, int hf) {
     SoftmaxScratch w;
     bf16x8 frag[16 + kPrefetch];
     auto wanted = [](int slot) __attribute__((always_inline)) { return (slot & 1) ? kHasPV : kHasS; };
@@ -239,7 +217,7 @@ __device__ __forceinline__ void pipelined_substep(const LaneAddr &la, const Half
             mfma_acc<kF16>(o[(i / 2) % kDB], frag[i], p_prev[(i / 2) / kDB]);
         }
         __builtin_amdgcn_sched_barrier(0);
-        if (i == 0 && __builtin_expect(mask_cur != kMaskNone, 0)) mask_scores(s_cur, mask_cur, k0h_cur, qpos, W, S, hf);
+        if (i == 0 && __builtin_expect(mask_cur, 0)) mask_scores(s_cur, k0h_cur, qpos, W, S, hf);
         softmax_chunk<kF16>(i, s_cur, c2, st, w, p_cur);
         if (i == 15) {  // P^T of this half is complete (and two MFMAs old)
             mfma_rowsum<kF16>(lsum[0], sel, p_cur[0]);
@@ -446,18 +424,9 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
 
     // A wave needs no mask on a 32-key half when all its keys are visible to all
     // its 32 rows: at or below the first row's diagonal, and inside the window of
-    // its last prompt row (if it has one) or all sinks.  Otherwise: which tests?
+    // its last prompt row (if it has one) or all sinks.
     const int wbound = window_bound(p0, kPRows, p.W, p.P);
-    auto mask_kind = [&](int k0h) __attribute__((always_inline)) -> int {
-        const bool causal = k0h + 31 > p0;    // some key lies beyond the first row's diagonal
-        const bool window = k0h <= wbound;    // some key lies in front of some row's window
-        if (!causal && (!window || k0h + 31 < S)) return kMaskNone;
-        if (k0h >= S) return !window ? kMaskCausal : !causal ? kMaskWindow : kMaskAll;  // no sink key in the half
-        // sink keys in the half: if every other key lies in front of every row's window (all rows prompt rows,
-        // the first row's window starts behind the half), "is a sink" is the whole test
-        if (!causal && p0 + kPRows - 1 < p.P && k0h + 31 <= p0 - p.W) return kMaskSink;
-        return kMaskAll;
-    };
+    auto half_masked = [&](int k0h) __attribute__((always_inline)) { return !((k0h + 31 <= p0) && ((k0h > wbound) || (k0h + 31 < S))); };
 
     // (Worked out here, while the first copies travel.)
     // Steps [ja, jb) of this wave need no mask.  Step t runs the softmax of the visited halves
@@ -491,7 +460,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     rs.lb = 0.f;
     {
         qk_half<kF16>(la, 0u, qf, s_a);
-        mask_scores(s_a, kMaskAll, 32 * half_of(0), qpos, W, S, hf);
+        mask_scores(s_a, 32 * half_of(0), qpos, W, S, hf);
         float mx = s_a[0];
 #pragma unroll
         for (int e = 1; e < 16; ++e) mx = fmaxf(mx, s_a[e]);
@@ -503,7 +472,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     // softmax of (tile 0, half 0) | scores of (tile 0, half 1); no P V product is due yet
     {
         const HalfOffsets h = {kHalfBytes, 0, 0, 0};
-        pipelined_substep<kF16, true, false, true, false>(la, h, fpre, qf, s_b, s_a, p_a, p_b, oacc, rs, lsum, sel, c2, kMaskNone, 0,
+        pipelined_substep<kF16, true, false, true, false>(la, h, fpre, qf, s_b, s_a, p_a, p_b, oacc, rs, lsum, sel, c2, false, 0,
                                               qpos, W, S, hf);
     }
     // every wave is done with K(0), which is free afterwards
@@ -522,7 +491,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     // halves, the jump to the band, the ragged last half, the end of the list).  The lean one
     // serves the interior of a wave's band, where no half needs a mask and the next tiles
     // simply follow the previous ones in memory.
-    auto substeps = [&](auto ring_pos, int mask_p, int k0p, int mask_0, int k0) __attribute__((always_inline)) {
+    auto substeps = [&](auto ring_pos, bool mask_p, int k0p, bool mask_0, int k0) __attribute__((always_inline)) {
         constexpr int R = decltype(ring_pos)::value;
         constexpr uint32_t kb0 = R * kTileBytes, kb1 = kb0 + kHalfBytes;        // K(t)
         constexpr uint32_t vb0 = (1 - R) * kTileBytes, vb1 = vb0 + kHalfBytes;  // V(t-1)
@@ -543,7 +512,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     auto general_step = [&](auto ring_pos, int t) __attribute__((always_inline)) {
         constexpr int R = decltype(ring_pos)::value;
         const int k0p = 32 * half_of(2 * t - 1), k0 = 32 * half_of(2 * t);
-        substeps(ring_pos, mask_kind(k0p), k0p, mask_kind(k0), k0);
+        substeps(ring_pos, half_masked(k0p), k0p, half_masked(k0), k0);
         issue_k(t + 2, R);
         issue_v(t + 1, 1 - R);
     };
@@ -551,7 +520,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     const char *k_next = nullptr, *v_next = nullptr;
     auto lean_step = [&](auto ring_pos) __attribute__((always_inline)) {
         constexpr int R = decltype(ring_pos)::value;
-        substeps(ring_pos, kMaskNone, 0, kMaskNone, 0);
+        substeps(ring_pos, false, 0, false, 0);
         copy4(voff_k, k_next, (uint32_t)(R * kTileBytes + wave * 4096));
         k_next += (size_t)kBk * k_rsb;
         copy4(voff_v, v_next, (uint32_t)(kVRing + (1 - R) * kTileBytes + wave * 4096));
@@ -588,7 +557,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
         const int k0l = 32 * half_of(2 * J - 1);
         const HalfOffsets h = {0, vb, 0, 0};
         pipelined_substep<kF16, false, true, true, false>(la, h, fpre, qf, s_a, s_b, p_b, p_a, oacc, rs, lsum, sel, c2,
-                                                    mask_kind(k0l), k0l, qpos, W, S, hf);
+                                                    half_masked(k0l), k0l, qpos, W, S, hf);
         // (the column sums of p_b, issued at the end of the sub-step, complete under these)
         pv_half<true, kF16>(la, vb + kHalfBytes, p_b, oacc);
     }
