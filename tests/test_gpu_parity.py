@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 import torch
 
-from oracle import swaa_attn_oracle
+from oracle import swaa_attn_oracle, swaa_decode_oracle
 from paper_2512_10411_amd import binding
 from paper_2512_10411_amd.inputs import (WORKLOADS, bf16_bits_to_f32, f32_to_bf16_bits, make_qkv,
                                          make_workload, sample_rows)
@@ -289,3 +289,40 @@ def test_many_sink_tiles(S):
 def test_batched_uneven_gqa_groups_at_scale():
     # G = 7 = 4 + 2 + 1: all three workgroup shapes in one launch, several batch entries
     check(3, 14, 2, 1111, 128, 300, 4, seed=4800)
+
+
+def test_million_token_context_with_offsets_beyond_32_bits():
+    # N = 2^20 + 77 tokens, 20 query heads on 4 KV heads (groups of 4 + 1 heads): q and out are 5.4 GB
+    # each, so element offsets pass 2^31 and byte offsets 2^32.  The tensors are drawn on the GPU from
+    # a seeded generator; the oracle gets each sampled row as a one-token problem on the keys that
+    # row can see (its sinks and its window, which is the same set at any position).
+    B, Hq, Hkv, N, D, W, S = 1, 20, 4, (1 << 20) + 77, 128, 1000, 4
+    G = Hq // Hkv
+    gen = torch.Generator(device="cuda").manual_seed(2512104199)
+    print("[gen] 13 GB of q, k, v, out", flush=True)
+    q = torch.randn((B, Hq, N, D), device="cuda", dtype=torch.bfloat16, generator=gen)
+    k = torch.randn((B, Hkv, N, D), device="cuda", dtype=torch.bfloat16, generator=gen)
+    v = torch.randn((B, Hkv, N, D), device="cuda", dtype=torch.bfloat16, generator=gen)
+    print("[gpu] forward", flush=True)
+    out, lse = binding.swaa_attn_fwd(q, k, v, W, S)
+    torch.cuda.synchronize()
+    rng = np.random.Generator(np.random.Philox(9970))
+    samples = [(h, r) for h in (0, 7, 8, 15, 16, 19) for r in (0, 1, S, W - 1, W, W + 1, N // 2, N - 2, N - 1)]
+    samples += [(int(rng.integers(Hq)), int(rng.integers(N))) for _ in range(40)]
+
+    def bits(t):
+        return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+    worst_o = worst_l = 0.0
+    for h, r in samples:
+        lo = max(0, r - W + 1)
+        keys = list(range(min(S, lo))) + list(range(lo, r + 1))
+        idx = torch.tensor(keys, device="cuda")
+        ks, vs = k[:, h // G:h // G + 1].index_select(2, idx), v[:, h // G:h // G + 1].index_select(2, idx)
+        ro, rl = swaa_decode_oracle(bits(q[:, h:h + 1, r:r + 1]), bits(ks), bits(vs), W, min(S, lo), 1 / math.sqrt(D))
+        worst_o = max(worst_o, float(np.abs(out[0, h, r].float().cpu().numpy() - ro[0, 0, 0]).max()))
+        worst_l = max(worst_l, abs(float(lse[0, h, r]) - float(rl[0, 0, 0])))
+    print(f"[parity] million tokens, {len(samples)} sampled rows: O max-abs {worst_o:.3e}; LSE max-abs {worst_l:.3e}", flush=True)
+    assert worst_o <= 2e-2 and worst_l <= 1e-3
+    # every row was written: no NaN left from an untouched output, and LSE within the range scores allow
+    assert torch.isfinite(lse).all() and torch.isfinite(out[:, ::7].float()).all()
