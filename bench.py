@@ -45,6 +45,7 @@ MEASURED_TRAFFIC_BYTES = {
     "long128k_full": (1.833e11, "profiles/swaa_fwd_pipelined_long128k_full.txt"),
     "decode128k_full": (5.41e8, "profiles/swaa_decode_decode128k_full.txt"),
     "decode16k_b16": (1.079e9, "profiles/swaa_decode_decode16k_b16.txt"),
+    "decode128k_swa": (3.67e7, "profiles/swaa_decode_decode128k_swa.txt"),
     "mid_bwd": (1.63e9, "profiles/swaa_bwd_mid_bwd.txt"),
 }
 MIN_WARMUP_S = 0.05  # the clocks settle only after some tens of ms of continuous work
