@@ -240,7 +240,9 @@ __device__ __forceinline__ void pipelined_substep(const LaneAddr &la, const Half
 // max-based second pass; so does a sum of rounded P below 2^-6 (a row without a visible
 // key in its first half has reference 0, and if all its scores lie several nats below that
 // its terms are subnormal or vanish).
-template <bool kF16>
+// kPaged: k and v are a paged cache addressed through p.block_table (its own instantiation, so
+// that the contiguous kernel carries none of the table arithmetic).
+template <bool kF16, bool kPaged>
 __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const FwdParams p) {
     WorkItem wi;
     if (!decode_work(p, wi)) return;
@@ -344,13 +346,13 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     // half, where it starts, whether its rows run past the sequence's last row (then they
     // repeat that row -- they are masked later -- so that the reads stay in bounds; the padding
     // half repeats the last real half).  A tile that does not exist is not copied.
-    const int *bt = p.block_table ? p.block_table + (size_t)wi.b * p.bt_stride : nullptr;
+    const int *bt = kPaged ? p.block_table + (size_t)wi.b * p.bt_stride : nullptr;
     auto issue_tile = [&](int j, int buf, bool is_k) __attribute__((always_inline)) {
         if (2 * j >= n_halves) return;
         const int g = min(half_of(2 * j + hslot), hb_hi);
         const uint32_t rsb = is_k ? k_rsb : v_rsb;
         const uint32_t l = (uint32_t)((is_k ? 0 : kVRing) + buf * kTileBytes + wave * 4096);
-        if (bt) {
+        if constexpr (kPaged) {
             // Paged cache: this wave's 16 rows start at a multiple of 16, so they share a page and
             // the table lookup is uniform.  A block that starts past the last token is replaced by
             // the block that holds it, rows past it repeat it (all masked later); the page number
@@ -518,9 +520,38 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     };
     // the lean step's copies: this wave's half of K tile t + 2 and of V tile t + 1
     const char *k_next = nullptr, *v_next = nullptr;
+    // The lean step over a paged cache: the 16 rows a wave copies per tile lie in one page (page
+    // sizes are multiples of 16), so a copy needs that page's number -- a block-table entry, a
+    // scalar load.  It is asked for one step ahead: on entry (pg_k, in_k) are page and row
+    // inside it of this wave's rows of K tile t + 2, (pg_v, in_v) those of V tile t + 1 (the
+    // keys of K tile t + 1, so last step's pg_k), and the entry of tile t + 3 is requested
+    // before the arithmetic and has landed when the step ends.
+    int pg_k = 0, in_k = 0, pg_v = 0, in_v = 0, key_n = 0;
+    auto paged_base = [&](bool is_k, int page, int in_page) __attribute__((always_inline)) {
+        // (the row offsets in voff_* count from the half's first row: step back this wave's hrow0 rows;
+        // the page number is clamped to the cache whatever the table says)
+        page = min(max(page, 0), p.num_pages - 1);
+        return reinterpret_cast<const char *>(is_k ? kg : vg) + ((long long)page * (is_k ? p.k_sb : p.v_sb)) * 2 +
+               (long long)(in_page - hrow0) * (long long)(is_k ? k_rsb : v_rsb);
+    };
     auto lean_step = [&](auto ring_pos) __attribute__((always_inline)) {
         constexpr int R = decltype(ring_pos)::value;
+        int pg_n = 0, in_n = 0;
+        if constexpr (kPaged) {
+            key_n += kBk;
+            const int kc = min(key_n, (Nk - 1) & ~15);  // (past the lean range the entry is asked for but not used)
+            pg_n = bt[kc / p.page_size];
+            in_n = kc % p.page_size;
+        }
         substeps(ring_pos, false, 0, false, 0);
+        if constexpr (kPaged) {
+            k_next = paged_base(true, pg_k, in_k);
+            v_next = paged_base(false, pg_v, in_v);
+            pg_v = pg_k;
+            in_v = in_k;
+            pg_k = pg_n;
+            in_k = in_n;
+        }
         copy4(voff_k, k_next, (uint32_t)(R * kTileBytes + wave * 4096));
         k_next += (size_t)kBk * k_rsb;
         copy4(voff_v, v_next, (uint32_t)(kVRing + (1 - R) * kTileBytes + wave * 4096));
@@ -535,11 +566,20 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     // in pairs: odd, even).
     const int lean_end = min(jb, ((n_halves - 6 - (last_ragged ? 1 : 0)) >> 1) + 1);
     const int lean_begin = ja | 1;
-    bool lean_pending = lean_begin + 1 < lean_end && !bt;  // (a paged cache has no "next 64 rows")
+    bool lean_pending = lean_begin + 1 < lean_end;
     for (int t = 1; t < J;) {  // t is odd here
         if (lean_pending && t == lean_begin) {
-            k_next = reinterpret_cast<const char *>(kg) + (size_t)(32 * half_of(2 * t + 4 + hslot)) * k_rsb;
-            v_next = reinterpret_cast<const char *>(vg) + (size_t)(32 * half_of(2 * t + 2 + hslot)) * v_rsb;
+            if constexpr (!kPaged) {
+                k_next = reinterpret_cast<const char *>(kg) + (size_t)(32 * half_of(2 * t + 4 + hslot)) * k_rsb;
+                v_next = reinterpret_cast<const char *>(vg) + (size_t)(32 * half_of(2 * t + 2 + hslot)) * v_rsb;
+            } else {
+                // (both tiles are band tiles inside the sequence: their keys are 64 apart)
+                key_n = 32 * half_of(2 * t + 4 + hslot) + hrow0;
+                pg_k = bt[key_n / p.page_size];
+                in_k = key_n % p.page_size;
+                pg_v = bt[(key_n - kBk) / p.page_size];
+                in_v = (key_n - kBk) % p.page_size;
+            }
             for (; t + 1 < lean_end; t += 2) {
                 lean_step(odd);
                 lean_step(even);
@@ -568,8 +608,12 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     // (workgroup-wide OR through four flag words at the start of the V buffer that does NOT hold
     // the last tile: other waves may still be reading the last tile's V rows in their tail, and
     // the K ring becomes the O staging area right after the vote)
+    // (what the rest of the kernel needs of the lane id is worked out again here, so that it
+    // occupies no registers through the key loop)
+    const int lane_e = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    const int l32_e = lane_e & 31;
     float l_row = half_swap_sum(rs.l);
-    float lb_row = rowsum_of_column(lsum, l32);
+    float lb_row = rowsum_of_column(lsum, l32_e);
     bool redo;
     {
         // a sum inside (kSumFloor, kSumLimit), tested on the bit pattern: positive floats order like
@@ -582,9 +626,9 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
         // row whose terms all sank into (or below) the subnormals has a small sum of rounded P
         // (a row that took its reference from a visible key has a term of 2^4)
         const bool p_sound = !kF16 || (__float_as_uint(lb_row) - 0x3c800000u) < (0x7f800000u - 0x3c800000u);  // [2^-6, inf)
-        const int mine = __any(!(in_range && p_sound) && r0 + l32 < Nq) ? 1 : 0;
+        const int mine = __any(!(in_range && p_sound) && r0 + l32_e < Nq) ? 1 : 0;
         const uint32_t flag_base = (uint32_t)(kVRing + (J & 1) * kTileBytes);
-        if (lane == 0) *(int __attribute__((address_space(3))) *)(uintptr_t)(flag_base + wave * 4) = mine;
+        if (lane_e == 0) *(int __attribute__((address_space(3))) *)(uintptr_t)(flag_base + wave * 4) = mine;
         __syncthreads();
         int any = 0;
 #pragma unroll
@@ -634,6 +678,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     // of the K ring, which nobody reads any more), so that the stores to HBM are whole rows;
     // lse = (mc + log2 l) * ln 2 -------------------
     {
+        const int lane = lane_e, l32 = l32_e, hf = lane_e >> 5, lrow = lane_e >> 4, lchk = lane_e & 15;
         const uint32_t stage = (uint32_t)(wave * kStageBytes);
         const float inv_l = 1.f / lb_row;  // rows past the end: never stored
         const int fr = ((l32 & 7) << 1) | ((l32 >> 3) & 1);
@@ -669,10 +714,15 @@ hipError_t launch_fwd_pipelined_d128(const FwdParams &p, hipStream_t stream) {
     const unsigned grid = (unsigned)(p.chunk * kXcds);
     // (64 KiB of dynamic LDS is what a kernel gets without asking)
     static_assert(kSmemBytes <= 64 * 1024, "more would need hipFuncSetAttribute");
-    if (p.fp16)
-        hipLaunchKernelGGL(swaa_fwd_pipelined_kernel<true>, dim3(grid), dim3(kPThreads), kSmemBytes, stream, p);
+    const bool paged = p.block_table != nullptr;
+    if (p.fp16 && paged)
+        hipLaunchKernelGGL((swaa_fwd_pipelined_kernel<true, true>), dim3(grid), dim3(kPThreads), kSmemBytes, stream, p);
+    else if (p.fp16)
+        hipLaunchKernelGGL((swaa_fwd_pipelined_kernel<true, false>), dim3(grid), dim3(kPThreads), kSmemBytes, stream, p);
+    else if (paged)
+        hipLaunchKernelGGL((swaa_fwd_pipelined_kernel<false, true>), dim3(grid), dim3(kPThreads), kSmemBytes, stream, p);
     else
-        hipLaunchKernelGGL(swaa_fwd_pipelined_kernel<false>, dim3(grid), dim3(kPThreads), kSmemBytes, stream, p);
+        hipLaunchKernelGGL((swaa_fwd_pipelined_kernel<false, false>), dim3(grid), dim3(kPThreads), kSmemBytes, stream, p);
     return hipGetLastError();
 }
 
