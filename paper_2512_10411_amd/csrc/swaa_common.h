@@ -22,6 +22,28 @@ constexpr int kWaveRows = 64;  // ... of 64 query rows each (the pipelined kerne
 constexpr int kWgRows = 256;   // query rows (head x position) per workgroup of the plain and backward kernels
 constexpr int kXcds = 8;       // accelerator dies; workgroups are dealt to them round-robin
 
+// Division of a number below 2^31 by a divisor fixed at launch, as a multiplication: with
+// l = ceil(log2 d) and m = ceil(2^(31 + l) / d) (which fits 32 bits), n / d = (n * m) >> (31 + l)
+// exactly: m d - 2^(31 + l) < d <= 2^l, so the product overshoots n / d by less than 1 / d.
+// Every wave of every workgroup decodes its work item with three such divisions; done the long
+// way they are about a hundred instructions in front of the first memory request.
+struct FastDiv {
+    unsigned m;
+    int sh;  // negative: the divisor is 1
+};
+inline FastDiv make_fastdiv(unsigned d) {
+    FastDiv f{0u, -1};
+    if (d <= 1) return f;
+    int l = 0;
+    while ((1ull << l) < d) ++l;
+    f.m = (unsigned)(((1ull << (31 + l)) + d - 1) / d);
+    f.sh = l - 1;
+    return f;
+}
+__device__ __forceinline__ unsigned fastdiv(unsigned n, const FastDiv f) {
+    return f.sh < 0 ? n : __umulhi(n, f.m) >> f.sh;
+}
+
 struct FwdParams {
     const __bf16 *q;
     const __bf16 *k;
@@ -57,6 +79,7 @@ struct FwdParams {
     int wg_rows;  // 256 (plain forward and backward kernels) or 128 (pipelined forward)
     int n4, has2, has1;
     int nt_h4, nt_h2, nt_h1;  // row tiles of a sequence of Nq rows for workgroups of 4, 2 and 1 heads
+    FastDiv div_tiles_per_pair, div_hkv, div_nt_h4;  // for the work-list decode of every workgroup
     int tiles_per_pair;
     long long total_items;
     long long chunk;  // work items per XCD
@@ -117,13 +140,13 @@ __device__ __forceinline__ bool decode_work(const FwdParams &p, WorkItem &w) {
     const unsigned item = (bid % kXcds) * chunk + slot;
     if (slot >= chunk || item >= (unsigned)p.total_items) return false;
     const unsigned tpp = (unsigned)p.tiles_per_pair, hkv = (unsigned)p.Hkv;
-    const unsigned pair = item / tpp;
+    const unsigned pair = fastdiv(item, p.div_tiles_per_pair);
     unsigned r = item - pair * tpp;
-    w.b = (int)(pair / hkv);
+    w.b = (int)fastdiv(pair, p.div_hkv);
     w.kvh = (int)(pair - (unsigned)w.b * hkv);
     const unsigned nt4 = (unsigned)p.nt_h4, nt2 = (unsigned)p.nt_h2;
     if (r < (unsigned)p.n4 * nt4) {
-        const unsigned g = r / nt4;
+        const unsigned g = fastdiv(r, p.div_nt_h4);
         w.hpb = 4;
         w.h0 = 4 * (int)g;
         w.pt = (int)(nt4 - 1 - (r - g * nt4));
@@ -155,6 +178,9 @@ inline bool plan_work(FwdParams &p, int rows, int wg_rows) {
     p.nt_h1 = (rows + wg_rows - 1) / wg_rows;
     p.tiles_per_pair = p.n4 * p.nt_h4 + p.has2 * p.nt_h2 + p.has1 * p.nt_h1;
     p.total_items = (long long)p.B * p.Hkv * p.tiles_per_pair;
+    p.div_tiles_per_pair = make_fastdiv((unsigned)p.tiles_per_pair);
+    p.div_hkv = make_fastdiv((unsigned)p.Hkv);
+    p.div_nt_h4 = make_fastdiv((unsigned)p.nt_h4);
     p.chunk = (p.total_items + kXcds - 1) / kXcds;
     return p.chunk * kXcds <= 0x7fffffffLL;
 }
