@@ -174,3 +174,26 @@ def test_packed_chunks_over_a_paged_cache_with_different_lengths():
         ro, rl = swaa_decode_oracle(q, k, v, W, S, 1 / math.sqrt(D))
         assert_parity(out[None, :, r0:r0 + nq[b]], lse[None, :, r0:r0 + nq[b]], ro, rl, tag=f"packed paged seq {b}")
         r0 += nq[b]
+
+
+@pytest.mark.parametrize("page_size", [16, 48, 256])
+def test_paged_prefill_equals_the_contiguous_call_bit_for_bit(page_size):
+    # long unmasked stretches of the band, where the paged kernel asks for its block-table
+    # entries one step ahead: same arithmetic as the contiguous kernel, so the same bits
+    B, Hq, Hkv, N, D = 2, 10, 2, 6144, 128
+    gen = torch.Generator(device="cuda").manual_seed(8870 + page_size)
+    q = torch.randn((B, Hq, N, D), device="cuda", dtype=torch.bfloat16, generator=gen)
+    k = torch.randn((B, Hkv, N, D), device="cuda", dtype=torch.bfloat16, generator=gen)
+    v = torch.randn((B, Hkv, N, D), device="cuda", dtype=torch.bfloat16, generator=gen)
+    npg = N // page_size
+    perm = torch.randperm(B * npg + 5, device="cuda", generator=gen)[:B * npg]
+    table = perm.view(B, npg).to(torch.int32)
+    kc = torch.full((B * npg + 5, Hkv, page_size, D), float("nan"), device="cuda", dtype=torch.bfloat16)
+    vc = torch.zeros_like(kc)
+    kc[perm] = k.view(B, Hkv, npg, page_size, D).permute(0, 2, 1, 3, 4).reshape(B * npg, Hkv, page_size, D)
+    vc[perm] = v.view(B, Hkv, npg, page_size, D).permute(0, 2, 1, 3, 4).reshape(B * npg, Hkv, page_size, D)
+    for W, S, P in ((1500, 4, None), (N, 0, None), (700, 100, 6000)):
+        o1, l1 = binding.swaa_attn_fwd_ex(q, k, v, W, S, P)
+        o2, l2 = binding.swaa_attn_fwd_ex(q, kc, vc, W, S, P, block_table=table, max_seqlen_k=N)
+        torch.cuda.synchronize()
+        assert torch.equal(o1, o2) and torch.equal(l1, l2), (page_size, W, S, P)
