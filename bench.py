@@ -208,6 +208,11 @@ def main():
         ws = torch.empty(binding.swaa_attn_decode_workspace_bytes(w.B, w.Hq, w.Hkv, w.n_query, w.N, w.D, w.window,
                                                                   w.n_sink), dtype=torch.uint8, device="cuda")
 
+    if w.page_size:
+        # the same keys and values as a paged cache (pages in a seeded random order)
+        from paper_2512_10411_amd.inputs import paged_cache
+        kd, vd, table = paged_cache(kd, vd, w.page_size, w.seed + 31)
+
     if w.backward:
         import numpy as np
         from paper_2512_10411_amd.inputs import f32_to_bf16_bits
@@ -221,9 +226,15 @@ def main():
         if w.backward:
             binding.swaa_attn_bwd(qd, kd, vd, out, lse, dd, w.window, w.n_sink, None, w.scale, workspace=bws,
                                   stream=stream)
+        elif decode and w.page_size:
+            binding.swaa_attn_decode_ex(qd, kd, vd, w.window, w.n_sink, w.scale, block_table=table, max_seqlen_k=w.N,
+                                        out=out, lse=lse, workspace=ws, stream=stream)
         elif decode:
             binding.swaa_attn_decode(qd, kd, vd, w.window, w.n_sink, w.scale, out=out, lse=lse, workspace=ws,
                                      stream=stream)
+        elif w.page_size:
+            binding.swaa_attn_fwd_ex(qd, kd, vd, w.window, w.n_sink, w.n_prompt, w.scale, out=out, lse=lse,
+                                     stream=stream, block_table=table, max_seqlen_k=w.N)
         elif w.chunk or w.fmt == "fp16":
             binding.swaa_attn_fwd_ex(qd, kd, vd, w.window, w.n_sink, w.n_prompt, w.scale, out=out, lse=lse,
                                      stream=stream)
@@ -356,7 +367,7 @@ def main():
         from oracle import input_format
         with input_format(w.fmt):
             res["cpu_baseline"] = (cpu_baseline_backward(w, q, k, v, dout) if w.backward
-                                   else cpu_baseline_decode(w, q, k, v) if decode or w.chunk
+                                   else cpu_baseline_decode(w, q, k, v) if decode or (w.chunk and w.n_query < w.N)
                                    else cpu_baseline(w, q, k, v, args.cpu_seconds))
         res["cpu_baseline"]["gpu_over_cpu"] = value / res["cpu_baseline"]["value"]
     print(json.dumps(res), flush=True)

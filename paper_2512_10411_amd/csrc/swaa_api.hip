@@ -221,6 +221,7 @@ int decode_call(const swaa_decode_args *a, bool own_scratch) {
         if (bad_stride(t->stride_n, false) || t->stride_n < a->D || t->stride_n >= (1LL << 22)) return SWAA_ERR_SHAPE;
         if (bad_stride(t->stride_h, a->Hkv == 1) || bad_stride(t->stride_b, paged ? a->num_pages == 1 : a->B == 1))
             return SWAA_ERR_SHAPE;
+        if (paged && t->stride_b >= (1LL << 31)) return SWAA_ERR_SHAPE;  // a page of 4 GiB and more: not a page
     }
     if (misaligned(a->q) || misaligned(a->out)) return SWAA_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(a->lse) & 3u) != 0) return SWAA_ERR_ALIGN;
@@ -245,6 +246,7 @@ int decode_call(const swaa_decode_args *a, bool own_scratch) {
     p.bt_stride = a->block_table_stride;
     p.page_size = paged ? a->page_size : 1;
     p.num_pages = paged ? a->num_pages : 1;
+    p.div_page = swaa::make_fastdiv((unsigned)p.page_size);
     p.seq_lens = a->seq_lens;
     p.ws_o = static_cast<float *>(workspace);
     p.ws_ml = p.ws_o + p.items * (long long)p.col_stride * 128;

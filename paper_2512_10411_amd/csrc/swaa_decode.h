@@ -5,6 +5,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include "swaa_common.h"
+
 namespace swaa {
 
 // The query rows of one (batch, KV head) pair -- G heads x Nq rows, contiguous
@@ -39,8 +41,10 @@ struct DecodeParams {
     int col_stride;  // min(cols, 32): columns an item stores
     int n_halves;  // upper bound on the halves a sequence of at most Nk tokens visits
     int halves_per_split, n_splits;
-    long long items;  // B * Hkv * n_coltiles * n_splits
+    long long items;  // B * Hkv * n_coltiles * n_splits (below 2^31)
     int fp16;         // elements of q, k, v, out are IEEE binary16 instead of bfloat16
+    // divisions every workgroup makes, as multiplications (FastDiv)
+    FastDiv div_coltiles, div_splits, div_hkv, div_page;
 };
 
 // The halves a sequence of nk cached tokens visits: halves 0 .. n_sink-1, then key halves band0 ..

@@ -46,18 +46,23 @@ constexpr int kCopiesPerHalf = 16;                    // wave instructions per s
 constexpr int kMergeThreads = 1024;
 constexpr int kRounds = 1;  // rounds of resident workgroups the split plan aims for
 
-template <bool kF16>
+// kPaged: k and v are a paged cache addressed through p.block_table (its own instantiation).
+template <bool kF16, bool kPaged>
 __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParams p) {
     // XCD x takes the x-th contiguous chunk of the item list (column tiles of one
-    // split, which read the same keys, then run behind the same L2)
-    const long long chunk = (p.items + kXcds - 1) / kXcds;
-    const long long slot = blockIdx.x / kXcds;
-    const long long item = (long long)(blockIdx.x % kXcds) * chunk + slot;
-    if (slot >= chunk || item >= p.items) return;
-    const int ct = (int)(item % p.n_coltiles);
-    const int split = (int)((item / p.n_coltiles) % p.n_splits);
-    const int pair = (int)(item / ((long long)p.n_coltiles * p.n_splits));
-    const int b = pair / p.Hkv, kvh = pair % p.Hkv;
+    // split, which read the same keys, then run behind the same L2).  The list has fewer
+    // than 2^31 items: 32-bit arithmetic, divisions as multiplications.
+    const unsigned items = (unsigned)p.items;
+    const unsigned chunk = (items + kXcds - 1) / kXcds;
+    const unsigned slot = blockIdx.x / kXcds;
+    const unsigned item = (blockIdx.x % kXcds) * chunk + slot;
+    if (slot >= chunk || item >= items) return;
+    const unsigned item_ct = fastdiv(item, p.div_coltiles);       // item / n_coltiles
+    const int ct = (int)(item - item_ct * (unsigned)p.n_coltiles);
+    const unsigned upair = fastdiv(item_ct, p.div_splits);        // item / (n_coltiles * n_splits)
+    const int split = (int)(item_ct - upair * (unsigned)p.n_splits);
+    const int pair = (int)upair;
+    const int b = (int)fastdiv(upair, p.div_hkv), kvh = pair - b * p.Hkv;
 
     const int lane = threadIdx.x;
     const int l32 = lane & 31;
@@ -90,37 +95,102 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
         return 32 * (h < vh.n_sink ? h : h - vh.n_sink + vh.band0);
     };
 
-    const bool paged = p.block_table != nullptr;
+    constexpr bool paged = kPaged;
     const uint32_t k_rsb = (uint32_t)(p.k_sn * 2), v_rsb = (uint32_t)(p.v_sn * 2);  // row strides in bytes
     const char *kg = reinterpret_cast<const char *>(p.k + (paged ? 0 : b * p.k_sb) + (long long)kvh * p.k_sh);
     const char *vg = reinterpret_cast<const char *>(p.v + (paged ? 0 : b * p.v_sb) + (long long)kvh * p.v_sh);
-    const int *bt = paged ? p.block_table + (size_t)b * p.bt_stride : nullptr;
+    // (the table is only read while the kernel runs: addressed as constant memory, so that the
+    // lookups are scalar loads -- as vector loads they would share the tile copies' counter, and
+    // waiting for a table entry would mean waiting for every copy in flight)
+    typedef const int __attribute__((address_space(4))) *TablePtr;
+    const TablePtr bt = paged ? (TablePtr)(p.block_table + (size_t)b * p.bt_stride) : nullptr;
 
     // ---- HBM -> LDS copies of one half: instruction i moves rows 4i .. 4i+3, 16 lanes
     // per row; the XOR swizzle of the operand reads is applied on the global side.  Rows
     // past the end of the cache repeat its last row (they are masked later). ----
     const int lrow = lane >> 4, lchk = lane & 15;
-    auto issue_half = [&](int t, int stage) {
+    // Paged cache: the block-table entries one half needs -- one if a page holds a multiple of 32
+    // tokens, two for a multiple of 16, else none here (looked up per copy instruction).  They
+    // are scalar loads with a long way to go, asked for one loop iteration before the copy.
+    struct Pages {
+        int a, b;
+    };
+    const int pages_per_half = !paged ? 0 : p.page_size % 32 == 0 ? 1 : p.page_size % 16 == 0 ? 2 : 0;
+    auto lookup = [&](int t) __attribute__((always_inline)) {
+        Pages pg{0, 0};
+        if constexpr (paged) {
+            if (pages_per_half != 0) {
+                const int k0 = first_key(t);
+                pg.a = bt[fastdiv((unsigned)k0, p.div_page)];
+                pg.b = pages_per_half == 2 ? bt[fastdiv((unsigned)min(k0 + 16, Nk - 1), p.div_page)] : pg.a;
+            }
+        }
+        return pg;
+    };
+    auto issue_half = [&](int t, int stage, const Pages pg) __attribute__((always_inline)) {
         const int k0 = first_key(t);
         const uint32_t lds = (uint32_t)(stage * kDStageBytes);
-        if (paged) {
-            // page_size is a multiple of 4, halves start at multiples of 32: the four rows of one
-            // instruction share a page, so the page number is a uniform (scalar) table lookup
+        if constexpr (paged) {
+            if (pages_per_half == 0) {
+                // page_size is a multiple of 4 only: the four rows of one instruction share a
+                // page, so the page number is a uniform (scalar) table lookup per instruction
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int key4 = min(k0 + 4 * i, Nk - 1) & ~3;  // first row of the instruction, inside the cache
+                    const unsigned pi = fastdiv((unsigned)key4, p.div_page);
+                    const int page = min(max(bt[pi], 0), p.num_pages - 1);  // inside the cache whatever the table says
+                    const int in_page = key4 - (int)pi * p.page_size;
+                    const char *kb = kg + ((long long)page * p.k_sb + (long long)in_page * p.k_sn) * 2;
+                    const char *vb = vg + ((long long)page * p.v_sb + (long long)in_page * p.v_sn) * 2;
+                    const int row = min(key4 + lrow, Nk - 1) - key4;
+                    const int fk = ((4 * (i & 1) + lrow) << 1) | ((i >> 1) & 1);
+                    const uint32_t koff = (uint32_t)row * k_rsb + (uint32_t)((lchk ^ fk) << 4);
+                    const uint32_t voff = (uint32_t)row * v_rsb + (uint32_t)((lchk ^ (lrow << 2)) << 4);
+                    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(koff), "s"(kb),
+                                 "s"(lds + (uint32_t)(i * 1024))
+                                 : "memory");
+                    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(vb),
+                                 "s"(lds + (uint32_t)(kHalfBytes + i * 1024))
+                                 : "memory");
+                }
+                return;
+            }
+            // page_size a multiple of 16: rows 0..15 of the half lie in one page, rows 16..31 in one
+            // (the same one if page_size is a multiple of 32); their numbers came with `pg`.  Row
+            // offsets count from the half's first row, so the second base steps back 16 rows; if
+            // the cache ends inside the first 16 rows, every later row repeats its last row there.
+            // (page strides and row strides of a paged cache fit 32 bits -- the entry point checks --
+            // so each product is one 32 x 32 -> 64 bit multiplication, not the 64 x 64 bit one that
+            // costs six: this arithmetic sits in front of every copy of the wave's only instruction stream)
+            auto base_of = [](const char *g, long long sb, long long sn, int page, int row) __attribute__((always_inline)) {
+                const long long elems = (long long)((unsigned long long)(unsigned)page * (unsigned)sb) + (long long)row * (int)sn;
+                return g + 2 * elems;
+            };
+            const int in_a = k0 - (int)fastdiv((unsigned)k0, p.div_page) * p.page_size;
+            const int page_a = min(max(pg.a, 0), p.num_pages - 1);
+            const char *kb[2], *vb[2];
+            kb[0] = kb[1] = base_of(kg, p.k_sb, p.k_sn, page_a, in_a);
+            vb[0] = vb[1] = base_of(vg, p.v_sb, p.v_sn, page_a, in_a);
+            if (pages_per_half == 2 && k0 + 16 <= Nk - 1) {
+                const int in_b = k0 + 16 - (int)fastdiv((unsigned)(k0 + 16), p.div_page) * p.page_size;
+                const int page_b = min(max(pg.b, 0), p.num_pages - 1);
+                kb[1] = base_of(kg, p.k_sb, p.k_sn, page_b, in_b - 16);
+                vb[1] = base_of(vg, p.v_sb, p.v_sn, page_b, in_b - 16);
+            }
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const int key4 = min(k0 + 4 * i, Nk - 1) & ~3;  // first row of the instruction, inside the cache
-                const int page = min(max(bt[key4 / p.page_size], 0), p.num_pages - 1);  // inside the cache whatever the table says
-                const int in_page = key4 % p.page_size;
-                const char *kb = kg + ((long long)page * p.k_sb + (long long)in_page * p.k_sn) * 2;
-                const char *vb = vg + ((long long)page * p.v_sb + (long long)in_page * p.v_sn) * 2;
-                const int row = min(key4 + lrow, Nk - 1) - key4;
+                const int row = min(4 * i + lrow, Nk - 1 - k0);
                 const int fk = ((4 * (i & 1) + lrow) << 1) | ((i >> 1) & 1);
-                const uint32_t koff = (uint32_t)row * k_rsb + (uint32_t)((lchk ^ fk) << 4);
-                const uint32_t voff = (uint32_t)row * v_rsb + (uint32_t)((lchk ^ (lrow << 2)) << 4);
-                asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(koff), "s"(kb),
+                const uint32_t off = (uint32_t)row * k_rsb + (uint32_t)((lchk ^ fk) << 4);
+                asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(kb[i / 4]),
                              "s"(lds + (uint32_t)(i * 1024))
                              : "memory");
-                asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(vb),
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int row = min(4 * i + lrow, Nk - 1 - k0);
+                const uint32_t off = (uint32_t)row * v_rsb + (uint32_t)((lchk ^ (lrow << 2)) << 4);
+                asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(vb[i / 4]),
                              "s"(lds + (uint32_t)(kHalfBytes + i * 1024))
                              : "memory");
             }
@@ -165,9 +235,9 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
                          : "memory");
         }
     }
-    issue_half(0, 0);
+    issue_half(0, 0, lookup(0));
     if (n_mine >= 2) {
-        issue_half(1, 1);
+        issue_half(1, 1, lookup(1));
         asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
     } else {
         asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
@@ -178,7 +248,8 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
     // (the idle cycles keep the copies two wait states away from the first MFMA that reads them)
     asm volatile("s_nop 1"
                  : "+a"(qf[0]), "+a"(qf[1]), "+a"(qf[2]), "+a"(qf[3]), "+a"(qf[4]), "+a"(qf[5]), "+a"(qf[6]), "+a"(qf[7]));
-    if (n_mine >= 3) issue_half(2, 2);
+    if (n_mine >= 3) issue_half(2, 2, lookup(2));
+    Pages pg_next = n_mine >= 4 ? lookup(3) : Pages{0, 0};  // of the half the loop's first iteration issues
 
     f32x16 oacc[kDB];
 #pragma unroll
@@ -221,7 +292,8 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
 #pragma unroll
             for (int db = 0; db < kDB; ++db) vf[st][db] = load_v_frag(la, so + kHalfBytes, st, db);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        if (t + kDStages < n_mine) issue_half(t + kDStages, stage);
+        if (t + kDStages < n_mine) issue_half(t + kDStages, stage, pg_next);
+        if (t + kDStages + 1 < n_mine) pg_next = lookup(t + kDStages + 1);  // lands under this iteration's arithmetic
 
         f32x16 s;
         bf16x8 pf[2];
@@ -366,6 +438,9 @@ void plan_decode(DecodeParams &p) {
     p.halves_per_split = (int)hps;
     p.n_splits = (int)((p.n_halves + hps - 1) / hps);
     p.items = groups * p.n_splits;
+    p.div_coltiles = make_fastdiv((unsigned)p.n_coltiles);
+    p.div_splits = make_fastdiv((unsigned)p.n_splits);
+    p.div_hkv = make_fastdiv((unsigned)p.Hkv);
 }
 
 long long decode_workspace_floats(const DecodeParams &p) { return p.items * ((long long)p.col_stride * kD + 64); }
@@ -400,10 +475,15 @@ hipError_t decode_static_scratch(void **ptr) {
 hipError_t launch_decode(const DecodeParams &p, hipStream_t stream) {
     const long long chunk = (p.items + kXcds - 1) / kXcds;
     const dim3 grid((unsigned)(chunk * kXcds));
-    if (p.fp16)
-        hipLaunchKernelGGL(swaa_decode_split_kernel<true>, grid, dim3(64), kDSmemBytes, stream, p);
+    const bool paged = p.block_table != nullptr;
+    if (p.fp16 && paged)
+        hipLaunchKernelGGL((swaa_decode_split_kernel<true, true>), grid, dim3(64), kDSmemBytes, stream, p);
+    else if (p.fp16)
+        hipLaunchKernelGGL((swaa_decode_split_kernel<true, false>), grid, dim3(64), kDSmemBytes, stream, p);
+    else if (paged)
+        hipLaunchKernelGGL((swaa_decode_split_kernel<false, true>), grid, dim3(64), kDSmemBytes, stream, p);
     else
-        hipLaunchKernelGGL(swaa_decode_split_kernel<false>, grid, dim3(64), kDSmemBytes, stream, p);
+        hipLaunchKernelGGL((swaa_decode_split_kernel<false, false>), grid, dim3(64), kDSmemBytes, stream, p);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL(swaa_decode_merge_kernel, dim3((unsigned)((long long)p.B * p.Hq * p.Nq)), dim3(kMergeThreads), 0,

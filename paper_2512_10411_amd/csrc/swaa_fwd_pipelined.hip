@@ -346,7 +346,11 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     // half, where it starts, whether its rows run past the sequence's last row (then they
     // repeat that row -- they are masked later -- so that the reads stay in bounds; the padding
     // half repeats the last real half).  A tile that does not exist is not copied.
-    const int *bt = kPaged ? p.block_table + (size_t)wi.b * p.bt_stride : nullptr;
+    // (the table is only read while the kernel runs: addressed as constant memory, so that the
+    // lookups are scalar loads -- as vector loads they would share the tile copies' counter, and
+    // waiting for a table entry would mean waiting for every copy in flight)
+    typedef const int __attribute__((address_space(4))) *TablePtr;
+    const TablePtr bt = kPaged ? (TablePtr)(p.block_table + (size_t)wi.b * p.bt_stride) : nullptr;
     auto issue_tile = [&](int j, int buf, bool is_k) __attribute__((always_inline)) {
         if (2 * j >= n_halves) return;
         const int g = min(half_of(2 * j + hslot), hb_hi);

@@ -53,6 +53,7 @@ class Workload:
     backward: bool = False       # the timed call is the backward pass (the forward runs once, untimed)
     fmt: str = "bf16"            # element format of q, k, v, out: "bf16" or "fp16"
     recipe: str = "iid"          # "iid", or a structured score pattern laid over the draws (apply_recipe)
+    page_size: int = 0           # > 0: k and v are handed over as a paged cache of such pages in a seeded random order
 
     @property
     def scale(self) -> float:
@@ -85,6 +86,14 @@ WORKLOADS = {
     "decode128k_swa": Workload("decode128k_swa", 1, 32, 8, 131072, 128, 8192, 4, _SEED0 + 6, n_query=1),
     "decode16k_b16": Workload("decode16k_b16", 16, 32, 8, 16384, 128, 16384, 4, _SEED0 + 7, n_query=1),
     # the mid-size layer in binary16, the precision the paper serves in (Sec. 4.1.1); same draws
+    # the serving engine's cache layout (Sec. 4.1.1: vLLM, whose default page holds 16 tokens)
+    "decode16k_b16_paged": Workload("decode16k_b16_paged", 16, 32, 8, 16384, 128, 16384, 4, _SEED0 + 7, n_query=1,
+                                    page_size=16),
+    "decode128k_full_paged": Workload("decode128k_full_paged", 1, 32, 8, 131072, 128, 131072, 4, _SEED0 + 6, n_query=1,
+                                      page_size=16),
+    "mid_paged": Workload("mid_paged", 1, 32, 8, 16384, 128, 2048, 4, _SEED0 + 2, chunk=True, n_query=16384, page_size=16),
+    "long128k_swa_paged": Workload("long128k_swa_paged", 1, 32, 8, 131072, 128, 8192, 4, _SEED0 + 5, chunk=True,
+                                   n_query=131072, page_size=16),
     "mid_fp16": Workload("mid_fp16", 1, 32, 8, 16384, 128, 2048, 4, _SEED0 + 2, fmt="fp16"),
     # backward pass of the mid-size layer (fine-tuning under the window + sink mask)
     "mid_bwd": Workload("mid_bwd", 1, 32, 8, 16384, 128, 2048, 4, _SEED0 + 2, backward=True),
@@ -195,3 +204,24 @@ def sample_rows(N, window, n_sink, count=256, seed=0, tile=64):
         for r in rng.integers(0, N, size=count - len(rows)):
             rows.add(int(r))
     return np.array(sorted(rows), dtype=np.int32)
+
+
+def paged_cache(k, v, page_size: int, seed: int):
+    """Rearranges device tensors k, v [B, Hkv, N, D] (N a multiple of page_size) into a paged cache:
+    returns views (k_cache, v_cache) [num_pages, Hkv, page_size, D] and the int32 block table
+    [B, N / page_size], pages in a seeded random order with a few unused pages in between."""
+    import torch
+
+    B, Hkv, N, D = k.shape
+    assert N % page_size == 0
+    npg = N // page_size
+    num_pages = B * npg + 3
+    order = np.random.Generator(np.random.Philox(seed)).permutation(num_pages)[:B * npg].astype(np.int64)
+    perm = torch.from_numpy(order).to(k.device)
+    caches = []
+    for t in (k, v):
+        c = torch.zeros((num_pages, Hkv, page_size, D), dtype=t.dtype, device=t.device)
+        c[perm] = t.view(B, Hkv, npg, page_size, D).permute(0, 2, 1, 3, 4).reshape(B * npg, Hkv, page_size, D)
+        caches.append(c)
+    table = perm.view(B, npg).to(torch.int32)
+    return caches[0], caches[1], table

@@ -10,7 +10,8 @@ import torch
 
 from oracle import input_format, swaa_decode_oracle
 from paper_2512_10411_amd import binding
-from paper_2512_10411_amd.inputs import WORKLOADS, bf16_bits_to_f32, f32_to_bf16_bits, make_qkv, make_workload
+from paper_2512_10411_amd.inputs import (WORKLOADS, bf16_bits_to_f32, f32_to_bf16_bits, make_qkv, make_workload,
+                                          paged_cache)
 from gpu_util import assert_parity, to_device
 
 pytestmark = pytest.mark.gpu
@@ -102,14 +103,20 @@ def test_decode_rows_equal_one_pass_fa_decode_rows():
     assert (l1[:, :, P:] - l2).abs().max().item() <= 1e-3
 
 
-@pytest.mark.parametrize("name", ["decode128k_full", "decode128k_swa", "decode16k_b16"])
+@pytest.mark.parametrize("name", ["decode128k_full", "decode128k_swa", "decode16k_b16", "decode16k_b16_paged",
+                                  "decode128k_full_paged"])
 def test_decode_workloads_full_size(name):
     # full-size launches exactly as the benchmark times them; every output row is compared
     w = WORKLOADS[name]
     print(f"[gen] {name} ...", flush=True)
     q, k, v = make_workload(w)
     print(f"[gpu] {name}", flush=True)
-    out, lse = binding.swaa_attn_decode(to_device(q), to_device(k), to_device(v), w.window, w.n_sink, w.scale)
+    if w.page_size:  # the same keys and values as a paged cache, as the benchmark hands them over
+        kc, vc, table = paged_cache(to_device(k), to_device(v), w.page_size, w.seed + 31)
+        out, lse = binding.swaa_attn_decode_ex(to_device(q), kc, vc, w.window, w.n_sink, w.scale, block_table=table,
+                                               max_seqlen_k=w.N)
+    else:
+        out, lse = binding.swaa_attn_decode(to_device(q), to_device(k), to_device(v), w.window, w.n_sink, w.scale)
     torch.cuda.synchronize()
     print(f"[oracle] {name}", flush=True)
     ro, rl = swaa_decode_oracle(q, k, v, w.window, w.n_sink, w.scale)

@@ -11,7 +11,7 @@ import torch
 
 from oracle import swaa_attn_oracle, swaa_decode_oracle
 from paper_2512_10411_amd import binding
-from paper_2512_10411_amd.inputs import (WORKLOADS, bf16_bits_to_f32, f32_to_bf16_bits, make_qkv,
+from paper_2512_10411_amd.inputs import (WORKLOADS, bf16_bits_to_f32, f32_to_bf16_bits, make_qkv, paged_cache,
                                          make_workload, sample_rows)
 from gpu_util import assert_parity, errors as errors_of, to_device
 
@@ -243,7 +243,7 @@ def test_workload_tiny_all_rows():
 
 
 @pytest.mark.parametrize("names", [("mid",), ("pair32k_swa", "pair32k_full"), ("batched",),
-                                   ("long128k_swa", "long128k_full")])
+                                   ("long128k_swa", "long128k_full"), ("mid_paged",), ("long128k_swa_paged",)])
 def test_workload_full_size_sampled_rows(names):
     # full-size launch exactly as the benchmark times it; 256 sampled rows per head
     w0 = WORKLOADS[names[0]]
@@ -255,7 +255,13 @@ def test_workload_full_size_sampled_rows(names):
         assert w.seed == w0.seed
         rows = sample_rows(w.N, w.window, w.n_sink, count=256, seed=w.seed)
         print(f"[gpu] {name}", flush=True)
-        out, lse = binding.swaa_attn_fwd(qd, kd, vd, w.window, w.n_sink, w.scale)
+        if w.page_size:  # the same keys and values as a paged cache, as the benchmark hands them over
+            kc, vc, table = paged_cache(kd, vd, w.page_size, w.seed + 31)
+            out, lse = binding.swaa_attn_fwd_ex(qd, kc, vc, w.window, w.n_sink, None, w.scale, block_table=table,
+                                                max_seqlen_k=w.N)
+            del kc, vc
+        else:
+            out, lse = binding.swaa_attn_fwd(qd, kd, vd, w.window, w.n_sink, w.scale)
         torch.cuda.synchronize()
         assert torch.isfinite(lse).all()
         print(f"[oracle] {name}: {len(rows)} rows x {w.B * w.Hq} heads", flush=True)
