@@ -698,15 +698,17 @@ __global__ __launch_bounds__(kDkvThreads, 1) void swaa_bwd_dkv_dma_kernel(const 
             copy_rows(p.f.q + base * D, tq * kBq, 2 * wave + i, (uint32_t)(kQ + buf * kQTileBytes));
             copy_rows(p.dout + base * D, tq * kBq, 2 * wave + i, (uint32_t)(kDO + buf * kQTileBytes));
         }
+        // (asked for here, first touched in publish_rows at the end of the step: any arithmetic on
+        // them right away would make this wave wait for the loads, and with them for the copies above)
         if (tid < kBq) {
             const int row = min(tq * kBq + tid, N - 1);
-            lreg = p.f.lse[base + row] * 1.44269504088896340736f;
+            lreg = p.f.lse[base + row];
             dlreg = p.delta[base + row];
         }
     };
     auto publish_rows = [&](int buf) {
         if (tid < kBq) {
-            *(float __attribute__((address_space(3))) *)(uintptr_t)(kL + buf * kBq * 4 + tid * 4) = lreg;
+            *(float __attribute__((address_space(3))) *)(uintptr_t)(kL + buf * kBq * 4 + tid * 4) = lreg * 1.44269504088896340736f;
             *(float __attribute__((address_space(3))) *)(uintptr_t)(kDl + buf * kBq * 4 + tid * 4) = dlreg;
         }
     };
