@@ -21,7 +21,7 @@
 //     the stage just emptied, and only then the arithmetic runs: S^T = K Q^T (8
 //     MFMAs), max-based softmax (mask only on halves that are not fully visible),
 //     O^T += V^T P^T (8 MFMAs).  The copies thus never wait for arithmetic.  The
-//     query rows arrive through the ring's last stage before half 2 needs it.
+//     query rows are loaded from HBM in operand layout and parked in AccVGPRs.
 //   * The cache is a contiguous strided tensor or a paged one (a block table of
 //     page numbers per sequence, pages of page_size tokens: the layout of a
 //     serving engine's cache manager); sequences of a batch may have different
@@ -218,37 +218,25 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
     };
     const LaneAddr la = make_lane_addr(lane, 0);
 
-    // ---- start-up: the 32 query rows go first, into the K area of the last stage (laid out
-    // like a K half, so that the K fragment reader returns B operands of S^T = K Q^T); then
-    // halves 0 and 1.  Copies complete in order: once only those two are outstanding the
-    // query rows are there, get parked in AccVGPRs, and the last stage is free for half 2. ----
+    // ---- start-up: this lane's Q fragments (B operand of S^T = K Q^T: query row l32, 16 bytes at
+    // 32 ks + 16 hf) straight from HBM with ordinary loads, then the first three halves into the
+    // three stages.  The compiler places the wait for the Q loads in front of their first use,
+    // and that wait covers the copies issued behind them as well (it cannot see them): a short
+    // item has all its keys in flight at once and starts when they are there; a long one gives
+    // away the head start of its first two steps, once. ----
+    bf16x8 qf[kKS];
     {
-        const char *qg = reinterpret_cast<const char *>(p.q + ((size_t)b * p.Hq + (size_t)kvh * p.G) * p.Nq * kD);
-        const uint32_t lds = (uint32_t)((kDStages - 1) * kDStageBytes);
+        const char *qrow = reinterpret_cast<const char *>(p.q + ((size_t)b * p.Hq + (size_t)kvh * p.G) * p.Nq * kD) +
+                           (size_t)min(ct * 32 + l32, p.cols - 1) * kRowBytes + 16 * hf;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int qrow = min(ct * 32 + 4 * i + lrow, p.cols - 1);
-            const int fk = ((4 * (i & 1) + lrow) << 1) | ((i >> 1) & 1);
-            const uint32_t off = (uint32_t)(qrow * kRowBytes + ((lchk ^ fk) << 4));
-            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(qg),
-                         "s"(lds + (uint32_t)(i * 1024))
-                         : "memory");
-        }
+        for (int ks = 0; ks < kKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qrow + 32 * ks);
     }
     issue_half(0, 0, lookup(0));
-    if (n_mine >= 2) {
-        issue_half(1, 1, lookup(1));
-        asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
-    } else {
-        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-    }
-    bf16x8 qf[kKS];
-#pragma unroll
-    for (int ks = 0; ks < kKS; ++ks) qf[ks] = load_k_frag(la, (uint32_t)((kDStages - 1) * kDStageBytes), ks);
-    // (the idle cycles keep the copies two wait states away from the first MFMA that reads them)
+    if (n_mine >= 2) issue_half(1, 1, lookup(1));
+    if (n_mine >= 3) issue_half(2, 2, lookup(2));
+    // (the idle cycles keep the loads two wait states away from the first MFMA that reads them)
     asm volatile("s_nop 1"
                  : "+a"(qf[0]), "+a"(qf[1]), "+a"(qf[2]), "+a"(qf[3]), "+a"(qf[4]), "+a"(qf[5]), "+a"(qf[6]), "+a"(qf[7]));
-    if (n_mine >= 3) issue_half(2, 2, lookup(2));
     Pages pg_next = n_mine >= 4 ? lookup(3) : Pages{0, 0};  // of the half the loop's first iteration issues
 
     f32x16 oacc[kDB];
