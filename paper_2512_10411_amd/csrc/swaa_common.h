@@ -40,8 +40,8 @@ inline FastDiv make_fastdiv(unsigned d) {
     f.sh = l - 1;
     return f;
 }
-__device__ __forceinline__ unsigned fastdiv(unsigned n, const FastDiv f) {
-    return f.sh < 0 ? n : __umulhi(n, f.m) >> f.sh;
+__host__ __device__ __forceinline__ unsigned fastdiv(unsigned n, const FastDiv f) {
+    return f.sh < 0 ? n : (unsigned)(((unsigned long long)n * f.m) >> 32) >> f.sh;  // (the upper half of one 32 x 32 bit product)
 }
 
 struct FwdParams {
