@@ -420,7 +420,12 @@ void plan_decode(DecodeParams &p) {
     const long long groups = (long long)p.B * p.Hkv * p.n_coltiles;
     const long long target_items = 256LL * 3 * kRounds;
     long long per_group = target_items / groups;
-    if (per_group < 1) per_group = 1;
+    // More (pair, column tile) groups than resident workgroups: one item per group would leave a
+    // second round of a few long items streaming alone at the end (100 sequences x 8 KV heads
+    // took 1.5 x the time of 96).  Many short items instead, kTailRounds rounds' worth: the
+    // partly filled tail is then one short item long.
+    constexpr long long kTailRounds = 8;
+    if (per_group < 1) per_group = (kTailRounds * target_items + groups - 1) / groups;
     long long hps = (p.n_halves + per_group - 1) / per_group;
     if (hps < 4) hps = 4;
     p.halves_per_split = (int)hps;

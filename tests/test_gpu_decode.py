@@ -284,3 +284,30 @@ def test_binary16_caches(Nq, G):
             with input_format("fp16"):
                 ro, rl = swaa_decode_oracle(qs, ks, vs, W, S, 1 / math.sqrt(D))
             assert_parity(o1[b:b + 1], l1[b:b + 1], ro, rl, tag=f"fp16 decode Nq{Nq} G{G} seq {b} Nk{lens[b]} W{W}")
+
+
+def test_more_pairs_than_resident_workgroups():
+    # 100 sequences x 8 KV heads = 800 (batch, KV head) pairs against 768 resident workgroups: the
+    # plan cuts every pair into several short splits instead of one item per pair
+    B, Hq, Hkv, Nq, D, max_len = 100, 16, 8, 1, 128, 640
+    rng = np.random.Generator(np.random.Philox(7990))
+    lens = [int(x) for x in rng.integers(1, max_len + 1, size=B)]
+    lens[0], lens[1] = max_len, 1
+    host = [make_qkv(1, Hq, Hkv, n, D, 7991 + i, n_query=Nq) for i, n in enumerate(lens)]
+    kb = torch.zeros((B, Hkv, max_len, D), dtype=torch.bfloat16, device="cuda")
+    vb = torch.zeros_like(kb)
+    for b, (_, k, v) in enumerate(host):
+        kb[b, :, :lens[b]], vb[b, :, :lens[b]] = to_device(k)[0], to_device(v)[0]
+    q = torch.cat([to_device(s[0]) for s in host], dim=0)
+    seq_lens = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    for W, S in ((10**9, 0), (100, 4)):
+        out, lse = binding.swaa_attn_decode_ex(q, kb, vb, W, S, seq_lens=seq_lens)
+        torch.cuda.synchronize()
+        worst = [0.0, 0.0, 0.0]
+        for b, (qs, ks, vs) in enumerate(host):
+            ro, rl = swaa_decode_oracle(qs, ks, vs, W, S, 1 / math.sqrt(D))
+            from gpu_util import errors
+            e = errors(out[b:b + 1], lse[b:b + 1], ro, rl)
+            worst = [max(a, c) for a, c in zip(worst, e)]
+        print(f"[parity] 800 pairs W{W}: O max-abs {worst[0]:.3e} mean-abs(max) {worst[1]:.3e} LSE {worst[2]:.3e}", flush=True)
+        assert worst[0] <= 2e-2 and worst[1] <= 2e-3 and worst[2] <= 1e-3
