@@ -41,10 +41,14 @@ struct DecodeParams {
     int col_stride;  // min(cols, 32): columns an item stores
     int n_halves;  // upper bound on the halves a sequence of at most Nk tokens visits
     int halves_per_split, n_splits;
-    long long items;  // B * Hkv * n_coltiles * n_splits (below 2^31)
+    long long items;  // B * Hkv * n_coltiles * n_splits (below 2^31): partial results in the workspace
+    // a workgroup computes tiles_per_item (1 or 2) column tiles of one (pair, split) from the same
+    // K and V fragments; n_ctgroups = ceil(n_coltiles / tiles_per_item) of them per (pair, split)
+    int tiles_per_item, n_ctgroups;
+    long long wg_items;  // B * Hkv * n_ctgroups * n_splits: workgroups that have work
     int fp16;         // elements of q, k, v, out are IEEE binary16 instead of bfloat16
     // divisions every workgroup makes, as multiplications (FastDiv)
-    FastDiv div_coltiles, div_splits, div_hkv, div_page;
+    FastDiv div_ctgroups, div_splits, div_hkv, div_page;
 };
 
 // The halves a sequence of nk cached tokens visits: halves 0 .. n_sink-1, then key halves band0 ..

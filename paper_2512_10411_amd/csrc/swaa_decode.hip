@@ -32,6 +32,7 @@
 // The split kernel declares no static LDS: its dynamic LDS starts at address 0
 // and all its LDS accesses use plain byte addresses.
 #include <atomic>
+#include <type_traits>
 
 #include "swaa_decode.h"
 #include "swaa_tile_d128.h"
@@ -47,22 +48,34 @@ constexpr int kMergeThreads = 1024;
 constexpr int kRounds = 1;  // rounds of resident workgroups the split plan aims for
 
 // kPaged: k and v are a paged cache addressed through p.block_table (its own instantiation).
-template <bool kF16, bool kPaged>
+// kTiles: column tiles a workgroup computes from the same K and V fragments (1, or 2 when a pair
+// has more than 32 query rows: two tiles in two workgroups would read every key twice).
+template <bool kF16, bool kPaged, int kTiles>
 __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParams p) {
     // XCD x takes the x-th contiguous chunk of the item list (column tiles of one
     // split, which read the same keys, then run behind the same L2).  The list has fewer
     // than 2^31 items: 32-bit arithmetic, divisions as multiplications.
-    const unsigned items = (unsigned)p.items;
+    const unsigned items = (unsigned)p.wg_items;
     const unsigned chunk = (items + kXcds - 1) / kXcds;
     const unsigned slot = blockIdx.x / kXcds;
-    const unsigned item = (blockIdx.x % kXcds) * chunk + slot;
-    if (slot >= chunk || item >= items) return;
-    const unsigned item_ct = fastdiv(item, p.div_coltiles);       // item / n_coltiles
-    const int ct = (int)(item - item_ct * (unsigned)p.n_coltiles);
-    const unsigned upair = fastdiv(item_ct, p.div_splits);        // item / (n_coltiles * n_splits)
+    const unsigned witem = (blockIdx.x % kXcds) * chunk + slot;
+    if (slot >= chunk || witem >= items) return;
+    const unsigned item_ct = fastdiv(witem, p.div_ctgroups);      // witem / n_ctgroups
+    const int ctg = (int)(witem - item_ct * (unsigned)p.n_ctgroups);
+    const unsigned upair = fastdiv(item_ct, p.div_splits);        // witem / (n_ctgroups * n_splits)
     const int split = (int)(item_ct - upair * (unsigned)p.n_splits);
     const int pair = (int)upair;
     const int b = (int)fastdiv(upair, p.div_hkv), kvh = pair - b * p.Hkv;
+    // this workgroup's column tiles and the workspace slots of their partial results
+    int ct[kTiles];
+    bool tile_valid[kTiles];
+    size_t item[kTiles];
+#pragma unroll
+    for (int j = 0; j < kTiles; ++j) {
+        ct[j] = ctg * kTiles + j;
+        tile_valid[j] = ct[j] < p.n_coltiles;  // (uniform; an odd number of tiles leaves the last workgroup one)
+        item[j] = ((size_t)pair * p.n_splits + split) * p.n_coltiles + min(ct[j], p.n_coltiles - 1);
+    }
 
     const int lane = threadIdx.x;
     const int l32 = lane & 31;
@@ -72,22 +85,29 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
     const int W = p.W, S = p.S;
     const VisitedHalves vh = visited_halves(Nk, p.Nq, W, S);
 
-    // this lane's query column: row c of the pair's G x Nq block (clamped: padding
+    // this lane's query column in each tile: row c of the pair's G x Nq block (clamped: padding
     // columns repeat the last row and are never stored)
-    const int c = ct * 32 + l32;
-    const bool col_valid = c < p.cols;
-    const int cc = min(c, p.cols - 1);
-    const int qpos = Nk - p.Nq + (cc % p.Nq);  // its position in the sequence
+    bool col_valid[kTiles];
+    int cc[kTiles], qpos[kTiles];
+#pragma unroll
+    for (int j = 0; j < kTiles; ++j) {
+        const int c = ct[j] * 32 + l32;
+        col_valid[j] = tile_valid[j] && c < p.cols;
+        cc[j] = min(c, p.cols - 1);
+        qpos[j] = Nk - p.Nq + (cc[j] % p.Nq);  // its position in the sequence
+    }
     const int pos_min = Nk - p.Nq, pos_max = Nk - 1;
 
     const int h_begin = split * p.halves_per_split;
     const int n_mine = min(vh.n - h_begin, p.halves_per_split);
     if (n_mine <= 0) {
         // a shorter sequence has no keys for this split: an empty partial result (weight 0 in the merge)
-        if (col_valid && hf == 0) {
-            p.ws_ml[(size_t)item * 64 + l32] = -INFINITY;
-            p.ws_ml[(size_t)item * 64 + 32 + l32] = 0.f;
-        }
+#pragma unroll
+        for (int j = 0; j < kTiles; ++j)
+            if (col_valid[j] && hf == 0) {
+                p.ws_ml[item[j] * 64 + l32] = -INFINITY;
+                p.ws_ml[item[j] * 64 + 32 + l32] = 0.f;
+            }
         return;
     }
     auto first_key = [&](int t) {
@@ -224,33 +244,39 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
     // and that wait covers the copies issued behind them as well (it cannot see them): a short
     // item has all its keys in flight at once and starts when they are there; a long one gives
     // away the head start of its first two steps, once. ----
-    bf16x8 qf[kKS];
-    {
-        const char *qrow = reinterpret_cast<const char *>(p.q + ((size_t)b * p.Hq + (size_t)kvh * p.G) * p.Nq * kD) +
-                           (size_t)min(ct * 32 + l32, p.cols - 1) * kRowBytes + 16 * hf;
+    bf16x8 qf[kTiles][kKS];
 #pragma unroll
-        for (int ks = 0; ks < kKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qrow + 32 * ks);
+    for (int j = 0; j < kTiles; ++j) {
+        const char *qrow = reinterpret_cast<const char *>(p.q + ((size_t)b * p.Hq + (size_t)kvh * p.G) * p.Nq * kD) +
+                           (size_t)cc[j] * kRowBytes + 16 * hf;
+#pragma unroll
+        for (int ks = 0; ks < kKS; ++ks) qf[j][ks] = *reinterpret_cast<const bf16x8 *>(qrow + 32 * ks);
     }
     issue_half(0, 0, lookup(0));
     if (n_mine >= 2) issue_half(1, 1, lookup(1));
     if (n_mine >= 3) issue_half(2, 2, lookup(2));
     // (the idle cycles keep the loads two wait states away from the first MFMA that reads them)
-    asm volatile("s_nop 1"
-                 : "+a"(qf[0]), "+a"(qf[1]), "+a"(qf[2]), "+a"(qf[3]), "+a"(qf[4]), "+a"(qf[5]), "+a"(qf[6]), "+a"(qf[7]));
+#pragma unroll
+    for (int j = 0; j < kTiles; ++j)
+        asm volatile("s_nop 1"
+                     : "+a"(qf[j][0]), "+a"(qf[j][1]), "+a"(qf[j][2]), "+a"(qf[j][3]), "+a"(qf[j][4]), "+a"(qf[j][5]),
+                       "+a"(qf[j][6]), "+a"(qf[j][7]));
     Pages pg_next = n_mine >= 4 ? lookup(3) : Pages{0, 0};  // of the half the loop's first iteration issues
 
-    f32x16 oacc[kDB];
+    f32x16 oacc[kTiles][kDB];
+    RowState rs[kTiles];
 #pragma unroll
-    for (int db = 0; db < kDB; ++db)
+    for (int j = 0; j < kTiles; ++j) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) oacc[db][e] = 0.f;
-    pin_acc(oacc);
-
+        for (int db = 0; db < kDB; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[j][db][e] = 0.f;
+        pin_acc(oacc[j]);
+        rs[j].mc = -INFINITY;
+        rs[j].l = 0.f;
+        rs[j].lb = 0.f;
+    }
     const float c2 = p.scale_log2;
-    RowState rs;
-    rs.mc = -INFINITY;
-    rs.l = 0.f;
-    rs.lb = 0.f;
 
     int stage = 0;
     for (int t = 0; t < n_mine; ++t) {
@@ -283,52 +309,59 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
         if (t + kDStages < n_mine) issue_half(t + kDStages, stage, pg_next);
         if (t + kDStages + 1 < n_mine) pg_next = lookup(t + kDStages + 1);  // lands under this iteration's arithmetic
 
-        f32x16 s;
-        bf16x8 pf[2];
-        float alpha;
-        mfma_s_first<kF16>(s, kf[0], qf[0]);
 #pragma unroll
-        for (int ks = 1; ks < kKS - 1; ++ks) mfma_s<kF16>(s, kf[ks], qf[ks]);
-        mfma_s_settled<kF16>(s, kf[kKS - 1], qf[kKS - 1]);
-        if (masked)
-            softmax_half<true, kF16>(s, k0h, qpos, W, S, hf, c2, rs, pf, alpha);
-        else
-            softmax_half<false, kF16>(s, k0h, qpos, W, S, hf, c2, rs, pf, alpha);
-        rescale(oacc, alpha);
+        for (int j = 0; j < kTiles; ++j) {
+            if (j > 0 && !tile_valid[j]) continue;  // (uniform)
+            f32x16 s;
+            bf16x8 pf[2];
+            float alpha;
+            mfma_s_first<kF16>(s, kf[0], qf[j][0]);
 #pragma unroll
-        for (int st = 0; st < 2; ++st)
+            for (int ks = 1; ks < kKS - 1; ++ks) mfma_s<kF16>(s, kf[ks], qf[j][ks]);
+            mfma_s_settled<kF16>(s, kf[kKS - 1], qf[j][kKS - 1]);
+            if (masked)
+                softmax_half<true, kF16>(s, k0h, qpos[j], W, S, hf, c2, rs[j], pf, alpha);
+            else
+                softmax_half<false, kF16>(s, k0h, qpos[j], W, S, hf, c2, rs[j], pf, alpha);
+            rescale(oacc[j], alpha);
 #pragma unroll
-            for (int db = 0; db < kDB; ++db) {
-                if (st == 1 && db == kDB - 1)
-                    mfma_acc_settled<kF16>(oacc[db], vf[st][db], pf[st]);  // the accumulators are read below / next time round
-                else
-                    mfma_acc<kF16>(oacc[db], vf[st][db], pf[st]);
-            }
+            for (int st = 0; st < 2; ++st)
+#pragma unroll
+                for (int db = 0; db < kDB; ++db) {
+                    if (st == 1 && db == kDB - 1)
+                        mfma_acc_settled<kF16>(oacc[j][db], vf[st][db], pf[st]);  // the accumulators are read below / next time round
+                    else
+                        mfma_acc<kF16>(oacc[j][db], vf[st][db], pf[st]);
+                }
+        }
         stage = (stage + 1 == kDStages) ? 0 : stage + 1;
     }
 
     // ---- partial result of the valid columns: O^T accumulators (row d, column l32), reference, sum ----
     // The merge divides by the fp32 sums it combines; a partial O is the sum over the
     // rounded P, so it is stored scaled by l / (sum of the rounded P).
-    float l_row, lb_row;
-    row_sums(rs, l_row, lb_row);
-    const float fix = lb_row > 0.f ? l_row / lb_row : 0.f;  // a column that saw no key: O = 0, l = 0
-    if (col_valid) {
-        float *wo = p.ws_o + ((size_t)item * p.col_stride + l32) * kD;
 #pragma unroll
-        for (int db = 0; db < kDB; ++db)
+    for (int j = 0; j < kTiles; ++j) {
+        float l_row, lb_row;
+        row_sums(rs[j], l_row, lb_row);
+        const float fix = lb_row > 0.f ? l_row / lb_row : 0.f;  // a column that saw no key: O = 0, l = 0
+        if (col_valid[j]) {
+            float *wo = p.ws_o + (item[j] * p.col_stride + l32) * kD;
 #pragma unroll
-            for (int e4 = 0; e4 < 4; ++e4) {
-                float4 o4;
-                o4.x = oacc[db][4 * e4 + 0] * fix;
-                o4.y = oacc[db][4 * e4 + 1] * fix;
-                o4.z = oacc[db][4 * e4 + 2] * fix;
-                o4.w = oacc[db][4 * e4 + 3] * fix;
-                *reinterpret_cast<float4 *>(wo + 32 * db + 8 * e4 + 4 * hf) = o4;
+            for (int db = 0; db < kDB; ++db)
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    float4 o4;
+                    o4.x = oacc[j][db][4 * e4 + 0] * fix;
+                    o4.y = oacc[j][db][4 * e4 + 1] * fix;
+                    o4.z = oacc[j][db][4 * e4 + 2] * fix;
+                    o4.w = oacc[j][db][4 * e4 + 3] * fix;
+                    *reinterpret_cast<float4 *>(wo + 32 * db + 8 * e4 + 4 * hf) = o4;
+                }
+            if (hf == 0) {
+                p.ws_ml[item[j] * 64 + l32] = rs[j].mc;
+                p.ws_ml[item[j] * 64 + 32 + l32] = l_row;
             }
-        if (hf == 0) {
-            p.ws_ml[(size_t)item * 64 + l32] = rs.mc;
-            p.ws_ml[(size_t)item * 64 + 32 + l32] = l_row;
         }
     }
 }
@@ -417,7 +450,9 @@ void plan_decode(DecodeParams &p) {
     p.n_halves = all < bound ? all : bound;
     // kRounds rounds of three workgroups per CU (one round measured fastest: every split is
     // resident at once and streams for the whole launch), but no split shorter than four halves
-    const long long groups = (long long)p.B * p.Hkv * p.n_coltiles;
+    p.tiles_per_item = p.n_coltiles >= 2 ? 2 : 1;
+    p.n_ctgroups = (p.n_coltiles + p.tiles_per_item - 1) / p.tiles_per_item;
+    const long long groups = (long long)p.B * p.Hkv * p.n_ctgroups;
     const long long target_items = 256LL * 3 * kRounds;
     long long per_group = target_items / groups;
     // More (pair, column tile) groups than resident workgroups: one item per group would leave a
@@ -430,8 +465,9 @@ void plan_decode(DecodeParams &p) {
     if (hps < 4) hps = 4;
     p.halves_per_split = (int)hps;
     p.n_splits = (int)((p.n_halves + hps - 1) / hps);
-    p.items = groups * p.n_splits;
-    p.div_coltiles = make_fastdiv((unsigned)p.n_coltiles);
+    p.wg_items = groups * p.n_splits;
+    p.items = (long long)p.B * p.Hkv * p.n_coltiles * p.n_splits;
+    p.div_ctgroups = make_fastdiv((unsigned)p.n_ctgroups);
     p.div_splits = make_fastdiv((unsigned)p.n_splits);
     p.div_hkv = make_fastdiv((unsigned)p.Hkv);
 }
@@ -466,17 +502,27 @@ hipError_t decode_static_scratch(void **ptr) {
 }
 
 hipError_t launch_decode(const DecodeParams &p, hipStream_t stream) {
-    const long long chunk = (p.items + kXcds - 1) / kXcds;
+    const long long chunk = (p.wg_items + kXcds - 1) / kXcds;
     const dim3 grid((unsigned)(chunk * kXcds));
     const bool paged = p.block_table != nullptr;
+    auto launch = [&](auto f16, auto pg, auto tiles) {
+        hipLaunchKernelGGL((swaa_decode_split_kernel<decltype(f16)::value, decltype(pg)::value, decltype(tiles)::value>), grid,
+                           dim3(64), kDSmemBytes, stream, p);
+    };
+    auto pick_tiles = [&](auto f16, auto pg) {
+        if (p.tiles_per_item == 2)
+            launch(f16, pg, std::integral_constant<int, 2>{});
+        else
+            launch(f16, pg, std::integral_constant<int, 1>{});
+    };
     if (p.fp16 && paged)
-        hipLaunchKernelGGL((swaa_decode_split_kernel<true, true>), grid, dim3(64), kDSmemBytes, stream, p);
+        pick_tiles(std::true_type{}, std::true_type{});
     else if (p.fp16)
-        hipLaunchKernelGGL((swaa_decode_split_kernel<true, false>), grid, dim3(64), kDSmemBytes, stream, p);
+        pick_tiles(std::true_type{}, std::false_type{});
     else if (paged)
-        hipLaunchKernelGGL((swaa_decode_split_kernel<false, true>), grid, dim3(64), kDSmemBytes, stream, p);
+        pick_tiles(std::false_type{}, std::true_type{});
     else
-        hipLaunchKernelGGL((swaa_decode_split_kernel<false, false>), grid, dim3(64), kDSmemBytes, stream, p);
+        pick_tiles(std::false_type{}, std::false_type{});
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL(swaa_decode_merge_kernel, dim3((unsigned)((long long)p.B * p.Hq * p.Nq)), dim3(kMergeThreads), 0,
