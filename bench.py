@@ -208,6 +208,11 @@ def main():
         ws = torch.empty(binding.swaa_attn_decode_workspace_bytes(w.B, w.Hq, w.Hkv, w.n_query, w.N, w.D, w.window,
                                                                   w.n_sink), dtype=torch.uint8, device="cuda")
 
+    if w.packed_lens:
+        import numpy as np
+        cu = torch.from_numpy(np.concatenate([[0], np.cumsum(w.packed_lens)]).astype(np.int32)).cuda()
+        qd, kd, vd, out, lse = qd[0], kd[0], vd[0], out[0], lse[0]  # [H, T, D] / [H, T]
+
     if w.page_size:
         # the same keys and values as a paged cache (pages in a seeded random order)
         from paper_2512_10411_amd.inputs import paged_cache
@@ -226,6 +231,9 @@ def main():
         if w.backward:
             binding.swaa_attn_bwd(qd, kd, vd, out, lse, dd, w.window, w.n_sink, None, w.scale, workspace=bws,
                                   stream=stream)
+        elif w.packed_lens:
+            binding.swaa_attn_fwd_ex(qd, kd, vd, w.window, w.n_sink, None, w.scale, cu_seqlens_q=cu, cu_seqlens_k=cu,
+                                     max_seqlen_q=w.N, max_seqlen_k=w.N, out=out, lse=lse, stream=stream)
         elif decode and w.page_size:
             binding.swaa_attn_decode_ex(qd, kd, vd, w.window, w.n_sink, w.scale, block_table=table, max_seqlen_k=w.N,
                                         out=out, lse=lse, workspace=ws, stream=stream)
@@ -277,7 +285,9 @@ def main():
     kern_avg_ms = ev0.elapsed_time(ev1) / args.steps
     ms_per_step = wall * 1e3 / args.steps
 
-    if decode or w.chunk:
+    if w.packed_lens:
+        pairs = sum(binding.swaa_visible_pairs(n, w.window, w.n_sink) for n in w.packed_lens) * w.Hq
+    elif decode or w.chunk:
         pairs, algo_bytes = decode_counts(w)
     else:
         pairs = binding.swaa_visible_pairs_fa_decode(w.N, w.window, w.n_sink, n_prompt) * w.B * w.Hq
@@ -294,7 +304,7 @@ def main():
     # The same tensors with window = N (the full-attention layer next to this SWA layer):
     # the time ratio should follow the visible-pair ratio if the work is linear in N * W.
     linear_in_w = None
-    plain_prefill = not (decode or w.chunk or w.backward or w.fmt == "fp16") and w.n_prompt is None
+    plain_prefill = not (decode or w.chunk or w.backward or w.fmt == "fp16" or w.packed_lens) and w.n_prompt is None
     if plain_prefill and w.window < w.N and not args.no_linear_in_w:
         def full_step():
             binding.swaa_attn_fwd(qd, kd, vd, w.N, w.n_sink, w.scale, out=out, lse=lse, stream=stream)
@@ -358,12 +368,15 @@ def main():
                    "D": w.D,
                    "window": w.window, "n_sink": w.n_sink, "n_prompt": n_prompt, "seed": w.seed, "k_mult": w.k_mult,
                    "visible_pairs": pairs, "flops_per_step": flops,
-                   "pct_bf16_mfma_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS},
+                   "pct_bf16_mfma_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS,
+                   **({"packed_lens": list(w.packed_lens)} if w.packed_lens else {})},
         "roofline": roofline,
     }
     if linear_in_w is not None:
         res["linear_in_w"] = linear_in_w
-    if not args.no_cpu_baseline:
+    if w.packed_lens:
+        res["cpu_baseline"] = None  # (the oracle is timed on the fixed-length workloads)
+    elif not args.no_cpu_baseline:
         from oracle import input_format
         with input_format(w.fmt):
             res["cpu_baseline"] = (cpu_baseline_backward(w, q, k, v, dout) if w.backward

@@ -165,6 +165,12 @@ typedef struct swaa_fwd_args {
     /* paged key/value cache (block_table NULL: k, v are tensors as described above) */
     const int *block_table; /* device, B rows of block_table_stride ints, or NULL */
     int block_table_stride, page_size, num_pages;
+    /* Packed batches: the number of rows of the packed q tensor (at least cu_seqlens_q[B]; the
+     * host cannot read that), or 0 if not known.  With it the launch holds one workgroup per row
+     * tile a sequence really has instead of B times the longest sequence's: batches of very
+     * different lengths run many times faster.  Rows beyond a total stated too small are not
+     * computed.  Ignored for fixed-length batches. */
+    long long total_rows_q;
 } swaa_fwd_args;
 
 int swaa_attn_fwd_ex(const swaa_fwd_args *args);

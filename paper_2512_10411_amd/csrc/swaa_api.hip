@@ -130,7 +130,10 @@ int swaa_attn_fwd_ex(const swaa_fwd_args *a) {
     // the pipelined kernel (head dimension 128, either 16-bit format) runs workgroups of 128
     // rows, two per compute unit; other head dimensions run on the plain kernel
     const bool pipelined = D == 128;
-    if (!swaa::plan_work(p, Nq, pipelined ? 128 : swaa::fwd_simple_wg_rows(D))) return SWAA_ERR_SHAPE;
+    const int wg_rows = pipelined ? 128 : swaa::fwd_simple_wg_rows(D);
+    if (a->total_rows_q < 0) return SWAA_ERR_SHAPE;
+    if (packed && a->total_rows_q > 0 ? !swaa::plan_work_packed(p, Nq, wg_rows, a->total_rows_q) : !swaa::plan_work(p, Nq, wg_rows))
+        return SWAA_ERR_SHAPE;
 
     hipStream_t s = static_cast<hipStream_t>(a->stream);
     const hipError_t err = pipelined ? swaa::launch_fwd_pipelined_d128(p, s) : swaa::launch_fwd_simple(p, D, s);
@@ -143,7 +146,7 @@ int swaa_attn_fwd_fa_decode(const void *q, const void *k, const void *v, void *o
     if (!q || !k || !v || !out || !lse) return SWAA_ERR_NULL;
     if (B < 1 || Hq < 1 || Hkv < 1 || N < 1 || D < 1) return SWAA_ERR_SHAPE;
     // contiguous [B, H, N, D] tensors, every sequence N rows on N keys
-    swaa_fwd_args a;
+    swaa_fwd_args a{};
     const long long nd = (long long)N * D;
     a.q = {const_cast<void *>(q), Hq * nd, nd, D};
     a.k = {const_cast<void *>(k), Hkv * nd, nd, D};

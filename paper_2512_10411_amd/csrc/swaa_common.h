@@ -83,6 +83,11 @@ struct FwdParams {
     int tiles_per_pair;
     long long total_items;
     long long chunk;  // work items per XCD
+    // Packed batches whose total number of query rows the caller has stated: the work list holds
+    // every sequence's own row tiles, one sequence after the other (no items for rows a shorter
+    // sequence does not have); total_items and chunk are then upper bounds, the workgroups work
+    // out the true ones from cu_q / cu_k (decode_work_packed).
+    int packed_compact;
 };
 
 // One sequence as a workgroup sees it: the query rows are the newest nq of its nk
@@ -132,7 +137,89 @@ struct WorkItem {
 // Workgroups reach the 8 XCDs round-robin; XCD x takes the x-th contiguous
 // chunk of the work list, so the position tiles of one KV head, whose K/V
 // bands overlap, run behind the same L2.  Inside a pair, long rows go first.
+// The work list of a packed batch, sequence by sequence: sequence b of nq_b query rows (the
+// smaller of its rows, the plan's Nq and its keys -- what seq_geom makes of it) has Hkv pairs of
+// n4 ceil(nq_b / r4) + has2 ceil(nq_b / r2) + has1 ceil(nq_b / r1) row tiles, r4 = wg_rows / 4
+// and so on.  Every wave reads the sequence lengths (64 per round, one per lane), adds them up,
+// cuts the true total into eight chunks as decode_work does, and finds the sequence that holds
+// its item by a prefix sum over the lanes.
+__device__ __forceinline__ bool decode_work_packed(const FwdParams &p, WorkItem &w) {
+    const int lane = threadIdx.x & 63;
+    const unsigned bid = blockIdx.x;
+    const unsigned xcd = bid % kXcds, slot = bid / kXcds;
+    const int s1 = p.wg_rows == 128 ? 7 : 8;  // log2 of the rows of a one-head tile (two heads: half, four: a quarter)
+    auto rows_of = [&](int b) {  // nq_b of sequence b (0 for b >= B)
+        if (b >= p.B) return 0;
+        const int nq = p.cu_q[b + 1] - p.cu_q[b];
+        const int nk = p.cu_k[b + 1] - p.cu_k[b];
+        return max(0, min(min(nq, p.Nq), min(nk, p.Nk)));
+    };
+    auto tiles_of = [&](int nq) {  // row tiles of one pair
+        return (unsigned)(p.n4 * ((nq + (1 << (s1 - 2)) - 1) >> (s1 - 2)) + p.has2 * ((nq + (1 << (s1 - 1)) - 1) >> (s1 - 1)) +
+                          p.has1 * ((nq + (1 << s1) - 1) >> s1));
+    };
+    auto scan = [&](unsigned x) {  // inclusive prefix sum over the 64 lanes
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const unsigned y = (unsigned)__shfl_up((int)x, d);
+            x += lane >= d ? y : 0u;
+        }
+        return x;
+    };
+    unsigned total = 0;
+    for (int c0 = 0; c0 < p.B; c0 += 64) total += (unsigned)__shfl((int)scan(tiles_of(rows_of(c0 + lane)) * (unsigned)p.Hkv), 63);
+    total = (unsigned)__builtin_amdgcn_readfirstlane((int)total);
+    const unsigned chunk = (total + kXcds - 1) / kXcds;
+    const unsigned item = xcd * chunk + slot;
+    if (slot >= chunk || item >= total) return false;
+    unsigned before = 0;
+    for (int c0 = 0; c0 < p.B; c0 += 64) {
+        const int nq = rows_of(c0 + lane);
+        const unsigned incl = scan(tiles_of(nq) * (unsigned)p.Hkv);
+        const unsigned in_round = (unsigned)__builtin_amdgcn_readfirstlane(__shfl((int)incl, 63));  // (uniform: a scalar branch below)
+        if (item - before < in_round) {
+            const unsigned rel = item - before;
+            const int n = __popcll(__ballot(incl <= rel));  // sequences of this round that end at or before the item
+            const unsigned base = n ? (unsigned)__shfl((int)incl, n - 1) : 0u;
+            const int nq_b = __shfl(nq, n);
+            // (everything below is the same in all lanes; read through the first lane so that the
+            // compiler knows it and keeps addresses built from it in scalar registers)
+            const int nq_u = __builtin_amdgcn_readfirstlane(nq_b);
+            unsigned r = (unsigned)__builtin_amdgcn_readfirstlane((int)(rel - base));  // inside sequence c0 + n
+            const unsigned tpp_u = tiles_of(nq_u);
+            w.b = __builtin_amdgcn_readfirstlane(c0 + n);
+            w.kvh = (int)(r / tpp_u);
+            r -= (unsigned)w.kvh * tpp_u;
+            const unsigned nt4 = (unsigned)((nq_u + (1 << (s1 - 2)) - 1) >> (s1 - 2));
+            const unsigned nt2 = (unsigned)((nq_u + (1 << (s1 - 1)) - 1) >> (s1 - 1));
+            const unsigned nt1 = (unsigned)((nq_u + (1 << s1) - 1) >> s1);
+            if (r < (unsigned)p.n4 * nt4) {
+                const unsigned g = r / nt4;
+                w.hpb = 4;
+                w.h0 = 4 * (int)g;
+                w.pt = (int)(nt4 - 1 - (r - g * nt4));
+                return true;
+            }
+            r -= (unsigned)p.n4 * nt4;
+            if (p.has2 && r < nt2) {
+                w.hpb = 2;
+                w.h0 = 4 * p.n4;
+                w.pt = (int)(nt2 - 1 - r);
+                return true;
+            }
+            if (p.has2) r -= nt2;
+            w.hpb = 1;
+            w.h0 = p.G - 1;
+            w.pt = (int)(nt1 - 1 - r);
+            return true;
+        }
+        before += in_round;
+    }
+    return false;
+}
+
 __device__ __forceinline__ bool decode_work(const FwdParams &p, WorkItem &w) {
+    if (p.packed_compact) return decode_work_packed(p, w);
     // (the entry points refuse work lists of 2^31 items or more: 32-bit arithmetic, whose
     // divisions cost a fraction of the 64-bit ones -- every wave of every workgroup pays them)
     const unsigned bid = blockIdx.x;
@@ -177,11 +264,28 @@ inline bool plan_work(FwdParams &p, int rows, int wg_rows) {
     p.nt_h2 = (rows + wg_rows / 2 - 1) / (wg_rows / 2);
     p.nt_h1 = (rows + wg_rows - 1) / wg_rows;
     p.tiles_per_pair = p.n4 * p.nt_h4 + p.has2 * p.nt_h2 + p.has1 * p.nt_h1;
+    p.packed_compact = 0;
     p.total_items = (long long)p.B * p.Hkv * p.tiles_per_pair;
     p.div_tiles_per_pair = make_fastdiv((unsigned)p.tiles_per_pair);
     p.div_hkv = make_fastdiv((unsigned)p.Hkv);
     p.div_nt_h4 = make_fastdiv((unsigned)p.nt_h4);
     p.chunk = (p.total_items + kXcds - 1) / kXcds;
+    return p.chunk * kXcds <= 0x7fffffffLL;
+}
+
+// The plan of a packed batch of B sequences with total_rows query rows in all (each at most
+// `rows` long): the compact work list of decode_work_packed, bounded from above -- a sequence
+// adds at most one partly filled tile per head group to total_rows / tile rows.
+inline bool plan_work_packed(FwdParams &p, int rows, int wg_rows, long long total_rows) {
+    if (!plan_work(p, rows, wg_rows)) return false;
+    if (wg_rows != 128 && wg_rows != 256) return true;  // (decode_work_packed knows these two; else the plain list)
+    auto bound = [&](int tile_rows) { return (total_rows + tile_rows - 1) / tile_rows + p.B; };
+    const long long tiles = p.n4 * bound(wg_rows / 4) + p.has2 * bound(wg_rows / 2) + p.has1 * bound(wg_rows);
+    const long long items = (long long)p.Hkv * tiles;
+    if (items >= p.total_items) return true;  // nothing gained (sequences of nearly equal length)
+    p.packed_compact = 1;
+    p.total_items = items;
+    p.chunk = (items + kXcds - 1) / kXcds;
     return p.chunk * kXcds <= 0x7fffffffLL;
 }
 

@@ -54,6 +54,7 @@ class Workload:
     fmt: str = "bf16"            # element format of q, k, v, out: "bf16" or "fp16"
     recipe: str = "iid"          # "iid", or a structured score pattern laid over the draws (apply_recipe)
     page_size: int = 0           # > 0: k and v are handed over as a paged cache of such pages in a seeded random order
+    packed_lens: tuple = ()      # a packed batch: sequences of these lengths back to back in one [H, sum, D] tensor (B = their number, N = the longest)
 
     @property
     def scale(self) -> float:
@@ -94,6 +95,14 @@ WORKLOADS = {
     "mid_paged": Workload("mid_paged", 1, 32, 8, 16384, 128, 2048, 4, _SEED0 + 2, chunk=True, n_query=16384, page_size=16),
     "long128k_swa_paged": Workload("long128k_swa_paged", 1, 32, 8, 131072, 128, 8192, 4, _SEED0 + 5, chunk=True,
                                    n_query=131072, page_size=16),
+    # prefill of a serving batch: prompts of different lengths packed into one tensor (cu_seqlens)
+    "packed8_mixed": Workload("packed8_mixed", 8, 32, 8, 15909, 128, 1024, 4, _SEED0 + 9,
+                              packed_lens=(12277, 10653, 12581, 8731, 11479, 11232, 9705, 15909)),
+    "packed61_skewed": Workload("packed61_skewed", 61, 32, 8, 16000, 128, 1024, 4, _SEED0 + 10,
+                                packed_lens=(16000, 113, 179, 227, 99, 52, 242, 367, 282, 348, 142, 344, 215, 91, 286, 372,
+                                             198, 218, 55, 109, 166, 267, 334, 61, 274, 97, 109, 141, 195, 313, 162, 219,
+                                             320, 210, 212, 335, 247, 387, 240, 399, 204, 301, 130, 179, 72, 79, 298, 97,
+                                             126, 252, 317, 392, 233, 234, 195, 276, 97, 224, 369, 361, 231)),
     "mid_fp16": Workload("mid_fp16", 1, 32, 8, 16384, 128, 2048, 4, _SEED0 + 2, fmt="fp16"),
     # backward pass of the mid-size layer (fine-tuning under the window + sink mask)
     "mid_bwd": Workload("mid_bwd", 1, 32, 8, 16384, 128, 2048, 4, _SEED0 + 2, backward=True),
@@ -179,6 +188,8 @@ def make_qkv(B, Hq, Hkv, N, D, seed, k_mult=1.0, chunk_rows=1 << 22, n_query=Non
 
 def make_workload(w: Workload):
     """q, k, v (uint16 bf16 bits) for a named workload."""
+    if w.packed_lens:  # one [1, H, sum of the lengths, D] tensor each; the sequence boundaries are the caller's offsets
+        return make_qkv(1, w.Hq, w.Hkv, sum(w.packed_lens), w.D, w.seed, w.k_mult, fmt=w.fmt)
     q, k, v = make_qkv(w.B, w.Hq, w.Hkv, w.N, w.D, w.seed, w.k_mult, n_query=w.n_query, fmt=w.fmt)
     apply_recipe(w, q, k)
     return q, k, v

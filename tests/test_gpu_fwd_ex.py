@@ -197,3 +197,34 @@ def test_paged_prefill_equals_the_contiguous_call_bit_for_bit(page_size):
         o2, l2 = binding.swaa_attn_fwd_ex(q, kc, vc, W, S, P, block_table=table, max_seqlen_k=N)
         torch.cuda.synchronize()
         assert torch.equal(o1, o2) and torch.equal(l1, l2), (page_size, W, S, P)
+
+
+@pytest.mark.parametrize("D", [128, 64])
+def test_packed_batch_of_many_sequences_of_very_different_lengths(D):
+    # 150 sequences (three rounds of 64 in the work-list search), lengths from 1 to 3000 rows, some
+    # of them chunks of longer caches; the compact work list against the launch of B x longest
+    # sequence (same bits) and against the oracle
+    Hq, Hkv, W, S, B = 10, 2, 200, 4, 150
+    rng = np.random.Generator(np.random.Philox(8890 + D))
+    lens_k = [int(x) for x in rng.integers(1, 120, size=B)]
+    for i in (3, 70, 149):
+        lens_k[i] = int(rng.integers(1500, 3000))
+    lens_q = [n if rng.integers(0, 3) else max(1, n // 2) for n in lens_k]
+    cu_q = np.concatenate([[0], np.cumsum(lens_q)]).astype(np.int32)
+    cu_k = np.concatenate([[0], np.cumsum(lens_k)]).astype(np.int32)
+    seqs = [make_qkv(1, Hq, Hkv, nk, D, int(rng.integers(1 << 30)), n_query=None if nq == nk else nq)
+            for nq, nk in zip(lens_q, lens_k)]
+    q_pack = torch.cat([to_device(s[0])[0].permute(1, 0, 2) for s in seqs], dim=0).contiguous()
+    k_pack = torch.cat([to_device(s[1])[0].permute(1, 0, 2) for s in seqs], dim=0).contiguous()
+    v_pack = torch.cat([to_device(s[2])[0].permute(1, 0, 2) for s in seqs], dim=0).contiguous()
+    args = dict(cu_seqlens_q=torch.from_numpy(cu_q).cuda(), cu_seqlens_k=torch.from_numpy(cu_k).cuda(),
+                max_seqlen_q=max(lens_q), max_seqlen_k=max(lens_k))
+    out, lse = binding.swaa_attn_fwd_ex(q_pack.permute(1, 0, 2), k_pack.permute(1, 0, 2), v_pack.permute(1, 0, 2), W, S, None, **args)
+    o0, l0 = binding.swaa_attn_fwd_ex(q_pack.permute(1, 0, 2), k_pack.permute(1, 0, 2), v_pack.permute(1, 0, 2), W, S, None,
+                                      total_rows_q=0, **args)
+    torch.cuda.synchronize()
+    assert torch.equal(out, o0) and torch.equal(lse, l0)
+    for b, (qs, ks, vs) in enumerate(seqs):
+        ro, rl = swaa_decode_oracle(qs, ks, vs, W, S, 1 / math.sqrt(D))
+        assert_parity(out[:, cu_q[b]:cu_q[b + 1]].unsqueeze(0), lse[:, cu_q[b]:cu_q[b + 1]].unsqueeze(0), ro, rl,
+                      tag=f"packed, 150 sequences, seq {b}: Nq{lens_q[b]} Nk{lens_k[b]} D{D}")
