@@ -178,7 +178,7 @@ int swaa_attn_fwd(const void *q, const void *k, const void *v, void *out, float 
 namespace {
 
 // Shape checks shared by the two decode entry points; fills the shape fields and the plan.
-int decode_plan(swaa::DecodeParams &p, int B, int Hq, int Hkv, int Nq, int Nk, int D, int window, int n_sink) {
+int decode_plan(swaa::DecodeParams &p, int B, int Hq, int Hkv, int Nq, int Nk, int D, int window, int n_sink, bool ragged) {
     if (B < 1 || Hq < 1 || Hkv < 1 || Nq < 1 || Nk < 1 || D < 1) return SWAA_ERR_SHAPE;
     if (Hq % Hkv != 0 || Nq > Nk) return SWAA_ERR_SHAPE;
     if (window < 1 || n_sink < 0) return SWAA_ERR_SHAPE;
@@ -188,8 +188,8 @@ int decode_plan(swaa::DecodeParams &p, int B, int Hq, int Hkv, int Nq, int Nk, i
     p.W = window < Nk ? window : Nk;
     p.S = n_sink < Nk ? n_sink : Nk;
     if ((long long)p.G * Nq > 0x7fffffffLL / 256) return SWAA_ERR_SHAPE;
-    swaa::plan_decode(p);
-    if ((p.items + kXcds - 1) / kXcds * kXcds > 0x7fffffffLL || (long long)B * Hq * Nq > 0x7fffffffLL)
+    swaa::plan_decode(p, ragged);
+    if (p.items + 64 > 0x7fffffffLL || (long long)B * Hq * Nq > 0x7fffffffLL)
         return SWAA_ERR_SHAPE;
     return SWAA_OK;
 }
@@ -197,10 +197,16 @@ int decode_plan(swaa::DecodeParams &p, int B, int Hq, int Hkv, int Nq, int Nk, i
 }  // namespace
 
 long long swaa_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Nq, int Nk, int D, int window, int n_sink) {
-    swaa::DecodeParams p{};
-    const int rc = decode_plan(p, B, Hq, Hkv, Nq, Nk, D, window, n_sink);
-    if (rc != SWAA_OK) return rc;
-    return swaa::decode_workspace_floats(p) * (long long)sizeof(float);
+    // (the larger of the two plans: the call may or may not come with per-sequence lengths)
+    long long need = 0;
+    for (const bool ragged : {false, true}) {
+        swaa::DecodeParams p{};
+        const int rc = decode_plan(p, B, Hq, Hkv, Nq, Nk, D, window, n_sink, ragged);
+        if (rc != SWAA_OK) return rc;
+        const long long n = swaa::decode_workspace_floats(p) * (long long)sizeof(float);
+        need = n > need ? n : need;
+    }
+    return need;
 }
 
 namespace {
@@ -211,7 +217,7 @@ int decode_call(const swaa_decode_args *a, bool own_scratch) {
     if (!a) return SWAA_ERR_NULL;
     if (!a->q || !a->k.ptr || !a->v.ptr || !a->out || !a->lse) return SWAA_ERR_NULL;
     swaa::DecodeParams p{};
-    const int rc = decode_plan(p, a->B, a->Hq, a->Hkv, a->Nq, a->Nk, a->D, a->window, a->n_sink);
+    const int rc = decode_plan(p, a->B, a->Hq, a->Hkv, a->Nq, a->Nk, a->D, a->window, a->n_sink, a->seq_lens != nullptr && a->B > 1);
     if (rc != SWAA_OK) return rc;
     if (!positive_finite(a->scale)) return SWAA_ERR_SHAPE;
     if (a->dtype != SWAA_BF16 && a->dtype != SWAA_F16) return SWAA_ERR_UNSUPPORTED;

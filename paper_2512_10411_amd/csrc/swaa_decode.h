@@ -47,8 +47,9 @@ struct DecodeParams {
     int tiles_per_item, n_ctgroups;
     long long wg_items;  // B * Hkv * n_ctgroups * n_splits: workgroups that have work
     int fp16;         // elements of q, k, v, out are IEEE binary16 instead of bfloat16
+    int ragged;       // the plan was made for sequences of different lengths (plan_decode)
     // divisions every workgroup makes, as multiplications (FastDiv)
-    FastDiv div_ctgroups, div_splits, div_hkv, div_page;
+    FastDiv div_ctgroups, div_splits, div_hkv, div_page, div_per_round;
 };
 
 // The halves a sequence of nk cached tokens visits: halves 0 .. n_sink-1, then key halves band0 ..
@@ -66,8 +67,10 @@ __host__ __device__ inline VisitedHalves visited_halves(int nk, int nq, int W, i
     return h;
 }
 
-// Fills the plan fields (everything from `cols` on) from the shape fields.
-void plan_decode(DecodeParams &p);
+// Fills the plan fields (everything from `cols` on) from the shape fields.  ragged: the sequences
+// may hold far fewer than Nk tokens each (seq_lens is given): shorter splits, so that a batch with
+// one long sequence among short ones still has enough items with work.
+void plan_decode(DecodeParams &p, bool ragged);
 // Floats the workspace must hold for this plan.
 long long decode_workspace_floats(const DecodeParams &p);
 

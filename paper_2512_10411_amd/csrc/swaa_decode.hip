@@ -55,11 +55,24 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
     // XCD x takes the x-th contiguous chunk of the item list (column tiles of one
     // split, which read the same keys, then run behind the same L2).  The list has fewer
     // than 2^31 items: 32-bit arithmetic, divisions as multiplications.
+    // Workgroups reach the eight dies round-robin.  Sequences of one length: die x takes the x-th
+    // contiguous chunk of the item list (a die streams neighbouring memory: 3 % faster on one
+    // long sequence).  Per-sequence lengths: consecutive (pair, split) items go to consecutive
+    // dies, so that whatever the lengths every die gets its share of the long sequences.  Either
+    // way the column-tile groups of one (pair, split), which read the same keys, share a die.
     const unsigned items = (unsigned)p.wg_items;
-    const unsigned chunk = (items + kXcds - 1) / kXcds;
-    const unsigned slot = blockIdx.x / kXcds;
-    const unsigned witem = (blockIdx.x % kXcds) * chunk + slot;
-    if (slot >= chunk || witem >= items) return;
+    unsigned witem;
+    if (p.ragged) {
+        const unsigned per_round = kXcds * (unsigned)p.n_ctgroups;
+        const unsigned round = fastdiv(blockIdx.x, p.div_per_round), rem = blockIdx.x - round * per_round;
+        witem = round * per_round + (rem % kXcds) * (unsigned)p.n_ctgroups + rem / kXcds;
+    } else {
+        const unsigned chunk = (items + kXcds - 1) / kXcds;
+        const unsigned slot = blockIdx.x / kXcds;
+        witem = (blockIdx.x % kXcds) * chunk + slot;
+        if (slot >= chunk) return;
+    }
+    if (witem >= items) return;
     const unsigned item_ct = fastdiv(witem, p.div_ctgroups);      // witem / n_ctgroups
     const int ctg = (int)(witem - item_ct * (unsigned)p.n_ctgroups);
     const unsigned upair = fastdiv(item_ct, p.div_splits);        // witem / (n_ctgroups * n_splits)
@@ -439,7 +452,8 @@ __global__ __launch_bounds__(kMergeThreads) void swaa_decode_merge_kernel(const 
 
 }  // namespace
 
-void plan_decode(DecodeParams &p) {
+void plan_decode(DecodeParams &p, bool ragged) {
+    p.ragged = ragged ? 1 : 0;
     p.cols = p.G * p.Nq;
     p.n_coltiles = (p.cols + 31) / 32;
     p.col_stride = p.cols < 32 ? p.cols : 32;
@@ -453,7 +467,12 @@ void plan_decode(DecodeParams &p) {
     p.tiles_per_item = p.n_coltiles >= 2 ? 2 : 1;
     p.n_ctgroups = (p.n_coltiles + p.tiles_per_item - 1) / p.tiles_per_item;
     const long long groups = (long long)p.B * p.Hkv * p.n_ctgroups;
-    const long long target_items = 256LL * 3 * kRounds;
+    // With per-sequence lengths the plan, made for the longest sequence, aims for kRaggedRounds
+    // rounds: one sequence of Nk tokens among short ones then still fills the chip by itself when
+    // the batch has up to kRaggedRounds sequences' worth of pairs (the short ones' surplus items
+    // find no keys and end at once).
+    constexpr long long kRaggedRounds = 8;
+    const long long target_items = 256LL * 3 * (ragged ? kRaggedRounds : kRounds);
     long long per_group = target_items / groups;
     // More (pair, column tile) groups than resident workgroups: one item per group would leave a
     // second round of a few long items streaming alone at the end (100 sequences x 8 KV heads
@@ -468,6 +487,7 @@ void plan_decode(DecodeParams &p) {
     p.wg_items = groups * p.n_splits;
     p.items = (long long)p.B * p.Hkv * p.n_coltiles * p.n_splits;
     p.div_ctgroups = make_fastdiv((unsigned)p.n_ctgroups);
+    p.div_per_round = make_fastdiv((unsigned)(kXcds * p.n_ctgroups));
     p.div_splits = make_fastdiv((unsigned)p.n_splits);
     p.div_hkv = make_fastdiv((unsigned)p.Hkv);
 }
@@ -502,8 +522,11 @@ hipError_t decode_static_scratch(void **ptr) {
 }
 
 hipError_t launch_decode(const DecodeParams &p, hipStream_t stream) {
+    // (a whole number of rounds of 8 x column-tile groups covers both item orders)
+    const long long per_round = (long long)kXcds * p.n_ctgroups;
     const long long chunk = (p.wg_items + kXcds - 1) / kXcds;
-    const dim3 grid((unsigned)(chunk * kXcds));
+    const long long wgs = p.ragged ? (p.wg_items + per_round - 1) / per_round * per_round : chunk * kXcds;
+    const dim3 grid((unsigned)wgs);
     const bool paged = p.block_table != nullptr;
     auto launch = [&](auto f16, auto pg, auto tiles) {
         hipLaunchKernelGGL((swaa_decode_split_kernel<decltype(f16)::value, decltype(pg)::value, decltype(tiles)::value>), grid,
