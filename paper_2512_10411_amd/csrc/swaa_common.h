@@ -134,15 +134,14 @@ struct WorkItem {
     int pt;      // row tile of 256/hpb rows
 };
 
-// Workgroups reach the 8 XCDs round-robin; XCD x takes the x-th contiguous
-// chunk of the work list, so the position tiles of one KV head, whose K/V
-// bands overlap, run behind the same L2.  Inside a pair, long rows go first.
 // The work list of a packed batch, sequence by sequence: sequence b of nq_b query rows (the
 // smaller of its rows, the plan's Nq and its keys -- what seq_geom makes of it) has Hkv pairs of
 // n4 ceil(nq_b / r4) + has2 ceil(nq_b / r2) + has1 ceil(nq_b / r1) row tiles, r4 = wg_rows / 4
-// and so on.  Every wave reads the sequence lengths (64 per round, one per lane), adds them up,
-// cuts the true total into eight chunks as decode_work does, and finds the sequence that holds
-// its item by a prefix sum over the lanes.
+// and so on.  EVERY sequence's items are cut into eight contiguous chunks, one per XCD (XCD x
+// works through chunk x of sequence 0, then chunk x of sequence 1, ...): the sequences' caches
+// differ in length, so a chunk of the whole list would leave the long ones to one or two dies.
+// Every wave reads the sequence lengths (64 per round, one per lane) and finds the sequence
+// that holds its slot by a prefix sum of the chunk lengths over the lanes.
 __device__ __forceinline__ bool decode_work_packed(const FwdParams &p, WorkItem &w) {
     const int lane = threadIdx.x & 63;
     const unsigned bid = blockIdx.x;
@@ -166,27 +165,23 @@ __device__ __forceinline__ bool decode_work_packed(const FwdParams &p, WorkItem 
         }
         return x;
     };
-    unsigned total = 0;
-    for (int c0 = 0; c0 < p.B; c0 += 64) total += (unsigned)__shfl((int)scan(tiles_of(rows_of(c0 + lane)) * (unsigned)p.Hkv), 63);
-    total = (unsigned)__builtin_amdgcn_readfirstlane((int)total);
-    const unsigned chunk = (total + kXcds - 1) / kXcds;
-    const unsigned item = xcd * chunk + slot;
-    if (slot >= chunk || item >= total) return false;
     unsigned before = 0;
     for (int c0 = 0; c0 < p.B; c0 += 64) {
         const int nq = rows_of(c0 + lane);
-        const unsigned incl = scan(tiles_of(nq) * (unsigned)p.Hkv);
+        const unsigned incl = scan((tiles_of(nq) * (unsigned)p.Hkv + kXcds - 1) / kXcds);  // slots of this XCD up to and with the lane's sequence
         const unsigned in_round = (unsigned)__builtin_amdgcn_readfirstlane(__shfl((int)incl, 63));  // (uniform: a scalar branch below)
-        if (item - before < in_round) {
-            const unsigned rel = item - before;
-            const int n = __popcll(__ballot(incl <= rel));  // sequences of this round that end at or before the item
+        if (slot - before < in_round) {
+            const unsigned rel = slot - before;
+            const int n = __popcll(__ballot(incl <= rel));  // sequences of this round that end at or before the slot
             const unsigned base = n ? (unsigned)__shfl((int)incl, n - 1) : 0u;
             const int nq_b = __shfl(nq, n);
             // (everything below is the same in all lanes; read through the first lane so that the
             // compiler knows it and keeps addresses built from it in scalar registers)
             const int nq_u = __builtin_amdgcn_readfirstlane(nq_b);
-            unsigned r = (unsigned)__builtin_amdgcn_readfirstlane((int)(rel - base));  // inside sequence c0 + n
             const unsigned tpp_u = tiles_of(nq_u);
+            const unsigned items_u = tpp_u * (unsigned)p.Hkv;
+            unsigned r = xcd * ((items_u + kXcds - 1) / kXcds) + (unsigned)__builtin_amdgcn_readfirstlane((int)(rel - base));  // inside sequence c0 + n
+            if (r >= items_u) return false;  // (the sequence's last chunks are shorter)
             w.b = __builtin_amdgcn_readfirstlane(c0 + n);
             w.kvh = (int)(r / tpp_u);
             r -= (unsigned)w.kvh * tpp_u;
@@ -218,6 +213,9 @@ __device__ __forceinline__ bool decode_work_packed(const FwdParams &p, WorkItem 
     return false;
 }
 
+// Workgroups reach the 8 XCDs round-robin; XCD x takes the x-th contiguous
+// chunk of the work list, so the position tiles of one KV head, whose K/V
+// bands overlap, run behind the same L2.  Inside a pair, long rows go first.
 __device__ __forceinline__ bool decode_work(const FwdParams &p, WorkItem &w) {
     if (p.packed_compact) return decode_work_packed(p, w);
     // (the entry points refuse work lists of 2^31 items or more: 32-bit arithmetic, whose
@@ -275,18 +273,18 @@ inline bool plan_work(FwdParams &p, int rows, int wg_rows) {
 
 // The plan of a packed batch of B sequences with total_rows query rows in all (each at most
 // `rows` long): the compact work list of decode_work_packed, bounded from above -- a sequence
-// adds at most one partly filled tile per head group to total_rows / tile rows.
+// adds at most one partly filled tile per head group to total_rows / tile rows, and at most one
+// slot per XCD for the rounding of its eight chunks.
 inline bool plan_work_packed(FwdParams &p, int rows, int wg_rows, long long total_rows) {
     if (!plan_work(p, rows, wg_rows)) return false;
     if (wg_rows != 128 && wg_rows != 256) return true;  // (decode_work_packed knows these two; else the plain list)
     auto bound = [&](int tile_rows) { return (total_rows + tile_rows - 1) / tile_rows + p.B; };
     const long long tiles = p.n4 * bound(wg_rows / 4) + p.has2 * bound(wg_rows / 2) + p.has1 * bound(wg_rows);
     const long long items = (long long)p.Hkv * tiles;
-    if (items >= p.total_items) return true;  // nothing gained (sequences of nearly equal length)
     p.packed_compact = 1;
-    p.total_items = items;
-    p.chunk = (items + kXcds - 1) / kXcds;
-    return p.chunk * kXcds <= 0x7fffffffLL;
+    p.chunk = (items + kXcds - 1) / kXcds + p.B;
+    p.total_items = p.chunk * kXcds;
+    return p.total_items <= 0x7fffffffLL;
 }
 
 // Row block [p0, p0 + rows): a key is inside the window of every prompt row of

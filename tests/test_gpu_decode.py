@@ -311,3 +311,31 @@ def test_more_pairs_than_resident_workgroups():
             worst = [max(a, c) for a, c in zip(worst, e)]
         print(f"[parity] 800 pairs W{W}: O max-abs {worst[0]:.3e} mean-abs(max) {worst[1]:.3e} LSE {worst[2]:.3e}", flush=True)
         assert worst[0] <= 2e-2 and worst[1] <= 2e-3 and worst[2] <= 1e-3
+
+
+@pytest.mark.parametrize("Nq,paged", [(1, False), (1, True), (40, False)])
+def test_one_long_sequence_among_short_ones(Nq, paged):
+    # continuous batching: with sequence lengths the plan cuts for the longest cache into many short
+    # splits and deals the items to the dies in turn; the short sequences' surplus items find no keys
+    Hq, Hkv, D = 8, 2, 128
+    lens = [40000] + [Nq + 37 * i for i in range(11)]
+    rng = np.random.Generator(np.random.Philox(8100 + Nq))
+    host = [make_qkv(1, Hq, Hkv, n, D, int(rng.integers(1 << 30)), n_query=Nq) for n in lens]
+    seqs = [tuple(to_device(a) for a in s) for s in host]
+    q = torch.cat([s[0] for s in seqs], dim=0)
+    seq_lens = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    if paged:
+        kc, vc, table = _paged_cache(seqs, 16, Hkv, D, rng)
+        kb, vb, extra = kc.permute(0, 2, 1, 3), vc.permute(0, 2, 1, 3), dict(block_table=table, max_seqlen_k=max(lens))
+    else:
+        kb = torch.zeros((len(lens), Hkv, max(lens), D), dtype=torch.bfloat16, device="cuda")
+        vb = torch.zeros_like(kb)
+        for b, (_, k, v) in enumerate(seqs):
+            kb[b, :, :lens[b]], vb[b, :, :lens[b]] = k[0], v[0]
+        extra = {}
+    for W, S in ((10**9, 0), (3000, 4)):
+        out, lse = binding.swaa_attn_decode_ex(q, kb, vb, W, S, seq_lens=seq_lens, **extra)
+        torch.cuda.synchronize()
+        for b, (qs, ks, vs) in enumerate(host):
+            ro, rl = swaa_decode_oracle(qs, ks, vs, W, S, 1 / math.sqrt(D))
+            assert_parity(out[b:b + 1], lse[b:b + 1], ro, rl, tag=f"skewed batch Nq{Nq} paged{paged} seq {b} Nk{lens[b]} W{W}")
