@@ -234,8 +234,13 @@ int swaa_attn_decode(const void *q, const void *k, const void *v, void *out, flo
  *                 ptr + page * stride_b + kvh * stride_h + (j % page_size) * stride_n;
  *                 page_size a multiple of 4, block_table_stride * page_size >= Nk,
  *                 num_pages = pages in the cache (page numbers are clamped to it)
- *   Nk            the largest cache length (the key splits are planned for it);
- *                 workspace from swaa_attn_decode_workspace_bytes with this Nk
+ *   Nk            the largest cache length (an upper bound on seq_lens);
+ *                 workspace of at least swaa_attn_decode_ex_workspace_bytes(args) bytes
+ *
+ * With seq_lens (and 2 <= B <= 256) the key splits are planned on the device from the
+ * lengths themselves, so that every sequence gets splits in proportion to its length
+ * and a batch with one long sequence among short ones still fills the chip; without,
+ * they are planned for Nk.
  *   dtype         swaa_dtype of q, k, v and out: SWAA_BF16 (0, what a zeroed struct
  *                 and swaa_attn_decode select) or SWAA_F16, the precision the paper
  *                 serves in (Sec. 4.1.1); anything else: SWAA_ERR_UNSUPPORTED
@@ -267,6 +272,14 @@ int swaa_attn_decode_ex(const swaa_decode_args *args);
  * arguments are invalid.
  */
 long long swaa_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Nq, int Nk, int D, int window, int n_sink);
+
+/*
+ * The same for swaa_attn_decode_ex: reads the shape fields of args (B, Hq, Hkv, Nq, Nk,
+ * D, window, n_sink) and whether seq_lens is NULL (per-sequence lengths take another
+ * split plan, which may need more), nothing else, and no device memory.  Without
+ * seq_lens the result equals swaa_attn_decode_workspace_bytes.
+ */
+long long swaa_attn_decode_ex_workspace_bytes(const swaa_decode_args *args);
 
 /*
  * swaa_attn_decode for callers that cannot allocate device memory or hand over a

@@ -27,7 +27,7 @@ SWAA_F16 = 1
 # every symbol include/swaa.h declares
 EXPORTS = ("swaa_attn_fwd", "swaa_attn_fwd_fa_decode", "swaa_attn_fwd_ex", "swaa_visible_pairs",
            "swaa_visible_pairs_fa_decode",
-           "swaa_attn_decode", "swaa_attn_decode_ex", "swaa_attn_decode_workspace_bytes", "swaa_attn_decode_static", "swaa_attn_bwd", "swaa_attn_bwd_workspace_bytes",
+           "swaa_attn_decode", "swaa_attn_decode_ex", "swaa_attn_decode_workspace_bytes", "swaa_attn_decode_ex_workspace_bytes", "swaa_attn_decode_static", "swaa_attn_bwd", "swaa_attn_bwd_workspace_bytes",
            "swaa_status_string", "swaa_version")
 
 _lib = None
@@ -106,6 +106,8 @@ def load_library() -> ctypes.CDLL:
     lib.swaa_attn_decode_ex.argtypes = [ctypes.POINTER(SwaaDecodeArgs)]
     lib.swaa_attn_decode_workspace_bytes.restype = ctypes.c_longlong
     lib.swaa_attn_decode_workspace_bytes.argtypes = [ctypes.c_int] * 8
+    lib.swaa_attn_decode_ex_workspace_bytes.restype = ctypes.c_longlong
+    lib.swaa_attn_decode_ex_workspace_bytes.argtypes = [ctypes.POINTER(SwaaDecodeArgs)]
     lib.swaa_attn_bwd.restype = ctypes.c_int
     lib.swaa_attn_bwd.argtypes = [ctypes.c_void_p] * 9 + [ctypes.c_int] * 8 + [
         ctypes.c_float, ctypes.c_void_p, ctypes.c_longlong, ctypes.c_void_p]
@@ -472,6 +474,15 @@ def swaa_attn_bwd(q, k, v, out, lse, dout, window: int, n_sink: int, n_prompt: i
     return dq, dk, dv
 
 
+def swaa_attn_decode_ex_workspace_bytes(args: SwaaDecodeArgs) -> int:
+    """Bytes of workspace swaa_attn_decode_ex needs for this argument block (its shape fields
+    and whether seq_lens is set); raises SwaaError on invalid shapes."""
+    r = int(load_library().swaa_attn_decode_ex_workspace_bytes(ctypes.byref(args)))
+    if r < 0:
+        raise SwaaError(r, swaa_status_string(r))
+    return r
+
+
 def swaa_attn_decode_ex_raw(args: SwaaDecodeArgs) -> int:
     """The C call itself on a filled argument block; returns the status code."""
     return int(load_library().swaa_attn_decode_ex(ctypes.byref(args)))
@@ -514,14 +525,11 @@ def swaa_attn_decode_ex(q, k, v, window: int, n_sink: int, scale: float | None =
         raise ValueError("seq_lens must be a contiguous int32 [B] GPU tensor")
     if scale is None:
         scale = 1.0 / math.sqrt(D)
-    need = swaa_attn_decode_workspace_bytes(B, Hq, Hkv, Nq, Nk, D, window, n_sink)
     with torch.cuda.device(q.device):
         if out is None:
             out = torch.empty_like(q)
         if lse is None:
             lse = torch.empty((B, Hq, Nq), dtype=torch.float32, device=q.device)
-        if workspace is None:
-            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
         if stream is None:
             stream = torch.cuda.current_stream(q.device)
         a = SwaaDecodeArgs()
@@ -535,6 +543,9 @@ def swaa_attn_decode_ex(q, k, v, window: int, n_sink: int, scale: float | None =
         a.num_pages = k.shape[0] if paged else 0
         a.B, a.Hq, a.Hkv, a.Nq, a.Nk, a.D = B, Hq, Hkv, Nq, Nk, D
         a.window, a.n_sink, a.scale = int(window), int(n_sink), float(scale)
+        if workspace is None:
+            need = swaa_attn_decode_ex_workspace_bytes(a)
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
         a.workspace, a.workspace_bytes = workspace.data_ptr(), workspace.numel()
         a.stream = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
         a.dtype = SWAA_F16 if q.dtype == torch.float16 else SWAA_BF16

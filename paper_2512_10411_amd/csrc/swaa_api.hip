@@ -197,16 +197,16 @@ int decode_plan(swaa::DecodeParams &p, int B, int Hq, int Hkv, int Nq, int Nk, i
 }  // namespace
 
 long long swaa_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Nq, int Nk, int D, int window, int n_sink) {
-    // (the larger of the two plans: the call may or may not come with per-sequence lengths)
-    long long need = 0;
-    for (const bool ragged : {false, true}) {
-        swaa::DecodeParams p{};
-        const int rc = decode_plan(p, B, Hq, Hkv, Nq, Nk, D, window, n_sink, ragged);
-        if (rc != SWAA_OK) return rc;
-        const long long n = swaa::decode_workspace_floats(p) * (long long)sizeof(float);
-        need = n > need ? n : need;
-    }
-    return need;
+    swaa::DecodeParams p{};
+    const int rc = decode_plan(p, B, Hq, Hkv, Nq, Nk, D, window, n_sink, false);
+    return rc != SWAA_OK ? rc : swaa::decode_workspace_floats(p) * (long long)sizeof(float);
+}
+
+long long swaa_attn_decode_ex_workspace_bytes(const swaa_decode_args *a) {
+    if (!a) return SWAA_ERR_NULL;
+    swaa::DecodeParams p{};
+    const int rc = decode_plan(p, a->B, a->Hq, a->Hkv, a->Nq, a->Nk, a->D, a->window, a->n_sink, a->seq_lens != nullptr);
+    return rc != SWAA_OK ? rc : swaa::decode_workspace_floats(p) * (long long)sizeof(float);
 }
 
 namespace {
@@ -217,7 +217,7 @@ int decode_call(const swaa_decode_args *a, bool own_scratch) {
     if (!a) return SWAA_ERR_NULL;
     if (!a->q || !a->k.ptr || !a->v.ptr || !a->out || !a->lse) return SWAA_ERR_NULL;
     swaa::DecodeParams p{};
-    const int rc = decode_plan(p, a->B, a->Hq, a->Hkv, a->Nq, a->Nk, a->D, a->window, a->n_sink, a->seq_lens != nullptr && a->B > 1);
+    const int rc = decode_plan(p, a->B, a->Hq, a->Hkv, a->Nq, a->Nk, a->D, a->window, a->n_sink, a->seq_lens != nullptr);
     if (rc != SWAA_OK) return rc;
     if (!positive_finite(a->scale)) return SWAA_ERR_SHAPE;
     if (a->dtype != SWAA_BF16 && a->dtype != SWAA_F16) return SWAA_ERR_UNSUPPORTED;
@@ -259,6 +259,7 @@ int decode_call(const swaa_decode_args *a, bool own_scratch) {
     p.seq_lens = a->seq_lens;
     p.ws_o = static_cast<float *>(workspace);
     p.ws_ml = p.ws_o + p.items * (long long)p.col_stride * 128;
+    p.ws_units = reinterpret_cast<int *>(p.ws_ml + p.items * 64);
     p.fp16 = a->dtype == SWAA_F16 ? 1 : 0;
     p.scale_log2 = a->scale * 1.44269504088896340736f;
     const hipError_t err = swaa::launch_decode(p, static_cast<hipStream_t>(a->stream));

@@ -134,6 +134,24 @@ struct WorkItem {
     int pt;      // row tile of 256/hpb rows
 };
 
+// Inclusive prefix sum of x over the 64 lanes of a wave, all of them active: four shift-and-add
+// steps inside each row of 16 lanes (a lane without a source adds 0), then lane 15 of rows 0 and 2
+// into rows 1 and 3, then lane 31 into rows 2 and 3 -- data-parallel-primitive operands of the
+// vector adds, no trip through the LDS crossbar as with the shuffle functions.
+__device__ __forceinline__ unsigned wave_inclusive_scan(unsigned x) {
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, false);  // row_shr:1
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, false);  // row_shr:2
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, false);  // row_shr:4
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, false);  // row_shr:8
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xa, 0xf, false);  // row_bcast:15, rows 1 and 3
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xc, 0xf, false);  // row_bcast:31, rows 2 and 3
+    return x;
+}
+// Lane `src` (the same in all lanes) of x, as a uniform value.
+__device__ __forceinline__ unsigned wave_read_lane(unsigned x, int src) {
+    return (unsigned)__builtin_amdgcn_readlane((int)x, src);
+}
+
 // The work list of a packed batch, sequence by sequence: sequence b of nq_b query rows (the
 // smaller of its rows, the plan's Nq and its keys -- what seq_geom makes of it) has Hkv pairs of
 // n4 ceil(nq_b / r4) + has2 ceil(nq_b / r2) + has1 ceil(nq_b / r1) row tiles, r4 = wg_rows / 4
@@ -157,32 +175,23 @@ __device__ __forceinline__ bool decode_work_packed(const FwdParams &p, WorkItem 
         return (unsigned)(p.n4 * ((nq + (1 << (s1 - 2)) - 1) >> (s1 - 2)) + p.has2 * ((nq + (1 << (s1 - 1)) - 1) >> (s1 - 1)) +
                           p.has1 * ((nq + (1 << s1) - 1) >> s1));
     };
-    auto scan = [&](unsigned x) {  // inclusive prefix sum over the 64 lanes
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const unsigned y = (unsigned)__shfl_up((int)x, d);
-            x += lane >= d ? y : 0u;
-        }
-        return x;
-    };
     unsigned before = 0;
     for (int c0 = 0; c0 < p.B; c0 += 64) {
         const int nq = rows_of(c0 + lane);
-        const unsigned incl = scan((tiles_of(nq) * (unsigned)p.Hkv + kXcds - 1) / kXcds);  // slots of this XCD up to and with the lane's sequence
-        const unsigned in_round = (unsigned)__builtin_amdgcn_readfirstlane(__shfl((int)incl, 63));  // (uniform: a scalar branch below)
+        const unsigned incl = wave_inclusive_scan((tiles_of(nq) * (unsigned)p.Hkv + kXcds - 1) / kXcds);  // slots of this XCD up to and with the lane's sequence
+        const unsigned in_round = wave_read_lane(incl, 63);
         if (slot - before < in_round) {
             const unsigned rel = slot - before;
             const int n = __popcll(__ballot(incl <= rel));  // sequences of this round that end at or before the slot
-            const unsigned base = n ? (unsigned)__shfl((int)incl, n - 1) : 0u;
-            const int nq_b = __shfl(nq, n);
-            // (everything below is the same in all lanes; read through the first lane so that the
+            const unsigned base = n ? wave_read_lane(incl, n - 1) : 0u;
+            // (everything below is the same in all lanes, and read from one lane so that the
             // compiler knows it and keeps addresses built from it in scalar registers)
-            const int nq_u = __builtin_amdgcn_readfirstlane(nq_b);
+            const int nq_u = (int)wave_read_lane((unsigned)nq, n);
             const unsigned tpp_u = tiles_of(nq_u);
             const unsigned items_u = tpp_u * (unsigned)p.Hkv;
-            unsigned r = xcd * ((items_u + kXcds - 1) / kXcds) + (unsigned)__builtin_amdgcn_readfirstlane((int)(rel - base));  // inside sequence c0 + n
+            unsigned r = xcd * ((items_u + kXcds - 1) / kXcds) + (rel - base);  // inside sequence c0 + n
             if (r >= items_u) return false;  // (the sequence's last chunks are shorter)
-            w.b = __builtin_amdgcn_readfirstlane(c0 + n);
+            w.b = c0 + n;
             w.kvh = (int)(r / tpp_u);
             r -= (unsigned)w.kvh * tpp_u;
             const unsigned nt4 = (unsigned)((nq_u + (1 << (s1 - 2)) - 1) >> (s1 - 2));

@@ -23,6 +23,7 @@ struct DecodeParams {
     float *lse;
     float *ws_o;   // [items][col_stride][128]: sum of 2^(s c2 - mc) v over the item's keys
     float *ws_ml;  // [items][2][32]: mc (softmax reference, log2 units) and l (sum of 2^(s c2 - mc))
+    int *ws_units;  // ragged plans: [B][2], first (sequence, split) unit and number of splits of each sequence
     // Cache addressing, in elements; the head dimension is contiguous.
     //   contiguous: row `key` of (b, kvh) at  k + b * k_sb + kvh * k_sh + key * k_sn
     //   paged:      page = block_table[b * bt_stride + key / page_size] and the row at
@@ -41,13 +42,20 @@ struct DecodeParams {
     int col_stride;  // min(cols, 32): columns an item stores
     int n_halves;  // upper bound on the halves a sequence of at most Nk tokens visits
     int halves_per_split, n_splits;
-    long long items;  // B * Hkv * n_coltiles * n_splits (below 2^31): partial results in the workspace
+    long long items;  // B * Hkv * n_coltiles * n_splits (ragged: max_units * Hkv * n_coltiles; below 2^31): partial results in the workspace
     // a workgroup computes tiles_per_item (1 or 2) column tiles of one (pair, split) from the same
     // K and V fragments; n_ctgroups = ceil(n_coltiles / tiles_per_item) of them per (pair, split)
     int tiles_per_item, n_ctgroups;
-    long long wg_items;  // B * Hkv * n_ctgroups * n_splits: workgroups that have work
+    long long wg_items;  // B * Hkv * n_ctgroups * n_splits (ragged: max_units * Hkv * n_ctgroups, an upper bound): workgroups that have work
     int fp16;         // elements of q, k, v, out are IEEE binary16 instead of bfloat16
-    int ragged;       // the plan was made for sequences of different lengths (plan_decode)
+    // Sequences of different lengths (seq_lens given, a batch of 2 .. kRaggedMaxBatch): the splits are
+    // planned on the device.  Every wave adds up the halves all sequences visit, takes
+    // halves_per_split = max(4, ceil(sum / units_target)) and gives sequence b ceil(halves_b /
+    // halves_per_split) splits -- work in proportion to length, at most units_target + B
+    // (sequence, split) units in all (max_units: the launch and the workspace are sized for it).
+    // halves_per_split and n_splits above are then not used.
+    int ragged;
+    int units_target, max_units;
     // divisions every workgroup makes, as multiplications (FastDiv)
     FastDiv div_ctgroups, div_splits, div_hkv, div_page, div_per_round;
 };
@@ -68,8 +76,9 @@ __host__ __device__ inline VisitedHalves visited_halves(int nk, int nq, int W, i
 }
 
 // Fills the plan fields (everything from `cols` on) from the shape fields.  ragged: the sequences
-// may hold far fewer than Nk tokens each (seq_lens is given): shorter splits, so that a batch with
-// one long sequence among short ones still has enough items with work.
+// may hold far fewer than Nk tokens each (seq_lens is given): the device-side plan described at
+// DecodeParams::ragged, for batches of 2 .. kRaggedMaxBatch sequences (else the plan for Nk).
+constexpr int kRaggedMaxBatch = 256;
 void plan_decode(DecodeParams &p, bool ragged);
 // Floats the workspace must hold for this plan.
 long long decode_workspace_floats(const DecodeParams &p);

@@ -25,7 +25,8 @@
 //   * The cache is a contiguous strided tensor or a paged one (a block table of
 //     page numbers per sequence, pages of page_size tokens: the layout of a
 //     serving engine's cache manager); sequences of a batch may have different
-//     cache lengths (seq_lens), shorter ones leave empty partial results.
+//     cache lengths (seq_lens): the splits are then planned on the device, in
+//     proportion to the lengths (DecodeParams::ragged).
 //   * Each workgroup leaves (O unnormalised, reference, row sum) for its valid
 //     columns in the workspace; swaa_decode_merge_kernel combines the splits.
 //
@@ -47,19 +48,82 @@ constexpr int kCopiesPerHalf = 16;                    // wave instructions per s
 constexpr int kMergeThreads = 1024;
 constexpr int kRounds = 1;  // rounds of resident workgroups the split plan aims for
 
+// ---- the split plan of a batch with per-sequence lengths, worked out by every workgroup of the
+// split kernel (DecodeParams::ragged has the rules) ----
+// Lane l keeps the halves that sequences l, 64 + l, ... visit (0 beyond the batch).
+constexpr int kRaggedLaneRounds = kRaggedMaxBatch / 64;
+struct RaggedHalves {
+    unsigned n[kRaggedLaneRounds];
+};
+__device__ __forceinline__ RaggedHalves ragged_halves(const DecodeParams &p, int lane) {
+    RaggedHalves h;
+#pragma unroll
+    for (int r = 0; r < kRaggedLaneRounds; ++r) {
+        const int b = 64 * r + lane;
+        const int nk = max(min(p.seq_lens[min(b, p.B - 1)], p.Nk), p.Nq);
+        h.n[r] = b < p.B ? (unsigned)visited_halves(nk, p.Nq, p.W, p.S).n : 0u;
+    }
+    return h;
+}
+__device__ __forceinline__ unsigned ragged_halves_per_split(const DecodeParams &p, const RaggedHalves &h) {
+    auto sum_over_sequences = [&](auto f) {
+        unsigned mine = 0;
+#pragma unroll
+        for (int r = 0; r < kRaggedLaneRounds; ++r) mine += f(h.n[r]);
+        return wave_read_lane(wave_inclusive_scan(mine), 63);
+    };
+    const unsigned target = (unsigned)p.units_target;
+    const unsigned total = sum_over_sequences([](unsigned n) { return n; });
+    unsigned hps = (total + target - 1) / target;
+    hps = hps < 4u ? 4u : hps;
+    // Rounding up per sequence can leave a few units more than the target, i.e. a handful of
+    // workgroups in one more round than planned: lengthen the splits until the count fits (a
+    // few steps; whatever they end on, the count stays below units_target + B).
+    for (int it = 0; it < 4; ++it) {
+        const unsigned units = sum_over_sequences([&](unsigned n) { return (n + hps - 1) / hps; });
+        if (units <= target) break;
+        const unsigned longer = (hps * units + target - 1) / target;
+        hps = longer > hps ? longer : hps + 1;
+    }
+    return hps;
+}
+// The sequence and the split of unit `unit` of the list (sequence 0's splits, then sequence 1's, ...)
+// and how many splits that sequence has; false beyond the list's end.
+__device__ __forceinline__ bool ragged_find(const RaggedHalves &h, unsigned hps, unsigned unit, int &b, int &split, int &n_splits) {
+    unsigned before = 0;
+#pragma unroll
+    for (int r = 0; r < kRaggedLaneRounds; ++r) {
+        const unsigned mine = (h.n[r] + hps - 1) / hps;
+        const unsigned incl = wave_inclusive_scan(mine);
+        const unsigned in_round = wave_read_lane(incl, 63);
+        if (unit - before < in_round) {
+            const unsigned rel = unit - before;
+            const int n = __popcll(__ballot(incl <= rel));  // sequences of this round that end at or before the unit
+            const unsigned base = n ? wave_read_lane(incl, n - 1) : 0u;
+            // (the same in all lanes; read through the first lane so that the compiler knows it
+            // and keeps the addresses built from them in scalar registers)
+            b = __builtin_amdgcn_readfirstlane(64 * r + n);
+            split = __builtin_amdgcn_readfirstlane((int)(rel - base));
+            n_splits = (int)wave_read_lane(mine, n);
+            return true;
+        }
+        before += in_round;
+    }
+    return false;
+}
+
 // kPaged: k and v are a paged cache addressed through p.block_table (its own instantiation).
 // kTiles: column tiles a workgroup computes from the same K and V fragments (1, or 2 when a pair
 // has more than 32 query rows: two tiles in two workgroups would read every key twice).
 template <bool kF16, bool kPaged, int kTiles>
 __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParams p) {
-    // XCD x takes the x-th contiguous chunk of the item list (column tiles of one
-    // split, which read the same keys, then run behind the same L2).  The list has fewer
-    // than 2^31 items: 32-bit arithmetic, divisions as multiplications.
-    // Workgroups reach the eight dies round-robin.  Sequences of one length: die x takes the x-th
+    // Workgroups reach the eight dies round-robin; the list has fewer than 2^31 items: 32-bit
+    // arithmetic, divisions as multiplications.  Sequences of one length: die x takes the x-th
     // contiguous chunk of the item list (a die streams neighbouring memory: 3 % faster on one
-    // long sequence).  Per-sequence lengths: consecutive (pair, split) items go to consecutive
-    // dies, so that whatever the lengths every die gets its share of the long sequences.  Either
-    // way the column-tile groups of one (pair, split), which read the same keys, share a die.
+    // long sequence).  Per-sequence lengths: the units (sequence, split) x KV heads go to the
+    // dies in turn, so that whatever the lengths every die gets its share of the long sequences.
+    // Either way the column-tile groups of one (pair, split), which read the same keys, share a die.
+    const int lane = threadIdx.x;
     const unsigned items = (unsigned)p.wg_items;
     unsigned witem;
     if (p.ragged) {
@@ -75,10 +139,31 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
     if (witem >= items) return;
     const unsigned item_ct = fastdiv(witem, p.div_ctgroups);      // witem / n_ctgroups
     const int ctg = (int)(witem - item_ct * (unsigned)p.n_ctgroups);
-    const unsigned upair = fastdiv(item_ct, p.div_splits);        // witem / (n_ctgroups * n_splits)
-    const int split = (int)(item_ct - upair * (unsigned)p.n_splits);
-    const int pair = (int)upair;
-    const int b = (int)fastdiv(upair, p.div_hkv), kvh = pair - b * p.Hkv;
+    int b, kvh, split, halves_per_split;
+    size_t slot0;  // workspace slot of the item's column tile 0
+    if (p.ragged) {
+        const unsigned unit = fastdiv(item_ct, p.div_hkv);        // (sequence, split) units, KV head innermost
+        kvh = (int)(item_ct - unit * (unsigned)p.Hkv);
+        const RaggedHalves rh = ragged_halves(p, lane);
+        halves_per_split = __builtin_amdgcn_readfirstlane((int)ragged_halves_per_split(p, rh));
+        int n_splits;
+        if (!ragged_find(rh, (unsigned)halves_per_split, unit, b, split, n_splits)) return;  // beyond the true list
+        slot0 = (size_t)item_ct * p.n_coltiles;
+        // the sequence's first workgroup tells the merge kernel where its splits are (all lanes
+        // store the same two words: a branch on the lane id here would make the compiler treat
+        // what follows as lane-dependent, and the copies' base addresses must stay scalar)
+        if (split == 0 && kvh == 0 && ctg == 0) {
+            p.ws_units[2 * b] = (int)unit;
+            p.ws_units[2 * b + 1] = n_splits;
+        }
+    } else {
+        const unsigned upair = fastdiv(item_ct, p.div_splits);    // witem / (n_ctgroups * n_splits)
+        split = (int)(item_ct - upair * (unsigned)p.n_splits);
+        b = (int)fastdiv(upair, p.div_hkv);
+        kvh = (int)upair - b * p.Hkv;
+        halves_per_split = p.halves_per_split;
+        slot0 = ((size_t)upair * p.n_splits + split) * p.n_coltiles;
+    }
     // this workgroup's column tiles and the workspace slots of their partial results
     int ct[kTiles];
     bool tile_valid[kTiles];
@@ -87,14 +172,16 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
     for (int j = 0; j < kTiles; ++j) {
         ct[j] = ctg * kTiles + j;
         tile_valid[j] = ct[j] < p.n_coltiles;  // (uniform; an odd number of tiles leaves the last workgroup one)
-        item[j] = ((size_t)pair * p.n_splits + split) * p.n_coltiles + min(ct[j], p.n_coltiles - 1);
+        item[j] = slot0 + min(ct[j], p.n_coltiles - 1);
     }
 
-    const int lane = threadIdx.x;
     const int l32 = lane & 31;
     const int hf = lane >> 5;
     // this sequence's cache length (at least the query rows themselves) and its visited halves
-    const int Nk = p.seq_lens ? max(min(p.seq_lens[b], p.Nk), p.Nq) : p.Nk;
+    // (read as constant memory -- nothing writes the lengths while the kernel runs -- so that it is
+    // a scalar load whatever the kernel has stored before it)
+    typedef const int __attribute__((address_space(4))) *ConstInts;
+    const int Nk = p.seq_lens ? max(min(((ConstInts)p.seq_lens)[b], p.Nk), p.Nq) : p.Nk;
     const int W = p.W, S = p.S;
     const VisitedHalves vh = visited_halves(Nk, p.Nq, W, S);
 
@@ -111,8 +198,8 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
     }
     const int pos_min = Nk - p.Nq, pos_max = Nk - 1;
 
-    const int h_begin = split * p.halves_per_split;
-    const int n_mine = min(vh.n - h_begin, p.halves_per_split);
+    const int h_begin = split * halves_per_split;
+    const int n_mine = min(vh.n - h_begin, halves_per_split);
     if (n_mine <= 0) {
         // a shorter sequence has no keys for this split: an empty partial result (weight 0 in the merge)
 #pragma unroll
@@ -392,12 +479,20 @@ __global__ __launch_bounds__(kMergeThreads) void swaa_decode_merge_kernel(const 
     const int kvh = hq / p.G;
     const int c = (hq % p.G) * p.Nq + r;
     const int ct = c / 32, col = c % 32;
-    const long long pair = (long long)b * p.Hkv + kvh;
-    auto item_of = [&](int s) { return (pair * p.n_splits + s) * p.n_coltiles + ct; };
+    // the splits of this row's (batch, KV head) pair and the workspace slot of the first one
+    int n_splits = p.n_splits;
+    long long slot0 = ((long long)b * p.Hkv + kvh) * p.n_splits;
+    long long slot_step = 1;
+    if (p.ragged) {  // (the device-side plan: the sequence's first split workgroup has left it here)
+        n_splits = p.ws_units[2 * b + 1];
+        slot0 = (long long)p.ws_units[2 * b] * p.Hkv + kvh;
+        slot_step = p.Hkv;
+    }
+    auto item_of = [&](int s) { return (slot0 + s * slot_step) * p.n_coltiles + ct; };
 
     // largest reference over the splits: wave maxima by lane exchange, then one LDS round
     float m = -INFINITY;
-    for (int s = tid; s < p.n_splits; s += kMergeThreads) m = fmaxf(m, p.ws_ml[item_of(s) * 64 + col]);
+    for (int s = tid; s < n_splits; s += kMergeThreads) m = fmaxf(m, p.ws_ml[item_of(s) * 64 + col]);
 #pragma unroll
     for (int sh = 32; sh > 0; sh >>= 1) m = fmaxf(m, __shfl_xor(m, sh));
     if ((tid & 63) == 0) red[tid >> 6] = m;
@@ -412,12 +507,12 @@ __global__ __launch_bounds__(kMergeThreads) void swaa_decode_merge_kernel(const 
     const int d = tid % kD, g = tid / kD;
     constexpr int kGroups = kMergeThreads / kD;
     float acc = 0.f, l = 0.f;
-    for (int s0 = g; s0 < p.n_splits; s0 += 4 * kGroups) {
+    for (int s0 = g; s0 < n_splits; s0 += 4 * kGroups) {
         float mcs[4], ls[4], os[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int s = s0 + u * kGroups;
-            const bool there = s < p.n_splits;
+            const bool there = s < n_splits;
             const long long it = item_of(there ? s : s0);
             mcs[u] = p.ws_ml[it * 64 + col];
             ls[u] = p.ws_ml[it * 64 + 32 + col];
@@ -453,7 +548,6 @@ __global__ __launch_bounds__(kMergeThreads) void swaa_decode_merge_kernel(const 
 }  // namespace
 
 void plan_decode(DecodeParams &p, bool ragged) {
-    p.ragged = ragged ? 1 : 0;
     p.cols = p.G * p.Nq;
     p.n_coltiles = (p.cols + 31) / 32;
     p.col_stride = p.cols < 32 ? p.cols : 32;
@@ -467,12 +561,28 @@ void plan_decode(DecodeParams &p, bool ragged) {
     p.tiles_per_item = p.n_coltiles >= 2 ? 2 : 1;
     p.n_ctgroups = (p.n_coltiles + p.tiles_per_item - 1) / p.tiles_per_item;
     const long long groups = (long long)p.B * p.Hkv * p.n_ctgroups;
-    // With per-sequence lengths the plan, made for the longest sequence, aims for kRaggedRounds
-    // rounds: one sequence of Nk tokens among short ones then still fills the chip by itself when
-    // the batch has up to kRaggedRounds sequences' worth of pairs (the short ones' surplus items
-    // find no keys and end at once).
-    constexpr long long kRaggedRounds = 8;
-    const long long target_items = 256LL * 3 * (ragged ? kRaggedRounds : kRounds);
+    p.div_ctgroups = make_fastdiv((unsigned)p.n_ctgroups);
+    p.div_per_round = make_fastdiv((unsigned)(kXcds * p.n_ctgroups));
+    p.div_hkv = make_fastdiv((unsigned)p.Hkv);
+    p.ragged = ragged && p.B >= 2 && p.B <= kRaggedMaxBatch && (long long)p.B * p.n_halves < 0x7fffffffLL ? 1 : 0;
+    if (p.ragged) {
+        // Per-sequence lengths: kRaggedRounds rounds of resident workgroups' worth of (sequence,
+        // split) units, cut on the device in proportion to the sequences' lengths; kTailRounds
+        // with more (pair, column tile) groups than resident workgroups (see below).
+        constexpr long long kRaggedRounds = 2, kRaggedTailRounds = 8;
+        const long long units = 256LL * 3 * (groups > 256LL * 3 ? kRaggedTailRounds : kRaggedRounds) / ((long long)p.Hkv * p.n_ctgroups);
+        p.units_target = (int)(units < 1 ? 1 : units);
+        // (at most units_target + B units by the rounding of the device's division, and no
+        // sequence has more than ceil(n_halves / 4) splits)
+        const long long most = (long long)p.B * ((p.n_halves + 3) / 4);
+        p.max_units = (int)(p.units_target + p.B < most ? p.units_target + p.B : most);
+        p.halves_per_split = p.n_splits = 0;
+        p.div_splits = make_fastdiv(1u);
+        p.wg_items = (long long)p.max_units * p.Hkv * p.n_ctgroups;
+        p.items = (long long)p.max_units * p.Hkv * p.n_coltiles;
+        return;
+    }
+    const long long target_items = 256LL * 3 * kRounds;
     long long per_group = target_items / groups;
     // More (pair, column tile) groups than resident workgroups: one item per group would leave a
     // second round of a few long items streaming alone at the end (100 sequences x 8 KV heads
@@ -486,13 +596,13 @@ void plan_decode(DecodeParams &p, bool ragged) {
     p.n_splits = (int)((p.n_halves + hps - 1) / hps);
     p.wg_items = groups * p.n_splits;
     p.items = (long long)p.B * p.Hkv * p.n_coltiles * p.n_splits;
-    p.div_ctgroups = make_fastdiv((unsigned)p.n_ctgroups);
-    p.div_per_round = make_fastdiv((unsigned)(kXcds * p.n_ctgroups));
     p.div_splits = make_fastdiv((unsigned)p.n_splits);
-    p.div_hkv = make_fastdiv((unsigned)p.Hkv);
 }
 
-long long decode_workspace_floats(const DecodeParams &p) { return p.items * ((long long)p.col_stride * kD + 64); }
+long long decode_workspace_floats(const DecodeParams &p) {
+    // (per item O and 64 floats of references and row sums; ragged: two ints per sequence on top, rounded to 16 bytes)
+    return p.items * ((long long)p.col_stride * kD + 64) + (p.ragged ? (2LL * p.B + 3) / 4 * 4 : 0);
+}
 
 // ---- scratch memory for callers that cannot allocate -----------------------------------
 // swaa_attn_decode_static keeps the partial results of the key splits here instead of in

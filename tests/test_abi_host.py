@@ -225,3 +225,20 @@ def test_general_decode_argument_errors():
     assert call(seq_lens=p + 2) == binding.SWAA_ERR_ALIGN
     assert call(D=64) == binding.SWAA_ERR_UNSUPPORTED
     assert call(workspace_bytes=16) == binding.SWAA_ERR_WORKSPACE
+    assert call(dtype=7) == binding.SWAA_ERR_UNSUPPORTED
+
+    # the workspace of the general call: without sequence lengths what the plain call needs; with
+    # them the device-side split plan's bound, refused one byte short (checked before any launch)
+    lib = binding.load_library()
+    assert lib.swaa_attn_decode_ex_workspace_bytes(None) == binding.SWAA_ERR_NULL
+    plain = binding.swaa_attn_decode_workspace_bytes(2, 8, 2, 1, 1024, 128, 1024, 0)
+    assert binding.swaa_attn_decode_ex_workspace_bytes(args()) == plain
+    ragged = binding.swaa_attn_decode_ex_workspace_bytes(args(seq_lens=p))
+    assert 0 < ragged <= 2 * (1024 // 32 // 4) * 2 * (4 * 128 + 64) * 4 + 16   # B x ceil(halves / 4) units x Hkv items, B x 2 ints
+    assert call(seq_lens=p, workspace_bytes=ragged - 1) == binding.SWAA_ERR_WORKSPACE
+    with pytest.raises(binding.SwaaError):
+        binding.swaa_attn_decode_ex_workspace_bytes(args(Nq=2000))
+    # one sequence, and more sequences than the device-side plan takes: the plan for Nk
+    for B in (1, 300):
+        assert binding.swaa_attn_decode_ex_workspace_bytes(args(B=B, seq_lens=p)) == \
+            binding.swaa_attn_decode_workspace_bytes(B, 8, 2, 1, 1024, 128, 1024, 0)

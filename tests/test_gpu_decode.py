@@ -339,3 +339,28 @@ def test_one_long_sequence_among_short_ones(Nq, paged):
         for b, (qs, ks, vs) in enumerate(host):
             ro, rl = swaa_decode_oracle(qs, ks, vs, W, S, 1 / math.sqrt(D))
             assert_parity(out[b:b + 1], lse[b:b + 1], ro, rl, tag=f"skewed batch Nq{Nq} paged{paged} seq {b} Nk{lens[b]} W{W}")
+
+
+@pytest.mark.parametrize("B", [65, 256, 257])
+def test_batches_around_the_limits_of_the_device_side_split_plan(B):
+    # sequence lengths in the second round of 64 lanes, in the last lane of the last round, and one
+    # sequence more than the device-side plan takes (then the splits are planned for the longest)
+    Hq, Hkv, Nq, D, max_len = 2, 1, 1, 128, 900
+    rng = np.random.Generator(np.random.Philox(8200 + B))
+    lens = [int(x) for x in rng.integers(1, 200, size=B)]
+    lens[B - 1], lens[B // 2], lens[0] = max_len, 777, 1
+    host = [make_qkv(1, Hq, Hkv, n, D, 8300 + i, n_query=Nq) for i, n in enumerate(lens)]
+    kb = torch.zeros((B, Hkv, max_len, D), dtype=torch.bfloat16, device="cuda")
+    vb = torch.zeros_like(kb)
+    for b, (_, k, v) in enumerate(host):
+        kb[b, :, :lens[b]], vb[b, :, :lens[b]] = to_device(k)[0], to_device(v)[0]
+    q = torch.cat([to_device(s[0]) for s in host], dim=0)
+    out, lse = binding.swaa_attn_decode_ex(q, kb, vb, 10**9, 0, seq_lens=torch.tensor(lens, dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    from gpu_util import errors
+    worst = [0.0, 0.0, 0.0]
+    for b, (qs, ks, vs) in enumerate(host):
+        ro, rl = swaa_decode_oracle(qs, ks, vs, 10**9, 0, 1 / math.sqrt(D))
+        worst = [max(a, c) for a, c in zip(worst, errors(out[b:b + 1], lse[b:b + 1], ro, rl))]
+    print(f"[parity] B{B} ragged: O max-abs {worst[0]:.3e} mean-abs(max) {worst[1]:.3e} LSE {worst[2]:.3e}", flush=True)
+    assert worst[0] <= 2e-2 and worst[1] <= 2e-3 and worst[2] <= 1e-3
