@@ -46,6 +46,8 @@ MEASURED_TRAFFIC_BYTES = {
     "decode128k_full": (5.41e8, "profiles/swaa_decode_decode128k_full.txt"),
     "decode16k_b16": (1.079e9, "profiles/swaa_decode_decode16k_b16.txt"),
     "decode128k_swa": (3.67e7, "profiles/swaa_decode_decode128k_swa.txt"),
+    "decode_skewed_b16": (6.081e8, "profiles/swaa_decode_decode_skewed_b16.txt"),
+    "decode_mixed_b32": (1.078e9, "profiles/swaa_decode_decode_mixed_b32.txt"),
     "mid_bwd": (1.63e9, "profiles/swaa_bwd_mid_bwd.txt"),
 }
 MIN_WARMUP_S = 0.05  # the clocks settle only after some tens of ms of continuous work
@@ -77,6 +79,10 @@ def parse():
 
 def decode_counts(w):
     """(visible pairs per launch, algorithmic HBM bytes per launch) of a decode-shape workload."""
+    if w.seq_lens:  # one sequence at a time
+        import dataclasses
+        each = [decode_counts(dataclasses.replace(w, B=1, N=n, seq_lens=())) for n in w.seq_lens]
+        return sum(e[0] for e in each), sum(e[1] for e in each)
     Nq, Nk = w.n_query, w.N
     W, S = min(w.window, Nk), min(w.n_sink, Nk)
     pairs = 0
@@ -93,7 +99,13 @@ def cpu_baseline_decode(w, q, k, v):
     """Time the oracle as it stands on the whole decode-shape workload (it is small)."""
     from oracle import oracle_num_threads, swaa_decode_oracle
     t0 = time.perf_counter()
-    swaa_decode_oracle(q, k, v, w.window, w.n_sink, w.scale)
+    if w.seq_lens:  # sequence by sequence (k, v hold their tokens back to back)
+        t = 0
+        for b, n in enumerate(w.seq_lens):
+            swaa_decode_oracle(q[b:b + 1], k[:, :, t:t + n], v[:, :, t:t + n], w.window, w.n_sink, w.scale)
+            t += n
+    else:
+        swaa_decode_oracle(q, k, v, w.window, w.n_sink, w.scale)
     dt = time.perf_counter() - t0
     pairs, _ = decode_counts(w)
     return {
@@ -204,9 +216,23 @@ def main():
 
     n_prompt = w.N if w.n_prompt is None else w.n_prompt
     decode = w.n_query is not None and not w.chunk
+    seq_lens = None
+    if w.seq_lens:
+        # a [B, Hkv, longest, D] cache buffer, each sequence filled up to its own length
+        seq_lens = torch.tensor(w.seq_lens, dtype=torch.int32, device="cuda")
+        kbuf = torch.empty((w.B, w.Hkv, w.N, w.D), dtype=kd.dtype, device="cuda")  # (rows past a sequence's length are never read)
+        vbuf = torch.empty_like(kbuf)
+        t = 0
+        for b, n in enumerate(w.seq_lens):
+            kbuf[b, :, :n], vbuf[b, :, :n] = kd[0, :, t:t + n], vd[0, :, t:t + n]
+            t += n
+        kd, vd = kbuf, vbuf
     if decode:
-        ws = torch.empty(binding.swaa_attn_decode_workspace_bytes(w.B, w.Hq, w.Hkv, w.n_query, w.N, w.D, w.window,
-                                                                  w.n_sink), dtype=torch.uint8, device="cuda")
+        # (the general call's size for the workloads that go through it: sequence lengths change the split plan)
+        da = binding.SwaaDecodeArgs()
+        da.B, da.Hq, da.Hkv, da.Nq, da.Nk, da.D, da.window, da.n_sink = w.B, w.Hq, w.Hkv, w.n_query, w.N, w.D, w.window, w.n_sink
+        da.seq_lens = seq_lens.data_ptr() if seq_lens is not None else None
+        ws = torch.empty(binding.swaa_attn_decode_ex_workspace_bytes(da), dtype=torch.uint8, device="cuda")
 
     if w.packed_lens:
         import numpy as np
@@ -237,6 +263,9 @@ def main():
         elif decode and w.page_size:
             binding.swaa_attn_decode_ex(qd, kd, vd, w.window, w.n_sink, w.scale, block_table=table, max_seqlen_k=w.N,
                                         out=out, lse=lse, workspace=ws, stream=stream)
+        elif decode and w.seq_lens:
+            binding.swaa_attn_decode_ex(qd, kd, vd, w.window, w.n_sink, w.scale, seq_lens=seq_lens, out=out, lse=lse,
+                                        workspace=ws, stream=stream)
         elif decode:
             binding.swaa_attn_decode(qd, kd, vd, w.window, w.n_sink, w.scale, out=out, lse=lse, workspace=ws,
                                      stream=stream)
@@ -369,7 +398,8 @@ def main():
                    "window": w.window, "n_sink": w.n_sink, "n_prompt": n_prompt, "seed": w.seed, "k_mult": w.k_mult,
                    "visible_pairs": pairs, "flops_per_step": flops,
                    "pct_bf16_mfma_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS,
-                   **({"packed_lens": list(w.packed_lens)} if w.packed_lens else {})},
+                   **({"packed_lens": list(w.packed_lens)} if w.packed_lens else {}),
+                   **({"seq_lens": list(w.seq_lens)} if w.seq_lens else {})},
         "roofline": roofline,
     }
     if linear_in_w is not None:

@@ -55,6 +55,7 @@ class Workload:
     recipe: str = "iid"          # "iid", or a structured score pattern laid over the draws (apply_recipe)
     page_size: int = 0           # > 0: k and v are handed over as a paged cache of such pages in a seeded random order
     packed_lens: tuple = ()      # a packed batch: sequences of these lengths back to back in one [H, sum, D] tensor (B = their number, N = the longest)
+    seq_lens: tuple = ()         # a decode batch whose sequences hold this many cached tokens each (B = their number, N = the longest)
 
     @property
     def scale(self) -> float:
@@ -90,6 +91,12 @@ WORKLOADS = {
     # the serving engine's cache layout (Sec. 4.1.1: vLLM, whose default page holds 16 tokens)
     "decode16k_b16_paged": Workload("decode16k_b16_paged", 16, 32, 8, 16384, 128, 16384, 4, _SEED0 + 7, n_query=1,
                                     page_size=16),
+    # continuous batching (Sec. 4.1.1: served with vLLM, batch size 64): one long sequence among
+    # short ones, and a mix of lengths from 256 to 32k tokens
+    "decode_skewed_b16": Workload("decode_skewed_b16", 16, 32, 8, 131072, 128, 131072, 4, _SEED0 + 8, n_query=1,
+                                  seq_lens=(131072,) + (1024,) * 15),
+    "decode_mixed_b32": Workload("decode_mixed_b32", 32, 32, 8, 32768, 128, 32768, 4, _SEED0 + 9, n_query=1,
+                                 seq_lens=(32768, 16384, 8192, 4096, 2048, 1024, 512, 256) * 4),
     "decode128k_full_paged": Workload("decode128k_full_paged", 1, 32, 8, 131072, 128, 131072, 4, _SEED0 + 6, n_query=1,
                                       page_size=16),
     "mid_paged": Workload("mid_paged", 1, 32, 8, 16384, 128, 2048, 4, _SEED0 + 2, chunk=True, n_query=16384, page_size=16),
@@ -190,6 +197,10 @@ def make_workload(w: Workload):
     """q, k, v (uint16 bf16 bits) for a named workload."""
     if w.packed_lens:  # one [1, H, sum of the lengths, D] tensor each; the sequence boundaries are the caller's offsets
         return make_qkv(1, w.Hq, w.Hkv, sum(w.packed_lens), w.D, w.seed, w.k_mult, fmt=w.fmt)
+    if w.seq_lens:  # q [B, Hq, n_query, D]; k, v [1, Hkv, sum of the lengths, D], the sequences' tokens back to back
+        q, _, _ = make_qkv(w.B, w.Hq, 1, 1, w.D, w.seed, n_query=w.n_query, fmt=w.fmt)
+        _, k, v = make_qkv(1, 1, w.Hkv, sum(w.seq_lens), w.D, w.seed + 1, w.k_mult, n_query=1, fmt=w.fmt)
+        return q, k, v
     q, k, v = make_qkv(w.B, w.Hq, w.Hkv, w.N, w.D, w.seed, w.k_mult, n_query=w.n_query, fmt=w.fmt)
     apply_recipe(w, q, k)
     return q, k, v

@@ -364,3 +364,29 @@ def test_batches_around_the_limits_of_the_device_side_split_plan(B):
         worst = [max(a, c) for a, c in zip(worst, errors(out[b:b + 1], lse[b:b + 1], ro, rl))]
     print(f"[parity] B{B} ragged: O max-abs {worst[0]:.3e} mean-abs(max) {worst[1]:.3e} LSE {worst[2]:.3e}", flush=True)
     assert worst[0] <= 2e-2 and worst[1] <= 2e-3 and worst[2] <= 1e-3
+
+
+@pytest.mark.parametrize("name", ["decode_skewed_b16", "decode_mixed_b32"])
+def test_decode_workloads_with_sequence_lengths_full_size(name):
+    # the benchmark's batches of sequences of very different lengths, launched as it launches them
+    # (a [B, Hkv, longest, D] buffer filled up to each length, the rest left as allocated)
+    w = WORKLOADS[name]
+    print(f"[gen] {name} ...", flush=True)
+    q, k, v = make_workload(w)   # k, v: the sequences' tokens back to back
+    kd, vd = to_device(k), to_device(v)
+    kbuf = torch.empty((w.B, w.Hkv, w.N, w.D), dtype=torch.bfloat16, device="cuda")
+    vbuf = torch.empty_like(kbuf)
+    t = 0
+    for b, n in enumerate(w.seq_lens):
+        kbuf[b, :, :n], vbuf[b, :, :n] = kd[0, :, t:t + n], vd[0, :, t:t + n]
+        t += n
+    print(f"[gpu] {name}", flush=True)
+    out, lse = binding.swaa_attn_decode_ex(to_device(q), kbuf, vbuf, w.window, w.n_sink, w.scale,
+                                           seq_lens=torch.tensor(w.seq_lens, dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    print(f"[oracle] {name}", flush=True)
+    t = 0
+    for b, n in enumerate(w.seq_lens):
+        ro, rl = swaa_decode_oracle(q[b:b + 1], k[:, :, t:t + n], v[:, :, t:t + n], w.window, w.n_sink, w.scale)
+        assert_parity(out[b:b + 1], lse[b:b + 1], ro, rl, tag=f"{name} seq {b} ({n} tokens)")
+        t += n
