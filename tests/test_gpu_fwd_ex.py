@@ -228,3 +228,32 @@ def test_packed_batch_of_many_sequences_of_very_different_lengths(D):
         ro, rl = swaa_decode_oracle(qs, ks, vs, W, S, 1 / math.sqrt(D))
         assert_parity(out[:, cu_q[b]:cu_q[b + 1]].unsqueeze(0), lse[:, cu_q[b]:cu_q[b + 1]].unsqueeze(0), ro, rl,
                       tag=f"packed, 150 sequences, seq {b}: Nq{lens_q[b]} Nk{lens_k[b]} D{D}")
+
+
+@pytest.mark.parametrize("D", [128, 64])
+def test_packed_batch_with_empty_sequences(D):
+    # sequences without tokens, and sequences with cached keys but no new rows, between the others:
+    # they take no work items and leave the neighbours' rows alone (both work lists)
+    Hq, Hkv, W, S = 8, 2, 50, 4
+    lens_k = [0, 5, 0, 0, 130, 40, 0, 257, 0]
+    lens_q = [0, 5, 0, 0, 130, 0, 0, 100, 0]
+    rng = np.random.Generator(np.random.Philox(8900 + D))
+    cu_q = np.concatenate([[0], np.cumsum(lens_q)]).astype(np.int32)
+    cu_k = np.concatenate([[0], np.cumsum(lens_k)]).astype(np.int32)
+    seqs = [make_qkv(1, Hq, Hkv, max(nk, 1), D, int(rng.integers(1 << 30)), n_query=max(nq, 1)) for nq, nk in zip(lens_q, lens_k)]
+    q_pack = torch.cat([to_device(s[0])[0, :, :nq] for s, nq in zip(seqs, lens_q)], dim=1).contiguous()   # [Hq, Tq, D]
+    k_pack = torch.cat([to_device(s[1])[0, :, :nk] for s, nk in zip(seqs, lens_k)], dim=1).contiguous()
+    v_pack = torch.cat([to_device(s[2])[0, :, :nk] for s, nk in zip(seqs, lens_k)], dim=1).contiguous()
+    args = dict(cu_seqlens_q=torch.from_numpy(cu_q).cuda(), cu_seqlens_k=torch.from_numpy(cu_k).cuda(),
+                max_seqlen_q=max(lens_q), max_seqlen_k=max(lens_k))
+    for total in (None, 0):
+        out = torch.full_like(q_pack, 7.0)
+        lse = torch.full((Hq, q_pack.shape[1]), 7.0, dtype=torch.float32, device="cuda")
+        binding.swaa_attn_fwd_ex(q_pack, k_pack, v_pack, W, S, None, out=out, lse=lse, total_rows_q=total, **args)
+        torch.cuda.synchronize()
+        for b, (qs, ks, vs) in enumerate(seqs):
+            if lens_q[b] == 0:
+                continue
+            ro, rl = swaa_decode_oracle(qs, ks, vs, W, S, 1 / math.sqrt(D))
+            assert_parity(out[:, cu_q[b]:cu_q[b + 1]].unsqueeze(0), lse[:, cu_q[b]:cu_q[b + 1]].unsqueeze(0), ro, rl,
+                          tag=f"packed with empty sequences (rows stated: {total}), seq {b}")
