@@ -171,6 +171,11 @@ typedef struct swaa_fwd_args {
      * different lengths run many times faster.  Rows beyond a total stated too small are not
      * computed.  Ignored for fixed-length batches. */
     long long total_rows_q;
+    /* Per-sequence prompt lengths: device, B ints, or NULL.  With it sequence b takes
+     * n_prompts[b] (negative values count as 0) in place of n_prompt: in a batch of a
+     * serving engine every sequence has a prompt of its own (paper Sec. 3.1.1, FA Decode:
+     * the window applies to prompt tokens only). */
+    const int *n_prompts;
 } swaa_fwd_args;
 
 int swaa_attn_fwd_ex(const swaa_fwd_args *args);

@@ -49,7 +49,7 @@ class SwaaFwdArgs(ctypes.Structure):
                 ("window", ctypes.c_int), ("n_sink", ctypes.c_int), ("n_prompt", ctypes.c_int),
                 ("scale", ctypes.c_float), ("stream", ctypes.c_void_p), ("dtype", ctypes.c_int),
                 ("block_table", ctypes.c_void_p), ("block_table_stride", ctypes.c_int), ("page_size", ctypes.c_int),
-                ("num_pages", ctypes.c_int), ("total_rows_q", ctypes.c_longlong)]
+                ("num_pages", ctypes.c_int), ("total_rows_q", ctypes.c_longlong), ("n_prompts", ctypes.c_void_p)]
 
 
 class SwaaDecodeArgs(ctypes.Structure):
@@ -325,7 +325,7 @@ def swaa_attn_fwd_ex_raw(args: SwaaFwdArgs) -> int:
 def swaa_attn_fwd_ex(q, k, v, window: int, n_sink: int, n_prompt: int | None = None, scale: float | None = None,
                      cu_seqlens_q=None, cu_seqlens_k=None, max_seqlen_q: int | None = None,
                      max_seqlen_k: int | None = None, out=None, lse=None, stream=None, block_table=None,
-                     total_rows_q: int | None = None):
+                     total_rows_q: int | None = None, n_prompts=None):
     """General forward: strided tensors, Nq <= Nk (the query rows are the newest Nq of Nk
     tokens), packed variable-length batches.
 
@@ -337,7 +337,8 @@ def swaa_attn_fwd_ex(q, k, v, window: int, n_sink: int, n_prompt: int | None = N
     GPU, k, v views [num_pages, Hkv, page_size, D], max_seqlen_k the (largest) number of cached tokens;
     with cu_seqlens the key offsets only give the cache lengths.  total_rows_q (packed batches): the
     rows of the packed q tensor, taken from q by default; 0 makes the launch as large as B times the
-    longest sequence (slow for sequences of very different lengths).  bfloat16 or float16 tensors (all of
+    longest sequence (slow for sequences of very different lengths).  n_prompts: int32 [B] GPU tensor of
+    per-sequence prompt lengths, used in place of n_prompt.  bfloat16 or float16 tensors (all of
     one type).  out defaults to a new tensor with q's shape in q's memory order;
     lse is fp32 [B, Hq, Nq] ([Hq, Tq] when packed).  Returns (out, lse).
     """
@@ -412,6 +413,11 @@ def swaa_attn_fwd_ex(q, k, v, window: int, n_sink: int, n_prompt: int | None = N
         a.page_size = k.shape[2] if paged else 0
         a.num_pages = k.shape[0] if paged else 0
         a.total_rows_q = (q.shape[1] if packed else 0) if total_rows_q is None else int(total_rows_q)
+        if n_prompts is not None:
+            if n_prompts.dtype != torch.int32 or not n_prompts.is_cuda or not n_prompts.is_contiguous() \
+                    or n_prompts.shape != (B,):
+                raise ValueError("n_prompts must be a contiguous int32 [B] GPU tensor")
+            a.n_prompts = n_prompts.data_ptr()
         rc = swaa_attn_fwd_ex_raw(a)
     if rc != SWAA_OK:
         raise SwaaError(rc, swaa_status_string(rc))

@@ -101,8 +101,9 @@ int swaa_attn_fwd_ex(const swaa_fwd_args *a) {
     if (a->lse_stride_h < 0 || a->lse_stride_b < 0) return SWAA_ERR_SHAPE;
     if (packed && ((reinterpret_cast<uintptr_t>(a->cu_seqlens_q) | reinterpret_cast<uintptr_t>(a->cu_seqlens_k)) & 3u))
         return SWAA_ERR_ALIGN;
+    if (reinterpret_cast<uintptr_t>(a->n_prompts) & 3u) return SWAA_ERR_ALIGN;
 
-    FwdParams p;
+    FwdParams p{};
     p.q = static_cast<const __bf16 *>(a->q.ptr);
     p.k = static_cast<const __bf16 *>(a->k.ptr);
     p.v = static_cast<const __bf16 *>(a->v.ptr);
@@ -116,6 +117,7 @@ int swaa_attn_fwd_ex(const swaa_fwd_args *a) {
     p.fp16 = a->dtype == SWAA_F16 ? 1 : 0;
     p.cu_q = a->cu_seqlens_q;
     p.cu_k = a->cu_seqlens_k;
+    p.n_prompts = a->n_prompts;
     p.block_table = a->block_table;
     p.bt_stride = paged ? a->block_table_stride : 0;
     p.page_size = paged ? a->page_size : 1;

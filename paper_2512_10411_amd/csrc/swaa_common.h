@@ -60,6 +60,8 @@ struct FwdParams {
     // axis (sequence b owns rows [cu[b], cu[b+1])), batch strides unused; or null
     const int *cu_q;
     const int *cu_k;
+    // per-sequence prompt lengths (device, B ints) in place of P below, or null
+    const int *n_prompts;
     // paged key/value cache (pipelined kernel only), or block_table null: token j of sequence b
     // lives in page block_table[b * bt_stride + j / page_size], row j % page_size; k, v then point
     // at page 0 and k_sb, v_sb are the page strides.  page_size is a multiple of 16.
@@ -94,6 +96,7 @@ struct FwdParams {
 // tokens (row r sits at position nk - nq + r; nq = nk for a plain prefill).
 struct SeqGeom {
     int nq, nk;
+    int n_prompt;  // rows at positions >= n_prompt are generated tokens
     long long q_row0, k_row0;  // first row along the row axis of q / out / lse and of k / v
     long long q_batch, k_batch;  // batch index to multiply the batch strides with
 };
@@ -121,6 +124,7 @@ __device__ __forceinline__ bool seq_geom(const FwdParams &p, int b, SeqGeom &g) 
         g.nk = p.Nk;
         g.k_batch = b;
     }
+    g.n_prompt = p.n_prompts ? max(p.n_prompts[b], 0) : p.P;
     g.nq = min(min(g.nq, p.Nq), g.nk);  // never more rows than the plan covers, nor than tokens
     g.nk = min(g.nk, p.Nk);
     return g.nq > 0;

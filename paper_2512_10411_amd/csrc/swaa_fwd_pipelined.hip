@@ -268,7 +268,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     const int p0 = pos_off + r0;                   // first position of this wave
     const int qpos = p0 + l32;                     // this lane's query column
     // this lane's window: a generated token (position >= P) sees its whole prefix
-    const int W = (qpos >= p.P) ? Nk : p.W;
+    const int W = (qpos >= sg.n_prompt) ? Nk : p.W;
 
     const __bf16 *qg = p.q + sg.q_batch * p.q_sb + (long long)head * p.q_sh + sg.q_row0 * p.q_sn;
 
@@ -290,7 +290,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     // to its diagonal.  Two consecutive visited halves make one 64-key tile of the rings (a
     // tile need not be 64 consecutive keys: the last sink half and the first band half share
     // one); an odd count is padded with a half past the last row, which no row can see.
-    const int band_lo = (wg_p1 >= p.P) ? 0 : max(0, wg_p0 - p.W + 1);
+    const int band_lo = (wg_p1 >= sg.n_prompt) ? 0 : max(0, wg_p0 - p.W + 1);
     const int hb_lo = band_lo >> 5, hb_hi = wg_p1 >> 5;
     const int n_sink_h = min((min(S, band_lo) + 31) >> 5, hb_lo);
     const int n_halves = n_sink_h + (hb_hi - hb_lo + 1);
@@ -431,7 +431,7 @@ __global__ __launch_bounds__(kPThreads, 2) void swaa_fwd_pipelined_kernel(const 
     // A wave needs no mask on a 32-key half when all its keys are visible to all
     // its 32 rows: at or below the first row's diagonal, and inside the window of
     // its last prompt row (if it has one) or all sinks.
-    const int wbound = window_bound(p0, kPRows, p.W, p.P);
+    const int wbound = window_bound(p0, kPRows, p.W, sg.n_prompt);
     auto half_masked = [&](int k0h) __attribute__((always_inline)) { return !((k0h + 31 <= p0) && ((k0h > wbound) || (k0h + 31 < S))); };
 
     // (Worked out here, while the first copies travel.)

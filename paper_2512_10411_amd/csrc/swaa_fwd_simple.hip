@@ -94,7 +94,7 @@ __global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p
     const int rows_per_wg = kWgRows / hpb;
     const int wg_r0 = pt * rows_per_wg;  // first query row of the workgroup
     if (wg_r0 >= sg.nq) return;          // a shorter sequence of a packed batch
-    const int Nq = sg.nq, Nk = sg.nk, W = p.W, S = p.S, P = p.P;
+    const int Nq = sg.nq, Nk = sg.nk, W = p.W, S = p.S, P = sg.n_prompt;
     const int pos_off = Nk - Nq;  // query row r sits at position pos_off + r
 
     const int tid = threadIdx.x;

@@ -159,6 +159,7 @@ def test_general_forward_argument_errors():
     assert call(**{"q.stride_b": 0}) == binding.SWAA_ERR_SHAPE    # two batch entries on one address
     assert call(cu_seqlens_q=p) == binding.SWAA_ERR_NULL          # one offset array without the other
     assert call(cu_seqlens_q=p, cu_seqlens_k=p + 2) == binding.SWAA_ERR_ALIGN
+    assert call(n_prompts=p + 2) == binding.SWAA_ERR_ALIGN
     assert call(D=80) == binding.SWAA_ERR_UNSUPPORTED
     assert call(dtype=7) == binding.SWAA_ERR_UNSUPPORTED
     assert call(**{"k.ptr": p + 8}) == binding.SWAA_ERR_ALIGN

@@ -107,3 +107,43 @@ def test_fa_decode_workloads_full_size_sampled_rows(name):
     print(f"[oracle] {name}: {len(rows)} rows x {w.B * w.Hq} heads", flush=True)
     ro, rl = swaa_attn_oracle(q, k, v, w.window, w.n_sink, w.scale, rows=rows, n_prompt=P)
     assert_parity(out, lse, ro, rl, rows=rows, tag=name)
+
+
+@pytest.mark.parametrize("D", [128, 64])
+def test_prompt_lengths_of_their_own_per_sequence(D):
+    # a batch as a serving engine sees it: every sequence has its own prompt length (FA Decode,
+    # Sec. 3.1.1); fixed-length and packed calls, prompt lengths of 0, inside a row tile, and beyond
+    # the sequence
+    import math
+    from oracle import swaa_decode_oracle
+    Hq, Hkv, W, S = 8, 2, 64, 4
+    # fixed-length batch
+    B, N = 5, 700
+    prompts = [0, 100, 333, 699, 5000]
+    q, k, v = make_qkv(B, Hq, Hkv, N, D, seed=9700 + D)
+    out, lse = binding.swaa_attn_fwd_ex(to_device(q), to_device(k), to_device(v), W, S, 17,   # (n_prompt itself is ignored)
+                                        n_prompts=torch.tensor(prompts, dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    for b in range(B):
+        ro, rl = swaa_decode_oracle(q[b:b + 1], k[b:b + 1], v[b:b + 1], W, S, 1 / math.sqrt(D), n_prompt=prompts[b])
+        assert_parity(out[b:b + 1], lse[b:b + 1], ro, rl, tag=f"per-sequence prompt length {prompts[b]} of {N} D{D}")
+    # packed chunks: sequence b brings its newest nq[b] rows against nk[b] cached tokens
+    nk = [300, 64, 1000, 130]
+    nq = [300, 10, 400, 130]
+    prompts = [250, 60, 650, 0]
+    seqs = [make_qkv(1, Hq, Hkv, nk[i], D, 9750 + D + i, n_query=nq[i]) for i in range(len(nk))]
+    q_pack = torch.cat([to_device(s[0])[0] for s in seqs], dim=1).contiguous()
+    k_pack = torch.cat([to_device(s[1])[0] for s in seqs], dim=1).contiguous()
+    v_pack = torch.cat([to_device(s[2])[0] for s in seqs], dim=1).contiguous()
+    cu_q = torch.tensor(np.concatenate([[0], np.cumsum(nq)]), dtype=torch.int32, device="cuda")
+    cu_k = torch.tensor(np.concatenate([[0], np.cumsum(nk)]), dtype=torch.int32, device="cuda")
+    out, lse = binding.swaa_attn_fwd_ex(q_pack, k_pack, v_pack, W, S, None, cu_seqlens_q=cu_q, cu_seqlens_k=cu_k,
+                                        max_seqlen_q=max(nq), max_seqlen_k=max(nk),
+                                        n_prompts=torch.tensor(prompts, dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    r0 = 0
+    for b, (qs, ks, vs) in enumerate(seqs):
+        ro, rl = swaa_decode_oracle(qs, ks, vs, W, S, 1 / math.sqrt(D), n_prompt=prompts[b])
+        assert_parity(out[None, :, r0:r0 + nq[b]], lse[None, :, r0:r0 + nq[b]], ro, rl,
+                      tag=f"packed, per-sequence prompt length {prompts[b]} of {nk[b]} D{D}")
+        r0 += nq[b]
