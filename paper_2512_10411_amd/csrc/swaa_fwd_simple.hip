@@ -10,12 +10,14 @@
 // 32 up to 256 except 128, which has the software-pipelined kernel of its own.
 //
 // Shape of the kernel
-//   * One workgroup = 4 wavefronts = 256 "query rows" that share one KV head:
-//     hpb query heads (4, 2 or 1) x 256/hpb consecutive positions.  Each wave
-//     owns 64 positions of one head, so K/V tiles staged in LDS are reused by
+//   * One workgroup = 4 wavefronts = 128 "query rows" that share one KV head:
+//     hpb query heads (4, 2 or 1) x 128/hpb consecutive positions.  Each wave
+//     owns 32 positions of one head, so K/V tiles staged in LDS are reused by
 //     every query head of the GQA group and the dense band per wave is only
-//     W + 64 keys wide.  (Head dimensions above 128: 32 positions per wave, 128
-//     rows per workgroup, so that O^T and Q still fit the register file.)
+//     W + 32 keys wide.  Head dimensions up to 96 leave registers for three or
+//     four such workgroups per CU; above 128, O^T and Q of 32 positions fill the
+//     register file and one workgroup runs per CU.  (The kernel can also give a
+//     wave 64 positions, 256 rows per workgroup: no instantiation uses it now.)
 //   * KV tiles of 64 keys.  A workgroup visits only the tiles that hold sink
 //     keys [0, S) or band keys (first position - W, last position]; a wave
 //     skips the MFMA work of tiles that lie outside its own 64 positions' band
@@ -70,9 +72,15 @@ struct Elem<_Float16> {
     }
 };
 
-// QB: 32-row blocks of query positions per wave (2, or 1 for head dimensions above 128)
+// QB: 32-row blocks of query positions per wave (1 in every instantiation; 2 is possible up to D = 128)
+// Head dimensions up to kSmallD run 32 positions per wave and several workgroups per CU (the
+// registers allow it), so that one wave's softmax runs under another's matrix instructions:
+// measured against 64 positions per wave and one workgroup per CU, D = 64 is 1.25 - 1.37 x as
+// fast, D = 96 1.15 - 1.24 x.
+constexpr int kSmallD = 96;
+constexpr int min_blocks(int D) { return D <= 64 ? 4 : D <= kSmallD ? 3 : 1; }
 template <int D, typename E, int QB>
-__global__ __launch_bounds__(kThreads, 1) void swaa_fwd_kernel(const FwdParams p) {
+__global__ __launch_bounds__(kThreads, min_blocks(D)) void swaa_fwd_kernel(const FwdParams p) {
     using T = Tile<D>;
     using X = Elem<E>;
     using x8 = typename X::x8;
@@ -344,7 +352,7 @@ namespace {
 
 template <int D, typename E>
 hipError_t launch_one(const FwdParams &p, hipStream_t stream) {
-    constexpr int QB = D > 128 ? 1 : 2;
+    constexpr int QB = 1;
     using T = Tile<D>;
     constexpr int kBytes = (T::kKElems + T::kVElems) * 2;
     if (p.wg_rows != 4 * 32 * QB) return hipErrorInvalidValue;  // the plan must be the one for this instantiation
@@ -366,7 +374,7 @@ hipError_t launch_format(const FwdParams &p, hipStream_t stream) {
 
 }  // namespace
 
-int fwd_simple_wg_rows(int D) { return D > 128 ? 128 : 256; }
+int fwd_simple_wg_rows(int) { return 128; }
 
 hipError_t launch_fwd_simple(const FwdParams &p, int D, hipStream_t stream) {
     switch (D) {
