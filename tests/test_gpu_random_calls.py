@@ -120,3 +120,127 @@ def test_random_backward_calls(seed):
     assert_grad("dq", dq, rq, tag)
     assert_grad("dk", dk, rk, tag)
     assert_grad("dv", dv, rv, tag)
+
+
+def _paged(host_kv, lens, ps, Hkv, D, dt, rng):
+    """The sequences' keys and values as a paged cache (pages in random order, unused slots hold
+    noise, unused table entries point outside the cache); returns (k_cache, v_cache, block_table)."""
+    pages_of = [-(-n // ps) for n in lens]
+    order = rng.permutation(sum(pages_of) + 2)
+    kc = torch.randn((len(order), ps, Hkv, D), device="cuda").to(dt)
+    vc = torch.randn((len(order), ps, Hkv, D), device="cuda").to(dt)
+    table = np.full((len(lens), max(pages_of) + 1), 10**6, dtype=np.int32)
+    nxt = 0
+    for b, (kb, vb) in enumerate(host_kv):
+        for pg in range(pages_of[b]):
+            page = int(order[nxt]); nxt += 1
+            table[b, pg] = page
+            t0, t1 = pg * ps, min(lens[b], (pg + 1) * ps)
+            kc[page, :t1 - t0] = kb[:, t0:t1].permute(1, 0, 2)
+            vc[page, :t1 - t0] = vb[:, t0:t1].permute(1, 0, 2)
+    return kc.permute(0, 2, 1, 3), vc.permute(0, 2, 1, 3), torch.from_numpy(table).cuda()
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_decode_batches_with_sequence_lengths(seed):
+    # batches of up to 130 sequences with uniform, one-long-among-short and heavy-tailed lengths,
+    # contiguous and paged, both formats; three calls must give the same bits (the split plan is
+    # worked out on the device by every workgroup)
+    from oracle import input_format
+    from gpu_util import errors
+    rng = np.random.Generator(np.random.Philox(61000 + seed))
+    Hkv, G = int(rng.integers(1, 3)), int(rng.choice([1, 2, 4, 5, 8]))
+    B, Nq = int(rng.choice([2, 3, 7, 16, 64, 65, 130])), int(rng.choice([1, 1, 1, 2, 5, 9, 17]))
+    kind = seed % 3
+    if kind == 0:
+        lens = [int(x) for x in rng.integers(Nq, 400, size=B)]
+    elif kind == 1:
+        lens = [int(x) for x in rng.integers(Nq, 60, size=B)]
+        lens[int(rng.integers(0, B))] = int(rng.integers(2000, 9000))
+    else:
+        lens = [int(min(6000, Nq + rng.pareto(1.0) * 50)) for _ in range(B)]
+    W, S = int(rng.choice([1, 33, 100, 1000, 10**9, 10**9])), int(rng.choice([0, 4, 64, 100]))
+    fmt = "fp16" if rng.integers(0, 4) == 0 else "bf16"
+    dt = torch.float16 if fmt == "fp16" else torch.bfloat16
+    paged, ps = bool(rng.integers(0, 2)), int(rng.choice([4, 16, 32, 48]))
+    print(f"[case] seed {seed}: B{B} G{G} Hkv{Hkv} Nq{Nq} lengths {min(lens)}..{max(lens)} W{W} S{S} {fmt} paged {paged} ({ps})", flush=True)
+    host = [make_qkv(1, Hkv * G, Hkv, n, 128, 62000 + 1000 * seed + i, n_query=Nq, fmt=fmt) for i, n in enumerate(lens)]
+    q = torch.cat([to_device(h[0], fmt) for h in host], dim=0)
+    dev_kv = [(to_device(h[1], fmt)[0], to_device(h[2], fmt)[0]) for h in host]
+    sl = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    if paged:
+        kc, vc, table = _paged(dev_kv, lens, ps, Hkv, 128, dt, rng)
+        call = lambda: binding.swaa_attn_decode_ex(q, kc, vc, W, S, seq_lens=sl, block_table=table, max_seqlen_k=max(lens))
+    else:
+        kbuf = torch.randn((B, Hkv, max(lens), 128), device="cuda").to(dt)
+        vbuf = torch.randn((B, Hkv, max(lens), 128), device="cuda").to(dt)
+        for b, (kb, vb) in enumerate(dev_kv):
+            kbuf[b, :, :lens[b]], vbuf[b, :, :lens[b]] = kb, vb
+        call = lambda: binding.swaa_attn_decode_ex(q, kbuf, vbuf, W, S, seq_lens=sl)
+    outs = [tuple(t.clone() for t in call()) for _ in range(3)]
+    torch.cuda.synchronize()
+    assert all(torch.equal(outs[0][0], o) and torch.equal(outs[0][1], l) for o, l in outs[1:])
+    worst = [0.0, 0.0, 0.0]
+    with input_format(fmt):
+        for b, h in enumerate(host):
+            ro, rl = swaa_decode_oracle(h[0], h[1], h[2], W, S, 1 / math.sqrt(128))
+            worst = [max(a, c) for a, c in zip(worst, errors(outs[0][0][b:b + 1], outs[0][1][b:b + 1], ro, rl))]
+    print(f"[parity] seed {seed}: O max-abs {worst[0]:.3e} mean-abs(max) {worst[1]:.3e} LSE {worst[2]:.3e}", flush=True)
+    assert worst[0] <= 2e-2 and worst[1] <= 2e-3 and worst[2] <= 1e-3
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_packed_batches(seed):
+    # packed prefill batches of up to 70 sequences with heavy-tailed lengths: plain prefills and
+    # chunks against longer caches, sequences without new rows, contiguous and paged caches,
+    # per-sequence prompt lengths, head dimensions 64 / 96 / 128; the compact work list (twice) and
+    # the plain one must give the same bits
+    from oracle import input_format
+    from gpu_util import errors
+    rng = np.random.Generator(np.random.Philox(71000 + seed))
+    D, Hkv, G = int(rng.choice([128, 128, 128, 64, 96])), int(rng.integers(1, 3)), int(rng.choice([1, 2, 4, 5, 8]))
+    B = int(rng.choice([1, 2, 5, 9, 64, 70]))
+    nk = [int(min(3000, 1 + rng.pareto(1.0) * 40)) for _ in range(B)]
+    if rng.integers(0, 2):
+        nk[int(rng.integers(0, B))] = int(rng.integers(500, 3000))
+    nq = [n if rng.integers(0, 2) else int(rng.integers(1, n + 1)) for n in nk]
+    for i in range(B):
+        if rng.integers(0, 8) == 0:
+            nq[i] = 0   # no new rows
+    if sum(nq) == 0:
+        nq[0] = nk[0]
+    W, S = int(rng.choice([1, 33, 100, 1000, 10**9])), int(rng.choice([0, 4, 64]))
+    prompts = [int(rng.integers(0, n + 2)) for n in nk] if rng.integers(0, 2) else None
+    fmt = "fp16" if rng.integers(0, 4) == 0 else "bf16"
+    dt = torch.float16 if fmt == "fp16" else torch.bfloat16
+    paged, ps = D == 128 and bool(rng.integers(0, 2)), int(rng.choice([16, 32, 48]))
+    print(f"[case] seed {seed}: D{D} B{B} G{G} Hkv{Hkv} rows {sum(nq)} caches {min(nk)}..{max(nk)} W{W} S{S} {fmt} "
+          f"paged {paged} ({ps}) prompts {prompts is not None}", flush=True)
+    host = [make_qkv(1, Hkv * G, Hkv, nk[i], D, 72000 + 1000 * seed + i, n_query=max(nq[i], 1), fmt=fmt) for i in range(B)]
+    q_pack = torch.cat([to_device(h[0], fmt)[0, :, :nq[i]] for i, h in enumerate(host)], dim=1).contiguous()
+    args = dict(cu_seqlens_q=torch.tensor(np.concatenate([[0], np.cumsum(nq)]), dtype=torch.int32, device="cuda"),
+                cu_seqlens_k=torch.tensor(np.concatenate([[0], np.cumsum(nk)]), dtype=torch.int32, device="cuda"),
+                max_seqlen_q=max(max(nq), 1), max_seqlen_k=max(nk))
+    if prompts is not None:
+        args["n_prompts"] = torch.tensor(prompts, dtype=torch.int32, device="cuda")
+    dev_kv = [(to_device(h[1], fmt)[0], to_device(h[2], fmt)[0]) for h in host]
+    if paged:
+        kk, vv, args["block_table"] = _paged(dev_kv, nk, ps, Hkv, D, dt, rng)
+    else:
+        kk = torch.cat([kv[0] for kv in dev_kv], dim=1).contiguous()
+        vv = torch.cat([kv[1] for kv in dev_kv], dim=1).contiguous()
+    outs = [tuple(t.clone() for t in binding.swaa_attn_fwd_ex(q_pack, kk, vv, W, S, None, total_rows_q=total, **args))
+            for total in (None, None, 0)]
+    torch.cuda.synchronize()
+    assert all(torch.equal(outs[0][0], o) and torch.equal(outs[0][1], l) for o, l in outs[1:])
+    worst, r0 = [0.0, 0.0, 0.0], 0
+    with input_format(fmt):
+        for b, h in enumerate(host):
+            if nq[b] == 0:
+                continue
+            ro, rl = swaa_decode_oracle(h[0], h[1], h[2], W, S, 1 / math.sqrt(D), n_prompt=None if prompts is None else prompts[b])
+            e = errors(outs[0][0][None, :, r0:r0 + nq[b]], outs[0][1][None, :, r0:r0 + nq[b]], ro, rl)
+            worst = [max(a, c) for a, c in zip(worst, e)]
+            r0 += nq[b]
+    print(f"[parity] seed {seed}: O max-abs {worst[0]:.3e} mean-abs(max) {worst[1]:.3e} LSE {worst[2]:.3e}", flush=True)
+    assert worst[0] <= 2e-2 and worst[1] <= 2e-3 and worst[2] <= 1e-3
