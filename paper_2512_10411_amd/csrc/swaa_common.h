@@ -78,7 +78,7 @@ struct FwdParams {
     // cut into n4 groups of 4 heads, at most one group of 2 heads and at most
     // one single head; a workgroup is wg_rows query rows (head x position) on one
     // KV head: 4 heads x wg_rows/4 positions, 2 x wg_rows/2 or 1 x wg_rows.
-    int wg_rows;  // 256 (plain forward and backward kernels) or 128 (pipelined forward)
+    int wg_rows;  // 128 (forward kernels) or 256 (backward kernels)
     int n4, has2, has1;
     int nt_h4, nt_h2, nt_h1;  // row tiles of a sequence of Nq rows for workgroups of 4, 2 and 1 heads
     FastDiv div_tiles_per_pair, div_hkv, div_nt_h4;  // for the work-list decode of every workgroup
