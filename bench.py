@@ -37,15 +37,15 @@ HBM_PEAK_GBS = 8000.0           # MI355X HBM3E
 # sum over them).  roofline.traffic is NOT a reading of this run: traffic_source names the
 # file (or "--traffic-bytes"); workloads without a summary report null.
 MEASURED_TRAFFIC_BYTES = {
-    "mid": (4.009e8, "profiles/swaa_fwd_pipelined_mid.txt"),
-    "batched": (1.018e9, "profiles/swaa_fwd_pipelined_batched.txt"),
+    "mid": (4.02e8, "profiles/swaa_fwd_pipelined_mid.txt"),
+    "batched": (1.015e9, "profiles/swaa_fwd_pipelined_batched.txt"),
     "pair32k_swa": (1.083e9, "profiles/swaa_fwd_pipelined_pair32k_swa.txt"),
-    "pair32k_full": (2.641e9, "profiles/swaa_fwd_pipelined_pair32k_full.txt"),
-    "long128k_swa": (6.846e9, "profiles/swaa_fwd_pipelined_long128k_swa.txt"),
-    "long128k_full": (2.493e11, "profiles/swaa_fwd_pipelined_long128k_full.txt"),
-    "decode128k_full": (5.41e8, "profiles/swaa_decode_decode128k_full.txt"),
+    "pair32k_full": (2.64e9, "profiles/swaa_fwd_pipelined_pair32k_full.txt"),
+    "long128k_swa": (6.807e9, "profiles/swaa_fwd_pipelined_long128k_swa.txt"),
+    "long128k_full": (2.669e11, "profiles/swaa_fwd_pipelined_long128k_full.txt"),
+    "decode128k_full": (5.411e8, "profiles/swaa_decode_decode128k_full.txt"),
     "decode16k_b16": (1.079e9, "profiles/swaa_decode_decode16k_b16.txt"),
-    "decode128k_swa": (3.67e7, "profiles/swaa_decode_decode128k_swa.txt"),
+    "decode128k_swa": (3.665e7, "profiles/swaa_decode_decode128k_swa.txt"),
     "decode_skewed_b16": (6.081e8, "profiles/swaa_decode_decode_skewed_b16.txt"),
     "decode_mixed_b32": (1.078e9, "profiles/swaa_decode_decode_mixed_b32.txt"),
     "mid_bwd": (1.63e9, "profiles/swaa_bwd_mid_bwd.txt"),
