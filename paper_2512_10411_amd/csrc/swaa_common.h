@@ -186,7 +186,7 @@ __device__ __forceinline__ bool decode_work_packed(const FwdParams &p, WorkItem 
         const unsigned in_round = wave_read_lane(incl, 63);
         if (slot - before < in_round) {
             const unsigned rel = slot - before;
-            const int n = __popcll(__ballot(incl <= rel));  // sequences of this round that end at or before the slot
+            const int n = __popcll(__ballot(incl <= rel));  // sequences among these 64 that end at or before the slot
             const unsigned base = n ? wave_read_lane(incl, n - 1) : 0u;
             // (everything below is the same in all lanes, and read from one lane so that the
             // compiler knows it and keeps addresses built from it in scalar registers)

@@ -98,7 +98,7 @@ __device__ __forceinline__ bool ragged_find(const RaggedHalves &h, unsigned hps,
         const unsigned in_round = wave_read_lane(incl, 63);
         if (unit - before < in_round) {
             const unsigned rel = unit - before;
-            const int n = __popcll(__ballot(incl <= rel));  // sequences of this round that end at or before the unit
+            const int n = __popcll(__ballot(incl <= rel));  // sequences among these 64 that end at or before the unit
             const unsigned base = n ? wave_read_lane(incl, n - 1) : 0u;
             // (the same in all lanes; read through the first lane so that the compiler knows it
             // and keeps the addresses built from them in scalar registers)
