@@ -466,29 +466,50 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
     }
 }
 
-// One workgroup per output row: out = sum_s 2^(mc_s - m) O_s / sum_s 2^(mc_s - m) l_s
-// with m = max_s mc_s; lse = (m + log2 of the denominator) ln 2.
-__global__ __launch_bounds__(kMergeThreads) void swaa_decode_merge_kernel(const DecodeParams p) {
-    __shared__ float red[kMergeThreads];
-    __shared__ float lsum[kMergeThreads / kD];
-    const int tid = threadIdx.x;
-    const int row = blockIdx.x;  // (b, hq, r)
-    const int r = row % p.Nq;
-    const int hq = (row / p.Nq) % p.Hq;
-    const int b = row / (p.Nq * p.Hq);
+// ---- merging the splits: out = sum_s 2^(mc_s - m) O_s / sum_s 2^(mc_s - m) l_s with m = max_s mc_s;
+// lse = (m + log2 of the denominator) ln 2 ----
+// One output row (b, hq, r) and where its partial results are: n_splits items, `step` workspace
+// slots apart (times the column tiles), the first at slot0.
+struct MergeRow {
+    long long row;
+    int ct, col;
+    int n_splits;
+    long long slot0, step;
+};
+__device__ __forceinline__ MergeRow merge_row(const DecodeParams &p, long long row) {
+    MergeRow m;
+    m.row = row;
+    const int r = (int)(row % p.Nq);
+    const int hq = (int)((row / p.Nq) % p.Hq);
+    const int b = (int)(row / ((long long)p.Nq * p.Hq));
     const int kvh = hq / p.G;
     const int c = (hq % p.G) * p.Nq + r;
-    const int ct = c / 32, col = c % 32;
-    // the splits of this row's (batch, KV head) pair and the workspace slot of the first one
-    int n_splits = p.n_splits;
-    long long slot0 = ((long long)b * p.Hkv + kvh) * p.n_splits;
-    long long slot_step = 1;
+    m.ct = c / 32;
+    m.col = c % 32;
     if (p.ragged) {  // (the device-side plan: the sequence's first split workgroup has left it here)
-        n_splits = p.ws_units[2 * b + 1];
-        slot0 = (long long)p.ws_units[2 * b] * p.Hkv + kvh;
-        slot_step = p.Hkv;
+        m.n_splits = p.ws_units[2 * b + 1];
+        m.slot0 = (long long)p.ws_units[2 * b] * p.Hkv + kvh;
+        m.step = p.Hkv;
+    } else {
+        m.n_splits = p.n_splits;
+        m.slot0 = ((long long)b * p.Hkv + kvh) * p.n_splits;
+        m.step = 1;
     }
-    auto item_of = [&](int s) { return (slot0 + s * slot_step) * p.n_coltiles + ct; };
+    return m;
+}
+__device__ __forceinline__ void merge_store(const DecodeParams &p, long long row, int d, float o, float l, float m) {
+    if (p.fp16)
+        reinterpret_cast<_Float16 *>(p.out)[(size_t)row * kD + d] = (_Float16)(o / l);
+    else
+        p.out[(size_t)row * kD + d] = (__bf16)(o / l);
+    if (d == 0) p.lse[row] = (m + __builtin_amdgcn_logf(l)) * 0.69314718055994530942f;
+}
+
+// A whole workgroup of kMergeThreads on one row (many splits): red and lsum are its LDS.
+__device__ __forceinline__ void merge_row_by_workgroup(const DecodeParams &p, const MergeRow &mr, float *red, float *lsum) {
+    const int tid = threadIdx.x;
+    const int n_splits = mr.n_splits, col = mr.col;
+    auto item_of = [&](int s) { return (mr.slot0 + s * mr.step) * p.n_coltiles + mr.ct; };
 
     // largest reference over the splits: wave maxima by lane exchange, then one LDS round
     float m = -INFINITY;
@@ -537,42 +558,25 @@ __global__ __launch_bounds__(kMergeThreads) void swaa_decode_merge_kernel(const 
             o += red[gg * kD + d];
             lt += lsum[gg];
         }
-        if (p.fp16)
-            reinterpret_cast<_Float16 *>(p.out)[(size_t)row * kD + d] = (_Float16)(o / lt);
-        else
-            p.out[(size_t)row * kD + d] = (__bf16)(o / lt);
-        if (d == 0) p.lse[row] = (m + __builtin_amdgcn_logf(lt)) * 0.69314718055994530942f;
+        merge_store(p, mr.row, d, o, lt, m);
     }
 }
 
-// The same for plans with few splits per pair (at most kMergeRowSplits; sequences of one length):
-// a workgroup takes kMergeThreads / 128 output rows, 128 threads each (one per head dimension
-// element), and every thread adds up its row's splits by itself -- no exchange between threads.
-// A batch of many sequences has thousands of rows of two or three splits each; one workgroup of
-// 1024 threads per row spent most of the merge waiting for workgroup slots (64 sequences x 8
-// new tokens: the call took 275 us, 70 of them here).
+// 128 threads (one per head dimension element) on one row of at most kMergeRowSplits splits: every
+// thread adds up the row's splits by itself -- no exchange between threads.
 constexpr int kMergeRowSplits = 8;
-__global__ __launch_bounds__(kMergeThreads) void swaa_decode_merge_rows_kernel(const DecodeParams p) {
-    const int d = threadIdx.x % kD;
-    const long long row = (long long)blockIdx.x * (kMergeThreads / kD) + threadIdx.x / kD;  // (b, hq, r)
-    if (row >= (long long)p.B * p.Hq * p.Nq) return;
-    const int r = (int)(row % p.Nq);
-    const int hq = (int)((row / p.Nq) % p.Hq);
-    const int b = (int)(row / ((long long)p.Nq * p.Hq));
-    const int kvh = hq / p.G;
-    const int c = (hq % p.G) * p.Nq + r;
-    const int ct = c / 32, col = c % 32;
-    const long long item0 = (((long long)b * p.Hkv + kvh) * p.n_splits) * p.n_coltiles + ct;
+__device__ __forceinline__ void merge_row_by_group(const DecodeParams &p, const MergeRow &mr, int d) {
+    const long long item0 = mr.slot0 * p.n_coltiles + mr.ct, item_step = mr.step * p.n_coltiles;
     float mcs[kMergeRowSplits], ls[kMergeRowSplits], os[kMergeRowSplits];
     // (a split that saw no visible key has reference -inf and may not have written its O: loaded all
-    // the same and left out by selection; splits beyond the plan's repeat split 0 and count as empty)
+    // the same and left out by selection; splits beyond the row's repeat split 0 and count as empty)
 #pragma unroll
     for (int s = 0; s < kMergeRowSplits; ++s) {
-        const bool there = s < p.n_splits;
-        const long long it = item0 + (long long)(there ? s : 0) * p.n_coltiles;
-        mcs[s] = p.ws_ml[it * 64 + col];
-        ls[s] = p.ws_ml[it * 64 + 32 + col];
-        os[s] = p.ws_o[(it * p.col_stride + col) * kD + d];
+        const bool there = s < mr.n_splits;
+        const long long it = item0 + (there ? s : 0) * item_step;
+        mcs[s] = p.ws_ml[it * 64 + mr.col];
+        ls[s] = p.ws_ml[it * 64 + 32 + mr.col];
+        os[s] = p.ws_o[(it * p.col_stride + mr.col) * kD + d];
         if (!there) mcs[s] = -INFINITY;
     }
     float m = mcs[0];
@@ -586,11 +590,59 @@ __global__ __launch_bounds__(kMergeThreads) void swaa_decode_merge_rows_kernel(c
         l += empty ? 0.f : w * ls[s];
         acc += empty ? 0.f : w * os[s];
     }
-    if (p.fp16)
-        reinterpret_cast<_Float16 *>(p.out)[(size_t)row * kD + d] = (_Float16)(acc / l);
-    else
-        p.out[(size_t)row * kD + d] = (__bf16)(acc / l);
-    if (d == 0) p.lse[row] = (m + __builtin_amdgcn_logf(l)) * 0.69314718055994530942f;
+    merge_store(p, mr.row, d, acc, l, m);
+}
+
+// Sequences of one length, more than kMergeRowSplits splits per pair: one workgroup per output row.
+__global__ __launch_bounds__(kMergeThreads) void swaa_decode_merge_kernel(const DecodeParams p) {
+    __shared__ float red[kMergeThreads];
+    __shared__ float lsum[kMergeThreads / kD];
+    merge_row_by_workgroup(p, merge_row(p, blockIdx.x), red, lsum);
+}
+
+// Sequences of one length, at most kMergeRowSplits splits per pair: kMergeThreads / 128 output rows
+// per workgroup.  A batch of many sequences has thousands of rows of two or three splits each;
+// one workgroup of 1024 threads per row spent most of the merge waiting for workgroup slots (64
+// sequences x 8 new tokens: the call took 275 us, 70 of them here).
+__global__ __launch_bounds__(kMergeThreads) void swaa_decode_merge_rows_kernel(const DecodeParams p) {
+    const long long row = (long long)blockIdx.x * (kMergeThreads / kD) + threadIdx.x / kD;
+    if (row >= (long long)p.B * p.Hq * p.Nq) return;
+    merge_row_by_group(p, merge_row(p, row), threadIdx.x % kD);
+}
+
+// Per-sequence lengths: both at once.  The first n_small workgroups take kMergeThreads / 128 rows
+// each and merge those of at most kMergeRowSplits splits, 128 threads per row.  The rows of the
+// sequences with more splits -- there are at most (units_target + B) / (kMergeRowSplits + 1) such
+// sequences -- are left to the workgroups behind them, one row each: workgroup n_small + k looks
+// for the (k / (Hq Nq))-th such sequence in the plan the split kernel has left (a prefix sum of
+// flags over the lanes, every wave for itself) and goes home if there is none.
+__global__ __launch_bounds__(kMergeThreads) void swaa_decode_merge_ragged_kernel(const DecodeParams p, unsigned n_small) {
+    __shared__ float red[kMergeThreads];
+    __shared__ float lsum[kMergeThreads / kD];
+    if (blockIdx.x < n_small) {
+        const long long row = (long long)blockIdx.x * (kMergeThreads / kD) + threadIdx.x / kD;
+        if (row >= (long long)p.B * p.Hq * p.Nq) return;
+        const MergeRow mr = merge_row(p, row);
+        if (mr.n_splits <= kMergeRowSplits) merge_row_by_group(p, mr, threadIdx.x % kD);
+        return;
+    }
+    const unsigned k = blockIdx.x - n_small, rows_per_seq = (unsigned)(p.Hq * p.Nq);
+    const unsigned want = k / rows_per_seq;  // the want-th sequence with many splits (from 0)
+    const int lane = threadIdx.x & 63;
+    unsigned before = 0;
+    int b = -1;
+    for (int c0 = 0; c0 < p.B; c0 += 64) {
+        const bool many = c0 + lane < p.B && p.ws_units[2 * (c0 + lane) + 1] > kMergeRowSplits;
+        const unsigned incl = wave_inclusive_scan(many ? 1u : 0u);
+        const unsigned in_round = wave_read_lane(incl, 63);
+        if (want - before < in_round) {
+            b = c0 + __popcll(__ballot(incl <= want - before));
+            break;
+        }
+        before += in_round;
+    }
+    if (b < 0) return;  // (the same in every wave of the workgroup)
+    merge_row_by_workgroup(p, merge_row(p, (long long)b * rows_per_seq + (k - want * rows_per_seq)), red, lsum);
 }
 
 }  // namespace
@@ -707,10 +759,16 @@ hipError_t launch_decode(const DecodeParams &p, hipStream_t stream) {
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     const long long rows = (long long)p.B * p.Hq * p.Nq;
-    if (!p.ragged && p.n_splits <= kMergeRowSplits) {
-        constexpr int kRowsPerWg = kMergeThreads / kD;
-        hipLaunchKernelGGL(swaa_decode_merge_rows_kernel, dim3((unsigned)((rows + kRowsPerWg - 1) / kRowsPerWg)),
-                           dim3(kMergeThreads), 0, stream, p);
+    constexpr int kRowsPerWg = kMergeThreads / kD;
+    const unsigned n_small = (unsigned)((rows + kRowsPerWg - 1) / kRowsPerWg);
+    if (p.ragged) {
+        long long many = ((long long)p.units_target + p.B) / (kMergeRowSplits + 1);  // sequences that can have more splits
+        many = many < p.B ? many : p.B;
+        if (n_small + many * p.Hq * p.Nq > 0x7fffffffLL) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(swaa_decode_merge_ragged_kernel, dim3(n_small + (unsigned)(many * p.Hq * p.Nq)), dim3(kMergeThreads),
+                           0, stream, p, n_small);
+    } else if (p.n_splits <= kMergeRowSplits) {
+        hipLaunchKernelGGL(swaa_decode_merge_rows_kernel, dim3(n_small), dim3(kMergeThreads), 0, stream, p);
     } else {
         hipLaunchKernelGGL(swaa_decode_merge_kernel, dim3((unsigned)rows), dim3(kMergeThreads), 0, stream, p);
     }
