@@ -258,6 +258,10 @@ __device__ __forceinline__ void softmax_half(f32x16 &s, int k0h, int qpos, int W
 // (the accumulators must be settled: pv_half<true>, or other MFMAs since their last update)
 __device__ __forceinline__ void rescale(f32x16 (&o)[kDB], float alpha) {
     if (__any(alpha != 1.f)) {
+        // (pinned on entry too: the copies from the accumulator registers that the multiplications
+        // need then stay inside this branch -- the compiler had moved all 64 of them in front of
+        // it, into every trip round the key loop, taken or not)
+        pin_acc(o);
 #pragma unroll
         for (int db = 0; db < kDB; ++db)
 #pragma unroll
