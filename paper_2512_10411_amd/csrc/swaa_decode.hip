@@ -41,9 +41,13 @@
 namespace swaa {
 namespace {
 
-constexpr int kDStages = 3;
 constexpr int kDStageBytes = 2 * kHalfBytes;          // K half, then V half
-constexpr int kDSmemBytes = kDStages * kDStageBytes;  // 48 KiB
+// Stages of the ring: three (48 KiB, three workgroups per CU) for one column tile per workgroup,
+// where the copies in flight are what counts; two (32 KiB) for two tiles, whose 450 registers
+// leave one wave per SIMD, so that four such workgroups fit a CU: those shapes are bound by the
+// wave's own instruction stream, and a fourth wave per CU is a third more of it.
+constexpr int decode_stages(int tiles) { return tiles == 2 ? 2 : 3; }
+constexpr int decode_wgs_per_cu(int tiles) { return tiles == 2 ? 4 : 3; }
 constexpr int kCopiesPerHalf = 16;                    // wave instructions per stage: 8 for K, 8 for V
 constexpr int kMergeThreads = 1024;
 constexpr int kRounds = 1;  // rounds of resident workgroups the split plan aims for
@@ -123,6 +127,7 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
     // long sequence).  Per-sequence lengths: the units (sequence, split) x KV heads go to the
     // dies in turn, so that whatever the lengths every die gets its share of the long sequences.
     // Either way the column-tile groups of one (pair, split), which read the same keys, share a die.
+    constexpr int kDStages = decode_stages(kTiles);
     const int lane = threadIdx.x;
     const unsigned items = (unsigned)p.wg_items;
     unsigned witem;
@@ -354,14 +359,14 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
     }
     issue_half(0, 0, lookup(0));
     if (n_mine >= 2) issue_half(1, 1, lookup(1));
-    if (n_mine >= 3) issue_half(2, 2, lookup(2));
+    if (kDStages >= 3 && n_mine >= 3) issue_half(2, 2, lookup(2));
     // (the idle cycles keep the loads two wait states away from the first MFMA that reads them)
 #pragma unroll
     for (int j = 0; j < kTiles; ++j)
         asm volatile("s_nop 1"
                      : "+a"(qf[j][0]), "+a"(qf[j][1]), "+a"(qf[j][2]), "+a"(qf[j][3]), "+a"(qf[j][4]), "+a"(qf[j][5]),
                        "+a"(qf[j][6]), "+a"(qf[j][7]));
-    Pages pg_next = n_mine >= 4 ? lookup(3) : Pages{0, 0};  // of the half the loop's first iteration issues
+    Pages pg_next = n_mine > kDStages ? lookup(kDStages) : Pages{0, 0};  // of the half the loop's first iteration issues
 
     f32x16 oacc[kTiles][kDB];
     RowState rs[kTiles];
@@ -388,7 +393,7 @@ __global__ __launch_bounds__(64) void swaa_decode_split_kernel(const DecodeParam
             asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
         else
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        static_assert(kDStages == 3 && kCopiesPerHalf == 16, "wait counts above");
+        static_assert(kDStages <= 3 && kCopiesPerHalf == 16, "wait counts above");
 
         const uint32_t so = (uint32_t)(stage * kDStageBytes);
         const int k0h = first_key(t);
@@ -670,7 +675,8 @@ void plan_decode(DecodeParams &p, bool ragged) {
         // split) units, cut on the device in proportion to the sequences' lengths; kTailRounds
         // with more (pair, column tile) groups than resident workgroups (see below).
         constexpr long long kRaggedRounds = 2, kRaggedTailRounds = 8;
-        const long long units = 256LL * 3 * (groups > 256LL * 3 ? kRaggedTailRounds : kRaggedRounds) / ((long long)p.Hkv * p.n_ctgroups);
+        const long long resident = 256LL * decode_wgs_per_cu(p.tiles_per_item);
+        const long long units = resident * (groups > resident ? kRaggedTailRounds : kRaggedRounds) / ((long long)p.Hkv * p.n_ctgroups);
         p.units_target = (int)(units < 1 ? 1 : units);
         // (at most units_target + B units by the rounding of the device's division, and no
         // sequence has more than ceil(n_halves / 4) splits)
@@ -682,7 +688,7 @@ void plan_decode(DecodeParams &p, bool ragged) {
         p.items = (long long)p.max_units * p.Hkv * p.n_coltiles;
         return;
     }
-    const long long target_items = 256LL * 3 * kRounds;
+    const long long target_items = 256LL * decode_wgs_per_cu(p.tiles_per_item) * kRounds;
     long long per_group = target_items / groups;
     // More (pair, column tile) groups than resident workgroups: one item per group would leave a
     // second round of a few long items streaming alone at the end (100 sequences x 8 KV heads
@@ -740,7 +746,7 @@ hipError_t launch_decode(const DecodeParams &p, hipStream_t stream) {
     const bool paged = p.block_table != nullptr;
     auto launch = [&](auto f16, auto pg, auto tiles) {
         hipLaunchKernelGGL((swaa_decode_split_kernel<decltype(f16)::value, decltype(pg)::value, decltype(tiles)::value>), grid,
-                           dim3(64), kDSmemBytes, stream, p);
+                           dim3(64), decode_stages(decltype(tiles)::value) * kDStageBytes, stream, p);
     };
     auto pick_tiles = [&](auto f16, auto pg) {
         if (p.tiles_per_item == 2)
