@@ -15,7 +15,8 @@
 //     LDS, filled by global_load_lds_dwordx4 with whole 256-byte rows per 16
 //     lanes.  No barriers: a wave waits on its own copies only.  48 KiB of LDS
 //     per workgroup lets three of them share a CU: 96 KiB of copies in flight
-//     per CU, 24 MiB over the chip.
+//     per CU, 24 MiB over the chip.  (Workgroups that compute two column tiles
+//     take a two-stage ring and run four to a CU: decode_stages.)
 //   * Per half: all K and V^T operand fragments go from LDS to registers (V^T
 //     through transposing reads), the copy of the half three ahead is issued into
 //     the stage just emptied, and only then the arithmetic runs: S^T = K Q^T (8
