@@ -76,9 +76,11 @@ struct Elem<_Float16> {
 // Head dimensions up to kSmallD run 32 positions per wave and several workgroups per CU (the
 // registers allow it), so that one wave's softmax runs under another's matrix instructions:
 // measured against 64 positions per wave and one workgroup per CU, D = 64 is 1.25 - 1.37 x as
-// fast, D = 96 1.15 - 1.24 x.
+// fast, D = 96 1.15 - 1.24 x.  D = 160 still fits two workgroups per CU with a few registers
+// spilled outside the loop (1.4 - 1.5 x); from 192 on the spills land inside it and cost more
+// than the second workgroup brings.
 constexpr int kSmallD = 96;
-constexpr int min_blocks(int D) { return D <= 64 ? 4 : D <= kSmallD ? 3 : 1; }
+constexpr int min_blocks(int D) { return D <= 64 ? 4 : D <= kSmallD ? 3 : D <= 160 ? 2 : 1; }
 template <int D, typename E, int QB>
 __global__ __launch_bounds__(kThreads, min_blocks(D)) void swaa_fwd_kernel(const FwdParams p) {
     using T = Tile<D>;
